@@ -1,0 +1,188 @@
+/*
+ * revffn.h - C ABI of the RevFFN reversible block for AMD MI355X (gfx950).
+ *
+ * The block (paper section 3.1, Eq. 1-2, with the projection adapters of
+ * section 3.2) splits the hidden state H[B,S,d] into two streams of width
+ * h = d/2 and updates them as
+ *
+ *     Y1 = X1 + P_dn_a( Attn_pt(P_up_a Norm X1, P_up_a Norm X2, P_up_a Norm X2) )
+ *     Y2 = X2 + P_dn_m( MoE_pt(P_up_m Norm Y1) )
+ *
+ * where Attn_pt is multi-head softmax attention (queries from stream 1, keys and
+ * values from stream 2) and MoE_pt is a top-k routed mixture of SwiGLU experts
+ * plus an optional sigmoid-gated shared SwiGLU expert.  The inverse rebuilds
+ * (X1, X2) from (Y1, Y2); the backward pass recomputes all activations from a
+ * supplied (rebuilt) input instead of reading cached ones.
+ *
+ * Conventions common to every call
+ *  - All tensor pointers are DEVICE pointers owned by the caller.  The library
+ *    never frees or reallocates them.  Host pointers are marked "host".
+ *  - Element type of streams, weights and gradients is given by config.dtype:
+ *    0 = float32, 1 = bfloat16 (fp32 accumulation).  b_router and the routing
+ *    outputs are always float32 / int32.
+ *  - Linear weights are row-major [out, in] and are applied as x @ W^T.
+ *  - A stream is token-major [T, h], T = B*S, token t = b*S + s, with row
+ *    stride `ld` elements (ld >= h).  ld = d lets the two halves of one [T, d]
+ *    hidden tensor be passed without a copy (section 3.1, the split display).
+ *  - Every call only enqueues work on `hip_stream` (a hipStream_t; NULL = the
+ *    default stream) and returns; it never synchronises.  Calls on one context
+ *    must be issued on one stream at a time (they share the context workspace).
+ *  - Return value: 0 on success, a negative REVFFN_E* code otherwise.  No call
+ *    throws or aborts.  On error nothing has been enqueued.
+ *  - Results are deterministic: no floating-point atomics anywhere, so the same
+ *    inputs give bit-identical outputs, and the routing recomputed by the
+ *    inverse/backward from Y1 is bit-identical to the forward routing.
+ */
+#ifndef REVFFN_H
+#define REVFFN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  REVFFN_OK = 0,
+  REVFFN_EINVAL = -1,      /* bad config value                                  */
+  REVFFN_ESHAPE = -2,      /* B, S or ld out of range for this context          */
+  REVFFN_ENULL = -3,       /* a required pointer is NULL                        */
+  REVFFN_EWORKSPACE = -4,  /* device allocation of the workspace failed         */
+  REVFFN_EHIP = -5,        /* a HIP runtime call failed                         */
+  REVFFN_EUNSUPPORTED = -6 /* valid request this build does not implement       */
+};
+
+enum { REVFFN_F32 = 0, REVFFN_BF16 = 1 };
+
+/* Geometry and the readings the paper leaves open (all switchable). */
+typedef struct revffn_config {
+  int32_t d_model;         /* d; even                                             */
+  int32_t n_heads;         /* n_heads * head_dim == d_model                       */
+  int32_t head_dim;        /* even (rotary pairs)                                 */
+  int32_t n_experts;       /* E, 1..256                                           */
+  int32_t top_k;           /* 1..min(E, 16)                                       */
+  int32_t d_expert;        /* I, routed expert intermediate width                 */
+  int32_t d_shared;        /* Is, shared expert intermediate width; 0 = none      */
+  int32_t dtype;           /* REVFFN_F32 or REVFFN_BF16                           */
+  int32_t causal;          /* 1 = causal mask                                     */
+  int32_t use_rope;        /* 1 = rotary encoding on Q and K (half-split pairs)   */
+  int32_t norm_topk_prob;  /* 1 = renormalise routing weights over the top-k set  */
+  int32_t n_inv_iters;     /* fixed-point iterations of the inverse (>= 0);
+                              the paper uses 1 (end of section 3.1)               */
+  float rope_theta;        /* e.g. 1e6                                            */
+  float rms_eps;           /* e.g. 1e-6                                           */
+} revffn_config;
+
+/* Weights of one block.  Device pointers, dtype = config.dtype unless noted. */
+typedef struct revffn_weights {
+  const void *norm_a1, *norm_a2, *norm_m; /* [h] RMSNorm gains for X1, X2, Y1        */
+  const void *pup_a, *pdn_a;              /* [d,h], [h,d] attention adapters (3.2)   */
+  const void *pup_m, *pdn_m;              /* [d,h], [h,d] MoE adapters (3.2)         */
+  const void *wq, *wk, *wv, *wo;          /* [d,d]                                   */
+  const void *bq, *bk, *bv;               /* [d] or NULL                             */
+  const void *w_router;                   /* [E,d]                                   */
+  const float *b_router;                  /* [E] float32 or NULL (added to logits)   */
+  const void *w_gate_up;                  /* [E,2I,d]: I gate rows then I up rows    */
+  const void *w_down;                     /* [E,d,I]                                 */
+  const void *ws_gate_up;                 /* [2Is,d]; NULL iff d_shared == 0         */
+  const void *ws_down;                    /* [d,Is]                                  */
+  const void *ws_gate;                    /* [d] shared-expert sigmoid gate          */
+} revffn_weights;
+
+/* Where weight gradients go: same shapes and dtype as the weights (b_router:
+ * float32).  A NULL field means "this gradient is not wanted" and its GEMM is
+ * skipped (section 3.3: stage 1 trains only the adapters; stage 2 keeps the
+ * routers frozen).  Non-NULL fields are OVERWRITTEN, not accumulated. */
+typedef struct revffn_grads {
+  void *norm_a1, *norm_a2, *norm_m;
+  void *pup_a, *pdn_a, *pup_m, *pdn_m;
+  void *wq, *wk, *wv, *wo;
+  void *bq, *bk, *bv;
+  void *w_router;
+  float *b_router;
+  void *w_gate_up, *w_down;
+  void *ws_gate_up, *ws_down, *ws_gate;
+} revffn_grads;
+
+typedef struct revffn_ctx revffn_ctx; /* opaque: owns the device workspace only */
+
+/* Device bytes a context for up to max_B x max_S tokens allocates; 0 if cfg is invalid. */
+size_t revffn_workspace_bytes(const revffn_config *cfg, int32_t max_B, int32_t max_S);
+
+/* Validate cfg (host) and allocate the workspace on the current device.
+ * The only calls that allocate or free device memory are create and destroy. */
+int revffn_create(revffn_ctx **out, const revffn_config *cfg, int32_t max_B, int32_t max_S);
+void revffn_destroy(revffn_ctx *ctx);
+
+/* Change the inverse's fixed-point iteration count of an existing context. */
+int revffn_set_inv_iters(revffn_ctx *ctx, int32_t n_inv_iters);
+
+/* Eq. 1-2.  x1, x2: [T,h] inputs; y1, y2: [T,h] outputs, all with row stride ld.
+ * y1 may alias x1 and y2 may alias x2 (in-place update). */
+int revffn_forward(revffn_ctx *ctx, const revffn_weights *w,
+                   const void *x1, const void *x2, void *y1, void *y2,
+                   int32_t B, int32_t S, int64_t ld, void *hip_stream);
+
+/* Inverse display of section 3.1: X2^ = Y2 - MoE branch at Y1 (exact up to the
+ * rounding of one subtraction); X1^ by n_inv_iters fixed-point iterations
+ * x <- Y1 - attention branch(x, X2^) started at x = Y1.  x1 may alias y1 and x2
+ * may alias y2.  residual (device float[1], may be NULL) receives
+ * max |x_n - x_(n-1)| of the last iteration, so a caller can detect a
+ * non-contracting iteration. */
+int revffn_inverse(revffn_ctx *ctx, const revffn_weights *w,
+                   const void *y1, const void *y2, void *x1, void *x2,
+                   int32_t B, int32_t S, int64_t ld, float *residual, void *hip_stream);
+
+/* Gradient of Eq. 1-2 at block input (x1, x2) (normally the rebuilt one) for
+ * upstream gradients (dy1, dy2).  Activations are recomputed, none is cached
+ * between calls (section 3.1).  y1: the exact stream-1 block output held by the
+ * sweep, used for the MoE half so that the recomputed routing equals the forward
+ * routing; NULL = recompute it as x1 + attention branch.  dx1/dx2 may alias
+ * dy1/dy2.  g may be NULL (input gradients only). */
+int revffn_backward(revffn_ctx *ctx, const revffn_weights *w,
+                    const void *x1, const void *x2, const void *y1,
+                    const void *dy1, const void *dy2, void *dx1, void *dx2,
+                    const revffn_grads *g, int32_t B, int32_t S, int64_t ld, void *hip_stream);
+
+/* Stack of n_blocks blocks (section 3.1: only the last hidden state is kept).
+ * Forward: (x1,x2) -> (y1,y2) through w[0..n_blocks-1], no stream swap between
+ * blocks; y may alias x.  Backward sweep: starting from the stack output (y1,y2),
+ * which is OVERWRITTEN in place by each block's rebuilt input, and (dy1,dy2),
+ * overwritten in place by the gradient flowing down; on return they hold the
+ * rebuilt stack input and its gradient.  g: host array of n_blocks grads structs
+ * or NULL. */
+int revffn_stack_forward(revffn_ctx *ctx, const revffn_weights *w /*host array*/, int32_t n_blocks,
+                         const void *x1, const void *x2, void *y1, void *y2,
+                         int32_t B, int32_t S, int64_t ld, void *hip_stream);
+int revffn_stack_backward(revffn_ctx *ctx, const revffn_weights *w /*host array*/,
+                          const revffn_grads *g /*host array or NULL*/, int32_t n_blocks,
+                          void *y1, void *y2, void *dy1, void *dy2,
+                          int32_t B, int32_t S, int64_t ld, void *hip_stream);
+
+/* Parity taps (not on the hot path).  Copy the routing of the most recent
+ * forward / inverse / backward call on ctx into caller DEVICE buffers (any may
+ * be NULL): idx [T,k] expert per slot, slots by descending logit, equal logits
+ * to the lower expert index; wts [T,k] routing weights; counts [E];
+ * offsets [E+1] exclusive prefix sum; row_map [T*k]: permuted row -> t*k + slot,
+ * grouped by expert, (token, slot) order kept inside an expert. */
+int revffn_get_routing(revffn_ctx *ctx, int32_t *idx, float *wts, int32_t *counts,
+                       int32_t *offsets, int32_t *row_map, void *hip_stream);
+
+/* With taps enabled, forward/inverse also keep the two branch outputs (the terms
+ * added to X1 and X2 in Eq. 1-2) in float32, before the residual add rounds them
+ * away.  which: 0 = attention branch [T,h], 1 = MoE branch [T,h].  dst: device
+ * float [T,h], dense. */
+int revffn_enable_taps(revffn_ctx *ctx, int32_t on);
+int revffn_get_branch(revffn_ctx *ctx, int32_t which, float *dst, void *hip_stream);
+
+/* Select kernels: 0 = automatic (MFMA kernels where the shape allows),
+ * 1 = force the generic kernels (any shape, slow).  For tests. */
+int revffn_set_kernel_mode(revffn_ctx *ctx, int32_t mode);
+
+const char *revffn_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* REVFFN_H */

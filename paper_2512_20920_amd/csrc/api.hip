@@ -1,0 +1,600 @@
+// C ABI of the RevFFN block: argument validation, workspace, and the sequence of kernel
+// launches for forward (Eq. 1-2), inverse (the display under them) and backward.
+// No device synchronisation and no allocation happens outside create/destroy.
+#include "../../include/revffn.h"
+#include "kernels.h"
+
+#include <math.h>
+#include <new>
+#include <stdlib.h>
+#include <string.h>
+#include <vector>
+
+namespace {
+
+struct Carver {            // hands out 256-byte aligned slices of one allocation (or just counts)
+  char* base = nullptr;
+  size_t off = 0;
+  void* take(size_t bytes) {
+    size_t a = (off + 255) & ~(size_t)255;
+    off = a + bytes;
+    return base ? (void*)(base + a) : nullptr;
+  }
+};
+
+}  // namespace
+
+struct revffn_ctx {
+  revffn_config cfg;
+  int dt, es;                 // element type / size of streams and weights
+  int maxT;
+  int mode = 0;               // 0 auto, 1 generic kernels only
+  int taps = 0;
+  int device = 0;
+  void* slab = nullptr;
+  size_t slab_bytes = 0;
+  int lastT = 0;
+  // attention half
+  void *n12, *U12, *Q, *K, *V, *O, *AO;
+  float* lse;
+  // moe half
+  void *n3, *Um;
+  float *wrp, *probs, *gamma, *wts;
+  int *idx, *counts, *offsets, *row_map, *inv_map;
+  int *tg_a, *tm_a, *tg_b, *tm_b;
+  int max_tiles_a, max_tiles_b;
+  void *GU, *Hh, *Yp, *GUs, *Hs, *Ys, *RS;
+  float *tapA, *tapM;
+  void *y1c, *xtmp;
+  float* resid_dev;
+  // backward
+  void *dRS, *dYp, *dYs, *dHs, *dGUs, *dUm_sh, *dHh, *dGU, *dXg, *dUm, *dn3, *g1;
+  float *dw, *dzext, *rinv, *partial;
+  void *dAO, *dO, *dQ, *dK, *dV, *dU12, *dn12;
+  float* dvec;
+  float* rope_cs;
+};
+
+namespace {
+
+const int BM_A = 64;    // m-tile height of the generic grouped GEMM
+const int BM_B = 128;   // m-tile height of the MFMA grouped GEMM
+
+int check_cfg(const revffn_config* c) {
+  if (!c) return REVFFN_ENULL;
+  if (c->d_model < 2 || (c->d_model & 1)) return REVFFN_EINVAL;
+  if (c->n_heads < 1 || c->head_dim < 2 || (c->head_dim & 1) || c->head_dim > 1024) return REVFFN_EINVAL;
+  if ((long long)c->n_heads * c->head_dim != c->d_model) return REVFFN_EINVAL;
+  if (c->n_experts < 1 || c->n_experts > 256) return REVFFN_EINVAL;
+  if (c->top_k < 1 || c->top_k > c->n_experts || c->top_k > 16) return REVFFN_EINVAL;
+  if (c->d_expert < 1 || c->d_shared < 0) return REVFFN_EINVAL;
+  if (c->dtype != REVFFN_F32 && c->dtype != REVFFN_BF16) return REVFFN_EINVAL;
+  if (c->n_inv_iters < 0 || c->n_inv_iters > 1024) return REVFFN_EINVAL;
+  if (!(c->rms_eps >= 0.f) || !(c->rope_theta > 0.f)) return REVFFN_EINVAL;
+  return REVFFN_OK;
+}
+
+// Lays out every workspace buffer; with c->slab == nullptr it only measures.
+size_t carve(revffn_ctx* c, char* base) {
+  const revffn_config& f = c->cfg;
+  const size_t T = (size_t)c->maxT, d = f.d_model, h = d / 2, E = f.n_experts, k = f.top_k, I = f.d_expert,
+               Is = f.d_shared, N = T * k, es = c->es, H = f.n_heads;
+  const size_t E1 = E + (Is ? 1 : 0);
+  Carver cv;
+  cv.base = base;
+  c->n12 = cv.take(2 * T * h * es);
+  c->U12 = cv.take(2 * T * d * es);
+  c->Q = cv.take(T * d * es);
+  c->K = cv.take(T * d * es);
+  c->V = cv.take(T * d * es);
+  c->O = cv.take(T * d * es);
+  c->AO = cv.take(T * d * es);
+  c->lse = (float*)cv.take(T * H * 4);
+  c->n3 = cv.take(T * h * es);
+  c->Um = cv.take(T * d * es);
+  c->wrp = (float*)cv.take(E1 * h * 4);
+  c->probs = (float*)cv.take(T * E * 4);
+  c->gamma = (float*)cv.take(T * 4);
+  c->wts = (float*)cv.take(N * 4);
+  c->idx = (int*)cv.take(N * 4);
+  c->counts = (int*)cv.take(E * 4);
+  c->offsets = (int*)cv.take((E + 1) * 4);
+  c->row_map = (int*)cv.take(N * 4);
+  c->inv_map = (int*)cv.take(N * 4);
+  c->max_tiles_a = (int)(N / BM_A + E + 1);
+  c->max_tiles_b = (int)(N / BM_B + E + 1);
+  c->tg_a = (int*)cv.take(c->max_tiles_a * 4);
+  c->tm_a = (int*)cv.take(c->max_tiles_a * 4);
+  c->tg_b = (int*)cv.take(c->max_tiles_b * 4);
+  c->tm_b = (int*)cv.take(c->max_tiles_b * 4);
+  c->GU = cv.take(N * 2 * I * es);
+  c->Hh = cv.take(N * I * es);
+  c->Yp = cv.take(N * d * es);
+  c->GUs = Is ? cv.take(T * 2 * Is * es) : nullptr;
+  c->Hs = Is ? cv.take(T * Is * es) : nullptr;
+  c->Ys = Is ? cv.take(T * d * es) : nullptr;
+  c->RS = cv.take(T * d * es);
+  c->tapA = (float*)cv.take(T * h * 4);
+  c->tapM = (float*)cv.take(T * h * 4);
+  c->y1c = cv.take(T * h * es);
+  c->xtmp = cv.take(T * h * es);
+  c->resid_dev = (float*)cv.take(256);
+  c->dRS = cv.take(T * d * es);
+  c->dYp = cv.take(N * d * es);
+  c->dYs = Is ? cv.take(T * d * es) : nullptr;
+  c->dHs = Is ? cv.take(T * Is * es) : nullptr;
+  c->dGUs = Is ? cv.take(T * 2 * Is * es) : nullptr;
+  c->dUm_sh = Is ? cv.take(T * d * es) : nullptr;
+  c->dHh = cv.take(N * I * es);
+  c->dGU = cv.take(N * 2 * I * es);
+  c->dXg = cv.take(N * d * es);
+  c->dUm = cv.take(T * d * es);
+  c->dn3 = cv.take(T * h * es);
+  c->g1 = cv.take(T * h * es);
+  c->dw = (float*)cv.take(N * 4);
+  c->dzext = (float*)cv.take(T * E1 * 4);
+  c->rinv = (float*)cv.take(2 * T * 4);
+  size_t maxcols = d > E1 ? d : E1;
+  c->partial = (float*)cv.take(colsum_partial_floats((int)(2 * T), (int)maxcols) * 4);
+  c->dAO = cv.take(T * d * es);
+  c->dO = cv.take(T * d * es);
+  c->dQ = cv.take(T * d * es);
+  c->dK = cv.take(T * d * es);
+  c->dV = cv.take(T * d * es);
+  c->dU12 = cv.take(2 * T * d * es);
+  c->dn12 = cv.take(2 * T * h * es);
+  c->dvec = (float*)cv.take(T * H * 4);
+  c->rope_cs = (float*)cv.take(T * (f.head_dim / 2) * 8);
+  return cv.off + 256;
+}
+
+inline char* at(void* p, size_t elems, int es) { return (char*)p + elems * (size_t)es; }
+inline const char* at(const void* p, size_t elems, int es) { return (const char*)p + elems * (size_t)es; }
+
+// ---- GEMM shorthands --------------------------------------------------------------
+// C[M,N] = A[M,K] . W^T, W row-major [N,K]
+GemmArgs nt(const void* A, i64 lda, const void* W, i64 ldw, void* C, i64 ldc, int M, int N, int K) {
+  GemmArgs g;
+  g.A = A; g.lda = lda; g.B = W; g.ldb = ldw; g.C = C; g.ldc = ldc; g.M = M; g.N = N; g.K = K;
+  return g;
+}
+// C[M,N] = A[M,K] . W, W row-major [K,N]
+GemmArgs nn(const void* A, i64 lda, const void* W, i64 ldw, void* C, i64 ldc, int M, int N, int K) {
+  GemmArgs g = nt(A, lda, W, ldw, C, ldc, M, N, K);
+  g.b_trans = 1;
+  return g;
+}
+// C[M,N] = A^T . Bm, A row-major [K,M], Bm row-major [K,N]
+GemmArgs tn(const void* A, i64 lda, const void* Bm, i64 ldb, void* C, i64 ldc, int M, int N, int K) {
+  GemmArgs g = nt(A, lda, Bm, ldb, C, ldc, M, N, K);
+  g.a_trans = 1;
+  g.b_trans = 1;
+  return g;
+}
+
+int run_gemm(revffn_ctx* c, GemmArgs g, int ta, int tb, int tc, hipStream_t s) {
+  GemmTypes t{ta, tb, tc, c->dt};
+  if (c->dt == 1 && c->mode == 0 && ta == 1 && tb == 1) {
+    if (g.group_mode == 1) { g.tile_group = c->tg_b; g.tile_m0 = c->tm_b; g.max_tiles = c->max_tiles_b; g.tile_bm = BM_B; }
+    if (launch_gemm_mfma(g, t, s) == 0) return 0;
+  }
+  if (g.group_mode == 1) { g.tile_group = c->tg_a; g.tile_m0 = c->tm_a; g.max_tiles = c->max_tiles_a; g.tile_bm = BM_A; }
+  return launch_gemm_generic(g, t, s) == 0 ? 0 : REVFFN_EUNSUPPORTED;
+}
+int run_gemm(revffn_ctx* c, const GemmArgs& g, hipStream_t s) { return run_gemm(c, g, c->dt, c->dt, c->dt, s); }
+
+#define TRY(x) do { int _e = (x); if (_e) return _e; } while (0)
+
+// ---- attention half ---------------------------------------------------------------
+// Recomputes n12, U12, Q, (K, V), O, lse, AO at streams (x1, x2).
+int attn_acts(revffn_ctx* c, const revffn_weights* w, const void* x1, i64 ld1, const void* x2, i64 ld2, int B, int S,
+              bool do_kv, hipStream_t s) {
+  const revffn_config& f = c->cfg;
+  const int T = B * S, d = f.d_model, h = d / 2, es = c->es, dt = c->dt;
+  launch_rmsnorm_fwd(dt, x1, ld1, w->norm_a1, c->n12, h, T, h, f.rms_eps, s);
+  if (do_kv) launch_rmsnorm_fwd(dt, x2, ld2, w->norm_a2, at(c->n12, (size_t)T * h, es), h, T, h, f.rms_eps, s);
+  // the same P_up serves both streams: one GEMM over the stacked rows
+  TRY(run_gemm(c, nt(c->n12, h, w->pup_a, h, c->U12, d, do_kv ? 2 * T : T, d, h), s));
+  GemmArgs gq = nt(c->U12, d, w->wq, d, c->Q, d, T, d, d);
+  gq.bias = w->bq;
+  TRY(run_gemm(c, gq, s));
+  if (do_kv) {
+    const void* U2 = at(c->U12, (size_t)T * d, es);
+    GemmArgs gk = nt(U2, d, w->wk, d, c->K, d, T, d, d);
+    gk.bias = w->bk;
+    TRY(run_gemm(c, gk, s));
+    GemmArgs gv = nt(U2, d, w->wv, d, c->V, d, T, d, d);
+    gv.bias = w->bv;
+    TRY(run_gemm(c, gv, s));
+  }
+  if (f.use_rope) {
+    launch_rope(dt, c->Q, c->rope_cs, T, S, f.n_heads, f.head_dim, 1.f, s);
+    if (do_kv) launch_rope(dt, c->K, c->rope_cs, T, S, f.n_heads, f.head_dim, 1.f, s);
+  }
+  bool done = false;
+  if (dt == 1 && c->mode == 0)
+    done = launch_attn_fwd_flash(c->Q, c->K, c->V, c->O, c->lse, B, S, f.n_heads, f.head_dim, f.causal, s) == 0;
+  if (!done) launch_attn_fwd_generic(dt, c->Q, c->K, c->V, c->O, c->lse, B, S, f.n_heads, f.head_dim, f.causal, s);
+  TRY(run_gemm(c, nt(c->O, d, w->wo, d, c->AO, d, T, d, d), s));
+  return 0;
+}
+// dst = resid + sign * P_dn_a(AO)     (Eq. 1 and the second line of the inverse)
+int attn_out(revffn_ctx* c, const revffn_weights* w, const void* resid, i64 ldr, float sign, void* dst, i64 ldd,
+             int T, hipStream_t s) {
+  const int d = c->cfg.d_model, h = d / 2;
+  GemmArgs g = nt(c->AO, d, w->pdn_a, d, dst, ldd, T, h, d);
+  g.resid = resid; g.ldr = ldr; g.resid_sign = sign;
+  if (c->taps) { g.tap = c->tapA; g.ldtap = h; }
+  return run_gemm(c, g, s);
+}
+
+// ---- MoE half ---------------------------------------------------------------------
+// Recomputes n3, Um, routing, GU, Hh, Yp, shared expert and RS at y1.
+int moe_acts(revffn_ctx* c, const revffn_weights* w, const void* y1, i64 ld, int T, hipStream_t s) {
+  const revffn_config& f = c->cfg;
+  const int d = f.d_model, h = d / 2, E = f.n_experts, k = f.top_k, I = f.d_expert, Is = f.d_shared, dt = c->dt;
+  const int N = T * k;
+  launch_rmsnorm_fwd(dt, y1, ld, w->norm_m, c->n3, h, T, h, f.rms_eps, s);
+  TRY(run_gemm(c, nt(c->n3, h, w->pup_m, h, c->Um, d, T, d, h), s));
+  // folded fp32 router matrix  wrp = [W_r ; w_shared_gate] . P_up_m
+  TRY(run_gemm(c, nn(w->w_router, d, w->pup_m, h, c->wrp, h, E, h, d), dt, dt, 0, s));
+  if (Is) TRY(run_gemm(c, nn(w->ws_gate, d, w->pup_m, h, c->wrp + (size_t)E * h, h, 1, h, d), dt, dt, 0, s));
+  launch_router(dt, y1, ld, w->norm_m, c->wrp, w->b_router, c->probs, c->idx, c->wts, c->gamma, T, h, E, k,
+                Is ? 1 : 0, f.norm_topk_prob, f.rms_eps, s);
+  launch_permute(c->idx, T, k, E, c->counts, c->offsets, c->row_map, c->inv_map, c->tg_a, c->tm_a, c->max_tiles_a,
+                 BM_A, c->tg_b, c->tm_b, c->max_tiles_b, BM_B, s);
+  // routed experts: GU = Xg . Wgu_e^T (rows gathered from Um through row_map), SwiGLU, Yp = Hh . Wd_e^T
+  GemmArgs g1 = nt(c->Um, d, w->w_gate_up, d, c->GU, 2 * I, N, 2 * I, d);
+  g1.group_mode = 1; g1.n_groups = E; g1.offsets = c->offsets; g1.b_group_stride = (i64)2 * I * d;
+  g1.a_gather = c->row_map; g1.gather_div = k;
+  TRY(run_gemm(c, g1, s));
+  launch_swiglu_fwd(dt, c->GU, c->Hh, N, I, s);
+  GemmArgs g2 = nt(c->Hh, I, w->w_down, I, c->Yp, d, N, d, I);
+  g2.group_mode = 1; g2.n_groups = E; g2.offsets = c->offsets; g2.b_group_stride = (i64)d * I;
+  TRY(run_gemm(c, g2, s));
+  if (Is) {
+    TRY(run_gemm(c, nt(c->Um, d, w->ws_gate_up, d, c->GUs, 2 * Is, T, 2 * Is, d), s));
+    launch_swiglu_fwd(dt, c->GUs, c->Hs, T, Is, s);
+    TRY(run_gemm(c, nt(c->Hs, Is, w->ws_down, Is, c->Ys, d, T, d, Is), s));
+  }
+  launch_combine(dt, c->Yp, c->inv_map, c->wts, Is ? c->Ys : nullptr, c->gamma, c->RS, T, d, k, s);
+  c->lastT = T;
+  return 0;
+}
+// dst = resid + sign * P_dn_m(RS)     (Eq. 2 and the first line of the inverse)
+int moe_out(revffn_ctx* c, const revffn_weights* w, const void* resid, i64 ldr, float sign, void* dst, i64 ldd,
+            int T, hipStream_t s) {
+  const int d = c->cfg.d_model, h = d / 2;
+  GemmArgs g = nt(c->RS, d, w->pdn_m, d, dst, ldd, T, h, d);
+  g.resid = resid; g.ldr = ldr; g.resid_sign = sign;
+  if (c->taps) { g.tap = c->tapM; g.ldtap = h; }
+  return run_gemm(c, g, s);
+}
+
+int check_call(revffn_ctx* c, const revffn_weights* w, int B, int S, i64 ld) {
+  if (!c || !w) return REVFFN_ENULL;
+  if (B < 1 || S < 1) return REVFFN_ESHAPE;
+  if ((i64)B * S > c->maxT) return REVFFN_ESHAPE;
+  if (ld < c->cfg.d_model / 2) return REVFFN_ESHAPE;
+  if (!w->norm_a1 || !w->norm_a2 || !w->norm_m || !w->pup_a || !w->pdn_a || !w->pup_m || !w->pdn_m || !w->wq ||
+      !w->wk || !w->wv || !w->wo || !w->w_router || !w->w_gate_up || !w->w_down)
+    return REVFFN_ENULL;
+  if (c->cfg.d_shared && (!w->ws_gate_up || !w->ws_down || !w->ws_gate)) return REVFFN_ENULL;
+  return 0;
+}
+
+int forward_impl(revffn_ctx* c, const revffn_weights* w, const void* x1, const void* x2, void* y1, void* y2, int B,
+                 int S, i64 ld, hipStream_t s) {
+  const int T = B * S;
+  TRY(attn_acts(c, w, x1, ld, x2, ld, B, S, true, s));
+  TRY(attn_out(c, w, x1, ld, 1.f, y1, ld, T, s));                 // Eq. 1
+  TRY(moe_acts(c, w, y1, ld, T, s));
+  TRY(moe_out(c, w, x2, ld, 1.f, y2, ld, T, s));                  // Eq. 2
+  return 0;
+}
+
+// y1k/ldk: where the exact Y1 stays readable during and after the call (== y1 unless in place)
+int inverse_impl(revffn_ctx* c, const revffn_weights* w, const void* y1, const void* y2, void* x1, void* x2, int B,
+                 int S, i64 ld, float* residual, hipStream_t s, const void** y1_kept, i64* ld_kept) {
+  const int T = B * S, h = c->cfg.d_model / 2, dt = c->dt;
+  const int n = c->cfg.n_inv_iters;
+  const void* y1k = y1;
+  i64 ldk = ld;
+  if (x1 == y1 && (n >= 1)) {             // in place: Y1 is needed after x1 starts being overwritten
+    launch_copy_rows(dt, y1, ld, c->y1c, h, T, h, s);
+    y1k = c->y1c;
+    ldk = h;
+  }
+  TRY(moe_acts(c, w, y1k, ldk, T, s));
+  TRY(moe_out(c, w, y2, ld, -1.f, x2, ld, T, s));                 // X2^ = Y2 - MoE branch(Y1)
+  if (n == 0) {
+    if (x1 != y1) launch_copy_rows(dt, y1, ld, x1, ld, T, h, s);
+    if (residual) launch_fill_u32((uint32_t*)residual, 0, 1, s);
+  }
+  for (int it = 1; it <= n; it++) {
+    const void* xin = (it == 1) ? y1k : x1;                       // iterate, started at Y1
+    i64 ldin = (it == 1) ? ldk : ld;
+    TRY(attn_acts(c, w, xin, ldin, x2, ld, B, S, it == 1, s));        // K, V depend on X2^ only: once
+    if (it == n && residual) {
+      TRY(attn_out(c, w, y1k, ldk, -1.f, c->xtmp, h, T, s));
+      launch_fill_u32((uint32_t*)residual, 0, 1, s);
+      launch_absdiff_max_copy(dt, c->xtmp, h, xin, ldin, x1, ld, residual, T, h, s);
+    } else {
+      TRY(attn_out(c, w, y1k, ldk, -1.f, x1, ld, T, s));          // x <- Y1 - attention branch(x, X2^)
+    }
+  }
+  if (y1_kept) { *y1_kept = y1k; *ld_kept = ldk; }
+  return 0;
+}
+
+void* gfield(const revffn_grads* g, size_t off) { return g ? *(void* const*)((const char*)g + off) : nullptr; }
+#define GF(name) gfield(g, offsetof(revffn_grads, name))
+
+int backward_impl(revffn_ctx* c, const revffn_weights* w, const void* x1, const void* x2, const void* y1, i64 ldy,
+                  const void* dy1, const void* dy2, void* dx1, void* dx2, const revffn_grads* g, int B, int S,
+                  i64 ld, bool reuse_moe, hipStream_t s) {
+  const revffn_config& f = c->cfg;
+  const int T = B * S, d = f.d_model, h = d / 2, E = f.n_experts, k = f.top_k, I = f.d_expert, Is = f.d_shared;
+  const int N = T * k, E1 = E + (Is ? 1 : 0), dt = c->dt, es = c->es;
+  // ---- recompute the attention half at (x1, x2)
+  TRY(attn_acts(c, w, x1, ld, x2, ld, B, S, true, s));
+  if (!y1) {
+    TRY(attn_out(c, w, x1, ld, 1.f, c->y1c, h, T, s));
+    y1 = c->y1c;
+    ldy = h;
+    reuse_moe = false;
+  }
+  // ---- recompute the MoE half at the exact y1
+  if (!reuse_moe) TRY(moe_acts(c, w, y1, ldy, T, s));
+  // ---- MoE half backward: Y2 = X2 + P_dn_m(RS)
+  if (GF(pdn_m)) TRY(run_gemm(c, tn(dy2, ld, c->RS, d, GF(pdn_m), d, h, d, T), s));
+  TRY(run_gemm(c, nn(dy2, ld, w->pdn_m, d, c->dRS, d, T, d, h), s));
+  launch_moe_bwd_rows(dt, c->dRS, c->Yp, c->Ys, c->inv_map, c->wts, c->gamma, c->dYp, c->dYs, c->dw, c->dzext, T, d,
+                      k, E1, Is ? 1 : 0, s);
+  if (Is) {
+    if (GF(ws_down)) TRY(run_gemm(c, tn(c->dYs, d, c->Hs, Is, GF(ws_down), Is, d, Is, T), s));
+    TRY(run_gemm(c, nn(c->dYs, d, w->ws_down, Is, c->dHs, Is, T, Is, d), s));
+    launch_swiglu_bwd(dt, c->dHs, c->GUs, c->dGUs, T, Is, s);
+    if (GF(ws_gate_up)) TRY(run_gemm(c, tn(c->dGUs, 2 * Is, c->Um, d, GF(ws_gate_up), d, 2 * Is, d, T), s));
+    TRY(run_gemm(c, nn(c->dGUs, 2 * Is, w->ws_gate_up, d, c->dUm_sh, d, T, d, 2 * Is), s));
+  }
+  {
+    GemmArgs a = nn(c->dYp, d, w->w_down, I, c->dHh, I, N, I, d);          // dHh = dYp . Wd_e
+    a.group_mode = 1; a.n_groups = E; a.offsets = c->offsets; a.b_group_stride = (i64)d * I;
+    TRY(run_gemm(c, a, s));
+    launch_swiglu_bwd(dt, c->dHh, c->GU, c->dGU, N, I, s);
+    if (GF(w_down)) {
+      GemmArgs b = tn(c->dYp, d, c->Hh, I, GF(w_down), I, d, I, 0);        // dWd_e = dYp_e^T . Hh_e
+      b.group_mode = 2; b.n_groups = E; b.offsets = c->offsets; b.c_group_stride = (i64)d * I;
+      TRY(run_gemm(c, b, s));
+    }
+    if (GF(w_gate_up)) {
+      GemmArgs b = tn(c->dGU, 2 * I, c->Um, d, GF(w_gate_up), d, 2 * I, d, 0);   // dWgu_e = dGU_e^T . Xg_e
+      b.group_mode = 2; b.n_groups = E; b.offsets = c->offsets; b.c_group_stride = (i64)2 * I * d;
+      b.b_gather = c->row_map; b.gather_div = k;
+      TRY(run_gemm(c, b, s));
+    }
+    GemmArgs e = nn(c->dGU, 2 * I, w->w_gate_up, d, c->dXg, d, N, d, 2 * I);     // dXg = dGU . Wgu_e
+    e.group_mode = 1; e.n_groups = E; e.offsets = c->offsets; e.b_group_stride = (i64)2 * I * d;
+    TRY(run_gemm(c, e, s));
+  }
+  launch_router_bwd(c->probs, c->idx, c->wts, c->dw, c->dzext, T, E, k, E1, f.norm_topk_prob, s);
+  if (GF(w_router)) TRY(run_gemm(c, tn(c->dzext, E1, c->Um, d, GF(w_router), d, E, d, T), 0, dt, dt, s));
+  if (Is && GF(ws_gate)) TRY(run_gemm(c, tn(c->dzext + E, E1, c->Um, d, GF(ws_gate), d, 1, d, T), 0, dt, dt, s));
+  if (g && g->b_router) launch_colsum(0, c->dzext, E1, 0, nullptr, 0, nullptr, 0, g->b_router, c->partial, T, E, s);
+  launch_dum_finalize(dt, c->dXg, c->inv_map, Is ? c->dUm_sh : nullptr, c->dzext, w->w_router, w->ws_gate, c->dUm, T,
+                      d, k, E, E1, s);
+  if (GF(pup_m)) TRY(run_gemm(c, tn(c->dUm, d, c->n3, h, GF(pup_m), h, d, h, T), s));
+  TRY(run_gemm(c, nn(c->dUm, d, w->pup_m, h, c->dn3, h, T, h, d), s));
+  // g1 = dY1 + Norm'(dn3): total gradient at Y1
+  launch_rmsnorm_bwd(dt, c->dn3, h, y1, ldy, w->norm_m, dy1, ld, c->g1, h, c->rinv, T, h, f.rms_eps, s);
+  if (GF(norm_m)) launch_colsum(dt, y1, ldy, dt, c->dn3, h, c->rinv, dt, GF(norm_m), c->partial, T, h, s);
+  // ---- attention half backward: Y1 = X1 + P_dn_a(AO)
+  if (GF(pdn_a)) TRY(run_gemm(c, tn(c->g1, h, c->AO, d, GF(pdn_a), d, h, d, T), s));
+  TRY(run_gemm(c, nn(c->g1, h, w->pdn_a, d, c->dAO, d, T, d, h), s));
+  if (GF(wo)) TRY(run_gemm(c, tn(c->dAO, d, c->O, d, GF(wo), d, d, d, T), s));
+  TRY(run_gemm(c, nn(c->dAO, d, w->wo, d, c->dO, d, T, d, d), s));
+  bool done = false;
+  if (dt == 1 && c->mode == 0)
+    done = launch_attn_bwd_flash(c->Q, c->K, c->V, c->O, c->dO, c->lse, c->dvec, c->dQ, c->dK, c->dV, B, S, f.n_heads,
+                                 f.head_dim, f.causal, s) == 0;
+  if (!done)
+    launch_attn_bwd_generic(dt, c->Q, c->K, c->V, c->O, c->dO, c->lse, c->dvec, c->dQ, c->dK, c->dV, B, S, f.n_heads,
+                            f.head_dim, f.causal, s);
+  if (f.use_rope) {
+    launch_rope(dt, c->dQ, c->rope_cs, T, S, f.n_heads, f.head_dim, -1.f, s);
+    launch_rope(dt, c->dK, c->rope_cs, T, S, f.n_heads, f.head_dim, -1.f, s);
+  }
+  const void* U1 = c->U12;
+  const void* U2 = at(c->U12, (size_t)T * d, es);
+  void* dU1 = c->dU12;
+  void* dU2 = at(c->dU12, (size_t)T * d, es);
+  if (GF(wq)) TRY(run_gemm(c, tn(c->dQ, d, U1, d, GF(wq), d, d, d, T), s));
+  if (GF(wk)) TRY(run_gemm(c, tn(c->dK, d, U2, d, GF(wk), d, d, d, T), s));
+  if (GF(wv)) TRY(run_gemm(c, tn(c->dV, d, U2, d, GF(wv), d, d, d, T), s));
+  if (GF(bq) && w->bq) launch_colsum(dt, c->dQ, d, dt, nullptr, 0, nullptr, dt, GF(bq), c->partial, T, d, s);
+  if (GF(bk) && w->bk) launch_colsum(dt, c->dK, d, dt, nullptr, 0, nullptr, dt, GF(bk), c->partial, T, d, s);
+  if (GF(bv) && w->bv) launch_colsum(dt, c->dV, d, dt, nullptr, 0, nullptr, dt, GF(bv), c->partial, T, d, s);
+  TRY(run_gemm(c, nn(c->dQ, d, w->wq, d, dU1, d, T, d, d), s));
+  TRY(run_gemm(c, nn(c->dK, d, w->wk, d, dU2, d, T, d, d), s));
+  {
+    GemmArgs a = nn(c->dV, d, w->wv, d, dU2, d, T, d, d);        // dU2 += dV . Wv
+    a.resid = dU2; a.ldr = d; a.resid_sign = 1.f;
+    TRY(run_gemm(c, a, s));
+  }
+  if (GF(pup_a)) TRY(run_gemm(c, tn(c->dU12, d, c->n12, h, GF(pup_a), h, d, h, 2 * T), s));
+  TRY(run_gemm(c, nn(c->dU12, d, w->pup_a, h, c->dn12, h, 2 * T, h, d), s));
+  // dX1 = g1 + Norm'(dn1);  dX2 = dY2 + Norm'(dn2)
+  launch_rmsnorm_bwd(dt, c->dn12, h, x1, ld, w->norm_a1, c->g1, h, dx1, ld, c->rinv, T, h, f.rms_eps, s);
+  launch_rmsnorm_bwd(dt, at(c->dn12, (size_t)T * h, es), h, x2, ld, w->norm_a2, dy2, ld, dx2, ld, c->rinv + T, T, h,
+                     f.rms_eps, s);
+  if (GF(norm_a1)) launch_colsum(dt, x1, ld, dt, c->dn12, h, c->rinv, dt, GF(norm_a1), c->partial, T, h, s);
+  if (GF(norm_a2))
+    launch_colsum(dt, x2, ld, dt, at(c->dn12, (size_t)T * h, es), h, c->rinv + T, dt, GF(norm_a2), c->partial, T, h, s);
+  return 0;
+}
+
+}  // namespace
+
+// ====================================================================================
+extern "C" {
+
+size_t revffn_workspace_bytes(const revffn_config* cfg, int32_t max_B, int32_t max_S) {
+  if (check_cfg(cfg) || max_B < 1 || max_S < 1) return 0;
+  revffn_ctx tmp;
+  memset(&tmp, 0, sizeof(tmp));
+  tmp.cfg = *cfg;
+  tmp.dt = cfg->dtype;
+  tmp.es = cfg->dtype == REVFFN_BF16 ? 2 : 4;
+  tmp.maxT = max_B * max_S;
+  return carve(&tmp, nullptr);
+}
+
+int revffn_create(revffn_ctx** out, const revffn_config* cfg, int32_t max_B, int32_t max_S) {
+  if (!out) return REVFFN_ENULL;
+  *out = nullptr;
+  int e = check_cfg(cfg);
+  if (e) return e;
+  if (max_B < 1 || max_S < 1 || (long long)max_B * max_S > (1 << 24)) return REVFFN_ESHAPE;
+  revffn_ctx* c = new (std::nothrow) revffn_ctx;
+  if (!c) return REVFFN_EWORKSPACE;
+  memset(c, 0, sizeof(*c));
+  c->cfg = *cfg;
+  c->dt = cfg->dtype;
+  c->es = cfg->dtype == REVFFN_BF16 ? 2 : 4;
+  c->maxT = max_B * max_S;
+  c->slab_bytes = carve(c, nullptr);
+  if (hipGetDevice(&c->device) != hipSuccess) { delete c; return REVFFN_EHIP; }
+  if (hipMalloc(&c->slab, c->slab_bytes) != hipSuccess) { (void)hipGetLastError(); delete c; return REVFFN_EWORKSPACE; }
+  carve(c, (char*)c->slab);
+  // rotary table: cs[s][i] = (cos, sin)(s * theta^(-2i/dh)), built in double precision on the host
+  const int half = cfg->head_dim / 2;
+  std::vector<float> tab((size_t)c->maxT * half * 2);
+  for (int sp = 0; sp < c->maxT; sp++)
+    for (int i = 0; i < half; i++) {
+      double ang = (double)sp * pow((double)cfg->rope_theta, -2.0 * i / (double)cfg->head_dim);
+      tab[((size_t)sp * half + i) * 2 + 0] = (float)cos(ang);
+      tab[((size_t)sp * half + i) * 2 + 1] = (float)sin(ang);
+    }
+  if (hipMemcpy(c->rope_cs, tab.data(), tab.size() * 4, hipMemcpyHostToDevice) != hipSuccess) {
+    (void)hipFree(c->slab);
+    delete c;
+    return REVFFN_EHIP;
+  }
+  *out = c;
+  return REVFFN_OK;
+}
+
+void revffn_destroy(revffn_ctx* c) {
+  if (!c) return;
+  if (c->slab) (void)hipFree(c->slab);
+  delete c;
+}
+
+int revffn_set_inv_iters(revffn_ctx* c, int32_t n) {
+  if (!c) return REVFFN_ENULL;
+  if (n < 0 || n > 1024) return REVFFN_EINVAL;
+  c->cfg.n_inv_iters = n;
+  return 0;
+}
+int revffn_enable_taps(revffn_ctx* c, int32_t on) {
+  if (!c) return REVFFN_ENULL;
+  c->taps = on ? 1 : 0;
+  return 0;
+}
+int revffn_set_kernel_mode(revffn_ctx* c, int32_t mode) {
+  if (!c) return REVFFN_ENULL;
+  if (mode != 0 && mode != 1) return REVFFN_EINVAL;
+  c->mode = mode;
+  return 0;
+}
+
+int revffn_forward(revffn_ctx* c, const revffn_weights* w, const void* x1, const void* x2, void* y1, void* y2,
+                   int32_t B, int32_t S, int64_t ld, void* stream) {
+  TRY(check_call(c, w, B, S, ld));
+  if (!x1 || !x2 || !y1 || !y2) return REVFFN_ENULL;
+  return forward_impl(c, w, x1, x2, y1, y2, B, S, ld, (hipStream_t)stream);
+}
+
+int revffn_inverse(revffn_ctx* c, const revffn_weights* w, const void* y1, const void* y2, void* x1, void* x2,
+                   int32_t B, int32_t S, int64_t ld, float* residual, void* stream) {
+  TRY(check_call(c, w, B, S, ld));
+  if (!x1 || !x2 || !y1 || !y2) return REVFFN_ENULL;
+  return inverse_impl(c, w, y1, y2, x1, x2, B, S, ld, residual, (hipStream_t)stream, nullptr, nullptr);
+}
+
+int revffn_backward(revffn_ctx* c, const revffn_weights* w, const void* x1, const void* x2, const void* y1,
+                    const void* dy1, const void* dy2, void* dx1, void* dx2, const revffn_grads* g, int32_t B,
+                    int32_t S, int64_t ld, void* stream) {
+  TRY(check_call(c, w, B, S, ld));
+  if (!x1 || !x2 || !dy1 || !dy2 || !dx1 || !dx2) return REVFFN_ENULL;
+  return backward_impl(c, w, x1, x2, y1, ld, dy1, dy2, dx1, dx2, g, B, S, ld, false, (hipStream_t)stream);
+}
+
+int revffn_stack_forward(revffn_ctx* c, const revffn_weights* w, int32_t n_blocks, const void* x1, const void* x2,
+                         void* y1, void* y2, int32_t B, int32_t S, int64_t ld, void* stream) {
+  if (n_blocks < 1) return REVFFN_EINVAL;
+  if (!c || !w) return REVFFN_ENULL;
+  for (int l = 0; l < n_blocks; l++) TRY(check_call(c, w + l, B, S, ld));
+  if (!x1 || !x2 || !y1 || !y2) return REVFFN_ENULL;
+  for (int l = 0; l < n_blocks; l++) {
+    TRY(forward_impl(c, w + l, l == 0 ? x1 : y1, l == 0 ? x2 : y2, y1, y2, B, S, ld, (hipStream_t)stream));
+  }
+  return 0;
+}
+
+int revffn_stack_backward(revffn_ctx* c, const revffn_weights* w, const revffn_grads* g, int32_t n_blocks, void* y1,
+                          void* y2, void* dy1, void* dy2, int32_t B, int32_t S, int64_t ld, void* stream) {
+  if (n_blocks < 1) return REVFFN_EINVAL;
+  if (!c || !w) return REVFFN_ENULL;
+  for (int l = 0; l < n_blocks; l++) TRY(check_call(c, w + l, B, S, ld));
+  if (!y1 || !y2 || !dy1 || !dy2) return REVFFN_ENULL;
+  hipStream_t s = (hipStream_t)stream;
+  for (int l = n_blocks - 1; l >= 0; l--) {
+    // rebuild this block's input in place; the exact Y1 survives in the workspace copy, and the MoE
+    // activations computed at it by the inverse are reused by the backward pass
+    const void* y1k = nullptr;
+    i64 ldk = 0;
+    TRY(inverse_impl(c, w + l, y1, y2, y1, y2, B, S, ld, nullptr, s, &y1k, &ldk));
+    TRY(backward_impl(c, w + l, y1, y2, y1k, ldk, dy1, dy2, dy1, dy2, g ? g + l : nullptr, B, S, ld, true, s));
+  }
+  return 0;
+}
+
+int revffn_get_routing(revffn_ctx* c, int32_t* idx, float* wts, int32_t* counts, int32_t* offsets, int32_t* row_map,
+                       void* stream) {
+  if (!c) return REVFFN_ENULL;
+  if (c->lastT <= 0) return REVFFN_EINVAL;
+  hipStream_t s = (hipStream_t)stream;
+  const size_t N = (size_t)c->lastT * c->cfg.top_k, E = c->cfg.n_experts;
+  hipError_t e = hipSuccess;
+  if (idx && e == hipSuccess) e = hipMemcpyAsync(idx, c->idx, N * 4, hipMemcpyDeviceToDevice, s);
+  if (wts && e == hipSuccess) e = hipMemcpyAsync(wts, c->wts, N * 4, hipMemcpyDeviceToDevice, s);
+  if (counts && e == hipSuccess) e = hipMemcpyAsync(counts, c->counts, E * 4, hipMemcpyDeviceToDevice, s);
+  if (offsets && e == hipSuccess) e = hipMemcpyAsync(offsets, c->offsets, (E + 1) * 4, hipMemcpyDeviceToDevice, s);
+  if (row_map && e == hipSuccess) e = hipMemcpyAsync(row_map, c->row_map, N * 4, hipMemcpyDeviceToDevice, s);
+  return e == hipSuccess ? 0 : REVFFN_EHIP;
+}
+
+int revffn_get_branch(revffn_ctx* c, int32_t which, float* dst, void* stream) {
+  if (!c || !dst) return REVFFN_ENULL;
+  if (!c->taps || c->lastT <= 0 || (which != 0 && which != 1)) return REVFFN_EINVAL;
+  size_t bytes = (size_t)c->lastT * (c->cfg.d_model / 2) * 4;
+  hipError_t e = hipMemcpyAsync(dst, which == 0 ? c->tapA : c->tapM, bytes, hipMemcpyDeviceToDevice, (hipStream_t)stream);
+  return e == hipSuccess ? 0 : REVFFN_EHIP;
+}
+
+const char* revffn_strerror(int code) {
+  switch (code) {
+    case REVFFN_OK: return "ok";
+    case REVFFN_EINVAL: return "invalid configuration value";
+    case REVFFN_ESHAPE: return "batch, sequence length or row stride out of range for this context";
+    case REVFFN_ENULL: return "required pointer is NULL";
+    case REVFFN_EWORKSPACE: return "workspace allocation failed";
+    case REVFFN_EHIP: return "HIP runtime call failed";
+    case REVFFN_EUNSUPPORTED: return "request not implemented by this build";
+    default: return "unknown error";
+  }
+}
+
+}  // extern "C"

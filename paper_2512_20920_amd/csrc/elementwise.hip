@@ -1,0 +1,277 @@
+// Memory-bound kernels of the RevFFN block: RMSNorm (Norm of Eq. 1-2) forward and
+// backward, rotary encoding, SwiGLU, row gathers/copies, deterministic column sums.
+#include "kernels.h"
+
+#define DISPATCH_DT(dt, ...)                                  \
+  do {                                                        \
+    if ((dt) == 0) { typedef float T; __VA_ARGS__; }          \
+    else { typedef bf16 T; __VA_ARGS__; }                     \
+  } while (0)
+
+// ---------------------------------------------------------------------------------
+// RMSNorm forward: one wave per token row.
+// ---------------------------------------------------------------------------------
+template <class T>
+__global__ void __launch_bounds__(256) rmsnorm_fwd_k(const T* __restrict__ x, i64 ldx, const T* __restrict__ g,
+                                                     T* __restrict__ out, i64 ldo, int rows, int h, float eps) {
+  int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  int lane = threadIdx.x & 63;
+  if (row >= rows) return;
+  const T* xr = x + (i64)row * ldx;
+  float ss = 0.f;
+  for (int j = lane; j < h; j += 64) { float v = to_f(xr[j]); ss += v * v; }
+  ss = wave_sum(ss);
+  float r = 1.0f / sqrtf(ss / (float)h + eps);
+  T* orow = out + (i64)row * ldo;
+  for (int j = lane; j < h; j += 64) orow[j] = from_f<T>(to_f(xr[j]) * r * to_f(g[j]));
+}
+
+void launch_rmsnorm_fwd(int dt, const void* x, i64 ldx, const void* g, void* out, i64 ldo, int rows, int h,
+                        float eps, hipStream_t s) {
+  if (rows <= 0) return;
+  DISPATCH_DT(dt, hipLaunchKernelGGL(rmsnorm_fwd_k<T>, dim3(cdiv(rows, 4)), dim3(256), 0, s, (const T*)x, ldx,
+                                     (const T*)g, (T*)out, ldo, rows, h, eps));
+}
+
+// RMSNorm backward for the input:  dx = r*(g.dy) - x*r^3*mean_j(x_j g_j dy_j), plus an
+// optional base term (the residual path of Eq. 1-2).  1/rms is kept per row.
+template <class T>
+__global__ void __launch_bounds__(256) rmsnorm_bwd_k(const T* __restrict__ dy, i64 ldd, const T* __restrict__ x,
+                                                     i64 ldx, const T* __restrict__ g, const T* base, i64 ldb,
+                                                     T* dx, i64 ldo, float* __restrict__ rinv, int rows, int h,
+                                                     float eps) {
+  int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  int lane = threadIdx.x & 63;
+  if (row >= rows) return;
+  const T* xr = x + (i64)row * ldx;
+  const T* dr = dy + (i64)row * ldd;
+  float ss = 0.f, sd = 0.f;
+  for (int j = lane; j < h; j += 64) {
+    float v = to_f(xr[j]);
+    ss += v * v;
+    sd += v * to_f(g[j]) * to_f(dr[j]);
+  }
+  ss = wave_sum(ss);
+  sd = wave_sum(sd);
+  float r = 1.0f / sqrtf(ss / (float)h + eps);
+  float c = r * r * r * sd / (float)h;
+  if (lane == 0) rinv[row] = r;
+  for (int j = lane; j < h; j += 64) {
+    float v = r * to_f(g[j]) * to_f(dr[j]) - to_f(xr[j]) * c;
+    if (base) v += to_f(base[(i64)row * ldb + j]);
+    dx[(i64)row * ldo + j] = from_f<T>(v);
+  }
+}
+
+void launch_rmsnorm_bwd(int dt, const void* dy, i64 ldd, const void* x, i64 ldx, const void* g, const void* base,
+                        i64 ldb, void* dx, i64 ldo, float* rinv, int rows, int h, float eps, hipStream_t s) {
+  if (rows <= 0) return;
+  DISPATCH_DT(dt, hipLaunchKernelGGL(rmsnorm_bwd_k<T>, dim3(cdiv(rows, 4)), dim3(256), 0, s, (const T*)dy, ldd,
+                                     (const T*)x, ldx, (const T*)g, (const T*)base, ldb, (T*)dx, ldo, rinv, rows,
+                                     h, eps));
+}
+
+// ---------------------------------------------------------------------------------
+// Deterministic column sum in two stages (used for gain, bias and router-bias gradients).
+// Stage 1: block (column tile of 64, row chunk c) -> partial[c][col]; stage 2 adds the
+// chunks in index order.
+// ---------------------------------------------------------------------------------
+#define COLSUM_CHUNK 256
+size_t colsum_partial_floats(int rows, int cols) { return (size_t)cdiv(rows > 0 ? rows : 1, COLSUM_CHUNK) * cols; }
+
+template <class TA, class TB>
+__global__ void __launch_bounds__(256) colsum1_k(const TA* __restrict__ a, i64 lda, const TB* __restrict__ b,
+                                                 i64 ldb, const float* __restrict__ sc,
+                                                 float* __restrict__ partial, int rows, int cols) {
+  __shared__ float red[4][64];
+  int c = blockIdx.x * 64 + (threadIdx.x & 63);
+  int q = threadIdx.x >> 6;
+  int r0 = blockIdx.y * COLSUM_CHUNK;
+  int r1 = min(rows, r0 + COLSUM_CHUNK);
+  float acc = 0.f;
+  if (c < cols) {
+    for (int t = r0 + q; t < r1; t += 4) {
+      float v = to_f(a[(i64)t * lda + c]);
+      if (b) v *= to_f(b[(i64)t * ldb + c]);
+      if (sc) v *= sc[t];
+      acc += v;
+    }
+  }
+  red[q][threadIdx.x & 63] = acc;
+  __syncthreads();
+  if (q == 0 && c < cols) {
+    float v = (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
+    partial[(i64)blockIdx.y * cols + c] = v;
+  }
+}
+template <class TO>
+__global__ void colsum2_k(const float* __restrict__ partial, TO* __restrict__ out, int chunks, int cols) {
+  int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= cols) return;
+  float acc = 0.f;
+  for (int i = 0; i < chunks; i++) acc += partial[(i64)i * cols + c];
+  out[c] = from_f<TO>(acc);
+}
+
+template <class TA, class TB>
+static void colsum_go(const void* a, i64 lda, const void* b, i64 ldb, const float* sc, int tout, void* out,
+                      float* partial, int rows, int cols, hipStream_t s) {
+  int chunks = cdiv(rows > 0 ? rows : 1, COLSUM_CHUNK);
+  hipLaunchKernelGGL((colsum1_k<TA, TB>), dim3(cdiv(cols, 64), chunks), dim3(256), 0, s, (const TA*)a, lda,
+                     (const TB*)b, ldb, sc, partial, rows, cols);
+  if (tout == 0)
+    hipLaunchKernelGGL(colsum2_k<float>, dim3(cdiv(cols, 256)), dim3(256), 0, s, partial, (float*)out, chunks, cols);
+  else
+    hipLaunchKernelGGL(colsum2_k<bf16>, dim3(cdiv(cols, 256)), dim3(256), 0, s, partial, (bf16*)out, chunks, cols);
+}
+
+void launch_colsum(int ta, const void* a, i64 lda, int tb, const void* b, i64 ldb, const float* sc, int tout,
+                   void* out, float* partial, int rows, int cols, hipStream_t s) {
+  if (cols <= 0) return;
+  if (ta == 0 && tb == 0) colsum_go<float, float>(a, lda, b, ldb, sc, tout, out, partial, rows, cols, s);
+  else if (ta == 0 && tb == 1) colsum_go<float, bf16>(a, lda, b, ldb, sc, tout, out, partial, rows, cols, s);
+  else if (ta == 1 && tb == 0) colsum_go<bf16, float>(a, lda, b, ldb, sc, tout, out, partial, rows, cols, s);
+  else colsum_go<bf16, bf16>(a, lda, b, ldb, sc, tout, out, partial, rows, cols, s);
+}
+
+// ---------------------------------------------------------------------------------
+// Rotary encoding in place on buf[T, H*dh]; half-split pairing (i, i+dh/2); the angle of
+// pair i at sequence position s comes from a host-built table cs[s][i] = (cos, sin).
+// sign = -1 applies the inverse rotation (the backward of the forward rotation).
+// ---------------------------------------------------------------------------------
+template <class T>
+__global__ void __launch_bounds__(256) rope_k(T* __restrict__ buf, const float2* __restrict__ cs, i64 total, int S,
+                                              int H, int half, float sign) {
+  i64 e = (i64)blockIdx.x * 256 + threadIdx.x;
+  if (e >= total) return;
+  int i = (int)(e % half);
+  i64 th = e / half;          // token*H + head
+  i64 t = th / H;
+  int spos = (int)(t % S);
+  float2 c = cs[(i64)spos * half + i];
+  float sn = sign * c.y;
+  T* p = buf + th * (2 * half);
+  float a = to_f(p[i]), b = to_f(p[i + half]);
+  p[i] = from_f<T>(a * c.x - b * sn);
+  p[i + half] = from_f<T>(b * c.x + a * sn);
+}
+
+void launch_rope(int dt, void* buf, const float* cs_table, int Tn, int S, int H, int dh, float sign,
+                 hipStream_t s) {
+  i64 total = (i64)Tn * H * (dh / 2);
+  if (total <= 0) return;
+  DISPATCH_DT(dt, hipLaunchKernelGGL(rope_k<T>, dim3(cdiv(total, 256)), dim3(256), 0, s, (T*)buf,
+                                     (const float2*)cs_table, total, S, H, dh / 2, sign));
+}
+
+// ---------------------------------------------------------------------------------
+// SwiGLU: hh = silu(G) * U on gu[rows, 2I] = [G | U]; and its backward.
+// ---------------------------------------------------------------------------------
+template <class T>
+__global__ void __launch_bounds__(256) swiglu_fwd_k(const T* __restrict__ gu, T* __restrict__ hh, i64 total, int I) {
+  i64 e = (i64)blockIdx.x * 256 + threadIdx.x;
+  if (e >= total) return;
+  i64 r = e / I;
+  int j = (int)(e % I);
+  float g = to_f(gu[r * 2 * I + j]), u = to_f(gu[r * 2 * I + I + j]);
+  hh[e] = from_f<T>(g * sigmoid_f(g) * u);
+}
+template <class T>
+__global__ void __launch_bounds__(256) swiglu_bwd_k(const T* __restrict__ dhh, const T* __restrict__ gu,
+                                                    T* __restrict__ dgu, i64 total, int I) {
+  i64 e = (i64)blockIdx.x * 256 + threadIdx.x;
+  if (e >= total) return;
+  i64 r = e / I;
+  int j = (int)(e % I);
+  float g = to_f(gu[r * 2 * I + j]), u = to_f(gu[r * 2 * I + I + j]);
+  float dh = to_f(dhh[e]);
+  float sg = sigmoid_f(g);
+  dgu[r * 2 * I + j] = from_f<T>(dh * u * sg * (1.f + g * (1.f - sg)));
+  dgu[r * 2 * I + I + j] = from_f<T>(dh * g * sg);
+}
+void launch_swiglu_fwd(int dt, const void* gu, void* hh, i64 rows, int I, hipStream_t s) {
+  i64 total = rows * I;
+  if (total <= 0) return;
+  DISPATCH_DT(dt, hipLaunchKernelGGL(swiglu_fwd_k<T>, dim3(cdiv(total, 256)), dim3(256), 0, s, (const T*)gu,
+                                     (T*)hh, total, I));
+}
+void launch_swiglu_bwd(int dt, const void* dhh, const void* gu, void* dgu, i64 rows, int I, hipStream_t s) {
+  i64 total = rows * I;
+  if (total <= 0) return;
+  DISPATCH_DT(dt, hipLaunchKernelGGL(swiglu_bwd_k<T>, dim3(cdiv(total, 256)), dim3(256), 0, s, (const T*)dhh,
+                                     (const T*)gu, (T*)dgu, total, I));
+}
+
+// ---------------------------------------------------------------------------------
+// Row gather (dst[r] = src[row_map[r] / div]) and strided row copy.
+// ---------------------------------------------------------------------------------
+template <class T>
+__global__ void __launch_bounds__(256) gather_rows_k(const T* __restrict__ src, const int* __restrict__ row_map,
+                                                     int div, T* __restrict__ dst, int rows, int cols) {
+  int r = blockIdx.x;
+  if (r >= rows) return;
+  const T* sp = src + (i64)(row_map[r] / div) * cols;
+  T* dp = dst + (i64)r * cols;
+  for (int c = threadIdx.x; c < cols; c += 256) dp[c] = sp[c];
+}
+void launch_gather_rows(int dt, const void* src, const int* row_map, int div, void* dst, int rows, int cols,
+                        hipStream_t s) {
+  if (rows <= 0) return;
+  DISPATCH_DT(dt, hipLaunchKernelGGL(gather_rows_k<T>, dim3(rows), dim3(256), 0, s, (const T*)src, row_map, div,
+                                     (T*)dst, rows, cols));
+}
+template <class T>
+__global__ void __launch_bounds__(256) copy_rows_k(const T* __restrict__ src, i64 lds_, T* __restrict__ dst, i64 ldd,
+                                                   int rows, int cols) {
+  i64 e = (i64)blockIdx.x * 256 + threadIdx.x;
+  if (e >= (i64)rows * cols) return;
+  i64 r = e / cols;
+  int c = (int)(e % cols);
+  dst[r * ldd + c] = src[r * lds_ + c];
+}
+void launch_copy_rows(int dt, const void* src, i64 lds_, void* dst, i64 ldd, int rows, int cols, hipStream_t s) {
+  i64 total = (i64)rows * cols;
+  if (total <= 0) return;
+  DISPATCH_DT(dt, hipLaunchKernelGGL(copy_rows_k<T>, dim3(cdiv(total, 256)), dim3(256), 0, s, (const T*)src, lds_,
+                                     (T*)dst, ldd, rows, cols));
+}
+
+__global__ void fill_u32_k(uint32_t* p, uint32_t v, int n) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+void launch_fill_u32(uint32_t* p, uint32_t v, int n, hipStream_t s) {
+  if (n <= 0) return;
+  hipLaunchKernelGGL(fill_u32_k, dim3(cdiv(n, 256)), dim3(256), 0, s, p, v, n);
+}
+
+// res = max |a - b| over all elements (non-negative floats compare like their bit patterns, so
+// an integer atomic max is exact and order-independent); then dst = a.
+template <class T>
+__global__ void __launch_bounds__(256) absdiff_max_copy_k(const T* __restrict__ a, i64 lda, const T* b, i64 ldb,
+                                                          T* dst, i64 ldd, float* res, int rows, int cols) {
+  __shared__ float red[4];
+  i64 e = (i64)blockIdx.x * 256 + threadIdx.x;
+  float m = 0.f;
+  if (e < (i64)rows * cols) {
+    i64 r = e / cols;
+    int c = (int)(e % cols);
+    T av = a[r * lda + c];
+    m = fabsf(to_f(av) - to_f(b[r * ldb + c]));
+    dst[r * ldd + c] = av;
+  }
+  m = wave_max(m);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    m = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    atomicMax((unsigned int*)res, __float_as_uint(m));
+  }
+}
+void launch_absdiff_max_copy(int dt, const void* a, i64 lda, const void* b, i64 ldb, void* dst, i64 ldd,
+                             float* res, int rows, int cols, hipStream_t s) {
+  i64 total = (i64)rows * cols;
+  if (total <= 0) return;
+  DISPATCH_DT(dt, hipLaunchKernelGGL(absdiff_max_copy_k<T>, dim3(cdiv(total, 256)), dim3(256), 0, s, (const T*)a,
+                                     lda, (const T*)b, ldb, (T*)dst, ldd, res, rows, cols));
+}

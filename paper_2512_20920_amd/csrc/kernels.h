@@ -1,0 +1,102 @@
+// Internal launcher interface between the C-ABI layer and the HIP kernels.
+// dt: 0 = float32, 1 = bfloat16 element type of streams / weights / activations.
+#pragma once
+#include "common.h"
+
+// One GEMM problem  C[M,N] = epilogue( sum_k A(m,k) * B(k,n) ).
+// Operands are row-major matrices RA / RB addressed through a transpose flag:
+//   a_trans = 0: A(m,k) = RA[row(m)*lda + k]      a_trans = 1: A(m,k) = RA[row(k)*lda + m]
+//   b_trans = 0: B(k,n) = RB[n*ldb + k]  ([out,in] weight)   b_trans = 1: B(k,n) = RB[row(k)*ldb + n]
+// row(i) = i, or gather[i] / gather_div when a gather list is given (a_gather acts on
+// the RA row index, b_gather on the RB row index when b_trans = 1).
+// Epilogue:  v = acc * (row_scale ? row_scale[m] : 1) + (bias ? bias[n] : 0);
+//            if (tap) tap[m*ldtap+n] = v;
+//            if (resid) v = resid[m*ldr+n] + resid_sign * v;      C[m*ldc+n] = v
+// Grouping (routed experts):
+//   group_mode 1: rows are partitioned by offsets[]; m-tiles come from a device tile
+//                 list (tile_group/tile_m0, built for tile height tile_bm); B of group g is
+//                 RB + g*b_group_stride.  M is ignored (rows are absolute permuted rows).
+//   group_mode 2: the k range of group g is [offsets[g], offsets[g+1]); C of group g is
+//                 C + g*c_group_stride (written with zeros when the range is empty).
+struct GemmArgs {
+  const void* A = nullptr; const void* B = nullptr; void* C = nullptr;
+  int M = 0, N = 0, K = 0;
+  i64 lda = 0, ldb = 0, ldc = 0;
+  int a_trans = 0, b_trans = 0;
+  const int* a_gather = nullptr; const int* b_gather = nullptr; int gather_div = 1;
+  const float* row_scale = nullptr; const void* bias = nullptr;
+  const void* resid = nullptr; i64 ldr = 0; float resid_sign = 1.f;
+  float* tap = nullptr; i64 ldtap = 0;
+  int group_mode = 0; int n_groups = 1; const int* offsets = nullptr;
+  const int* tile_group = nullptr; const int* tile_m0 = nullptr; int max_tiles = 0; int tile_bm = 0;
+  i64 b_group_stride = 0, c_group_stride = 0;
+};
+
+// element types of A, B, C: 0 = f32, 1 = bf16.  bias and resid have C's... no: the
+// storage dtype `dt` of the call (bias/resid are streams or weights).
+struct GemmTypes { int ta, tb, tc, tside; };
+
+int launch_gemm_generic(const GemmArgs& g, GemmTypes t, hipStream_t s);
+// bf16 x bf16 MFMA path; returns 1 if the problem does not meet its alignment rules
+// (nothing launched), 0 if launched.
+int launch_gemm_mfma(const GemmArgs& g, GemmTypes t, hipStream_t s);
+
+// ---- normalisation / element-wise ------------------------------------------------
+void launch_rmsnorm_fwd(int dt, const void* x, i64 ldx, const void* g, void* out, i64 ldo,
+                        int rows, int h, float eps, hipStream_t s);
+// dx = base + rmsnorm_bwd(dy; x, g);  rinv[rows] receives 1/rms per row (for the gain gradient)
+void launch_rmsnorm_bwd(int dt, const void* dy, i64 ldd, const void* x, i64 ldx, const void* g,
+                        const void* base, i64 ldb, void* dx, i64 ldo, float* rinv,
+                        int rows, int h, float eps, hipStream_t s);
+// out[j] = sum_t a[t*lda+j] * (b ? b[t*ldb+j] : 1) * (sc ? sc[t] : 1); ta/tb/tout element types.
+// partial must hold >= colsum_partial_floats(rows, cols) floats.
+size_t colsum_partial_floats(int rows, int cols);
+void launch_colsum(int ta, const void* a, i64 lda, int tb, const void* b, i64 ldb, const float* sc,
+                   int tout, void* out, float* partial, int rows, int cols, hipStream_t s);
+void launch_rope(int dt, void* buf, const float* cs_table, int T, int S, int H, int dh, float sign,
+                 hipStream_t s);
+void launch_swiglu_fwd(int dt, const void* gu, void* hh, i64 rows, int I, hipStream_t s);
+void launch_swiglu_bwd(int dt, const void* dhh, const void* gu, void* dgu, i64 rows, int I, hipStream_t s);
+void launch_gather_rows(int dt, const void* src, const int* row_map, int div, void* dst, int rows, int cols,
+                        hipStream_t s);
+void launch_copy_rows(int dt, const void* src, i64 lds_, void* dst, i64 ldd, int rows, int cols, hipStream_t s);
+// res[0] = max |a - b| (bitwise max of non-negative floats; res must be zeroed first) ; dst = a
+void launch_fill_u32(uint32_t* p, uint32_t v, int n, hipStream_t s);
+void launch_absdiff_max_copy(int dt, const void* a, i64 lda, const void* b, i64 ldb, void* dst, i64 ldd,
+                             float* res, int rows, int cols, hipStream_t s);
+
+// ---- routing ---------------------------------------------------------------------
+// logits from the folded fp32 router matrix wrp [E1,h] (E1 = E (+1: shared gate row)).
+void launch_router(int dt, const void* y1, i64 ld, const void* gain, const float* wrp, const float* b_router,
+                   float* probs, int* idx, float* wts, float* gamma, int T, int h, int E, int k, int has_gate,
+                   int norm_topk, float eps, hipStream_t s);
+// counts/offsets/row_map/inv_map and the two m-tile lists (tile heights bm_a, bm_b)
+void launch_permute(const int* idx, int T, int k, int E, int* counts, int* offsets, int* row_map, int* inv_map,
+                    int* tile_group_a, int* tile_m0_a, int max_tiles_a, int bm_a,
+                    int* tile_group_b, int* tile_m0_b, int max_tiles_b, int bm_b, hipStream_t s);
+void launch_combine(int dt, const void* yp, const int* inv_map, const float* wts, const void* ys,
+                    const float* gamma, void* rs, int T, int d, int k, hipStream_t s);
+void launch_moe_bwd_rows(int dt, const void* drs, const void* yp, const void* ys, const int* inv_map,
+                         const float* wts, const float* gamma, void* dyp, void* dys, float* dw, float* dzext,
+                         int T, int d, int k, int E1, int has_gate, hipStream_t s);
+void launch_router_bwd(const float* probs, const int* idx, const float* wts, const float* dw, float* dzext,
+                       int T, int E, int k, int E1, int norm_topk, hipStream_t s);
+void launch_dum_finalize(int dt, const void* dxg, const int* inv_map, const void* dum_sh, const float* dzext,
+                         const void* w_router, const void* ws_gate, void* dum, int T, int d, int k, int E,
+                         int E1, hipStream_t s);
+
+// ---- attention -------------------------------------------------------------------
+// Q,K,V,O,dO,...: [T, H*dh] token-major, head hh occupies columns hh*dh..; lse/dvec: [B,H,S] float
+void launch_attn_fwd_generic(int dt, const void* q, const void* k, const void* v, void* o, float* lse,
+                             int B, int S, int H, int dh, int causal, hipStream_t s);
+void launch_attn_dvec(int dt, const void* o, const void* d_o, float* dvec, int B, int S, int H, int dh,
+                      hipStream_t s);
+void launch_attn_bwd_generic(int dt, const void* q, const void* k, const void* v, const void* o,
+                             const void* d_o, const float* lse, float* dvec, void* dq, void* dk, void* dv,
+                             int B, int S, int H, int dh, int causal, hipStream_t s);
+// MFMA flash kernels (bf16, dh = 128); return 1 if unsupported shape.
+int launch_attn_fwd_flash(const void* q, const void* k, const void* v, void* o, float* lse,
+                          int B, int S, int H, int dh, int causal, hipStream_t s);
+int launch_attn_bwd_flash(const void* q, const void* k, const void* v, const void* o, const void* d_o,
+                          const float* lse, float* dvec, void* dq, void* dk, void* dv,
+                          int B, int S, int H, int dh, int causal, hipStream_t s);

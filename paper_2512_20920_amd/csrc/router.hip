@@ -1,0 +1,330 @@
+// Routing of the MoE half (MLP_pt of section 3.2 read as a Qwen2-MoE sparse block):
+// router logits, softmax, top-k, per-expert offsets and the token permutation, the
+// weighted combine, and the element-wise parts of their backward passes.
+// Everything here is deterministic: integer results depend only on the logits' bits.
+#include "kernels.h"
+
+#define DISPATCH_DT(dt, ...)                                  \
+  do {                                                        \
+    if ((dt) == 0) { typedef float T; __VA_ARGS__; }          \
+    else { typedef bf16 T; __VA_ARGS__; }                     \
+  } while (0)
+
+// ---------------------------------------------------------------------------------
+// Router.  The logits are z = W_r (P_up_m Norm(Y1)) + b.  They are evaluated as
+// (W_r P_up_m) Norm(Y1) with the product matrix wrp held in fp32 and Norm(Y1) recomputed in
+// fp32 from the stored Y1, so the selection depends only on the bits of Y1 and the weights,
+// not on the rounding of the bf16 intermediate P_up_m Norm(Y1).  Row E of wrp (optional) is
+// the shared expert's gate vector folded the same way.
+// One wave per token.  Outputs: probs[T,E] (softmax over all experts), idx/wts[T,k] (slots
+// by descending logit, equal logits -> lower expert index), gamma[T] = sigmoid(gate logit).
+// ---------------------------------------------------------------------------------
+#define ROUTER_MAX_E1 257
+template <class T>
+__global__ void __launch_bounds__(256) router_k(const T* __restrict__ y1, i64 ld, const T* __restrict__ gain,
+                                                const float* __restrict__ wrp, const float* __restrict__ b_router,
+                                                float* __restrict__ probs, int* __restrict__ idx,
+                                                float* __restrict__ wts, float* __restrict__ gamma, int Tn, int h,
+                                                int E, int k, int has_gate, int norm_topk, float eps) {
+  extern __shared__ float sm[];          // per wave: n[h] then z[E1]
+  const int E1 = E + (has_gate ? 1 : 0);
+  const int wv = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  float* nv = sm + (size_t)wv * (h + E1);
+  float* z = nv + h;
+  const int t = blockIdx.x * 4 + wv;
+  if (t >= Tn) return;                   // whole wave leaves; no block barriers below
+  const T* yr = y1 + (i64)t * ld;
+  float ss = 0.f;
+  for (int j = lane; j < h; j += 64) { float v = to_f(yr[j]); ss += v * v; }
+  ss = wave_sum(ss);
+  const float r = 1.0f / sqrtf(ss / (float)h + eps);
+  for (int j = lane; j < h; j += 64) nv[j] = to_f(yr[j]) * r * to_f(gain[j]);
+  // (same-wave LDS traffic is ordered; no barrier needed between the phases of one wave)
+  for (int e = 0; e < E1; e++) {
+    const float* wr = wrp + (size_t)e * h;
+    float acc = 0.f;
+    for (int j = lane; j < h; j += 64) acc += nv[j] * wr[j];
+    acc = wave_sum(acc);
+    if (lane == 0) z[e] = acc + ((e < E && b_router) ? b_router[e] : 0.f);
+  }
+  __builtin_amdgcn_wave_barrier();
+  // softmax over the E routed logits
+  float mx = -INFINITY;
+  for (int e = lane; e < E; e += 64) mx = fmaxf(mx, z[e]);
+  mx = wave_max(mx);
+  float sum = 0.f;
+  for (int e = lane; e < E; e += 64) sum += __expf(z[e] - mx);
+  sum = wave_sum(sum);
+  const float inv = 1.0f / sum;
+  for (int e = lane; e < E; e += 64) probs[(i64)t * E + e] = __expf(z[e] - mx) * inv;
+  // top-k by k rounds of (value desc, index asc) arg-max; a chosen logit is overwritten by -inf
+  __builtin_amdgcn_wave_barrier();
+  float wsum = 0.f;
+  float myw = 0.f;                        // lane s keeps the weight of slot s
+  for (int s = 0; s < k; s++) {
+    float bv = -INFINITY;
+    int bi = 0x7fffffff;
+    for (int e = lane; e < E; e += 64) {
+      float v = z[e];
+      if (v > bv || (v == bv && e < bi)) { bv = v; bi = e; }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      float ov = __shfl_xor(bv, o, WAVE);
+      int oi = __shfl_xor(bi, o, WAVE);
+      if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+    }
+    // the comparator is a total order, so every lane now holds the same (bv, bi)
+    float p = __expf(bv - mx) * inv;
+    wsum += p;
+    if (lane == s) myw = p;
+    if (lane == 0) { idx[(i64)t * k + s] = bi; z[bi] = -INFINITY; }
+    __builtin_amdgcn_wave_barrier();      // LDS traffic of one wave is executed in order
+  }
+  if (lane < k) wts[(i64)t * k + lane] = norm_topk ? myw / wsum : myw;
+  if (has_gate && lane == 0) gamma[t] = sigmoid_f(z[E]);
+}
+
+void launch_router(int dt, const void* y1, i64 ld, const void* gain, const float* wrp, const float* b_router,
+                   float* probs, int* idx, float* wts, float* gamma, int Tn, int h, int E, int k, int has_gate,
+                   int norm_topk, float eps, hipStream_t s) {
+  if (Tn <= 0) return;
+  size_t smem = (size_t)4 * (h + E + 1) * sizeof(float);
+  DISPATCH_DT(dt, hipLaunchKernelGGL(router_k<T>, dim3(cdiv(Tn, 4)), dim3(256), smem, s, (const T*)y1, ld,
+                                     (const T*)gain, wrp, b_router, probs, idx, wts, gamma, Tn, h, E, k, has_gate,
+                                     norm_topk, eps));
+}
+
+// ---------------------------------------------------------------------------------
+// Permutation.  One workgroup of 16 waves; wave w owns the contiguous slice of the T*k
+// (token, slot) entries [w*per, (w+1)*per).  Pass 1 counts per (wave, expert); the prefix
+// over waves gives each wave its first row inside every expert; pass 2 hands out rows in
+// entry order, which keeps (token, slot) order inside an expert (a stable grouping).
+// Also emits the m-tile lists used by the grouped GEMMs: tile i covers rows
+// [tile_m0[i], min(tile_m0[i]+bm, offsets[g+1])) of expert g = tile_group[i]; unused = -1.
+// ---------------------------------------------------------------------------------
+#define PERM_WAVES 16
+__device__ __forceinline__ void same_expert_mask(int x, bool valid, int nbits, unsigned long long& same) {
+  same = __ballot(valid);
+  for (int b = 0; b < nbits; b++) {
+    unsigned long long m = __ballot(valid && ((x >> b) & 1));
+    same &= ((x >> b) & 1) ? m : ~m;
+  }
+}
+
+__global__ void __launch_bounds__(PERM_WAVES * 64) permute_k(
+    const int* __restrict__ idx, int N, int E, int* __restrict__ counts, int* __restrict__ offsets,
+    int* __restrict__ row_map, int* __restrict__ inv_map, int* tile_group_a, int* tile_m0_a, int max_tiles_a,
+    int bm_a, int* tile_group_b, int* tile_m0_b, int max_tiles_b, int bm_b) {
+  extern __shared__ int ism[];            // cnt[PERM_WAVES][E], then off[E+1]
+  int* cnt = ism;
+  int* off = ism + PERM_WAVES * E;
+  const int wv = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const unsigned long long below = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+  int nbits = 0;
+  while ((1 << nbits) < E) nbits++;
+  for (int i = threadIdx.x; i < PERM_WAVES * E; i += blockDim.x) cnt[i] = 0;
+  __syncthreads();
+  const int per = (N + PERM_WAVES - 1) / PERM_WAVES;
+  const int lo = wv * per, hi = min(N, lo + per);
+  int* mycnt = cnt + wv * E;
+  for (int base = lo; base < hi; base += 64) {
+    int f = base + lane;
+    bool valid = f < hi;
+    int x = valid ? idx[f] : 0;
+    unsigned long long same;
+    same_expert_mask(x, valid, nbits, same);
+    if (valid && (same & below) == 0) mycnt[x] += __popcll(same);   // group leader; groups are disjoint
+  }
+  __syncthreads();
+  // exclusive prefix over waves per expert, totals, offsets
+  for (int e = threadIdx.x; e < E; e += blockDim.x) {
+    int run = 0;
+    for (int w = 0; w < PERM_WAVES; w++) { int c = cnt[w * E + e]; cnt[w * E + e] = run; run += c; }
+    counts[e] = run;
+    off[e + 1] = run;                     // totals for now
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    off[0] = 0;
+    for (int e = 0; e < E; e++) off[e + 1] += off[e];
+    for (int e = 0; e <= E; e++) offsets[e] = off[e];
+    int na = 0, nb = 0;
+    for (int e = 0; e < E; e++) {
+      for (int m = off[e]; m < off[e + 1]; m += bm_a) if (na < max_tiles_a) { tile_group_a[na] = e; tile_m0_a[na] = m; na++; }
+      for (int m = off[e]; m < off[e + 1]; m += bm_b) if (nb < max_tiles_b) { tile_group_b[nb] = e; tile_m0_b[nb] = m; nb++; }
+    }
+    for (; na < max_tiles_a; na++) { tile_group_a[na] = -1; tile_m0_a[na] = 0; }
+    for (; nb < max_tiles_b; nb++) { tile_group_b[nb] = -1; tile_m0_b[nb] = 0; }
+  }
+  __syncthreads();
+  for (int base = lo; base < hi; base += 64) {
+    int f = base + lane;
+    bool valid = f < hi;
+    int x = valid ? idx[f] : 0;
+    unsigned long long same;
+    same_expert_mask(x, valid, nbits, same);
+    int rank = __popcll(same & below);
+    int start = valid ? mycnt[x] : 0;     // every lane of a group reads before its leader updates
+    if (valid && rank == 0) mycnt[x] = start + __popcll(same);
+    if (valid) {
+      int pos = off[x] + start + rank;
+      row_map[pos] = f;
+      inv_map[f] = pos;
+    }
+  }
+}
+
+void launch_permute(const int* idx, int Tn, int k, int E, int* counts, int* offsets, int* row_map, int* inv_map,
+                    int* tile_group_a, int* tile_m0_a, int max_tiles_a, int bm_a, int* tile_group_b,
+                    int* tile_m0_b, int max_tiles_b, int bm_b, hipStream_t s) {
+  size_t smem = (size_t)(PERM_WAVES * E + E + 1) * sizeof(int);
+  hipLaunchKernelGGL(permute_k, dim3(1), dim3(PERM_WAVES * 64), smem, s, idx, Tn * k, E, counts, offsets, row_map,
+                     inv_map, tile_group_a, tile_m0_a, max_tiles_a, bm_a, tile_group_b, tile_m0_b, max_tiles_b,
+                     bm_b);
+}
+
+// ---------------------------------------------------------------------------------
+// Combine: rs[t] = sum_slot wts[t,slot] * yp[inv_map[t*k+slot]] + gamma[t] * ys[t], slots added
+// in slot order (fixed order, no atomics).
+// ---------------------------------------------------------------------------------
+template <class T>
+__global__ void __launch_bounds__(256) combine_k(const T* __restrict__ yp, const int* __restrict__ inv_map,
+                                                 const float* __restrict__ wts, const T* __restrict__ ys,
+                                                 const float* __restrict__ gamma, T* __restrict__ rs, int d, int k) {
+  const int t = blockIdx.x;
+  for (int c = threadIdx.x; c < d; c += 256) {
+    float acc = 0.f;
+    for (int s = 0; s < k; s++) {
+      int pos = inv_map[(i64)t * k + s];
+      acc += wts[(i64)t * k + s] * to_f(yp[(i64)pos * d + c]);
+    }
+    if (ys) acc += gamma[t] * to_f(ys[(i64)t * d + c]);
+    rs[(i64)t * d + c] = from_f<T>(acc);
+  }
+}
+void launch_combine(int dt, const void* yp, const int* inv_map, const float* wts, const void* ys,
+                    const float* gamma, void* rs, int Tn, int d, int k, hipStream_t s) {
+  if (Tn <= 0) return;
+  DISPATCH_DT(dt, hipLaunchKernelGGL(combine_k<T>, dim3(Tn), dim3(256), 0, s, (const T*)yp, inv_map, wts,
+                                     (const T*)ys, gamma, (T*)rs, d, k));
+}
+
+// ---------------------------------------------------------------------------------
+// Backward of the combine, one workgroup per token:
+//   dgamma = <drs, ys>, gate-logit gradient dzext[t,E] = dgamma*gamma*(1-gamma), dys = gamma*drs
+//   dw[t,slot] = <drs, yp[pos]>,  dyp[pos] = wts[t,slot]*drs
+// ---------------------------------------------------------------------------------
+template <class T>
+__global__ void __launch_bounds__(256) moe_bwd_rows_k(const T* __restrict__ drs, const T* __restrict__ yp,
+                                                      const T* __restrict__ ys, const int* __restrict__ inv_map,
+                                                      const float* __restrict__ wts, const float* __restrict__ gamma,
+                                                      T* __restrict__ dyp, T* __restrict__ dys, float* __restrict__ dw,
+                                                      float* __restrict__ dzext, int d, int k, int E1, int has_gate) {
+  __shared__ float red[4];
+  const int t = blockIdx.x;
+  const T* dr = drs + (i64)t * d;
+  if (has_gate) {
+    float g = gamma[t];
+    float acc = 0.f;
+    for (int c = threadIdx.x; c < d; c += 256) {
+      float v = to_f(dr[c]);
+      acc += v * to_f(ys[(i64)t * d + c]);
+      dys[(i64)t * d + c] = from_f<T>(g * v);
+    }
+    acc = block_sum_256(acc, red);
+    if (threadIdx.x == 0) dzext[(i64)t * E1 + (E1 - 1)] = acc * g * (1.f - g);
+  }
+  for (int s = 0; s < k; s++) {
+    int pos = inv_map[(i64)t * k + s];
+    float w = wts[(i64)t * k + s];
+    float acc = 0.f;
+    for (int c = threadIdx.x; c < d; c += 256) {
+      float v = to_f(dr[c]);
+      acc += v * to_f(yp[(i64)pos * d + c]);
+      dyp[(i64)pos * d + c] = from_f<T>(w * v);
+    }
+    acc = block_sum_256(acc, red);
+    if (threadIdx.x == 0) dw[(i64)t * k + s] = acc;
+  }
+}
+void launch_moe_bwd_rows(int dt, const void* drs, const void* yp, const void* ys, const int* inv_map,
+                         const float* wts, const float* gamma, void* dyp, void* dys, float* dw, float* dzext,
+                         int Tn, int d, int k, int E1, int has_gate, hipStream_t s) {
+  if (Tn <= 0) return;
+  DISPATCH_DT(dt, hipLaunchKernelGGL(moe_bwd_rows_k<T>, dim3(Tn), dim3(256), 0, s, (const T*)drs, (const T*)yp,
+                                     (const T*)ys, inv_map, wts, gamma, (T*)dyp, (T*)dys, dw, dzext, d, k, E1,
+                                     has_gate));
+}
+
+// ---------------------------------------------------------------------------------
+// Backward of softmax + top-k weights (the selection itself carries no gradient):
+//   dp_sel = dw                      (or (dw - sum dw*w) / sum_sel p with renormalisation)
+//   dz_j   = p_j * ([j selected] dp_j - sum_sel dp_e p_e)        for every expert j
+// One thread per token; writes columns 0..E-1 of dzext[T,E1].
+// ---------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) router_bwd_k(const float* __restrict__ probs, const int* __restrict__ idx,
+                                                    const float* __restrict__ wts, const float* __restrict__ dw,
+                                                    float* __restrict__ dzext, int Tn, int E, int k, int E1,
+                                                    int norm_topk) {
+  int t = blockIdx.x * 256 + threadIdx.x;
+  if (t >= Tn) return;
+  const float* p = probs + (i64)t * E;
+  float dps[16];
+  int sel[16];
+  float ssum = 0.f, dww = 0.f;
+  for (int s = 0; s < k; s++) {
+    sel[s] = idx[(i64)t * k + s];
+    ssum += p[sel[s]];
+    dww += dw[(i64)t * k + s] * wts[(i64)t * k + s];
+  }
+  float inner = 0.f;
+  for (int s = 0; s < k; s++) {
+    float v = dw[(i64)t * k + s];
+    if (norm_topk) v = (v - dww) / ssum;
+    dps[s] = v;
+    inner += v * p[sel[s]];
+  }
+  for (int j = 0; j < E; j++) {
+    float dp = 0.f;
+    for (int s = 0; s < k; s++) if (sel[s] == j) dp = dps[s];
+    dzext[(i64)t * E1 + j] = p[j] * (dp - inner);
+  }
+}
+void launch_router_bwd(const float* probs, const int* idx, const float* wts, const float* dw, float* dzext, int Tn,
+                       int E, int k, int E1, int norm_topk, hipStream_t s) {
+  if (Tn <= 0) return;
+  hipLaunchKernelGGL(router_bwd_k, dim3(cdiv(Tn, 256)), dim3(256), 0, s, probs, idx, wts, dw, dzext, Tn, E, k, E1,
+                     norm_topk);
+}
+
+// ---------------------------------------------------------------------------------
+// Gradient at the MoE input Um, all three sources added in a fixed order:
+//   dum[t] = dum_sh[t] (shared expert) + sum_slot dxg[pos(t,slot)] (routed experts)
+//          + sum_e dzext[t,e] * Wext[e]    (router rows, then the shared gate row)
+// ---------------------------------------------------------------------------------
+template <class T>
+__global__ void __launch_bounds__(256) dum_finalize_k(const T* __restrict__ dxg, const int* __restrict__ inv_map,
+                                                      const T* __restrict__ dum_sh, const float* __restrict__ dzext,
+                                                      const T* __restrict__ w_router, const T* __restrict__ ws_gate,
+                                                      T* __restrict__ dum, int d, int k, int E, int E1) {
+  extern __shared__ float dzs[];
+  const int t = blockIdx.x;
+  for (int e = threadIdx.x; e < E1; e += 256) dzs[e] = dzext[(i64)t * E1 + e];
+  __syncthreads();
+  for (int c = threadIdx.x; c < d; c += 256) {
+    float acc = dum_sh ? to_f(dum_sh[(i64)t * d + c]) : 0.f;
+    for (int s = 0; s < k; s++) acc += to_f(dxg[(i64)inv_map[(i64)t * k + s] * d + c]);
+    for (int e = 0; e < E; e++) acc += dzs[e] * to_f(w_router[(i64)e * d + c]);
+    if (E1 > E) acc += dzs[E] * to_f(ws_gate[c]);
+    dum[(i64)t * d + c] = from_f<T>(acc);
+  }
+}
+void launch_dum_finalize(int dt, const void* dxg, const int* inv_map, const void* dum_sh, const float* dzext,
+                         const void* w_router, const void* ws_gate, void* dum, int Tn, int d, int k, int E, int E1,
+                         hipStream_t s) {
+  if (Tn <= 0) return;
+  DISPATCH_DT(dt, hipLaunchKernelGGL(dum_finalize_k<T>, dim3(Tn), dim3(256), E1 * sizeof(float), s, (const T*)dxg,
+                                     inv_map, (const T*)dum_sh, dzext, (const T*)w_router, (const T*)ws_gate,
+                                     (T*)dum, d, k, E, E1));
+}

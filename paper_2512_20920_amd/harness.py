@@ -1,0 +1,52 @@
+"""Device-memory helpers around the binding: upload seeded host arrays, allocate gradient
+buffers, download results.  No arithmetic of the method lives here."""
+import numpy as np
+import torch
+
+from .binding import Config, WEIGHT_FIELDS
+
+F32_ONLY = ("b_router",)
+
+
+def torch_dtype(dtype):
+    return torch.bfloat16 if dtype in ("bf16", 1) else torch.float32
+
+
+def make_config(wl, causal=True, use_rope=True, norm_topk_prob=False, n_inv_iters=1,
+                rope_theta=1.0e6, rms_eps=1.0e-6, dtype=None):
+    """Config for a synth.Workload-like object (needs d_model, n_heads, ... and dtype)."""
+    dt = wl.dtype if dtype is None else dtype
+    return Config(d_model=wl.d_model, n_heads=wl.n_heads, head_dim=wl.head_dim, n_experts=wl.n_experts,
+                  top_k=wl.top_k, d_expert=wl.d_expert, d_shared=wl.d_shared,
+                  dtype=1 if dt == "bf16" else 0, causal=int(causal), use_rope=int(use_rope),
+                  norm_topk_prob=int(norm_topk_prob), n_inv_iters=n_inv_iters,
+                  rope_theta=rope_theta, rms_eps=rms_eps)
+
+
+def upload(x, dtype, device="cuda"):
+    """float64 host array (already holding storage-rounded values) -> device tensor."""
+    return torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(device).to(torch_dtype(dtype)).contiguous()
+
+
+def upload_weights(W, dtype, device="cuda"):
+    out = {}
+    for n in WEIGHT_FIELDS:
+        v = W.get(n)
+        if v is None:
+            out[n] = None
+        else:
+            out[n] = upload(v, "f32" if n in F32_ONLY else dtype, device)
+    return out
+
+
+def alloc_grads(Wdev, skip=()):
+    """A gradient buffer per present weight (filled with NaN so an unwritten one is noticed)."""
+    out = {}
+    for n in WEIGHT_FIELDS:
+        v = Wdev.get(n)
+        out[n] = None if (v is None or n in skip) else torch.full_like(v, float("nan"))
+    return out
+
+
+def download(t):
+    return t.detach().float().cpu().numpy().astype(np.float64)

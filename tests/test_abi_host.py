@@ -1,0 +1,88 @@
+"""Host-only checks of the C ABI: the library loads, exports every declared symbol, and rejects
+bad arguments with error codes before touching the GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2512_20920_amd as R
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(R.library_path()):
+        import __graft_entry__
+        __graft_entry__.build()
+    return R.load_library()
+
+
+def good_cfg(**kw):
+    base = dict(d_model=64, n_heads=4, head_dim=16, n_experts=8, top_k=2, d_expert=128, d_shared=0, dtype=0,
+                causal=1, use_rope=1, norm_topk_prob=0, n_inv_iters=1, rope_theta=1e6, rms_eps=1e-6)
+    base.update(kw)
+    return R.Config(**base)
+
+
+def test_every_declared_symbol_is_exported(lib):
+    header = open(os.path.join(ROOT, "include", "revffn.h")).read()
+    declared = set(re.findall(r"\b(revffn_[a-z_]+)\s*\(", header))
+    assert declared == set(R.EXPORTED_SYMBOLS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_struct_layouts_match_header():
+    assert ctypes.sizeof(R.Config) == 14 * 4
+    assert ctypes.sizeof(R.Weights) == 21 * ctypes.sizeof(ctypes.c_void_p)
+    assert ctypes.sizeof(R.Grads) == ctypes.sizeof(R.Weights)
+    header = open(os.path.join(ROOT, "include", "revffn.h")).read()
+    body = header[header.index("typedef struct revffn_weights {"):header.index("} revffn_weights;")]
+    order = re.findall(r"\*\s*([a-z_0-9]+)\s*[,;]", body)
+    assert tuple(order) == R.WEIGHT_FIELDS
+
+
+def test_workspace_bytes_and_bad_configs(lib):
+    cfg = good_cfg()
+    n = lib.revffn_workspace_bytes(ctypes.byref(cfg), 2, 32)
+    assert n > 0
+    assert lib.revffn_workspace_bytes(ctypes.byref(cfg), 4, 32) > n
+    bad = [dict(d_model=63), dict(n_heads=3), dict(top_k=0), dict(top_k=9), dict(n_experts=0), dict(dtype=2),
+           dict(head_dim=15, n_heads=4, d_model=60), dict(n_inv_iters=-1), dict(rope_theta=0.0), dict(d_expert=0),
+           dict(n_experts=300, top_k=2), dict(top_k=17, n_experts=32)]
+    for kw in bad:
+        c = good_cfg(**kw)
+        assert lib.revffn_workspace_bytes(ctypes.byref(c), 2, 32) == 0, kw
+        h = ctypes.c_void_p()
+        assert lib.revffn_create(ctypes.byref(h), ctypes.byref(c), 2, 32) == -1, kw
+        assert not h.value
+    h = ctypes.c_void_p()
+    assert lib.revffn_create(ctypes.byref(h), ctypes.byref(cfg), 0, 32) == -2
+    assert lib.revffn_create(None, ctypes.byref(cfg), 2, 32) == -3
+    assert lib.revffn_create(ctypes.byref(h), None, 2, 32) == -3
+
+
+def test_null_context_and_strerror(lib):
+    w = R.Weights()
+    assert lib.revffn_forward(None, ctypes.byref(w), 1, 1, 1, 1, 1, 1, 32, None) == -3
+    assert lib.revffn_inverse(None, ctypes.byref(w), 1, 1, 1, 1, 1, 1, 32, None, None) == -3
+    assert lib.revffn_backward(None, ctypes.byref(w), 1, 1, 1, 1, 1, 1, 1, None, 1, 1, 32, None) == -3
+    assert lib.revffn_get_routing(None, None, None, None, None, None, None) == -3
+    assert lib.revffn_set_inv_iters(None, 1) == -3
+    lib.revffn_destroy(None)
+    seen = set()
+    for code in range(0, -7, -1):
+        msg = R.revffn_strerror(code)
+        assert msg and msg != "unknown error"
+        seen.add(msg)
+    assert len(seen) == 7 and R.revffn_strerror(-99) == "unknown error"
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    import paper_2512_20920_amd.binding as bnd
+    monkeypatch.setattr(bnd, "_LIB", None)
+    monkeypatch.setattr(bnd, "_HERE", str(tmp_path))
+    with pytest.raises(R.RevffnError):
+        bnd.load_library()
