@@ -1,0 +1,139 @@
+#!/usr/bin/env python3
+"""Headline benchmark: one RevFFN block, forward + inverse + backward, at the Qwen1.5-MoE-A2.7B
+layer shape (batch 4 x seq 512, bf16 storage, fp32 accumulation) on ONE MI355X.
+
+A "step" is one pass of the whole hot path over one batch: revffn_forward, revffn_inverse
+(rebuilding the input from the output) and revffn_backward (recomputing activations from the
+rebuilt input, all weight gradients written).  Inputs and weights are resident in HBM before
+the timed region.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+
+
+def cpu_baseline(wl, W32, x1, x2, dy1, dy2, n_inv_iters):
+    """Time the fp64 oracle (as it stands) on the first sequence of the same batch."""
+    import numpy as np
+    from oracle import revffn_oracle as O
+    S = wl.S
+    cores = len(os.sched_getaffinity(0))
+    W = O.as_f64(W32)                         # promotion of the stored weights is not timed
+    cfg = O.Config(wl.d_model, wl.n_heads, wl.head_dim, wl.n_experts, wl.top_k, wl.d_expert, wl.d_shared,
+                   n_inv_iters=n_inv_iters)
+    a, b, ga, gb = (np.ascontiguousarray(t[:S]) for t in (x1, x2, dy1, dy2))
+    t0 = time.perf_counter()
+    y1, y2 = O.forward(a, b, W, cfg, 1, S)
+    O.grads_reconstructed(y1, y2, ga, gb, W, cfg, 1, S)
+    dt = time.perf_counter() - t0
+    return {"value": S / dt, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+            "sample": f"forward+inverse+backward of sequence 0 (B=1, S={S}) of the same batch, full-size weights, "
+                      f"numpy float64, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="qwen_b4s512")
+    ap.add_argument("--inv-iters", type=int, default=1, help="fixed-point iterations of the inverse (paper: 1)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import synth
+    import paper_2512_20920_amd as R
+    from paper_2512_20920_amd import harness as Hn
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(1)
+    wl = synth.WORKLOADS[args.workload]
+    t_setup = time.perf_counter()
+    W32 = synth.make_weights(wl, f64=False)
+    x1, x2, dy1, dy2 = synth.make_inputs(wl)
+    Wd = Hn.upload_weights(W32, wl.dtype)
+    G = Hn.alloc_grads(Wd)
+    up = lambda a: Hn.upload(a, wl.dtype)
+    x1d, x2d, dy1d, dy2d = up(x1), up(x2), up(dy1), up(dy2)
+    new = lambda: torch.empty((wl.T, wl.h), dtype=Hn.torch_dtype(wl.dtype), device="cuda")
+    y1d, y2d, r1d, r2d, dx1d, dx2d = new(), new(), new(), new(), new(), new()
+    ctx = R.Context(Hn.make_config(wl, n_inv_iters=args.inv_iters), wl.B, wl.S)
+    wstruct = R.binding._struct(R.Weights, Wd)
+    gstruct = R.binding._struct(R.Grads, G)
+    stream = torch.cuda.current_stream()
+    t_setup = time.perf_counter() - t_setup
+
+    def step():
+        R.revffn_forward(ctx, wstruct, x1d, x2d, y1d, y2d, wl.B, wl.S, wl.h, stream)
+        R.revffn_inverse(ctx, wstruct, y1d, y2d, r1d, r2d, wl.B, wl.S, wl.h, None, stream)
+        R.revffn_backward(ctx, wstruct, r1d, r2d, y1d, dy1d, dy2d, dx1d, dx2d, gstruct, wl.B, wl.S, wl.h, stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ctx.profile_enable(True)            # HIP events around every GEMM / attention launch, on this stream
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record(stream)
+    for _ in range(args.steps):
+        step()
+    e1.record(stream)
+    torch.cuda.synchronize()
+    ms_per_step = e0.elapsed_time(e1) / args.steps
+    prof = ctx.profile_read()
+    ctx.profile_enable(False)
+
+    # dominant kernel family of the timed region and its roofline
+    dom = max(prof, key=lambda k: prof[k]["ms"]) if prof else None
+    roofline = None
+    if dom:
+        p = prof[dom]
+        avg_ms = p["ms"] / p["launches"]
+        tflops = p["flops"] / p["launches"] / (avg_ms * 1e-3) / 1e12
+        gbs = p["bytes"] / p["launches"] / (avg_ms * 1e-3) / 1e9
+        # the bound is whichever roofline the kernel family's summed work sits closer to
+        if tflops / PEAK_BF16_TFLOPS >= gbs / PEAK_HBM_GBS:
+            roofline = {"bound": "mfma", "achieved": tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                        "frac": tflops / PEAK_BF16_TFLOPS}
+        else:
+            roofline = {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                        "frac": gbs / PEAK_HBM_GBS}
+        roofline.update({"kernel": dom, "launches_per_step": p["launches"] / args.steps,
+                         "avg_launch_us": avg_ms * 1e3, "share_of_step": p["ms"] / args.steps / ms_per_step,
+                         "traffic": None})
+    kernels = {k: {"ms_per_step": v["ms"] / args.steps, "launches_per_step": v["launches"] / args.steps,
+                   "tflops": v["flops"] / (v["ms"] * 1e-3) / 1e12, "gbs": v["bytes"] / (v["ms"] * 1e-3) / 1e9}
+               for k, v in prof.items()}
+
+    out = {
+        "metric": "RevFFN block fwd+inverse+bwd tokens/s at Qwen1.5-MoE shape",
+        "value": wl.T / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16" if wl.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"{wl.name}: 1 RevFFN block, d={wl.d_model}, {wl.n_heads} heads x {wl.head_dim}, "
+                               f"{wl.n_experts} experts top-{wl.top_k} I={wl.d_expert}, shared {wl.d_shared}, "
+                               f"B={wl.B} S={wl.S}, weights N(0,0.02) inputs N(0,1) seed {wl.seed}",
+                   "n_inv_iters": args.inv_iters, "setup_s": round(t_setup, 1)},
+        "roofline": roofline, "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, W32, x1, x2, dy1, dy2, args.inv_iters)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -180,6 +180,40 @@ int revffn_get_branch(revffn_ctx *ctx, int32_t which, float *dst, void *hip_stre
  * 1 = force the generic kernels (any shape, slow).  For tests. */
 int revffn_set_kernel_mode(revffn_ctx *ctx, int32_t mode);
 
+/* Kernel-level entry points for unit tests and micro-benchmarks of the two dense kernels
+ * (they need no context).  dtype as in revffn_config; kernel_mode as in
+ * revffn_set_kernel_mode.  op_gemm: C[M,N] = A . B with A(m,k) = a[m*lda+k] (a_trans=0) or
+ * a[k*lda+m] (a_trans=1), B(k,n) = b[n*ldb+k] (b_trans=0) or b[k*ldb+n] (b_trans=1); C has
+ * dtype `dtype`, or float32 if out_f32.  op_attention_*: softmax(Q K^T / sqrt(dh) + causal
+ * mask) V on q,k,v,o,d_o,dq,dk,dv laid out [B*S, H*dh] (head hh in columns hh*dh..), lse
+ * and dvec float [B,H,S]; the backward needs o and lse from the forward and uses dvec as
+ * scratch.  Return 0, REVFFN_EINVAL, or REVFFN_EUNSUPPORTED (kernel_mode 2 = MFMA kernels
+ * only, refused when the shape does not fit them). */
+int revffn_op_gemm(int32_t dtype, int32_t kernel_mode, const void *a, const void *b, void *c,
+                   int32_t M, int32_t N, int32_t K, int64_t lda, int64_t ldb, int64_t ldc,
+                   int32_t a_trans, int32_t b_trans, int32_t out_f32, void *hip_stream);
+int revffn_op_attention_fwd(int32_t dtype, int32_t kernel_mode, const void *q, const void *k,
+                            const void *v, void *o, float *lse, int32_t B, int32_t S, int32_t H,
+                            int32_t dh, int32_t causal, void *hip_stream);
+int revffn_op_attention_bwd(int32_t dtype, int32_t kernel_mode, const void *q, const void *k,
+                            const void *v, const void *o, const void *d_o, const float *lse,
+                            float *dvec, void *dq, void *dk, void *dv, int32_t B, int32_t S,
+                            int32_t H, int32_t dh, int32_t causal, void *hip_stream);
+
+/* Per-kernel timing for measurement (off by default).  While enabled, every GEMM and
+ * attention launch of this context is bracketed by two HIP events recorded on the launch
+ * stream, together with its algorithmic work: GEMM 2*M*N*K flops and each operand and the
+ * result moved once; attention core 4*B*S*S*d flops forward, 10*B*S*S*d backward, halved
+ * under the causal mask.  enable(on) also discards earlier records.  read() blocks the
+ * host until the recorded events have completed and returns the sums over all launches of
+ * kernel `kid` since enable: elapsed milliseconds, launch count, flops, bytes (any output
+ * may be NULL).  kernel_name(kid) is the kernel family the id stands for, NULL past the
+ * last id. */
+int revffn_profile_enable(revffn_ctx *ctx, int32_t on);
+int revffn_profile_read(revffn_ctx *ctx, int32_t kid, double *ms_total, int64_t *launches,
+                        double *flops, double *bytes);
+const char *revffn_profile_kernel_name(int32_t kid);
+
 const char *revffn_strerror(int code);
 
 #ifdef __cplusplus

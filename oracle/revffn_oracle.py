@@ -65,6 +65,11 @@ PARAM_NAMES = (
 )
 
 
+def as_f64(W):
+    """Weights dict with every array promoted to float64 (no copy where it already is)."""
+    return {k: (None if v is None else np.asarray(v, dtype=np.float64)) for k, v in W.items()}
+
+
 # --------------------------------------------------------------------------
 # element functions
 # --------------------------------------------------------------------------
@@ -132,7 +137,26 @@ def attention_core(Q, K, V, causal):
     return O, P
 
 
+def attention_core_backward(dO, Q, K, V, P):
+    """Reverse-mode through attention_core given its probabilities P: returns dQ, dK, dV."""
+    B, S, H, dh = Q.shape
+    dQ = np.zeros_like(Q)
+    dK = np.zeros_like(K)
+    dV = np.zeros_like(V)
+    for b in range(B):
+        for hh in range(H):
+            p = P[b, hh]
+            do = dO[b, :, hh, :]
+            dV[b, :, hh, :] = p.T @ do
+            dp = do @ V[b, :, hh, :].T
+            ds = p * (dp - np.sum(dp * p, axis=-1, keepdims=True))
+            dQ[b, :, hh, :] = ds @ K[b, :, hh, :] / np.sqrt(dh)
+            dK[b, :, hh, :] = ds.T @ Q[b, :, hh, :] / np.sqrt(dh)
+    return dQ, dK, dV
+
+
 def attn_half_forward(x1, x2, W, cfg, B, S, keep_probs=True):
+    W = as_f64(W)
     T = B * S
     H, dh, d = cfg.n_heads, cfg.head_dim, cfg.d_model
     n1 = rmsnorm(x1, W["norm_a1"], cfg.rms_eps)
@@ -165,6 +189,7 @@ def attn_half_forward(x1, x2, W, cfg, B, S, keep_probs=True):
 
 def attn_half_backward(dA, c, W, cfg, B, S):
     """Reverse-mode through attn_half_forward.  Returns dx1, dx2, grads."""
+    W = as_f64(W)
     T = B * S
     H, dh, d = cfg.n_heads, cfg.head_dim, cfg.d_model
     g = {}
@@ -172,19 +197,7 @@ def attn_half_backward(dA, c, W, cfg, B, S):
     dAO = dA @ W["pdn_a"]
     g["wo"] = dAO.T @ c["O"]
     dO = (dAO @ W["wo"]).reshape(B, S, H, dh)
-    Q, K, V, P = c["Q"], c["K"], c["V"], c["P"]
-    dQ = np.zeros_like(Q)
-    dK = np.zeros_like(K)
-    dV = np.zeros_like(V)
-    for b in range(B):
-        for hh in range(H):
-            p = P[b, hh]
-            do = dO[b, :, hh, :]
-            dV[b, :, hh, :] = p.T @ do
-            dp = do @ V[b, :, hh, :].T
-            ds = p * (dp - np.sum(dp * p, axis=-1, keepdims=True))
-            dQ[b, :, hh, :] = ds @ K[b, :, hh, :] / np.sqrt(dh)
-            dK[b, :, hh, :] = ds.T @ Q[b, :, hh, :] / np.sqrt(dh)
+    dQ, dK, dV = attention_core_backward(dO, c["Q"], c["K"], c["V"], c["P"])
     if cfg.use_rope:
         dQ = rope(dQ, cfg.rope_theta, sign=-1.0)
         dK = rope(dK, cfg.rope_theta, sign=-1.0)
@@ -248,6 +261,7 @@ def permutation(idx, n_experts):
 # MoE half:  M = P_dn_m( MLP_pt(P_up_m Norm Y1) )
 # --------------------------------------------------------------------------
 def moe_half_forward(y1, W, cfg):
+    W = as_f64(W)
     T = y1.shape[0]
     E, k, I, d = cfg.n_experts, cfg.top_k, cfg.d_expert, cfg.d_model
     n3 = rmsnorm(y1, W["norm_m"], cfg.rms_eps)
@@ -291,6 +305,7 @@ def moe_half_forward(y1, W, cfg):
 def moe_half_backward(dM, c, W, cfg):
     """Reverse-mode through moe_half_forward.  The top-k selection itself has zero
     gradient; the routing probabilities do carry gradient to every logit."""
+    W = as_f64(W)
     T = dM.shape[0]
     E, k, I, d = cfg.n_experts, cfg.top_k, cfg.d_expert, cfg.d_model
     Um = c["Um"]

@@ -9,7 +9,8 @@ EXPORTED_SYMBOLS = (
     "revffn_workspace_bytes", "revffn_create", "revffn_destroy", "revffn_set_inv_iters",
     "revffn_forward", "revffn_inverse", "revffn_backward", "revffn_stack_forward",
     "revffn_stack_backward", "revffn_get_routing", "revffn_enable_taps", "revffn_get_branch",
-    "revffn_set_kernel_mode", "revffn_strerror",
+    "revffn_set_kernel_mode", "revffn_strerror", "revffn_profile_enable", "revffn_profile_read",
+    "revffn_profile_kernel_name", "revffn_op_gemm", "revffn_op_attention_fwd", "revffn_op_attention_bwd",
 )
 
 WEIGHT_FIELDS = (
@@ -70,10 +71,20 @@ def load_library():
                                           vp, vp, vp, vp, i32, i32, i64, vp]
     lib.revffn_get_routing.argtypes = [vp, vp, vp, vp, vp, vp, vp]
     lib.revffn_get_branch.argtypes = [vp, i32, vp, vp]
+    lib.revffn_op_gemm.argtypes = [i32, i32, vp, vp, vp, i32, i32, i32, i64, i64, i64, i32, i32, i32, vp]
+    lib.revffn_op_attention_fwd.argtypes = [i32, i32, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp]
+    lib.revffn_op_attention_bwd.argtypes = [i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
+                                            i32, i32, i32, i32, i32, vp]
+    lib.revffn_profile_enable.argtypes = [vp, i32]
+    lib.revffn_profile_read.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64),
+                                        ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
+    lib.revffn_profile_kernel_name.restype = ctypes.c_char_p
+    lib.revffn_profile_kernel_name.argtypes = [i32]
     lib.revffn_strerror.restype = ctypes.c_char_p
     lib.revffn_strerror.argtypes = [ctypes.c_int]
     for name in EXPORTED_SYMBOLS:
-        if name not in ("revffn_workspace_bytes", "revffn_destroy", "revffn_strerror"):
+        if name not in ("revffn_workspace_bytes", "revffn_destroy", "revffn_strerror",
+                        "revffn_profile_kernel_name"):
             getattr(lib, name).restype = ctypes.c_int
     _LIB = lib
     return lib
@@ -147,6 +158,23 @@ class Context:
     def set_kernel_mode(self, mode):
         _check(self.lib.revffn_set_kernel_mode(self.handle, mode))
 
+    def profile_enable(self, on=True):
+        _check(self.lib.revffn_profile_enable(self.handle, 1 if on else 0))
+
+    def profile_read(self):
+        """{kernel family: dict(ms, launches, flops, bytes)} summed since profile_enable (blocks)."""
+        out, kid = {}, 0
+        while True:
+            name = self.lib.revffn_profile_kernel_name(kid)
+            if name is None:
+                return out
+            ms, n, fl, by = ctypes.c_double(), ctypes.c_int64(), ctypes.c_double(), ctypes.c_double()
+            _check(self.lib.revffn_profile_read(self.handle, kid, ctypes.byref(ms), ctypes.byref(n),
+                                                ctypes.byref(fl), ctypes.byref(by)))
+            if n.value:
+                out[name.decode()] = dict(ms=ms.value, launches=n.value, flops=fl.value, bytes=by.value)
+            kid += 1
+
 
 def _w(weights):
     return weights if isinstance(weights, Weights) else _struct(Weights, weights)
@@ -199,3 +227,20 @@ def revffn_get_routing(ctx, idx=None, wts=None, counts=None, offsets=None, row_m
 
 def revffn_get_branch(ctx, which, dst, stream=None):
     _check(ctx.lib.revffn_get_branch(ctx.handle, which, _ptr(dst), _stream(stream)))
+
+
+def revffn_op_gemm(dtype, kernel_mode, a, b, c, M, N, K, lda, ldb, ldc, a_trans, b_trans, out_f32=False, stream=None):
+    _check(load_library().revffn_op_gemm(dtype, kernel_mode, _ptr(a), _ptr(b), _ptr(c), M, N, K, lda, ldb, ldc,
+                                         int(a_trans), int(b_trans), int(out_f32), _stream(stream)))
+
+
+def revffn_op_attention_fwd(dtype, kernel_mode, q, k, v, o, lse, B, S, H, dh, causal, stream=None):
+    _check(load_library().revffn_op_attention_fwd(dtype, kernel_mode, _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse),
+                                                  B, S, H, dh, int(causal), _stream(stream)))
+
+
+def revffn_op_attention_bwd(dtype, kernel_mode, q, k, v, o, d_o, lse, dvec, dq, dk, dv, B, S, H, dh, causal,
+                            stream=None):
+    _check(load_library().revffn_op_attention_bwd(dtype, kernel_mode, _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(d_o),
+                                                  _ptr(lse), _ptr(dvec), _ptr(dq), _ptr(dk), _ptr(dv), B, S, H, dh,
+                                                  int(causal), _stream(stream)))

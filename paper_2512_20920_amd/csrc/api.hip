@@ -24,7 +24,17 @@ struct Carver {            // hands out 256-byte aligned slices of one allocatio
 
 }  // namespace
 
+enum { KID_GEMM_NT = 0, KID_GEMM_NN, KID_GEMM_TN, KID_GEMM_GENERIC, KID_ATTN_FWD_FLASH, KID_ATTN_BWD_FLASH,
+       KID_ATTN_FWD_GENERIC, KID_ATTN_BWD_GENERIC, KID_COUNT };
+static const char* const kid_names[KID_COUNT] = {"gemm_mfma_nt", "gemm_mfma_nn", "gemm_mfma_tn", "gemm_generic",
+                                                 "attn_fwd_flash", "attn_bwd_flash", "attn_fwd_generic",
+                                                 "attn_bwd_generic"};
+struct ProfRec { int kid; hipEvent_t a, b; double flops, bytes; };
+
 struct revffn_ctx {
+  bool prof_on = false;
+  std::vector<ProfRec>* prof = nullptr;        // launches recorded since profiling was switched on
+  std::vector<hipEvent_t>* ev_pool = nullptr;  // recycled events
   revffn_config cfg;
   int dt, es;                 // element type / size of streams and weights
   int maxT;
@@ -172,14 +182,55 @@ GemmArgs tn(const void* A, i64 lda, const void* Bm, i64 ldb, void* C, i64 ldc, i
   return g;
 }
 
+// ---- optional per-kernel timing with HIP events on the launch stream -----------------
+hipEvent_t prof_event(revffn_ctx* c) {
+  hipEvent_t e = nullptr;
+  if (!c->ev_pool->empty()) { e = c->ev_pool->back(); c->ev_pool->pop_back(); }
+  else (void)hipEventCreate(&e);
+  return e;
+}
+struct ProfScope {
+  revffn_ctx* c; hipStream_t s; ProfRec r; bool on;
+  ProfScope(revffn_ctx* c_, hipStream_t s_, double flops, double bytes) : c(c_), s(s_), on(c_->prof_on) {
+    if (!on) return;
+    r.kid = -1; r.flops = flops; r.bytes = bytes; r.a = prof_event(c); r.b = prof_event(c);
+    (void)hipEventRecord(r.a, s);
+  }
+  void done(int kid) {
+    if (!on) return;
+    r.kid = kid;
+    (void)hipEventRecord(r.b, s);
+    c->prof->push_back(r);
+  }
+};
+
+// algorithmic work of one GEMM launch: 2*M*N*K flops; every operand and the result moved once
+void gemm_work(const revffn_ctx* c, const GemmArgs& g, int ta, int tb, int tc, double* flops, double* bytes) {
+  const double ea = ta ? 2 : 4, eb = tb ? 2 : 4, ec = tc ? 2 : 4;
+  double M = g.M, N = g.N, K = g.K, G = g.n_groups;
+  if (g.group_mode == 1) { *flops = 2 * M * N * K; *bytes = M * K * ea + G * N * K * eb + M * N * ec; }
+  else if (g.group_mode == 2) { double R = (double)c->lastT * c->cfg.top_k;     // rows summed over groups
+    *flops = 2 * M * N * R; *bytes = R * M * ea + R * N * eb + G * M * N * ec; }
+  else { *flops = 2 * M * N * K; *bytes = M * K * ea + N * K * eb + M * N * ec; }
+  if (g.resid) *bytes += M * N * (c->es);
+}
+
 int run_gemm(revffn_ctx* c, GemmArgs g, int ta, int tb, int tc, hipStream_t s) {
   GemmTypes t{ta, tb, tc, c->dt};
+  double fl = 0, by = 0;
+  if (c->prof_on) gemm_work(c, g, ta, tb, tc, &fl, &by);
+  ProfScope ps(c, s, fl, by);
   if (c->dt == 1 && c->mode == 0 && ta == 1 && tb == 1) {
     if (g.group_mode == 1) { g.tile_group = c->tg_b; g.tile_m0 = c->tm_b; g.max_tiles = c->max_tiles_b; g.tile_bm = BM_B; }
-    if (launch_gemm_mfma(g, t, s) == 0) return 0;
+    if (launch_gemm_mfma(g, t, s) == 0) {
+      ps.done(g.a_trans ? KID_GEMM_TN : (g.b_trans ? KID_GEMM_NN : KID_GEMM_NT));
+      return 0;
+    }
   }
   if (g.group_mode == 1) { g.tile_group = c->tg_a; g.tile_m0 = c->tm_a; g.max_tiles = c->max_tiles_a; g.tile_bm = BM_A; }
-  return launch_gemm_generic(g, t, s) == 0 ? 0 : REVFFN_EUNSUPPORTED;
+  int e = launch_gemm_generic(g, t, s) == 0 ? 0 : REVFFN_EUNSUPPORTED;
+  ps.done(KID_GEMM_GENERIC);
+  return e;
 }
 int run_gemm(revffn_ctx* c, const GemmArgs& g, hipStream_t s) { return run_gemm(c, g, c->dt, c->dt, c->dt, s); }
 
@@ -211,10 +262,16 @@ int attn_acts(revffn_ctx* c, const revffn_weights* w, const void* x1, i64 ld1, c
     launch_rope(dt, c->Q, c->rope_cs, T, S, f.n_heads, f.head_dim, 1.f, s);
     if (do_kv) launch_rope(dt, c->K, c->rope_cs, T, S, f.n_heads, f.head_dim, 1.f, s);
   }
-  bool done = false;
-  if (dt == 1 && c->mode == 0)
-    done = launch_attn_fwd_flash(c->Q, c->K, c->V, c->O, c->lse, B, S, f.n_heads, f.head_dim, f.causal, s) == 0;
-  if (!done) launch_attn_fwd_generic(dt, c->Q, c->K, c->V, c->O, c->lse, B, S, f.n_heads, f.head_dim, f.causal, s);
+  {
+    // algorithmic work of the attention core: QK^T and PV, halved by the causal mask
+    double fl = 4.0 * B * (double)S * S * d * (f.causal ? 0.5 : 1.0), by = 4.0 * T * d * es;
+    ProfScope ps(c, s, fl, by);
+    bool done = false;
+    if (dt == 1 && c->mode == 0)
+      done = launch_attn_fwd_flash(c->Q, c->K, c->V, c->O, c->lse, B, S, f.n_heads, f.head_dim, f.causal, s) == 0;
+    if (!done) launch_attn_fwd_generic(dt, c->Q, c->K, c->V, c->O, c->lse, B, S, f.n_heads, f.head_dim, f.causal, s);
+    ps.done(done ? KID_ATTN_FWD_FLASH : KID_ATTN_FWD_GENERIC);
+  }
   TRY(run_gemm(c, nt(c->O, d, w->wo, d, c->AO, d, T, d, d), s));
   return 0;
 }
@@ -394,13 +451,19 @@ int backward_impl(revffn_ctx* c, const revffn_weights* w, const void* x1, const 
   TRY(run_gemm(c, nn(c->g1, h, w->pdn_a, d, c->dAO, d, T, d, h), s));
   if (GF(wo)) TRY(run_gemm(c, tn(c->dAO, d, c->O, d, GF(wo), d, d, d, T), s));
   TRY(run_gemm(c, nn(c->dAO, d, w->wo, d, c->dO, d, T, d, d), s));
-  bool done = false;
-  if (dt == 1 && c->mode == 0)
-    done = launch_attn_bwd_flash(c->Q, c->K, c->V, c->O, c->dO, c->lse, c->dvec, c->dQ, c->dK, c->dV, B, S, f.n_heads,
-                                 f.head_dim, f.causal, s) == 0;
-  if (!done)
-    launch_attn_bwd_generic(dt, c->Q, c->K, c->V, c->O, c->dO, c->lse, c->dvec, c->dQ, c->dK, c->dV, B, S, f.n_heads,
-                            f.head_dim, f.causal, s);
+  {
+    // five S x S x dh products (scores, dP, dV, dQ, dK), halved by the causal mask
+    double fl = 10.0 * B * (double)S * S * d * (f.causal ? 0.5 : 1.0), by = 8.0 * T * d * es;
+    ProfScope ps(c, s, fl, by);
+    bool done = false;
+    if (dt == 1 && c->mode == 0)
+      done = launch_attn_bwd_flash(c->Q, c->K, c->V, c->O, c->dO, c->lse, c->dvec, c->dQ, c->dK, c->dV, B, S,
+                                   f.n_heads, f.head_dim, f.causal, s) == 0;
+    if (!done)
+      launch_attn_bwd_generic(dt, c->Q, c->K, c->V, c->O, c->dO, c->lse, c->dvec, c->dQ, c->dK, c->dV, B, S,
+                              f.n_heads, f.head_dim, f.causal, s);
+    ps.done(done ? KID_ATTN_BWD_FLASH : KID_ATTN_BWD_GENERIC);
+  }
   if (f.use_rope) {
     launch_rope(dt, c->dQ, c->rope_cs, T, S, f.n_heads, f.head_dim, -1.f, s);
     launch_rope(dt, c->dK, c->rope_cs, T, S, f.n_heads, f.head_dim, -1.f, s);
@@ -442,7 +505,6 @@ extern "C" {
 size_t revffn_workspace_bytes(const revffn_config* cfg, int32_t max_B, int32_t max_S) {
   if (check_cfg(cfg) || max_B < 1 || max_S < 1) return 0;
   revffn_ctx tmp;
-  memset(&tmp, 0, sizeof(tmp));
   tmp.cfg = *cfg;
   tmp.dt = cfg->dtype;
   tmp.es = cfg->dtype == REVFFN_BF16 ? 2 : 4;
@@ -459,13 +521,20 @@ int revffn_create(revffn_ctx** out, const revffn_config* cfg, int32_t max_B, int
   revffn_ctx* c = new (std::nothrow) revffn_ctx;
   if (!c) return REVFFN_EWORKSPACE;
   memset(c, 0, sizeof(*c));
+  c->prof = new (std::nothrow) std::vector<ProfRec>();
+  c->ev_pool = new (std::nothrow) std::vector<hipEvent_t>();
+  if (!c->prof || !c->ev_pool) { delete c->prof; delete c->ev_pool; delete c; return REVFFN_EWORKSPACE; }
   c->cfg = *cfg;
   c->dt = cfg->dtype;
   c->es = cfg->dtype == REVFFN_BF16 ? 2 : 4;
   c->maxT = max_B * max_S;
   c->slab_bytes = carve(c, nullptr);
-  if (hipGetDevice(&c->device) != hipSuccess) { delete c; return REVFFN_EHIP; }
-  if (hipMalloc(&c->slab, c->slab_bytes) != hipSuccess) { (void)hipGetLastError(); delete c; return REVFFN_EWORKSPACE; }
+  if (hipGetDevice(&c->device) != hipSuccess) { delete c->prof; delete c->ev_pool; delete c; return REVFFN_EHIP; }
+  if (hipMalloc(&c->slab, c->slab_bytes) != hipSuccess) {
+    (void)hipGetLastError();
+    delete c->prof; delete c->ev_pool; delete c;
+    return REVFFN_EWORKSPACE;
+  }
   carve(c, (char*)c->slab);
   // rotary table: cs[s][i] = (cos, sin)(s * theta^(-2i/dh)), built in double precision on the host
   const int half = cfg->head_dim / 2;
@@ -478,17 +547,59 @@ int revffn_create(revffn_ctx** out, const revffn_config* cfg, int32_t max_B, int
     }
   if (hipMemcpy(c->rope_cs, tab.data(), tab.size() * 4, hipMemcpyHostToDevice) != hipSuccess) {
     (void)hipFree(c->slab);
-    delete c;
+    delete c->prof; delete c->ev_pool; delete c;
     return REVFFN_EHIP;
   }
   *out = c;
   return REVFFN_OK;
 }
 
+static void prof_clear(revffn_ctx* c) {
+  for (auto& r : *c->prof) { c->ev_pool->push_back(r.a); c->ev_pool->push_back(r.b); }
+  c->prof->clear();
+}
+
 void revffn_destroy(revffn_ctx* c) {
   if (!c) return;
+  if (c->prof) {
+    prof_clear(c);
+    for (hipEvent_t e : *c->ev_pool) (void)hipEventDestroy(e);
+    delete c->prof;
+    delete c->ev_pool;
+  }
   if (c->slab) (void)hipFree(c->slab);
   delete c;
+}
+
+int revffn_profile_enable(revffn_ctx* c, int32_t on) {
+  if (!c) return REVFFN_ENULL;
+  prof_clear(c);
+  c->prof_on = on != 0;
+  return 0;
+}
+
+int revffn_profile_read(revffn_ctx* c, int32_t kid, double* ms_total, int64_t* launches, double* flops,
+                        double* bytes) {
+  if (!c) return REVFFN_ENULL;
+  if (kid < 0 || kid >= KID_COUNT) return REVFFN_EINVAL;
+  double ms = 0, fl = 0, by = 0;
+  int64_t n = 0;
+  for (auto& r : *c->prof) {
+    if (r.kid != kid) continue;
+    if (hipEventSynchronize(r.b) != hipSuccess) return REVFFN_EHIP;
+    float t = 0.f;
+    if (hipEventElapsedTime(&t, r.a, r.b) != hipSuccess) return REVFFN_EHIP;
+    ms += t; fl += r.flops; by += r.bytes; n++;
+  }
+  if (ms_total) *ms_total = ms;
+  if (launches) *launches = n;
+  if (flops) *flops = fl;
+  if (bytes) *bytes = by;
+  return 0;
+}
+
+const char* revffn_profile_kernel_name(int32_t kid) {
+  return (kid >= 0 && kid < KID_COUNT) ? kid_names[kid] : nullptr;
 }
 
 int revffn_set_inv_iters(revffn_ctx* c, int32_t n) {
@@ -582,6 +693,47 @@ int revffn_get_branch(revffn_ctx* c, int32_t which, float* dst, void* stream) {
   size_t bytes = (size_t)c->lastT * (c->cfg.d_model / 2) * 4;
   hipError_t e = hipMemcpyAsync(dst, which == 0 ? c->tapA : c->tapM, bytes, hipMemcpyDeviceToDevice, (hipStream_t)stream);
   return e == hipSuccess ? 0 : REVFFN_EHIP;
+}
+
+int revffn_op_gemm(int32_t dtype, int32_t kernel_mode, const void* a, const void* b, void* c, int32_t M, int32_t N,
+                   int32_t K, int64_t lda, int64_t ldb, int64_t ldc, int32_t a_trans, int32_t b_trans,
+                   int32_t out_f32, void* stream) {
+  if ((dtype != 0 && dtype != 1) || kernel_mode < 0 || kernel_mode > 2 || !a || !b || !c || M < 1 || N < 1 || K < 0)
+    return REVFFN_EINVAL;
+  GemmArgs g = nt(a, lda, b, ldb, c, ldc, M, N, K);
+  g.a_trans = a_trans ? 1 : 0;
+  g.b_trans = b_trans ? 1 : 0;
+  GemmTypes t{dtype, dtype, out_f32 ? 0 : dtype, dtype};
+  if (dtype == 1 && kernel_mode != 1 && launch_gemm_mfma(g, t, (hipStream_t)stream) == 0) return 0;
+  if (kernel_mode == 2) return REVFFN_EUNSUPPORTED;
+  return launch_gemm_generic(g, t, (hipStream_t)stream) == 0 ? 0 : REVFFN_EUNSUPPORTED;
+}
+
+int revffn_op_attention_fwd(int32_t dtype, int32_t kernel_mode, const void* q, const void* k, const void* v, void* o,
+                            float* lse, int32_t B, int32_t S, int32_t H, int32_t dh, int32_t causal, void* stream) {
+  if ((dtype != 0 && dtype != 1) || kernel_mode < 0 || kernel_mode > 2 || !q || !k || !v || !o || !lse || B < 1 ||
+      S < 1 || H < 1 || dh < 2 || dh > 1024)
+    return REVFFN_EINVAL;
+  hipStream_t s = (hipStream_t)stream;
+  if (dtype == 1 && kernel_mode != 1 && launch_attn_fwd_flash(q, k, v, o, lse, B, S, H, dh, causal, s) == 0) return 0;
+  if (kernel_mode == 2) return REVFFN_EUNSUPPORTED;
+  launch_attn_fwd_generic(dtype, q, k, v, o, lse, B, S, H, dh, causal, s);
+  return 0;
+}
+
+int revffn_op_attention_bwd(int32_t dtype, int32_t kernel_mode, const void* q, const void* k, const void* v,
+                            const void* o, const void* d_o, const float* lse, float* dvec, void* dq, void* dk, void* dv,
+                            int32_t B, int32_t S, int32_t H, int32_t dh, int32_t causal, void* stream) {
+  if ((dtype != 0 && dtype != 1) || kernel_mode < 0 || kernel_mode > 2 || !q || !k || !v || !o || !d_o || !lse ||
+      !dvec || !dq || !dk || !dv || B < 1 || S < 1 || H < 1 || dh < 2 || dh > 1024)
+    return REVFFN_EINVAL;
+  hipStream_t s = (hipStream_t)stream;
+  if (dtype == 1 && kernel_mode != 1 &&
+      launch_attn_bwd_flash(q, k, v, o, d_o, lse, dvec, dq, dk, dv, B, S, H, dh, causal, s) == 0)
+    return 0;
+  if (kernel_mode == 2) return REVFFN_EUNSUPPORTED;
+  launch_attn_bwd_generic(dtype, q, k, v, o, d_o, lse, dvec, dq, dk, dv, B, S, H, dh, causal, s);
+  return 0;
 }
 
 const char* revffn_strerror(int code) {

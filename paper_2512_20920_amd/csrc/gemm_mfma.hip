@@ -1,3 +1,268 @@
-// bf16 MFMA GEMM (placeholder until the MFMA kernels land: reports "not taken").
+// bf16 GEMM on the gfx950 matrix cores (v_mfma_f32_32x32x16_bf16, fp32 accumulation) for
+// every dense contraction of the block: adapters, Q/K/V/O projections, shared expert,
+// grouped routed experts (forward, data gradient, weight gradient).
+//
+// Workgroup = 256 threads = 4 waves (2x2); workgroup tile BM x BN, k-step 64, two LDS
+// stages.  Operand tiles are staged global -> registers -> LDS while the previous stage
+// is multiplied.  An operand whose contraction index is contiguous in memory is read from
+// LDS with 16-byte reads; an operand whose contraction index is the slow one (the
+// "transposed" layouts of the data- and weight-gradient GEMMs) is kept as stored and read
+// with the transposing LDS read ds_read_b64_tr_b16, whose lane mapping is: inside each
+// block of 16 lanes, lane j receives element (j & 3) of the 8-byte words addressed by
+// lanes 4*e + (j >> 2), e = 0..3.
 #include "kernels.h"
-int launch_gemm_mfma(const GemmArgs&, GemmTypes, hipStream_t) { return 1; }
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+
+#define BK 64
+
+// LDS tile of one operand.  TR = 0: [ROWS][BK] with row stride BK+8 elements (144 B: the 16
+// rows read together by a 16-byte fragment read start on distinct 16-byte bank groups).
+// TR = 1: [BK][ROWS] with row stride ROWS+32 elements (the 4 k-rows x 64 B read together by a
+// transposing read fall on disjoint banks).
+template <bool TR, int ROWS>
+struct Tile {
+  static constexpr int stride = TR ? ROWS + 32 : BK + 8;
+  static constexpr int elems = TR ? BK * stride : ROWS * stride;
+  static constexpr int chunks = ROWS / 32;        // 16-byte chunks per thread per k-step
+};
+
+struct OperandSrc {
+  const bf16* base;     // matrix base (already offset by group)
+  i64 ld;
+  const int* gather;    // row indirection or nullptr
+  int div;
+  int row0;             // first tile row (m0 or n0) in the non-contraction index
+  int row_lim;          // exclusive bound of valid rows
+};
+
+// ---- global -> registers ----------------------------------------------------------
+template <bool TR, int ROWS>
+__device__ __forceinline__ void load_tile(const OperandSrc& s, int k0, int k_end, uint4 (&regs)[Tile<TR, ROWS>::chunks],
+                                          const i64 (&rowoff)[Tile<TR, ROWS>::chunks]) {
+  constexpr int NC = Tile<TR, ROWS>::chunks;
+#pragma unroll
+  for (int i = 0; i < NC; i++) {
+    int c = threadIdx.x + 256 * i;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (!TR) {
+      int kc = c & 7;
+      int k = k0 + kc * 8;
+      if (k < k_end) v = *(const uint4*)(s.base + rowoff[i] + k);
+    } else {
+      int krow = c / (ROWS / 8), mc = c % (ROWS / 8);
+      int k = k0 + krow;
+      int m = s.row0 + mc * 8;
+      if (k < k_end && m < s.row_lim) {
+        i64 r = s.gather ? (i64)(s.gather[k] / s.div) : (i64)k;
+        v = *(const uint4*)(s.base + r * s.ld + m);
+      }
+    }
+    regs[i] = v;
+  }
+}
+
+// per-thread row offsets of the non-transposed operand (fixed over the k loop); rows past
+// the limit are clamped to the last valid row (their products are never stored)
+template <int ROWS>
+__device__ __forceinline__ void row_offsets(const OperandSrc& s, i64 (&rowoff)[ROWS / 32]) {
+#pragma unroll
+  for (int i = 0; i < ROWS / 32; i++) {
+    int c = threadIdx.x + 256 * i;
+    int r = s.row0 + (c >> 3);
+    if (r >= s.row_lim) r = s.row_lim - 1;
+    i64 rr = s.gather ? (i64)(s.gather[r] / s.div) : (i64)r;
+    rowoff[i] = rr * s.ld;
+  }
+}
+
+// ---- registers -> LDS -------------------------------------------------------------
+template <bool TR, int ROWS>
+__device__ __forceinline__ void store_tile(bf16* lds, const uint4 (&regs)[Tile<TR, ROWS>::chunks]) {
+  constexpr int NC = Tile<TR, ROWS>::chunks;
+  constexpr int ST = Tile<TR, ROWS>::stride;
+#pragma unroll
+  for (int i = 0; i < NC; i++) {
+    int c = threadIdx.x + 256 * i;
+    int off;
+    if (!TR) off = (c >> 3) * ST + (c & 7) * 8;
+    else off = (c / (ROWS / 8)) * ST + (c % (ROWS / 8)) * 8;
+    *(uint4*)(lds + off) = regs[i];
+  }
+}
+
+// ---- LDS -> MFMA operand fragment: 32 rows x 16 k, lane (r = lane & 31, g = lane >> 5)
+// holds k = 8g..8g+7 of row r ---------------------------------------------------------
+template <bool TR, int ROWS>
+__device__ __forceinline__ bf16x8 load_frag(const bf16* lds, int r0, int kk, int lane) {
+  constexpr int ST = Tile<TR, ROWS>::stride;
+  if (!TR) {
+    return *(const bf16x8*)(lds + (r0 + (lane & 31)) * ST + kk * 16 + (lane >> 5) * 8);
+  } else {
+    int blk = lane >> 4, i = lane & 15;
+    int krow = kk * 16 + (blk >> 1) * 8 + (i >> 2);
+    int mcol = r0 + (blk & 1) * 16 + (i & 3) * 4;
+    const bf16* p = lds + krow * ST + mcol;
+    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p));
+    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 4 * ST));
+    s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, v);
+  }
+}
+
+template <int BM, int BN, bool AT, bool BT, class TC>
+__global__ void __launch_bounds__(256) gemm_mfma_k(GemmArgs g) {
+  typedef Tile<AT, BM> TA_;
+  typedef Tile<BT, BN> TB_;
+  constexpr int WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  bf16* sA = (bf16*)smem_raw;                       // 2 stages of A then 2 stages of B
+  bf16* sB = sA + 2 * TA_::elems;
+
+  const bf16* A = (const bf16*)g.A;
+  const bf16* Bm = (const bf16*)g.B;
+  TC* C = (TC*)g.C;
+  int m0, m_end, k0 = 0, k_end = g.K;
+  if (g.group_mode == 1) {
+    int ti = blockIdx.y;
+    int grp = g.tile_group[ti];
+    if (grp < 0) return;
+    m0 = g.tile_m0[ti];
+    m_end = min(g.offsets[grp + 1], m0 + BM);
+    Bm += (i64)grp * g.b_group_stride;
+  } else {
+    m0 = blockIdx.y * BM;
+    m_end = g.M;
+    if (g.group_mode == 2) {
+      int grp = blockIdx.z;
+      k0 = g.offsets[grp];
+      k_end = g.offsets[grp + 1];
+      C += (i64)grp * g.c_group_stride;
+    }
+  }
+  const int n0 = blockIdx.x * BN;
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const int wm = (wv >> 1) * WM, wn = (wv & 1) * WN;
+
+  OperandSrc sa{A, g.lda, g.a_gather, g.gather_div, m0, m_end};
+  OperandSrc sb{Bm, g.ldb, g.b_gather, g.gather_div, n0, g.N};
+  i64 offA[TA_::chunks], offB[TB_::chunks];
+  if (!AT) row_offsets<BM>(sa, offA);
+  if (!BT) row_offsets<BN>(sb, offB);
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; i++)
+#pragma unroll
+    for (int j = 0; j < TN; j++)
+#pragma unroll
+      for (int e = 0; e < 16; e++) acc[i][j][e] = 0.f;
+
+  uint4 ra[TA_::chunks], rb[TB_::chunks];
+  const int nk = (k_end - k0 + BK - 1) / BK;
+  if (nk > 0) {
+    load_tile<AT, BM>(sa, k0, k_end, ra, offA);
+    load_tile<BT, BN>(sb, k0, k_end, rb, offB);
+    store_tile<AT, BM>(sA, ra);
+    store_tile<BT, BN>(sB, rb);
+  }
+  __syncthreads();
+  for (int kt = 0; kt < nk; kt++) {
+    const int cur = kt & 1;
+    if (kt + 1 < nk) {
+      load_tile<AT, BM>(sa, k0 + (kt + 1) * BK, k_end, ra, offA);
+      load_tile<BT, BN>(sb, k0 + (kt + 1) * BK, k_end, rb, offB);
+    }
+    const bf16* cA = sA + cur * TA_::elems;
+    const bf16* cB = sB + cur * TB_::elems;
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; kk++) {
+      bf16x8 fa[TM], fb[TN];
+#pragma unroll
+      for (int i = 0; i < TM; i++) fa[i] = load_frag<AT, BM>(cA, wm + i * 32, kk, lane);
+#pragma unroll
+      for (int j = 0; j < TN; j++) fb[j] = load_frag<BT, BN>(cB, wn + j * 32, kk, lane);
+#pragma unroll
+      for (int i = 0; i < TM; i++)
+#pragma unroll
+        for (int j = 0; j < TN; j++)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    }
+    if (kt + 1 < nk) {
+      store_tile<AT, BM>(sA + (cur ^ 1) * TA_::elems, ra);
+      store_tile<BT, BN>(sB + (cur ^ 1) * TB_::elems, rb);
+    }
+    __syncthreads();
+  }
+
+  // ---- epilogue: lane holds column n = lane & 31 and rows (e>>2)*8 + (lane>>5)*4 + (e&3)
+  const bf16* bias = (const bf16*)g.bias;
+  const bf16* resid = (const bf16*)g.resid;
+#pragma unroll
+  for (int j = 0; j < TN; j++) {
+    const int n = n0 + wn + j * 32 + (lane & 31);
+    if (n >= g.N) continue;
+    const float bv = bias ? (float)bias[n] : 0.f;
+#pragma unroll
+    for (int i = 0; i < TM; i++) {
+#pragma unroll
+      for (int e = 0; e < 16; e++) {
+        const int m = m0 + wm + i * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+        if (m >= m_end) continue;
+        float v = acc[i][j][e];
+        if (g.row_scale) v *= g.row_scale[m];
+        v += bv;
+        if (g.tap) g.tap[(i64)m * g.ldtap + n] = v;
+        if (resid) v = (float)resid[(i64)m * g.ldr + n] + g.resid_sign * v;
+        C[(i64)m * g.ldc + n] = (TC)v;
+      }
+    }
+  }
+}
+
+template <int BM, int BN, bool AT, bool BT, class TC>
+static void go(const GemmArgs& g, hipStream_t s) {
+  dim3 grid;
+  if (g.group_mode == 1) grid = dim3(cdiv(g.N, BN), g.max_tiles, 1);
+  else grid = dim3(cdiv(g.N, BN), cdiv(g.M, BM), g.group_mode == 2 ? g.n_groups : 1);
+  if (grid.x == 0 || grid.y == 0 || grid.z == 0) return;
+  size_t smem = (size_t)2 * (Tile<AT, BM>::elems + Tile<BT, BN>::elems) * sizeof(bf16);
+  static bool attr_set = false;
+  if (!attr_set) {
+    (void)hipFuncSetAttribute((const void*)gemm_mfma_k<BM, BN, AT, BT, TC>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                              (int)smem);
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((gemm_mfma_k<BM, BN, AT, BT, TC>), grid, dim3(256), smem, s, g);
+}
+
+static bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+
+int launch_gemm_mfma(const GemmArgs& g, GemmTypes t, hipStream_t s) {
+  if (t.ta != 1 || t.tb != 1 || t.tside != 1) return 1;
+  if (!aligned16(g.A) || !aligned16(g.B) || (g.lda & 7) || (g.ldb & 7)) return 1;
+  if ((g.b_group_stride & 7) || (g.c_group_stride & 7)) return 1;
+  if (!g.a_trans && (g.K & 7)) return 1;
+  if (!g.b_trans && (g.K & 7)) return 1;
+  if (g.a_trans && (g.M & 7)) return 1;
+  if (g.b_trans && (g.N & 7)) return 1;
+  if (g.a_trans && !g.b_trans) return 1;                 // layout not used by the block
+  if (g.group_mode == 2 && !(g.a_trans && g.b_trans)) return 1;
+  if (g.group_mode == 1 && (g.a_trans || g.tile_bm != 128)) return 1;
+  if (g.a_gather && g.a_trans) return 1;
+  if (g.b_gather && !g.b_trans) return 1;
+  if (g.group_mode != 1 && g.M <= 0) return 1;
+  const bool f32out = t.tc == 0;
+  if (!g.a_trans && !g.b_trans) {
+    if (f32out) go<128, 128, false, false, float>(g, s); else go<128, 128, false, false, bf16>(g, s);
+  } else if (!g.a_trans && g.b_trans) {
+    if (f32out) go<128, 128, false, true, float>(g, s); else go<128, 128, false, true, bf16>(g, s);
+  } else {
+    if (f32out) go<128, 128, true, true, float>(g, s); else go<128, 128, true, true, bf16>(g, s);
+  }
+  return 0;
+}

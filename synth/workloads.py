@@ -80,9 +80,9 @@ def weight_shapes(wl):
 
 def bf16_bits(x):
     """float array -> uint16 bfloat16 bit patterns, round-to-nearest-even."""
-    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
-    u = u + 0x7FFF + ((u >> 16) & 1)
-    return (u >> 16).astype(np.uint16)
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    u = u + (np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1)))     # finite inputs: no wrap-around
+    return (u >> np.uint32(16)).astype(np.uint16)
 
 
 def bits_to_f64(bits):
@@ -94,11 +94,18 @@ def round_bf16(x):
     return bits_to_f64(bf16_bits(x))
 
 
-def _store(x, dtype):
-    """Round to the storage dtype; return float64 holding exactly the stored value."""
+def _store(x, dtype, f64=True):
+    """Round float32 values to the storage dtype.  Returns an array holding exactly the stored
+    values: float64 if f64 else float32 (both represent bf16 and fp32 values exactly)."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
     if dtype == "bf16":
-        return round_bf16(x)
-    return np.asarray(x, dtype=np.float32).astype(np.float64)
+        if x.size > (1 << 20):
+            # same round-to-nearest-even as bf16_bits, done by torch's multi-threaded cast
+            import torch
+            x = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()
+        else:
+            x = (bf16_bits(x).astype(np.uint32) << 16).view(np.float32)
+    return x.astype(np.float64) if f64 else x
 
 
 def zipf_router_bias(wl, seed, alpha=None):
@@ -109,10 +116,10 @@ def zipf_router_bias(wl, seed, alpha=None):
     return a * (-1.2 * np.log(rank.astype(np.float64)))
 
 
-def make_weights(wl, block=0, alpha=None):
-    """One block's weights as float64 arrays holding storage-rounded values.
-    b_router is fp32 at the boundary in both dtypes.  Block l of a stack uses
-    seed + 1000*(l+1)."""
+def make_weights(wl, block=0, alpha=None, f64=True):
+    """One block's weights as float64 (or, with f64=False, float32) arrays holding
+    storage-rounded values.  b_router is fp32 at the boundary in both dtypes.
+    Block l of a stack uses seed + 1000*(l+1)."""
     rng = np.random.default_rng(wl.seed + 1000 * (block + 1))
     W = {}
     for name, shp in weight_shapes(wl).items():
@@ -124,8 +131,9 @@ def make_weights(wl, block=0, alpha=None):
             W[name] = np.asarray(zipf_router_bias(wl, wl.seed, alpha), dtype=np.float32).astype(np.float64)
             continue
         else:
-            v = 0.02 * rng.standard_normal(shp, dtype=np.float32)
-        W[name] = _store(v, wl.dtype)
+            v = rng.standard_normal(shp, dtype=np.float32)
+            v *= np.float32(0.02)
+        W[name] = _store(v, wl.dtype, f64)
     for name in WEIGHT_FIELDS:
         W.setdefault(name, None)
     return W
