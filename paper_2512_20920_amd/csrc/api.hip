@@ -60,6 +60,8 @@ struct revffn_ctx {
   // backward
   void *dRS, *dYp, *dYs, *dHs, *dGUs, *dUm_sh, *dHh, *dGU, *dXg, *dUm, *dn3, *g1;
   float *dw, *dzext, *rinv, *partial;
+  float *zraw, *splitk_ws;
+  void* dwr_tmp;
   void *dAO, *dO, *dQ, *dK, *dV, *dU12, *dn12;
   float* dvec;
   float* rope_cs;
@@ -69,6 +71,8 @@ namespace {
 
 const int BM_A = 64;    // m-tile height of the generic grouped GEMM
 const int BM_B = 128;   // m-tile height of the MFMA grouped GEMM
+// k-slices of the small fp32 GEMMs around the router (each would otherwise run on a handful of CUs)
+const int SPLIT_FOLD = 16, SPLIT_LOGITS = 8, SPLIT_DWR = 32;
 
 int check_cfg(const revffn_config* c) {
   if (!c) return REVFFN_ENULL;
@@ -143,6 +147,14 @@ size_t carve(revffn_ctx* c, char* base) {
   c->g1 = cv.take(T * h * es);
   c->dw = (float*)cv.take(N * 4);
   c->dzext = (float*)cv.take(T * E1 * 4);
+  c->zraw = (float*)cv.take(T * E1 * 4);
+  c->dwr_tmp = cv.take(E1 * d * es);
+  {
+    size_t a = SPLIT_FOLD * E1 * h, b2 = SPLIT_LOGITS * T * E1, c3 = SPLIT_DWR * E1 * d;
+    size_t mx = a > b2 ? a : b2;
+    if (c3 > mx) mx = c3;
+    c->splitk_ws = (float*)cv.take(mx * 4);
+  }
   c->rinv = (float*)cv.take(2 * T * 4);
   size_t maxcols = d > E1 ? d : E1;
   c->partial = (float*)cv.take(colsum_partial_floats((int)(2 * T), (int)maxcols) * 4);
@@ -293,10 +305,25 @@ int moe_acts(revffn_ctx* c, const revffn_weights* w, const void* y1, i64 ld, int
   const int N = T * k;
   launch_rmsnorm_fwd(dt, y1, ld, w->norm_m, c->n3, h, T, h, f.rms_eps, s);
   TRY(run_gemm(c, nt(c->n3, h, w->pup_m, h, c->Um, d, T, d, h), s));
-  // folded fp32 router matrix  wrp = [W_r ; w_shared_gate] . P_up_m
-  TRY(run_gemm(c, nn(w->w_router, d, w->pup_m, h, c->wrp, h, E, h, d), dt, dt, 0, s));
-  if (Is) TRY(run_gemm(c, nn(w->ws_gate, d, w->pup_m, h, c->wrp + (size_t)E * h, h, 1, h, d), dt, dt, 0, s));
-  launch_router(dt, y1, ld, w->norm_m, c->wrp, w->b_router, c->probs, c->idx, c->wts, c->gamma, T, h, E, k,
+  // folded fp32 router matrix  wrp = [W_r ; w_shared_gate] . P_up_m . diag(gain), then the raw logits
+  // zraw = Y1 . wrp^T, both as fp32 split-k GEMMs on the vector ALUs
+  {
+    GemmArgs a = nn(w->w_router, d, w->pup_m, h, c->wrp, h, E, h, d);
+    a.split_k = SPLIT_FOLD; a.splitk_ws = c->splitk_ws; a.col_scale = w->norm_m;
+    GemmTypes t{dt, dt, 0, dt};
+    if (launch_gemm_generic(a, t, s)) return REVFFN_EUNSUPPORTED;
+    if (Is) {
+      GemmArgs b2 = nn(w->ws_gate, d, w->pup_m, h, c->wrp + (size_t)E * h, h, 1, h, d);
+      b2.split_k = SPLIT_FOLD; b2.splitk_ws = c->splitk_ws; b2.col_scale = w->norm_m;
+      if (launch_gemm_generic(b2, t, s)) return REVFFN_EUNSUPPORTED;
+    }
+    const int E1 = E + (Is ? 1 : 0);
+    GemmArgs z = nt(y1, ld, c->wrp, h, c->zraw, E1, T, E1, h);
+    z.split_k = SPLIT_LOGITS; z.splitk_ws = c->splitk_ws;
+    GemmTypes tz{dt, 0, 0, dt};
+    if (launch_gemm_generic(z, tz, s)) return REVFFN_EUNSUPPORTED;
+  }
+  launch_router(dt, y1, ld, c->zraw, w->b_router, c->probs, c->idx, c->wts, c->gamma, T, h, E, k,
                 Is ? 1 : 0, f.norm_topk_prob, f.rms_eps, s);
   launch_permute(c->idx, T, k, E, c->counts, c->offsets, c->row_map, c->inv_map, c->tg_a, c->tm_a, c->max_tiles_a,
                  BM_A, c->tg_b, c->tm_b, c->max_tiles_b, BM_B, s);
@@ -436,8 +463,15 @@ int backward_impl(revffn_ctx* c, const revffn_weights* w, const void* x1, const 
     TRY(run_gemm(c, e, s));
   }
   launch_router_bwd(c->probs, c->idx, c->wts, c->dw, c->dzext, T, E, k, E1, f.norm_topk_prob, s);
-  if (GF(w_router)) TRY(run_gemm(c, tn(c->dzext, E1, c->Um, d, GF(w_router), d, E, d, T), 0, dt, dt, s));
-  if (Is && GF(ws_gate)) TRY(run_gemm(c, tn(c->dzext + E, E1, c->Um, d, GF(ws_gate), d, 1, d, T), 0, dt, dt, s));
+  if (GF(w_router) || (Is && GF(ws_gate))) {
+    // [dW_r ; dw_shared_gate] = dzext^T . Um in one fp32-A split-k GEMM, then the rows go to their buffers
+    GemmArgs a = tn(c->dzext, E1, c->Um, d, c->dwr_tmp, d, E1, d, T);
+    a.split_k = SPLIT_DWR; a.splitk_ws = c->splitk_ws;
+    GemmTypes t{0, dt, dt, dt};
+    if (launch_gemm_generic(a, t, s)) return REVFFN_EUNSUPPORTED;
+    if (GF(w_router)) launch_copy_rows(dt, c->dwr_tmp, d, GF(w_router), d, E, d, s);
+    if (Is && GF(ws_gate)) launch_copy_rows(dt, at(c->dwr_tmp, (size_t)E * d, es), d, GF(ws_gate), d, 1, d, s);
+  }
   if (g && g->b_router) launch_colsum(0, c->dzext, E1, 0, nullptr, 0, nullptr, 0, g->b_router, c->partial, T, E, s);
   launch_dum_finalize(dt, c->dXg, c->inv_map, Is ? c->dUm_sh : nullptr, c->dzext, w->w_router, w->ws_gate, c->dUm, T,
                       d, k, E, E1, s);

@@ -30,6 +30,10 @@ __global__ void __launch_bounds__(256) gemm_generic_k(GemmArgs g) {
       k0 = g.offsets[grp];
       k_end = g.offsets[grp + 1];
       C += (i64)grp * g.c_group_stride;
+    } else if (g.split_k > 1) {
+      int per = ((g.K + g.split_k - 1) / g.split_k + GK - 1) / GK * GK;
+      k0 = blockIdx.z * per;
+      k_end = min(g.K, k0 + per);
     }
   }
   const int n0 = blockIdx.x * GT;
@@ -91,8 +95,23 @@ __global__ void __launch_bounds__(256) gemm_generic_k(GemmArgs g) {
     }
     __syncthreads();
   }
+  if (g.split_k > 1) {                       // raw partial sums; the epilogue runs in splitk_reduce_k
+    float* ws = g.splitk_ws + (i64)blockIdx.z * g.M * g.N;
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+      int m = m0 + ty * 4 + i;
+      if (m >= m_end) continue;
+#pragma unroll
+      for (int j = 0; j < 4; j++) {
+        int n = n0 + tx * 4 + j;
+        if (n < g.N) ws[(i64)m * g.N + n] = acc[i][j];
+      }
+    }
+    return;
+  }
   const TS* bias = (const TS*)g.bias;
   const TS* resid = (const TS*)g.resid;
+  const TS* cscale = (const TS*)g.col_scale;
 #pragma unroll
   for (int i = 0; i < 4; i++) {
     int m = m0 + ty * 4 + i;
@@ -103,6 +122,7 @@ __global__ void __launch_bounds__(256) gemm_generic_k(GemmArgs g) {
       int n = n0 + tx * 4 + j;
       if (n >= g.N) continue;
       float v = acc[i][j] * rs;
+      if (cscale) v *= to_f(cscale[n]);
       if (bias) v += to_f(bias[n]);
       if (g.tap) g.tap[(i64)m * g.ldtap + n] = v;
       if (resid) v = to_f(resid[(i64)m * g.ldr + n]) + g.resid_sign * v;
@@ -111,23 +131,43 @@ __global__ void __launch_bounds__(256) gemm_generic_k(GemmArgs g) {
   }
 }
 
+// adds the split-k slices in index order, then the usual epilogue
+template <class TC, class TS>
+__global__ void __launch_bounds__(256) splitk_reduce_k(GemmArgs g) {
+  i64 e = (i64)blockIdx.x * 256 + threadIdx.x;
+  if (e >= (i64)g.M * g.N) return;
+  int m = (int)(e / g.N), n = (int)(e % g.N);
+  float v = 0.f;
+  for (int z = 0; z < g.split_k; z++) v += g.splitk_ws[(i64)z * g.M * g.N + e];
+  if (g.row_scale) v *= g.row_scale[m];
+  if (g.col_scale) v *= to_f(((const TS*)g.col_scale)[n]);
+  if (g.bias) v += to_f(((const TS*)g.bias)[n]);
+  if (g.tap) g.tap[(i64)m * g.ldtap + n] = v;
+  if (g.resid) v = to_f(((const TS*)g.resid)[(i64)m * g.ldr + n]) + g.resid_sign * v;
+  ((TC*)g.C)[(i64)m * g.ldc + n] = from_f<TC>(v);
+}
+
 template <class TA, class TB, class TC, class TS>
 static void go(const GemmArgs& g, hipStream_t s) {
   dim3 grid;
   if (g.group_mode == 1) grid = dim3(cdiv(g.N, GT), g.max_tiles, 1);
-  else grid = dim3(cdiv(g.N, GT), cdiv(g.M, GT), g.group_mode == 2 ? g.n_groups : 1);
+  else grid = dim3(cdiv(g.N, GT), cdiv(g.M, GT), g.group_mode == 2 ? g.n_groups : (g.split_k > 1 ? g.split_k : 1));
   if (grid.x == 0 || grid.y == 0 || grid.z == 0) return;
   hipLaunchKernelGGL((gemm_generic_k<TA, TB, TC, TS>), grid, dim3(256), 0, s, g);
+  if (g.group_mode == 0 && g.split_k > 1)
+    hipLaunchKernelGGL((splitk_reduce_k<TC, TS>), dim3(cdiv((i64)g.M * g.N, 256)), dim3(256), 0, s, g);
 }
 
 int launch_gemm_generic(const GemmArgs& g, GemmTypes t, hipStream_t s) {
   if (g.group_mode == 1 && g.tile_bm != GT) return -1;
+  if (g.split_k > 1 && (g.group_mode != 0 || !g.splitk_ws)) return -1;
   int key = t.ta * 8 + t.tb * 4 + t.tc * 2 + t.tside;
   switch (key) {
     case 0: go<float, float, float, float>(g, s); break;            // fp32 everything
     case 15: go<bf16, bf16, bf16, bf16>(g, s); break;               // bf16 everything
     case 13: go<bf16, bf16, float, bf16>(g, s); break;              // bf16 in, fp32 out (router fold)
     case 7: go<float, bf16, bf16, bf16>(g, s); break;               // fp32 A (router logit gradients), bf16 B/C
+    case 9: go<bf16, float, float, bf16>(g, s); break;              // bf16 A, fp32 B/C (router logits)
     default: return -1;
   }
   return 0;

@@ -10,6 +10,7 @@
 // row(i) = i, or gather[i] / gather_div when a gather list is given (a_gather acts on
 // the RA row index, b_gather on the RB row index when b_trans = 1).
 // Epilogue:  v = acc * (row_scale ? row_scale[m] : 1) + (bias ? bias[n] : 0);
+//            (generic kernel only: v *= col_scale[n] first, if col_scale is given)
 //            if (tap) tap[m*ldtap+n] = v;
 //            if (resid) v = resid[m*ldr+n] + resid_sign * v;      C[m*ldc+n] = v
 // Grouping (routed experts):
@@ -30,6 +31,10 @@ struct GemmArgs {
   int group_mode = 0; int n_groups = 1; const int* offsets = nullptr;
   const int* tile_group = nullptr; const int* tile_m0 = nullptr; int max_tiles = 0; int tile_bm = 0;
   i64 b_group_stride = 0, c_group_stride = 0;
+  // generic kernel only: the k range is cut into split_k slices whose fp32 partial tiles go to
+  // splitk_ws[slice][M][N]; a second kernel adds the slices in index order and applies the epilogue
+  int split_k = 1; float* splitk_ws = nullptr;
+  const void* col_scale = nullptr;
 };
 
 // element types of A, B, C: 0 = f32, 1 = bf16.  bias and resid have C's... no: the
@@ -66,8 +71,8 @@ void launch_absdiff_max_copy(int dt, const void* a, i64 lda, const void* b, i64 
                              float* res, int rows, int cols, hipStream_t s);
 
 // ---- routing ---------------------------------------------------------------------
-// logits from the folded fp32 router matrix wrp [E1,h] (E1 = E (+1: shared gate row)).
-void launch_router(int dt, const void* y1, i64 ld, const void* gain, const float* wrp, const float* b_router,
+// zraw[T,E1] = Y1 . (gain * wrp)^T in fp32 (E1 = E (+1: shared gate row)); the kernel scales by 1/rms(Y1)
+void launch_router(int dt, const void* y1, i64 ld, const float* zraw, const float* b_router,
                    float* probs, int* idx, float* wts, float* gamma, int T, int h, int E, int k, int has_gate,
                    int norm_topk, float eps, hipStream_t s);
 // counts/offsets/row_map/inv_map and the two m-tile lists (tile heights bm_a, bm_b)

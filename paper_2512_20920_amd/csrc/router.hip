@@ -12,25 +12,23 @@
 
 // ---------------------------------------------------------------------------------
 // Router.  The logits are z = W_r (P_up_m Norm(Y1)) + b.  They are evaluated as
-// (W_r P_up_m) Norm(Y1) with the product matrix wrp held in fp32 and Norm(Y1) recomputed in
-// fp32 from the stored Y1, so the selection depends only on the bits of Y1 and the weights,
-// not on the rounding of the bf16 intermediate P_up_m Norm(Y1).  Row E of wrp (optional) is
-// the shared expert's gate vector folded the same way.
+// (W_r P_up_m diag(gain)) Y1 / rms(Y1) with the product matrix held in fp32 and applied to the
+// stored Y1 by an fp32 GEMM (zraw), so the selection depends only on the bits of Y1 and the
+// weights, not on the rounding of the bf16 intermediate P_up_m Norm(Y1).  Column E of zraw
+// (optional) is the shared expert's gate vector folded the same way.
 // One wave per token.  Outputs: probs[T,E] (softmax over all experts), idx/wts[T,k] (slots
 // by descending logit, equal logits -> lower expert index), gamma[T] = sigmoid(gate logit).
 // ---------------------------------------------------------------------------------
-#define ROUTER_MAX_E1 257
 template <class T>
-__global__ void __launch_bounds__(256) router_k(const T* __restrict__ y1, i64 ld, const T* __restrict__ gain,
-                                                const float* __restrict__ wrp, const float* __restrict__ b_router,
+__global__ void __launch_bounds__(256) router_k(const T* __restrict__ y1, i64 ld, const float* __restrict__ zraw,
+                                                const float* __restrict__ b_router,
                                                 float* __restrict__ probs, int* __restrict__ idx,
                                                 float* __restrict__ wts, float* __restrict__ gamma, int Tn, int h,
                                                 int E, int k, int has_gate, int norm_topk, float eps) {
-  extern __shared__ float sm[];          // per wave: n[h] then z[E1]
+  extern __shared__ float sm[];          // per wave: z[E1]
   const int E1 = E + (has_gate ? 1 : 0);
   const int wv = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  float* nv = sm + (size_t)wv * (h + E1);
-  float* z = nv + h;
+  float* z = sm + (size_t)wv * E1;
   const int t = blockIdx.x * 4 + wv;
   if (t >= Tn) return;                   // whole wave leaves; no block barriers below
   const T* yr = y1 + (i64)t * ld;
@@ -38,16 +36,9 @@ __global__ void __launch_bounds__(256) router_k(const T* __restrict__ y1, i64 ld
   for (int j = lane; j < h; j += 64) { float v = to_f(yr[j]); ss += v * v; }
   ss = wave_sum(ss);
   const float r = 1.0f / sqrtf(ss / (float)h + eps);
-  for (int j = lane; j < h; j += 64) nv[j] = to_f(yr[j]) * r * to_f(gain[j]);
-  // (same-wave LDS traffic is ordered; no barrier needed between the phases of one wave)
-  for (int e = 0; e < E1; e++) {
-    const float* wr = wrp + (size_t)e * h;
-    float acc = 0.f;
-    for (int j = lane; j < h; j += 64) acc += nv[j] * wr[j];
-    acc = wave_sum(acc);
-    if (lane == 0) z[e] = acc + ((e < E && b_router) ? b_router[e] : 0.f);
-  }
-  __builtin_amdgcn_wave_barrier();
+  for (int e = lane; e < E1; e += 64)
+    z[e] = zraw[(i64)t * E1 + e] * r + ((e < E && b_router) ? b_router[e] : 0.f);
+  __builtin_amdgcn_wave_barrier();       // LDS traffic of one wave is executed in order
   // softmax over the E routed logits
   float mx = -INFINITY;
   for (int e = lane; e < E; e += 64) mx = fmaxf(mx, z[e]);
@@ -85,14 +76,13 @@ __global__ void __launch_bounds__(256) router_k(const T* __restrict__ y1, i64 ld
   if (has_gate && lane == 0) gamma[t] = sigmoid_f(z[E]);
 }
 
-void launch_router(int dt, const void* y1, i64 ld, const void* gain, const float* wrp, const float* b_router,
-                   float* probs, int* idx, float* wts, float* gamma, int Tn, int h, int E, int k, int has_gate,
-                   int norm_topk, float eps, hipStream_t s) {
+void launch_router(int dt, const void* y1, i64 ld, const float* zraw, const float* b_router, float* probs, int* idx,
+                   float* wts, float* gamma, int Tn, int h, int E, int k, int has_gate, int norm_topk, float eps,
+                   hipStream_t s) {
   if (Tn <= 0) return;
-  size_t smem = (size_t)4 * (h + E + 1) * sizeof(float);
-  DISPATCH_DT(dt, hipLaunchKernelGGL(router_k<T>, dim3(cdiv(Tn, 4)), dim3(256), smem, s, (const T*)y1, ld,
-                                     (const T*)gain, wrp, b_router, probs, idx, wts, gamma, Tn, h, E, k, has_gate,
-                                     norm_topk, eps));
+  size_t smem = (size_t)4 * (E + 1) * sizeof(float);
+  DISPATCH_DT(dt, hipLaunchKernelGGL(router_k<T>, dim3(cdiv(Tn, 4)), dim3(256), smem, s, (const T*)y1, ld, zraw,
+                                     b_router, probs, idx, wts, gamma, Tn, h, E, k, has_gate, norm_topk, eps));
 }
 
 // ---------------------------------------------------------------------------------
