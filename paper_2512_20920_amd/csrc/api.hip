@@ -44,6 +44,7 @@ struct revffn_ctx {
   void* slab = nullptr;
   size_t slab_bytes = 0;
   int lastT = 0;
+  int lastT_rows = 0;         // lastT * top_k: permuted rows of the current routing
   // attention half
   void *n12, *U12, *Q, *K, *V, *O, *AO;
   float* lse;
@@ -53,7 +54,7 @@ struct revffn_ctx {
   int *idx, *counts, *offsets, *row_map, *inv_map;
   int *tg_a, *tm_a, *tg_b, *tm_b;
   int max_tiles_a, max_tiles_b;
-  void *GU, *Hh, *Yp, *GUs, *Hs, *Ys, *RS;
+  void *Xg, *GU, *Hh, *Yp, *GUs, *Hs, *Ys, *RS;
   float *tapA, *tapM;
   void *y1c, *xtmp;
   float* resid_dev;
@@ -121,6 +122,7 @@ size_t carve(revffn_ctx* c, char* base) {
   c->tm_a = (int*)cv.take(c->max_tiles_a * 4);
   c->tg_b = (int*)cv.take(c->max_tiles_b * 4);
   c->tm_b = (int*)cv.take(c->max_tiles_b * 4);
+  c->Xg = cv.take(N * d * es);
   c->GU = cv.take(N * 2 * I * es);
   c->Hh = cv.take(N * I * es);
   c->Yp = cv.take(N * d * es);
@@ -221,7 +223,7 @@ void gemm_work(const revffn_ctx* c, const GemmArgs& g, int ta, int tb, int tc, d
   const double ea = ta ? 2 : 4, eb = tb ? 2 : 4, ec = tc ? 2 : 4;
   double M = g.M, N = g.N, K = g.K, G = g.n_groups;
   if (g.group_mode == 1) { *flops = 2 * M * N * K; *bytes = M * K * ea + G * N * K * eb + M * N * ec; }
-  else if (g.group_mode == 2) { double R = (double)c->lastT * c->cfg.top_k;     // rows summed over groups
+  else if (g.group_mode == 2) { double R = K;                                     // rows summed over groups
     *flops = 2 * M * N * R; *bytes = R * M * ea + R * N * eb + G * M * N * ec; }
   else { *flops = 2 * M * N * K; *bytes = M * K * ea + N * K * eb + M * N * ec; }
   if (g.resid) *bytes += M * N * (c->es);
@@ -233,7 +235,12 @@ int run_gemm(revffn_ctx* c, GemmArgs g, int ta, int tb, int tc, hipStream_t s) {
   if (c->prof_on) gemm_work(c, g, ta, tb, tc, &fl, &by);
   ProfScope ps(c, s, fl, by);
   if (c->dt == 1 && c->mode == 0 && ta == 1 && tb == 1) {
-    if (g.group_mode == 1) { g.tile_group = c->tg_b; g.tile_m0 = c->tm_b; g.max_tiles = c->max_tiles_b; g.tile_bm = BM_B; }
+    if (g.group_mode == 1) {
+      // short experts (few rows each): the 64-row tile list wastes fewer padded rows
+      bool small = (i64)c->lastT_rows < (i64)96 * c->cfg.n_experts * 2;
+      if (small) { g.tile_group = c->tg_a; g.tile_m0 = c->tm_a; g.max_tiles = c->max_tiles_a; g.tile_bm = BM_A; }
+      else { g.tile_group = c->tg_b; g.tile_m0 = c->tm_b; g.max_tiles = c->max_tiles_b; g.tile_bm = BM_B; }
+    }
     if (launch_gemm_mfma(g, t, s) == 0) {
       ps.done(g.a_trans ? KID_GEMM_TN : (g.b_trans ? KID_GEMM_NN : KID_GEMM_NT));
       return 0;
@@ -303,6 +310,8 @@ int moe_acts(revffn_ctx* c, const revffn_weights* w, const void* y1, i64 ld, int
   const revffn_config& f = c->cfg;
   const int d = f.d_model, h = d / 2, E = f.n_experts, k = f.top_k, I = f.d_expert, Is = f.d_shared, dt = c->dt;
   const int N = T * k;
+  c->lastT = T;
+  c->lastT_rows = N;
   launch_rmsnorm_fwd(dt, y1, ld, w->norm_m, c->n3, h, T, h, f.rms_eps, s);
   TRY(run_gemm(c, nt(c->n3, h, w->pup_m, h, c->Um, d, T, d, h), s));
   // folded fp32 router matrix  wrp = [W_r ; w_shared_gate] . P_up_m . diag(gain), then the raw logits
@@ -448,14 +457,15 @@ int backward_impl(revffn_ctx* c, const revffn_weights* w, const void* x1, const 
     TRY(run_gemm(c, a, s));
     launch_swiglu_bwd(dt, c->dHh, c->GU, c->dGU, N, I, s);
     if (GF(w_down)) {
-      GemmArgs b = tn(c->dYp, d, c->Hh, I, GF(w_down), I, d, I, 0);        // dWd_e = dYp_e^T . Hh_e
+      GemmArgs b = tn(c->dYp, d, c->Hh, I, GF(w_down), I, d, I, N);        // dWd_e = dYp_e^T . Hh_e
       b.group_mode = 2; b.n_groups = E; b.offsets = c->offsets; b.c_group_stride = (i64)d * I;
       TRY(run_gemm(c, b, s));
     }
     if (GF(w_gate_up)) {
-      GemmArgs b = tn(c->dGU, 2 * I, c->Um, d, GF(w_gate_up), d, 2 * I, d, 0);   // dWgu_e = dGU_e^T . Xg_e
+      // dWgu_e = dGU_e^T . Xg_e, with the permuted input rows Xg materialised once
+      launch_gather_rows(dt, c->Um, c->row_map, k, c->Xg, N, d, s);
+      GemmArgs b = tn(c->dGU, 2 * I, c->Xg, d, GF(w_gate_up), d, 2 * I, d, N);
       b.group_mode = 2; b.n_groups = E; b.offsets = c->offsets; b.c_group_stride = (i64)2 * I * d;
-      b.b_gather = c->row_map; b.gather_div = k;
       TRY(run_gemm(c, b, s));
     }
     GemmArgs e = nn(c->dGU, 2 * I, w->w_gate_up, d, c->dXg, d, N, d, 2 * I);     // dXg = dGU . Wgu_e

@@ -31,52 +31,62 @@ struct Tile {
   static constexpr int chunks = ROWS / 32;        // 16-byte chunks per thread per k-step
 };
 
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+
+// Operands are read through raw buffer descriptors: a load whose byte offset is at or past
+// num_records returns zeros.  Every matrix handed to this kernel spans less than 2 GiB from
+// its base (checked on the host), so num_records = 2 GiB and the offset OOB below stand for
+// "this chunk lies outside the k range / past the last row: give me zeros" without a branch,
+// which keeps the loads of several k-tiles in flight together.
+#define BUF_RECORDS 0x80000000u
+#define OOB 0x80000000u
+
 struct OperandSrc {
-  const bf16* base;     // matrix base (already offset by group)
-  i64 ld;
-  const int* gather;    // row indirection or nullptr
+  __amdgpu_buffer_rsrc_t rsrc;   // matrix base (already offset by group)
+  unsigned ld_bytes;             // row stride in bytes
+  const int* gather;             // row indirection (non-transposed A only) or nullptr
   int div;
-  int row0;             // first tile row (m0 or n0) in the non-contraction index
-  int row_lim;          // exclusive bound of valid rows
+  int row0;                      // first tile row (m0 or n0) in the non-contraction index
+  int row_lim;                   // exclusive bound of valid rows
 };
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p) {
+  return __builtin_amdgcn_make_buffer_rsrc((void*)p, 0, BUF_RECORDS, 0x00020000);
+}
 
 // ---- global -> registers ----------------------------------------------------------
 template <bool TR, int ROWS>
 __device__ __forceinline__ void load_tile(const OperandSrc& s, int k0, int k_end, uint4 (&regs)[Tile<TR, ROWS>::chunks],
-                                          const i64 (&rowoff)[Tile<TR, ROWS>::chunks]) {
+                                          const unsigned (&rowoff)[Tile<TR, ROWS>::chunks]) {
   constexpr int NC = Tile<TR, ROWS>::chunks;
 #pragma unroll
   for (int i = 0; i < NC; i++) {
     int c = threadIdx.x + 256 * i;
-    uint4 v = make_uint4(0, 0, 0, 0);
+    unsigned off;
     if (!TR) {
-      int kc = c & 7;
-      int k = k0 + kc * 8;
-      if (k < k_end) v = *(const uint4*)(s.base + rowoff[i] + k);
+      int k = k0 + (c & 7) * 8;
+      off = (k < k_end) ? rowoff[i] + (unsigned)k * 2u : OOB;
     } else {
-      int krow = c / (ROWS / 8), mc = c % (ROWS / 8);
-      int k = k0 + krow;
-      int m = s.row0 + mc * 8;
-      if (k < k_end && m < s.row_lim) {
-        i64 r = s.gather ? (i64)(s.gather[k] / s.div) : (i64)k;
-        v = *(const uint4*)(s.base + r * s.ld + m);
-      }
+      int k = k0 + c / (ROWS / 8);
+      int m = s.row0 + (c % (ROWS / 8)) * 8;
+      off = (k < k_end && m < s.row_lim) ? (unsigned)k * s.ld_bytes + (unsigned)m * 2u : OOB;
     }
-    regs[i] = v;
+    u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(s.rsrc, off, 0, 0);
+    regs[i] = make_uint4(v[0], v[1], v[2], v[3]);
   }
 }
 
-// per-thread row offsets of the non-transposed operand (fixed over the k loop); rows past
+// per-thread row byte offsets of the non-transposed operand (fixed over the k loop); rows past
 // the limit are clamped to the last valid row (their products are never stored)
 template <int ROWS>
-__device__ __forceinline__ void row_offsets(const OperandSrc& s, i64 (&rowoff)[ROWS / 32]) {
+__device__ __forceinline__ void row_offsets(const OperandSrc& s, unsigned (&rowoff)[ROWS / 32]) {
 #pragma unroll
   for (int i = 0; i < ROWS / 32; i++) {
     int c = threadIdx.x + 256 * i;
     int r = s.row0 + (c >> 3);
     if (r >= s.row_lim) r = s.row_lim - 1;
-    i64 rr = s.gather ? (i64)(s.gather[r] / s.div) : (i64)r;
-    rowoff[i] = rr * s.ld;
+    unsigned rr = s.gather ? (unsigned)(s.gather[r] / s.div) : (unsigned)r;
+    rowoff[i] = rr * s.ld_bytes;
   }
 }
 
@@ -114,11 +124,16 @@ __device__ __forceinline__ bf16x8 load_frag(const bf16* lds, int r0, int kk, int
   }
 }
 
-template <int BM, int BN, bool AT, bool BT, class TC>
+// PD = number of k-tiles kept in flight in registers ahead of the one being multiplied
+#define PD 3
+
+template <int BM, int BN, int WGM, bool AT, bool BT, class TC>
 __global__ void __launch_bounds__(256) gemm_mfma_k(GemmArgs g) {
   typedef Tile<AT, BM> TA_;
   typedef Tile<BT, BN> TB_;
-  constexpr int WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32;
+  constexpr int WGN = 4 / WGM;                       // waves along n
+  constexpr int WM = BM / WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32;
+  static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile must be made of 32x32 blocks");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   bf16* sA = (bf16*)smem_raw;                       // 2 stages of A then 2 stages of B
   bf16* sB = sA + 2 * TA_::elems;
@@ -146,11 +161,11 @@ __global__ void __launch_bounds__(256) gemm_mfma_k(GemmArgs g) {
   }
   const int n0 = blockIdx.x * BN;
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-  const int wm = (wv >> 1) * WM, wn = (wv & 1) * WN;
+  const int wm = (wv / WGN) * WM, wn = (wv % WGN) * WN;
 
-  OperandSrc sa{A, g.lda, g.a_gather, g.gather_div, m0, m_end};
-  OperandSrc sb{Bm, g.ldb, g.b_gather, g.gather_div, n0, g.N};
-  i64 offA[TA_::chunks], offB[TB_::chunks];
+  OperandSrc sa{make_rsrc(A), (unsigned)g.lda * 2u, g.a_gather, g.gather_div, m0, m_end};
+  OperandSrc sb{make_rsrc(Bm), (unsigned)g.ldb * 2u, nullptr, 1, n0, g.N};
+  unsigned offA[TA_::chunks], offB[TB_::chunks];
   if (!AT) row_offsets<BM>(sa, offA);
   if (!BT) row_offsets<BN>(sb, offB);
 
@@ -162,41 +177,49 @@ __global__ void __launch_bounds__(256) gemm_mfma_k(GemmArgs g) {
 #pragma unroll
       for (int e = 0; e < 16; e++) acc[i][j][e] = 0.f;
 
-  uint4 ra[TA_::chunks], rb[TB_::chunks];
+  // Software pipeline: register set u holds k-tile kt+PD while tile kt is multiplied from LDS and
+  // tile kt+1 moves from its register set into the other LDS stage.  Loads and LDS stores are
+  // unconditional (a tile past the end of the k range reads as zeros through the OOB offset), so
+  // the loop body is straight-line code and the compiler can keep 2*PD-1 tile loads outstanding;
+  // only the multiply is skipped for the padding tiles.
+  uint4 ra[PD][TA_::chunks], rb[PD][TB_::chunks];
   const int nk = (k_end - k0 + BK - 1) / BK;
-  if (nk > 0) {
-    load_tile<AT, BM>(sa, k0, k_end, ra, offA);
-    load_tile<BT, BN>(sb, k0, k_end, rb, offB);
-    store_tile<AT, BM>(sA, ra);
-    store_tile<BT, BN>(sB, rb);
+#pragma unroll
+  for (int p = 0; p < PD; p++) {
+    load_tile<AT, BM>(sa, k0 + p * BK, k_end, ra[p], offA);
+    load_tile<BT, BN>(sb, k0 + p * BK, k_end, rb[p], offB);
   }
+  store_tile<AT, BM>(sA, ra[0]);
+  store_tile<BT, BN>(sB, rb[0]);
   __syncthreads();
-  for (int kt = 0; kt < nk; kt++) {
-    const int cur = kt & 1;
-    if (kt + 1 < nk) {
-      load_tile<AT, BM>(sa, k0 + (kt + 1) * BK, k_end, ra, offA);
-      load_tile<BT, BN>(sb, k0 + (kt + 1) * BK, k_end, rb, offB);
+  for (int kt0 = 0; kt0 < nk; kt0 += PD) {
+#pragma unroll
+    for (int u = 0; u < PD; u++) {
+      const int kt = kt0 + u;
+      const int cur = kt & 1;
+      load_tile<AT, BM>(sa, k0 + (kt + PD) * BK, k_end, ra[u], offA);
+      load_tile<BT, BN>(sb, k0 + (kt + PD) * BK, k_end, rb[u], offB);
+      if (kt < nk) {                                  // uniform over the workgroup
+        const bf16* cA = sA + cur * TA_::elems;
+        const bf16* cB = sB + cur * TB_::elems;
+#pragma unroll
+        for (int kk = 0; kk < BK / 16; kk++) {
+          bf16x8 fa[TM], fb[TN];
+#pragma unroll
+          for (int i = 0; i < TM; i++) fa[i] = load_frag<AT, BM>(cA, wm + i * 32, kk, lane);
+#pragma unroll
+          for (int j = 0; j < TN; j++) fb[j] = load_frag<BT, BN>(cB, wn + j * 32, kk, lane);
+#pragma unroll
+          for (int i = 0; i < TM; i++)
+#pragma unroll
+            for (int j = 0; j < TN; j++)
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        }
+      }
+      store_tile<AT, BM>(sA + (cur ^ 1) * TA_::elems, ra[(u + 1) % PD]);   // tile kt+1
+      store_tile<BT, BN>(sB + (cur ^ 1) * TB_::elems, rb[(u + 1) % PD]);
+      __syncthreads();
     }
-    const bf16* cA = sA + cur * TA_::elems;
-    const bf16* cB = sB + cur * TB_::elems;
-#pragma unroll
-    for (int kk = 0; kk < BK / 16; kk++) {
-      bf16x8 fa[TM], fb[TN];
-#pragma unroll
-      for (int i = 0; i < TM; i++) fa[i] = load_frag<AT, BM>(cA, wm + i * 32, kk, lane);
-#pragma unroll
-      for (int j = 0; j < TN; j++) fb[j] = load_frag<BT, BN>(cB, wn + j * 32, kk, lane);
-#pragma unroll
-      for (int i = 0; i < TM; i++)
-#pragma unroll
-        for (int j = 0; j < TN; j++)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
-    }
-    if (kt + 1 < nk) {
-      store_tile<AT, BM>(sA + (cur ^ 1) * TA_::elems, ra);
-      store_tile<BT, BN>(sB + (cur ^ 1) * TB_::elems, rb);
-    }
-    __syncthreads();
   }
 
   // ---- epilogue: lane holds column n = lane & 31 and rows (e>>2)*8 + (lane>>5)*4 + (e&3)
@@ -224,7 +247,7 @@ __global__ void __launch_bounds__(256) gemm_mfma_k(GemmArgs g) {
   }
 }
 
-template <int BM, int BN, bool AT, bool BT, class TC>
+template <int BM, int BN, int WGM, bool AT, bool BT, class TC>
 static void go(const GemmArgs& g, hipStream_t s) {
   dim3 grid;
   if (g.group_mode == 1) grid = dim3(cdiv(g.N, BN), g.max_tiles, 1);
@@ -233,11 +256,23 @@ static void go(const GemmArgs& g, hipStream_t s) {
   size_t smem = (size_t)2 * (Tile<AT, BM>::elems + Tile<BT, BN>::elems) * sizeof(bf16);
   static bool attr_set = false;
   if (!attr_set) {
-    (void)hipFuncSetAttribute((const void*)gemm_mfma_k<BM, BN, AT, BT, TC>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                              (int)smem);
+    (void)hipFuncSetAttribute((const void*)gemm_mfma_k<BM, BN, WGM, AT, BT, TC>,
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     attr_set = true;
   }
-  hipLaunchKernelGGL((gemm_mfma_k<BM, BN, AT, BT, TC>), grid, dim3(256), smem, s, g);
+  hipLaunchKernelGGL((gemm_mfma_k<BM, BN, WGM, AT, BT, TC>), grid, dim3(256), smem, s, g);
+}
+
+template <bool AT, bool BT, class TC>
+static void pick_tile(const GemmArgs& g, hipStream_t s) {
+  if (g.group_mode == 1) {
+    if (g.tile_bm == 64) go<64, 128, 1, AT, BT, TC>(g, s); else go<128, 128, 2, AT, BT, TC>(g, s);
+    return;
+  }
+  // small problems: narrower tiles so that every CU gets at least two workgroups
+  i64 tiles = (i64)cdiv(g.M, 128) * cdiv(g.N, 128) * (g.group_mode == 2 ? g.n_groups : 1);
+  if (tiles < 512 && g.N >= 128) go<128, 64, 2, AT, BT, TC>(g, s);
+  else go<128, 128, 2, AT, BT, TC>(g, s);
 }
 
 static bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
@@ -252,17 +287,24 @@ int launch_gemm_mfma(const GemmArgs& g, GemmTypes t, hipStream_t s) {
   if (g.b_trans && (g.N & 7)) return 1;
   if (g.a_trans && !g.b_trans) return 1;                 // layout not used by the block
   if (g.group_mode == 2 && !(g.a_trans && g.b_trans)) return 1;
-  if (g.group_mode == 1 && (g.a_trans || g.tile_bm != 128)) return 1;
+  if (g.group_mode == 1 && (g.a_trans || (g.tile_bm != 128 && g.tile_bm != 64))) return 1;
   if (g.a_gather && g.a_trans) return 1;
-  if (g.b_gather && !g.b_trans) return 1;
+  if (g.b_gather) return 1;                              // gather along k is not taken: materialise the rows
   if (g.group_mode != 1 && g.M <= 0) return 1;
+  if (g.split_k > 1 || g.col_scale) return 1;
+  // every operand must span less than 2 GiB from its base (32-bit buffer offsets)
+  {
+    const i64 lim = (i64)1 << 30;                        // elements
+    i64 a_rows = g.a_trans ? g.K : g.M, b_rows = g.b_trans ? g.K : g.N;
+    if (a_rows * g.lda >= lim || b_rows * g.ldb >= lim) return 1;
+  }
   const bool f32out = t.tc == 0;
   if (!g.a_trans && !g.b_trans) {
-    if (f32out) go<128, 128, false, false, float>(g, s); else go<128, 128, false, false, bf16>(g, s);
+    if (f32out) pick_tile<false, false, float>(g, s); else pick_tile<false, false, bf16>(g, s);
   } else if (!g.a_trans && g.b_trans) {
-    if (f32out) go<128, 128, false, true, float>(g, s); else go<128, 128, false, true, bf16>(g, s);
+    if (f32out) pick_tile<false, true, float>(g, s); else pick_tile<false, true, bf16>(g, s);
   } else {
-    if (f32out) go<128, 128, true, true, float>(g, s); else go<128, 128, true, true, bf16>(g, s);
+    if (f32out) pick_tile<true, true, float>(g, s); else pick_tile<true, true, bf16>(g, s);
   }
   return 0;
 }
