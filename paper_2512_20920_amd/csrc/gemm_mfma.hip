@@ -11,6 +11,7 @@
 // block of 16 lanes, lane j receives element (j & 3) of the 8-byte words addressed by
 // lanes 4*e + (j >> 2), e = 0..3.
 #include "kernels.h"
+#include <stdlib.h>
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
@@ -202,18 +203,25 @@ __global__ void __launch_bounds__(256) gemm_mfma_k(GemmArgs g) {
       if (kt < nk) {                                  // uniform over the workgroup
         const bf16* cA = sA + cur * TA_::elems;
         const bf16* cB = sB + cur * TB_::elems;
+        // fragments of k-step kk+1 are fetched from LDS while the MFMAs of k-step kk issue
+        bf16x8 fa[2][TM], fb[2][TN];
+#pragma unroll
+        for (int i = 0; i < TM; i++) fa[0][i] = load_frag<AT, BM>(cA, wm + i * 32, 0, lane);
+#pragma unroll
+        for (int j = 0; j < TN; j++) fb[0][j] = load_frag<BT, BN>(cB, wn + j * 32, 0, lane);
 #pragma unroll
         for (int kk = 0; kk < BK / 16; kk++) {
-          bf16x8 fa[TM], fb[TN];
+          if (kk + 1 < BK / 16) {
 #pragma unroll
-          for (int i = 0; i < TM; i++) fa[i] = load_frag<AT, BM>(cA, wm + i * 32, kk, lane);
+            for (int i = 0; i < TM; i++) fa[(kk + 1) & 1][i] = load_frag<AT, BM>(cA, wm + i * 32, kk + 1, lane);
 #pragma unroll
-          for (int j = 0; j < TN; j++) fb[j] = load_frag<BT, BN>(cB, wn + j * 32, kk, lane);
+            for (int j = 0; j < TN; j++) fb[(kk + 1) & 1][j] = load_frag<BT, BN>(cB, wn + j * 32, kk + 1, lane);
+          }
 #pragma unroll
           for (int i = 0; i < TM; i++)
 #pragma unroll
             for (int j = 0; j < TN; j++)
-              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kk & 1][i], fb[kk & 1][j], acc[i][j], 0, 0, 0);
         }
       }
       store_tile<AT, BM>(sA + (cur ^ 1) * TA_::elems, ra[(u + 1) % PD]);   // tile kt+1
@@ -263,8 +271,22 @@ static void go(const GemmArgs& g, hipStream_t s) {
   hipLaunchKernelGGL((gemm_mfma_k<BM, BN, WGM, AT, BT, TC>), grid, dim3(256), smem, s, g);
 }
 
+// REVFFN_GEMM_TILE (tuning aid): 1 = 128x128, 2 = 128x64, 3 = 64x128 for every non-grouped problem
+static int tile_override() {
+  static int v = -1;
+  if (v < 0) { const char* e = getenv("REVFFN_GEMM_TILE"); v = e ? atoi(e) : 0; }
+  return v;
+}
+
 template <bool AT, bool BT, class TC>
 static void pick_tile(const GemmArgs& g, hipStream_t s) {
+  if (g.group_mode != 1 && tile_override()) {
+    switch (tile_override()) {
+      case 1: go<128, 128, 2, AT, BT, TC>(g, s); return;
+      case 2: go<128, 64, 2, AT, BT, TC>(g, s); return;
+      case 3: go<64, 128, 1, AT, BT, TC>(g, s); return;
+    }
+  }
   if (g.group_mode == 1) {
     if (g.tile_bm == 64) go<64, 128, 1, AT, BT, TC>(g, s); else go<128, 128, 2, AT, BT, TC>(g, s);
     return;
