@@ -22,7 +22,7 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 
 
 def cpu_baseline(wl, W32, x1, x2, dy1, dy2, n_inv_iters):
-    """Time the fp64 oracle (as it stands) on the first sequence of the same batch."""
+    """Time the fp64 oracle (as it stands) on the same batch."""
     import numpy as np
     from oracle import revffn_oracle as O
     S = wl.S
@@ -30,14 +30,15 @@ def cpu_baseline(wl, W32, x1, x2, dy1, dy2, n_inv_iters):
     W = O.as_f64(W32)                         # promotion of the stored weights is not timed
     cfg = O.Config(wl.d_model, wl.n_heads, wl.head_dim, wl.n_experts, wl.top_k, wl.d_expert, wl.d_shared,
                    n_inv_iters=n_inv_iters)
-    a, b, ga, gb = (np.ascontiguousarray(t[:S]) for t in (x1, x2, dy1, dy2))
+    nb = min(wl.B, 4)                         # whole sequences; a few seconds each
+    a, b, ga, gb = (np.ascontiguousarray(t[:nb * S]) for t in (x1, x2, dy1, dy2))
     t0 = time.perf_counter()
-    y1, y2 = O.forward(a, b, W, cfg, 1, S)
-    O.grads_reconstructed(y1, y2, ga, gb, W, cfg, 1, S)
+    y1, y2 = O.forward(a, b, W, cfg, nb, S)
+    O.grads_reconstructed(y1, y2, ga, gb, W, cfg, nb, S)
     dt = time.perf_counter() - t0
-    return {"value": S / dt, "unit": "tokens/s", "cores": cores, "kind": "oracle",
-            "sample": f"forward+inverse+backward of sequence 0 (B=1, S={S}) of the same batch, full-size weights, "
-                      f"numpy float64, {dt:.1f} s"}
+    return {"value": nb * S / dt, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+            "sample": f"forward + inverse + backward of {nb} of the {wl.B} sequences (S={S}) of the same batch, "
+                      f"full-size weights, numpy float64, {dt:.1f} s"}
 
 
 def main():
@@ -48,6 +49,9 @@ def main():
     ap.add_argument("--workload", default="qwen_b4s512")
     ap.add_argument("--inv-iters", type=int, default=1, help="fixed-point iterations of the inverse (paper: 1)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--separate-calls", action="store_true",
+                    help="revffn_inverse + revffn_backward as two calls (MoE half evaluated twice) instead of "
+                         "revffn_inverse_backward")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -78,9 +82,14 @@ def main():
     t_setup = time.perf_counter() - t_setup
 
     def step():
+        # forward, then the sweep step: inverse (input rebuilt from the output) + backward at the rebuilt input
         R.revffn_forward(ctx, wstruct, x1d, x2d, y1d, y2d, wl.B, wl.S, wl.h, stream)
-        R.revffn_inverse(ctx, wstruct, y1d, y2d, r1d, r2d, wl.B, wl.S, wl.h, None, stream)
-        R.revffn_backward(ctx, wstruct, r1d, r2d, y1d, dy1d, dy2d, dx1d, dx2d, gstruct, wl.B, wl.S, wl.h, stream)
+        if args.separate_calls:
+            R.revffn_inverse(ctx, wstruct, y1d, y2d, r1d, r2d, wl.B, wl.S, wl.h, None, stream)
+            R.revffn_backward(ctx, wstruct, r1d, r2d, y1d, dy1d, dy2d, dx1d, dx2d, gstruct, wl.B, wl.S, wl.h, stream)
+        else:
+            R.revffn_inverse_backward(ctx, wstruct, y1d, y2d, r1d, r2d, dy1d, dy2d, dx1d, dx2d, gstruct,
+                                      wl.B, wl.S, wl.h, None, stream)
 
     for _ in range(args.warmup):
         step()
@@ -127,7 +136,7 @@ def main():
         "config": {"workload": f"{wl.name}: 1 RevFFN block, d={wl.d_model}, {wl.n_heads} heads x {wl.head_dim}, "
                                f"{wl.n_experts} experts top-{wl.top_k} I={wl.d_expert}, shared {wl.d_shared}, "
                                f"B={wl.B} S={wl.S}, weights N(0,0.02) inputs N(0,1) seed {wl.seed}",
-                   "n_inv_iters": args.inv_iters, "setup_s": round(t_setup, 1)},
+                   "n_inv_iters": args.inv_iters, "calls": "forward+inverse+backward" if args.separate_calls else "forward+inverse_backward", "setup_s": round(t_setup, 1)},
         "roofline": roofline, "kernels": kernels,
     }
     if not args.no_cpu_baseline:

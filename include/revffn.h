@@ -24,9 +24,13 @@
  *  - A stream is token-major [T, h], T = B*S, token t = b*S + s, with row
  *    stride `ld` elements (ld >= h).  ld = d lets the two halves of one [T, d]
  *    hidden tensor be passed without a copy (section 3.1, the split display).
- *  - Every call only enqueues work on `hip_stream` (a hipStream_t; NULL = the
- *    default stream) and returns; it never synchronises.  Calls on one context
- *    must be issued on one stream at a time (they share the context workspace).
+ *  - Every call only enqueues work and returns; it never synchronises the host.
+ *    Work is ordered after what `hip_stream` (a hipStream_t; NULL = the default
+ *    stream) already holds, and `hip_stream` is ordered after all of it when the call
+ *    returns; independent branches inside a call run on two helper streams owned by
+ *    the context (default priority; set REVFFN_NO_STREAMS=1 to keep everything on
+ *    `hip_stream`).  Calls on one context must be issued on one stream at a time
+ *    (they share the context workspace).
  *  - Return value: 0 on success, a negative REVFFN_E* code otherwise.  No call
  *    throws or aborts.  On error nothing has been enqueued.
  *  - Results are deterministic: no floating-point atomics anywhere, so the same
@@ -144,6 +148,17 @@ int revffn_backward(revffn_ctx *ctx, const revffn_weights *w,
                     const void *x1, const void *x2, const void *y1,
                     const void *dy1, const void *dy2, void *dx1, void *dx2,
                     const revffn_grads *g, int32_t B, int32_t S, int64_t ld, void *hip_stream);
+
+/* One step of the reversible backward sweep (section 3.1): revffn_inverse followed by
+ * revffn_backward at the rebuilt input, in one call.  The MoE half is evaluated once, at the
+ * exact y1, and serves both the inverse (X2^ = Y2 - MoE branch) and the backward pass; the
+ * results are bit-identical to the two separate calls.  x1/x2 (rebuilt input, out) may alias
+ * y1/y2; dx1/dx2 may alias dy1/dy2. */
+int revffn_inverse_backward(revffn_ctx *ctx, const revffn_weights *w,
+                            const void *y1, const void *y2, void *x1, void *x2,
+                            const void *dy1, const void *dy2, void *dx1, void *dx2,
+                            const revffn_grads *g, int32_t B, int32_t S, int64_t ld,
+                            float *residual, void *hip_stream);
 
 /* Stack of n_blocks blocks (section 3.1: only the last hidden state is kept).
  * Forward: (x1,x2) -> (y1,y2) through w[0..n_blocks-1], no stream swap between

@@ -43,6 +43,10 @@ struct revffn_ctx {
   int device = 0;
   void* slab = nullptr;
   size_t slab_bytes = 0;
+  hipStream_t side[2] = {nullptr, nullptr};   // helper streams for independent branches of one call
+  std::vector<hipEvent_t>* sync_ev = nullptr;  // ring of timing-free events for fork/join
+  size_t sync_next = 0;
+  bool use_streams = true;
   int lastT = 0;
   int lastT_rows = 0;         // lastT * top_k: permuted rows of the current routing
   // attention half
@@ -60,7 +64,7 @@ struct revffn_ctx {
   float* resid_dev;
   // backward
   void *dRS, *dYp, *dYs, *dHs, *dGUs, *dUm_sh, *dHh, *dGU, *dXg, *dUm, *dn3, *g1;
-  float *dw, *dzext, *rinv, *partial;
+  float *dw, *dzext, *rinv, *rinv3, *partial;
   float *zraw, *splitk_ws;
   void* dwr_tmp;
   void *dAO, *dO, *dQ, *dK, *dV, *dU12, *dn12;
@@ -158,6 +162,7 @@ size_t carve(revffn_ctx* c, char* base) {
     c->splitk_ws = (float*)cv.take(mx * 4);
   }
   c->rinv = (float*)cv.take(2 * T * 4);
+  c->rinv3 = (float*)cv.take(T * 4);
   size_t maxcols = d > E1 ? d : E1;
   c->partial = (float*)cv.take(colsum_partial_floats((int)(2 * T), (int)maxcols) * 4);
   c->dAO = cv.take(T * d * es);
@@ -255,6 +260,25 @@ int run_gemm(revffn_ctx* c, const GemmArgs& g, hipStream_t s) { return run_gemm(
 
 #define TRY(x) do { int _e = (x); if (_e) return _e; } while (0)
 
+// ---- fork / join between the caller's stream and the context's helper streams ----------
+// Independent branches of one call (K and V projections next to Q, the shared expert next to
+// the routed experts, every weight-gradient GEMM next to the data-gradient chain) run on helper
+// streams of default priority, so that launches too small to fill 256 CUs overlap.
+hipEvent_t next_sync(revffn_ctx* c) {
+  hipEvent_t e = (*c->sync_ev)[c->sync_next % c->sync_ev->size()];
+  c->sync_next++;
+  return e;
+}
+// stream `to` waits for everything enqueued so far on `from`
+void after(revffn_ctx* c, hipStream_t from, hipStream_t to) {
+  if (from == to) return;
+  hipEvent_t e = next_sync(c);
+  (void)hipEventRecord(e, from);
+  (void)hipStreamWaitEvent(to, e, 0);
+}
+// helper stream i, or the main stream when helper streams are switched off
+hipStream_t side(revffn_ctx* c, hipStream_t main, int i) { return c->use_streams ? c->side[i] : main; }
+
 // ---- attention half ---------------------------------------------------------------
 // Recomputes n12, U12, Q, (K, V), O, lse, AO at streams (x1, x2).
 int attn_acts(revffn_ctx* c, const revffn_weights* w, const void* x1, i64 ld1, const void* x2, i64 ld2, int B, int S,
@@ -265,21 +289,23 @@ int attn_acts(revffn_ctx* c, const revffn_weights* w, const void* x1, i64 ld1, c
   if (do_kv) launch_rmsnorm_fwd(dt, x2, ld2, w->norm_a2, at(c->n12, (size_t)T * h, es), h, T, h, f.rms_eps, s);
   // the same P_up serves both streams: one GEMM over the stacked rows
   TRY(run_gemm(c, nt(c->n12, h, w->pup_a, h, c->U12, d, do_kv ? 2 * T : T, d, h), s));
+  hipStream_t s0 = side(c, s, 0), s1 = side(c, s, 1);
+  if (do_kv) { after(c, s, s0); after(c, s, s1); }
   GemmArgs gq = nt(c->U12, d, w->wq, d, c->Q, d, T, d, d);
   gq.bias = w->bq;
   TRY(run_gemm(c, gq, s));
+  if (f.use_rope) launch_rope(dt, c->Q, c->rope_cs, T, S, f.n_heads, f.head_dim, 1.f, s);
   if (do_kv) {
     const void* U2 = at(c->U12, (size_t)T * d, es);
     GemmArgs gk = nt(U2, d, w->wk, d, c->K, d, T, d, d);
     gk.bias = w->bk;
-    TRY(run_gemm(c, gk, s));
+    TRY(run_gemm(c, gk, s0));
+    if (f.use_rope) launch_rope(dt, c->K, c->rope_cs, T, S, f.n_heads, f.head_dim, 1.f, s0);
     GemmArgs gv = nt(U2, d, w->wv, d, c->V, d, T, d, d);
     gv.bias = w->bv;
-    TRY(run_gemm(c, gv, s));
-  }
-  if (f.use_rope) {
-    launch_rope(dt, c->Q, c->rope_cs, T, S, f.n_heads, f.head_dim, 1.f, s);
-    if (do_kv) launch_rope(dt, c->K, c->rope_cs, T, S, f.n_heads, f.head_dim, 1.f, s);
+    TRY(run_gemm(c, gv, s1));
+    after(c, s0, s);
+    after(c, s1, s);
   }
   {
     // algorithmic work of the attention core: QK^T and PV, halved by the causal mask
@@ -314,6 +340,13 @@ int moe_acts(revffn_ctx* c, const revffn_weights* w, const void* y1, i64 ld, int
   c->lastT_rows = N;
   launch_rmsnorm_fwd(dt, y1, ld, w->norm_m, c->n3, h, T, h, f.rms_eps, s);
   TRY(run_gemm(c, nt(c->n3, h, w->pup_m, h, c->Um, d, T, d, h), s));
+  hipStream_t s0 = side(c, s, 0);
+  if (Is) {                               // the shared expert needs Um only: next to routing + routed experts
+    after(c, s, s0);
+    TRY(run_gemm(c, nt(c->Um, d, w->ws_gate_up, d, c->GUs, 2 * Is, T, 2 * Is, d), s0));
+    launch_swiglu_fwd(dt, c->GUs, c->Hs, T, Is, s0);
+    TRY(run_gemm(c, nt(c->Hs, Is, w->ws_down, Is, c->Ys, d, T, d, Is), s0));
+  }
   // folded fp32 router matrix  wrp = [W_r ; w_shared_gate] . P_up_m . diag(gain), then the raw logits
   // zraw = Y1 . wrp^T, both as fp32 split-k GEMMs on the vector ALUs
   {
@@ -345,11 +378,7 @@ int moe_acts(revffn_ctx* c, const revffn_weights* w, const void* y1, i64 ld, int
   GemmArgs g2 = nt(c->Hh, I, w->w_down, I, c->Yp, d, N, d, I);
   g2.group_mode = 1; g2.n_groups = E; g2.offsets = c->offsets; g2.b_group_stride = (i64)d * I;
   TRY(run_gemm(c, g2, s));
-  if (Is) {
-    TRY(run_gemm(c, nt(c->Um, d, w->ws_gate_up, d, c->GUs, 2 * Is, T, 2 * Is, d), s));
-    launch_swiglu_fwd(dt, c->GUs, c->Hs, T, Is, s);
-    TRY(run_gemm(c, nt(c->Hs, Is, w->ws_down, Is, c->Ys, d, T, d, Is), s));
-  }
+  if (Is) after(c, s0, s);
   launch_combine(dt, c->Yp, c->inv_map, c->wts, Is ? c->Ys : nullptr, c->gamma, c->RS, T, d, k, s);
   c->lastT = T;
   return 0;
@@ -440,33 +469,46 @@ int backward_impl(revffn_ctx* c, const revffn_weights* w, const void* x1, const 
   // ---- recompute the MoE half at the exact y1
   if (!reuse_moe) TRY(moe_acts(c, w, y1, ldy, T, s));
   // ---- MoE half backward: Y2 = X2 + P_dn_m(RS)
-  if (GF(pdn_m)) TRY(run_gemm(c, tn(dy2, ld, c->RS, d, GF(pdn_m), d, h, d, T), s));
+  // sw: weight gradients (leaves of the graph, joined at the very end); s0: shared-expert branch
+  hipStream_t sw = side(c, s, 1), s0 = side(c, s, 0);
+  if (GF(pdn_m)) {
+    // reads dy2: stays on the caller's stream when dx2 aliases dy2 (dx2 is written at the very end)
+    hipStream_t sp = (dx2 == dy2) ? s : sw;
+    after(c, s, sp);
+    TRY(run_gemm(c, tn(dy2, ld, c->RS, d, GF(pdn_m), d, h, d, T), sp));
+  }
   TRY(run_gemm(c, nn(dy2, ld, w->pdn_m, d, c->dRS, d, T, d, h), s));
   launch_moe_bwd_rows(dt, c->dRS, c->Yp, c->Ys, c->inv_map, c->wts, c->gamma, c->dYp, c->dYs, c->dw, c->dzext, T, d,
                       k, E1, Is ? 1 : 0, s);
   if (Is) {
-    if (GF(ws_down)) TRY(run_gemm(c, tn(c->dYs, d, c->Hs, Is, GF(ws_down), Is, d, Is, T), s));
-    TRY(run_gemm(c, nn(c->dYs, d, w->ws_down, Is, c->dHs, Is, T, Is, d), s));
-    launch_swiglu_bwd(dt, c->dHs, c->GUs, c->dGUs, T, Is, s);
-    if (GF(ws_gate_up)) TRY(run_gemm(c, tn(c->dGUs, 2 * Is, c->Um, d, GF(ws_gate_up), d, 2 * Is, d, T), s));
-    TRY(run_gemm(c, nn(c->dGUs, 2 * Is, w->ws_gate_up, d, c->dUm_sh, d, T, d, 2 * Is), s));
+    after(c, s, s0);
+    if (GF(ws_down)) { after(c, s, sw); TRY(run_gemm(c, tn(c->dYs, d, c->Hs, Is, GF(ws_down), Is, d, Is, T), sw)); }
+    TRY(run_gemm(c, nn(c->dYs, d, w->ws_down, Is, c->dHs, Is, T, Is, d), s0));
+    launch_swiglu_bwd(dt, c->dHs, c->GUs, c->dGUs, T, Is, s0);
+    if (GF(ws_gate_up)) {
+      after(c, s0, sw);
+      TRY(run_gemm(c, tn(c->dGUs, 2 * Is, c->Um, d, GF(ws_gate_up), d, 2 * Is, d, T), sw));
+    }
+    TRY(run_gemm(c, nn(c->dGUs, 2 * Is, w->ws_gate_up, d, c->dUm_sh, d, T, d, 2 * Is), s0));
   }
   {
+    if (GF(w_down)) {
+      after(c, s, sw);
+      GemmArgs b = tn(c->dYp, d, c->Hh, I, GF(w_down), I, d, I, N);        // dWd_e = dYp_e^T . Hh_e
+      b.group_mode = 2; b.n_groups = E; b.offsets = c->offsets; b.c_group_stride = (i64)d * I;
+      TRY(run_gemm(c, b, sw));
+    }
     GemmArgs a = nn(c->dYp, d, w->w_down, I, c->dHh, I, N, I, d);          // dHh = dYp . Wd_e
     a.group_mode = 1; a.n_groups = E; a.offsets = c->offsets; a.b_group_stride = (i64)d * I;
     TRY(run_gemm(c, a, s));
     launch_swiglu_bwd(dt, c->dHh, c->GU, c->dGU, N, I, s);
-    if (GF(w_down)) {
-      GemmArgs b = tn(c->dYp, d, c->Hh, I, GF(w_down), I, d, I, N);        // dWd_e = dYp_e^T . Hh_e
-      b.group_mode = 2; b.n_groups = E; b.offsets = c->offsets; b.c_group_stride = (i64)d * I;
-      TRY(run_gemm(c, b, s));
-    }
     if (GF(w_gate_up)) {
       // dWgu_e = dGU_e^T . Xg_e, with the permuted input rows Xg materialised once
-      launch_gather_rows(dt, c->Um, c->row_map, k, c->Xg, N, d, s);
+      after(c, s, sw);
+      launch_gather_rows(dt, c->Um, c->row_map, k, c->Xg, N, d, sw);
       GemmArgs b = tn(c->dGU, 2 * I, c->Xg, d, GF(w_gate_up), d, 2 * I, d, N);
       b.group_mode = 2; b.n_groups = E; b.offsets = c->offsets; b.c_group_stride = (i64)2 * I * d;
-      TRY(run_gemm(c, b, s));
+      TRY(run_gemm(c, b, sw));
     }
     GemmArgs e = nn(c->dGU, 2 * I, w->w_gate_up, d, c->dXg, d, N, d, 2 * I);     // dXg = dGU . Wgu_e
     e.group_mode = 1; e.n_groups = E; e.offsets = c->offsets; e.b_group_stride = (i64)2 * I * d;
@@ -482,18 +524,23 @@ int backward_impl(revffn_ctx* c, const revffn_weights* w, const void* x1, const 
     if (GF(w_router)) launch_copy_rows(dt, c->dwr_tmp, d, GF(w_router), d, E, d, s);
     if (Is && GF(ws_gate)) launch_copy_rows(dt, at(c->dwr_tmp, (size_t)E * d, es), d, GF(ws_gate), d, 1, d, s);
   }
-  if (g && g->b_router) launch_colsum(0, c->dzext, E1, 0, nullptr, 0, nullptr, 0, g->b_router, c->partial, T, E, s);
+  if (g && g->b_router) {
+    after(c, s, sw);
+    launch_colsum(0, c->dzext, E1, 0, nullptr, 0, nullptr, 0, g->b_router, c->partial, T, E, sw);
+  }
+  if (Is) after(c, s0, s);
   launch_dum_finalize(dt, c->dXg, c->inv_map, Is ? c->dUm_sh : nullptr, c->dzext, w->w_router, w->ws_gate, c->dUm, T,
                       d, k, E, E1, s);
-  if (GF(pup_m)) TRY(run_gemm(c, tn(c->dUm, d, c->n3, h, GF(pup_m), h, d, h, T), s));
+  if (GF(pup_m)) { after(c, s, sw); TRY(run_gemm(c, tn(c->dUm, d, c->n3, h, GF(pup_m), h, d, h, T), sw)); }
   TRY(run_gemm(c, nn(c->dUm, d, w->pup_m, h, c->dn3, h, T, h, d), s));
   // g1 = dY1 + Norm'(dn3): total gradient at Y1
-  launch_rmsnorm_bwd(dt, c->dn3, h, y1, ldy, w->norm_m, dy1, ld, c->g1, h, c->rinv, T, h, f.rms_eps, s);
-  if (GF(norm_m)) launch_colsum(dt, y1, ldy, dt, c->dn3, h, c->rinv, dt, GF(norm_m), c->partial, T, h, s);
+  launch_rmsnorm_bwd(dt, c->dn3, h, y1, ldy, w->norm_m, dy1, ld, c->g1, h, c->rinv3, T, h, f.rms_eps, s);
   // ---- attention half backward: Y1 = X1 + P_dn_a(AO)
-  if (GF(pdn_a)) TRY(run_gemm(c, tn(c->g1, h, c->AO, d, GF(pdn_a), d, h, d, T), s));
+  after(c, s, sw);
+  if (GF(norm_m)) launch_colsum(dt, y1, ldy, dt, c->dn3, h, c->rinv3, dt, GF(norm_m), c->partial, T, h, sw);
+  if (GF(pdn_a)) TRY(run_gemm(c, tn(c->g1, h, c->AO, d, GF(pdn_a), d, h, d, T), sw));
   TRY(run_gemm(c, nn(c->g1, h, w->pdn_a, d, c->dAO, d, T, d, h), s));
-  if (GF(wo)) TRY(run_gemm(c, tn(c->dAO, d, c->O, d, GF(wo), d, d, d, T), s));
+  if (GF(wo)) { after(c, s, sw); TRY(run_gemm(c, tn(c->dAO, d, c->O, d, GF(wo), d, d, d, T), sw)); }
   TRY(run_gemm(c, nn(c->dAO, d, w->wo, d, c->dO, d, T, d, d), s));
   {
     // five S x S x dh products (scores, dP, dV, dQ, dK), halved by the causal mask
@@ -516,28 +563,33 @@ int backward_impl(revffn_ctx* c, const revffn_weights* w, const void* x1, const 
   const void* U2 = at(c->U12, (size_t)T * d, es);
   void* dU1 = c->dU12;
   void* dU2 = at(c->dU12, (size_t)T * d, es);
-  if (GF(wq)) TRY(run_gemm(c, tn(c->dQ, d, U1, d, GF(wq), d, d, d, T), s));
-  if (GF(wk)) TRY(run_gemm(c, tn(c->dK, d, U2, d, GF(wk), d, d, d, T), s));
-  if (GF(wv)) TRY(run_gemm(c, tn(c->dV, d, U2, d, GF(wv), d, d, d, T), s));
-  if (GF(bq) && w->bq) launch_colsum(dt, c->dQ, d, dt, nullptr, 0, nullptr, dt, GF(bq), c->partial, T, d, s);
-  if (GF(bk) && w->bk) launch_colsum(dt, c->dK, d, dt, nullptr, 0, nullptr, dt, GF(bk), c->partial, T, d, s);
-  if (GF(bv) && w->bv) launch_colsum(dt, c->dV, d, dt, nullptr, 0, nullptr, dt, GF(bv), c->partial, T, d, s);
-  TRY(run_gemm(c, nn(c->dQ, d, w->wq, d, dU1, d, T, d, d), s));
+  after(c, s, sw);
+  after(c, s, s0);
+  if (GF(wq)) TRY(run_gemm(c, tn(c->dQ, d, U1, d, GF(wq), d, d, d, T), sw));
+  if (GF(wk)) TRY(run_gemm(c, tn(c->dK, d, U2, d, GF(wk), d, d, d, T), sw));
+  if (GF(wv)) TRY(run_gemm(c, tn(c->dV, d, U2, d, GF(wv), d, d, d, T), sw));
+  if (GF(bq) && w->bq) launch_colsum(dt, c->dQ, d, dt, nullptr, 0, nullptr, dt, GF(bq), c->partial, T, d, sw);
+  if (GF(bk) && w->bk) launch_colsum(dt, c->dK, d, dt, nullptr, 0, nullptr, dt, GF(bk), c->partial, T, d, sw);
+  if (GF(bv) && w->bv) launch_colsum(dt, c->dV, d, dt, nullptr, 0, nullptr, dt, GF(bv), c->partial, T, d, sw);
+  TRY(run_gemm(c, nn(c->dQ, d, w->wq, d, dU1, d, T, d, d), s0));
   TRY(run_gemm(c, nn(c->dK, d, w->wk, d, dU2, d, T, d, d), s));
   {
     GemmArgs a = nn(c->dV, d, w->wv, d, dU2, d, T, d, d);        // dU2 += dV . Wv
     a.resid = dU2; a.ldr = d; a.resid_sign = 1.f;
     TRY(run_gemm(c, a, s));
   }
-  if (GF(pup_a)) TRY(run_gemm(c, tn(c->dU12, d, c->n12, h, GF(pup_a), h, d, h, 2 * T), s));
+  after(c, s0, s);
+  if (GF(pup_a)) { after(c, s, sw); TRY(run_gemm(c, tn(c->dU12, d, c->n12, h, GF(pup_a), h, d, h, 2 * T), sw)); }
   TRY(run_gemm(c, nn(c->dU12, d, w->pup_a, h, c->dn12, h, 2 * T, h, d), s));
   // dX1 = g1 + Norm'(dn1);  dX2 = dY2 + Norm'(dn2)
   launch_rmsnorm_bwd(dt, c->dn12, h, x1, ld, w->norm_a1, c->g1, h, dx1, ld, c->rinv, T, h, f.rms_eps, s);
   launch_rmsnorm_bwd(dt, at(c->dn12, (size_t)T * h, es), h, x2, ld, w->norm_a2, dy2, ld, dx2, ld, c->rinv + T, T, h,
                      f.rms_eps, s);
-  if (GF(norm_a1)) launch_colsum(dt, x1, ld, dt, c->dn12, h, c->rinv, dt, GF(norm_a1), c->partial, T, h, s);
+  after(c, s, sw);
+  if (GF(norm_a1)) launch_colsum(dt, x1, ld, dt, c->dn12, h, c->rinv, dt, GF(norm_a1), c->partial, T, h, sw);
   if (GF(norm_a2))
-    launch_colsum(dt, x2, ld, dt, at(c->dn12, (size_t)T * h, es), h, c->rinv + T, dt, GF(norm_a2), c->partial, T, h, s);
+    launch_colsum(dt, x2, ld, dt, at(c->dn12, (size_t)T * h, es), h, c->rinv + T, dt, GF(norm_a2), c->partial, T, h, sw);
+  after(c, sw, s);                       // every weight gradient is complete for the caller's stream
   return 0;
 }
 
@@ -555,6 +607,8 @@ size_t revffn_workspace_bytes(const revffn_config* cfg, int32_t max_B, int32_t m
   tmp.maxT = max_B * max_S;
   return carve(&tmp, nullptr);
 }
+
+void revffn_destroy(revffn_ctx* c);
 
 int revffn_create(revffn_ctx** out, const revffn_config* cfg, int32_t max_B, int32_t max_S) {
   if (!out) return REVFFN_ENULL;
@@ -580,6 +634,16 @@ int revffn_create(revffn_ctx** out, const revffn_config* cfg, int32_t max_B, int
     return REVFFN_EWORKSPACE;
   }
   carve(c, (char*)c->slab);
+  c->use_streams = getenv("REVFFN_NO_STREAMS") == nullptr;
+  c->sync_ev = new (std::nothrow) std::vector<hipEvent_t>();
+  bool ok = c->sync_ev != nullptr;
+  for (int i = 0; ok && i < 2; i++) ok = hipStreamCreateWithFlags(&c->side[i], hipStreamNonBlocking) == hipSuccess;
+  for (int i = 0; ok && i < 96; i++) {
+    hipEvent_t e;
+    ok = hipEventCreateWithFlags(&e, hipEventDisableTiming) == hipSuccess;
+    if (ok) c->sync_ev->push_back(e);
+  }
+  if (!ok) { revffn_destroy(c); return REVFFN_EHIP; }
   // rotary table: cs[s][i] = (cos, sin)(s * theta^(-2i/dh)), built in double precision on the host
   const int half = cfg->head_dim / 2;
   std::vector<float> tab((size_t)c->maxT * half * 2);
@@ -605,12 +669,18 @@ static void prof_clear(revffn_ctx* c) {
 
 void revffn_destroy(revffn_ctx* c) {
   if (!c) return;
+  (void)hipDeviceSynchronize();          // helper streams may still hold work of the last call
   if (c->prof) {
     prof_clear(c);
     for (hipEvent_t e : *c->ev_pool) (void)hipEventDestroy(e);
     delete c->prof;
     delete c->ev_pool;
   }
+  if (c->sync_ev) {
+    for (hipEvent_t e : *c->sync_ev) (void)hipEventDestroy(e);
+    delete c->sync_ev;
+  }
+  for (int i = 0; i < 2; i++) if (c->side[i]) (void)hipStreamDestroy(c->side[i]);
   if (c->slab) (void)hipFree(c->slab);
   delete c;
 }
@@ -684,6 +754,18 @@ int revffn_backward(revffn_ctx* c, const revffn_weights* w, const void* x1, cons
   TRY(check_call(c, w, B, S, ld));
   if (!x1 || !x2 || !dy1 || !dy2 || !dx1 || !dx2) return REVFFN_ENULL;
   return backward_impl(c, w, x1, x2, y1, ld, dy1, dy2, dx1, dx2, g, B, S, ld, false, (hipStream_t)stream);
+}
+
+int revffn_inverse_backward(revffn_ctx* c, const revffn_weights* w, const void* y1, const void* y2, void* x1, void* x2,
+                            const void* dy1, const void* dy2, void* dx1, void* dx2, const revffn_grads* g, int32_t B,
+                            int32_t S, int64_t ld, float* residual, void* stream) {
+  TRY(check_call(c, w, B, S, ld));
+  if (!y1 || !y2 || !x1 || !x2 || !dy1 || !dy2 || !dx1 || !dx2) return REVFFN_ENULL;
+  hipStream_t s = (hipStream_t)stream;
+  const void* y1k = nullptr;
+  i64 ldk = 0;
+  TRY(inverse_impl(c, w, y1, y2, x1, x2, B, S, ld, residual, s, &y1k, &ldk));
+  return backward_impl(c, w, x1, x2, y1k, ldk, dy1, dy2, dx1, dx2, g, B, S, ld, true, s);
 }
 
 int revffn_stack_forward(revffn_ctx* c, const revffn_weights* w, int32_t n_blocks, const void* x1, const void* x2,

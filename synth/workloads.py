@@ -60,7 +60,7 @@ WEIGHT_FIELDS = (
 # Scale of the Zipf router bias b_e = ZIPF_ALPHA * (-1.2 * ln rank_e), chosen so the
 # hottest expert gets about 8x the mean load on the zipf workload.  The value is
 # written by tests/golden/calibrate_zipf.py (which calls only the oracle).
-ZIPF_ALPHA = 0.28
+ZIPF_ALPHA = 0.2691
 
 
 def weight_shapes(wl):

@@ -178,6 +178,55 @@ def test_deterministic_and_in_place_and_strided(name):
     assert torch.equal(dxa, dxc) and torch.equal(dxb, dxd)
 
 
+@pytest.mark.parametrize("name", ["mid_f32", "mid_bf16"])
+def test_inverse_backward_equals_the_two_calls(name):
+    wl = synth.WORKLOADS[name]
+    case = Case(wl)
+    case.ctx.set_inv_iters(2)
+    y1d, y2d = case.forward()
+    x1d, x2d, res_a = case.inverse(y1d, y2d, want_residual=True)
+    dx1, dx2, G = case.backward(x1d, x2d, y1d)
+    # fused, out of place
+    r1, r2, o1, o2 = case.empty(), case.empty(), case.empty(), case.empty()
+    G2 = Hn.alloc_grads(case.Wd)
+    res = torch.zeros((1,), dtype=torch.float32, device="cuda")
+    R.revffn_inverse_backward(case.ctx, case.Wd, y1d, y2d, r1, r2, case.up(case.dy1), case.up(case.dy2), o1, o2, G2,
+                              wl.B, wl.S, wl.h, res)
+    torch.cuda.synchronize()
+    assert torch.equal(r1, x1d) and torch.equal(r2, x2d) and torch.equal(o1, dx1) and torch.equal(o2, dx2)
+    assert float(res.item()) == res_a
+    for k in G:
+        if G[k] is not None:
+            assert torch.equal(G[k], G2[k]), k
+    # fused, fully in place (the sweep's calling pattern)
+    a, b, ga, gb = y1d.clone(), y2d.clone(), case.up(case.dy1), case.up(case.dy2)
+    G3 = Hn.alloc_grads(case.Wd)
+    R.revffn_inverse_backward(case.ctx, case.Wd, a, b, a, b, ga, gb, ga, gb, G3, wl.B, wl.S, wl.h, None)
+    torch.cuda.synchronize()
+    assert torch.equal(a, x1d) and torch.equal(b, x2d) and torch.equal(ga, dx1) and torch.equal(gb, dx2)
+    for k in G:
+        if G[k] is not None:
+            assert torch.equal(G[k], G3[k]), k
+
+
+def test_helper_streams_do_not_change_results(monkeypatch):
+    """Same bits with the work spread over the helper streams and with everything on one stream."""
+    wl = synth.WORKLOADS["mid_bf16"]
+    outs = []
+    for no_streams in (False, True):
+        if no_streams:
+            monkeypatch.setenv("REVFFN_NO_STREAMS", "1")
+        else:
+            monkeypatch.delenv("REVFFN_NO_STREAMS", raising=False)
+        case = Case(wl)
+        y1d, y2d = case.forward()
+        x1d, x2d = case.inverse(y1d, y2d, n_iters=2)
+        dx1, dx2, G = case.backward(x1d, x2d, y1d)
+        outs.append([y1d, y2d, x1d, x2d, dx1, dx2] + [G[k] for k in sorted(G) if G[k] is not None])
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
+
+
 def test_frozen_groups_are_skipped():
     """NULL gradient fields (adapter-only stage; frozen routers) leave the others unchanged."""
     wl = synth.WORKLOADS["mid_f32"]
