@@ -67,6 +67,7 @@ struct revffn_ctx {
   float *dw, *dzext, *rinv, *rinv3, *partial;
   float *zraw, *splitk_ws;
   void* dwr_tmp;
+  void* wr_ext;
   void *dAO, *dO, *dQ, *dK, *dV, *dU12, *dn12;
   float* dvec;
   float* rope_cs;
@@ -155,6 +156,7 @@ size_t carve(revffn_ctx* c, char* base) {
   c->dzext = (float*)cv.take(T * E1 * 4);
   c->zraw = (float*)cv.take(T * E1 * 4);
   c->dwr_tmp = cv.take(E1 * d * es);
+  c->wr_ext = cv.take(E1 * d * es);
   {
     size_t a = SPLIT_FOLD * E1 * h, b2 = SPLIT_LOGITS * T * E1, c3 = SPLIT_DWR * E1 * d;
     size_t mx = a > b2 ? a : b2;
@@ -350,15 +352,12 @@ int moe_acts(revffn_ctx* c, const revffn_weights* w, const void* y1, i64 ld, int
   // folded fp32 router matrix  wrp = [W_r ; w_shared_gate] . P_up_m . diag(gain), then the raw logits
   // zraw = Y1 . wrp^T, both as fp32 split-k GEMMs on the vector ALUs
   {
-    GemmArgs a = nn(w->w_router, d, w->pup_m, h, c->wrp, h, E, h, d);
+    // [W_r ; w_shared_gate] stacked into one [E1, d] matrix so that the fold is a single GEMM
+    launch_copy_rows(dt, w->w_router, d, c->wr_ext, d, E, d, s);
+    if (Is) launch_copy_rows(dt, w->ws_gate, d, at(c->wr_ext, (size_t)E * d, c->es), d, 1, d, s);
+    GemmArgs a = nn(c->wr_ext, d, w->pup_m, h, c->wrp, h, E + (Is ? 1 : 0), h, d);
     a.split_k = SPLIT_FOLD; a.splitk_ws = c->splitk_ws; a.col_scale = w->norm_m;
-    GemmTypes t{dt, dt, 0, dt};
-    if (launch_gemm_generic(a, t, s)) return REVFFN_EUNSUPPORTED;
-    if (Is) {
-      GemmArgs b2 = nn(w->ws_gate, d, w->pup_m, h, c->wrp + (size_t)E * h, h, 1, h, d);
-      b2.split_k = SPLIT_FOLD; b2.splitk_ws = c->splitk_ws; b2.col_scale = w->norm_m;
-      if (launch_gemm_generic(b2, t, s)) return REVFFN_EUNSUPPORTED;
-    }
+    TRY(run_gemm(c, a, dt, dt, 0, s));
     const int E1 = E + (Is ? 1 : 0);
     GemmArgs z = nt(y1, ld, c->wrp, h, c->zraw, E1, T, E1, h);
     z.split_k = SPLIT_LOGITS; z.splitk_ws = c->splitk_ws;

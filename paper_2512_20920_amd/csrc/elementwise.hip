@@ -76,7 +76,7 @@ void launch_rmsnorm_bwd(int dt, const void* dy, i64 ldd, const void* x, i64 ldx,
 // Stage 1: block (column tile of 64, row chunk c) -> partial[c][col]; stage 2 adds the
 // chunks in index order.
 // ---------------------------------------------------------------------------------
-#define COLSUM_CHUNK 256
+#define COLSUM_CHUNK 64
 size_t colsum_partial_floats(int rows, int cols) { return (size_t)cdiv(rows > 0 ? rows : 1, COLSUM_CHUNK) * cols; }
 
 template <class TA, class TB>
@@ -189,15 +189,58 @@ __global__ void __launch_bounds__(256) swiglu_bwd_k(const T* __restrict__ dhh, c
   dgu[r * 2 * I + j] = from_f<T>(dh * u * sg * (1.f + g * (1.f - sg)));
   dgu[r * 2 * I + I + j] = from_f<T>(dh * g * sg);
 }
+// bf16, I % 8 == 0: one thread handles 8 consecutive columns with 16-byte accesses
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+__global__ void __launch_bounds__(256) swiglu_fwd_v8_k(const bf16* __restrict__ gu, bf16* __restrict__ hh, i64 total8,
+                                                       int I8) {
+  i64 e = (i64)blockIdx.x * 256 + threadIdx.x;
+  if (e >= total8) return;
+  i64 r = e / I8;
+  int j = (int)(e % I8) * 8;
+  const int I = I8 * 8;
+  bf16x8_t g = *(const bf16x8_t*)(gu + r * 2 * I + j), u = *(const bf16x8_t*)(gu + r * 2 * I + I + j), o;
+#pragma unroll
+  for (int q = 0; q < 8; q++) { float gv = (float)g[q]; o[q] = (__bf16)(gv * sigmoid_f(gv) * (float)u[q]); }
+  *(bf16x8_t*)(hh + r * I + j) = o;
+}
+__global__ void __launch_bounds__(256) swiglu_bwd_v8_k(const bf16* __restrict__ dhh, const bf16* __restrict__ gu,
+                                                       bf16* __restrict__ dgu, i64 total8, int I8) {
+  i64 e = (i64)blockIdx.x * 256 + threadIdx.x;
+  if (e >= total8) return;
+  i64 r = e / I8;
+  int j = (int)(e % I8) * 8;
+  const int I = I8 * 8;
+  bf16x8_t g = *(const bf16x8_t*)(gu + r * 2 * I + j), u = *(const bf16x8_t*)(gu + r * 2 * I + I + j);
+  bf16x8_t dh = *(const bf16x8_t*)(dhh + r * I + j), og, ou;
+#pragma unroll
+  for (int q = 0; q < 8; q++) {
+    float gv = (float)g[q], d = (float)dh[q], sg = sigmoid_f(gv);
+    og[q] = (__bf16)(d * (float)u[q] * sg * (1.f + gv * (1.f - sg)));
+    ou[q] = (__bf16)(d * gv * sg);
+  }
+  *(bf16x8_t*)(dgu + r * 2 * I + j) = og;
+  *(bf16x8_t*)(dgu + r * 2 * I + I + j) = ou;
+}
+
 void launch_swiglu_fwd(int dt, const void* gu, void* hh, i64 rows, int I, hipStream_t s) {
   i64 total = rows * I;
   if (total <= 0) return;
+  if (dt == 1 && (I & 7) == 0 && (((uintptr_t)gu | (uintptr_t)hh) & 15) == 0) {
+    hipLaunchKernelGGL(swiglu_fwd_v8_k, dim3(cdiv(total / 8, 256)), dim3(256), 0, s, (const bf16*)gu, (bf16*)hh,
+                       total / 8, I / 8);
+    return;
+  }
   DISPATCH_DT(dt, hipLaunchKernelGGL(swiglu_fwd_k<T>, dim3(cdiv(total, 256)), dim3(256), 0, s, (const T*)gu,
                                      (T*)hh, total, I));
 }
 void launch_swiglu_bwd(int dt, const void* dhh, const void* gu, void* dgu, i64 rows, int I, hipStream_t s) {
   i64 total = rows * I;
   if (total <= 0) return;
+  if (dt == 1 && (I & 7) == 0 && (((uintptr_t)gu | (uintptr_t)dhh | (uintptr_t)dgu) & 15) == 0) {
+    hipLaunchKernelGGL(swiglu_bwd_v8_k, dim3(cdiv(total / 8, 256)), dim3(256), 0, s, (const bf16*)dhh,
+                       (const bf16*)gu, (bf16*)dgu, total / 8, I / 8);
+    return;
+  }
   DISPATCH_DT(dt, hipLaunchKernelGGL(swiglu_bwd_k<T>, dim3(cdiv(total, 256)), dim3(256), 0, s, (const T*)dhh,
                                      (const T*)gu, (T*)dgu, total, I));
 }

@@ -158,6 +158,14 @@ static void go(const GemmArgs& g, hipStream_t s) {
     hipLaunchKernelGGL((splitk_reduce_k<TC, TS>), dim3(cdiv((i64)g.M * g.N, 256)), dim3(256), 0, s, g);
 }
 
+void launch_splitk_reduce(const GemmArgs& g, GemmTypes t, hipStream_t s) {
+  dim3 grid(cdiv((i64)g.M * g.N, 256));
+  if (t.tc == 0 && t.tside == 0) hipLaunchKernelGGL((splitk_reduce_k<float, float>), grid, dim3(256), 0, s, g);
+  else if (t.tc == 0) hipLaunchKernelGGL((splitk_reduce_k<float, bf16>), grid, dim3(256), 0, s, g);
+  else if (t.tside == 0) hipLaunchKernelGGL((splitk_reduce_k<bf16, float>), grid, dim3(256), 0, s, g);
+  else hipLaunchKernelGGL((splitk_reduce_k<bf16, bf16>), grid, dim3(256), 0, s, g);
+}
+
 int launch_gemm_generic(const GemmArgs& g, GemmTypes t, hipStream_t s) {
   if (g.group_mode == 1 && g.tile_bm != GT) return -1;
   if (g.split_k > 1 && (g.group_mode != 0 || !g.splitk_ws)) return -1;

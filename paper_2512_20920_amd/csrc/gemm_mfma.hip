@@ -158,6 +158,10 @@ __global__ void __launch_bounds__(256) gemm_mfma_k(GemmArgs g) {
       k0 = g.offsets[grp];
       k_end = g.offsets[grp + 1];
       C += (i64)grp * g.c_group_stride;
+    } else if (g.split_k > 1) {                      // k slices of whole k-tiles; partial sums go to splitk_ws
+      int per = ((g.K + BK - 1) / BK + g.split_k - 1) / g.split_k * BK;
+      k0 = min(g.K, (int)blockIdx.z * per);
+      k_end = min(g.K, k0 + per);
     }
   }
   const int n0 = blockIdx.x * BN;
@@ -231,6 +235,22 @@ __global__ void __launch_bounds__(256) gemm_mfma_k(GemmArgs g) {
   }
 
   // ---- epilogue: lane holds column n = lane & 31 and rows (e>>2)*8 + (lane>>5)*4 + (e&3)
+  if (g.group_mode == 0 && g.split_k > 1) {
+    float* ws = g.splitk_ws + (i64)blockIdx.z * g.M * g.N;
+#pragma unroll
+    for (int j = 0; j < TN; j++) {
+      const int n = n0 + wn + j * 32 + (lane & 31);
+      if (n >= g.N) continue;
+#pragma unroll
+      for (int i = 0; i < TM; i++)
+#pragma unroll
+        for (int e = 0; e < 16; e++) {
+          const int m = m0 + wm + i * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+          if (m < m_end) ws[(i64)m * g.N + n] = acc[i][j][e];
+        }
+    }
+    return;
+  }
   const bf16* bias = (const bf16*)g.bias;
   const bf16* resid = (const bf16*)g.resid;
 #pragma unroll
@@ -259,7 +279,7 @@ template <int BM, int BN, int WGM, bool AT, bool BT, class TC>
 static void go(const GemmArgs& g, hipStream_t s) {
   dim3 grid;
   if (g.group_mode == 1) grid = dim3(cdiv(g.N, BN), g.max_tiles, 1);
-  else grid = dim3(cdiv(g.N, BN), cdiv(g.M, BM), g.group_mode == 2 ? g.n_groups : 1);
+  else grid = dim3(cdiv(g.N, BN), cdiv(g.M, BM), g.group_mode == 2 ? g.n_groups : (g.split_k > 1 ? g.split_k : 1));
   if (grid.x == 0 || grid.y == 0 || grid.z == 0) return;
   size_t smem = (size_t)2 * (Tile<AT, BM>::elems + Tile<BT, BN>::elems) * sizeof(bf16);
   static bool attr_set = false;
@@ -313,7 +333,8 @@ int launch_gemm_mfma(const GemmArgs& g, GemmTypes t, hipStream_t s) {
   if (g.a_gather && g.a_trans) return 1;
   if (g.b_gather) return 1;                              // gather along k is not taken: materialise the rows
   if (g.group_mode != 1 && g.M <= 0) return 1;
-  if (g.split_k > 1 || g.col_scale) return 1;
+  if (g.split_k > 1 && (g.group_mode != 0 || !g.splitk_ws)) return 1;
+  if (g.col_scale && g.split_k <= 1) return 1;           // column scale lives in the split-k reduction only
   // every operand must span less than 2 GiB from its base (32-bit buffer offsets)
   {
     const i64 lim = (i64)1 << 30;                        // elements
@@ -328,5 +349,6 @@ int launch_gemm_mfma(const GemmArgs& g, GemmTypes t, hipStream_t s) {
   } else {
     if (f32out) pick_tile<true, true, float>(g, s); else pick_tile<true, true, bf16>(g, s);
   }
+  if (g.group_mode == 0 && g.split_k > 1) launch_splitk_reduce(g, t, s);
   return 0;
 }

@@ -42,6 +42,8 @@ struct GemmArgs {
 struct GemmTypes { int ta, tb, tc, tside; };
 
 int launch_gemm_generic(const GemmArgs& g, GemmTypes t, hipStream_t s);
+// second stage of a split-k GEMM: adds the slices in splitk_ws in index order, applies the epilogue
+void launch_splitk_reduce(const GemmArgs& g, GemmTypes t, hipStream_t s);
 // bf16 x bf16 MFMA path; returns 1 if the problem does not meet its alignment rules
 // (nothing launched), 0 if launched.
 int launch_gemm_mfma(const GemmArgs& g, GemmTypes t, hipStream_t s);

@@ -138,14 +138,25 @@ __global__ void __launch_bounds__(PERM_WAVES * 64) permute_k(
   if (threadIdx.x == 0) {
     off[0] = 0;
     for (int e = 0; e < E; e++) off[e + 1] += off[e];
-    for (int e = 0; e <= E; e++) offsets[e] = off[e];
-    int na = 0, nb = 0;
-    for (int e = 0; e < E; e++) {
-      for (int m = off[e]; m < off[e + 1]; m += bm_a) if (na < max_tiles_a) { tile_group_a[na] = e; tile_m0_a[na] = m; na++; }
-      for (int m = off[e]; m < off[e + 1]; m += bm_b) if (nb < max_tiles_b) { tile_group_b[nb] = e; tile_m0_b[nb] = m; nb++; }
+  }
+  __syncthreads();
+  for (int e = threadIdx.x; e <= E; e += blockDim.x) offsets[e] = off[e];
+  // tile lists: expert e owns the slots after the tiles of experts 0..e-1 (tile counts are tiny, so
+  // every thread recounts its prefix); slots past the last tile are marked unused
+  for (int pass = 0; pass < 2; pass++) {
+    const int bm = pass ? bm_b : bm_a, mx = pass ? max_tiles_b : max_tiles_a;
+    int* tg = pass ? tile_group_b : tile_group_a;
+    int* tm = pass ? tile_m0_b : tile_m0_a;
+    int total = 0;
+    for (int e = 0; e < E; e++) total += (off[e + 1] - off[e] + bm - 1) / bm;
+    for (int e = threadIdx.x; e < E; e += blockDim.x) {
+      int first = 0;
+      for (int q = 0; q < e; q++) first += (off[q + 1] - off[q] + bm - 1) / bm;
+      int i = first;
+      for (int m = off[e]; m < off[e + 1]; m += bm, i++)
+        if (i < mx) { tg[i] = e; tm[i] = m; }
     }
-    for (; na < max_tiles_a; na++) { tile_group_a[na] = -1; tile_m0_a[na] = 0; }
-    for (; nb < max_tiles_b; nb++) { tile_group_b[nb] = -1; tile_m0_b[nb] = 0; }
+    for (int i = total + threadIdx.x; i < mx; i += blockDim.x) { tg[i] = -1; tm[i] = 0; }
   }
   __syncthreads();
   for (int base = lo; base < hi; base += 64) {
@@ -293,28 +304,48 @@ void launch_router_bwd(const float* probs, const int* idx, const float* wts, con
 //   dum[t] = dum_sh[t] (shared expert) + sum_slot dxg[pos(t,slot)] (routed experts)
 //          + sum_e dzext[t,e] * Wext[e]    (router rows, then the shared gate row)
 // ---------------------------------------------------------------------------------
+#define DUM_TOK 8
 template <class T>
 __global__ void __launch_bounds__(256) dum_finalize_k(const T* __restrict__ dxg, const int* __restrict__ inv_map,
                                                       const T* __restrict__ dum_sh, const float* __restrict__ dzext,
                                                       const T* __restrict__ w_router, const T* __restrict__ ws_gate,
-                                                      T* __restrict__ dum, int d, int k, int E, int E1) {
-  extern __shared__ float dzs[];
-  const int t = blockIdx.x;
-  for (int e = threadIdx.x; e < E1; e += 256) dzs[e] = dzext[(i64)t * E1 + e];
+                                                      T* __restrict__ dum, int Tn, int d, int k, int E, int E1) {
+  // one workgroup = DUM_TOK tokens; a router row is read once for all of them
+  extern __shared__ float dzs[];           // [DUM_TOK][E1]
+  const int t0 = blockIdx.x * DUM_TOK;
+  const int nt = min(DUM_TOK, Tn - t0);
+  for (int i = threadIdx.x; i < DUM_TOK * E1; i += 256) {
+    int tt = i / E1;
+    dzs[i] = (tt < nt) ? dzext[(i64)(t0 + tt) * E1 + (i % E1)] : 0.f;
+  }
   __syncthreads();
   for (int c = threadIdx.x; c < d; c += 256) {
-    float acc = dum_sh ? to_f(dum_sh[(i64)t * d + c]) : 0.f;
-    for (int s = 0; s < k; s++) acc += to_f(dxg[(i64)inv_map[(i64)t * k + s] * d + c]);
-    for (int e = 0; e < E; e++) acc += dzs[e] * to_f(w_router[(i64)e * d + c]);
-    if (E1 > E) acc += dzs[E] * to_f(ws_gate[c]);
-    dum[(i64)t * d + c] = from_f<T>(acc);
+    float acc[DUM_TOK];
+#pragma unroll
+    for (int tt = 0; tt < DUM_TOK; tt++) {
+      float a = 0.f;
+      if (tt < nt) {
+        const i64 t = t0 + tt;
+        a = dum_sh ? to_f(dum_sh[t * d + c]) : 0.f;
+        for (int s = 0; s < k; s++) a += to_f(dxg[(i64)inv_map[t * k + s] * d + c]);
+      }
+      acc[tt] = a;
+    }
+    for (int e = 0; e < E1; e++) {
+      float wv = (e < E) ? to_f(w_router[(i64)e * d + c]) : to_f(ws_gate[c]);
+#pragma unroll
+      for (int tt = 0; tt < DUM_TOK; tt++) acc[tt] += dzs[tt * E1 + e] * wv;
+    }
+#pragma unroll
+    for (int tt = 0; tt < DUM_TOK; tt++)
+      if (tt < nt) dum[(i64)(t0 + tt) * d + c] = from_f<T>(acc[tt]);
   }
 }
 void launch_dum_finalize(int dt, const void* dxg, const int* inv_map, const void* dum_sh, const float* dzext,
                          const void* w_router, const void* ws_gate, void* dum, int Tn, int d, int k, int E, int E1,
                          hipStream_t s) {
   if (Tn <= 0) return;
-  DISPATCH_DT(dt, hipLaunchKernelGGL(dum_finalize_k<T>, dim3(Tn), dim3(256), E1 * sizeof(float), s, (const T*)dxg,
-                                     inv_map, (const T*)dum_sh, dzext, (const T*)w_router, (const T*)ws_gate,
-                                     (T*)dum, d, k, E, E1));
+  DISPATCH_DT(dt, hipLaunchKernelGGL(dum_finalize_k<T>, dim3(cdiv(Tn, DUM_TOK)), dim3(256),
+                                     DUM_TOK * E1 * sizeof(float), s, (const T*)dxg, inv_map, (const T*)dum_sh, dzext,
+                                     (const T*)w_router, (const T*)ws_gate, (T*)dum, Tn, d, k, E, E1));
 }
