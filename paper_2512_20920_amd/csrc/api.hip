@@ -244,7 +244,7 @@ int run_gemm(revffn_ctx* c, GemmArgs g, int ta, int tb, int tc, hipStream_t s) {
   if (c->dt == 1 && c->mode == 0 && ta == 1 && tb == 1) {
     if (g.group_mode == 1) {
       // short experts (few rows each): the 64-row tile list wastes fewer padded rows
-      bool small = (i64)c->lastT_rows < (i64)96 * c->cfg.n_experts * 2;
+      bool small = false;   // the 128-row expert tile skips empty 32-row blocks itself
       if (small) { g.tile_group = c->tg_a; g.tile_m0 = c->tm_a; g.max_tiles = c->max_tiles_a; g.tile_bm = BM_A; }
       else { g.tile_group = c->tg_b; g.tile_m0 = c->tm_b; g.max_tiles = c->max_tiles_b; g.tile_bm = BM_B; }
     }

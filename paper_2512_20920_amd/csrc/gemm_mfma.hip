@@ -19,17 +19,16 @@ typedef __attribute__((ext_vector_type(8))) short s16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
-#define BK 64
 
 // LDS tile of one operand.  TR = 0: [ROWS][BK] with row stride BK+8 elements (144 B: the 16
 // rows read together by a 16-byte fragment read start on distinct 16-byte bank groups).
 // TR = 1: [BK][ROWS] with row stride ROWS+32 elements (the 4 k-rows x 64 B read together by a
 // transposing read fall on disjoint banks).
-template <bool TR, int ROWS>
+template <bool TR, int ROWS, int BK>
 struct Tile {
   static constexpr int stride = TR ? ROWS + 32 : BK + 8;
   static constexpr int elems = TR ? BK * stride : ROWS * stride;
-  static constexpr int chunks = ROWS / 32;        // 16-byte chunks per thread per k-step
+  static constexpr int chunks = ROWS * (BK / 8) / 256;   // 16-byte chunks per thread per k-step
 };
 
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
@@ -56,16 +55,16 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p) {
 }
 
 // ---- global -> registers ----------------------------------------------------------
-template <bool TR, int ROWS>
-__device__ __forceinline__ void load_tile(const OperandSrc& s, int k0, int k_end, uint4 (&regs)[Tile<TR, ROWS>::chunks],
-                                          const unsigned (&rowoff)[Tile<TR, ROWS>::chunks]) {
-  constexpr int NC = Tile<TR, ROWS>::chunks;
+template <bool TR, int ROWS, int BK>
+__device__ __forceinline__ void load_tile(const OperandSrc& s, int k0, int k_end, uint4 (&regs)[Tile<TR, ROWS, BK>::chunks],
+                                          const unsigned (&rowoff)[Tile<TR, ROWS, BK>::chunks]) {
+  constexpr int NC = Tile<TR, ROWS, BK>::chunks;
 #pragma unroll
   for (int i = 0; i < NC; i++) {
     int c = threadIdx.x + 256 * i;
     unsigned off;
     if (!TR) {
-      int k = k0 + (c & 7) * 8;
+      int k = k0 + (c % (BK / 8)) * 8;
       off = (k < k_end) ? rowoff[i] + (unsigned)k * 2u : OOB;
     } else {
       int k = k0 + c / (ROWS / 8);
@@ -79,28 +78,29 @@ __device__ __forceinline__ void load_tile(const OperandSrc& s, int k0, int k_end
 
 // per-thread row byte offsets of the non-transposed operand (fixed over the k loop); rows past
 // the limit are clamped to the last valid row (their products are never stored)
-template <int ROWS>
-__device__ __forceinline__ void row_offsets(const OperandSrc& s, unsigned (&rowoff)[ROWS / 32]) {
+template <int ROWS, int BK>
+__device__ __forceinline__ void row_offsets(const OperandSrc& s, unsigned (&rowoff)[ROWS * (BK / 8) / 256]) {
 #pragma unroll
-  for (int i = 0; i < ROWS / 32; i++) {
+  for (int i = 0; i < ROWS * (BK / 8) / 256; i++) {
     int c = threadIdx.x + 256 * i;
-    int r = s.row0 + (c >> 3);
-    if (r >= s.row_lim) r = s.row_lim - 1;
+    int r = s.row0 + c / (BK / 8);
+    const bool in = r < s.row_lim;
+    if (!in) r = s.row_lim - 1;
     unsigned rr = s.gather ? (unsigned)(s.gather[r] / s.div) : (unsigned)r;
-    rowoff[i] = rr * s.ld_bytes;
+    rowoff[i] = in ? rr * s.ld_bytes : OOB;            // rows past the limit read as zeros, without traffic
   }
 }
 
 // ---- registers -> LDS -------------------------------------------------------------
-template <bool TR, int ROWS>
-__device__ __forceinline__ void store_tile(bf16* lds, const uint4 (&regs)[Tile<TR, ROWS>::chunks]) {
-  constexpr int NC = Tile<TR, ROWS>::chunks;
-  constexpr int ST = Tile<TR, ROWS>::stride;
+template <bool TR, int ROWS, int BK>
+__device__ __forceinline__ void store_tile(bf16* lds, const uint4 (&regs)[Tile<TR, ROWS, BK>::chunks]) {
+  constexpr int NC = Tile<TR, ROWS, BK>::chunks;
+  constexpr int ST = Tile<TR, ROWS, BK>::stride;
 #pragma unroll
   for (int i = 0; i < NC; i++) {
     int c = threadIdx.x + 256 * i;
     int off;
-    if (!TR) off = (c >> 3) * ST + (c & 7) * 8;
+    if (!TR) off = (c / (BK / 8)) * ST + (c % (BK / 8)) * 8;
     else off = (c / (ROWS / 8)) * ST + (c % (ROWS / 8)) * 8;
     *(uint4*)(lds + off) = regs[i];
   }
@@ -108,9 +108,9 @@ __device__ __forceinline__ void store_tile(bf16* lds, const uint4 (&regs)[Tile<T
 
 // ---- LDS -> MFMA operand fragment: 32 rows x 16 k, lane (r = lane & 31, g = lane >> 5)
 // holds k = 8g..8g+7 of row r ---------------------------------------------------------
-template <bool TR, int ROWS>
+template <bool TR, int ROWS, int BK>
 __device__ __forceinline__ bf16x8 load_frag(const bf16* lds, int r0, int kk, int lane) {
-  constexpr int ST = Tile<TR, ROWS>::stride;
+  constexpr int ST = Tile<TR, ROWS, BK>::stride;
   if (!TR) {
     return *(const bf16x8*)(lds + (r0 + (lane & 31)) * ST + kk * 16 + (lane >> 5) * 8);
   } else {
@@ -128,10 +128,10 @@ __device__ __forceinline__ bf16x8 load_frag(const bf16* lds, int r0, int kk, int
 // PD = number of k-tiles kept in flight in registers ahead of the one being multiplied
 #define PD 3
 
-template <int BM, int BN, int WGM, bool AT, bool BT, class TC>
+template <int BM, int BN, int BK, int WGM, bool AT, bool BT, class TC, bool RB>
 __global__ void __launch_bounds__(256) gemm_mfma_k(GemmArgs g) {
-  typedef Tile<AT, BM> TA_;
-  typedef Tile<BT, BN> TB_;
+  typedef Tile<AT, BM, BK> TA_;
+  typedef Tile<BT, BN, BK> TB_;
   constexpr int WGN = 4 / WGM;                       // waves along n
   constexpr int WM = BM / WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32;
   static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile must be made of 32x32 blocks");
@@ -171,8 +171,11 @@ __global__ void __launch_bounds__(256) gemm_mfma_k(GemmArgs g) {
   OperandSrc sa{make_rsrc(A), (unsigned)g.lda * 2u, g.a_gather, g.gather_div, m0, m_end};
   OperandSrc sb{make_rsrc(Bm), (unsigned)g.ldb * 2u, nullptr, 1, n0, g.N};
   unsigned offA[TA_::chunks], offB[TB_::chunks];
-  if (!AT) row_offsets<BM>(sa, offA);
-  if (!BT) row_offsets<BN>(sb, offB);
+  if (!AT) row_offsets<BM, BK>(sa, offA);
+  if (!BT) row_offsets<BN, BK>(sb, offB);
+
+  // 32-row blocks of this wave's tile that hold at least one valid row (partial expert tiles)
+  const int tm_eff = RB ? min(TM, max(0, (m_end - m0 - wm + 31) / 32)) : TM;
 
   f32x16 acc[TM][TN];
 #pragma unroll
@@ -191,45 +194,49 @@ __global__ void __launch_bounds__(256) gemm_mfma_k(GemmArgs g) {
   const int nk = (k_end - k0 + BK - 1) / BK;
 #pragma unroll
   for (int p = 0; p < PD; p++) {
-    load_tile<AT, BM>(sa, k0 + p * BK, k_end, ra[p], offA);
-    load_tile<BT, BN>(sb, k0 + p * BK, k_end, rb[p], offB);
+    load_tile<AT, BM, BK>(sa, k0 + p * BK, k_end, ra[p], offA);
+    load_tile<BT, BN, BK>(sb, k0 + p * BK, k_end, rb[p], offB);
   }
-  store_tile<AT, BM>(sA, ra[0]);
-  store_tile<BT, BN>(sB, rb[0]);
+  store_tile<AT, BM, BK>(sA, ra[0]);
+  store_tile<BT, BN, BK>(sB, rb[0]);
   __syncthreads();
   for (int kt0 = 0; kt0 < nk; kt0 += PD) {
 #pragma unroll
     for (int u = 0; u < PD; u++) {
       const int kt = kt0 + u;
       const int cur = kt & 1;
-      load_tile<AT, BM>(sa, k0 + (kt + PD) * BK, k_end, ra[u], offA);
-      load_tile<BT, BN>(sb, k0 + (kt + PD) * BK, k_end, rb[u], offB);
+      load_tile<AT, BM, BK>(sa, k0 + (kt + PD) * BK, k_end, ra[u], offA);
+      load_tile<BT, BN, BK>(sb, k0 + (kt + PD) * BK, k_end, rb[u], offB);
       if (kt < nk) {                                  // uniform over the workgroup
         const bf16* cA = sA + cur * TA_::elems;
         const bf16* cB = sB + cur * TB_::elems;
         // fragments of k-step kk+1 are fetched from LDS while the MFMAs of k-step kk issue
         bf16x8 fa[2][TM], fb[2][TN];
 #pragma unroll
-        for (int i = 0; i < TM; i++) fa[0][i] = load_frag<AT, BM>(cA, wm + i * 32, 0, lane);
+        for (int i = 0; i < TM; i++)
+          if (!RB || i < tm_eff) fa[0][i] = load_frag<AT, BM, BK>(cA, wm + i * 32, 0, lane);
 #pragma unroll
-        for (int j = 0; j < TN; j++) fb[0][j] = load_frag<BT, BN>(cB, wn + j * 32, 0, lane);
+        for (int j = 0; j < TN; j++) fb[0][j] = load_frag<BT, BN, BK>(cB, wn + j * 32, 0, lane);
 #pragma unroll
         for (int kk = 0; kk < BK / 16; kk++) {
           if (kk + 1 < BK / 16) {
 #pragma unroll
-            for (int i = 0; i < TM; i++) fa[(kk + 1) & 1][i] = load_frag<AT, BM>(cA, wm + i * 32, kk + 1, lane);
+            for (int i = 0; i < TM; i++)
+              if (!RB || i < tm_eff) fa[(kk + 1) & 1][i] = load_frag<AT, BM, BK>(cA, wm + i * 32, kk + 1, lane);
 #pragma unroll
-            for (int j = 0; j < TN; j++) fb[(kk + 1) & 1][j] = load_frag<BT, BN>(cB, wn + j * 32, kk + 1, lane);
+            for (int j = 0; j < TN; j++) fb[(kk + 1) & 1][j] = load_frag<BT, BN, BK>(cB, wn + j * 32, kk + 1, lane);
           }
 #pragma unroll
           for (int i = 0; i < TM; i++)
+            if (!RB || i < tm_eff) {
 #pragma unroll
-            for (int j = 0; j < TN; j++)
-              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kk & 1][i], fb[kk & 1][j], acc[i][j], 0, 0, 0);
+              for (int j = 0; j < TN; j++)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kk & 1][i], fb[kk & 1][j], acc[i][j], 0, 0, 0);
+            }
         }
       }
-      store_tile<AT, BM>(sA + (cur ^ 1) * TA_::elems, ra[(u + 1) % PD]);   // tile kt+1
-      store_tile<BT, BN>(sB + (cur ^ 1) * TB_::elems, rb[(u + 1) % PD]);
+      store_tile<AT, BM, BK>(sA + (cur ^ 1) * TA_::elems, ra[(u + 1) % PD]);   // tile kt+1
+      store_tile<BT, BN, BK>(sB + (cur ^ 1) * TB_::elems, rb[(u + 1) % PD]);
       __syncthreads();
     }
   }
@@ -275,20 +282,20 @@ __global__ void __launch_bounds__(256) gemm_mfma_k(GemmArgs g) {
   }
 }
 
-template <int BM, int BN, int WGM, bool AT, bool BT, class TC>
+template <int BM, int BN, int BK, int WGM, bool AT, bool BT, class TC, bool RB = false>
 static void go(const GemmArgs& g, hipStream_t s) {
   dim3 grid;
   if (g.group_mode == 1) grid = dim3(cdiv(g.N, BN), g.max_tiles, 1);
   else grid = dim3(cdiv(g.N, BN), cdiv(g.M, BM), g.group_mode == 2 ? g.n_groups : (g.split_k > 1 ? g.split_k : 1));
   if (grid.x == 0 || grid.y == 0 || grid.z == 0) return;
-  size_t smem = (size_t)2 * (Tile<AT, BM>::elems + Tile<BT, BN>::elems) * sizeof(bf16);
+  size_t smem = (size_t)2 * (Tile<AT, BM, BK>::elems + Tile<BT, BN, BK>::elems) * sizeof(bf16);
   static bool attr_set = false;
   if (!attr_set) {
-    (void)hipFuncSetAttribute((const void*)gemm_mfma_k<BM, BN, WGM, AT, BT, TC>,
+    (void)hipFuncSetAttribute((const void*)gemm_mfma_k<BM, BN, BK, WGM, AT, BT, TC, RB>,
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     attr_set = true;
   }
-  hipLaunchKernelGGL((gemm_mfma_k<BM, BN, WGM, AT, BT, TC>), grid, dim3(256), smem, s, g);
+  hipLaunchKernelGGL((gemm_mfma_k<BM, BN, BK, WGM, AT, BT, TC, RB>), grid, dim3(256), smem, s, g);
 }
 
 // REVFFN_GEMM_TILE (tuning aid): 1 = 128x128, 2 = 128x64, 3 = 64x128 for every non-grouped problem
@@ -302,19 +309,34 @@ template <bool AT, bool BT, class TC>
 static void pick_tile(const GemmArgs& g, hipStream_t s) {
   if (g.group_mode != 1 && tile_override()) {
     switch (tile_override()) {
-      case 1: go<128, 128, 2, AT, BT, TC>(g, s); return;
-      case 2: go<128, 64, 2, AT, BT, TC>(g, s); return;
-      case 3: go<64, 128, 1, AT, BT, TC>(g, s); return;
+      case 1: go<128, 128, 64, 2, AT, BT, TC>(g, s); return;
+      case 2: go<128, 64, 64, 2, AT, BT, TC>(g, s); return;
+      case 3: go<64, 128, 64, 1, AT, BT, TC>(g, s); return;
+      case 4: go<128, 128, 32, 2, AT, BT, TC>(g, s); return;
     }
   }
   if (g.group_mode == 1) {
-    if (g.tile_bm == 64) go<64, 128, 1, AT, BT, TC>(g, s); else go<128, 128, 2, AT, BT, TC>(g, s);
+    // expert tiles.  Variant 1 (waves split the weight columns and skip the 32-row blocks a short expert
+    // does not fill) measured slightly slower than the plain 2x2 wave layout at ~137 rows per expert
+    static int v = -1;                 // REVFFN_GROUPED_VARIANT (tuning aid): 0 = 2x2 waves, 1 = 1x4 waves + skipping
+    if (v < 0) { const char* e = getenv("REVFFN_GROUPED_VARIANT"); v = e ? atoi(e) : 0; }
+    if (g.tile_bm == 64) go<64, 128, 64, 1, AT, BT, TC>(g, s);
+    else if (v == 0) go<128, 128, 64, 2, AT, BT, TC>(g, s);
+    else go<128, 128, 64, 1, AT, BT, TC, true>(g, s);
+    return;
+  }
+  if (g.group_mode == 2) {
+    // per-expert weight gradients: the k range is one expert's rows; short ranges take the k-step 32 kernel
+    // (less padding, smaller LDS footprint, more workgroups per CU to hide the load latency)
+    static int v = -1;                 // REVFFN_WGRAD_BK32 (tuning aid)
+    if (v < 0) { const char* e = getenv("REVFFN_WGRAD_BK32"); v = e ? atoi(e) : 1; }
+    if (v && g.K < (i64)192 * g.n_groups) go<128, 128, 32, 2, AT, BT, TC>(g, s); else go<128, 128, 64, 2, AT, BT, TC>(g, s);
     return;
   }
   // small problems: narrower tiles so that every CU gets at least two workgroups
-  i64 tiles = (i64)cdiv(g.M, 128) * cdiv(g.N, 128) * (g.group_mode == 2 ? g.n_groups : 1);
-  if (tiles < 512 && g.N >= 128) go<128, 64, 2, AT, BT, TC>(g, s);
-  else go<128, 128, 2, AT, BT, TC>(g, s);
+  i64 tiles = (i64)cdiv(g.M, 128) * cdiv(g.N, 128);
+  if (tiles < 512 && g.N >= 128) go<128, 64, 64, 2, AT, BT, TC>(g, s);
+  else go<128, 128, 64, 2, AT, BT, TC>(g, s);
 }
 
 static bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
