@@ -67,7 +67,8 @@ struct revffn_ctx {
   float *dw, *dzext, *rinv, *rinv3, *partial;
   float *zraw, *splitk_ws;
   void* dwr_tmp;
-  void* wr_ext;
+  void* wr_ext;               // [E1p, d]: router rows, shared-gate row, zero rows up to a multiple of 8
+  void *dzb, *dUm_r;          // bf16 logit gradients [T, E1p] and the router term of dUm [T, d]
   void *dAO, *dO, *dQ, *dK, *dV, *dU12, *dn12;
   float* dvec;
   float* rope_cs;
@@ -156,7 +157,10 @@ size_t carve(revffn_ctx* c, char* base) {
   c->dzext = (float*)cv.take(T * E1 * 4);
   c->zraw = (float*)cv.take(T * E1 * 4);
   c->dwr_tmp = cv.take(E1 * d * es);
-  c->wr_ext = cv.take(E1 * d * es);
+  const size_t E1p = (E1 + 7) / 8 * 8;
+  c->wr_ext = cv.take(E1p * d * es);
+  c->dzb = cv.take(T * E1p * 2);
+  c->dUm_r = cv.take(T * d * es);
   {
     size_t a = SPLIT_FOLD * E1 * h, b2 = SPLIT_LOGITS * T * E1, c3 = SPLIT_DWR * E1 * d;
     size_t mx = a > b2 ? a : b2;
@@ -528,8 +532,17 @@ int backward_impl(revffn_ctx* c, const revffn_weights* w, const void* x1, const 
     launch_colsum(0, c->dzext, E1, 0, nullptr, 0, nullptr, 0, g->b_router, c->partial, T, E, sw);
   }
   if (Is) after(c, s0, s);
-  launch_dum_finalize(dt, c->dXg, c->inv_map, Is ? c->dUm_sh : nullptr, c->dzext, w->w_router, w->ws_gate, c->dUm, T,
-                      d, k, E, E1, s);
+  const void* dum_r = nullptr;
+  if (dt == 1 && c->mode == 0) {
+    // router term of dUm on the matrix cores: dUm_r = dz . [W_r ; w_gate ; 0], contraction over E1p
+    const int E1p = (E1 + 7) / 8 * 8;
+    launch_dz_to_bf16(c->dzext, c->dzb, T, E1, E1p, s);
+    GemmArgs a = nn(c->dzb, E1p, c->wr_ext, d, c->dUm_r, d, T, d, E1p);
+    GemmTypes tt{1, 1, 1, 1};
+    if (launch_gemm_mfma(a, tt, s) == 0) dum_r = c->dUm_r;
+  }
+  launch_dum_finalize(dt, c->dXg, c->inv_map, Is ? c->dUm_sh : nullptr, dum_r, c->dzext, w->w_router, w->ws_gate,
+                      c->dUm, T, d, k, E, E1, s);
   if (GF(pup_m)) { after(c, s, sw); TRY(run_gemm(c, tn(c->dUm, d, c->n3, h, GF(pup_m), h, d, h, T), sw)); }
   TRY(run_gemm(c, nn(c->dUm, d, w->pup_m, h, c->dn3, h, T, h, d), s));
   // g1 = dY1 + Norm'(dn3): total gradient at Y1
@@ -633,6 +646,7 @@ int revffn_create(revffn_ctx** out, const revffn_config* cfg, int32_t max_B, int
     return REVFFN_EWORKSPACE;
   }
   carve(c, (char*)c->slab);
+  (void)hipMemset(c->wr_ext, 0, (size_t)((c->cfg.n_experts + (c->cfg.d_shared ? 1 : 0) + 7) / 8 * 8) * c->cfg.d_model * c->es);
   c->use_streams = getenv("REVFFN_NO_STREAMS") == nullptr;
   c->sync_ev = new (std::nothrow) std::vector<hipEvent_t>();
   bool ok = c->sync_ev != nullptr;

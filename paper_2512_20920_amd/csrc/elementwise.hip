@@ -76,18 +76,19 @@ void launch_rmsnorm_bwd(int dt, const void* dy, i64 ldd, const void* x, i64 ldx,
 // Stage 1: block (column tile of 64, row chunk c) -> partial[c][col]; stage 2 adds the
 // chunks in index order.
 // ---------------------------------------------------------------------------------
-#define COLSUM_CHUNK 64
-size_t colsum_partial_floats(int rows, int cols) { return (size_t)cdiv(rows > 0 ? rows : 1, COLSUM_CHUNK) * cols; }
+#define COLSUM_CHUNKS 16
+static int colsum_chunk_rows(int rows) { int c = cdiv(rows > 0 ? rows : 1, COLSUM_CHUNKS); return c < 32 ? 32 : c; }
+size_t colsum_partial_floats(int rows, int cols) { return (size_t)(COLSUM_CHUNKS + 1) * cols; }
 
 template <class TA, class TB>
 __global__ void __launch_bounds__(256) colsum1_k(const TA* __restrict__ a, i64 lda, const TB* __restrict__ b,
                                                  i64 ldb, const float* __restrict__ sc,
-                                                 float* __restrict__ partial, int rows, int cols) {
+                                                 float* __restrict__ partial, int rows, int cols, int chunk) {
   __shared__ float red[4][64];
   int c = blockIdx.x * 64 + (threadIdx.x & 63);
   int q = threadIdx.x >> 6;
-  int r0 = blockIdx.y * COLSUM_CHUNK;
-  int r1 = min(rows, r0 + COLSUM_CHUNK);
+  int r0 = blockIdx.y * chunk;
+  int r1 = min(rows, r0 + chunk);
   float acc = 0.f;
   if (c < cols) {
     for (int t = r0 + q; t < r1; t += 4) {
@@ -116,9 +117,10 @@ __global__ void colsum2_k(const float* __restrict__ partial, TO* __restrict__ ou
 template <class TA, class TB>
 static void colsum_go(const void* a, i64 lda, const void* b, i64 ldb, const float* sc, int tout, void* out,
                       float* partial, int rows, int cols, hipStream_t s) {
-  int chunks = cdiv(rows > 0 ? rows : 1, COLSUM_CHUNK);
+  int chunk = colsum_chunk_rows(rows);
+  int chunks = cdiv(rows > 0 ? rows : 1, chunk);
   hipLaunchKernelGGL((colsum1_k<TA, TB>), dim3(cdiv(cols, 64), chunks), dim3(256), 0, s, (const TA*)a, lda,
-                     (const TB*)b, ldb, sc, partial, rows, cols);
+                     (const TB*)b, ldb, sc, partial, rows, cols, chunk);
   if (tout == 0)
     hipLaunchKernelGGL(colsum2_k<float>, dim3(cdiv(cols, 256)), dim3(256), 0, s, partial, (float*)out, chunks, cols);
   else

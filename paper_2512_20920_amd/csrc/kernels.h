@@ -88,9 +88,10 @@ void launch_moe_bwd_rows(int dt, const void* drs, const void* yp, const void* ys
                          int T, int d, int k, int E1, int has_gate, hipStream_t s);
 void launch_router_bwd(const float* probs, const int* idx, const float* wts, const float* dw, float* dzext,
                        int T, int E, int k, int E1, int norm_topk, hipStream_t s);
-void launch_dum_finalize(int dt, const void* dxg, const int* inv_map, const void* dum_sh, const float* dzext,
-                         const void* w_router, const void* ws_gate, void* dum, int T, int d, int k, int E,
-                         int E1, hipStream_t s);
+void launch_dum_finalize(int dt, const void* dxg, const int* inv_map, const void* dum_sh, const void* dum_r,
+                         const float* dzext, const void* w_router, const void* ws_gate, void* dum, int T, int d,
+                         int k, int E, int E1, hipStream_t s);
+void launch_dz_to_bf16(const float* dzext, void* dzb, int T, int E1, int E1p, hipStream_t s);
 
 // ---- attention -------------------------------------------------------------------
 // Q,K,V,O,dO,...: [T, H*dh] token-major, head hh occupies columns hh*dh..; lse/dvec: [B,H,S] float

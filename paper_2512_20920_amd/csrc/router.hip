@@ -304,48 +304,52 @@ void launch_router_bwd(const float* probs, const int* idx, const float* wts, con
 //   dum[t] = dum_sh[t] (shared expert) + sum_slot dxg[pos(t,slot)] (routed experts)
 //          + sum_e dzext[t,e] * Wext[e]    (router rows, then the shared gate row)
 // ---------------------------------------------------------------------------------
-#define DUM_TOK 8
+// dum[t] = dum_sh[t] + sum_slot dxg[pos(t,slot)] + router term, where the router term is either the
+// precomputed dum_r[t] (bf16 path: a k = E1 GEMM on the matrix cores) or, when dum_r is null, is
+// accumulated here from dzext and the router / shared-gate rows.
 template <class T>
 __global__ void __launch_bounds__(256) dum_finalize_k(const T* __restrict__ dxg, const int* __restrict__ inv_map,
-                                                      const T* __restrict__ dum_sh, const float* __restrict__ dzext,
+                                                      const T* __restrict__ dum_sh, const T* __restrict__ dum_r,
+                                                      const float* __restrict__ dzext,
                                                       const T* __restrict__ w_router, const T* __restrict__ ws_gate,
-                                                      T* __restrict__ dum, int Tn, int d, int k, int E, int E1) {
-  // one workgroup = DUM_TOK tokens; a router row is read once for all of them
-  extern __shared__ float dzs[];           // [DUM_TOK][E1]
-  const int t0 = blockIdx.x * DUM_TOK;
-  const int nt = min(DUM_TOK, Tn - t0);
-  for (int i = threadIdx.x; i < DUM_TOK * E1; i += 256) {
-    int tt = i / E1;
-    dzs[i] = (tt < nt) ? dzext[(i64)(t0 + tt) * E1 + (i % E1)] : 0.f;
+                                                      T* __restrict__ dum, int d, int k, int E, int E1) {
+  extern __shared__ float dzs[];
+  const int t = blockIdx.x;
+  if (!dum_r) {
+    for (int e = threadIdx.x; e < E1; e += 256) dzs[e] = dzext[(i64)t * E1 + e];
+    __syncthreads();
   }
-  __syncthreads();
   for (int c = threadIdx.x; c < d; c += 256) {
-    float acc[DUM_TOK];
-#pragma unroll
-    for (int tt = 0; tt < DUM_TOK; tt++) {
-      float a = 0.f;
-      if (tt < nt) {
-        const i64 t = t0 + tt;
-        a = dum_sh ? to_f(dum_sh[t * d + c]) : 0.f;
-        for (int s = 0; s < k; s++) a += to_f(dxg[(i64)inv_map[t * k + s] * d + c]);
-      }
-      acc[tt] = a;
+    float acc = dum_sh ? to_f(dum_sh[(i64)t * d + c]) : 0.f;
+    for (int s = 0; s < k; s++) acc += to_f(dxg[(i64)inv_map[(i64)t * k + s] * d + c]);
+    if (dum_r) {
+      acc += to_f(dum_r[(i64)t * d + c]);
+    } else {
+      for (int e = 0; e < E; e++) acc += dzs[e] * to_f(w_router[(i64)e * d + c]);
+      if (E1 > E) acc += dzs[E] * to_f(ws_gate[c]);
     }
-    for (int e = 0; e < E1; e++) {
-      float wv = (e < E) ? to_f(w_router[(i64)e * d + c]) : to_f(ws_gate[c]);
-#pragma unroll
-      for (int tt = 0; tt < DUM_TOK; tt++) acc[tt] += dzs[tt * E1 + e] * wv;
-    }
-#pragma unroll
-    for (int tt = 0; tt < DUM_TOK; tt++)
-      if (tt < nt) dum[(i64)(t0 + tt) * d + c] = from_f<T>(acc[tt]);
+    dum[(i64)t * d + c] = from_f<T>(acc);
   }
 }
-void launch_dum_finalize(int dt, const void* dxg, const int* inv_map, const void* dum_sh, const float* dzext,
-                         const void* w_router, const void* ws_gate, void* dum, int Tn, int d, int k, int E, int E1,
-                         hipStream_t s) {
+void launch_dum_finalize(int dt, const void* dxg, const int* inv_map, const void* dum_sh, const void* dum_r,
+                         const float* dzext, const void* w_router, const void* ws_gate, void* dum, int Tn, int d,
+                         int k, int E, int E1, hipStream_t s) {
   if (Tn <= 0) return;
-  DISPATCH_DT(dt, hipLaunchKernelGGL(dum_finalize_k<T>, dim3(cdiv(Tn, DUM_TOK)), dim3(256),
-                                     DUM_TOK * E1 * sizeof(float), s, (const T*)dxg, inv_map, (const T*)dum_sh, dzext,
-                                     (const T*)w_router, (const T*)ws_gate, (T*)dum, Tn, d, k, E, E1));
+  DISPATCH_DT(dt, hipLaunchKernelGGL(dum_finalize_k<T>, dim3(Tn), dim3(256), E1 * sizeof(float), s, (const T*)dxg,
+                                     inv_map, (const T*)dum_sh, (const T*)dum_r, dzext, (const T*)w_router,
+                                     (const T*)ws_gate, (T*)dum, d, k, E, E1));
+}
+
+// bf16 copy of the logit gradients, zero-padded to E1p columns: the A operand of the router term GEMM
+__global__ void __launch_bounds__(256) dz_to_bf16_k(const float* __restrict__ dzext, bf16* __restrict__ dzb, int Tn,
+                                                    int E1, int E1p) {
+  i64 i = (i64)blockIdx.x * 256 + threadIdx.x;
+  if (i >= (i64)Tn * E1p) return;
+  int e = (int)(i % E1p);
+  i64 t = i / E1p;
+  dzb[i] = (e < E1) ? (bf16)dzext[t * E1 + e] : (bf16)0.f;
+}
+void launch_dz_to_bf16(const float* dzext, void* dzb, int Tn, int E1, int E1p, hipStream_t s) {
+  if (Tn <= 0) return;
+  hipLaunchKernelGGL(dz_to_bf16_k, dim3(cdiv((i64)Tn * E1p, 256)), dim3(256), 0, s, dzext, (bf16*)dzb, Tn, E1, E1p);
 }
