@@ -41,6 +41,70 @@ def cpu_baseline(wl, W32, x1, x2, dy1, dy2, n_inv_iters):
                       f"full-size weights, numpy float64, {dt:.1f} s"}
 
 
+def bench_stack(args, wl):
+    """Stack of wl.n_blocks blocks: forward keeping only the last state, then the backward sweep that
+    rebuilds every block's input from its output (no cached activations).  Reports tokens/s, peak HBM
+    bytes and the reconstruction drift at the stack input."""
+    import numpy as np
+    import torch
+    import synth
+    import paper_2512_20920_amd as R
+    from paper_2512_20920_amd import harness as Hn
+
+    t_setup = time.perf_counter()
+    L = wl.n_blocks
+    Wds, Gs = [], []
+    for l in range(L):
+        Wd = Hn.upload_weights(synth.make_weights(wl, block=l, f64=False), wl.dtype)
+        Wds.append(Wd)
+        Gs.append(Hn.alloc_grads(Wd))
+    x1, x2, dy1, dy2 = synth.make_inputs(wl)
+    up = lambda a: Hn.upload(a, wl.dtype)
+    x1d, x2d, dy1d, dy2d = up(x1), up(x2), up(dy1), up(dy2)
+    new = lambda: torch.empty((wl.T, wl.h), dtype=Hn.torch_dtype(wl.dtype), device="cuda")
+    y1d, y2d, s1, s2, g1, g2 = new(), new(), new(), new(), new(), new()
+    ctx = R.Context(Hn.make_config(wl, n_inv_iters=args.inv_iters), wl.B, wl.S)
+    ws = (R.Weights * L)(*[R.binding._struct(R.Weights, w) for w in Wds])
+    gs = (R.Grads * L)(*[R.binding._struct(R.Grads, g) for g in Gs])
+    stream = torch.cuda.current_stream()
+    t_setup = time.perf_counter() - t_setup
+
+    def step():
+        R.binding._check(ctx.lib.revffn_stack_forward(ctx.handle, ws, L, x1d.data_ptr(), x2d.data_ptr(), y1d.data_ptr(),
+                                                      y2d.data_ptr(), wl.B, wl.S, wl.h, stream.cuda_stream))
+        s1.copy_(y1d); s2.copy_(y2d); g1.copy_(dy1d); g2.copy_(dy2d)      # the sweep works in place
+        R.binding._check(ctx.lib.revffn_stack_backward(ctx.handle, ws, gs, L, s1.data_ptr(), s2.data_ptr(), g1.data_ptr(),
+                                                       g2.data_ptr(), wl.B, wl.S, wl.h, stream.cuda_stream))
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for _ in range(args.steps):
+        step()
+    e1.record(stream)
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / args.steps
+    drift1 = float((s1.float() - x1d.float()).abs().max())
+    drift2 = float((s2.float() - x2d.float()).abs().max())
+    weights_bytes = sum(t.numel() * t.element_size() for w in Wds for t in w.values() if t is not None)
+    out = {
+        "metric": "RevFFN 24-block stack forward + reconstructing backward sweep, tokens/s",
+        "value": wl.T / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"{wl.name}: {L} RevFFN blocks at the Qwen1.5-MoE-A2.7B layer shape, B={wl.B} S={wl.S}",
+                   "n_inv_iters": args.inv_iters, "setup_s": round(t_setup, 1)},
+        "peak_hbm_bytes": int(torch.cuda.max_memory_allocated()) + int(ctx.workspace_bytes(wl.B, wl.S)),
+        "weights_bytes": int(weights_bytes), "gradient_bytes": int(weights_bytes),
+        "activation_workspace_bytes": int(ctx.workspace_bytes(wl.B, wl.S)),
+        "reconstruction_drift_at_stack_input": {"max_abs_x1": drift1, "max_abs_x2": drift2,
+                                                "note": "max |rebuilt - true| after walking all blocks down"},
+    }
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -66,6 +130,8 @@ def main():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(1)
     wl = synth.WORKLOADS[args.workload]
+    if wl.n_blocks > 1:
+        return bench_stack(args, wl)
     t_setup = time.perf_counter()
     W32 = synth.make_weights(wl, f64=False)
     x1, x2, dy1, dy2 = synth.make_inputs(wl)

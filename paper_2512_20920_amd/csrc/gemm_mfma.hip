@@ -260,6 +260,24 @@ __global__ void __launch_bounds__(256) gemm_mfma_k(GemmArgs g) {
   }
   const bf16* bias = (const bf16*)g.bias;
   const bf16* resid = (const bf16*)g.resid;
+  if (!g.row_scale && !bias && !g.tap && !resid) {
+    // plain store (all weight gradients, most projections): no per-element epilogue work
+    const bool full = (m0 + BM <= m_end) && (n0 + BN <= g.N);
+#pragma unroll
+    for (int j = 0; j < TN; j++) {
+      const int n = n0 + wn + j * 32 + (lane & 31);
+#pragma unroll
+      for (int i = 0; i < TM; i++) {
+        TC* cp = C + (i64)(m0 + wm + i * 32 + (lane >> 5) * 4) * g.ldc + n;
+#pragma unroll
+        for (int e = 0; e < 16; e++) {
+          const int dm = (e >> 2) * 8 + (e & 3);
+          if (full || (n < g.N && m0 + wm + i * 32 + (lane >> 5) * 4 + dm < m_end)) cp[(i64)dm * g.ldc] = (TC)acc[i][j][e];
+        }
+      }
+    }
+    return;
+  }
 #pragma unroll
   for (int j = 0; j < TN; j++) {
     const int n = n0 + wn + j * 32 + (lane & 31);
