@@ -71,14 +71,14 @@ __device__ __forceinline__ void store_rows64(bf16* lds, int stride, const uint4 
 // Forward.  Workgroup = 128 queries of one (batch, head); wave = 32 queries; keys/values
 // streamed in tiles of 64.
 // ------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(256) flash_fwd_k(const bf16* __restrict__ q, const bf16* __restrict__ k,
+__global__ void __launch_bounds__(256, 2) flash_fwd_k(const bf16* __restrict__ q, const bf16* __restrict__ k,
                                                    const bf16* __restrict__ v, bf16* __restrict__ o,
                                                    float* __restrict__ lse, int S, int H, int causal, float scale) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   bf16* sK = (bf16*)smem_raw;               // 2 stages [64][KST]
   bf16* sV = sK + 2 * BKV * KST;            // 2 stages [64][VST]
-  const int qt = gridDim.x - 1 - blockIdx.x;        // long (late) query tiles first
-  const int hh = blockIdx.y, b = blockIdx.z;
+  const int qt = gridDim.y - 1 - blockIdx.y;        // long (late) query tiles first, for every head
+  const int hh = blockIdx.x, b = blockIdx.z;
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6, g = lane >> 5;
   const i64 ld = (i64)H * DH;
   const bf16* qb = q + (i64)b * S * ld + hh * DH;
@@ -130,22 +130,34 @@ __global__ void __launch_bounds__(256) flash_fwd_k(const bf16* __restrict__ q, c
 #pragma unroll
         for (int j = 0; j < 2; j++)
           sacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(cK, KST, j * 32, kk, lane), qf[kk], sacc[j], 0, 0, 0);
-      // scores in the log2 domain; mask keys past the sequence end or after the query
+      // scores in the log2 domain; keys past the sequence end or after the query are masked, which
+      // only tiles on the diagonal or at the end of the sequence need
+      const bool need_mask = (kv0 + BKV > S) || (causal && kv0 + BKV - 1 > qw);
       float mx = -INFINITY;
+      if (need_mask) {
 #pragma unroll
-      for (int j = 0; j < 2; j++)
+        for (int j = 0; j < 2; j++)
 #pragma unroll
-        for (int e = 0; e < 16; e++) {
-          int kv = kv0 + j * 32 + (e >> 2) * 8 + g * 4 + (e & 3);
-          float sv = sacc[j][e] * sl2;
-          if (kv >= S || (causal && kv > myq)) sv = -INFINITY;
-          sacc[j][e] = sv;
-          mx = fmaxf(mx, sv);
-        }
+          for (int e = 0; e < 16; e++) {
+            int kv = kv0 + j * 32 + (e >> 2) * 8 + g * 4 + (e & 3);
+            float sv = sacc[j][e] * sl2;
+            if (kv >= S || (causal && kv > myq)) sv = -INFINITY;
+            sacc[j][e] = sv;
+            mx = fmaxf(mx, sv);
+          }
+      } else {
+#pragma unroll
+        for (int j = 0; j < 2; j++)
+#pragma unroll
+          for (int e = 0; e < 16; e++) {
+            float sv = sacc[j][e] * sl2;
+            sacc[j][e] = sv;
+            mx = fmaxf(mx, sv);
+          }
+      }
       mx = fmaxf(mx, __shfl_xor(mx, 32, WAVE));
       const float mn = fmaxf(m, mx);
       const float msafe = (mn == -INFINITY) ? 0.f : mn;
-      const float alpha = fast_exp2(m - msafe);
       float rs = 0.f;
 #pragma unroll
       for (int j = 0; j < 2; j++)
@@ -156,12 +168,19 @@ __global__ void __launch_bounds__(256) flash_fwd_k(const bf16* __restrict__ q, c
           rs += p;
         }
       rs += __shfl_xor(rs, 32, WAVE);
-      l = l * alpha + rs;
+      // the running maximum settles after the first tiles: rescale the accumulator only when some
+      // query of this wave actually raised it
+      if (__any(mn > m)) {
+        const float alpha = fast_exp2(m - msafe);
+        l = l * alpha + rs;
+#pragma unroll
+        for (int i = 0; i < 4; i++)
+#pragma unroll
+          for (int e = 0; e < 16; e++) oacc[i][e] *= alpha;
+      } else {
+        l += rs;
+      }
       m = mn;
-#pragma unroll
-      for (int i = 0; i < 4; i++)
-#pragma unroll
-        for (int e = 0; e < 16; e++) oacc[i][e] *= alpha;
       // O^T[dh, q] += V^T[dh, kv] P^T[kv, q]
 #pragma unroll
       for (int j = 0; j < 2; j++)
@@ -206,7 +225,7 @@ int launch_attn_fwd_flash(const void* q, const void* k, const void* v, void* o, 
     (void)hipFuncSetAttribute((const void*)flash_fwd_k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     attr_set = true;
   }
-  hipLaunchKernelGGL(flash_fwd_k, dim3(cdiv(S, 128), H, B), dim3(256), smem, s, (const bf16*)q, (const bf16*)k,
+  hipLaunchKernelGGL(flash_fwd_k, dim3(H, cdiv(S, 128), B), dim3(256), smem, s, (const bf16*)q, (const bf16*)k,
                      (const bf16*)v, (bf16*)o, lse, S, H, causal, 1.0f / sqrtf((float)dh));
   return 0;
 }
@@ -217,15 +236,15 @@ int launch_attn_fwd_flash(const void* q, const void* k, const void* v, void* o, 
 //   S^T = K Q^T,  P^T = exp(S^T*scale - lse),  dP^T = V dO^T,  dS^T = P^T (dP^T - D) scale,
 //   dQ^T += K^T dS^T.
 // ------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(256) flash_bwd_dq_k(const bf16* __restrict__ q, const bf16* __restrict__ k,
+__global__ void __launch_bounds__(256, 2) flash_bwd_dq_k(const bf16* __restrict__ q, const bf16* __restrict__ k,
                                                       const bf16* __restrict__ v, const bf16* __restrict__ d_o,
                                                       const float* __restrict__ lse, const float* __restrict__ dvec,
                                                       bf16* __restrict__ dq, int S, int H, int causal, float scale) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   bf16* sK = (bf16*)smem_raw;               // 2 stages [64][KST]
   bf16* sV = sK + 2 * BKV * KST;            // 2 stages [64][KST]
-  const int qt = gridDim.x - 1 - blockIdx.x;
-  const int hh = blockIdx.y, b = blockIdx.z;
+  const int qt = gridDim.y - 1 - blockIdx.y;
+  const int hh = blockIdx.x, b = blockIdx.z;
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6, g = lane >> 5;
   const i64 ld = (i64)H * DH;
   const i64 boff = (i64)b * S * ld + hh * DH;
@@ -282,13 +301,16 @@ __global__ void __launch_bounds__(256) flash_bwd_dq_k(const bf16* __restrict__ q
           sacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(cK, KST, j * 32, kk, lane), qf[kk], sacc[j], 0, 0, 0);
           dpacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(cV, KST, j * 32, kk, lane), dof[kk], dpacc[j], 0, 0, 0);
         }
+      const bool need_mask = (kv0 + BKV > S) || (causal && kv0 + BKV - 1 > qw);
 #pragma unroll
       for (int j = 0; j < 2; j++)
 #pragma unroll
         for (int e = 0; e < 16; e++) {
-          int kv = kv0 + j * 32 + (e >> 2) * 8 + g * 4 + (e & 3);
           float p = fast_exp2(sacc[j][e] * sl2 - mylse);
-          if (kv >= S || (causal && kv > myq)) p = 0.f;
+          if (need_mask) {
+            int kv = kv0 + j * 32 + (e >> 2) * 8 + g * 4 + (e & 3);
+            if (kv >= S || (causal && kv > myq)) p = 0.f;
+          }
           sacc[j][e] = p * (dpacc[j][e] - myD) * scale;      // dS^T
         }
 #pragma unroll
@@ -338,8 +360,8 @@ __global__ void __launch_bounds__(256) flash_bwd_dkv_k(const bf16* __restrict__ 
   bf16* sO = sQ + 2 * BKV * KST;            // 2 stages [64][KST]  (dO)
   float* sL = (float*)(sO + 2 * BKV * KST); // 2 stages [64] lse (log2 domain), then 2 stages [64] D
   float* sD = sL + 2 * BKV;
-  const int kt = blockIdx.x;                // early key tiles see the most queries when causal: first
-  const int hh = blockIdx.y, b = blockIdx.z;
+  const int kt = blockIdx.y;                // early key tiles see the most queries when causal: first
+  const int hh = blockIdx.x, b = blockIdx.z;
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6, g = lane >> 5;
   const i64 ld = (i64)H * DH;
   const i64 boff = (i64)b * S * ld + hh * DH;
@@ -413,15 +435,22 @@ __global__ void __launch_bounds__(256) flash_bwd_dkv_k(const bf16* __restrict__ 
           sacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(cQ, KST, j * 32, kk, lane), kf[kk], sacc[j], 0, 0, 0);
           dpacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(cO, KST, j * 32, kk, lane), vf[kk], dpacc[j], 0, 0, 0);
         }
+      const bool need_mask = causal && (q0 < kw + 31);           // some query of the tile precedes some key of the wave
 #pragma unroll
       for (int j = 0; j < 2; j++)
 #pragma unroll
-        for (int e = 0; e < 16; e++) {
-          int r = j * 32 + (e >> 2) * 8 + g * 4 + (e & 3);      // query row inside the tile
-          float p = fast_exp2(sacc[j][e] * sl2 - cL[r]);
-          if (causal && mykv > q0 + r) p = 0.f;
-          dpacc[j][e] = p * (dpacc[j][e] - cD[r]) * scale;       // dS
-          sacc[j][e] = p;                                         // P
+        for (int eb = 0; eb < 4; eb++) {
+          const int r0 = j * 32 + eb * 8 + g * 4;                 // 4 consecutive query rows inside the tile
+          const float4 l4 = *(const float4*)(cL + r0), d4 = *(const float4*)(cD + r0);
+          const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dv4[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+          for (int i = 0; i < 4; i++) {
+            const int e = eb * 4 + i;
+            float p = fast_exp2(sacc[j][e] * sl2 - lv[i]);
+            if (need_mask && mykv > q0 + r0 + i) p = 0.f;
+            dpacc[j][e] = p * (dpacc[j][e] - dv4[i]) * scale;     // dS
+            sacc[j][e] = p;                                        // P
+          }
         }
 #pragma unroll
       for (int j = 0; j < 2; j++)
@@ -478,7 +507,7 @@ int launch_attn_bwd_flash(const void* q, const void* k, const void* v, const voi
     (void)hipFuncSetAttribute((const void*)flash_bwd_dkv_k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm2);
     attr_set = true;
   }
-  dim3 grid(cdiv(S, 128), H, B);
+  dim3 grid(H, cdiv(S, 128), B);
   hipLaunchKernelGGL(flash_bwd_dq_k, grid, dim3(256), sm1, s, (const bf16*)q, (const bf16*)k, (const bf16*)v,
                      (const bf16*)d_o, lse, dvec, (bf16*)dq, S, H, causal, scale);
   hipLaunchKernelGGL(flash_bwd_dkv_k, grid, dim3(256), sm2, s, (const bf16*)q, (const bf16*)k, (const bf16*)v,
