@@ -105,6 +105,18 @@ def bench_stack(args, wl):
     print(json.dumps(out))
 
 
+def measured_traffic(workload, family):
+    """HBM bytes per launch of a kernel family (fetched + written), from the committed rocprofv3 --pmc FETCH_SIZE /
+    WRITE_SIZE summary of this workload; None when no such summary exists for it."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", f"hbm_traffic__{workload}.json")
+    try:
+        with open(path) as f:
+            fam = json.load(f)["families"].get(family)
+    except (OSError, ValueError, KeyError):
+        return None
+    return None if fam is None else fam["fetch_bytes_per_launch"] + fam["write_bytes_per_launch"]
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -113,6 +125,8 @@ def main():
     ap.add_argument("--workload", default="qwen_b4s512")
     ap.add_argument("--inv-iters", type=int, default=1, help="fixed-point iterations of the inverse (paper: 1)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-events", action="store_true",
+                    help="time the steps without the per-launch HIP events (no roofline object)")
     ap.add_argument("--separate-calls", action="store_true",
                     help="revffn_inverse + revffn_backward as two calls (MoE half evaluated twice) instead of "
                          "revffn_inverse_backward")
@@ -160,7 +174,7 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    ctx.profile_enable(True)            # HIP events around every GEMM / attention launch, on this stream
+    ctx.profile_enable(not args.no_kernel_events)   # HIP events around every GEMM / attention launch, on its stream
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     e0.record(stream)
@@ -189,7 +203,7 @@ def main():
                         "frac": gbs / PEAK_HBM_GBS}
         roofline.update({"kernel": dom, "launches_per_step": p["launches"] / args.steps,
                          "avg_launch_us": avg_ms * 1e3, "share_of_step": p["ms"] / args.steps / ms_per_step,
-                         "traffic": None})
+                         "traffic": measured_traffic(wl.name, dom)})
     kernels = {k: {"ms_per_step": v["ms"] / args.steps, "launches_per_step": v["launches"] / args.steps,
                    "tflops": v["flops"] / (v["ms"] * 1e-3) / 1e12, "gbs": v["bytes"] / (v["ms"] * 1e-3) / 1e9}
                for k, v in prof.items()}

@@ -24,11 +24,11 @@ typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 // rows read together by a 16-byte fragment read start on distinct 16-byte bank groups).
 // TR = 1: [BK][ROWS] with row stride ROWS+32 elements (the 4 k-rows x 64 B read together by a
 // transposing read fall on disjoint banks).
-template <bool TR, int ROWS, int BK>
+template <bool TR, int ROWS, int BK, int NT>
 struct Tile {
   static constexpr int stride = TR ? ROWS + 32 : BK + 8;
   static constexpr int elems = TR ? BK * stride : ROWS * stride;
-  static constexpr int chunks = ROWS * (BK / 8) / 256;   // 16-byte chunks per thread per k-step
+  static constexpr int chunks = ROWS * (BK / 8) / NT;   // 16-byte chunks per thread per k-step
 };
 
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
@@ -55,13 +55,14 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p) {
 }
 
 // ---- global -> registers ----------------------------------------------------------
-template <bool TR, int ROWS, int BK>
-__device__ __forceinline__ void load_tile(const OperandSrc& s, int k0, int k_end, uint4 (&regs)[Tile<TR, ROWS, BK>::chunks],
-                                          const unsigned (&rowoff)[Tile<TR, ROWS, BK>::chunks]) {
-  constexpr int NC = Tile<TR, ROWS, BK>::chunks;
+template <bool TR, int ROWS, int BK, int NT>
+__device__ __forceinline__ void load_tile(const OperandSrc& s, int k0, int k_end,
+                                          uint4 (&regs)[Tile<TR, ROWS, BK, NT>::chunks],
+                                          const unsigned (&rowoff)[Tile<TR, ROWS, BK, NT>::chunks]) {
+  constexpr int NC = Tile<TR, ROWS, BK, NT>::chunks;
 #pragma unroll
   for (int i = 0; i < NC; i++) {
-    int c = threadIdx.x + 256 * i;
+    int c = threadIdx.x + NT * i;
     unsigned off;
     if (!TR) {
       int k = k0 + (c % (BK / 8)) * 8;
@@ -78,11 +79,11 @@ __device__ __forceinline__ void load_tile(const OperandSrc& s, int k0, int k_end
 
 // per-thread row byte offsets of the non-transposed operand (fixed over the k loop); rows past
 // the limit are clamped to the last valid row (their products are never stored)
-template <int ROWS, int BK>
-__device__ __forceinline__ void row_offsets(const OperandSrc& s, unsigned (&rowoff)[ROWS * (BK / 8) / 256]) {
+template <int ROWS, int BK, int NT>
+__device__ __forceinline__ void row_offsets(const OperandSrc& s, unsigned (&rowoff)[ROWS * (BK / 8) / NT]) {
 #pragma unroll
-  for (int i = 0; i < ROWS * (BK / 8) / 256; i++) {
-    int c = threadIdx.x + 256 * i;
+  for (int i = 0; i < ROWS * (BK / 8) / NT; i++) {
+    int c = threadIdx.x + NT * i;
     int r = s.row0 + c / (BK / 8);
     const bool in = r < s.row_lim;
     if (!in) r = s.row_lim - 1;
@@ -92,13 +93,13 @@ __device__ __forceinline__ void row_offsets(const OperandSrc& s, unsigned (&rowo
 }
 
 // ---- registers -> LDS -------------------------------------------------------------
-template <bool TR, int ROWS, int BK>
-__device__ __forceinline__ void store_tile(bf16* lds, const uint4 (&regs)[Tile<TR, ROWS, BK>::chunks]) {
-  constexpr int NC = Tile<TR, ROWS, BK>::chunks;
-  constexpr int ST = Tile<TR, ROWS, BK>::stride;
+template <bool TR, int ROWS, int BK, int NT>
+__device__ __forceinline__ void store_tile(bf16* lds, const uint4 (&regs)[Tile<TR, ROWS, BK, NT>::chunks]) {
+  constexpr int NC = Tile<TR, ROWS, BK, NT>::chunks;
+  constexpr int ST = Tile<TR, ROWS, BK, NT>::stride;
 #pragma unroll
   for (int i = 0; i < NC; i++) {
-    int c = threadIdx.x + 256 * i;
+    int c = threadIdx.x + NT * i;
     int off;
     if (!TR) off = (c / (BK / 8)) * ST + (c % (BK / 8)) * 8;
     else off = (c / (ROWS / 8)) * ST + (c % (ROWS / 8)) * 8;
@@ -110,7 +111,7 @@ __device__ __forceinline__ void store_tile(bf16* lds, const uint4 (&regs)[Tile<T
 // holds k = 8g..8g+7 of row r ---------------------------------------------------------
 template <bool TR, int ROWS, int BK>
 __device__ __forceinline__ bf16x8 load_frag(const bf16* lds, int r0, int kk, int lane) {
-  constexpr int ST = Tile<TR, ROWS, BK>::stride;
+  constexpr int ST = Tile<TR, ROWS, BK, 256>::stride;
   if (!TR) {
     return *(const bf16x8*)(lds + (r0 + (lane & 31)) * ST + kk * 16 + (lane >> 5) * 8);
   } else {
@@ -127,12 +128,12 @@ __device__ __forceinline__ bf16x8 load_frag(const bf16* lds, int r0, int kk, int
 
 // PD = number of k-tiles kept in flight in registers ahead of the one being multiplied
 #define PD 3
-
-template <int BM, int BN, int BK, int WGM, bool AT, bool BT, class TC, bool RB>
-__global__ void __launch_bounds__(256) gemm_mfma_k(GemmArgs g) {
-  typedef Tile<AT, BM, BK> TA_;
-  typedef Tile<BT, BN, BK> TB_;
-  constexpr int WGN = 4 / WGM;                       // waves along n
+template <int BM, int BN, int BK, int WGM, bool AT, bool BT, class TC, bool RB, int NW>
+__global__ void __launch_bounds__(NW * 64) gemm_mfma_k(GemmArgs g) {
+  constexpr int NT = NW * 64;                       // threads per workgroup
+  typedef Tile<AT, BM, BK, NT> TA_;
+  typedef Tile<BT, BN, BK, NT> TB_;
+  constexpr int WGN = NW / WGM;                      // waves along n
   constexpr int WM = BM / WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32;
   static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile must be made of 32x32 blocks");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
@@ -142,37 +143,66 @@ __global__ void __launch_bounds__(256) gemm_mfma_k(GemmArgs g) {
   const bf16* A = (const bf16*)g.A;
   const bf16* Bm = (const bf16*)g.B;
   TC* C = (TC*)g.C;
+  // ---- which tile this workgroup computes.  Workgroups go to the 8 XCDs round-robin by linear id and every
+  // XCD has an L2 of its own, so with xcd_m != 0 (1-D grid) XCD c = id & 7 gets tiles that share operands:
+  // a consecutive run of the expert tile list, whole experts of a per-expert weight gradient, or one
+  // rectangle of an xcd_m x (8 / xcd_m) split of a dense problem's tiles (m fastest inside the rectangle).
+  int bx, by, bz = blockIdx.z;
+  if (g.xcd_m == 0) { bx = blockIdx.x; by = blockIdx.y; }
+  else {
+    const int c = blockIdx.x & 7, loc = blockIdx.x >> 3;
+    if (g.group_mode == 1) {
+      const int total = g.tiles_n * g.tile_count[0];
+      const int q = total >> 3, r = total & 7;
+      if (loc >= q + (c < r ? 1 : 0)) return;
+      const int nl = c * q + min(c, r) + loc;
+      by = nl / g.tiles_n; bx = nl - by * g.tiles_n;
+    } else if (g.group_mode == 2) {
+      const int per = g.tiles_n * g.tiles_m;
+      const int round = loc / per, t = loc - round * per;
+      bz = round * 8 + c;
+      if (bz >= g.n_groups) return;
+      by = t / g.tiles_n; bx = t - by * g.tiles_n;
+    } else {
+      const int xm = g.xcd_m, xn = 8 / xm;
+      const int sm = (g.tiles_m + xm - 1) / xm, sn = (g.tiles_n + xn - 1) / xn;
+      const int cm = c / xn, cn = c - cm * xn;
+      const int ln = loc / sm, lm = loc - ln * sm;
+      by = cm * sm + lm; bx = cn * sn + ln;
+      if (by >= g.tiles_m || bx >= g.tiles_n) return;
+    }
+  }
   int m0, m_end, k0 = 0, k_end = g.K;
   if (g.group_mode == 1) {
-    int ti = blockIdx.y;
+    int ti = by;
     int grp = g.tile_group[ti];
     if (grp < 0) return;
     m0 = g.tile_m0[ti];
     m_end = min(g.offsets[grp + 1], m0 + BM);
     Bm += (i64)grp * g.b_group_stride;
   } else {
-    m0 = blockIdx.y * BM;
+    m0 = by * BM;
     m_end = g.M;
     if (g.group_mode == 2) {
-      int grp = blockIdx.z;
+      int grp = bz;
       k0 = g.offsets[grp];
       k_end = g.offsets[grp + 1];
       C += (i64)grp * g.c_group_stride;
     } else if (g.split_k > 1) {                      // k slices of whole k-tiles; partial sums go to splitk_ws
       int per = ((g.K + BK - 1) / BK + g.split_k - 1) / g.split_k * BK;
-      k0 = min(g.K, (int)blockIdx.z * per);
+      k0 = min(g.K, bz * per);
       k_end = min(g.K, k0 + per);
     }
   }
-  const int n0 = blockIdx.x * BN;
+  const int n0 = bx * BN;
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   const int wm = (wv / WGN) * WM, wn = (wv % WGN) * WN;
 
   OperandSrc sa{make_rsrc(A), (unsigned)g.lda * 2u, g.a_gather, g.gather_div, m0, m_end};
   OperandSrc sb{make_rsrc(Bm), (unsigned)g.ldb * 2u, nullptr, 1, n0, g.N};
   unsigned offA[TA_::chunks], offB[TB_::chunks];
-  if (!AT) row_offsets<BM, BK>(sa, offA);
-  if (!BT) row_offsets<BN, BK>(sb, offB);
+  if (!AT) row_offsets<BM, BK, NT>(sa, offA);
+  if (!BT) row_offsets<BN, BK, NT>(sb, offB);
 
   // 32-row blocks of this wave's tile that hold at least one valid row (partial expert tiles)
   const int tm_eff = RB ? min(TM, max(0, (m_end - m0 - wm + 31) / 32)) : TM;
@@ -194,19 +224,19 @@ __global__ void __launch_bounds__(256) gemm_mfma_k(GemmArgs g) {
   const int nk = (k_end - k0 + BK - 1) / BK;
 #pragma unroll
   for (int p = 0; p < PD; p++) {
-    load_tile<AT, BM, BK>(sa, k0 + p * BK, k_end, ra[p], offA);
-    load_tile<BT, BN, BK>(sb, k0 + p * BK, k_end, rb[p], offB);
+    load_tile<AT, BM, BK, NT>(sa, k0 + p * BK, k_end, ra[p], offA);
+    load_tile<BT, BN, BK, NT>(sb, k0 + p * BK, k_end, rb[p], offB);
   }
-  store_tile<AT, BM, BK>(sA, ra[0]);
-  store_tile<BT, BN, BK>(sB, rb[0]);
+  store_tile<AT, BM, BK, NT>(sA, ra[0]);
+  store_tile<BT, BN, BK, NT>(sB, rb[0]);
   __syncthreads();
   for (int kt0 = 0; kt0 < nk; kt0 += PD) {
 #pragma unroll
     for (int u = 0; u < PD; u++) {
       const int kt = kt0 + u;
       const int cur = kt & 1;
-      load_tile<AT, BM, BK>(sa, k0 + (kt + PD) * BK, k_end, ra[u], offA);
-      load_tile<BT, BN, BK>(sb, k0 + (kt + PD) * BK, k_end, rb[u], offB);
+      load_tile<AT, BM, BK, NT>(sa, k0 + (kt + PD) * BK, k_end, ra[u], offA);
+      load_tile<BT, BN, BK, NT>(sb, k0 + (kt + PD) * BK, k_end, rb[u], offB);
       if (kt < nk) {                                  // uniform over the workgroup
         const bf16* cA = sA + cur * TA_::elems;
         const bf16* cB = sB + cur * TB_::elems;
@@ -235,15 +265,15 @@ __global__ void __launch_bounds__(256) gemm_mfma_k(GemmArgs g) {
             }
         }
       }
-      store_tile<AT, BM, BK>(sA + (cur ^ 1) * TA_::elems, ra[(u + 1) % PD]);   // tile kt+1
-      store_tile<BT, BN, BK>(sB + (cur ^ 1) * TB_::elems, rb[(u + 1) % PD]);
+      store_tile<AT, BM, BK, NT>(sA + (cur ^ 1) * TA_::elems, ra[(u + 1) % PD]);   // tile kt+1
+      store_tile<BT, BN, BK, NT>(sB + (cur ^ 1) * TB_::elems, rb[(u + 1) % PD]);
       __syncthreads();
     }
   }
 
   // ---- epilogue: lane holds column n = lane & 31 and rows (e>>2)*8 + (lane>>5)*4 + (e&3)
   if (g.group_mode == 0 && g.split_k > 1) {
-    float* ws = g.splitk_ws + (i64)blockIdx.z * g.M * g.N;
+    float* ws = g.splitk_ws + (i64)bz * g.M * g.N;
 #pragma unroll
     for (int j = 0; j < TN; j++) {
       const int n = n0 + wn + j * 32 + (lane & 31);
@@ -300,20 +330,47 @@ __global__ void __launch_bounds__(256) gemm_mfma_k(GemmArgs g) {
   }
 }
 
-template <int BM, int BN, int BK, int WGM, bool AT, bool BT, class TC, bool RB = false>
-static void go(const GemmArgs& g, hipStream_t s) {
-  dim3 grid;
-  if (g.group_mode == 1) grid = dim3(cdiv(g.N, BN), g.max_tiles, 1);
-  else grid = dim3(cdiv(g.N, BN), cdiv(g.M, BM), g.group_mode == 2 ? g.n_groups : (g.split_k > 1 ? g.split_k : 1));
-  if (grid.x == 0 || grid.y == 0 || grid.z == 0) return;
-  size_t smem = (size_t)2 * (Tile<AT, BM, BK>::elems + Tile<BT, BN, BK>::elems) * sizeof(bf16);
+// REVFFN_XCD (tuning aid): 0 = plain 2-D grids, tiles land on the XCDs round-robin
+static int xcd_enabled() {
+  static int v = -1;
+  if (v < 0) { const char* e = getenv("REVFFN_XCD"); v = e ? atoi(e) : 1; }
+  return v;
+}
+
+template <int BM, int BN, int BK, int WGM, bool AT, bool BT, class TC, bool RB = false, int NW = 4>
+static void go(const GemmArgs& g0, hipStream_t s) {
+  GemmArgs g = g0;
+  g.tiles_n = cdiv(g.N, BN);
+  g.tiles_m = g.group_mode == 1 ? g.max_tiles : cdiv(g.M, BM);
+  const int zdim = g.group_mode == 2 ? g.n_groups : (g.group_mode == 0 && g.split_k > 1 ? g.split_k : 1);
+  if (g.tiles_n <= 0 || g.tiles_m <= 0 || zdim <= 0) return;
+  dim3 grid(g.tiles_n, g.tiles_m, zdim);
+  g.xcd_m = 0;
+  if (xcd_enabled()) {
+    if (g.group_mode == 1) {
+      if (g.tile_count) { g.xcd_m = 1; grid = dim3(g.tiles_n * g.tiles_m, 1, 1); }
+    } else if (g.group_mode == 2) {
+      // whole experts per XCD: less traffic, but uneven expert sizes then leave XCDs idle (measured slower
+      // under a skewed routing, equal under a balanced one), so only on request (REVFFN_XCD=2)
+      if (xcd_enabled() == 2) { g.xcd_m = 1; grid = dim3(8 * cdiv(g.n_groups, 8) * g.tiles_n * g.tiles_m, 1, 1); }
+    } else if ((i64)g.tiles_n * g.tiles_m >= 64) {
+      // the split of the tiles over the XCDs that touches the fewest operand rows per XCD
+      i64 best = -1;
+      for (int xm = 1; xm <= 8; xm *= 2) {
+        i64 cost = (i64)cdiv(g.tiles_m, xm) * BM + (i64)cdiv(g.tiles_n, 8 / xm) * BN;
+        if (best < 0 || cost < best) { best = cost; g.xcd_m = xm; }
+      }
+      grid = dim3(8 * cdiv(g.tiles_m, g.xcd_m) * cdiv(g.tiles_n, 8 / g.xcd_m), 1, zdim);
+    }
+  }
+  size_t smem = (size_t)2 * (Tile<AT, BM, BK, NW * 64>::elems + Tile<BT, BN, BK, NW * 64>::elems) * sizeof(bf16);
   static bool attr_set = false;
   if (!attr_set) {
-    (void)hipFuncSetAttribute((const void*)gemm_mfma_k<BM, BN, BK, WGM, AT, BT, TC, RB>,
+    (void)hipFuncSetAttribute((const void*)gemm_mfma_k<BM, BN, BK, WGM, AT, BT, TC, RB, NW>,
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     attr_set = true;
   }
-  hipLaunchKernelGGL((gemm_mfma_k<BM, BN, BK, WGM, AT, BT, TC, RB>), grid, dim3(256), smem, s, g);
+  hipLaunchKernelGGL((gemm_mfma_k<BM, BN, BK, WGM, AT, BT, TC, RB, NW>), grid, dim3(NW * 64), smem, s, g);
 }
 
 // REVFFN_GEMM_TILE (tuning aid): 1 = 128x128, 2 = 128x64, 3 = 64x128 for every non-grouped problem

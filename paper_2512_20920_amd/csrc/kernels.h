@@ -35,6 +35,10 @@ struct GemmArgs {
   // splitk_ws[slice][M][N]; a second kernel adds the slices in index order and applies the epilogue
   int split_k = 1; float* splitk_ws = nullptr;
   const void* col_scale = nullptr;
+  // group_mode 1: number of m-tiles of the list actually in use (device scalar written by the permutation kernel)
+  const int* tile_count = nullptr;
+  // set by the MFMA launcher: XCD-aware placement of the tiles (0 = plain 2-D grid), tile counts of the problem
+  int xcd_m = 0, tiles_m = 0, tiles_n = 0;
 };
 
 // element types of A, B, C: 0 = f32, 1 = bf16.  bias and resid have C's... no: the
@@ -77,10 +81,12 @@ void launch_absdiff_max_copy(int dt, const void* a, i64 lda, const void* b, i64 
 void launch_router(int dt, const void* y1, i64 ld, const float* zraw, const float* b_router,
                    float* probs, int* idx, float* wts, float* gamma, int T, int h, int E, int k, int has_gate,
                    int norm_topk, float eps, hipStream_t s);
-// counts/offsets/row_map/inv_map and the two m-tile lists (tile heights bm_a, bm_b)
+// m-tile lists of the grouped GEMMs for two tile heights: list i covers every expert's rows with
+// tiles of bm[i] rows (group[i][t] = expert or -1 for an unused slot, m0[i][t] = first row, count[i] = tiles in use)
+struct TileLists { int* group[2]; int* m0[2]; int max_tiles[2]; int bm[2]; int* count; };
+// counts/offsets/row_map/inv_map and the tile lists
 void launch_permute(const int* idx, int T, int k, int E, int* counts, int* offsets, int* row_map, int* inv_map,
-                    int* tile_group_a, int* tile_m0_a, int max_tiles_a, int bm_a,
-                    int* tile_group_b, int* tile_m0_b, int max_tiles_b, int bm_b, hipStream_t s);
+                    const TileLists& tl, hipStream_t s);
 void launch_combine(int dt, const void* yp, const int* inv_map, const float* wts, const void* ys,
                     const float* gamma, void* rs, int T, int d, int k, hipStream_t s);
 void launch_moe_bwd_rows(int dt, const void* drs, const void* yp, const void* ys, const int* inv_map,

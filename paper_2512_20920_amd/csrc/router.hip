@@ -104,8 +104,7 @@ __device__ __forceinline__ void same_expert_mask(int x, bool valid, int nbits, u
 
 __global__ void __launch_bounds__(PERM_WAVES * 64) permute_k(
     const int* __restrict__ idx, int N, int E, int* __restrict__ counts, int* __restrict__ offsets,
-    int* __restrict__ row_map, int* __restrict__ inv_map, int* tile_group_a, int* tile_m0_a, int max_tiles_a,
-    int bm_a, int* tile_group_b, int* tile_m0_b, int max_tiles_b, int bm_b) {
+    int* __restrict__ row_map, int* __restrict__ inv_map, TileLists tl) {
   extern __shared__ int ism[];            // cnt[PERM_WAVES][E], then off[E+1]
   int* cnt = ism;
   int* off = ism + PERM_WAVES * E;
@@ -144,9 +143,9 @@ __global__ void __launch_bounds__(PERM_WAVES * 64) permute_k(
   // tile lists: expert e owns the slots after the tiles of experts 0..e-1 (tile counts are tiny, so
   // every thread recounts its prefix); slots past the last tile are marked unused
   for (int pass = 0; pass < 2; pass++) {
-    const int bm = pass ? bm_b : bm_a, mx = pass ? max_tiles_b : max_tiles_a;
-    int* tg = pass ? tile_group_b : tile_group_a;
-    int* tm = pass ? tile_m0_b : tile_m0_a;
+    const int bm = tl.bm[pass], mx = tl.max_tiles[pass];
+    int* tg = tl.group[pass];
+    int* tm = tl.m0[pass];
     int total = 0;
     for (int e = 0; e < E; e++) total += (off[e + 1] - off[e] + bm - 1) / bm;
     for (int e = threadIdx.x; e < E; e += blockDim.x) {
@@ -157,6 +156,7 @@ __global__ void __launch_bounds__(PERM_WAVES * 64) permute_k(
         if (i < mx) { tg[i] = e; tm[i] = m; }
     }
     for (int i = total + threadIdx.x; i < mx; i += blockDim.x) { tg[i] = -1; tm[i] = 0; }
+    if (threadIdx.x == 0) tl.count[pass] = min(total, mx);
   }
   __syncthreads();
   for (int base = lo; base < hi; base += 64) {
@@ -177,12 +177,10 @@ __global__ void __launch_bounds__(PERM_WAVES * 64) permute_k(
 }
 
 void launch_permute(const int* idx, int Tn, int k, int E, int* counts, int* offsets, int* row_map, int* inv_map,
-                    int* tile_group_a, int* tile_m0_a, int max_tiles_a, int bm_a, int* tile_group_b,
-                    int* tile_m0_b, int max_tiles_b, int bm_b, hipStream_t s) {
+                    const TileLists& tl, hipStream_t s) {
   size_t smem = (size_t)(PERM_WAVES * E + E + 1) * sizeof(int);
   hipLaunchKernelGGL(permute_k, dim3(1), dim3(PERM_WAVES * 64), smem, s, idx, Tn * k, E, counts, offsets, row_map,
-                     inv_map, tile_group_a, tile_m0_a, max_tiles_a, bm_a, tile_group_b, tile_m0_b, max_tiles_b,
-                     bm_b);
+                     inv_map, tl);
 }
 
 // ---------------------------------------------------------------------------------
