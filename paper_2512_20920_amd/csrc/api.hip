@@ -43,7 +43,7 @@ struct revffn_ctx {
   int device = 0;
   void* slab = nullptr;
   size_t slab_bytes = 0;
-  hipStream_t side[2] = {nullptr, nullptr};   // helper streams for independent branches of one call
+  hipStream_t side[3] = {nullptr, nullptr, nullptr};   // helper streams for independent branches of one call
   std::vector<hipEvent_t>* sync_ev = nullptr;  // ring of timing-free events for fork/join
   size_t sync_next = 0;
   bool use_streams = true;
@@ -66,7 +66,8 @@ struct revffn_ctx {
   // backward
   void *dRS, *dYp, *dYs, *dHs, *dGUs, *dUm_sh, *dHh, *dGU, *dXg, *dUm, *dn3, *g1;
   float *dw, *dzext, *rinv, *rinv3, *partial;
-  float *zraw, *splitk_ws;
+  float *splitk_ws, *splitk_ws_r;   // split-k slices: weight-gradient side, router side (fold, then logits)
+  bool fold_queued = false;         // the router fold of this call is already enqueued on helper stream 2
   void* dwr_tmp;
   void* wr_ext;               // [E1p, d]: router rows, shared-gate row, zero rows up to a multiple of 8
   void *dzb, *dUm_r;          // bf16 logit gradients [T, E1p] and the router term of dUm [T, d]
@@ -157,7 +158,6 @@ size_t carve(revffn_ctx* c, char* base) {
   c->g1 = cv.take(T * h * es);
   c->dw = (float*)cv.take(N * 4);
   c->dzext = (float*)cv.take(T * E1 * 4);
-  c->zraw = (float*)cv.take(T * E1 * 4);
   c->dwr_tmp = cv.take(E1 * d * es);
   const size_t E1p = (E1 + 7) / 8 * 8;
   c->wr_ext = cv.take(E1p * d * es);
@@ -165,9 +165,8 @@ size_t carve(revffn_ctx* c, char* base) {
   c->dUm_r = cv.take(T * d * es);
   {
     size_t a = SPLIT_FOLD * E1 * h, b2 = SPLIT_LOGITS * T * E1, c3 = SPLIT_DWR * E1 * d;
-    size_t mx = a > b2 ? a : b2;
-    if (c3 > mx) mx = c3;
-    c->splitk_ws = (float*)cv.take(mx * 4);
+    c->splitk_ws_r = (float*)cv.take((a > b2 ? a : b2) * 4);
+    c->splitk_ws = (float*)cv.take(c3 * 4);
   }
   c->rinv = (float*)cv.take(2 * T * 4);
   c->rinv3 = (float*)cv.take(T * 4);
@@ -337,13 +336,45 @@ int attn_out(revffn_ctx* c, const revffn_weights* w, const void* resid, i64 ldr,
 }
 
 // ---- MoE half ---------------------------------------------------------------------
+// Folded fp32 router matrix wrp = [W_r ; w_shared_gate] . P_up_m . diag(gain).  It depends on the weights only, so a
+// call that starts with the attention half enqueues it at once on helper stream 2, next to that half.
+void router_fold(revffn_ctx* c, const revffn_weights* w, hipStream_t s) {
+  const revffn_config& f = c->cfg;
+  const int d = f.d_model, h = d / 2, E = f.n_experts, Is = f.d_shared, dt = c->dt;
+  hipStream_t sr = side(c, s, 2);
+  after(c, s, sr);                        // everything that read wr_ext / wrp before is on s
+  // [W_r ; w_shared_gate] stacked into one [E1, d] matrix so that the fold is a single GEMM
+  launch_copy_rows(dt, w->w_router, d, c->wr_ext, d, E, d, sr);
+  if (Is) launch_copy_rows(dt, w->ws_gate, d, at(c->wr_ext, (size_t)E * d, c->es), d, 1, d, sr);
+  GemmArgs a = nn(c->wr_ext, d, w->pup_m, h, c->wrp, h, E + (Is ? 1 : 0), h, d);
+  a.split_k = SPLIT_FOLD; a.splitk_ws = c->splitk_ws_r; a.col_scale = w->norm_m;
+  (void)run_gemm(c, a, dt, dt, 0, sr);
+  c->fold_queued = true;
+}
+
 // Recomputes n3, Um, routing, GU, Hh, Yp, shared expert and RS at y1.
 int moe_acts(revffn_ctx* c, const revffn_weights* w, const void* y1, i64 ld, int T, hipStream_t s) {
   const revffn_config& f = c->cfg;
   const int d = f.d_model, h = d / 2, E = f.n_experts, k = f.top_k, I = f.d_expert, Is = f.d_shared, dt = c->dt;
-  const int N = T * k;
+  const int N = T * k, E1 = E + (Is ? 1 : 0);
   c->lastT = T;
   c->lastT_rows = N;
+  // Routing needs Y1 and the weights only (the logits are Y1 . wrp^T in fp32, scaled by 1/rms(Y1) in the router
+  // kernel), so fold, logits, top-k and the permutation run on helper stream 2 next to the norm and the up-projection.
+  hipStream_t sr = side(c, s, 2);
+  if (c->fold_queued) after(c, s, sr);    // y1 is complete on s
+  else router_fold(c, w, s);              // (forks from s as well)
+  c->fold_queued = false;
+  {
+    GemmArgs z = nt(y1, ld, c->wrp, h, c->splitk_ws_r, E1, T, E1, h);
+    z.split_k = SPLIT_LOGITS; z.splitk_ws = c->splitk_ws_r; z.splitk_raw = 1;   // the router kernel adds the slices
+    GemmTypes tz{dt, 0, 0, dt};
+    if (launch_gemm_generic(z, tz, sr)) return REVFFN_EUNSUPPORTED;
+  }
+  launch_router(dt, y1, ld, c->splitk_ws_r, SPLIT_LOGITS, w->b_router, c->probs, c->idx, c->wts, c->gamma, T, h, E, k,
+                Is ? 1 : 0, f.norm_topk_prob, f.rms_eps, sr);
+  TileLists tl{{c->tg_a, c->tg_b}, {c->tm_a, c->tm_b}, {c->max_tiles_a, c->max_tiles_b}, {BM_A, BM_B}, c->tile_cnt};
+  launch_permute(c->idx, T, k, E, c->counts, c->offsets, c->row_map, c->inv_map, tl, sr);
   launch_rmsnorm_fwd(dt, y1, ld, w->norm_m, c->n3, h, T, h, f.rms_eps, s);
   TRY(run_gemm(c, nt(c->n3, h, w->pup_m, h, c->Um, d, T, d, h), s));
   hipStream_t s0 = side(c, s, 0);
@@ -353,25 +384,7 @@ int moe_acts(revffn_ctx* c, const revffn_weights* w, const void* y1, i64 ld, int
     launch_swiglu_fwd(dt, c->GUs, c->Hs, T, Is, s0);
     TRY(run_gemm(c, nt(c->Hs, Is, w->ws_down, Is, c->Ys, d, T, d, Is), s0));
   }
-  // folded fp32 router matrix  wrp = [W_r ; w_shared_gate] . P_up_m . diag(gain), then the raw logits
-  // zraw = Y1 . wrp^T, both as fp32 split-k GEMMs on the vector ALUs
-  {
-    // [W_r ; w_shared_gate] stacked into one [E1, d] matrix so that the fold is a single GEMM
-    launch_copy_rows(dt, w->w_router, d, c->wr_ext, d, E, d, s);
-    if (Is) launch_copy_rows(dt, w->ws_gate, d, at(c->wr_ext, (size_t)E * d, c->es), d, 1, d, s);
-    GemmArgs a = nn(c->wr_ext, d, w->pup_m, h, c->wrp, h, E + (Is ? 1 : 0), h, d);
-    a.split_k = SPLIT_FOLD; a.splitk_ws = c->splitk_ws; a.col_scale = w->norm_m;
-    TRY(run_gemm(c, a, dt, dt, 0, s));
-    const int E1 = E + (Is ? 1 : 0);
-    GemmArgs z = nt(y1, ld, c->wrp, h, c->zraw, E1, T, E1, h);
-    z.split_k = SPLIT_LOGITS; z.splitk_ws = c->splitk_ws;
-    GemmTypes tz{dt, 0, 0, dt};
-    if (launch_gemm_generic(z, tz, s)) return REVFFN_EUNSUPPORTED;
-  }
-  launch_router(dt, y1, ld, c->zraw, w->b_router, c->probs, c->idx, c->wts, c->gamma, T, h, E, k,
-                Is ? 1 : 0, f.norm_topk_prob, f.rms_eps, s);
-  TileLists tl{{c->tg_a, c->tg_b}, {c->tm_a, c->tm_b}, {c->max_tiles_a, c->max_tiles_b}, {BM_A, BM_B}, c->tile_cnt};
-  launch_permute(c->idx, T, k, E, c->counts, c->offsets, c->row_map, c->inv_map, tl, s);
+  after(c, sr, s);                        // routing and permutation are ready
   // routed experts: GU = Xg . Wgu_e^T (rows gathered from Um through row_map), SwiGLU, Yp = Hh . Wd_e^T
   GemmArgs g1 = nt(c->Um, d, w->w_gate_up, d, c->GU, 2 * I, N, 2 * I, d);
   g1.group_mode = 1; g1.n_groups = E; g1.offsets = c->offsets; g1.b_group_stride = (i64)2 * I * d;
@@ -398,6 +411,7 @@ int moe_out(revffn_ctx* c, const revffn_weights* w, const void* resid, i64 ldr, 
 
 int check_call(revffn_ctx* c, const revffn_weights* w, int B, int S, i64 ld) {
   if (!c || !w) return REVFFN_ENULL;
+  c->fold_queued = false;
   if (B < 1 || S < 1) return REVFFN_ESHAPE;
   if ((i64)B * S > c->maxT) return REVFFN_ESHAPE;
   if (ld < c->cfg.d_model / 2) return REVFFN_ESHAPE;
@@ -411,6 +425,7 @@ int check_call(revffn_ctx* c, const revffn_weights* w, int B, int S, i64 ld) {
 int forward_impl(revffn_ctx* c, const revffn_weights* w, const void* x1, const void* x2, void* y1, void* y2, int B,
                  int S, i64 ld, hipStream_t s) {
   const int T = B * S;
+  router_fold(c, w, s);
   TRY(attn_acts(c, w, x1, ld, x2, ld, B, S, true, s));
   TRY(attn_out(c, w, x1, ld, 1.f, y1, ld, T, s));                 // Eq. 1
   TRY(moe_acts(c, w, y1, ld, T, s));
@@ -457,12 +472,14 @@ void* gfield(const revffn_grads* g, size_t off) { return g ? *(void* const*)((co
 
 int backward_impl(revffn_ctx* c, const revffn_weights* w, const void* x1, const void* x2, const void* y1, i64 ldy,
                   const void* dy1, const void* dy2, void* dx1, void* dx2, const revffn_grads* g, int B, int S,
-                  i64 ld, bool reuse_moe, hipStream_t s) {
+                  i64 ld, bool reuse_moe, bool reuse_kv, hipStream_t s) {
   const revffn_config& f = c->cfg;
   const int T = B * S, d = f.d_model, h = d / 2, E = f.n_experts, k = f.top_k, I = f.d_expert, Is = f.d_shared;
   const int N = T * k, E1 = E + (Is ? 1 : 0), dt = c->dt, es = c->es;
   // ---- recompute the attention half at (x1, x2)
-  TRY(attn_acts(c, w, x1, ld, x2, ld, B, S, true, s));
+  // (K, V and the normalised, lifted X2 are still those of the inverse when it ran in the same call: same X2 bits)
+  if (!y1 || !reuse_moe) router_fold(c, w, s);
+  TRY(attn_acts(c, w, x1, ld, x2, ld, B, S, !reuse_kv, s));
   if (!y1) {
     TRY(attn_out(c, w, x1, ld, 1.f, c->y1c, h, T, s));
     y1 = c->y1c;
@@ -527,9 +544,12 @@ int backward_impl(revffn_ctx* c, const revffn_weights* w, const void* x1, const 
     if (GF(w_router)) launch_copy_rows(dt, c->dwr_tmp, d, GF(w_router), d, E, d, s);
     if (Is && GF(ws_gate)) launch_copy_rows(dt, at(c->dwr_tmp, (size_t)E * d, es), d, GF(ws_gate), d, 1, d, s);
   }
+  // every column sum (bias and gain gradients) goes to helper stream 2: they share one scratch buffer, and the
+  // weight-gradient GEMMs keep helper stream 1 to themselves
+  hipStream_t sc = side(c, s, 2);
   if (g && g->b_router) {
-    after(c, s, sw);
-    launch_colsum(0, c->dzext, E1, 0, nullptr, 0, nullptr, 0, g->b_router, c->partial, T, E, sw);
+    after(c, s, sc);
+    launch_colsum(0, c->dzext, E1, 0, nullptr, 0, nullptr, 0, g->b_router, c->partial, T, E, sc);
   }
   if (Is) after(c, s0, s);
   const void* dum_r = nullptr;
@@ -548,9 +568,8 @@ int backward_impl(revffn_ctx* c, const revffn_weights* w, const void* x1, const 
   // g1 = dY1 + Norm'(dn3): total gradient at Y1
   launch_rmsnorm_bwd(dt, c->dn3, h, y1, ldy, w->norm_m, dy1, ld, c->g1, h, c->rinv3, T, h, f.rms_eps, s);
   // ---- attention half backward: Y1 = X1 + P_dn_a(AO)
-  after(c, s, sw);
-  if (GF(norm_m)) launch_colsum(dt, y1, ldy, dt, c->dn3, h, c->rinv3, dt, GF(norm_m), c->partial, T, h, sw);
-  if (GF(pdn_a)) TRY(run_gemm(c, tn(c->g1, h, c->AO, d, GF(pdn_a), d, h, d, T), sw));
+  if (GF(norm_m)) { after(c, s, sc); launch_colsum(dt, y1, ldy, dt, c->dn3, h, c->rinv3, dt, GF(norm_m), c->partial, T, h, sc); }
+  if (GF(pdn_a)) { after(c, s, sw); TRY(run_gemm(c, tn(c->g1, h, c->AO, d, GF(pdn_a), d, h, d, T), sw)); }
   TRY(run_gemm(c, nn(c->g1, h, w->pdn_a, d, c->dAO, d, T, d, h), s));
   if (GF(wo)) { after(c, s, sw); TRY(run_gemm(c, tn(c->dAO, d, c->O, d, GF(wo), d, d, d, T), sw)); }
   TRY(run_gemm(c, nn(c->dAO, d, w->wo, d, c->dO, d, T, d, d), s));
@@ -577,12 +596,13 @@ int backward_impl(revffn_ctx* c, const revffn_weights* w, const void* x1, const 
   void* dU2 = at(c->dU12, (size_t)T * d, es);
   after(c, s, sw);
   after(c, s, s0);
+  after(c, s, sc);
   if (GF(wq)) TRY(run_gemm(c, tn(c->dQ, d, U1, d, GF(wq), d, d, d, T), sw));
   if (GF(wk)) TRY(run_gemm(c, tn(c->dK, d, U2, d, GF(wk), d, d, d, T), sw));
   if (GF(wv)) TRY(run_gemm(c, tn(c->dV, d, U2, d, GF(wv), d, d, d, T), sw));
-  if (GF(bq) && w->bq) launch_colsum(dt, c->dQ, d, dt, nullptr, 0, nullptr, dt, GF(bq), c->partial, T, d, sw);
-  if (GF(bk) && w->bk) launch_colsum(dt, c->dK, d, dt, nullptr, 0, nullptr, dt, GF(bk), c->partial, T, d, sw);
-  if (GF(bv) && w->bv) launch_colsum(dt, c->dV, d, dt, nullptr, 0, nullptr, dt, GF(bv), c->partial, T, d, sw);
+  if (GF(bq) && w->bq) launch_colsum(dt, c->dQ, d, dt, nullptr, 0, nullptr, dt, GF(bq), c->partial, T, d, sc);
+  if (GF(bk) && w->bk) launch_colsum(dt, c->dK, d, dt, nullptr, 0, nullptr, dt, GF(bk), c->partial, T, d, sc);
+  if (GF(bv) && w->bv) launch_colsum(dt, c->dV, d, dt, nullptr, 0, nullptr, dt, GF(bv), c->partial, T, d, sc);
   TRY(run_gemm(c, nn(c->dQ, d, w->wq, d, dU1, d, T, d, d), s0));
   TRY(run_gemm(c, nn(c->dK, d, w->wk, d, dU2, d, T, d, d), s));
   {
@@ -597,11 +617,12 @@ int backward_impl(revffn_ctx* c, const revffn_weights* w, const void* x1, const 
   launch_rmsnorm_bwd(dt, c->dn12, h, x1, ld, w->norm_a1, c->g1, h, dx1, ld, c->rinv, T, h, f.rms_eps, s);
   launch_rmsnorm_bwd(dt, at(c->dn12, (size_t)T * h, es), h, x2, ld, w->norm_a2, dy2, ld, dx2, ld, c->rinv + T, T, h,
                      f.rms_eps, s);
-  after(c, s, sw);
-  if (GF(norm_a1)) launch_colsum(dt, x1, ld, dt, c->dn12, h, c->rinv, dt, GF(norm_a1), c->partial, T, h, sw);
+  after(c, s, sc);
+  if (GF(norm_a1)) launch_colsum(dt, x1, ld, dt, c->dn12, h, c->rinv, dt, GF(norm_a1), c->partial, T, h, sc);
   if (GF(norm_a2))
-    launch_colsum(dt, x2, ld, dt, at(c->dn12, (size_t)T * h, es), h, c->rinv + T, dt, GF(norm_a2), c->partial, T, h, sw);
+    launch_colsum(dt, x2, ld, dt, at(c->dn12, (size_t)T * h, es), h, c->rinv + T, dt, GF(norm_a2), c->partial, T, h, sc);
   after(c, sw, s);                       // every weight gradient is complete for the caller's stream
+  after(c, sc, s);
   return 0;
 }
 
@@ -650,7 +671,7 @@ int revffn_create(revffn_ctx** out, const revffn_config* cfg, int32_t max_B, int
   c->use_streams = getenv("REVFFN_NO_STREAMS") == nullptr;
   c->sync_ev = new (std::nothrow) std::vector<hipEvent_t>();
   bool ok = c->sync_ev != nullptr;
-  for (int i = 0; ok && i < 2; i++) ok = hipStreamCreateWithFlags(&c->side[i], hipStreamNonBlocking) == hipSuccess;
+  for (int i = 0; ok && i < 3; i++) ok = hipStreamCreateWithFlags(&c->side[i], hipStreamNonBlocking) == hipSuccess;
   for (int i = 0; ok && i < 96; i++) {
     hipEvent_t e;
     ok = hipEventCreateWithFlags(&e, hipEventDisableTiming) == hipSuccess;
@@ -693,7 +714,7 @@ void revffn_destroy(revffn_ctx* c) {
     for (hipEvent_t e : *c->sync_ev) (void)hipEventDestroy(e);
     delete c->sync_ev;
   }
-  for (int i = 0; i < 2; i++) if (c->side[i]) (void)hipStreamDestroy(c->side[i]);
+  for (int i = 0; i < 3; i++) if (c->side[i]) (void)hipStreamDestroy(c->side[i]);
   if (c->slab) (void)hipFree(c->slab);
   delete c;
 }
@@ -766,7 +787,7 @@ int revffn_backward(revffn_ctx* c, const revffn_weights* w, const void* x1, cons
                     int32_t S, int64_t ld, void* stream) {
   TRY(check_call(c, w, B, S, ld));
   if (!x1 || !x2 || !dy1 || !dy2 || !dx1 || !dx2) return REVFFN_ENULL;
-  return backward_impl(c, w, x1, x2, y1, ld, dy1, dy2, dx1, dx2, g, B, S, ld, false, (hipStream_t)stream);
+  return backward_impl(c, w, x1, x2, y1, ld, dy1, dy2, dx1, dx2, g, B, S, ld, false, false, (hipStream_t)stream);
 }
 
 int revffn_inverse_backward(revffn_ctx* c, const revffn_weights* w, const void* y1, const void* y2, void* x1, void* x2,
@@ -778,7 +799,7 @@ int revffn_inverse_backward(revffn_ctx* c, const revffn_weights* w, const void* 
   const void* y1k = nullptr;
   i64 ldk = 0;
   TRY(inverse_impl(c, w, y1, y2, x1, x2, B, S, ld, residual, s, &y1k, &ldk));
-  return backward_impl(c, w, x1, x2, y1k, ldk, dy1, dy2, dx1, dx2, g, B, S, ld, true, s);
+  return backward_impl(c, w, x1, x2, y1k, ldk, dy1, dy2, dx1, dx2, g, B, S, ld, true, c->cfg.n_inv_iters >= 1, s);
 }
 
 int revffn_stack_forward(revffn_ctx* c, const revffn_weights* w, int32_t n_blocks, const void* x1, const void* x2,
@@ -806,7 +827,7 @@ int revffn_stack_backward(revffn_ctx* c, const revffn_weights* w, const revffn_g
     const void* y1k = nullptr;
     i64 ldk = 0;
     TRY(inverse_impl(c, w + l, y1, y2, y1, y2, B, S, ld, nullptr, s, &y1k, &ldk));
-    TRY(backward_impl(c, w + l, y1, y2, y1k, ldk, dy1, dy2, dy1, dy2, g ? g + l : nullptr, B, S, ld, true, s));
+    TRY(backward_impl(c, w + l, y1, y2, y1k, ldk, dy1, dy2, dy1, dy2, g ? g + l : nullptr, B, S, ld, true, c->cfg.n_inv_iters >= 1, s));
   }
   return 0;
 }

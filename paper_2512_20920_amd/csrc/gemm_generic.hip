@@ -154,7 +154,7 @@ static void go(const GemmArgs& g, hipStream_t s) {
   else grid = dim3(cdiv(g.N, GT), cdiv(g.M, GT), g.group_mode == 2 ? g.n_groups : (g.split_k > 1 ? g.split_k : 1));
   if (grid.x == 0 || grid.y == 0 || grid.z == 0) return;
   hipLaunchKernelGGL((gemm_generic_k<TA, TB, TC, TS>), grid, dim3(256), 0, s, g);
-  if (g.group_mode == 0 && g.split_k > 1)
+  if (g.group_mode == 0 && g.split_k > 1 && !g.splitk_raw)
     hipLaunchKernelGGL((splitk_reduce_k<TC, TS>), dim3(cdiv((i64)g.M * g.N, 256)), dim3(256), 0, s, g);
 }
 

@@ -146,7 +146,7 @@ __global__ void __launch_bounds__(NW * 64) gemm_mfma_k(GemmArgs g) {
   // ---- which tile this workgroup computes.  Workgroups go to the 8 XCDs round-robin by linear id and every
   // XCD has an L2 of its own, so with xcd_m != 0 (1-D grid) XCD c = id & 7 gets tiles that share operands:
   // a consecutive run of the expert tile list, whole experts of a per-expert weight gradient, or one
-  // rectangle of an xcd_m x (8 / xcd_m) split of a dense problem's tiles (m fastest inside the rectangle).
+  // rectangle of an xcd_m x (8 / xcd_m) split of a dense problem's tiles.
   int bx, by, bz = blockIdx.z;
   if (g.xcd_m == 0) { bx = blockIdx.x; by = blockIdx.y; }
   else {
@@ -167,7 +167,11 @@ __global__ void __launch_bounds__(NW * 64) gemm_mfma_k(GemmArgs g) {
       const int xm = g.xcd_m, xn = 8 / xm;
       const int sm = (g.tiles_m + xm - 1) / xm, sn = (g.tiles_n + xn - 1) / xn;
       const int cm = c / xn, cn = c - cm * xn;
-      const int ln = loc / sm, lm = loc - ln * sm;
+      // inside the rectangle: bands of 8 m-tiles, m fastest inside a band, so that the ~64 workgroups an XCD
+      // runs together form an 8 x 8 block of tiles
+      const int band = loc / (8 * sn), r = loc - band * 8 * sn;
+      const int bh = min(8, sm - band * 8);
+      const int ln = r / bh, lm = band * 8 + (r - ln * bh);
       by = cm * sm + lm; bx = cn * sn + ln;
       if (by >= g.tiles_m || bx >= g.tiles_n) return;
     }

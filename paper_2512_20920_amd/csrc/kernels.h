@@ -34,6 +34,7 @@ struct GemmArgs {
   // generic kernel only: the k range is cut into split_k slices whose fp32 partial tiles go to
   // splitk_ws[slice][M][N]; a second kernel adds the slices in index order and applies the epilogue
   int split_k = 1; float* splitk_ws = nullptr;
+  int splitk_raw = 0;                    // generic kernel: leave the slices in splitk_ws, the consumer adds them
   const void* col_scale = nullptr;
   // group_mode 1: number of m-tiles of the list actually in use (device scalar written by the permutation kernel)
   const int* tile_count = nullptr;
@@ -78,7 +79,7 @@ void launch_absdiff_max_copy(int dt, const void* a, i64 lda, const void* b, i64 
 
 // ---- routing ---------------------------------------------------------------------
 // zraw[T,E1] = Y1 . (gain * wrp)^T in fp32 (E1 = E (+1: shared gate row)); the kernel scales by 1/rms(Y1)
-void launch_router(int dt, const void* y1, i64 ld, const float* zraw, const float* b_router,
+void launch_router(int dt, const void* y1, i64 ld, const float* zparts, int n_parts, const float* b_router,
                    float* probs, int* idx, float* wts, float* gamma, int T, int h, int E, int k, int has_gate,
                    int norm_topk, float eps, hipStream_t s);
 // m-tile lists of the grouped GEMMs for two tile heights: list i covers every expert's rows with

@@ -20,8 +20,8 @@
 // by descending logit, equal logits -> lower expert index), gamma[T] = sigmoid(gate logit).
 // ---------------------------------------------------------------------------------
 template <class T>
-__global__ void __launch_bounds__(256) router_k(const T* __restrict__ y1, i64 ld, const float* __restrict__ zraw,
-                                                const float* __restrict__ b_router,
+__global__ void __launch_bounds__(256) router_k(const T* __restrict__ y1, i64 ld, const float* __restrict__ zparts,
+                                                int n_parts, const float* __restrict__ b_router,
                                                 float* __restrict__ probs, int* __restrict__ idx,
                                                 float* __restrict__ wts, float* __restrict__ gamma, int Tn, int h,
                                                 int E, int k, int has_gate, int norm_topk, float eps) {
@@ -36,8 +36,11 @@ __global__ void __launch_bounds__(256) router_k(const T* __restrict__ y1, i64 ld
   for (int j = lane; j < h; j += 64) { float v = to_f(yr[j]); ss += v * v; }
   ss = wave_sum(ss);
   const float r = 1.0f / sqrtf(ss / (float)h + eps);
-  for (int e = lane; e < E1; e += 64)
-    z[e] = zraw[(i64)t * E1 + e] * r + ((e < E && b_router) ? b_router[e] : 0.f);
+  for (int e = lane; e < E1; e += 64) {
+    float raw = 0.f;                     // the k-slices of the logit GEMM, added in slice order
+    for (int p = 0; p < n_parts; p++) raw += zparts[((i64)p * Tn + t) * E1 + e];
+    z[e] = raw * r + ((e < E && b_router) ? b_router[e] : 0.f);
+  }
   __builtin_amdgcn_wave_barrier();       // LDS traffic of one wave is executed in order
   // softmax over the E routed logits
   float mx = -INFINITY;
@@ -76,13 +79,13 @@ __global__ void __launch_bounds__(256) router_k(const T* __restrict__ y1, i64 ld
   if (has_gate && lane == 0) gamma[t] = sigmoid_f(z[E]);
 }
 
-void launch_router(int dt, const void* y1, i64 ld, const float* zraw, const float* b_router, float* probs, int* idx,
+void launch_router(int dt, const void* y1, i64 ld, const float* zparts, int n_parts, const float* b_router, float* probs, int* idx,
                    float* wts, float* gamma, int Tn, int h, int E, int k, int has_gate, int norm_topk, float eps,
                    hipStream_t s) {
   if (Tn <= 0) return;
   size_t smem = (size_t)4 * (E + 1) * sizeof(float);
-  DISPATCH_DT(dt, hipLaunchKernelGGL(router_k<T>, dim3(cdiv(Tn, 4)), dim3(256), smem, s, (const T*)y1, ld, zraw,
-                                     b_router, probs, idx, wts, gamma, Tn, h, E, k, has_gate, norm_topk, eps));
+  DISPATCH_DT(dt, hipLaunchKernelGGL(router_k<T>, dim3(cdiv(Tn, 4)), dim3(256), smem, s, (const T*)y1, ld, zparts,
+                                     n_parts, b_router, probs, idx, wts, gamma, Tn, h, E, k, has_gate, norm_topk, eps));
 }
 
 // ---------------------------------------------------------------------------------
