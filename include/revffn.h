@@ -27,9 +27,9 @@
  *  - Every call only enqueues work and returns; it never synchronises the host.
  *    Work is ordered after what `hip_stream` (a hipStream_t; NULL = the default
  *    stream) already holds, and `hip_stream` is ordered after all of it when the call
- *    returns; independent branches inside a call run on two helper streams owned by
- *    the context (default priority; set REVFFN_NO_STREAMS=1 to keep everything on
- *    `hip_stream`).  Calls on one context must be issued on one stream at a time
+ *    returns; independent branches inside a call run on three helper streams owned by
+ *    the context (default priority; revffn_set_helper_streams(ctx, 0) or the environment
+ *    variable REVFFN_NO_STREAMS=1 at creation keep everything on `hip_stream`).  Calls on one context must be issued on one stream at a time
  *    (they share the context workspace).
  *  - Return value: 0 on success, a negative REVFFN_E* code otherwise.  No call
  *    throws or aborts.  On error nothing has been enqueued.
@@ -194,6 +194,10 @@ int revffn_get_branch(revffn_ctx *ctx, int32_t which, float *dst, void *hip_stre
 /* Select kernels: 0 = automatic (MFMA kernels where the shape allows),
  * 1 = force the generic kernels (any shape, slow).  For tests. */
 int revffn_set_kernel_mode(revffn_ctx *ctx, int32_t mode);
+
+/* Helper streams on (default) or off for the following calls.  Off: every kernel of a call runs on
+ * `hip_stream` in program order (same results bit for bit; used to time kernels one at a time). */
+int revffn_set_helper_streams(revffn_ctx *ctx, int32_t on);
 
 /* Kernel-level entry points for unit tests and micro-benchmarks of the two dense kernels
  * (they need no context).  dtype as in revffn_config; kernel_mode as in

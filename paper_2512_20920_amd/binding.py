@@ -9,7 +9,7 @@ EXPORTED_SYMBOLS = (
     "revffn_workspace_bytes", "revffn_create", "revffn_destroy", "revffn_set_inv_iters",
     "revffn_forward", "revffn_inverse", "revffn_backward", "revffn_inverse_backward", "revffn_stack_forward",
     "revffn_stack_backward", "revffn_get_routing", "revffn_enable_taps", "revffn_get_branch",
-    "revffn_set_kernel_mode", "revffn_strerror", "revffn_profile_enable", "revffn_profile_read",
+    "revffn_set_kernel_mode", "revffn_set_helper_streams", "revffn_strerror", "revffn_profile_enable", "revffn_profile_read",
     "revffn_profile_kernel_name", "revffn_op_gemm", "revffn_op_attention_fwd", "revffn_op_attention_bwd",
 )
 
@@ -62,6 +62,7 @@ def load_library():
     lib.revffn_set_inv_iters.argtypes = [vp, i32]
     lib.revffn_enable_taps.argtypes = [vp, i32]
     lib.revffn_set_kernel_mode.argtypes = [vp, i32]
+    lib.revffn_set_helper_streams.argtypes = [vp, i32]
     lib.revffn_forward.argtypes = [vp, ctypes.POINTER(Weights), vp, vp, vp, vp, i32, i32, i64, vp]
     lib.revffn_inverse.argtypes = [vp, ctypes.POINTER(Weights), vp, vp, vp, vp, i32, i32, i64, vp, vp]
     lib.revffn_backward.argtypes = [vp, ctypes.POINTER(Weights), vp, vp, vp, vp, vp, vp, vp,
@@ -159,6 +160,9 @@ class Context:
 
     def set_kernel_mode(self, mode):
         _check(self.lib.revffn_set_kernel_mode(self.handle, mode))
+
+    def set_helper_streams(self, on=True):
+        _check(self.lib.revffn_set_helper_streams(self.handle, 1 if on else 0))
 
     def profile_enable(self, on=True):
         _check(self.lib.revffn_profile_enable(self.handle, 1 if on else 0))

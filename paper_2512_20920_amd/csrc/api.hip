@@ -56,7 +56,7 @@ struct revffn_ctx {
   void *n3, *Um;
   float *wrp, *probs, *gamma, *wts;
   int *idx, *counts, *offsets, *row_map, *inv_map;
-  int *tg_a, *tm_a, *tg_b, *tm_b;
+  int *tg_a, *tm_a, *tg_b, *tm_b, *tf_a, *tf_b;
   int max_tiles_a, max_tiles_b;
   int* tile_cnt;              // tiles in use of the two lists
   void *Xg, *GU, *Hh, *Yp, *GUs, *Hs, *Ys, *RS;
@@ -131,6 +131,8 @@ size_t carve(revffn_ctx* c, char* base) {
   c->tg_b = (int*)cv.take(c->max_tiles_b * 4);
   c->tm_b = (int*)cv.take(c->max_tiles_b * 4);
   c->tile_cnt = (int*)cv.take(2 * 4);
+  c->tf_a = (int*)cv.take(c->max_tiles_a * 4);
+  c->tf_b = (int*)cv.take(c->max_tiles_b * 4);
   c->Xg = cv.take(N * d * es);
   c->GU = cv.take(N * 2 * I * es);
   c->Hh = cv.take(N * I * es);
@@ -250,6 +252,7 @@ int run_gemm(revffn_ctx* c, GemmArgs g, int ta, int tb, int tc, hipStream_t s) {
     if (g.group_mode == 1) {
       // 128-row tiles; a 256-row tile (8 waves, each weight tile read once per expert) measured 2-3 % slower
       g.tile_group = c->tg_b; g.tile_m0 = c->tm_b; g.max_tiles = c->max_tiles_b; g.tile_bm = BM_B; g.tile_count = c->tile_cnt + 1;
+      if (c->max_tiles_b < 32768) g.tile_first = c->tf_b;      // (the packed entry holds 15 + 16 bits)
     }
     if (launch_gemm_mfma(g, t, s) == 0) {
       ps.done(g.a_trans ? KID_GEMM_TN : (g.b_trans ? KID_GEMM_NN : KID_GEMM_NT));
@@ -373,7 +376,7 @@ int moe_acts(revffn_ctx* c, const revffn_weights* w, const void* y1, i64 ld, int
   }
   launch_router(dt, y1, ld, c->splitk_ws_r, SPLIT_LOGITS, w->b_router, c->probs, c->idx, c->wts, c->gamma, T, h, E, k,
                 Is ? 1 : 0, f.norm_topk_prob, f.rms_eps, sr);
-  TileLists tl{{c->tg_a, c->tg_b}, {c->tm_a, c->tm_b}, {c->max_tiles_a, c->max_tiles_b}, {BM_A, BM_B}, c->tile_cnt};
+  TileLists tl{{c->tg_a, c->tg_b}, {c->tm_a, c->tm_b}, {c->tf_a, c->tf_b}, {c->max_tiles_a, c->max_tiles_b}, {BM_A, BM_B}, c->tile_cnt};
   launch_permute(c->idx, T, k, E, c->counts, c->offsets, c->row_map, c->inv_map, tl, sr);
   launch_rmsnorm_fwd(dt, y1, ld, w->norm_m, c->n3, h, T, h, f.rms_eps, s);
   TRY(run_gemm(c, nt(c->n3, h, w->pup_m, h, c->Um, d, T, d, h), s));
@@ -765,6 +768,12 @@ int revffn_set_kernel_mode(revffn_ctx* c, int32_t mode) {
   if (!c) return REVFFN_ENULL;
   if (mode != 0 && mode != 1) return REVFFN_EINVAL;
   c->mode = mode;
+  return 0;
+}
+
+int revffn_set_helper_streams(revffn_ctx* c, int32_t on) {
+  if (!c) return REVFFN_ENULL;
+  c->use_streams = on != 0;
   return 0;
 }
 

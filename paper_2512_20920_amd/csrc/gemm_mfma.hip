@@ -129,7 +129,7 @@ __device__ __forceinline__ bf16x8 load_frag(const bf16* lds, int r0, int kk, int
 // PD = number of k-tiles kept in flight in registers ahead of the one being multiplied
 #define PD 3
 template <int BM, int BN, int BK, int WGM, bool AT, bool BT, class TC, bool RB, int NW>
-__global__ void __launch_bounds__(NW * 64) gemm_mfma_k(GemmArgs g) {
+__global__ void __launch_bounds__(NW * 64, BK == 32 ? 3 : 1) gemm_mfma_k(GemmArgs g) {
   constexpr int NT = NW * 64;                       // threads per workgroup
   typedef Tile<AT, BM, BK, NT> TA_;
   typedef Tile<BT, BN, BK, NT> TB_;
@@ -157,6 +157,13 @@ __global__ void __launch_bounds__(NW * 64) gemm_mfma_k(GemmArgs g) {
       if (loc >= q + (c < r ? 1 : 0)) return;
       const int nl = c * q + min(c, r) + loc;
       by = nl / g.tiles_n; bx = nl - by * g.tiles_n;
+      if (g.tile_first) {
+        // inside one expert the m-tiles are the fastest index, so that the workgroups that read the same
+        // weight tile run next to each other and the second read is served by the L2
+        const int pk = g.tile_first[by], f = pk >> 16, cnt = pk & 0xffff;
+        const int local = nl - f * g.tiles_n;
+        bx = local / cnt; by = f + (local - bx * cnt);
+      }
     } else if (g.group_mode == 2) {
       const int per = g.tiles_n * g.tiles_m;
       const int round = loc / per, t = loc - round * per;

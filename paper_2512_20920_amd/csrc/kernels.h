@@ -38,6 +38,7 @@ struct GemmArgs {
   const void* col_scale = nullptr;
   // group_mode 1: number of m-tiles of the list actually in use (device scalar written by the permutation kernel)
   const int* tile_count = nullptr;
+  const int* tile_first = nullptr;       // per tile: (first tile of its expert) << 16 | tiles of that expert
   // set by the MFMA launcher: XCD-aware placement of the tiles (0 = plain 2-D grid), tile counts of the problem
   int xcd_m = 0, tiles_m = 0, tiles_n = 0;
 };
@@ -83,8 +84,9 @@ void launch_router(int dt, const void* y1, i64 ld, const float* zparts, int n_pa
                    float* probs, int* idx, float* wts, float* gamma, int T, int h, int E, int k, int has_gate,
                    int norm_topk, float eps, hipStream_t s);
 // m-tile lists of the grouped GEMMs for two tile heights: list i covers every expert's rows with
-// tiles of bm[i] rows (group[i][t] = expert or -1 for an unused slot, m0[i][t] = first row, count[i] = tiles in use)
-struct TileLists { int* group[2]; int* m0[2]; int max_tiles[2]; int bm[2]; int* count; };
+// tiles of bm[i] rows (group[i][t] = expert or -1 for an unused slot, m0[i][t] = first row, first[i][t] = packed
+// (first tile of t's expert) * 65536 + (tiles of that expert), count[i] = tiles in use)
+struct TileLists { int* group[2]; int* m0[2]; int* first[2]; int max_tiles[2]; int bm[2]; int* count; };
 // counts/offsets/row_map/inv_map and the tile lists
 void launch_permute(const int* idx, int T, int k, int E, int* counts, int* offsets, int* row_map, int* inv_map,
                     const TileLists& tl, hipStream_t s);

@@ -149,16 +149,18 @@ __global__ void __launch_bounds__(PERM_WAVES * 64) permute_k(
     const int bm = tl.bm[pass], mx = tl.max_tiles[pass];
     int* tg = tl.group[pass];
     int* tm = tl.m0[pass];
+    int* tf = tl.first[pass];
     int total = 0;
     for (int e = 0; e < E; e++) total += (off[e + 1] - off[e] + bm - 1) / bm;
     for (int e = threadIdx.x; e < E; e += blockDim.x) {
       int first = 0;
       for (int q = 0; q < e; q++) first += (off[q + 1] - off[q] + bm - 1) / bm;
       int i = first;
+      const int mine = (off[e + 1] - off[e] + bm - 1) / bm;
       for (int m = off[e]; m < off[e + 1]; m += bm, i++)
-        if (i < mx) { tg[i] = e; tm[i] = m; }
+        if (i < mx) { tg[i] = e; tm[i] = m; tf[i] = (first << 16) | mine; }
     }
-    for (int i = total + threadIdx.x; i < mx; i += blockDim.x) { tg[i] = -1; tm[i] = 0; }
+    for (int i = total + threadIdx.x; i < mx; i += blockDim.x) { tg[i] = -1; tm[i] = 0; tf[i] = (i << 16) | 1; }
     if (threadIdx.x == 0) tl.count[pass] = min(total, mx);
   }
   __syncthreads();
