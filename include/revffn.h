@@ -219,6 +219,19 @@ int revffn_op_attention_bwd(int32_t dtype, int32_t kernel_mode, const void *q, c
                             float *dvec, void *dq, void *dk, void *dv, int32_t B, int32_t S,
                             int32_t H, int32_t dh, int32_t causal, void *hip_stream);
 
+/* Host-only check hook (no GPU work): where the MFMA GEMM's XCD-aware launch places its workgroups.
+ * Workgroups reach the 8 XCDs round-robin by linear id; the kernel maps workgroup `i` back to a tile so that
+ * each XCD works on tiles that share operands.  This call runs the same index function on the host for every
+ * workgroup of the grid the launcher would use and writes (n-tile, m-tile, group) to out[3*i..3*i+2], or
+ * (-1,-1,-1) for a workgroup that exits without a tile.  group_mode 0: dense problem of tiles_m x tiles_n tiles
+ * of bm x bn elements; 1: expert tile list with room for tiles_m entries of which n_used are in use,
+ * tile_first[t] (host pointer, n_used entries, may be NULL) = (first tile of t's expert) << 16 | tiles of that
+ * expert; 2: per-expert weight gradients, n_groups experts of tiles_m x tiles_n tiles each.  Returns the
+ * number of workgroups in the grid, or REVFFN_EINVAL (bad arguments, or more workgroups than max_wg). */
+int revffn_op_tile_placement(int32_t group_mode, int32_t tiles_m, int32_t tiles_n, int32_t bm, int32_t bn,
+                             int32_t n_groups, const int32_t *tile_first, int32_t n_used, int32_t *out,
+                             int32_t max_wg);
+
 /* Per-kernel timing for measurement (off by default).  While enabled, every GEMM and
  * attention launch of this context is bracketed by two HIP events recorded on the launch
  * stream, together with its algorithmic work: GEMM 2*M*N*K flops and each operand and the

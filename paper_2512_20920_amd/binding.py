@@ -11,6 +11,7 @@ EXPORTED_SYMBOLS = (
     "revffn_stack_backward", "revffn_get_routing", "revffn_enable_taps", "revffn_get_branch",
     "revffn_set_kernel_mode", "revffn_set_helper_streams", "revffn_strerror", "revffn_profile_enable", "revffn_profile_read",
     "revffn_profile_kernel_name", "revffn_op_gemm", "revffn_op_attention_fwd", "revffn_op_attention_bwd",
+    "revffn_op_tile_placement",
 )
 
 WEIGHT_FIELDS = (
@@ -76,6 +77,7 @@ def load_library():
     lib.revffn_get_branch.argtypes = [vp, i32, vp, vp]
     lib.revffn_op_gemm.argtypes = [i32, i32, vp, vp, vp, i32, i32, i32, i64, i64, i64, i32, i32, i32, vp]
     lib.revffn_op_attention_fwd.argtypes = [i32, i32, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp]
+    lib.revffn_op_tile_placement.argtypes = [i32, i32, i32, i32, i32, i32, vp, i32, vp, i32]
     lib.revffn_op_attention_bwd.argtypes = [i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                                             i32, i32, i32, i32, i32, vp]
     lib.revffn_profile_enable.argtypes = [vp, i32]
@@ -247,6 +249,23 @@ def revffn_get_branch(ctx, which, dst, stream=None):
 def revffn_op_gemm(dtype, kernel_mode, a, b, c, M, N, K, lda, ldb, ldc, a_trans, b_trans, out_f32=False, stream=None):
     _check(load_library().revffn_op_gemm(dtype, kernel_mode, _ptr(a), _ptr(b), _ptr(c), M, N, K, lda, ldb, ldc,
                                          int(a_trans), int(b_trans), int(out_f32), _stream(stream)))
+
+
+def revffn_op_tile_placement(group_mode, tiles_m, tiles_n, bm, bn, n_groups=1, tile_first=None, n_used=0):
+    """Host-only: (n-tile, m-tile, group) of every workgroup of the launch, -1s for workgroups without a tile.
+    Returns an int32 numpy array [workgroups, 3]."""
+    import numpy as np
+    cap = 8 * (tiles_m + 8) * (tiles_n + 8) * (n_groups + 8 if group_mode == 2 else 1)
+    out = np.empty((cap, 3), dtype=np.int32)
+    tf = None
+    if tile_first is not None:
+        tf = np.ascontiguousarray(tile_first, dtype=np.int32)
+    n = load_library().revffn_op_tile_placement(group_mode, tiles_m, tiles_n, bm, bn, n_groups,
+                                                tf.ctypes.data if tf is not None else None, n_used,
+                                                out.ctypes.data, cap)
+    if n < 0:
+        _check(n)
+    return out[:n].copy()
 
 
 def revffn_op_attention_fwd(dtype, kernel_mode, q, k, v, o, lse, B, S, H, dh, causal, stream=None):

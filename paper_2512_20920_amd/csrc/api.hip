@@ -771,6 +771,26 @@ int revffn_set_kernel_mode(revffn_ctx* c, int32_t mode) {
   return 0;
 }
 
+int revffn_op_tile_placement(int32_t group_mode, int32_t tiles_m, int32_t tiles_n, int32_t bm, int32_t bn,
+                             int32_t n_groups, const int32_t* tile_first, int32_t n_used, int32_t* out,
+                             int32_t max_wg) {
+  if (group_mode < 0 || group_mode > 2 || tiles_m < 1 || tiles_n < 1 || bm < 1 || bn < 1 || !out) return REVFFN_EINVAL;
+  if (group_mode == 1 && (n_used < 0 || n_used > tiles_m)) return REVFFN_EINVAL;
+  if (group_mode == 2 && n_groups < 1) return REVFFN_EINVAL;
+  int xcd_m = 1;
+  long long grid;
+  if (group_mode == 0) { xcd_m = pick_xcd_m(tiles_m, tiles_n, bm, bn); grid = dense_grid_x(xcd_m, tiles_m, tiles_n); }
+  else if (group_mode == 1) grid = (long long)tiles_n * tiles_m;
+  else grid = 8LL * ((n_groups + 7) / 8) * tiles_n * tiles_m;
+  if (grid > max_wg) return REVFFN_EINVAL;
+  for (int i = 0; i < (int)grid; i++) {
+    int bx = -1, by = -1, bz = 0;
+    if (!place_tile(group_mode, xcd_m, tiles_m, tiles_n, n_groups, n_used, tile_first, i, &bx, &by, &bz)) bx = by = bz = -1;
+    out[3 * i] = bx; out[3 * i + 1] = by; out[3 * i + 2] = bz;
+  }
+  return (int)grid;
+}
+
 int revffn_set_helper_streams(revffn_ctx* c, int32_t on) {
   if (!c) return REVFFN_ENULL;
   c->use_streams = on != 0;

@@ -143,46 +143,11 @@ __global__ void __launch_bounds__(NW * 64, BK == 32 ? 3 : 1) gemm_mfma_k(GemmArg
   const bf16* A = (const bf16*)g.A;
   const bf16* Bm = (const bf16*)g.B;
   TC* C = (TC*)g.C;
-  // ---- which tile this workgroup computes.  Workgroups go to the 8 XCDs round-robin by linear id and every
-  // XCD has an L2 of its own, so with xcd_m != 0 (1-D grid) XCD c = id & 7 gets tiles that share operands:
-  // a consecutive run of the expert tile list, whole experts of a per-expert weight gradient, or one
-  // rectangle of an xcd_m x (8 / xcd_m) split of a dense problem's tiles.
-  int bx, by, bz = blockIdx.z;
-  if (g.xcd_m == 0) { bx = blockIdx.x; by = blockIdx.y; }
-  else {
-    const int c = blockIdx.x & 7, loc = blockIdx.x >> 3;
-    if (g.group_mode == 1) {
-      const int total = g.tiles_n * g.tile_count[0];
-      const int q = total >> 3, r = total & 7;
-      if (loc >= q + (c < r ? 1 : 0)) return;
-      const int nl = c * q + min(c, r) + loc;
-      by = nl / g.tiles_n; bx = nl - by * g.tiles_n;
-      if (g.tile_first) {
-        // inside one expert the m-tiles are the fastest index, so that the workgroups that read the same
-        // weight tile run next to each other and the second read is served by the L2
-        const int pk = g.tile_first[by], f = pk >> 16, cnt = pk & 0xffff;
-        const int local = nl - f * g.tiles_n;
-        bx = local / cnt; by = f + (local - bx * cnt);
-      }
-    } else if (g.group_mode == 2) {
-      const int per = g.tiles_n * g.tiles_m;
-      const int round = loc / per, t = loc - round * per;
-      bz = round * 8 + c;
-      if (bz >= g.n_groups) return;
-      by = t / g.tiles_n; bx = t - by * g.tiles_n;
-    } else {
-      const int xm = g.xcd_m, xn = 8 / xm;
-      const int sm = (g.tiles_m + xm - 1) / xm, sn = (g.tiles_n + xn - 1) / xn;
-      const int cm = c / xn, cn = c - cm * xn;
-      // inside the rectangle: bands of 8 m-tiles, m fastest inside a band, so that the ~64 workgroups an XCD
-      // runs together form an 8 x 8 block of tiles
-      const int band = loc / (8 * sn), r = loc - band * 8 * sn;
-      const int bh = min(8, sm - band * 8);
-      const int ln = r / bh, lm = band * 8 + (r - ln * bh);
-      by = cm * sm + lm; bx = cn * sn + ln;
-      if (by >= g.tiles_m || bx >= g.tiles_n) return;
-    }
-  }
+  // ---- which tile this workgroup computes (plain 2-D grid, or the XCD-aware placement of a 1-D grid)
+  int bx = blockIdx.x, by = blockIdx.y, bz = blockIdx.z;
+  if (g.xcd_m != 0 && !place_tile(g.group_mode, g.xcd_m, g.tiles_m, g.tiles_n, g.n_groups,
+                                  g.group_mode == 1 ? g.tile_count[0] : 0, g.tile_first, (int)blockIdx.x, &bx, &by, &bz))
+    return;
   int m0, m_end, k0 = 0, k_end = g.K;
   if (g.group_mode == 1) {
     int ti = by;
@@ -365,13 +330,8 @@ static void go(const GemmArgs& g0, hipStream_t s) {
       // under a skewed routing, equal under a balanced one), so only on request (REVFFN_XCD=2)
       if (xcd_enabled() == 2) { g.xcd_m = 1; grid = dim3(8 * cdiv(g.n_groups, 8) * g.tiles_n * g.tiles_m, 1, 1); }
     } else if ((i64)g.tiles_n * g.tiles_m >= 64) {
-      // the split of the tiles over the XCDs that touches the fewest operand rows per XCD
-      i64 best = -1;
-      for (int xm = 1; xm <= 8; xm *= 2) {
-        i64 cost = (i64)cdiv(g.tiles_m, xm) * BM + (i64)cdiv(g.tiles_n, 8 / xm) * BN;
-        if (best < 0 || cost < best) { best = cost; g.xcd_m = xm; }
-      }
-      grid = dim3(8 * cdiv(g.tiles_m, g.xcd_m) * cdiv(g.tiles_n, 8 / g.xcd_m), 1, zdim);
+      g.xcd_m = pick_xcd_m(g.tiles_m, g.tiles_n, BM, BN);
+      grid = dim3(dense_grid_x(g.xcd_m, g.tiles_m, g.tiles_n), 1, zdim);
     }
   }
   size_t smem = (size_t)2 * (Tile<AT, BM, BK, NW * 64>::elems + Tile<BT, BN, BK, NW * 64>::elems) * sizeof(bf16);

@@ -43,6 +43,63 @@ struct GemmArgs {
   int xcd_m = 0, tiles_m = 0, tiles_n = 0;
 };
 
+// ---- XCD-aware tile placement of the MFMA GEMM (1-D grid of `grid_x` workgroups) ------------------------
+// Workgroups go to the 8 XCDs round-robin by linear id and every XCD has an L2 of its own, so workgroup `bid`
+// (XCD bid & 7) is handed a tile that shares operands with the other tiles of its XCD:
+//   dense (group_mode 0): one rectangle of an xcd_m x (8 / xcd_m) split of the tile grid, walked in bands of
+//     8 m-tiles with m fastest, so that the ~64 workgroups an XCD runs together form an 8 x 8 block of tiles;
+//   expert tiles (group_mode 1): a consecutive run of the (n-tile, m-tile) pairs of the tile list in use
+//     (n_used entries); inside one expert the m-tiles are the fastest index (tile_first[t] = first tile of t's
+//     expert << 16 | tiles of that expert), so the workgroups that read one weight tile run next to each other;
+//   per-expert weight gradients (group_mode 2): whole experts per XCD, bz = the expert.
+// Returns false for a workgroup that has no tile (it exits at once).  Host and device share this code so that
+// the index arithmetic can be checked on the host.
+__host__ __device__ inline bool place_tile(int group_mode, int xcd_m, int tiles_m, int tiles_n, int n_groups,
+                                           int n_used, const int* tile_first, int bid, int* bx, int* by, int* bz) {
+  const int c = bid & 7, loc = bid >> 3;
+  if (group_mode == 1) {
+    const int total = tiles_n * n_used;
+    const int q = total >> 3, r = total & 7;
+    if (loc >= q + (c < r ? 1 : 0)) return false;
+    const int nl = c * q + (c < r ? c : r) + loc;
+    *by = nl / tiles_n; *bx = nl - *by * tiles_n;
+    if (tile_first) {
+      const int pk = tile_first[*by], f = pk >> 16, cnt = pk & 0xffff;
+      const int local = nl - f * tiles_n;
+      *bx = local / cnt; *by = f + (local - *bx * cnt);
+    }
+    return true;
+  }
+  if (group_mode == 2) {
+    const int per = tiles_n * tiles_m;
+    const int round = loc / per, t = loc - round * per;
+    *bz = round * 8 + c;
+    if (*bz >= n_groups) return false;
+    *by = t / tiles_n; *bx = t - *by * tiles_n;
+    return true;
+  }
+  const int xm = xcd_m, xn = 8 / xm;
+  const int sm = (tiles_m + xm - 1) / xm, sn = (tiles_n + xn - 1) / xn;
+  const int cm = c / xn, cn = c - cm * xn;
+  const int band = loc / (8 * sn), r = loc - band * 8 * sn;
+  const int bh = sm - band * 8 < 8 ? sm - band * 8 : 8;
+  const int ln = r / bh, lm = band * 8 + (r - ln * bh);
+  *by = cm * sm + lm; *bx = cn * sn + ln;
+  return *by < tiles_m && *bx < tiles_n;
+}
+// the split of a dense problem's tiles over the XCDs that touches the fewest operand rows per XCD, and its grid
+inline int pick_xcd_m(int tiles_m, int tiles_n, int bm, int bn) {
+  long long best = -1; int pick = 1;
+  for (int xm = 1; xm <= 8; xm *= 2) {
+    long long cost = (long long)((tiles_m + xm - 1) / xm) * bm + (long long)((tiles_n + 8 / xm - 1) / (8 / xm)) * bn;
+    if (best < 0 || cost < best) { best = cost; pick = xm; }
+  }
+  return pick;
+}
+inline int dense_grid_x(int xcd_m, int tiles_m, int tiles_n) {
+  return 8 * ((tiles_m + xcd_m - 1) / xcd_m) * ((tiles_n + 8 / xcd_m - 1) / (8 / xcd_m));
+}
+
 // element types of A, B, C: 0 = f32, 1 = bf16.  bias and resid have C's... no: the
 // storage dtype `dt` of the call (bias/resid are streams or weights).
 struct GemmTypes { int ta, tb, tc, tside; };

@@ -86,3 +86,48 @@ def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(bnd, "_HERE", str(tmp_path))
     with pytest.raises(R.RevffnError):
         bnd.load_library()
+
+
+def test_tile_placement_covers_every_tile_once():
+    """The XCD-aware workgroup -> tile map of the MFMA GEMM (the same index function the kernel runs, evaluated on
+    the host by the library) is a bijection onto the tiles: no tile twice, none missing, no tile out of range."""
+    import numpy as np
+    R = pytest.importorskip("paper_2512_20920_amd")
+    rng = np.random.default_rng(0)
+    # dense problems, including tile grids that the 2-D split over 8 XCDs does not divide evenly
+    for tiles_m, tiles_n in [(8, 8), (16, 32), (9, 21), (17, 5), (1, 64), (64, 1), (3, 88), (33, 7), (16, 176)]:
+        for bm, bn in [(128, 128), (128, 64)]:
+            wg = R.revffn_op_tile_placement(0, tiles_m, tiles_n, bm, bn)
+            live = wg[wg[:, 0] >= 0]
+            assert len(live) == tiles_m * tiles_n and len(wg) % 8 == 0
+            assert live[:, 0].max() < tiles_n and live[:, 1].max() < tiles_m
+            assert len({(int(x), int(y)) for x, y, _ in live}) == tiles_m * tiles_n
+    # expert tile lists: random tiles per expert (some experts empty), unused slots after the last tile
+    for _ in range(40):
+        tiles_n = int(rng.integers(1, 30))
+        per_expert = rng.integers(0, 5, size=int(rng.integers(1, 24)))
+        first = np.concatenate([[0], np.cumsum(per_expert)])
+        tf = np.concatenate([np.full(c, (f << 16) | c, dtype=np.int32) for f, c in zip(first[:-1], per_expert)]
+                            + [np.zeros(0, np.int32)])
+        n_used = int(per_expert.sum())
+        for use_first in (True, False):
+            wg = R.revffn_op_tile_placement(1, n_used + 7, tiles_n, 128, 128, 1, tf if use_first else None, n_used)
+            live = wg[wg[:, 0] >= 0]
+            assert len(live) == tiles_n * n_used
+            if n_used:
+                assert live[:, 0].max() < tiles_n and live[:, 1].max() < n_used
+            assert len({(int(x), int(y)) for x, y, _ in live}) == tiles_n * n_used
+            if use_first and n_used:
+                # the m-tiles of one expert and one n-tile are consecutive workgroups of one XCD
+                order = {(int(x), int(y)): i for i, (x, y, _) in enumerate(wg) if x >= 0}
+                for f, c in zip(first[:-1], per_expert):
+                    for j in range(1, int(c)):
+                        a, b = order[(0, int(f) + j - 1)], order[(0, int(f) + j)]
+                        assert (a & 7) != (b & 7) or b - a == 8
+    # per-expert weight gradients: every (expert, tile) once, whole experts per XCD
+    wg = R.revffn_op_tile_placement(2, 3, 5, 128, 128, n_groups=13)
+    live = wg[wg[:, 0] >= 0]
+    assert len(live) == 13 * 15 and len({tuple(map(int, r)) for r in live}) == 13 * 15
+    xcd = np.arange(len(wg)) & 7
+    for e in range(13):
+        assert len(set(xcd[(wg[:, 2] == e)])) == 1

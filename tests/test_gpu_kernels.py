@@ -21,7 +21,10 @@ def _bf(rng, shape, scale=1.0):
 
 
 @pytest.mark.parametrize("layout", ["nt", "nn", "tn"])
-@pytest.mark.parametrize("M,N,K", [(128, 128, 64), (200, 328, 136), (1, 64, 520), (300, 8, 72), (257, 129 * 8, 24)])
+@pytest.mark.parametrize("M,N,K", [(128, 128, 64), (200, 328, 136), (1, 64, 520), (300, 8, 72), (257, 129 * 8, 24),
+                                   # 64 tiles or more: the XCD-aware tile placement, with ragged last tiles and
+                                   # rectangles that do not divide the tile grid evenly
+                                   (1100, 1304, 72), (2056, 520, 40), (392, 4104, 24)])
 def test_mfma_gemm_layouts(layout, M, N, K):
     if layout == "tn":
         M = (M + 7) // 8 * 8
