@@ -56,9 +56,10 @@ struct revffn_ctx {
   void *n3, *Um;
   float *wrp, *probs, *gamma, *wts;
   int *idx, *counts, *offsets, *row_map, *inv_map;
-  int *tg_a, *tm_a, *tg_b, *tm_b, *tf_a, *tf_b;
-  int max_tiles_a, max_tiles_b;
-  int* tile_cnt;              // tiles in use of the two lists
+  int *tg_a, *tm_a, *tg_b, *tm_b, *tf_a, *tf_b, *tg_c, *tm_c, *tf_c;
+  int max_tiles_a, max_tiles_b, max_tiles_c;
+  int expert_tile = 0;        // m-tile height of the MFMA expert GEMMs forced to 128 or 256 (REVFFN_EXPERT_TILE), 0 = by rows per expert
+  int* tile_cnt;              // tiles in use of the three lists
   void *Xg, *GU, *Hh, *Yp, *GUs, *Hs, *Ys, *RS;
   float *tapA, *tapM;
   void *y1c, *xtmp;
@@ -79,7 +80,8 @@ struct revffn_ctx {
 namespace {
 
 const int BM_A = 64;    // m-tile height of the generic grouped GEMM
-const int BM_B = 128;   // m-tile height of the MFMA grouped GEMM
+const int BM_B = 128;   // m-tile heights of the MFMA grouped GEMM
+const int BM_C = 256;
 // k-slices of the small fp32 GEMMs around the router (each would otherwise run on a handful of CUs)
 const int SPLIT_FOLD = 16, SPLIT_LOGITS = 8, SPLIT_DWR = 32;
 
@@ -130,7 +132,11 @@ size_t carve(revffn_ctx* c, char* base) {
   c->tm_a = (int*)cv.take(c->max_tiles_a * 4);
   c->tg_b = (int*)cv.take(c->max_tiles_b * 4);
   c->tm_b = (int*)cv.take(c->max_tiles_b * 4);
-  c->tile_cnt = (int*)cv.take(2 * 4);
+  c->max_tiles_c = (int)(N / BM_C + E + 1);
+  c->tg_c = (int*)cv.take(c->max_tiles_c * 4);
+  c->tm_c = (int*)cv.take(c->max_tiles_c * 4);
+  c->tf_c = (int*)cv.take(c->max_tiles_c * 4);
+  c->tile_cnt = (int*)cv.take(3 * 4);
   c->tf_a = (int*)cv.take(c->max_tiles_a * 4);
   c->tf_b = (int*)cv.take(c->max_tiles_b * 4);
   c->Xg = cv.take(N * d * es);
@@ -250,9 +256,16 @@ int run_gemm(revffn_ctx* c, GemmArgs g, int ta, int tb, int tc, hipStream_t s) {
   ProfScope ps(c, s, fl, by);
   if (c->dt == 1 && c->mode == 0 && ta == 1 && tb == 1) {
     if (g.group_mode == 1) {
-      // 128-row tiles; a 256-row tile (8 waves, each weight tile read once per expert) measured 2-3 % slower
-      g.tile_group = c->tg_b; g.tile_m0 = c->tm_b; g.max_tiles = c->max_tiles_b; g.tile_bm = BM_B; g.tile_count = c->tile_cnt + 1;
-      if (c->max_tiles_b < 32768) g.tile_first = c->tf_b;      // (the packed entry holds 15 + 16 bits)
+      // experts with more than ~96 rows on average: one 256-row tile (8 waves) streams each weight tile once where two
+      // 128-row tiles stream it twice (rows past the expert's end cost no traffic); measured 2-3 % of a step
+      const bool tall = c->expert_tile ? c->expert_tile == 256 : (i64)c->lastT_rows > (i64)96 * c->cfg.n_experts;
+      if (tall) {
+        g.tile_group = c->tg_c; g.tile_m0 = c->tm_c; g.max_tiles = c->max_tiles_c; g.tile_bm = BM_C; g.tile_count = c->tile_cnt + 2;
+        if (c->max_tiles_c < 32768) g.tile_first = c->tf_c;      // (the packed entry holds 15 + 16 bits)
+      } else {
+        g.tile_group = c->tg_b; g.tile_m0 = c->tm_b; g.max_tiles = c->max_tiles_b; g.tile_bm = BM_B; g.tile_count = c->tile_cnt + 1;
+        if (c->max_tiles_b < 32768) g.tile_first = c->tf_b;
+      }
     }
     if (launch_gemm_mfma(g, t, s) == 0) {
       ps.done(g.a_trans ? KID_GEMM_TN : (g.b_trans ? KID_GEMM_NN : KID_GEMM_NT));
@@ -376,7 +389,8 @@ int moe_acts(revffn_ctx* c, const revffn_weights* w, const void* y1, i64 ld, int
   }
   launch_router(dt, y1, ld, c->splitk_ws_r, SPLIT_LOGITS, w->b_router, c->probs, c->idx, c->wts, c->gamma, T, h, E, k,
                 Is ? 1 : 0, f.norm_topk_prob, f.rms_eps, sr);
-  TileLists tl{{c->tg_a, c->tg_b}, {c->tm_a, c->tm_b}, {c->tf_a, c->tf_b}, {c->max_tiles_a, c->max_tiles_b}, {BM_A, BM_B}, c->tile_cnt};
+  TileLists tl{{c->tg_a, c->tg_b, c->tg_c}, {c->tm_a, c->tm_b, c->tm_c}, {c->tf_a, c->tf_b, c->tf_c},
+               {c->max_tiles_a, c->max_tiles_b, c->max_tiles_c}, {BM_A, BM_B, BM_C}, c->tile_cnt};
   launch_permute(c->idx, T, k, E, c->counts, c->offsets, c->row_map, c->inv_map, tl, sr);
   launch_rmsnorm_fwd(dt, y1, ld, w->norm_m, c->n3, h, T, h, f.rms_eps, s);
   TRY(run_gemm(c, nt(c->n3, h, w->pup_m, h, c->Um, d, T, d, h), s));
@@ -672,6 +686,7 @@ int revffn_create(revffn_ctx** out, const revffn_config* cfg, int32_t max_B, int
   carve(c, (char*)c->slab);
   (void)hipMemset(c->wr_ext, 0, (size_t)((c->cfg.n_experts + (c->cfg.d_shared ? 1 : 0) + 7) / 8 * 8) * c->cfg.d_model * c->es);
   c->use_streams = getenv("REVFFN_NO_STREAMS") == nullptr;
+  { const char* e = getenv("REVFFN_EXPERT_TILE"); if (e && (atoi(e) == 256 || atoi(e) == 128)) c->expert_tile = atoi(e); }
   c->sync_ev = new (std::nothrow) std::vector<hipEvent_t>();
   bool ok = c->sync_ev != nullptr;
   for (int i = 0; ok && i < 3; i++) ok = hipStreamCreateWithFlags(&c->side[i], hipStreamNonBlocking) == hipSuccess;

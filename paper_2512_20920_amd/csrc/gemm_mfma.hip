@@ -2,14 +2,24 @@
 // every dense contraction of the block: adapters, Q/K/V/O projections, shared expert,
 // grouped routed experts (forward, data gradient, weight gradient).
 //
-// Workgroup = 256 threads = 4 waves (2x2); workgroup tile BM x BN, k-step 64, two LDS
-// stages.  Operand tiles are staged global -> registers -> LDS while the previous stage
-// is multiplied.  An operand whose contraction index is contiguous in memory is read from
-// LDS with 16-byte reads; an operand whose contraction index is the slow one (the
-// "transposed" layouts of the data- and weight-gradient GEMMs) is kept as stored and read
-// with the transposing LDS read ds_read_b64_tr_b16, whose lane mapping is: inside each
-// block of 16 lanes, lane j receives element (j & 3) of the 8-byte words addressed by
-// lanes 4*e + (j >> 2), e = 0..3.
+// Workgroup = NW waves laid out WGM x (NW / WGM) over a BM x BN tile, k-step 64 (128 bytes per
+// row), NS LDS stages.  Operand tiles go from global memory straight into LDS
+// (buffer_load_dwordx4 ... lds: lane l of a wave-load lands at M0 + 16*l), NS-1 k-tiles ahead of
+// the one being multiplied, and the loads of the next tile are issued between the MFMA groups of
+// the current one, so that the load path and the matrix pipe run together instead of in turns.
+// There is no register staging and no LDS store instruction.
+//
+// Because a wave-load fills 1 KiB of LDS in lane order, bank-conflict-free fragment reads cannot
+// come from row padding; each lane instead fetches the 16-byte chunk that belongs in its slot
+// under an XOR swizzle:
+//  * operand with the contraction index contiguous in memory ("rows x k"): LDS row = 128 bytes =
+//    8 chunks, chunk c of row r sits in slot c ^ ((r >> 1) & 7); fragments are 16-byte reads;
+//  * operand with the contraction index as the slow one ("k x rows", the transposed layouts of
+//    the data- and weight-gradient GEMMs): kept as stored, LDS row k = ROWS*2 bytes, and the
+//    64-byte group G of row k sits in group G ^ (k & 3) (ROWS = 64: G ^ ((k >> 1) & 1)); fragments
+//    come from the transposing read ds_read_b64_tr_b16, whose lane mapping is: inside each block
+//    of 16 lanes, lane j receives element (j & 3) of the 8-byte words addressed by lanes
+//    4*e + (j >> 2), e = 0..3.
 #include "kernels.h"
 #include <stdlib.h>
 
@@ -18,128 +28,238 @@ typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
-
-
-// LDS tile of one operand.  TR = 0: [ROWS][BK] with row stride BK+8 elements (144 B: the 16
-// rows read together by a 16-byte fragment read start on distinct 16-byte bank groups).
-// TR = 1: [BK][ROWS] with row stride ROWS+32 elements (the 4 k-rows x 64 B read together by a
-// transposing read fall on disjoint banks).
-template <bool TR, int ROWS, int BK, int NT>
-struct Tile {
-  static constexpr int stride = TR ? ROWS + 32 : BK + 8;
-  static constexpr int elems = TR ? BK * stride : ROWS * stride;
-  static constexpr int chunks = ROWS * (BK / 8) / NT;   // 16-byte chunks per thread per k-step
-};
-
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
-// Operands are read through raw buffer descriptors: a load whose byte offset is at or past
-// num_records returns zeros.  Every matrix handed to this kernel spans less than 2 GiB from
-// its base (checked on the host), so num_records = 2 GiB and the offset OOB below stand for
-// "this chunk lies outside the k range / past the last row: give me zeros" without a branch,
-// which keeps the loads of several k-tiles in flight together.
+// Operands are read through raw buffer descriptors with num_records = 2 GiB: a load whose byte
+// offset is at or past that returns zeros (into LDS here) without traffic.  Every matrix handed
+// to this kernel spans less than 2 GiB from its base (checked on the host), so the offset OOB
+// stands for "outside the k range / past the last row" without a branch.
 #define BUF_RECORDS 0x80000000u
 #define OOB 0x80000000u
+#define BK 64
 
-struct OperandSrc {
-  __amdgpu_buffer_rsrc_t rsrc;   // matrix base (already offset by group)
-  unsigned ld_bytes;             // row stride in bytes
-  const int* gather;             // row indirection (non-transposed A only) or nullptr
-  int div;
-  int row0;                      // first tile row (m0 or n0) in the non-contraction index
-  int row_lim;                   // exclusive bound of valid rows
-};
+// one wave-load: 64 lanes x 16 bytes from desc + voff (per lane) to LDS at lds_addr + 16 * lane
+__device__ __forceinline__ void load_lds_b128(u32x4 desc, unsigned lds_addr, unsigned voff) {
+  asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+               :: "s"(lds_addr), "v"(voff), "s"(desc) : "memory", "m0");
+}
+template <int N> __device__ __forceinline__ void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory"); }
 
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p) {
-  return __builtin_amdgcn_make_buffer_rsrc((void*)p, 0, BUF_RECORDS, 0x00020000);
+__device__ __forceinline__ u32x4 make_desc(const void* p) {
+  const unsigned long long a = (unsigned long long)p;
+  u32x4 d = {(unsigned)a, (unsigned)(a >> 32), BUF_RECORDS, 0x00020000u};
+  return d;
 }
 
-// ---- global -> registers ----------------------------------------------------------
-template <bool TR, int ROWS, int BK, int NT>
-__device__ __forceinline__ void load_tile(const OperandSrc& s, int k0, int k_end,
-                                          uint4 (&regs)[Tile<TR, ROWS, BK, NT>::chunks],
-                                          const unsigned (&rowoff)[Tile<TR, ROWS, BK, NT>::chunks]) {
-  constexpr int NC = Tile<TR, ROWS, BK, NT>::chunks;
-#pragma unroll
-  for (int i = 0; i < NC; i++) {
-    int c = threadIdx.x + NT * i;
-    unsigned off;
-    if (!TR) {
-      int k = k0 + (c % (BK / 8)) * 8;
-      off = (k < k_end) ? rowoff[i] + (unsigned)k * 2u : OOB;
-    } else {
-      int k = k0 + c / (ROWS / 8);
-      int m = s.row0 + (c % (ROWS / 8)) * 8;
-      off = (k < k_end && m < s.row_lim) ? (unsigned)k * s.ld_bytes + (unsigned)m * 2u : OOB;
-    }
-    u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(s.rsrc, off, 0, 0);
-    regs[i] = make_uint4(v[0], v[1], v[2], v[3]);
-  }
-}
-
-// per-thread row byte offsets of the non-transposed operand (fixed over the k loop); rows past
-// the limit are clamped to the last valid row (their products are never stored)
-template <int ROWS, int BK, int NT>
-__device__ __forceinline__ void row_offsets(const OperandSrc& s, unsigned (&rowoff)[ROWS * (BK / 8) / NT]) {
-#pragma unroll
-  for (int i = 0; i < ROWS * (BK / 8) / NT; i++) {
-    int c = threadIdx.x + NT * i;
-    int r = s.row0 + c / (BK / 8);
-    const bool in = r < s.row_lim;
-    if (!in) r = s.row_lim - 1;
-    unsigned rr = s.gather ? (unsigned)(s.gather[r] / s.div) : (unsigned)r;
-    rowoff[i] = in ? rr * s.ld_bytes : OOB;            // rows past the limit read as zeros, without traffic
-  }
-}
-
-// ---- registers -> LDS -------------------------------------------------------------
-template <bool TR, int ROWS, int BK, int NT>
-__device__ __forceinline__ void store_tile(bf16* lds, const uint4 (&regs)[Tile<TR, ROWS, BK, NT>::chunks]) {
-  constexpr int NC = Tile<TR, ROWS, BK, NT>::chunks;
-  constexpr int ST = Tile<TR, ROWS, BK, NT>::stride;
-#pragma unroll
-  for (int i = 0; i < NC; i++) {
-    int c = threadIdx.x + NT * i;
-    int off;
-    if (!TR) off = (c / (BK / 8)) * ST + (c % (BK / 8)) * 8;
-    else off = (c / (ROWS / 8)) * ST + (c % (ROWS / 8)) * 8;
-    *(uint4*)(lds + off) = regs[i];
-  }
-}
-
-// ---- LDS -> MFMA operand fragment: 32 rows x 16 k, lane (r = lane & 31, g = lane >> 5)
-// holds k = 8g..8g+7 of row r ---------------------------------------------------------
-template <bool TR, int ROWS, int BK>
-__device__ __forceinline__ bf16x8 load_frag(const bf16* lds, int r0, int kk, int lane) {
-  constexpr int ST = Tile<TR, ROWS, BK, 256>::stride;
+// Where the 16-byte chunk at LDS position `pos` (in chunks, lane order of the wave-loads) of one operand tile
+// comes from: byte offset of that chunk at k-tile 0 relative to the operand base, and the number of k-tiles for
+// which it lies inside the k range (0 = never: a row past the limit).  krange = elements of the k range.
+template <bool TR, int ROWS>
+__device__ __forceinline__ void chunk_source(int pos, int row0, int row_lim, unsigned ld_bytes, int k0, int krange,
+                                             const int* gather, int div, unsigned* base, int* ntiles) {
   if (!TR) {
-    return *(const bf16x8*)(lds + (r0 + (lane & 31)) * ST + kk * 16 + (lane >> 5) * 8);
+    const int r = pos >> 3, slot = pos & 7;
+    const int c = slot ^ ((r >> 1) & 7);                          // k-chunk of row r that lives in this slot
+    int row = row0 + r;
+    const bool in = row < row_lim;
+    if (!in) row = row_lim - 1;
+    const unsigned rr = gather ? (unsigned)(gather[row] / div) : (unsigned)row;
+    *base = rr * ld_bytes + (unsigned)(k0 + c * 8) * 2u;
+    *ntiles = in ? (krange - c * 8 + BK - 1) / BK : 0;
   } else {
-    int blk = lane >> 4, i = lane & 15;
-    int krow = kk * 16 + (blk >> 1) * 8 + (i >> 2);
-    int mcol = r0 + (blk & 1) * 16 + (i & 3) * 4;
-    const bf16* p = lds + krow * ST + mcol;
+    constexpr int CPR = ROWS / 8;                                 // chunks per LDS row (one k)
+    const int kr = pos / CPR, slot = pos % CPR;
+    const int gsw = (CPR >= 16) ? (kr & 3) : ((kr >> 1) & 1);
+    const int c = (((slot >> 2) ^ gsw) << 2) | (slot & 3);        // 8-element column chunk that lives in this slot
+    const int col = row0 + c * 8;
+    *base = (unsigned)(k0 + kr) * ld_bytes + (unsigned)col * 2u;
+    *ntiles = col < row_lim ? (krange - kr + BK - 1) / BK : 0;
+  }
+}
+
+// Per-lane LDS byte offset (inside the operand's tile, k-step kk = 0) of the MFMA fragment rows r0..r0+31:
+// lane (r = lane & 31, g = lane >> 5) holds k = 16*kk + 8*g .. +7 of row r0 + r.
+template <bool TR, int ROWS>
+__device__ __forceinline__ unsigned frag_base(int r0, int lane) {
+  if (!TR) return (unsigned)(r0 + (lane & 31)) * 128u;
+  const int blk = lane >> 4, i = lane & 15;
+  const int kr = (blk >> 1) * 8 + (i >> 2);
+  const int col = r0 + (blk & 1) * 16 + (i & 3) * 4;
+  constexpr int CPR = ROWS / 8;
+  const int c = col >> 3;
+  const int gsw = (CPR >= 16) ? (kr & 3) : ((kr >> 1) & 1);       // unchanged by + 4, + 8, + 16*kk
+  const int slot = (((c >> 2) ^ gsw) << 2) | (c & 3);
+  return (unsigned)kr * (ROWS * 2u) + (unsigned)slot * 16u + (unsigned)(col & 7) * 2u;
+}
+template <bool TR, int ROWS>
+__device__ __forceinline__ bf16x8 load_frag(const unsigned char* tile, unsigned fb, int r0, int kk, int lane) {
+  if (!TR) {
+    const int sw = ((r0 + (lane & 31)) >> 1) & 7;
+    return *(const bf16x8*)(tile + fb + ((((kk * 2) + (lane >> 5)) ^ sw) << 4));
+  } else {
+    const unsigned char* p = tile + fb + kk * 16 * (ROWS * 2);
     s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p));
-    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 4 * ST));
+    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 4 * (ROWS * 2)));
     s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     return __builtin_bit_cast(bf16x8, v);
   }
 }
 
-// PD = number of k-tiles kept in flight in registers ahead of the one being multiplied
-#define PD 3
-template <int BM, int BN, int BK, int WGM, bool AT, bool BT, class TC, bool RB, int NW>
-__global__ void __launch_bounds__(NW * 64, BK == 32 ? 3 : 1) gemm_mfma_k(GemmArgs g) {
-  constexpr int NT = NW * 64;                       // threads per workgroup
-  typedef Tile<AT, BM, BK, NT> TA_;
-  typedef Tile<BT, BN, BK, NT> TB_;
+// One output tile: TE 32-row blocks per wave (TE = the wave tile's full height except in the SKIP kernels).
+template <int BM, int BN, int WGM, bool AT, bool BT, class TC, int NW, int NS, int TE>
+__device__ __forceinline__ void gemm_tile(const GemmArgs& g, const bf16* A, const bf16* Bm, TC* C, int bx, int bz,
+                                          int m0, int m_end, int k0, int k_end) {
   constexpr int WGN = NW / WGM;                      // waves along n
-  constexpr int WM = BM / WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32;
+  constexpr int WM = BM / WGM, WN = BN / WGN, TN = WN / 32;
+  constexpr int STAGE = (BM + BN) * 128;             // bytes of one LDS stage: A tile, then B tile
+  constexpr int LPW = (BM + BN) / 8 / NW;            // wave-loads (1 KiB) per wave per stage
   static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile must be made of 32x32 blocks");
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  bf16* sA = (bf16*)smem_raw;                       // 2 stages of A then 2 stages of B
-  bf16* sB = sA + 2 * TA_::elems;
+  static_assert((BM + BN) % (8 * NW) == 0 && BM % 8 == 0, "wave-loads must divide evenly");
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  const int n0 = bx * BN;
+  const int lane = threadIdx.x & 63, wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wm = (wv / WGN) * WM, wn = (wv % WGN) * WN;
+  const int krange = k_end - k0;
+  const int nk = (krange + BK - 1) / BK;
 
+  // ---- this wave's loads: wave-load j = wv*LPW + i fills LDS chunks [64 j, 64 j + 64) of a stage; the first
+  // BM/8 wave-loads are the A tile, the rest the B tile
+  const u32x4 da = make_desc(A), db = make_desc(Bm);
+  const unsigned lda_b = (unsigned)g.lda * 2u, ldb_b = (unsigned)g.ldb * 2u;
+  const unsigned kstep_a = AT ? BK * lda_b : BK * 2u, kstep_b = BT ? BK * ldb_b : BK * 2u;
+  unsigned base[LPW];
+  int ntile[LPW];
+#pragma unroll
+  for (int i = 0; i < LPW; i++) {
+    const int j = wv * LPW + i;
+    if (j < BM / 8) chunk_source<AT, BM>(j * 64 + lane, m0, m_end, lda_b, k0, krange, g.a_gather, g.gather_div, &base[i], &ntile[i]);
+    else chunk_source<BT, BN>((j - BM / 8) * 64 + lane, n0, g.N, ldb_b, k0, krange, nullptr, 1, &base[i], &ntile[i]);
+  }
+  const unsigned lds0 = (unsigned)(unsigned long long)(__attribute__((address_space(3))) unsigned char*)smem;
+  const unsigned lw = __builtin_amdgcn_readfirstlane(lds0 + (unsigned)wv * LPW * 1024u);
+  auto issue = [&](int kt, int i) {                  // wave-load i of k-tile kt into stage kt % NS
+    const bool isA = (wv * LPW + i) < BM / 8;        // wave-uniform
+    const unsigned off = kt < ntile[i] ? base[i] + (unsigned)kt * (isA ? kstep_a : kstep_b) : OOB;
+    load_lds_b128(isA ? da : db, lw + (unsigned)(kt % NS) * STAGE + i * 1024, off);
+  };
+
+  f32x16 acc[TE][TN];
+#pragma unroll
+  for (int i = 0; i < TE; i++)
+#pragma unroll
+    for (int j = 0; j < TN; j++)
+#pragma unroll
+      for (int e = 0; e < 16; e++) acc[i][j][e] = 0.f;
+  unsigned fba[TE], fbb[TN];
+#pragma unroll
+  for (int i = 0; i < TE; i++) fba[i] = frag_base<AT, BM>(wm + i * 32, lane);
+#pragma unroll
+  for (int j = 0; j < TN; j++) fbb[j] = BM * 128u + frag_base<BT, BN>(wn + j * 32, lane);
+
+  // ---- pipeline: tiles kt+1 .. kt+NS-1 are in flight while tile kt is multiplied.  A tile past the end of the
+  // k range is loaded as zeros (OOB), so every iteration issues the same number of loads and the wait count
+  // below is a constant.
+#pragma unroll
+  for (int p = 0; p < NS - 1; p++)
+#pragma unroll
+    for (int i = 0; i < LPW; i++) issue(p, i);
+  for (int kt = 0; kt < nk; kt++) {
+    wait_vmcnt<LPW * (NS - 2)>();                    // this wave's share of tile kt has landed in LDS
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // and its LDS reads of tile kt-1 have returned
+    __builtin_amdgcn_s_barrier();                    // ... for every wave: stage (kt-1) % NS may be overwritten
+    const unsigned char* st = smem + (kt % NS) * STAGE;
+    // fragments of k-step kk+1 are fetched from LDS, and a share of the loads of tile kt+NS-1 issued, while the
+    // MFMAs of k-step kk run
+    bf16x8 fa[2][TE], fb[2][TN];
+#pragma unroll
+    for (int i = 0; i < TE; i++) fa[0][i] = load_frag<AT, BM>(st, fba[i], wm + i * 32, 0, lane);
+#pragma unroll
+    for (int j = 0; j < TN; j++) fb[0][j] = load_frag<BT, BN>(st, fbb[j], wn + j * 32, 0, lane);
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; kk++) {
+#pragma unroll
+      for (int i = kk * LPW / 4; i < (kk + 1) * LPW / 4; i++) issue(kt + NS - 1, i);
+      if (kk + 1 < BK / 16) {
+#pragma unroll
+        for (int i = 0; i < TE; i++) fa[(kk + 1) & 1][i] = load_frag<AT, BM>(st, fba[i], wm + i * 32, kk + 1, lane);
+#pragma unroll
+        for (int j = 0; j < TN; j++) fb[(kk + 1) & 1][j] = load_frag<BT, BN>(st, fbb[j], wn + j * 32, kk + 1, lane);
+      }
+#pragma unroll
+      for (int i = 0; i < TE; i++)
+#pragma unroll
+        for (int j = 0; j < TN; j++)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kk & 1][i], fb[kk & 1][j], acc[i][j], 0, 0, 0);
+    }
+  }
+  wait_vmcnt<0>();                                   // the zero-filled loads past the last tile
+
+  // ---- epilogue: lane holds column n = lane & 31 and rows (e>>2)*8 + (lane>>5)*4 + (e&3)
+  if (g.group_mode == 0 && g.split_k > 1) {
+    float* ws = g.splitk_ws + (i64)bz * g.M * g.N;
+#pragma unroll
+    for (int j = 0; j < TN; j++) {
+      const int n = n0 + wn + j * 32 + (lane & 31);
+      if (n >= g.N) continue;
+#pragma unroll
+      for (int i = 0; i < TE; i++)
+#pragma unroll
+        for (int e = 0; e < 16; e++) {
+          const int m = m0 + wm + i * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+          if (m < m_end) ws[(i64)m * g.N + n] = acc[i][j][e];
+        }
+    }
+    return;
+  }
+  const bf16* bias = (const bf16*)g.bias;
+  const bf16* resid = (const bf16*)g.resid;
+  if (!g.row_scale && !bias && !g.tap && !resid) {
+    // plain store (all weight gradients, most projections): no per-element epilogue work
+    const bool full = (m0 + BM <= m_end) && (n0 + BN <= g.N);
+#pragma unroll
+    for (int j = 0; j < TN; j++) {
+      const int n = n0 + wn + j * 32 + (lane & 31);
+#pragma unroll
+      for (int i = 0; i < TE; i++) {
+        TC* cp = C + (i64)(m0 + wm + i * 32 + (lane >> 5) * 4) * g.ldc + n;
+#pragma unroll
+        for (int e = 0; e < 16; e++) {
+          const int dm = (e >> 2) * 8 + (e & 3);
+          if (full || (n < g.N && m0 + wm + i * 32 + (lane >> 5) * 4 + dm < m_end)) cp[(i64)dm * g.ldc] = (TC)acc[i][j][e];
+        }
+      }
+    }
+    return;
+  }
+#pragma unroll
+  for (int j = 0; j < TN; j++) {
+    const int n = n0 + wn + j * 32 + (lane & 31);
+    if (n >= g.N) continue;
+    const float bv = bias ? (float)bias[n] : 0.f;
+#pragma unroll
+    for (int i = 0; i < TE; i++) {
+#pragma unroll
+      for (int e = 0; e < 16; e++) {
+        const int m = m0 + wm + i * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+        if (m >= m_end) continue;
+        float v = acc[i][j][e];
+        if (g.row_scale) v *= g.row_scale[m];
+        v += bv;
+        if (g.tap) g.tap[(i64)m * g.ldtap + n] = v;
+        if (resid) v = (float)resid[(i64)m * g.ldr + n] + g.resid_sign * v;
+        C[(i64)m * g.ldc + n] = (TC)v;
+      }
+    }
+  }
+}
+
+// SKIP (expert tiles, WGM = 1: every wave spans all BM rows): a tile whose expert ends early multiplies only the
+// 32-row blocks that hold rows, TE = ceil(rows / 32) of them, through a loop specialised for TE; such a tile still
+// streams its whole weight panel, but costs TE / 4 of the matrix-core time.
+template <int BM, int BN, int WGM, bool AT, bool BT, class TC, int NW, int NS, bool SKIP>
+__global__ void __launch_bounds__(NW * 64) gemm_mfma_k(GemmArgs g) {
+  constexpr int TM = BM / WGM / 32;
+  static_assert(!SKIP || WGM == 1, "row-block skipping needs waves that span all rows of the tile");
   const bf16* A = (const bf16*)g.A;
   const bf16* Bm = (const bf16*)g.B;
   TC* C = (TC*)g.C;
@@ -170,140 +290,13 @@ __global__ void __launch_bounds__(NW * 64, BK == 32 ? 3 : 1) gemm_mfma_k(GemmArg
       k_end = min(g.K, k0 + per);
     }
   }
-  const int n0 = bx * BN;
-  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-  const int wm = (wv / WGN) * WM, wn = (wv % WGN) * WN;
-
-  OperandSrc sa{make_rsrc(A), (unsigned)g.lda * 2u, g.a_gather, g.gather_div, m0, m_end};
-  OperandSrc sb{make_rsrc(Bm), (unsigned)g.ldb * 2u, nullptr, 1, n0, g.N};
-  unsigned offA[TA_::chunks], offB[TB_::chunks];
-  if (!AT) row_offsets<BM, BK, NT>(sa, offA);
-  if (!BT) row_offsets<BN, BK, NT>(sb, offB);
-
-  // 32-row blocks of this wave's tile that hold at least one valid row (partial expert tiles)
-  const int tm_eff = RB ? min(TM, max(0, (m_end - m0 - wm + 31) / 32)) : TM;
-
-  f32x16 acc[TM][TN];
-#pragma unroll
-  for (int i = 0; i < TM; i++)
-#pragma unroll
-    for (int j = 0; j < TN; j++)
-#pragma unroll
-      for (int e = 0; e < 16; e++) acc[i][j][e] = 0.f;
-
-  // Software pipeline: register set u holds k-tile kt+PD while tile kt is multiplied from LDS and
-  // tile kt+1 moves from its register set into the other LDS stage.  Loads and LDS stores are
-  // unconditional (a tile past the end of the k range reads as zeros through the OOB offset), so
-  // the loop body is straight-line code and the compiler can keep 2*PD-1 tile loads outstanding;
-  // only the multiply is skipped for the padding tiles.
-  uint4 ra[PD][TA_::chunks], rb[PD][TB_::chunks];
-  const int nk = (k_end - k0 + BK - 1) / BK;
-#pragma unroll
-  for (int p = 0; p < PD; p++) {
-    load_tile<AT, BM, BK, NT>(sa, k0 + p * BK, k_end, ra[p], offA);
-    load_tile<BT, BN, BK, NT>(sb, k0 + p * BK, k_end, rb[p], offB);
+  if (SKIP) {
+    const int te = (m_end - m0 + 31) >> 5;             // uniform over the workgroup
+    if (te == 1) { gemm_tile<BM, BN, WGM, AT, BT, TC, NW, NS, 1>(g, A, Bm, C, bx, bz, m0, m_end, k0, k_end); return; }
+    if (TM > 2 && te == 2) { gemm_tile<BM, BN, WGM, AT, BT, TC, NW, NS, (TM > 2 ? 2 : TM)>(g, A, Bm, C, bx, bz, m0, m_end, k0, k_end); return; }
+    if (TM > 3 && te == 3) { gemm_tile<BM, BN, WGM, AT, BT, TC, NW, NS, (TM > 3 ? 3 : TM)>(g, A, Bm, C, bx, bz, m0, m_end, k0, k_end); return; }
   }
-  store_tile<AT, BM, BK, NT>(sA, ra[0]);
-  store_tile<BT, BN, BK, NT>(sB, rb[0]);
-  __syncthreads();
-  for (int kt0 = 0; kt0 < nk; kt0 += PD) {
-#pragma unroll
-    for (int u = 0; u < PD; u++) {
-      const int kt = kt0 + u;
-      const int cur = kt & 1;
-      load_tile<AT, BM, BK, NT>(sa, k0 + (kt + PD) * BK, k_end, ra[u], offA);
-      load_tile<BT, BN, BK, NT>(sb, k0 + (kt + PD) * BK, k_end, rb[u], offB);
-      if (kt < nk) {                                  // uniform over the workgroup
-        const bf16* cA = sA + cur * TA_::elems;
-        const bf16* cB = sB + cur * TB_::elems;
-        // fragments of k-step kk+1 are fetched from LDS while the MFMAs of k-step kk issue
-        bf16x8 fa[2][TM], fb[2][TN];
-#pragma unroll
-        for (int i = 0; i < TM; i++)
-          if (!RB || i < tm_eff) fa[0][i] = load_frag<AT, BM, BK>(cA, wm + i * 32, 0, lane);
-#pragma unroll
-        for (int j = 0; j < TN; j++) fb[0][j] = load_frag<BT, BN, BK>(cB, wn + j * 32, 0, lane);
-#pragma unroll
-        for (int kk = 0; kk < BK / 16; kk++) {
-          if (kk + 1 < BK / 16) {
-#pragma unroll
-            for (int i = 0; i < TM; i++)
-              if (!RB || i < tm_eff) fa[(kk + 1) & 1][i] = load_frag<AT, BM, BK>(cA, wm + i * 32, kk + 1, lane);
-#pragma unroll
-            for (int j = 0; j < TN; j++) fb[(kk + 1) & 1][j] = load_frag<BT, BN, BK>(cB, wn + j * 32, kk + 1, lane);
-          }
-#pragma unroll
-          for (int i = 0; i < TM; i++)
-            if (!RB || i < tm_eff) {
-#pragma unroll
-              for (int j = 0; j < TN; j++)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kk & 1][i], fb[kk & 1][j], acc[i][j], 0, 0, 0);
-            }
-        }
-      }
-      store_tile<AT, BM, BK, NT>(sA + (cur ^ 1) * TA_::elems, ra[(u + 1) % PD]);   // tile kt+1
-      store_tile<BT, BN, BK, NT>(sB + (cur ^ 1) * TB_::elems, rb[(u + 1) % PD]);
-      __syncthreads();
-    }
-  }
-
-  // ---- epilogue: lane holds column n = lane & 31 and rows (e>>2)*8 + (lane>>5)*4 + (e&3)
-  if (g.group_mode == 0 && g.split_k > 1) {
-    float* ws = g.splitk_ws + (i64)bz * g.M * g.N;
-#pragma unroll
-    for (int j = 0; j < TN; j++) {
-      const int n = n0 + wn + j * 32 + (lane & 31);
-      if (n >= g.N) continue;
-#pragma unroll
-      for (int i = 0; i < TM; i++)
-#pragma unroll
-        for (int e = 0; e < 16; e++) {
-          const int m = m0 + wm + i * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
-          if (m < m_end) ws[(i64)m * g.N + n] = acc[i][j][e];
-        }
-    }
-    return;
-  }
-  const bf16* bias = (const bf16*)g.bias;
-  const bf16* resid = (const bf16*)g.resid;
-  if (!g.row_scale && !bias && !g.tap && !resid) {
-    // plain store (all weight gradients, most projections): no per-element epilogue work
-    const bool full = (m0 + BM <= m_end) && (n0 + BN <= g.N);
-#pragma unroll
-    for (int j = 0; j < TN; j++) {
-      const int n = n0 + wn + j * 32 + (lane & 31);
-#pragma unroll
-      for (int i = 0; i < TM; i++) {
-        TC* cp = C + (i64)(m0 + wm + i * 32 + (lane >> 5) * 4) * g.ldc + n;
-#pragma unroll
-        for (int e = 0; e < 16; e++) {
-          const int dm = (e >> 2) * 8 + (e & 3);
-          if (full || (n < g.N && m0 + wm + i * 32 + (lane >> 5) * 4 + dm < m_end)) cp[(i64)dm * g.ldc] = (TC)acc[i][j][e];
-        }
-      }
-    }
-    return;
-  }
-#pragma unroll
-  for (int j = 0; j < TN; j++) {
-    const int n = n0 + wn + j * 32 + (lane & 31);
-    if (n >= g.N) continue;
-    const float bv = bias ? (float)bias[n] : 0.f;
-#pragma unroll
-    for (int i = 0; i < TM; i++) {
-#pragma unroll
-      for (int e = 0; e < 16; e++) {
-        const int m = m0 + wm + i * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
-        if (m >= m_end) continue;
-        float v = acc[i][j][e];
-        if (g.row_scale) v *= g.row_scale[m];
-        v += bv;
-        if (g.tap) g.tap[(i64)m * g.ldtap + n] = v;
-        if (resid) v = (float)resid[(i64)m * g.ldr + n] + g.resid_sign * v;
-        C[(i64)m * g.ldc + n] = (TC)v;
-      }
-    }
-  }
+  gemm_tile<BM, BN, WGM, AT, BT, TC, NW, NS, TM>(g, A, Bm, C, bx, bz, m0, m_end, k0, k_end);
 }
 
 // REVFFN_XCD (tuning aid): 0 = plain 2-D grids, tiles land on the XCDs round-robin
@@ -313,7 +306,7 @@ static int xcd_enabled() {
   return v;
 }
 
-template <int BM, int BN, int BK, int WGM, bool AT, bool BT, class TC, bool RB = false, int NW = 4>
+template <int BM, int BN, int WGM, bool AT, bool BT, class TC, int NW, int NS, bool SKIP = false>
 static void go(const GemmArgs& g0, hipStream_t s) {
   GemmArgs g = g0;
   g.tiles_n = cdiv(g.N, BN);
@@ -334,17 +327,25 @@ static void go(const GemmArgs& g0, hipStream_t s) {
       grid = dim3(dense_grid_x(g.xcd_m, g.tiles_m, g.tiles_n), 1, zdim);
     }
   }
-  size_t smem = (size_t)2 * (Tile<AT, BM, BK, NW * 64>::elems + Tile<BT, BN, BK, NW * 64>::elems) * sizeof(bf16);
+  constexpr size_t smem = (size_t)NS * (BM + BN) * 128;
+  static_assert(smem <= 160 * 1024, "LDS stages exceed the CU's 160 KiB");
   static bool attr_set = false;
   if (!attr_set) {
-    (void)hipFuncSetAttribute((const void*)gemm_mfma_k<BM, BN, BK, WGM, AT, BT, TC, RB, NW>,
+    (void)hipFuncSetAttribute((const void*)gemm_mfma_k<BM, BN, WGM, AT, BT, TC, NW, NS, SKIP>,
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     attr_set = true;
   }
-  hipLaunchKernelGGL((gemm_mfma_k<BM, BN, BK, WGM, AT, BT, TC, RB, NW>), grid, dim3(NW * 64), smem, s, g);
+  hipLaunchKernelGGL((gemm_mfma_k<BM, BN, WGM, AT, BT, TC, NW, NS, SKIP>), grid, dim3(NW * 64), smem, s, g);
 }
 
-// REVFFN_GEMM_TILE (tuning aid): 1 = 128x128, 2 = 128x64, 3 = 64x128 for every non-grouped problem
+// The four tile shapes: 256x128 (8 waves, one workgroup per CU), 128x128 (4 waves, 4 stages), 128x64 and 64x128
+// (4 waves, two workgroups per CU).
+template <bool AT, bool BT, class TC> static void go_256x128(const GemmArgs& g, hipStream_t s) { go<256, 128, 4, AT, BT, TC, 8, 3>(g, s); }
+template <bool AT, bool BT, class TC> static void go_128x128(const GemmArgs& g, hipStream_t s) { go<128, 128, 2, AT, BT, TC, 4, 4>(g, s); }
+template <bool AT, bool BT, class TC> static void go_128x64(const GemmArgs& g, hipStream_t s) { go<128, 64, 2, AT, BT, TC, 4, 3>(g, s); }
+template <bool AT, bool BT, class TC> static void go_64x128(const GemmArgs& g, hipStream_t s) { go<64, 128, 1, AT, BT, TC, 4, 3>(g, s); }
+
+// REVFFN_GEMM_TILE (tuning aid): 1 = 128x128, 2 = 128x64, 3 = 64x128, 4 = 256x128 for every non-grouped problem
 static int tile_override() {
   static int v = -1;
   if (v < 0) { const char* e = getenv("REVFFN_GEMM_TILE"); v = e ? atoi(e) : 0; }
@@ -355,34 +356,42 @@ template <bool AT, bool BT, class TC>
 static void pick_tile(const GemmArgs& g, hipStream_t s) {
   if (g.group_mode != 1 && tile_override()) {
     switch (tile_override()) {
-      case 1: go<128, 128, 64, 2, AT, BT, TC>(g, s); return;
-      case 2: go<128, 64, 64, 2, AT, BT, TC>(g, s); return;
-      case 3: go<64, 128, 64, 1, AT, BT, TC>(g, s); return;
-      case 4: go<128, 128, 32, 2, AT, BT, TC>(g, s); return;
+      case 1: go_128x128<AT, BT, TC>(g, s); return;
+      case 2: go_128x64<AT, BT, TC>(g, s); return;
+      case 3: go_64x128<AT, BT, TC>(g, s); return;
+      case 4: go_256x128<AT, BT, TC>(g, s); return;
     }
   }
   if (g.group_mode == 1) {
-    // expert tiles.  Variant 1 (waves split the weight columns and skip the 32-row blocks a short expert
-    // does not fill) measured slightly slower than the plain 2x2 wave layout at ~137 rows per expert
-    static int v = -1;                 // REVFFN_GROUPED_VARIANT (tuning aid): 0 = 2x2 waves, 1 = 1x4 waves + skipping
+    // expert tiles: waves side by side along n, each spanning all rows, so that a tile whose expert ends early
+    // multiplies only the 32-row blocks that hold rows
+    static int v = -1;                 // REVFFN_GROUPED_VARIANT (tuning aid): 0 = skipping, 4 stages; 1 = 2x2 waves, no skipping; 2 = skipping, 2 stages
     if (v < 0) { const char* e = getenv("REVFFN_GROUPED_VARIANT"); v = e ? atoi(e) : 0; }
-    if (g.tile_bm == 64) go<64, 128, 64, 1, AT, BT, TC>(g, s);
-    else if (v == 0) go<128, 128, 64, 2, AT, BT, TC>(g, s);
-    else go<128, 128, 64, 1, AT, BT, TC, true>(g, s);
+    if (g.tile_bm == 64) go<64, 128, 1, AT, BT, TC, 4, 3, true>(g, s);
+    else if (g.tile_bm == 256) go_256x128<AT, BT, TC>(g, s);
+    else if (v == 1) go_128x128<AT, BT, TC>(g, s);
+    else if (v == 2) go<128, 128, 1, AT, BT, TC, 4, 2, true>(g, s);
+    else go<128, 128, 1, AT, BT, TC, 4, 4, true>(g, s);
     return;
   }
   if (g.group_mode == 2) {
-    // per-expert weight gradients: the k range is one expert's rows; short ranges take the k-step 32 kernel
-    // (less padding, smaller LDS footprint, more workgroups per CU to hide the load latency)
-    static int v = -1;                 // REVFFN_WGRAD_BK32 (tuning aid)
-    if (v < 0) { const char* e = getenv("REVFFN_WGRAD_BK32"); v = e ? atoi(e) : 1; }
-    if (v && g.K < (i64)192 * g.n_groups) go<128, 128, 32, 2, AT, BT, TC>(g, s); else go<128, 128, 64, 2, AT, BT, TC>(g, s);
+    // per-expert weight gradients: the k range is one expert's rows, a few k-tiles only, so a workgroup is mostly
+    // load latency and output stores: small LDS footprint, several workgroups per CU
+    static int v = -1;                 // REVFFN_WGRAD_TILE (tuning aid): 0 = 128x128 2 stages, 1 = 128x64 2 stages, 2 = 128x128 4 stages, 3 = 128x64 3 stages
+    if (v < 0) { const char* e = getenv("REVFFN_WGRAD_TILE"); v = e ? atoi(e) : 0; }
+    if (v == 1) go<128, 64, 2, AT, BT, TC, 4, 2>(g, s);
+    else if (v == 2) go_128x128<AT, BT, TC>(g, s);
+    else if (v == 3) go_128x64<AT, BT, TC>(g, s);
+    else go<128, 128, 2, AT, BT, TC, 4, 2>(g, s);
     return;
   }
-  // small problems: narrower tiles so that every CU gets at least two workgroups
-  i64 tiles = (i64)cdiv(g.M, 128) * cdiv(g.N, 128);
-  if (tiles < 512 && g.N >= 128) go<128, 64, 64, 2, AT, BT, TC>(g, s);
-  else go<128, 128, 64, 2, AT, BT, TC>(g, s);
+  // the largest tile that still gives every CU work: 256x128 from two rounds of workgroups on, 128x128 down to
+  // ~200 tiles, else 128x64
+  const i64 t256 = (i64)cdiv(g.M, 256) * cdiv(g.N, 128), t128 = (i64)cdiv(g.M, 128) * cdiv(g.N, 128);
+  const int z = g.split_k > 1 ? g.split_k : 1;
+  if (t256 * z >= 512) go_256x128<AT, BT, TC>(g, s);
+  else if (t128 * z >= 200 || g.N < 128) go_128x128<AT, BT, TC>(g, s);
+  else go_128x64<AT, BT, TC>(g, s);
 }
 
 static bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
@@ -397,7 +406,7 @@ int launch_gemm_mfma(const GemmArgs& g, GemmTypes t, hipStream_t s) {
   if (g.b_trans && (g.N & 7)) return 1;
   if (g.a_trans && !g.b_trans) return 1;                 // layout not used by the block
   if (g.group_mode == 2 && !(g.a_trans && g.b_trans)) return 1;
-  if (g.group_mode == 1 && (g.a_trans || (g.tile_bm != 128 && g.tile_bm != 64))) return 1;
+  if (g.group_mode == 1 && (g.a_trans || (g.tile_bm != 128 && g.tile_bm != 64 && g.tile_bm != 256))) return 1;
   if (g.a_gather && g.a_trans) return 1;
   if (g.b_gather) return 1;                              // gather along k is not taken: materialise the rows
   if (g.group_mode != 1 && g.M <= 0) return 1;

@@ -140,10 +140,10 @@ void launch_absdiff_max_copy(int dt, const void* a, i64 lda, const void* b, i64 
 void launch_router(int dt, const void* y1, i64 ld, const float* zparts, int n_parts, const float* b_router,
                    float* probs, int* idx, float* wts, float* gamma, int T, int h, int E, int k, int has_gate,
                    int norm_topk, float eps, hipStream_t s);
-// m-tile lists of the grouped GEMMs for two tile heights: list i covers every expert's rows with
+// m-tile lists of the grouped GEMMs for three tile heights: list i covers every expert's rows with
 // tiles of bm[i] rows (group[i][t] = expert or -1 for an unused slot, m0[i][t] = first row, first[i][t] = packed
 // (first tile of t's expert) * 65536 + (tiles of that expert), count[i] = tiles in use)
-struct TileLists { int* group[2]; int* m0[2]; int* first[2]; int max_tiles[2]; int bm[2]; int* count; };
+struct TileLists { int* group[3]; int* m0[3]; int* first[3]; int max_tiles[3]; int bm[3]; int* count; };
 // counts/offsets/row_map/inv_map and the tile lists
 void launch_permute(const int* idx, int T, int k, int E, int* counts, int* offsets, int* row_map, int* inv_map,
                     const TileLists& tl, hipStream_t s);

@@ -145,7 +145,7 @@ __global__ void __launch_bounds__(PERM_WAVES * 64) permute_k(
   for (int e = threadIdx.x; e <= E; e += blockDim.x) offsets[e] = off[e];
   // tile lists: expert e owns the slots after the tiles of experts 0..e-1 (tile counts are tiny, so
   // every thread recounts its prefix); slots past the last tile are marked unused
-  for (int pass = 0; pass < 2; pass++) {
+  for (int pass = 0; pass < 3; pass++) {
     const int bm = tl.bm[pass], mx = tl.max_tiles[pass];
     int* tg = tl.group[pass];
     int* tm = tl.m0[pass];
