@@ -82,8 +82,9 @@ namespace {
 const int BM_A = 64;    // m-tile height of the generic grouped GEMM
 const int BM_B = 128;   // m-tile heights of the MFMA grouped GEMM
 const int BM_C = 256;
+static_assert(!(BM_A & (BM_A - 1)) && !(BM_B & (BM_B - 1)) && !(BM_C & (BM_C - 1)), "the permutation kernel takes tile heights that are powers of two");
 // k-slices of the small fp32 GEMMs around the router (each would otherwise run on a handful of CUs)
-const int SPLIT_FOLD = 16, SPLIT_LOGITS = 8, SPLIT_DWR = 32;
+const int SPLIT_FOLD = 16, SPLIT_LOGITS = 16, SPLIT_DWR = 32;
 
 int check_cfg(const revffn_config* c) {
   if (!c) return REVFFN_ENULL;

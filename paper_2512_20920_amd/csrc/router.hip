@@ -3,6 +3,7 @@
 // weighted combine, and the element-wise parts of their backward passes.
 // Everything here is deterministic: integer results depend only on the logits' bits.
 #include "kernels.h"
+#include <initializer_list>
 
 #define DISPATCH_DT(dt, ...)                                  \
   do {                                                        \
@@ -97,6 +98,7 @@ void launch_router(int dt, const void* y1, i64 ld, const float* zparts, int n_pa
 // [tile_m0[i], min(tile_m0[i]+bm, offsets[g+1])) of expert g = tile_group[i]; unused = -1.
 // ---------------------------------------------------------------------------------
 #define PERM_WAVES 16
+#define PERM_UNROLL 8
 __device__ __forceinline__ void same_expert_mask(int x, bool valid, int nbits, unsigned long long& same) {
   same = __ballot(valid);
   for (int b = 0; b < nbits; b++) {
@@ -108,7 +110,7 @@ __device__ __forceinline__ void same_expert_mask(int x, bool valid, int nbits, u
 __global__ void __launch_bounds__(PERM_WAVES * 64) permute_k(
     const int* __restrict__ idx, int N, int E, int* __restrict__ counts, int* __restrict__ offsets,
     int* __restrict__ row_map, int* __restrict__ inv_map, TileLists tl) {
-  extern __shared__ int ism[];            // cnt[PERM_WAVES][E], then off[E+1]
+  extern __shared__ int ism[];            // cnt[PERM_WAVES][E], off[E+1], tile counts [E+1]
   int* cnt = ism;
   int* off = ism + PERM_WAVES * E;
   const int wv = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -120,13 +122,20 @@ __global__ void __launch_bounds__(PERM_WAVES * 64) permute_k(
   const int per = (N + PERM_WAVES - 1) / PERM_WAVES;
   const int lo = wv * per, hi = min(N, lo + per);
   int* mycnt = cnt + wv * E;
-  for (int base = lo; base < hi; base += 64) {
-    int f = base + lane;
-    bool valid = f < hi;
-    int x = valid ? idx[f] : 0;
-    unsigned long long same;
-    same_expert_mask(x, valid, nbits, same);
-    if (valid && (same & below) == 0) mycnt[x] += __popcll(same);   // group leader; groups are disjoint
+  for (int base0 = lo; base0 < hi; base0 += 64 * PERM_UNROLL) {
+    int xs[PERM_UNROLL];                  // the loads of a batch are independent: one memory latency per batch
+#pragma unroll
+    for (int u = 0; u < PERM_UNROLL; u++) { int f = base0 + u * 64 + lane; xs[u] = f < hi ? idx[f] : 0; }
+#pragma unroll
+    for (int u = 0; u < PERM_UNROLL; u++) {
+      int f = base0 + u * 64 + lane;
+      bool valid = f < hi;
+      int x = xs[u];
+      unsigned long long same;
+      same_expert_mask(x, valid, nbits, same);
+      if (valid && (same & below) == 0) mycnt[x] += __popcll(same);   // group leader; groups are disjoint
+      __builtin_amdgcn_wave_barrier();
+    }
   }
   __syncthreads();
   // exclusive prefix over waves per expert, totals, offsets
@@ -143,47 +152,60 @@ __global__ void __launch_bounds__(PERM_WAVES * 64) permute_k(
   }
   __syncthreads();
   for (int e = threadIdx.x; e <= E; e += blockDim.x) offsets[e] = off[e];
-  // tile lists: expert e owns the slots after the tiles of experts 0..e-1 (tile counts are tiny, so
-  // every thread recounts its prefix); slots past the last tile are marked unused
+  // tile lists: expert e owns the slots after the tiles of experts 0..e-1; slots past the last tile are marked
+  // unused.  Tile heights are powers of two, so tile counts are shifts (no integer division in these loops).
+  int* tcnt = cnt + PERM_WAVES * E + E + 1;   // [E + 1]: tiles per expert, then their total
   for (int pass = 0; pass < 3; pass++) {
-    const int bm = tl.bm[pass], mx = tl.max_tiles[pass];
+    const int bm = tl.bm[pass], mx = tl.max_tiles[pass], sh = 31 - __clz(bm);
     int* tg = tl.group[pass];
     int* tm = tl.m0[pass];
     int* tf = tl.first[pass];
-    int total = 0;
-    for (int e = 0; e < E; e++) total += (off[e + 1] - off[e] + bm - 1) / bm;
+    __syncthreads();                        // the previous pass is done with tcnt
+    for (int e = threadIdx.x; e < E; e += blockDim.x) tcnt[e] = (off[e + 1] - off[e] + bm - 1) >> sh;
+    __syncthreads();
+    if (threadIdx.x == 0) { int t = 0; for (int e = 0; e < E; e++) t += tcnt[e]; tcnt[E] = t; }
     for (int e = threadIdx.x; e < E; e += blockDim.x) {
       int first = 0;
-      for (int q = 0; q < e; q++) first += (off[q + 1] - off[q] + bm - 1) / bm;
+      for (int q = 0; q < e; q++) first += tcnt[q];
       int i = first;
-      const int mine = (off[e + 1] - off[e] + bm - 1) / bm;
+      const int mine = tcnt[e];
       for (int m = off[e]; m < off[e + 1]; m += bm, i++)
         if (i < mx) { tg[i] = e; tm[i] = m; tf[i] = (first << 16) | mine; }
     }
+    __syncthreads();
+    const int total = tcnt[E];
     for (int i = total + threadIdx.x; i < mx; i += blockDim.x) { tg[i] = -1; tm[i] = 0; tf[i] = (i << 16) | 1; }
     if (threadIdx.x == 0) tl.count[pass] = min(total, mx);
   }
   __syncthreads();
-  for (int base = lo; base < hi; base += 64) {
-    int f = base + lane;
-    bool valid = f < hi;
-    int x = valid ? idx[f] : 0;
-    unsigned long long same;
-    same_expert_mask(x, valid, nbits, same);
-    int rank = __popcll(same & below);
-    int start = valid ? mycnt[x] : 0;     // every lane of a group reads before its leader updates
-    if (valid && rank == 0) mycnt[x] = start + __popcll(same);
-    if (valid) {
-      int pos = off[x] + start + rank;
-      row_map[pos] = f;
-      inv_map[f] = pos;
+  for (int base0 = lo; base0 < hi; base0 += 64 * PERM_UNROLL) {
+    int xs[PERM_UNROLL];
+#pragma unroll
+    for (int u = 0; u < PERM_UNROLL; u++) { int f = base0 + u * 64 + lane; xs[u] = f < hi ? idx[f] : 0; }
+#pragma unroll
+    for (int u = 0; u < PERM_UNROLL; u++) {
+      int f = base0 + u * 64 + lane;
+      bool valid = f < hi;
+      int x = xs[u];
+      unsigned long long same;
+      same_expert_mask(x, valid, nbits, same);
+      int rank = __popcll(same & below);
+      int start = valid ? mycnt[x] : 0;     // every lane of a group reads before its leader updates
+      __builtin_amdgcn_wave_barrier();
+      if (valid && rank == 0) mycnt[x] = start + __popcll(same);
+      __builtin_amdgcn_wave_barrier();
+      if (valid) {
+        int pos = off[x] + start + rank;
+        row_map[pos] = f;
+        inv_map[f] = pos;
+      }
     }
   }
 }
 
 void launch_permute(const int* idx, int Tn, int k, int E, int* counts, int* offsets, int* row_map, int* inv_map,
                     const TileLists& tl, hipStream_t s) {
-  size_t smem = (size_t)(PERM_WAVES * E + E + 1) * sizeof(int);
+  size_t smem = (size_t)(PERM_WAVES * E + 2 * (E + 1)) * sizeof(int);
   hipLaunchKernelGGL(permute_k, dim3(1), dim3(PERM_WAVES * 64), smem, s, idx, Tn * k, E, counts, offsets, row_map,
                      inv_map, tl);
 }
@@ -207,9 +229,48 @@ __global__ void __launch_bounds__(256) combine_k(const T* __restrict__ yp, const
     rs[(i64)t * d + c] = from_f<T>(acc);
   }
 }
+// bf16, d % 8 == 0, 16-byte aligned rows: one lane handles 8 consecutive columns with 16-byte accesses
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+static bool vec8_ok(int dt, int d, std::initializer_list<const void*> ptrs) {
+  if (dt != 1 || (d & 7)) return false;
+  for (const void* q : ptrs) if ((uintptr_t)q & 15) return false;
+  return true;
+}
+__global__ void __launch_bounds__(256) combine_v8_k(const bf16* __restrict__ yp, const int* __restrict__ inv_map,
+                                                    const float* __restrict__ wts, const bf16* __restrict__ ys,
+                                                    const float* __restrict__ gamma, bf16* __restrict__ rs, int d, int k) {
+  const int t = blockIdx.x;
+  for (int c = threadIdx.x * 8; c < d; c += 256 * 8) {
+    float acc[8];
+#pragma unroll
+    for (int q = 0; q < 8; q++) acc[q] = 0.f;
+    for (int s = 0; s < k; s++) {
+      const int pos = inv_map[(i64)t * k + s];
+      const float w = wts[(i64)t * k + s];
+      const bf16x8_t v = *(const bf16x8_t*)(yp + (i64)pos * d + c);
+#pragma unroll
+      for (int q = 0; q < 8; q++) acc[q] += w * (float)v[q];
+    }
+    if (ys) {
+      const float g = gamma[t];
+      const bf16x8_t v = *(const bf16x8_t*)(ys + (i64)t * d + c);
+#pragma unroll
+      for (int q = 0; q < 8; q++) acc[q] += g * (float)v[q];
+    }
+    bf16x8_t o;
+#pragma unroll
+    for (int q = 0; q < 8; q++) o[q] = (__bf16)acc[q];
+    *(bf16x8_t*)(rs + (i64)t * d + c) = o;
+  }
+}
 void launch_combine(int dt, const void* yp, const int* inv_map, const float* wts, const void* ys,
                     const float* gamma, void* rs, int Tn, int d, int k, hipStream_t s) {
   if (Tn <= 0) return;
+  if (vec8_ok(dt, d, {yp, ys, rs})) {
+    hipLaunchKernelGGL(combine_v8_k, dim3(Tn), dim3(256), 0, s, (const bf16*)yp, inv_map, wts, (const bf16*)ys, gamma,
+                       (bf16*)rs, d, k);
+    return;
+  }
   DISPATCH_DT(dt, hipLaunchKernelGGL(combine_k<T>, dim3(Tn), dim3(256), 0, s, (const T*)yp, inv_map, wts,
                                      (const T*)ys, gamma, (T*)rs, d, k));
 }
@@ -252,10 +313,52 @@ __global__ void __launch_bounds__(256) moe_bwd_rows_k(const T* __restrict__ drs,
     if (threadIdx.x == 0) dw[(i64)t * k + s] = acc;
   }
 }
+__global__ void __launch_bounds__(256) moe_bwd_rows_v8_k(const bf16* __restrict__ drs, const bf16* __restrict__ yp,
+                                                         const bf16* __restrict__ ys, const int* __restrict__ inv_map,
+                                                         const float* __restrict__ wts, const float* __restrict__ gamma,
+                                                         bf16* __restrict__ dyp, bf16* __restrict__ dys,
+                                                         float* __restrict__ dw, float* __restrict__ dzext, int d, int k,
+                                                         int E1, int has_gate) {
+  __shared__ float red[4];
+  const int t = blockIdx.x;
+  const bf16* dr = drs + (i64)t * d;
+  if (has_gate) {
+    const float g = gamma[t];
+    float acc = 0.f;
+    for (int c = threadIdx.x * 8; c < d; c += 256 * 8) {
+      const bf16x8_t v = *(const bf16x8_t*)(dr + c), y = *(const bf16x8_t*)(ys + (i64)t * d + c);
+      bf16x8_t o;
+#pragma unroll
+      for (int q = 0; q < 8; q++) { acc += (float)v[q] * (float)y[q]; o[q] = (__bf16)(g * (float)v[q]); }
+      *(bf16x8_t*)(dys + (i64)t * d + c) = o;
+    }
+    acc = block_sum_256(acc, red);
+    if (threadIdx.x == 0) dzext[(i64)t * E1 + (E1 - 1)] = acc * g * (1.f - g);
+  }
+  for (int s = 0; s < k; s++) {
+    const int pos = inv_map[(i64)t * k + s];
+    const float w = wts[(i64)t * k + s];
+    float acc = 0.f;
+    for (int c = threadIdx.x * 8; c < d; c += 256 * 8) {
+      const bf16x8_t v = *(const bf16x8_t*)(dr + c), y = *(const bf16x8_t*)(yp + (i64)pos * d + c);
+      bf16x8_t o;
+#pragma unroll
+      for (int q = 0; q < 8; q++) { acc += (float)v[q] * (float)y[q]; o[q] = (__bf16)(w * (float)v[q]); }
+      *(bf16x8_t*)(dyp + (i64)pos * d + c) = o;
+    }
+    acc = block_sum_256(acc, red);
+    if (threadIdx.x == 0) dw[(i64)t * k + s] = acc;
+  }
+}
 void launch_moe_bwd_rows(int dt, const void* drs, const void* yp, const void* ys, const int* inv_map,
                          const float* wts, const float* gamma, void* dyp, void* dys, float* dw, float* dzext,
                          int Tn, int d, int k, int E1, int has_gate, hipStream_t s) {
   if (Tn <= 0) return;
+  if (vec8_ok(dt, d, {drs, yp, ys, dyp, dys})) {
+    hipLaunchKernelGGL(moe_bwd_rows_v8_k, dim3(Tn), dim3(256), 0, s, (const bf16*)drs, (const bf16*)yp, (const bf16*)ys,
+                       inv_map, wts, gamma, (bf16*)dyp, (bf16*)dys, dw, dzext, d, k, E1, has_gate);
+    return;
+  }
   DISPATCH_DT(dt, hipLaunchKernelGGL(moe_bwd_rows_k<T>, dim3(Tn), dim3(256), 0, s, (const T*)drs, (const T*)yp,
                                      (const T*)ys, inv_map, wts, gamma, (T*)dyp, (T*)dys, dw, dzext, d, k, E1,
                                      has_gate));
@@ -265,40 +368,35 @@ void launch_moe_bwd_rows(int dt, const void* drs, const void* yp, const void* ys
 // Backward of softmax + top-k weights (the selection itself carries no gradient):
 //   dp_sel = dw                      (or (dw - sum dw*w) / sum_sel p with renormalisation)
 //   dz_j   = p_j * ([j selected] dp_j - sum_sel dp_e p_e)        for every expert j
-// One thread per token; writes columns 0..E-1 of dzext[T,E1].
+// One wave per token, lanes over the experts; writes columns 0..E-1 of dzext[T,E1].
 // ---------------------------------------------------------------------------------
 __global__ void __launch_bounds__(256) router_bwd_k(const float* __restrict__ probs, const int* __restrict__ idx,
                                                     const float* __restrict__ wts, const float* __restrict__ dw,
                                                     float* __restrict__ dzext, int Tn, int E, int k, int E1,
                                                     int norm_topk) {
-  int t = blockIdx.x * 256 + threadIdx.x;
-  if (t >= Tn) return;
+  const int t = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (t >= Tn) return;                     // whole wave
   const float* p = probs + (i64)t * E;
-  float dps[16];
-  int sel[16];
+  // slot s lives in lane s (k <= 16); sums over the slots run in slot order on every lane
+  const int my_sel = lane < k ? idx[(i64)t * k + lane] : -1;
+  const float my_dw = lane < k ? dw[(i64)t * k + lane] : 0.f;
+  const float my_w = lane < k ? wts[(i64)t * k + lane] : 0.f;
+  const float my_p = lane < k ? p[my_sel] : 0.f;
   float ssum = 0.f, dww = 0.f;
-  for (int s = 0; s < k; s++) {
-    sel[s] = idx[(i64)t * k + s];
-    ssum += p[sel[s]];
-    dww += dw[(i64)t * k + s] * wts[(i64)t * k + s];
-  }
+  for (int s = 0; s < k; s++) { ssum += __shfl(my_p, s, WAVE); dww += __shfl(my_dw, s, WAVE) * __shfl(my_w, s, WAVE); }
+  const float my_dp = norm_topk ? (my_dw - dww) / ssum : my_dw;
   float inner = 0.f;
-  for (int s = 0; s < k; s++) {
-    float v = dw[(i64)t * k + s];
-    if (norm_topk) v = (v - dww) / ssum;
-    dps[s] = v;
-    inner += v * p[sel[s]];
-  }
-  for (int j = 0; j < E; j++) {
+  for (int s = 0; s < k; s++) inner += __shfl(my_dp, s, WAVE) * __shfl(my_p, s, WAVE);
+  for (int j = lane; j < E; j += 64) {
     float dp = 0.f;
-    for (int s = 0; s < k; s++) if (sel[s] == j) dp = dps[s];
+    for (int s = 0; s < k; s++) { const int sel = __shfl(my_sel, s, WAVE); const float v = __shfl(my_dp, s, WAVE); if (sel == j) dp = v; }
     dzext[(i64)t * E1 + j] = p[j] * (dp - inner);
   }
 }
 void launch_router_bwd(const float* probs, const int* idx, const float* wts, const float* dw, float* dzext, int Tn,
                        int E, int k, int E1, int norm_topk, hipStream_t s) {
   if (Tn <= 0) return;
-  hipLaunchKernelGGL(router_bwd_k, dim3(cdiv(Tn, 256)), dim3(256), 0, s, probs, idx, wts, dw, dzext, Tn, E, k, E1,
+  hipLaunchKernelGGL(router_bwd_k, dim3(cdiv(Tn, 4)), dim3(256), 0, s, probs, idx, wts, dw, dzext, Tn, E, k, E1,
                      norm_topk);
 }
 
@@ -334,10 +432,40 @@ __global__ void __launch_bounds__(256) dum_finalize_k(const T* __restrict__ dxg,
     dum[(i64)t * d + c] = from_f<T>(acc);
   }
 }
+__global__ void __launch_bounds__(256) dum_finalize_v8_k(const bf16* __restrict__ dxg, const int* __restrict__ inv_map,
+                                                         const bf16* __restrict__ dum_sh, const bf16* __restrict__ dum_r,
+                                                         bf16* __restrict__ dum, int d, int k) {
+  const int t = blockIdx.x;
+  for (int c = threadIdx.x * 8; c < d; c += 256 * 8) {
+    float acc[8];
+#pragma unroll
+    for (int q = 0; q < 8; q++) acc[q] = 0.f;
+    if (dum_sh) {
+      const bf16x8_t v = *(const bf16x8_t*)(dum_sh + (i64)t * d + c);
+#pragma unroll
+      for (int q = 0; q < 8; q++) acc[q] = (float)v[q];
+    }
+    for (int s = 0; s < k; s++) {
+      const bf16x8_t v = *(const bf16x8_t*)(dxg + (i64)inv_map[(i64)t * k + s] * d + c);
+#pragma unroll
+      for (int q = 0; q < 8; q++) acc[q] += (float)v[q];
+    }
+    const bf16x8_t r = *(const bf16x8_t*)(dum_r + (i64)t * d + c);
+    bf16x8_t o;
+#pragma unroll
+    for (int q = 0; q < 8; q++) o[q] = (__bf16)(acc[q] + (float)r[q]);
+    *(bf16x8_t*)(dum + (i64)t * d + c) = o;
+  }
+}
 void launch_dum_finalize(int dt, const void* dxg, const int* inv_map, const void* dum_sh, const void* dum_r,
                          const float* dzext, const void* w_router, const void* ws_gate, void* dum, int Tn, int d,
                          int k, int E, int E1, hipStream_t s) {
   if (Tn <= 0) return;
+  if (dum_r && vec8_ok(dt, d, {dxg, dum_sh, dum_r, dum})) {
+    hipLaunchKernelGGL(dum_finalize_v8_k, dim3(Tn), dim3(256), 0, s, (const bf16*)dxg, inv_map, (const bf16*)dum_sh,
+                       (const bf16*)dum_r, (bf16*)dum, d, k);
+    return;
+  }
   DISPATCH_DT(dt, hipLaunchKernelGGL(dum_finalize_k<T>, dim3(Tn), dim3(256), E1 * sizeof(float), s, (const T*)dxg,
                                      inv_map, (const T*)dum_sh, (const T*)dum_r, dzext, (const T*)w_router,
                                      (const T*)ws_gate, (T*)dum, d, k, E, E1));
