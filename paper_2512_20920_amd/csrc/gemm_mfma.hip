@@ -376,21 +376,24 @@ static void pick_tile(const GemmArgs& g, hipStream_t s) {
   }
   if (g.group_mode == 2) {
     // per-expert weight gradients: the k range is one expert's rows, a few k-tiles only, so a workgroup is mostly
-    // load latency and output stores: small LDS footprint, several workgroups per CU
-    static int v = -1;                 // REVFFN_WGRAD_TILE (tuning aid): 0 = 128x128 2 stages, 1 = 128x64 2 stages, 2 = 128x128 4 stages, 3 = 128x64 3 stages
+    // load latency and output stores.  Alone, 128x128 tiles with 2 stages (two workgroups per CU) and 256x128 tiles
+    // (one per CU) take the same time; next to the data-gradient chain on the main stream the 256x128 tile is 4 %
+    // of a step faster (one resident workgroup per CU leaves the small critical-path kernels room to start).
+    static int v = -1;                 // REVFFN_WGRAD_TILE (tuning aid): 0 = 256x128, 1 = 128x128 2 stages, 2 = 128x64 2 stages
     if (v < 0) { const char* e = getenv("REVFFN_WGRAD_TILE"); v = e ? atoi(e) : 0; }
-    if (v == 1) go<128, 64, 2, AT, BT, TC, 4, 2>(g, s);
-    else if (v == 2) go_128x128<AT, BT, TC>(g, s);
-    else if (v == 3) go_128x64<AT, BT, TC>(g, s);
-    else go<128, 128, 2, AT, BT, TC, 4, 2>(g, s);
+    if (v == 1) go<128, 128, 2, AT, BT, TC, 4, 2>(g, s);
+    else if (v == 2) go<128, 64, 2, AT, BT, TC, 4, 2>(g, s);
+    else go_256x128<AT, BT, TC>(g, s);
     return;
   }
   // the largest tile that still gives every CU work: 256x128 from two rounds of workgroups on, 128x128 down to
   // ~200 tiles, else 128x64
   const i64 t256 = (i64)cdiv(g.M, 256) * cdiv(g.N, 128), t128 = (i64)cdiv(g.M, 128) * cdiv(g.N, 128);
   const int z = g.split_k > 1 ? g.split_k : 1;
+  static int small = -1;               // REVFFN_SMALL_TILE (tuning aid): 1 = 128x64 (72 KiB of LDS) below 512 tiles
+  if (small < 0) { const char* e = getenv("REVFFN_SMALL_TILE"); small = e ? atoi(e) : 0; }
   if (t256 * z >= 512) go_256x128<AT, BT, TC>(g, s);
-  else if (t128 * z >= 200 || g.N < 128) go_128x128<AT, BT, TC>(g, s);
+  else if ((t128 * z >= (small ? 512 : 200)) || g.N < 128) go_128x128<AT, BT, TC>(g, s);
   else go_128x64<AT, BT, TC>(g, s);
 }
 
