@@ -125,6 +125,9 @@ def main():
     ap.add_argument("--workload", default="qwen_b4s512")
     ap.add_argument("--inv-iters", type=int, default=1, help="fixed-point iterations of the inverse (paper: 1)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run three plain 256 MiB device-to-device copies (the known-size reference for scaling "
+                         "rocprofv3's FETCH_SIZE / WRITE_SIZE counters) and exit")
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="skip the second pass with per-launch HIP events (no roofline object)")
     ap.add_argument("--separate-calls", action="store_true",
@@ -143,6 +146,15 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(1)
+    if args.copy_calibration:
+        a = torch.empty(256 * 1024 * 1024, dtype=torch.uint8, device="cuda")
+        b = torch.empty_like(a)
+        a.fill_(1)
+        for _ in range(3):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes": a.numel(), "copies": 3}))
+        return
     wl = synth.WORKLOADS[args.workload]
     if wl.n_blocks > 1:
         return bench_stack(args, wl)

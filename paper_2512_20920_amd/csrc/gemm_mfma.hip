@@ -105,7 +105,7 @@ __device__ __forceinline__ bf16x8 load_frag(const unsigned char* tile, unsigned 
   }
 }
 
-// One output tile: TE 32-row blocks per wave (TE = the wave tile's full height except in the SKIP kernels).
+// One output tile; TE = 32-row blocks per wave.
 template <int BM, int BN, int WGM, bool AT, bool BT, class TC, int NW, int NS, int TE>
 __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const bf16* A, const bf16* Bm, TC* C, int bx, int bz,
                                           int m0, int m_end, int k0, int k_end) {
@@ -253,13 +253,9 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const bf16* A, cons
   }
 }
 
-// SKIP (expert tiles, WGM = 1: every wave spans all BM rows): a tile whose expert ends early multiplies only the
-// 32-row blocks that hold rows, TE = ceil(rows / 32) of them, through a loop specialised for TE; such a tile still
-// streams its whole weight panel, but costs TE / 4 of the matrix-core time.
-template <int BM, int BN, int WGM, bool AT, bool BT, class TC, int NW, int NS, bool SKIP>
+template <int BM, int BN, int WGM, bool AT, bool BT, class TC, int NW, int NS>
 __global__ void __launch_bounds__(NW * 64) gemm_mfma_k(GemmArgs g) {
   constexpr int TM = BM / WGM / 32;
-  static_assert(!SKIP || WGM == 1, "row-block skipping needs waves that span all rows of the tile");
   const bf16* A = (const bf16*)g.A;
   const bf16* Bm = (const bf16*)g.B;
   TC* C = (TC*)g.C;
@@ -290,12 +286,6 @@ __global__ void __launch_bounds__(NW * 64) gemm_mfma_k(GemmArgs g) {
       k_end = min(g.K, k0 + per);
     }
   }
-  if (SKIP) {
-    const int te = (m_end - m0 + 31) >> 5;             // uniform over the workgroup
-    if (te == 1) { gemm_tile<BM, BN, WGM, AT, BT, TC, NW, NS, 1>(g, A, Bm, C, bx, bz, m0, m_end, k0, k_end); return; }
-    if (TM > 2 && te == 2) { gemm_tile<BM, BN, WGM, AT, BT, TC, NW, NS, (TM > 2 ? 2 : TM)>(g, A, Bm, C, bx, bz, m0, m_end, k0, k_end); return; }
-    if (TM > 3 && te == 3) { gemm_tile<BM, BN, WGM, AT, BT, TC, NW, NS, (TM > 3 ? 3 : TM)>(g, A, Bm, C, bx, bz, m0, m_end, k0, k_end); return; }
-  }
   gemm_tile<BM, BN, WGM, AT, BT, TC, NW, NS, TM>(g, A, Bm, C, bx, bz, m0, m_end, k0, k_end);
 }
 
@@ -306,7 +296,7 @@ static int xcd_enabled() {
   return v;
 }
 
-template <int BM, int BN, int WGM, bool AT, bool BT, class TC, int NW, int NS, bool SKIP = false>
+template <int BM, int BN, int WGM, bool AT, bool BT, class TC, int NW, int NS>
 static void go(const GemmArgs& g0, hipStream_t s) {
   GemmArgs g = g0;
   g.tiles_n = cdiv(g.N, BN);
@@ -331,21 +321,23 @@ static void go(const GemmArgs& g0, hipStream_t s) {
   static_assert(smem <= 160 * 1024, "LDS stages exceed the CU's 160 KiB");
   static bool attr_set = false;
   if (!attr_set) {
-    (void)hipFuncSetAttribute((const void*)gemm_mfma_k<BM, BN, WGM, AT, BT, TC, NW, NS, SKIP>,
+    (void)hipFuncSetAttribute((const void*)gemm_mfma_k<BM, BN, WGM, AT, BT, TC, NW, NS>,
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     attr_set = true;
   }
-  hipLaunchKernelGGL((gemm_mfma_k<BM, BN, WGM, AT, BT, TC, NW, NS, SKIP>), grid, dim3(NW * 64), smem, s, g);
+  hipLaunchKernelGGL((gemm_mfma_k<BM, BN, WGM, AT, BT, TC, NW, NS>), grid, dim3(NW * 64), smem, s, g);
 }
 
 // The four tile shapes: 256x128 (8 waves, one workgroup per CU), 128x128 (4 waves, 4 stages), 128x64 and 64x128
 // (4 waves, two workgroups per CU).
 template <bool AT, bool BT, class TC> static void go_256x128(const GemmArgs& g, hipStream_t s) { go<256, 128, 4, AT, BT, TC, 8, 3>(g, s); }
+template <bool AT, bool BT, class TC> static void go_256x256(const GemmArgs& g, hipStream_t s) { go<256, 256, 2, AT, BT, TC, 8, 2>(g, s); }
 template <bool AT, bool BT, class TC> static void go_128x128(const GemmArgs& g, hipStream_t s) { go<128, 128, 2, AT, BT, TC, 4, 4>(g, s); }
 template <bool AT, bool BT, class TC> static void go_128x64(const GemmArgs& g, hipStream_t s) { go<128, 64, 2, AT, BT, TC, 4, 3>(g, s); }
 template <bool AT, bool BT, class TC> static void go_64x128(const GemmArgs& g, hipStream_t s) { go<64, 128, 1, AT, BT, TC, 4, 3>(g, s); }
 
-// REVFFN_GEMM_TILE (tuning aid): 1 = 128x128, 2 = 128x64, 3 = 64x128, 4 = 256x128 for every non-grouped problem
+// REVFFN_GEMM_TILE (tuning aid): 1 = 128x128, 2 = 128x64, 3 = 64x128, 4 = 256x128, 5 = 256x256 (2 stages; measured
+// +3 % at 8192^3, worse on the block's shapes) for every non-grouped problem
 static int tile_override() {
   static int v = -1;
   if (v < 0) { const char* e = getenv("REVFFN_GEMM_TILE"); v = e ? atoi(e) : 0; }
@@ -360,18 +352,17 @@ static void pick_tile(const GemmArgs& g, hipStream_t s) {
       case 2: go_128x64<AT, BT, TC>(g, s); return;
       case 3: go_64x128<AT, BT, TC>(g, s); return;
       case 4: go_256x128<AT, BT, TC>(g, s); return;
+      case 5: go_256x256<AT, BT, TC>(g, s); return;
     }
   }
   if (g.group_mode == 1) {
-    // expert tiles: waves side by side along n, each spanning all rows, so that a tile whose expert ends early
-    // multiplies only the 32-row blocks that hold rows
-    static int v = -1;                 // REVFFN_GROUPED_VARIANT (tuning aid): 0 = skipping, 4 stages; 1 = 2x2 waves, no skipping; 2 = skipping, 2 stages
-    if (v < 0) { const char* e = getenv("REVFFN_GROUPED_VARIANT"); v = e ? atoi(e) : 0; }
-    if (g.tile_bm == 64) go<64, 128, 1, AT, BT, TC, 4, 3, true>(g, s);
-    else if (g.tile_bm == 256) go_256x128<AT, BT, TC>(g, s);
-    else if (v == 1) go_128x128<AT, BT, TC>(g, s);
-    else if (v == 2) go<128, 128, 1, AT, BT, TC, 4, 2, true>(g, s);
-    else go<128, 128, 1, AT, BT, TC, 4, 4, true>(g, s);
+    // expert tiles.  Skipping the MFMAs of the 32-row blocks past an expert's end (waves spanning all rows, a loop
+    // specialised per block count) measured no gain, and neither did a fifth LDS stage.
+    if constexpr (!AT) {
+      if (g.tile_bm == 64) go_64x128<AT, BT, TC>(g, s);
+      else if (g.tile_bm == 256) go_256x128<AT, BT, TC>(g, s);
+      else go_128x128<AT, BT, TC>(g, s);
+    }
     return;
   }
   if (g.group_mode == 2) {
@@ -390,10 +381,8 @@ static void pick_tile(const GemmArgs& g, hipStream_t s) {
   // ~200 tiles, else 128x64
   const i64 t256 = (i64)cdiv(g.M, 256) * cdiv(g.N, 128), t128 = (i64)cdiv(g.M, 128) * cdiv(g.N, 128);
   const int z = g.split_k > 1 ? g.split_k : 1;
-  static int small = -1;               // REVFFN_SMALL_TILE (tuning aid): 1 = 128x64 (72 KiB of LDS) below 512 tiles
-  if (small < 0) { const char* e = getenv("REVFFN_SMALL_TILE"); small = e ? atoi(e) : 0; }
   if (t256 * z >= 512) go_256x128<AT, BT, TC>(g, s);
-  else if ((t128 * z >= (small ? 512 : 200)) || g.N < 128) go_128x128<AT, BT, TC>(g, s);
+  else if ((t128 * z >= 200) || g.N < 128) go_128x128<AT, BT, TC>(g, s);
   else go_128x64<AT, BT, TC>(g, s);
 }
 
