@@ -1,6 +1,7 @@
 // Memory-bound kernels of the RevFFN block: RMSNorm (Norm of Eq. 1-2) forward and
 // backward, rotary encoding, SwiGLU, row gathers/copies, deterministic column sums.
 #include "kernels.h"
+#include <initializer_list>
 
 #define DISPATCH_DT(dt, ...)                                  \
   do {                                                        \
@@ -26,9 +27,45 @@ __global__ void __launch_bounds__(256) rmsnorm_fwd_k(const T* __restrict__ x, i6
   for (int j = lane; j < h; j += 64) orow[j] = from_f<T>(to_f(xr[j]) * r * to_f(g[j]));
 }
 
+// bf16 rows of h % 8 == 0 elements at 16-byte aligned addresses: 16-byte accesses, 8 elements per lane
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_v;
+static bool rows_vec8(int dt, int h, std::initializer_list<const void*> ptrs, std::initializer_list<i64> lds) {
+  if (dt != 1 || (h & 7)) return false;
+  for (const void* q : ptrs) if ((uintptr_t)q & 15) return false;
+  for (i64 l : lds) if (l & 7) return false;
+  return true;
+}
+__global__ void __launch_bounds__(256) rmsnorm_fwd_v8_k(const bf16* __restrict__ x, i64 ldx, const bf16* __restrict__ g,
+                                                        bf16* __restrict__ out, i64 ldo, int rows, int h, float eps) {
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (row >= rows) return;
+  const bf16* xr = x + (i64)row * ldx;
+  float ss = 0.f;
+  for (int j = lane * 8; j < h; j += 512) {
+    const bf16x8_v v = *(const bf16x8_v*)(xr + j);
+#pragma unroll
+    for (int q = 0; q < 8; q++) ss += (float)v[q] * (float)v[q];
+  }
+  ss = wave_sum(ss);
+  const float r = 1.0f / sqrtf(ss / (float)h + eps);
+  bf16* orow = out + (i64)row * ldo;
+  for (int j = lane * 8; j < h; j += 512) {
+    const bf16x8_v v = *(const bf16x8_v*)(xr + j), gv = *(const bf16x8_v*)(g + j);
+    bf16x8_v o;
+#pragma unroll
+    for (int q = 0; q < 8; q++) o[q] = (__bf16)((float)v[q] * r * (float)gv[q]);
+    *(bf16x8_v*)(orow + j) = o;
+  }
+}
+
 void launch_rmsnorm_fwd(int dt, const void* x, i64 ldx, const void* g, void* out, i64 ldo, int rows, int h,
                         float eps, hipStream_t s) {
   if (rows <= 0) return;
+  if (rows_vec8(dt, h, {x, g, out}, {ldx, ldo})) {
+    hipLaunchKernelGGL(rmsnorm_fwd_v8_k, dim3(cdiv(rows, 4)), dim3(256), 0, s, (const bf16*)x, ldx, (const bf16*)g,
+                       (bf16*)out, ldo, rows, h, eps);
+    return;
+  }
   DISPATCH_DT(dt, hipLaunchKernelGGL(rmsnorm_fwd_k<T>, dim3(cdiv(rows, 4)), dim3(256), 0, s, (const T*)x, ldx,
                                      (const T*)g, (T*)out, ldo, rows, h, eps));
 }
@@ -63,9 +100,49 @@ __global__ void __launch_bounds__(256) rmsnorm_bwd_k(const T* __restrict__ dy, i
   }
 }
 
+__global__ void __launch_bounds__(256) rmsnorm_bwd_v8_k(const bf16* __restrict__ dy, i64 ldd, const bf16* __restrict__ x,
+                                                        i64 ldx, const bf16* __restrict__ g, const bf16* base, i64 ldb,
+                                                        bf16* dx, i64 ldo, float* __restrict__ rinv, int rows, int h,
+                                                        float eps) {
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (row >= rows) return;
+  const bf16* xr = x + (i64)row * ldx;
+  const bf16* dr = dy + (i64)row * ldd;
+  float ss = 0.f, sd = 0.f;
+  for (int j = lane * 8; j < h; j += 512) {
+    const bf16x8_v v = *(const bf16x8_v*)(xr + j), gv = *(const bf16x8_v*)(g + j), d = *(const bf16x8_v*)(dr + j);
+#pragma unroll
+    for (int q = 0; q < 8; q++) { ss += (float)v[q] * (float)v[q]; sd += (float)v[q] * (float)gv[q] * (float)d[q]; }
+  }
+  ss = wave_sum(ss);
+  sd = wave_sum(sd);
+  const float r = 1.0f / sqrtf(ss / (float)h + eps);
+  const float c = r * r * r * sd / (float)h;
+  if (lane == 0) rinv[row] = r;
+  for (int j = lane * 8; j < h; j += 512) {
+    // (dx may alias base or dy: every lane reads its 8 elements of all inputs before it writes them)
+    const bf16x8_v v = *(const bf16x8_v*)(xr + j), gv = *(const bf16x8_v*)(g + j), d = *(const bf16x8_v*)(dr + j);
+    bf16x8_v b;
+    if (base) b = *(const bf16x8_v*)(base + (i64)row * ldb + j);
+    bf16x8_v o;
+#pragma unroll
+    for (int q = 0; q < 8; q++) {
+      float t = r * (float)gv[q] * (float)d[q] - (float)v[q] * c;
+      if (base) t += (float)b[q];
+      o[q] = (__bf16)t;
+    }
+    *(bf16x8_v*)(dx + (i64)row * ldo + j) = o;
+  }
+}
+
 void launch_rmsnorm_bwd(int dt, const void* dy, i64 ldd, const void* x, i64 ldx, const void* g, const void* base,
                         i64 ldb, void* dx, i64 ldo, float* rinv, int rows, int h, float eps, hipStream_t s) {
   if (rows <= 0) return;
+  if (rows_vec8(dt, h, {dy, x, g, base, dx}, {ldd, ldx, ldb, ldo})) {
+    hipLaunchKernelGGL(rmsnorm_bwd_v8_k, dim3(cdiv(rows, 4)), dim3(256), 0, s, (const bf16*)dy, ldd, (const bf16*)x, ldx,
+                       (const bf16*)g, (const bf16*)base, ldb, (bf16*)dx, ldo, rinv, rows, h, eps);
+    return;
+  }
   DISPATCH_DT(dt, hipLaunchKernelGGL(rmsnorm_bwd_k<T>, dim3(cdiv(rows, 4)), dim3(256), 0, s, (const T*)dy, ldd,
                                      (const T*)x, ldx, (const T*)g, (const T*)base, ldb, (T*)dx, ldo, rinv, rows,
                                      h, eps));
