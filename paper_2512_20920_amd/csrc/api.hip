@@ -553,22 +553,20 @@ int backward_impl(revffn_ctx* c, const revffn_weights* w, const void* x1, const 
     TRY(run_gemm(c, e, s));
   }
   launch_router_bwd(c->probs, c->idx, c->wts, c->dw, c->dzext, T, E, k, E1, f.norm_topk_prob, s);
+  // every column sum (bias and gain gradients) goes to helper stream 2: they share one scratch buffer, and the
+  // weight-gradient GEMMs keep helper stream 1 to themselves.  The router weight gradient goes there too.
+  hipStream_t sc = side(c, s, 2);
+  if (GF(w_router) || (Is && GF(ws_gate)) || (g && g->b_router)) after(c, s, sc);
   if (GF(w_router) || (Is && GF(ws_gate))) {
     // [dW_r ; dw_shared_gate] = dzext^T . Um in one fp32-A split-k GEMM, then the rows go to their buffers
     GemmArgs a = tn(c->dzext, E1, c->Um, d, c->dwr_tmp, d, E1, d, T);
     a.split_k = SPLIT_DWR; a.splitk_ws = c->splitk_ws;
     GemmTypes t{0, dt, dt, dt};
-    if (launch_gemm_generic(a, t, s)) return REVFFN_EUNSUPPORTED;
-    if (GF(w_router)) launch_copy_rows(dt, c->dwr_tmp, d, GF(w_router), d, E, d, s);
-    if (Is && GF(ws_gate)) launch_copy_rows(dt, at(c->dwr_tmp, (size_t)E * d, es), d, GF(ws_gate), d, 1, d, s);
+    if (launch_gemm_generic(a, t, sc)) return REVFFN_EUNSUPPORTED;
+    if (GF(w_router)) launch_copy_rows(dt, c->dwr_tmp, d, GF(w_router), d, E, d, sc);
+    if (Is && GF(ws_gate)) launch_copy_rows(dt, at(c->dwr_tmp, (size_t)E * d, es), d, GF(ws_gate), d, 1, d, sc);
   }
-  // every column sum (bias and gain gradients) goes to helper stream 2: they share one scratch buffer, and the
-  // weight-gradient GEMMs keep helper stream 1 to themselves
-  hipStream_t sc = side(c, s, 2);
-  if (g && g->b_router) {
-    after(c, s, sc);
-    launch_colsum(0, c->dzext, E1, 0, nullptr, 0, nullptr, 0, g->b_router, c->partial, T, E, sc);
-  }
+  if (g && g->b_router) launch_colsum(0, c->dzext, E1, 0, nullptr, 0, nullptr, 0, g->b_router, c->partial, T, E, sc);
   if (Is) after(c, s0, s);
   const void* dum_r = nullptr;
   if (dt == 1 && c->mode == 0) {

@@ -235,10 +235,39 @@ __global__ void __launch_bounds__(256) rope_k(T* __restrict__ buf, const float2*
   p[i + half] = from_f<T>(b * c.x + a * sn);
 }
 
+// bf16, half % 8 == 0: one lane rotates 8 consecutive pairs of one (token, head) with 16-byte accesses
+__global__ void __launch_bounds__(256) rope_v8_k(bf16* __restrict__ buf, const float2* __restrict__ cs, int total8,
+                                                 int S, int H, int half8, float sign) {
+  const int e = blockIdx.x * 256 + threadIdx.x;
+  if (e >= total8) return;
+  const int i = (e % half8) * 8;
+  const int th = e / half8;          // token*H + head
+  const int spos = (th / H) % S;
+  const int half = half8 * 8;
+  bf16* p = buf + (i64)th * (2 * half) + i;
+  const bf16x8_v a = *(const bf16x8_v*)p, b = *(const bf16x8_v*)(p + half);
+  const float2* c = cs + (i64)spos * half + i;
+  bf16x8_v oa, ob;
+#pragma unroll
+  for (int q = 0; q < 8; q++) {
+    const float2 cq = c[q];
+    const float sn = sign * cq.y, av = (float)a[q], bv = (float)b[q];
+    oa[q] = (__bf16)(av * cq.x - bv * sn);
+    ob[q] = (__bf16)(bv * cq.x + av * sn);
+  }
+  *(bf16x8_v*)p = oa;
+  *(bf16x8_v*)(p + half) = ob;
+}
+
 void launch_rope(int dt, void* buf, const float* cs_table, int Tn, int S, int H, int dh, float sign,
                  hipStream_t s) {
   i64 total = (i64)Tn * H * (dh / 2);
   if (total <= 0) return;
+  if (dt == 1 && (dh & 15) == 0 && ((uintptr_t)buf & 15) == 0 && total / 8 < (i64)1 << 31) {
+    hipLaunchKernelGGL(rope_v8_k, dim3(cdiv(total / 8, 256)), dim3(256), 0, s, (bf16*)buf, (const float2*)cs_table,
+                       (int)(total / 8), S, H, dh / 16, sign);
+    return;
+  }
   DISPATCH_DT(dt, hipLaunchKernelGGL(rope_k<T>, dim3(cdiv(total, 256)), dim3(256), 0, s, (T*)buf,
                                      (const float2*)cs_table, total, S, H, dh / 2, sign));
 }
