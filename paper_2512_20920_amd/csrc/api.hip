@@ -298,25 +298,52 @@ void after(revffn_ctx* c, hipStream_t from, hipStream_t to) {
   (void)hipEventRecord(e, from);
   (void)hipStreamWaitEvent(to, e, 0);
 }
+// the two halves of after(): an event that marks what `from` holds now, waited for later
+hipEvent_t mark(revffn_ctx* c, hipStream_t from) {
+  hipEvent_t e = next_sync(c);
+  (void)hipEventRecord(e, from);
+  return e;
+}
+void wait_for(hipStream_t to, hipEvent_t e) { (void)hipStreamWaitEvent(to, e, 0); }
 // helper stream i, or the main stream when helper streams are switched off
 hipStream_t side(revffn_ctx* c, hipStream_t main, int i) { return c->use_streams ? c->side[i] : main; }
 
 // ---- attention half ---------------------------------------------------------------
-// Recomputes n12, U12, Q, (K, V), O, lse, AO at streams (x1, x2).
-int attn_acts(revffn_ctx* c, const revffn_weights* w, const void* x1, i64 ld1, const void* x2, i64 ld2, int B, int S,
-              bool do_kv, hipStream_t s) {
+// Query side of the attention half at x1: n12[0:T], U12[0:T], Q.
+int attn_q(revffn_ctx* c, const revffn_weights* w, const void* x1, i64 ld1, int B, int S, hipStream_t s) {
   const revffn_config& f = c->cfg;
-  const int T = B * S, d = f.d_model, h = d / 2, es = c->es, dt = c->dt;
+  const int T = B * S, d = f.d_model, h = d / 2, dt = c->dt;
   launch_rmsnorm_fwd(dt, x1, ld1, w->norm_a1, c->n12, h, T, h, f.rms_eps, s);
-  if (do_kv) launch_rmsnorm_fwd(dt, x2, ld2, w->norm_a2, at(c->n12, (size_t)T * h, es), h, T, h, f.rms_eps, s);
-  // the same P_up serves both streams: one GEMM over the stacked rows
-  TRY(run_gemm(c, nt(c->n12, h, w->pup_a, h, c->U12, d, do_kv ? 2 * T : T, d, h), s));
-  hipStream_t s0 = side(c, s, 0), s1 = side(c, s, 1);
-  if (do_kv) { after(c, s, s0); after(c, s, s1); }
+  TRY(run_gemm(c, nt(c->n12, h, w->pup_a, h, c->U12, d, T, d, h), s));
   GemmArgs gq = nt(c->U12, d, w->wq, d, c->Q, d, T, d, d);
   gq.bias = w->bq;
   TRY(run_gemm(c, gq, s));
   if (f.use_rope) launch_rope(dt, c->Q, c->rope_cs, T, S, f.n_heads, f.head_dim, 1.f, s);
+  return 0;
+}
+// Recomputes n12, U12, Q, (K, V), O, lse, AO at streams (x1, x2).  q_done: attn_q(x1) has been enqueued already.
+int attn_acts(revffn_ctx* c, const revffn_weights* w, const void* x1, i64 ld1, const void* x2, i64 ld2, int B, int S,
+              bool do_kv, hipStream_t s, bool q_done = false) {
+  const revffn_config& f = c->cfg;
+  const int T = B * S, d = f.d_model, h = d / 2, es = c->es, dt = c->dt;
+  hipStream_t s0 = side(c, s, 0), s1 = side(c, s, 1);
+  if (q_done) {
+    if (do_kv) {
+      launch_rmsnorm_fwd(dt, x2, ld2, w->norm_a2, at(c->n12, (size_t)T * h, es), h, T, h, f.rms_eps, s);
+      TRY(run_gemm(c, nt(at(c->n12, (size_t)T * h, es), h, w->pup_a, h, at(c->U12, (size_t)T * d, es), d, T, d, h), s));
+      after(c, s, s0); after(c, s, s1);
+    }
+  } else {
+    launch_rmsnorm_fwd(dt, x1, ld1, w->norm_a1, c->n12, h, T, h, f.rms_eps, s);
+    if (do_kv) launch_rmsnorm_fwd(dt, x2, ld2, w->norm_a2, at(c->n12, (size_t)T * h, es), h, T, h, f.rms_eps, s);
+    // the same P_up serves both streams: one GEMM over the stacked rows
+    TRY(run_gemm(c, nt(c->n12, h, w->pup_a, h, c->U12, d, do_kv ? 2 * T : T, d, h), s));
+    if (do_kv) { after(c, s, s0); after(c, s, s1); }
+    GemmArgs gq = nt(c->U12, d, w->wq, d, c->Q, d, T, d, d);
+    gq.bias = w->bq;
+    TRY(run_gemm(c, gq, s));
+    if (f.use_rope) launch_rope(dt, c->Q, c->rope_cs, T, S, f.n_heads, f.head_dim, 1.f, s);
+  }
   if (do_kv) {
     const void* U2 = at(c->U12, (size_t)T * d, es);
     GemmArgs gk = nt(U2, d, w->wk, d, c->K, d, T, d, d);
@@ -369,8 +396,10 @@ void router_fold(revffn_ctx* c, const revffn_weights* w, hipStream_t s) {
   c->fold_queued = true;
 }
 
-// Recomputes n3, Um, routing, GU, Hh, Yp, shared expert and RS at y1.
-int moe_acts(revffn_ctx* c, const revffn_weights* w, const void* y1, i64 ld, int T, hipStream_t s) {
+// Recomputes n3, Um, routing, GU, Hh, Yp, shared expert and RS at y1.  q_x1 != null: the query side of the attention
+// half at q_x1 (which must not depend on this MoE evaluation) is enqueued on s while the routing chain runs.
+int moe_acts(revffn_ctx* c, const revffn_weights* w, const void* y1, i64 ld, int T, hipStream_t s,
+             const void* q_x1 = nullptr, i64 q_ld = 0, int qB = 0, int qS = 0) {
   const revffn_config& f = c->cfg;
   const int d = f.d_model, h = d / 2, E = f.n_experts, k = f.top_k, I = f.d_expert, Is = f.d_shared, dt = c->dt;
   const int N = T * k, E1 = E + (Is ? 1 : 0);
@@ -402,6 +431,7 @@ int moe_acts(revffn_ctx* c, const revffn_weights* w, const void* y1, i64 ld, int
     launch_swiglu_fwd(dt, c->GUs, c->Hs, T, Is, s0);
     TRY(run_gemm(c, nt(c->Hs, Is, w->ws_down, Is, c->Ys, d, T, d, Is), s0));
   }
+  if (q_x1) TRY(attn_q(c, w, q_x1, q_ld, qB, qS, s));
   after(c, sr, s);                        // routing and permutation are ready
   // routed experts: GU = Xg . Wgu_e^T (rows gathered from Um through row_map), SwiGLU, Yp = Hh . Wd_e^T
   GemmArgs g1 = nt(c->Um, d, w->w_gate_up, d, c->GU, 2 * I, N, 2 * I, d);
@@ -463,7 +493,9 @@ int inverse_impl(revffn_ctx* c, const revffn_weights* w, const void* y1, const v
     y1k = c->y1c;
     ldk = h;
   }
-  TRY(moe_acts(c, w, y1k, ldk, T, s));
+  // the first fixed-point iterate is Y1 itself, so its query side does not wait for X2^: it fills the main stream
+  // while the routing chain runs
+  TRY(moe_acts(c, w, y1k, ldk, T, s, n >= 1 ? y1k : nullptr, ldk, B, S));
   TRY(moe_out(c, w, y2, ld, -1.f, x2, ld, T, s));                 // X2^ = Y2 - MoE branch(Y1)
   if (n == 0) {
     if (x1 != y1) launch_copy_rows(dt, y1, ld, x1, ld, T, h, s);
@@ -472,7 +504,7 @@ int inverse_impl(revffn_ctx* c, const revffn_weights* w, const void* y1, const v
   for (int it = 1; it <= n; it++) {
     const void* xin = (it == 1) ? y1k : x1;                       // iterate, started at Y1
     i64 ldin = (it == 1) ? ldk : ld;
-    TRY(attn_acts(c, w, xin, ldin, x2, ld, B, S, it == 1, s));        // K, V depend on X2^ only: once
+    TRY(attn_acts(c, w, xin, ldin, x2, ld, B, S, it == 1, s, it == 1));   // K, V depend on X2^ only: once
     if (it == n && residual) {
       TRY(attn_out(c, w, y1k, ldk, -1.f, c->xtmp, h, T, s));
       launch_fill_u32((uint32_t*)residual, 0, 1, s);
@@ -507,7 +539,8 @@ int backward_impl(revffn_ctx* c, const revffn_weights* w, const void* x1, const 
   // ---- recompute the MoE half at the exact y1
   if (!reuse_moe) TRY(moe_acts(c, w, y1, ldy, T, s));
   // ---- MoE half backward: Y2 = X2 + P_dn_m(RS)
-  // sw: weight gradients (leaves of the graph, joined at the very end); s0: shared-expert branch
+  // sw: weight gradients of the MoE half (leaves of the graph, joined at the very end); s0: shared-expert branch,
+  // then the weight gradients of the attention half
   hipStream_t sw = side(c, s, 1), s0 = side(c, s, 0);
   if (GF(pdn_m)) {
     // reads dy2: stays on the caller's stream when dx2 aliases dy2 (dx2 is written at the very end)
@@ -585,9 +618,9 @@ int backward_impl(revffn_ctx* c, const revffn_weights* w, const void* x1, const 
   launch_rmsnorm_bwd(dt, c->dn3, h, y1, ldy, w->norm_m, dy1, ld, c->g1, h, c->rinv3, T, h, f.rms_eps, s);
   // ---- attention half backward: Y1 = X1 + P_dn_a(AO)
   if (GF(norm_m)) { after(c, s, sc); launch_colsum(dt, y1, ldy, dt, c->dn3, h, c->rinv3, dt, GF(norm_m), c->partial, T, h, sc); }
-  if (GF(pdn_a)) { after(c, s, sw); TRY(run_gemm(c, tn(c->g1, h, c->AO, d, GF(pdn_a), d, h, d, T), sw)); }
+  if (GF(pdn_a)) { after(c, s, s0); TRY(run_gemm(c, tn(c->g1, h, c->AO, d, GF(pdn_a), d, h, d, T), s0)); }
   TRY(run_gemm(c, nn(c->g1, h, w->pdn_a, d, c->dAO, d, T, d, h), s));
-  if (GF(wo)) { after(c, s, sw); TRY(run_gemm(c, tn(c->dAO, d, c->O, d, GF(wo), d, d, d, T), sw)); }
+  if (GF(wo)) { after(c, s, s0); TRY(run_gemm(c, tn(c->dAO, d, c->O, d, GF(wo), d, d, d, T), s0)); }
   TRY(run_gemm(c, nn(c->dAO, d, w->wo, d, c->dO, d, T, d, d), s));
   {
     // five S x S x dh products (scores, dP, dV, dQ, dK), halved by the causal mask
@@ -610,24 +643,25 @@ int backward_impl(revffn_ctx* c, const revffn_weights* w, const void* x1, const 
   const void* U2 = at(c->U12, (size_t)T * d, es);
   void* dU1 = c->dU12;
   void* dU2 = at(c->dU12, (size_t)T * d, es);
-  after(c, s, sw);
   after(c, s, s0);
   after(c, s, sc);
-  if (GF(wq)) TRY(run_gemm(c, tn(c->dQ, d, U1, d, GF(wq), d, d, d, T), sw));
-  if (GF(wk)) TRY(run_gemm(c, tn(c->dK, d, U2, d, GF(wk), d, d, d, T), sw));
-  if (GF(wv)) TRY(run_gemm(c, tn(c->dV, d, U2, d, GF(wv), d, d, d, T), sw));
+  // s0: dU1 next to dU2 on the main stream, then the projection weight gradients
+  TRY(run_gemm(c, nn(c->dQ, d, w->wq, d, dU1, d, T, d, d), s0));
+  hipEvent_t du1_done = mark(c, s0);
+  if (GF(wq)) TRY(run_gemm(c, tn(c->dQ, d, U1, d, GF(wq), d, d, d, T), s0));
+  if (GF(wk)) TRY(run_gemm(c, tn(c->dK, d, U2, d, GF(wk), d, d, d, T), s0));
+  if (GF(wv)) TRY(run_gemm(c, tn(c->dV, d, U2, d, GF(wv), d, d, d, T), s0));
   if (GF(bq) && w->bq) launch_colsum(dt, c->dQ, d, dt, nullptr, 0, nullptr, dt, GF(bq), c->partial, T, d, sc);
   if (GF(bk) && w->bk) launch_colsum(dt, c->dK, d, dt, nullptr, 0, nullptr, dt, GF(bk), c->partial, T, d, sc);
   if (GF(bv) && w->bv) launch_colsum(dt, c->dV, d, dt, nullptr, 0, nullptr, dt, GF(bv), c->partial, T, d, sc);
-  TRY(run_gemm(c, nn(c->dQ, d, w->wq, d, dU1, d, T, d, d), s0));
   TRY(run_gemm(c, nn(c->dK, d, w->wk, d, dU2, d, T, d, d), s));
   {
     GemmArgs a = nn(c->dV, d, w->wv, d, dU2, d, T, d, d);        // dU2 += dV . Wv
     a.resid = dU2; a.ldr = d; a.resid_sign = 1.f;
     TRY(run_gemm(c, a, s));
   }
-  after(c, s0, s);
-  if (GF(pup_a)) { after(c, s, sw); TRY(run_gemm(c, tn(c->dU12, d, c->n12, h, GF(pup_a), h, d, h, 2 * T), sw)); }
+  if (s0 != s) wait_for(s, du1_done);
+  if (GF(pup_a)) { after(c, s, s0); TRY(run_gemm(c, tn(c->dU12, d, c->n12, h, GF(pup_a), h, d, h, 2 * T), s0)); }
   TRY(run_gemm(c, nn(c->dU12, d, w->pup_a, h, c->dn12, h, 2 * T, h, d), s));
   // dX1 = g1 + Norm'(dn1);  dX2 = dY2 + Norm'(dn2)
   launch_rmsnorm_bwd(dt, c->dn12, h, x1, ld, w->norm_a1, c->g1, h, dx1, ld, c->rinv, T, h, f.rms_eps, s);
@@ -638,6 +672,7 @@ int backward_impl(revffn_ctx* c, const revffn_weights* w, const void* x1, const 
   if (GF(norm_a2))
     launch_colsum(dt, x2, ld, dt, at(c->dn12, (size_t)T * h, es), h, c->rinv + T, dt, GF(norm_a2), c->partial, T, h, sc);
   after(c, sw, s);                       // every weight gradient is complete for the caller's stream
+  after(c, s0, s);
   after(c, sc, s);
   return 0;
 }
