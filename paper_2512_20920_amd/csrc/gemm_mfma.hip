@@ -369,7 +369,9 @@ static void pick_tile(const GemmArgs& g, hipStream_t s) {
     // per-expert weight gradients: the k range is one expert's rows, a few k-tiles only, so a workgroup is mostly
     // load latency and output stores.  Alone, 128x128 tiles with 2 stages (two workgroups per CU) and 256x128 tiles
     // (one per CU) take the same time; next to the data-gradient chain on the main stream the 256x128 tile is 4 %
-    // of a step faster (one resident workgroup per CU leaves the small critical-path kernels room to start).
+    // of a step faster (one resident workgroup per CU leaves the small critical-path kernels room to start).  A
+    // persistent form (a workgroup walks over tiles and issues the next tile's first loads before it stores the
+    // finished one) is 5 % faster alone and 3 % of a step slower next to the main stream, so it is not used.
     static int v = -1;                 // REVFFN_WGRAD_TILE (tuning aid): 0 = 256x128, 1 = 128x128 2 stages, 2 = 128x64 2 stages
     if (v < 0) { const char* e = getenv("REVFFN_WGRAD_TILE"); v = e ? atoi(e) : 0; }
     if (v == 1) go<128, 128, 2, AT, BT, TC, 4, 2>(g, s);
