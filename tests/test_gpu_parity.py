@@ -225,6 +225,22 @@ def test_helper_streams_do_not_change_results(monkeypatch):
         outs.append([y1d, y2d, x1d, x2d, dx1, dx2] + [G[k] for k in sorted(G) if G[k] is not None])
     for a, b in zip(*outs):
         assert torch.equal(a, b)
+    # the same switch through the C-ABI on a live context, with the fused call at the paper's single iteration
+    monkeypatch.delenv("REVFFN_NO_STREAMS", raising=False)
+    case = Case(wl)
+    y1d, y2d = case.forward()
+    fused = []
+    for on in (True, False, True):
+        case.ctx.set_helper_streams(on)
+        r1, r2, o1, o2 = case.empty(), case.empty(), case.empty(), case.empty()
+        G = Hn.alloc_grads(case.Wd)
+        R.revffn_inverse_backward(case.ctx, case.Wd, y1d, y2d, r1, r2, case.up(case.dy1), case.up(case.dy2), o1, o2, G,
+                                  wl.B, wl.S, wl.h, None)
+        torch.cuda.synchronize()
+        fused.append([r1, r2, o1, o2] + [G[k] for k in sorted(G) if G[k] is not None])
+    for other in fused[1:]:
+        for a, b in zip(fused[0], other):
+            assert torch.equal(a, b)
 
 
 def test_frozen_groups_are_skipped():
