@@ -67,9 +67,27 @@ def bench_stack(args, wl):
     ws = (R.Weights * L)(*[R.binding._struct(R.Weights, w) for w in Wds])
     gs = (R.Grads * L)(*[R.binding._struct(R.Grads, g) for g in Gs])
     stream = torch.cuda.current_stream()
+    if args.stored:
+        # the non-reversible comparison: one context (one block's activations) per layer and every block boundary
+        # state kept; forward fills them, the backward walk reads them (no inverse, no recomputation)
+        ctxs = [ctx] + [R.Context(Hn.make_config(wl, n_inv_iters=args.inv_iters), wl.B, wl.S) for _ in range(L - 1)]
+        states = [(x1d, x2d)] + [(new(), new()) for _ in range(L)]
+        wstructs = [R.binding._struct(R.Weights, w) for w in Wds]
+        gstructs = [R.binding._struct(R.Grads, g) for g in Gs]
     t_setup = time.perf_counter() - t_setup
 
     def step():
+        if args.stored:
+            for l in range(L):
+                R.revffn_forward(ctxs[l], wstructs[l], states[l][0], states[l][1], states[l + 1][0], states[l + 1][1],
+                                 wl.B, wl.S, wl.h, stream)
+            ga, gb = dy1d, dy2d
+            for l in range(L - 1, -1, -1):
+                na, nb = (g1, g2) if ga is not g1 else (s1, s2)           # ping-pong gradient buffers
+                R.revffn_backward_stored(ctxs[l], wstructs[l], states[l][0], states[l][1], states[l + 1][0], ga, gb,
+                                         na, nb, gstructs[l], wl.B, wl.S, wl.h, stream)
+                ga, gb = na, nb
+            return
         R.binding._check(ctx.lib.revffn_stack_forward(ctx.handle, ws, L, x1d.data_ptr(), x2d.data_ptr(), y1d.data_ptr(),
                                                       y2d.data_ptr(), wl.B, wl.S, wl.h, stream.cuda_stream))
         s1.copy_(y1d); s2.copy_(y2d); g1.copy_(dy1d); g2.copy_(dy2d)      # the sweep works in place
@@ -86,19 +104,21 @@ def bench_stack(args, wl):
     e1.record(stream)
     torch.cuda.synchronize()
     ms = e0.elapsed_time(e1) / args.steps
-    drift1 = float((s1.float() - x1d.float()).abs().max())
-    drift2 = float((s2.float() - x2d.float()).abs().max())
+    drift1 = 0.0 if args.stored else float((s1.float() - x1d.float()).abs().max())
+    drift2 = 0.0 if args.stored else float((s2.float() - x2d.float()).abs().max())
     weights_bytes = sum(t.numel() * t.element_size() for w in Wds for t in w.values() if t is not None)
     out = {
-        "metric": "RevFFN 24-block stack forward + reconstructing backward sweep, tokens/s",
+        "metric": ("RevFFN 24-block stack forward + stored-activation backward (non-reversible comparison), tokens/s"
+                   if args.stored else "RevFFN 24-block stack forward + reconstructing backward sweep, tokens/s"),
         "value": wl.T / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": f"{wl.name}: {L} RevFFN blocks at the Qwen1.5-MoE-A2.7B layer shape, B={wl.B} S={wl.S}",
                    "n_inv_iters": args.inv_iters, "setup_s": round(t_setup, 1)},
-        "peak_hbm_bytes": int(torch.cuda.max_memory_allocated()) + int(ctx.workspace_bytes(wl.B, wl.S)),
+        "peak_hbm_bytes": int(torch.cuda.max_memory_allocated()) + int(ctx.workspace_bytes(wl.B, wl.S)) * (L if args.stored else 1),
         "weights_bytes": int(weights_bytes), "gradient_bytes": int(weights_bytes),
-        "activation_workspace_bytes": int(ctx.workspace_bytes(wl.B, wl.S)),
+        "activation_workspace_bytes": int(ctx.workspace_bytes(wl.B, wl.S)) * (L if args.stored else 1),
+        "activations": "stored: one workspace per block + every block boundary state" if args.stored else "reversible: one workspace",
         "reconstruction_drift_at_stack_input": {"max_abs_x1": drift1, "max_abs_x2": drift2,
                                                 "note": "max |rebuilt - true| after walking all blocks down"},
     }
@@ -125,6 +145,9 @@ def main():
     ap.add_argument("--workload", default="qwen_b4s512")
     ap.add_argument("--inv-iters", type=int, default=1, help="fixed-point iterations of the inverse (paper: 1)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--stored", action="store_true",
+                    help="stack workloads: the non-reversible comparison (activations of every block kept, "
+                         "revffn_backward_stored) instead of the reconstructing sweep")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run three plain 256 MiB device-to-device copies (the known-size reference for scaling "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters) and exit")

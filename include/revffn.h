@@ -149,6 +149,17 @@ int revffn_backward(revffn_ctx *ctx, const revffn_weights *w,
                     const void *dy1, const void *dy2, void *dx1, void *dx2,
                     const revffn_grads *g, int32_t B, int32_t S, int64_t ld, void *hip_stream);
 
+/* The non-reversible comparison route (the stored-activation baseline of the memory / speed comparison, section
+ * 4): the same gradient as revffn_backward(x1, x2, y1, ...), taken from the activations that the immediately
+ * preceding revffn_forward(x1, x2 -> y1, y2) on this context left in its workspace: no inverse, no recomputation,
+ * at the price of one context (one block's activations) per layer held between the two calls.  Returns
+ * REVFFN_EINVAL if the last call on this context was not an out-of-place revffn_forward with the same x1, x2, y1,
+ * B, S, ld, or if dx1/dx2 alias x1, x2 or y1; the stored state serves one call.  Same bits as revffn_backward. */
+int revffn_backward_stored(revffn_ctx *ctx, const revffn_weights *w,
+                           const void *x1, const void *x2, const void *y1,
+                           const void *dy1, const void *dy2, void *dx1, void *dx2,
+                           const revffn_grads *g, int32_t B, int32_t S, int64_t ld, void *hip_stream);
+
 /* One step of the reversible backward sweep (section 3.1): revffn_inverse followed by
  * revffn_backward at the rebuilt input, in one call.  The MoE half is evaluated once, at the
  * exact y1, and serves both the inverse (X2^ = Y2 - MoE branch) and the backward pass; the

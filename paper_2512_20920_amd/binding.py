@@ -7,7 +7,7 @@ _LIB = None
 
 EXPORTED_SYMBOLS = (
     "revffn_workspace_bytes", "revffn_create", "revffn_destroy", "revffn_set_inv_iters",
-    "revffn_forward", "revffn_inverse", "revffn_backward", "revffn_inverse_backward", "revffn_stack_forward",
+    "revffn_forward", "revffn_inverse", "revffn_backward", "revffn_backward_stored", "revffn_inverse_backward", "revffn_stack_forward",
     "revffn_stack_backward", "revffn_get_routing", "revffn_enable_taps", "revffn_get_branch",
     "revffn_set_kernel_mode", "revffn_set_helper_streams", "revffn_strerror", "revffn_profile_enable", "revffn_profile_read",
     "revffn_profile_kernel_name", "revffn_op_gemm", "revffn_op_attention_fwd", "revffn_op_attention_bwd",
@@ -68,6 +68,7 @@ def load_library():
     lib.revffn_inverse.argtypes = [vp, ctypes.POINTER(Weights), vp, vp, vp, vp, i32, i32, i64, vp, vp]
     lib.revffn_backward.argtypes = [vp, ctypes.POINTER(Weights), vp, vp, vp, vp, vp, vp, vp,
                                     ctypes.POINTER(Grads), i32, i32, i64, vp]
+    lib.revffn_backward_stored.argtypes = lib.revffn_backward.argtypes
     lib.revffn_inverse_backward.argtypes = [vp, ctypes.POINTER(Weights), vp, vp, vp, vp, vp, vp, vp, vp,
                                             ctypes.POINTER(Grads), i32, i32, i64, vp, vp]
     lib.revffn_stack_forward.argtypes = [vp, ctypes.POINTER(Weights), i32, vp, vp, vp, vp, i32, i32, i64, vp]
@@ -211,6 +212,13 @@ def revffn_backward(ctx, weights, x1, x2, y1, dy1, dy2, dx1, dx2, grads, B, S, l
     _check(ctx.lib.revffn_backward(ctx.handle, ctypes.byref(w), _ptr(x1), _ptr(x2), _ptr(y1), _ptr(dy1),
                                    _ptr(dy2), _ptr(dx1), _ptr(dx2), ctypes.byref(g) if g is not None else None,
                                    B, S, ld, _stream(stream)))
+
+
+def revffn_backward_stored(ctx, weights, x1, x2, y1, dy1, dy2, dx1, dx2, grads, B, S, ld, stream=None):
+    w, g = _w(weights), _g(grads)
+    _check(ctx.lib.revffn_backward_stored(ctx.handle, ctypes.byref(w), _ptr(x1), _ptr(x2), _ptr(y1), _ptr(dy1),
+                                          _ptr(dy2), _ptr(dx1), _ptr(dx2),
+                                          ctypes.byref(g) if g is not None else None, B, S, ld, _stream(stream)))
 
 
 def revffn_inverse_backward(ctx, weights, y1, y2, x1, x2, dy1, dy2, dx1, dx2, grads, B, S, ld, residual=None,

@@ -69,6 +69,10 @@ struct revffn_ctx {
   float *dw, *dzext, *rinv, *rinv3, *partial;
   float *splitk_ws, *splitk_ws_r;   // split-k slices: weight-gradient side, router side (fold, then logits)
   bool fold_queued = false;         // the router fold of this call is already enqueued on helper stream 2
+  // the workspace still holds every activation of this revffn_forward call (stored-activation backward)
+  const void *fwd_x1 = nullptr, *fwd_x2 = nullptr, *fwd_y1 = nullptr;
+  int fwd_B = 0, fwd_S = 0;
+  i64 fwd_ld = 0;
   void* dwr_tmp;
   void* wr_ext;               // [E1p, d]: router rows, shared-gate row, zero rows up to a multiple of 8
   void *dzb, *dUm_r;          // bf16 logit gradients [T, E1p] and the router term of dUm [T, d]
@@ -460,6 +464,7 @@ int moe_out(revffn_ctx* c, const revffn_weights* w, const void* resid, i64 ldr, 
 int check_call(revffn_ctx* c, const revffn_weights* w, int B, int S, i64 ld) {
   if (!c || !w) return REVFFN_ENULL;
   c->fold_queued = false;
+  c->fwd_x1 = nullptr;                    // any call invalidates the activations a forward call left behind
   if (B < 1 || S < 1) return REVFFN_ESHAPE;
   if ((i64)B * S > c->maxT) return REVFFN_ESHAPE;
   if (ld < c->cfg.d_model / 2) return REVFFN_ESHAPE;
@@ -522,14 +527,14 @@ void* gfield(const revffn_grads* g, size_t off) { return g ? *(void* const*)((co
 
 int backward_impl(revffn_ctx* c, const revffn_weights* w, const void* x1, const void* x2, const void* y1, i64 ldy,
                   const void* dy1, const void* dy2, void* dx1, void* dx2, const revffn_grads* g, int B, int S,
-                  i64 ld, bool reuse_moe, bool reuse_kv, hipStream_t s) {
+                  i64 ld, bool reuse_moe, bool reuse_kv, hipStream_t s, bool reuse_attn = false) {
   const revffn_config& f = c->cfg;
   const int T = B * S, d = f.d_model, h = d / 2, E = f.n_experts, k = f.top_k, I = f.d_expert, Is = f.d_shared;
   const int N = T * k, E1 = E + (Is ? 1 : 0), dt = c->dt, es = c->es;
   // ---- recompute the attention half at (x1, x2)
   // (K, V and the normalised, lifted X2 are still those of the inverse when it ran in the same call: same X2 bits)
   if (!y1 || !reuse_moe) router_fold(c, w, s);
-  TRY(attn_acts(c, w, x1, ld, x2, ld, B, S, !reuse_kv, s));
+  if (!reuse_attn) TRY(attn_acts(c, w, x1, ld, x2, ld, B, S, !reuse_kv, s));
   if (!y1) {
     TRY(attn_out(c, w, x1, ld, 1.f, c->y1c, h, T, s));
     y1 = c->y1c;
@@ -850,7 +855,22 @@ int revffn_forward(revffn_ctx* c, const revffn_weights* w, const void* x1, const
                    int32_t B, int32_t S, int64_t ld, void* stream) {
   TRY(check_call(c, w, B, S, ld));
   if (!x1 || !x2 || !y1 || !y2) return REVFFN_ENULL;
-  return forward_impl(c, w, x1, x2, y1, y2, B, S, ld, (hipStream_t)stream);
+  TRY(forward_impl(c, w, x1, x2, y1, y2, B, S, ld, (hipStream_t)stream));
+  if (x1 != y1 && x2 != y2) { c->fwd_x1 = x1; c->fwd_x2 = x2; c->fwd_y1 = y1; c->fwd_B = B; c->fwd_S = S; c->fwd_ld = ld; }
+  return 0;
+}
+
+int revffn_backward_stored(revffn_ctx* c, const revffn_weights* w, const void* x1, const void* x2, const void* y1,
+                           const void* dy1, const void* dy2, void* dx1, void* dx2, const revffn_grads* g, int32_t B,
+                           int32_t S, int64_t ld, void* stream) {
+  if (!c) return REVFFN_ENULL;
+  const bool match = c->fwd_x1 && c->fwd_x1 == x1 && c->fwd_x2 == x2 && c->fwd_y1 == y1 && c->fwd_B == B &&
+                     c->fwd_S == S && c->fwd_ld == ld;
+  TRY(check_call(c, w, B, S, ld));        // (also drops the stored state: it serves one backward call)
+  if (!x1 || !x2 || !y1 || !dy1 || !dy2 || !dx1 || !dx2) return REVFFN_ENULL;
+  if (!match) return REVFFN_EINVAL;
+  if (dx1 == x1 || dx1 == x2 || dx2 == x1 || dx2 == x2 || dx1 == y1 || dx2 == y1) return REVFFN_EINVAL;
+  return backward_impl(c, w, x1, x2, y1, ld, dy1, dy2, dx1, dx2, g, B, S, ld, true, true, (hipStream_t)stream, true);
 }
 
 int revffn_inverse(revffn_ctx* c, const revffn_weights* w, const void* y1, const void* y2, void* x1, void* x2,

@@ -262,6 +262,51 @@ def test_frozen_groups_are_skipped():
     assert torch.equal(o1, dx1) and torch.equal(o2, dx2)
 
 
+@pytest.mark.parametrize("name", ["tiny_shared_f32", "mid_bf16"])
+def test_stored_activation_backward(name):
+    """The non-reversible comparison route: gradients from the activations the forward call left in the workspace.
+    Same bits as the recomputing backward at the true input, within tolerance of the oracle's stored route, and
+    refused when the workspace no longer holds that forward call."""
+    wl = synth.WORKLOADS[name]
+    tol = TOL[wl.dtype]
+    case = Case(wl)
+    x1d, x2d = case.up(case.x1), case.up(case.x2)
+    dy1d, dy2d = case.up(case.dy1), case.up(case.dy2)
+    # reference: recomputing backward at the true input
+    y1d, y2d = case.empty(), case.empty()
+    R.revffn_forward(case.ctx, case.Wd, x1d, x2d, y1d, y2d, wl.B, wl.S, wl.h)
+    dx1, dx2, G = case.backward(x1d, x2d, y1d)
+    # stored route
+    R.revffn_forward(case.ctx, case.Wd, x1d, x2d, y1d, y2d, wl.B, wl.S, wl.h)
+    o1, o2 = case.empty(), case.empty()
+    Gs = Hn.alloc_grads(case.Wd)
+    R.revffn_backward_stored(case.ctx, case.Wd, x1d, x2d, y1d, dy1d, dy2d, o1, o2, Gs, wl.B, wl.S, wl.h)
+    torch.cuda.synchronize()
+    assert torch.equal(o1, dx1) and torch.equal(o2, dx2)
+    for k in G:
+        if G[k] is not None:
+            assert torch.equal(G[k], Gs[k]), k
+    # against the oracle's stored route
+    _, _, go = O.grads_stored(Hn.download(x1d), Hn.download(x2d), case.dy1, case.dy2, case.W, case.ocfg, wl.B, wl.S)
+    for k in ("pup_a", "pdn_m", "wq", "w_down", "w_gate_up"):
+        assert relerr(Hn.download(Gs[k]), go[k]) < tol, k
+    # the stored state serves one call, and only right after a matching out-of-place forward
+    with pytest.raises(R.RevffnError):
+        R.revffn_backward_stored(case.ctx, case.Wd, x1d, x2d, y1d, dy1d, dy2d, o1, o2, Gs, wl.B, wl.S, wl.h)
+    R.revffn_forward(case.ctx, case.Wd, x1d, x2d, y1d, y2d, wl.B, wl.S, wl.h)
+    R.revffn_inverse(case.ctx, case.Wd, y1d, y2d, case.empty(), case.empty(), wl.B, wl.S, wl.h, None)
+    with pytest.raises(R.RevffnError):
+        R.revffn_backward_stored(case.ctx, case.Wd, x1d, x2d, y1d, dy1d, dy2d, o1, o2, Gs, wl.B, wl.S, wl.h)
+    R.revffn_forward(case.ctx, case.Wd, x1d, x2d, y1d, y2d, wl.B, wl.S, wl.h)
+    with pytest.raises(R.RevffnError):
+        R.revffn_backward_stored(case.ctx, case.Wd, x2d, x1d, y1d, dy1d, dy2d, o1, o2, Gs, wl.B, wl.S, wl.h)
+    a, b = x1d.clone(), x2d.clone()
+    R.revffn_forward(case.ctx, case.Wd, a, b, a, b, wl.B, wl.S, wl.h)            # in place: nothing stored
+    with pytest.raises(R.RevffnError):
+        R.revffn_backward_stored(case.ctx, case.Wd, a, b, a, dy1d, dy2d, o1, o2, Gs, wl.B, wl.S, wl.h)
+    torch.cuda.synchronize()
+
+
 @pytest.mark.parametrize("name", ["mid_f32", "mid_bf16"])
 def test_stack_sweep_matches_blockwise_calls(name):
     import dataclasses
