@@ -64,6 +64,8 @@ def bench_stack(args, wl):
     new = lambda: torch.empty((wl.T, wl.h), dtype=Hn.torch_dtype(wl.dtype), device="cuda")
     y1d, y2d, s1, s2, g1, g2 = new(), new(), new(), new(), new(), new()
     ctx = R.Context(Hn.make_config(wl, n_inv_iters=args.inv_iters), wl.B, wl.S)
+    if args.inv_tol > 0:
+        ctx.set_inverse_tolerance(args.inv_tol, args.inv_max_iters)
     ws = (R.Weights * L)(*[R.binding._struct(R.Weights, w) for w in Wds])
     gs = (R.Grads * L)(*[R.binding._struct(R.Grads, g) for g in Gs])
     stream = torch.cuda.current_stream()
@@ -97,6 +99,8 @@ def bench_stack(args, wl):
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    if args.inv_tol > 0:
+        ctx.set_inverse_tolerance(args.inv_tol, args.inv_max_iters)       # (restarts the iteration statistics)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record(stream)
     for _ in range(args.steps):
@@ -104,6 +108,7 @@ def bench_stack(args, wl):
     e1.record(stream)
     torch.cuda.synchronize()
     ms = e0.elapsed_time(e1) / args.steps
+    inv_calls, inv_total = ctx.inverse_stats()[:2]
     drift1 = 0.0 if args.stored else float((s1.float() - x1d.float()).abs().max())
     drift2 = 0.0 if args.stored else float((s2.float() - x2d.float()).abs().max())
     weights_bytes = sum(t.numel() * t.element_size() for w in Wds for t in w.values() if t is not None)
@@ -114,7 +119,9 @@ def bench_stack(args, wl):
         "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": f"{wl.name}: {L} RevFFN blocks at the Qwen1.5-MoE-A2.7B layer shape, B={wl.B} S={wl.S}",
-                   "n_inv_iters": args.inv_iters, "setup_s": round(t_setup, 1)},
+                   "n_inv_iters": args.inv_iters, "setup_s": round(t_setup, 1),
+                   **({"inv_tol": args.inv_tol, "inv_max_iters": args.inv_max_iters,
+                       "mean_iters_per_inverse": inv_total / max(inv_calls, 1)} if args.inv_tol > 0 else {})},
         "peak_hbm_bytes": int(torch.cuda.max_memory_allocated()) + int(ctx.workspace_bytes(wl.B, wl.S)) * (L if args.stored else 1),
         "weights_bytes": int(weights_bytes), "gradient_bytes": int(weights_bytes),
         "activation_workspace_bytes": int(ctx.workspace_bytes(wl.B, wl.S)) * (L if args.stored else 1),
@@ -144,6 +151,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="qwen_b4s512")
     ap.add_argument("--inv-iters", type=int, default=1, help="fixed-point iterations of the inverse (paper: 1)")
+    ap.add_argument("--inv-tol", type=float, default=0.0,
+                    help="stack workloads: > 0 = iterate each inverse until successive iterates differ by at most this "
+                         "(host decision after every iteration), at most --inv-max-iters times")
+    ap.add_argument("--inv-max-iters", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--stored", action="store_true",
                     help="stack workloads: the non-reversible comparison (activations of every block kept, "

@@ -122,6 +122,23 @@ void revffn_destroy(revffn_ctx *ctx);
 /* Change the inverse's fixed-point iteration count of an existing context. */
 int revffn_set_inv_iters(revffn_ctx *ctx, int32_t n_inv_iters);
 
+/* Tolerance-driven inverse (the fixed-point iteration of section 3.1 run to a stopping rule instead of a fixed
+ * count).  tol > 0: every inverse on this context (revffn_inverse, revffn_inverse_backward, each block of
+ * revffn_stack_backward) iterates until max |x_n - x_(n-1)| <= tol (absolute, in the units of the streams) or
+ * max_iters (1..1024) iterations have run, whichever comes first, and n_inv_iters is ignored.  The stopping
+ * decision is taken on the host: after every iteration the call copies the one-float residual back and waits for
+ * the stream, so these calls are no longer asynchronous and cannot be captured into a graph.  In bf16 successive
+ * iterates stop changing at the rounding of the stored iterate (about 2^-8 of its largest element); a tolerance
+ * below that floor runs to max_iters.  tol = 0 switches back to the fixed count (max_iters ignored).  Resets the
+ * statistics below.  Returns REVFFN_EINVAL for a negative or NaN tol or max_iters out of range. */
+int revffn_set_inverse_tolerance(revffn_ctx *ctx, float tol, int32_t max_iters);
+
+/* Host-side statistics of the tolerance-driven inverse since revffn_set_inverse_tolerance: number of inverses run,
+ * iterations summed over them, and the iteration count and residual of the most recent one.  Any pointer may be
+ * NULL.  All zero while the tolerance is off. */
+int revffn_get_inverse_stats(revffn_ctx *ctx, int64_t *calls, int64_t *iters_total,
+                             int32_t *last_iters, float *last_residual);
+
 /* Eq. 1-2.  x1, x2: [T,h] inputs; y1, y2: [T,h] outputs, all with row stride ld.
  * y1 may alias x1 and y2 may alias x2 (in-place update). */
 int revffn_forward(revffn_ctx *ctx, const revffn_weights *w,

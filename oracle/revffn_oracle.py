@@ -378,27 +378,33 @@ def forward(x1, x2, W, cfg, B, S, return_cache=False):
     return y1, y2
 
 
-def inverse(y1, y2, W, cfg, B, S, n_iters=None, converge=False, return_info=False):
+def inverse(y1, y2, W, cfg, B, S, n_iters=None, converge=False, return_info=False, tol=None, max_iters=64):
     """Rebuild the block input from its output.  Stream 2 is exact.  Stream 1 is
     the fixed-point iteration x <- Y1 - Attn(Norm x, Norm X2^, Norm X2^) started
     from x = Y1, run n_iters times (default cfg.n_inv_iters), or, if converge, until
-    successive iterates differ by less than 1e-14 * max|Y1| (at most 64 times)."""
+    successive iterates differ by less than 1e-14 * max|Y1| (at most 64 times), or, if
+    tol is given, until max|x_n - x_(n-1)| <= tol (at most max_iters times)."""
     M, cm = moe_half_forward(y1, W, cfg)
     x2 = y2 - M
     x = y1.copy()
     n = cfg.n_inv_iters if n_iters is None else n_iters
     res, it = np.inf, 0
-    limit = 64 if converge else n
+    limit = max_iters if tol is not None else (64 if converge else n)
+    history = []
     while it < limit:
         A, _ = attn_half_forward(x, x2, W, cfg, B, S, keep_probs=False)
         xn = y1 - A
         res = float(np.max(np.abs(xn - x)))
+        history.append(res)
         x = xn
         it += 1
-        if converge and res < 1e-14 * float(np.max(np.abs(y1))):
+        if tol is not None:
+            if res <= tol:
+                break
+        elif converge and res < 1e-14 * float(np.max(np.abs(y1))):
             break
     if return_info:
-        return x, x2, dict(residual=res, iters=it, moe=cm)
+        return x, x2, dict(residual=res, iters=it, moe=cm, residuals=history)
     return x, x2
 
 

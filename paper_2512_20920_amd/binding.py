@@ -7,6 +7,7 @@ _LIB = None
 
 EXPORTED_SYMBOLS = (
     "revffn_workspace_bytes", "revffn_create", "revffn_destroy", "revffn_set_inv_iters",
+    "revffn_set_inverse_tolerance", "revffn_get_inverse_stats",
     "revffn_forward", "revffn_inverse", "revffn_backward", "revffn_backward_stored", "revffn_inverse_backward", "revffn_stack_forward",
     "revffn_stack_backward", "revffn_get_routing", "revffn_enable_taps", "revffn_get_branch",
     "revffn_set_kernel_mode", "revffn_set_helper_streams", "revffn_strerror", "revffn_profile_enable", "revffn_profile_read",
@@ -61,6 +62,9 @@ def load_library():
     lib.revffn_destroy.argtypes = [vp]
     lib.revffn_destroy.restype = None
     lib.revffn_set_inv_iters.argtypes = [vp, i32]
+    lib.revffn_set_inverse_tolerance.argtypes = [vp, ctypes.c_float, i32]
+    lib.revffn_get_inverse_stats.argtypes = [vp, ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int64),
+                                             ctypes.POINTER(i32), ctypes.POINTER(ctypes.c_float)]
     lib.revffn_enable_taps.argtypes = [vp, i32]
     lib.revffn_set_kernel_mode.argtypes = [vp, i32]
     lib.revffn_set_helper_streams.argtypes = [vp, i32]
@@ -157,6 +161,17 @@ class Context:
 
     def set_inv_iters(self, n):
         _check(self.lib.revffn_set_inv_iters(self.handle, n))
+
+    def set_inverse_tolerance(self, tol, max_iters=16):
+        _check(self.lib.revffn_set_inverse_tolerance(self.handle, float(tol), int(max_iters)))
+
+    def inverse_stats(self):
+        """(inverses run, iterations summed, iterations of the last one, residual of the last one)."""
+        calls, iters = ctypes.c_int64(0), ctypes.c_int64(0)
+        last, res = ctypes.c_int32(0), ctypes.c_float(0.0)
+        _check(self.lib.revffn_get_inverse_stats(self.handle, ctypes.byref(calls), ctypes.byref(iters),
+                                                 ctypes.byref(last), ctypes.byref(res)))
+        return calls.value, iters.value, last.value, res.value
 
     def enable_taps(self, on=True):
         _check(self.lib.revffn_enable_taps(self.handle, 1 if on else 0))

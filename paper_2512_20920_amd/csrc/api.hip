@@ -64,6 +64,12 @@ struct revffn_ctx {
   float *tapA, *tapM;
   void *y1c, *xtmp;
   float* resid_dev;
+  // tolerance-driven inverse: > 0 = iterate until max|x_n - x_(n-1)| <= inv_tol, at most inv_max_iters times
+  float inv_tol = 0.f;
+  int inv_max_iters = 0;
+  long long inv_calls = 0, inv_iters_total = 0;   // since the tolerance was last set
+  int inv_last_iters = 0;
+  float inv_last_residual = 0.f;
   // backward
   void *dRS, *dYp, *dYs, *dHs, *dGUs, *dUm_sh, *dHh, *dGU, *dXg, *dUm, *dn3, *g1;
   float *dw, *dzext, *rinv, *rinv3, *partial;
@@ -490,7 +496,8 @@ int forward_impl(revffn_ctx* c, const revffn_weights* w, const void* x1, const v
 int inverse_impl(revffn_ctx* c, const revffn_weights* w, const void* y1, const void* y2, void* x1, void* x2, int B,
                  int S, i64 ld, float* residual, hipStream_t s, const void** y1_kept, i64* ld_kept) {
   const int T = B * S, h = c->cfg.d_model / 2, dt = c->dt;
-  const int n = c->cfg.n_inv_iters;
+  const bool conv = c->inv_tol > 0.f;      // stop on the residual instead of after a fixed count
+  const int n = conv ? c->inv_max_iters : c->cfg.n_inv_iters;
   const void* y1k = y1;
   i64 ldk = ld;
   if (x1 == y1 && (n >= 1)) {             // in place: Y1 is needed after x1 starts being overwritten
@@ -510,13 +517,30 @@ int inverse_impl(revffn_ctx* c, const revffn_weights* w, const void* y1, const v
     const void* xin = (it == 1) ? y1k : x1;                       // iterate, started at Y1
     i64 ldin = (it == 1) ? ldk : ld;
     TRY(attn_acts(c, w, xin, ldin, x2, ld, B, S, it == 1, s, it == 1));   // K, V depend on X2^ only: once
-    if (it == n && residual) {
+    float* rdst = conv ? c->resid_dev : residual;
+    if (conv || (it == n && residual)) {
       TRY(attn_out(c, w, y1k, ldk, -1.f, c->xtmp, h, T, s));
-      launch_fill_u32((uint32_t*)residual, 0, 1, s);
-      launch_absdiff_max_copy(dt, c->xtmp, h, xin, ldin, x1, ld, residual, T, h, s);
+      launch_fill_u32((uint32_t*)rdst, 0, 1, s);
+      launch_absdiff_max_copy(dt, c->xtmp, h, xin, ldin, x1, ld, rdst, T, h, s);
     } else {
       TRY(attn_out(c, w, y1k, ldk, -1.f, x1, ld, T, s));          // x <- Y1 - attention branch(x, X2^)
     }
+    if (conv) {
+      // the one place where the host waits for the device inside a call: the stopping decision
+      float r = 0.f;
+      if (hipMemcpyAsync(&r, c->resid_dev, sizeof(float), hipMemcpyDeviceToHost, s) != hipSuccess) return REVFFN_EHIP;
+      if (hipStreamSynchronize(s) != hipSuccess) return REVFFN_EHIP;
+      c->inv_last_iters = it;
+      c->inv_last_residual = r;
+      if (r <= c->inv_tol || it == n) {     // (a NaN residual never passes and runs to the cap)
+        if (residual) launch_copy_rows(0 /* float */, c->resid_dev, 1, residual, 1, 1, 1, s);
+        break;
+      }
+    }
+  }
+  if (conv) {
+    c->inv_calls++;
+    c->inv_iters_total += c->inv_last_iters;
   }
   if (y1_kept) { *y1_kept = y1k; *ld_kept = ldk; }
   return 0;
@@ -811,6 +835,25 @@ int revffn_set_inv_iters(revffn_ctx* c, int32_t n) {
   if (!c) return REVFFN_ENULL;
   if (n < 0 || n > 1024) return REVFFN_EINVAL;
   c->cfg.n_inv_iters = n;
+  return 0;
+}
+int revffn_set_inverse_tolerance(revffn_ctx* c, float tol, int32_t max_iters) {
+  if (!c) return REVFFN_ENULL;
+  if (!(tol >= 0.f) || (tol > 0.f && (max_iters < 1 || max_iters > 1024))) return REVFFN_EINVAL;
+  c->inv_tol = tol;
+  c->inv_max_iters = tol > 0.f ? max_iters : 0;
+  c->inv_calls = c->inv_iters_total = 0;
+  c->inv_last_iters = 0;
+  c->inv_last_residual = 0.f;
+  return 0;
+}
+int revffn_get_inverse_stats(revffn_ctx* c, int64_t* calls, int64_t* iters_total, int32_t* last_iters,
+                             float* last_residual) {
+  if (!c) return REVFFN_ENULL;
+  if (calls) *calls = c->inv_calls;
+  if (iters_total) *iters_total = c->inv_iters_total;
+  if (last_iters) *last_iters = c->inv_last_iters;
+  if (last_residual) *last_residual = c->inv_last_residual;
   return 0;
 }
 int revffn_enable_taps(revffn_ctx* c, int32_t on) {

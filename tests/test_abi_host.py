@@ -71,6 +71,8 @@ def test_null_context_and_strerror(lib):
     assert lib.revffn_backward(None, ctypes.byref(w), 1, 1, 1, 1, 1, 1, 1, None, 1, 1, 32, None) == -3
     assert lib.revffn_get_routing(None, None, None, None, None, None, None) == -3
     assert lib.revffn_set_inv_iters(None, 1) == -3
+    assert lib.revffn_set_inverse_tolerance(None, 1e-3, 4) == -3
+    assert lib.revffn_get_inverse_stats(None, None, None, None, None) == -3
     lib.revffn_destroy(None)
     seen = set()
     for code in range(0, -7, -1):

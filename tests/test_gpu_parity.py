@@ -209,6 +209,121 @@ def test_inverse_backward_equals_the_two_calls(name):
             assert torch.equal(G[k], G3[k]), k
 
 
+def _slow_contraction_case(name):
+    """The synthetic weights contract by about 1e-5 per iteration; a sharper softmax (query projection x 128) and a
+    larger branch (down adapter x 128) slow that to about 1e-2, so that a tolerance separates several iteration counts."""
+    wl = synth.WORKLOADS[name]
+    W = dict(synth.make_weights(wl))
+    W["wq"] = W["wq"] * 128.0                   # (powers of two: the stored values stay exact)
+    W["pdn_a"] = W["pdn_a"] * 128.0
+    return Case(wl, weights=W)
+
+
+def test_inverse_tolerance_stops_where_the_oracle_does():
+    """Tolerance-driven inverse: the residual after each iteration and the iteration at which a given tolerance stops
+    the loop are those of the oracle's fixed-point iteration (section 3.1), and the result is bit-identical to the
+    fixed-count inverse with that many iterations."""
+    case = _slow_contraction_case("mid_f32")
+    wl, cfg, W = case.wl, case.ocfg, case.W
+    y1o, y2o = O.forward(case.x1, case.x2, W, cfg, wl.B, wl.S)
+    y1d, y2d = case.up(y1o), case.up(y2o)
+    y1h, y2h = Hn.download(y1d), Hn.download(y2d)
+    _, _, info = O.inverse(y1h, y2h, W, cfg, wl.B, wl.S, tol=0.0, max_iters=4, return_info=True)
+    r = info["residuals"]
+    assert len(r) == 4 and r[0] > 0.1 and r[2] > 1e-5 and all(r[i + 1] < 0.1 * r[i] for i in range(3)), r
+    floor = 8 * np.abs(y1h).max() * 2.0 ** -23
+    # residual sequence: cap the loop at k iterations with a tolerance it cannot reach
+    for k in (1, 2, 3):
+        case.ctx.set_inverse_tolerance(1e-30, k)
+        case.inverse(y1d, y2d)
+        calls, total, last, res = case.ctx.inverse_stats()
+        assert (calls, total, last) == (1, k, k)
+        assert abs(res - r[k - 1]) <= 0.02 * r[k - 1] + floor, (k, res, r)
+    # stopping point: a tolerance between two residuals of the sequence
+    for k in (1, 2, 3):
+        tol = 2.0 if k == 1 else float(np.sqrt(r[k - 2] * r[k - 1]))
+        xo, _, oi = O.inverse(y1h, y2h, W, cfg, wl.B, wl.S, tol=tol, max_iters=16, return_info=True)
+        assert oi["iters"] == k
+        case.ctx.set_inverse_tolerance(tol, 16)
+        x1d, x2d, res = case.inverse(y1d, y2d, want_residual=True)
+        calls, total, last, res_host = case.ctx.inverse_stats()
+        assert last == k and res == res_host and res <= tol
+        assert relerr(Hn.download(x1d), xo) < 1e-4
+        case.ctx.set_inverse_tolerance(0.0, 0)                    # back to the fixed count
+        f1, f2 = case.inverse(y1d, y2d, n_iters=k)
+        assert case.ctx.inverse_stats() == (0, 0, 0, 0.0)
+        assert torch.equal(f1, x1d) and torch.equal(f2, x2d)
+    # the fused sweep step and the in-place form follow the same rule
+    tol = float(np.sqrt(r[0] * r[1]))
+    case.ctx.set_inverse_tolerance(0.0, 0)
+    case.ctx.set_inv_iters(2)
+    a, b, ga, gb = y1d.clone(), y2d.clone(), case.up(case.dy1), case.up(case.dy2)
+    G1 = Hn.alloc_grads(case.Wd)
+    R.revffn_inverse_backward(case.ctx, case.Wd, a, b, a, b, ga, gb, ga, gb, G1, wl.B, wl.S, wl.h, None)
+    case.ctx.set_inv_iters(7)                                      # ignored while a tolerance is set
+    case.ctx.set_inverse_tolerance(tol, 16)
+    c, d, gc, gd = y1d.clone(), y2d.clone(), case.up(case.dy1), case.up(case.dy2)
+    G2 = Hn.alloc_grads(case.Wd)
+    R.revffn_inverse_backward(case.ctx, case.Wd, c, d, c, d, gc, gd, gc, gd, G2, wl.B, wl.S, wl.h, None)
+    torch.cuda.synchronize()
+    assert case.ctx.inverse_stats()[:3] == (1, 2, 2)
+    assert torch.equal(a, c) and torch.equal(b, d) and torch.equal(ga, gc) and torch.equal(gb, gd)
+    for k in G1:
+        if G1[k] is not None:
+            assert torch.equal(G1[k], G2[k]), k
+    # argument checks
+    lib = case.ctx.lib
+    assert lib.revffn_set_inverse_tolerance(case.ctx.handle, -1.0, 4) == -1
+    assert lib.revffn_set_inverse_tolerance(case.ctx.handle, float("nan"), 4) == -1
+    assert lib.revffn_set_inverse_tolerance(case.ctx.handle, 1e-3, 0) == -1
+    assert lib.revffn_set_inverse_tolerance(case.ctx.handle, 1e-3, 1025) == -1
+
+
+def test_inverse_tolerance_bf16_floor_and_stack():
+    """In bf16 successive iterates stop changing at the rounding of the stored iterate: a tolerance above the first
+    residual takes one iteration, one between the first residual and that floor takes two, one below the floor runs
+    to the cap.  The stack sweep applies the rule block by block."""
+    wl = synth.WORKLOADS["mid_bf16"]
+    case = Case(wl)
+    y1d, y2d = case.forward()
+    y1h, y2h = Hn.download(y1d), Hn.download(y2d)
+    _, _, info = O.inverse(y1h, y2h, case.W, case.ocfg, wl.B, wl.S, tol=0.0, max_iters=3, return_info=True)
+    r1 = info["residuals"][0]
+    ulp = 2.0 ** (np.floor(np.log2(np.abs(y1h).max())) - 7)        # spacing of bf16 at the largest element
+    assert r1 > 3 * ulp
+    for tol, want in ((2 * r1, 1), (float(np.sqrt(r1 * 1.5 * ulp)), 2), (ulp / 64, 5)):
+        case.ctx.set_inverse_tolerance(tol, 5)
+        x1d, x2d = case.inverse(y1d, y2d)
+        calls, total, last, res = case.ctx.inverse_stats()
+        assert last == want, (tol, want, last, res)
+        oi = O.inverse(y1h, y2h, case.W, case.ocfg, wl.B, wl.S, tol=tol, max_iters=5, return_info=True)[2]
+        if want < 5:
+            assert oi["iters"] == want
+        case.ctx.set_inverse_tolerance(0.0, 0)
+        f1, f2 = case.inverse(y1d, y2d, n_iters=want)
+        assert torch.equal(f1, x1d) and torch.equal(f2, x2d)
+    # stack: the sweep applies the rule in every block; same bits and same iteration counts as block-by-block calls
+    L = 3
+    Wds = [Hn.upload_weights(synth.make_weights(wl, block=l), wl.dtype) for l in range(L)]
+    o1, o2 = case.empty(), case.empty()
+    R.revffn_stack_forward(case.ctx, Wds, case.up(case.x1), case.up(case.x2), o1, o2, wl.B, wl.S, wl.h)
+    tol = float(np.sqrt(r1 * 1.5 * ulp))
+    case.ctx.set_inverse_tolerance(tol, 8)
+    s1, s2, g1, g2 = o1.clone(), o2.clone(), case.up(case.dy1), case.up(case.dy2)
+    R.revffn_stack_backward(case.ctx, Wds, None, s1, s2, g1, g2, wl.B, wl.S, wl.h)
+    torch.cuda.synchronize()
+    calls, total = case.ctx.inverse_stats()[:2]
+    case.ctx.set_inverse_tolerance(tol, 8)                         # (resets the statistics)
+    c1, c2, d1, d2 = o1.clone(), o2.clone(), case.up(case.dy1), case.up(case.dy2)
+    iters = []
+    for l in reversed(range(L)):
+        R.revffn_inverse_backward(case.ctx, Wds[l], c1, c2, c1, c2, d1, d2, d1, d2, None, wl.B, wl.S, wl.h, None)
+        iters.append(case.ctx.inverse_stats()[2])
+    torch.cuda.synchronize()
+    assert calls == L and total == sum(iters) and all(1 <= it <= 3 for it in iters), (calls, total, iters)
+    assert torch.equal(c1, s1) and torch.equal(c2, s2) and torch.equal(d1, g1) and torch.equal(d2, g2)
+
+
 def test_helper_streams_do_not_change_results(monkeypatch):
     """Same bits with the work spread over the helper streams and with everything on one stream."""
     wl = synth.WORKLOADS["mid_bf16"]
