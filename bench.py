@@ -59,11 +59,11 @@ def bench_stack(args, wl):
         Wds.append(Wd)
         Gs.append(Hn.alloc_grads(Wd))
     x1, x2, dy1, dy2 = synth.make_inputs(wl)
-    up = lambda a: Hn.upload(a, wl.dtype)
-    x1d, x2d, dy1d, dy2d = up(x1), up(x2), up(dy1), up(dy2)
-    new = lambda: torch.empty((wl.T, wl.h), dtype=Hn.torch_dtype(wl.dtype), device="cuda")
-    y1d, y2d, s1, s2, g1, g2 = new(), new(), new(), new(), new(), new()
-    ctx = R.Context(Hn.make_config(wl, n_inv_iters=args.inv_iters), wl.B, wl.S)
+    sdt = "f32" if args.fp32_streams else wl.dtype
+    x1d, x2d, dy1d, dy2d = Hn.upload(x1, sdt), Hn.upload(x2, sdt), Hn.upload(dy1, wl.dtype), Hn.upload(dy2, wl.dtype)
+    new = lambda dt=sdt: torch.empty((wl.T, wl.h), dtype=Hn.torch_dtype(dt), device="cuda")
+    y1d, y2d, s1, s2, g1, g2 = new(), new(), new(), new(), new(wl.dtype), new(wl.dtype)
+    ctx = R.Context(Hn.make_config(wl, n_inv_iters=args.inv_iters, fp32_streams=args.fp32_streams), wl.B, wl.S)
     if args.inv_tol > 0:
         ctx.set_inverse_tolerance(args.inv_tol, args.inv_max_iters)
     ws = (R.Weights * L)(*[R.binding._struct(R.Weights, w) for w in Wds])
@@ -72,10 +72,12 @@ def bench_stack(args, wl):
     if args.stored:
         # the non-reversible comparison: one context (one block's activations) per layer and every block boundary
         # state kept; forward fills them, the backward walk reads them (no inverse, no recomputation)
-        ctxs = [ctx] + [R.Context(Hn.make_config(wl, n_inv_iters=args.inv_iters), wl.B, wl.S) for _ in range(L - 1)]
+        ctxs = [ctx] + [R.Context(Hn.make_config(wl, n_inv_iters=args.inv_iters, fp32_streams=args.fp32_streams),
+                                  wl.B, wl.S) for _ in range(L - 1)]
         states = [(x1d, x2d)] + [(new(), new()) for _ in range(L)]
         wstructs = [R.binding._struct(R.Weights, w) for w in Wds]
         gstructs = [R.binding._struct(R.Grads, g) for g in Gs]
+        h1, h2 = new(wl.dtype), new(wl.dtype)
     t_setup = time.perf_counter() - t_setup
 
     def step():
@@ -85,7 +87,7 @@ def bench_stack(args, wl):
                                  wl.B, wl.S, wl.h, stream)
             ga, gb = dy1d, dy2d
             for l in range(L - 1, -1, -1):
-                na, nb = (g1, g2) if ga is not g1 else (s1, s2)           # ping-pong gradient buffers
+                na, nb = (g1, g2) if ga is not g1 else (h1, h2)           # ping-pong gradient buffers
                 R.revffn_backward_stored(ctxs[l], wstructs[l], states[l][0], states[l][1], states[l + 1][0], ga, gb,
                                          na, nb, gstructs[l], wl.B, wl.S, wl.h, stream)
                 ga, gb = na, nb
@@ -120,6 +122,7 @@ def bench_stack(args, wl):
         "data": "synthetic",
         "config": {"workload": f"{wl.name}: {L} RevFFN blocks at the Qwen1.5-MoE-A2.7B layer shape, B={wl.B} S={wl.S}",
                    "n_inv_iters": args.inv_iters, "setup_s": round(t_setup, 1),
+                   "residual_streams": "f32" if args.fp32_streams else wl.dtype,
                    **({"inv_tol": args.inv_tol, "inv_max_iters": args.inv_max_iters,
                        "mean_iters_per_inverse": inv_total / max(inv_calls, 1)} if args.inv_tol > 0 else {})},
         "peak_hbm_bytes": int(torch.cuda.max_memory_allocated()) + int(ctx.workspace_bytes(wl.B, wl.S)) * (L if args.stored else 1),
@@ -155,6 +158,8 @@ def main():
                     help="stack workloads: > 0 = iterate each inverse until successive iterates differ by at most this "
                          "(host decision after every iteration), at most --inv-max-iters times")
     ap.add_argument("--inv-max-iters", type=int, default=8)
+    ap.add_argument("--fp32-streams", action="store_true",
+                    help="keep the residual streams x1, x2, y1, y2 in float32 (weights, activations, gradients stay bf16)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--stored", action="store_true",
                     help="stack workloads: the non-reversible comparison (activations of every block kept, "
@@ -197,11 +202,11 @@ def main():
     x1, x2, dy1, dy2 = synth.make_inputs(wl)
     Wd = Hn.upload_weights(W32, wl.dtype)
     G = Hn.alloc_grads(Wd)
-    up = lambda a: Hn.upload(a, wl.dtype)
-    x1d, x2d, dy1d, dy2d = up(x1), up(x2), up(dy1), up(dy2)
-    new = lambda: torch.empty((wl.T, wl.h), dtype=Hn.torch_dtype(wl.dtype), device="cuda")
-    y1d, y2d, r1d, r2d, dx1d, dx2d = new(), new(), new(), new(), new(), new()
-    ctx = R.Context(Hn.make_config(wl, n_inv_iters=args.inv_iters), wl.B, wl.S)
+    sdt = "f32" if args.fp32_streams else wl.dtype
+    x1d, x2d, dy1d, dy2d = Hn.upload(x1, sdt), Hn.upload(x2, sdt), Hn.upload(dy1, wl.dtype), Hn.upload(dy2, wl.dtype)
+    new = lambda dt=sdt: torch.empty((wl.T, wl.h), dtype=Hn.torch_dtype(dt), device="cuda")
+    y1d, y2d, r1d, r2d, dx1d, dx2d = new(), new(), new(), new(), new(wl.dtype), new(wl.dtype)
+    ctx = R.Context(Hn.make_config(wl, n_inv_iters=args.inv_iters, fp32_streams=args.fp32_streams), wl.B, wl.S)
     wstruct = R.binding._struct(R.Weights, Wd)
     gstruct = R.binding._struct(R.Grads, G)
     stream = torch.cuda.current_stream()
@@ -278,7 +283,7 @@ def main():
         "config": {"workload": f"{wl.name}: 1 RevFFN block, d={wl.d_model}, {wl.n_heads} heads x {wl.head_dim}, "
                                f"{wl.n_experts} experts top-{wl.top_k} I={wl.d_expert}, shared {wl.d_shared}, "
                                f"B={wl.B} S={wl.S}, weights N(0,0.02) inputs N(0,1) seed {wl.seed}",
-                   "n_inv_iters": args.inv_iters, "calls": "forward+inverse+backward" if args.separate_calls else "forward+inverse_backward", "setup_s": round(t_setup, 1)},
+                   "n_inv_iters": args.inv_iters, "residual_streams": "f32" if args.fp32_streams else wl.dtype, "calls": "forward+inverse+backward" if args.separate_calls else "forward+inverse_backward", "setup_s": round(t_setup, 1)},
         "roofline": roofline, "kernels": kernels,
     }
     if not args.no_cpu_baseline:

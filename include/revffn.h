@@ -19,7 +19,9 @@
  *    never frees or reallocates them.  Host pointers are marked "host".
  *  - Element type of streams, weights and gradients is given by config.dtype:
  *    0 = float32, 1 = bfloat16 (fp32 accumulation).  b_router and the routing
- *    outputs are always float32 / int32.
+ *    outputs are always float32 / int32.  With config.fp32_streams the four
+ *    residual streams x1, x2, y1, y2 of every call are float32 arrays instead
+ *    (the gradient streams dy1, dy2, dx1, dx2 keep config.dtype).
  *  - Linear weights are row-major [out, in] and are applied as x @ W^T.
  *  - A stream is token-major [T, h], T = B*S, token t = b*S + s, with row
  *    stride `ld` elements (ld >= h).  ld = d lets the two halves of one [T, d]
@@ -76,6 +78,14 @@ typedef struct revffn_config {
                               the paper uses 1 (end of section 3.1)               */
   float rope_theta;        /* e.g. 1e6                                            */
   float rms_eps;           /* e.g. 1e-6                                           */
+  int32_t fp32_streams;    /* 1 = the residual streams x1, x2, y1, y2 (and the
+                              rebuilt ones) are float32 arrays whatever dtype is;
+                              weights, activations inside the block and the gradient
+                              streams dy*, dx* keep dtype.  The coupling adds of
+                              Eq. 1-2 and the subtractions of the inverse then round
+                              to float32 instead of dtype, which removes the storage
+                              rounding from the reconstruction.  0 = streams have
+                              dtype.  No effect with dtype REVFFN_F32.             */
 } revffn_config;
 
 /* Weights of one block.  Device pointers, dtype = config.dtype unless noted. */

@@ -36,7 +36,8 @@ struct revffn_ctx {
   std::vector<ProfRec>* prof = nullptr;        // launches recorded since profiling was switched on
   std::vector<hipEvent_t>* ev_pool = nullptr;  // recycled events
   revffn_config cfg;
-  int dt, es;                 // element type / size of streams and weights
+  int dt, es;                 // element type / size of weights, activations and gradients
+  int sdt, ses;               // element type / size of the residual streams x1, x2, y1, y2 (float32 with fp32_streams)
   int maxT;
   int mode = 0;               // 0 auto, 1 generic kernels only
   int taps = 0;
@@ -105,6 +106,7 @@ int check_cfg(const revffn_config* c) {
   if (c->top_k < 1 || c->top_k > c->n_experts || c->top_k > 16) return REVFFN_EINVAL;
   if (c->d_expert < 1 || c->d_shared < 0) return REVFFN_EINVAL;
   if (c->dtype != REVFFN_F32 && c->dtype != REVFFN_BF16) return REVFFN_EINVAL;
+  if (c->fp32_streams != 0 && c->fp32_streams != 1) return REVFFN_EINVAL;
   if (c->n_inv_iters < 0 || c->n_inv_iters > 1024) return REVFFN_EINVAL;
   if (!(c->rms_eps >= 0.f) || !(c->rope_theta > 0.f)) return REVFFN_EINVAL;
   return REVFFN_OK;
@@ -160,8 +162,8 @@ size_t carve(revffn_ctx* c, char* base) {
   c->RS = cv.take(T * d * es);
   c->tapA = (float*)cv.take(T * h * 4);
   c->tapM = (float*)cv.take(T * h * 4);
-  c->y1c = cv.take(T * h * es);
-  c->xtmp = cv.take(T * h * es);
+  c->y1c = cv.take(T * h * c->ses);
+  c->xtmp = cv.take(T * h * c->ses);
   c->resid_dev = (float*)cv.take(256);
   c->dRS = cv.take(T * d * es);
   c->dYp = cv.take(N * d * es);
@@ -257,7 +259,7 @@ void gemm_work(const revffn_ctx* c, const GemmArgs& g, int ta, int tb, int tc, d
   else if (g.group_mode == 2) { double R = K;                                     // rows summed over groups
     *flops = 2 * M * N * R; *bytes = R * M * ea + R * N * eb + G * M * N * ec; }
   else { *flops = 2 * M * N * K; *bytes = M * K * ea + N * K * eb + M * N * ec; }
-  if (g.resid) *bytes += M * N * (c->es);
+  if (g.resid) *bytes += M * N * (g.resid_f32 ? 4 : c->es);
 }
 
 int run_gemm(revffn_ctx* c, GemmArgs g, int ta, int tb, int tc, hipStream_t s) {
@@ -323,7 +325,7 @@ hipStream_t side(revffn_ctx* c, hipStream_t main, int i) { return c->use_streams
 int attn_q(revffn_ctx* c, const revffn_weights* w, const void* x1, i64 ld1, int B, int S, hipStream_t s) {
   const revffn_config& f = c->cfg;
   const int T = B * S, d = f.d_model, h = d / 2, dt = c->dt;
-  launch_rmsnorm_fwd(dt, x1, ld1, w->norm_a1, c->n12, h, T, h, f.rms_eps, s);
+  launch_rmsnorm_fwd(dt, c->sdt, x1, ld1, w->norm_a1, c->n12, h, T, h, f.rms_eps, s);
   TRY(run_gemm(c, nt(c->n12, h, w->pup_a, h, c->U12, d, T, d, h), s));
   GemmArgs gq = nt(c->U12, d, w->wq, d, c->Q, d, T, d, d);
   gq.bias = w->bq;
@@ -339,13 +341,13 @@ int attn_acts(revffn_ctx* c, const revffn_weights* w, const void* x1, i64 ld1, c
   hipStream_t s0 = side(c, s, 0), s1 = side(c, s, 1);
   if (q_done) {
     if (do_kv) {
-      launch_rmsnorm_fwd(dt, x2, ld2, w->norm_a2, at(c->n12, (size_t)T * h, es), h, T, h, f.rms_eps, s);
+      launch_rmsnorm_fwd(dt, c->sdt, x2, ld2, w->norm_a2, at(c->n12, (size_t)T * h, es), h, T, h, f.rms_eps, s);
       TRY(run_gemm(c, nt(at(c->n12, (size_t)T * h, es), h, w->pup_a, h, at(c->U12, (size_t)T * d, es), d, T, d, h), s));
       after(c, s, s0); after(c, s, s1);
     }
   } else {
-    launch_rmsnorm_fwd(dt, x1, ld1, w->norm_a1, c->n12, h, T, h, f.rms_eps, s);
-    if (do_kv) launch_rmsnorm_fwd(dt, x2, ld2, w->norm_a2, at(c->n12, (size_t)T * h, es), h, T, h, f.rms_eps, s);
+    launch_rmsnorm_fwd(dt, c->sdt, x1, ld1, w->norm_a1, c->n12, h, T, h, f.rms_eps, s);
+    if (do_kv) launch_rmsnorm_fwd(dt, c->sdt, x2, ld2, w->norm_a2, at(c->n12, (size_t)T * h, es), h, T, h, f.rms_eps, s);
     // the same P_up serves both streams: one GEMM over the stacked rows
     TRY(run_gemm(c, nt(c->n12, h, w->pup_a, h, c->U12, d, do_kv ? 2 * T : T, d, h), s));
     if (do_kv) { after(c, s, s0); after(c, s, s1); }
@@ -384,9 +386,9 @@ int attn_out(revffn_ctx* c, const revffn_weights* w, const void* resid, i64 ldr,
              int T, hipStream_t s) {
   const int d = c->cfg.d_model, h = d / 2;
   GemmArgs g = nt(c->AO, d, w->pdn_a, d, dst, ldd, T, h, d);
-  g.resid = resid; g.ldr = ldr; g.resid_sign = sign;
+  g.resid = resid; g.ldr = ldr; g.resid_sign = sign; g.resid_f32 = c->sdt == REVFFN_F32;
   if (c->taps) { g.tap = c->tapA; g.ldtap = h; }
-  return run_gemm(c, g, s);
+  return run_gemm(c, g, c->dt, c->dt, c->sdt, s);
 }
 
 // ---- MoE half ---------------------------------------------------------------------
@@ -424,15 +426,15 @@ int moe_acts(revffn_ctx* c, const revffn_weights* w, const void* y1, i64 ld, int
   {
     GemmArgs z = nt(y1, ld, c->wrp, h, c->splitk_ws_r, E1, T, E1, h);
     z.split_k = SPLIT_LOGITS; z.splitk_ws = c->splitk_ws_r; z.splitk_raw = 1;   // the router kernel adds the slices
-    GemmTypes tz{dt, 0, 0, dt};
+    GemmTypes tz{c->sdt, 0, 0, dt};
     if (launch_gemm_generic(z, tz, sr)) return REVFFN_EUNSUPPORTED;
   }
-  launch_router(dt, y1, ld, c->splitk_ws_r, SPLIT_LOGITS, w->b_router, c->probs, c->idx, c->wts, c->gamma, T, h, E, k,
+  launch_router(c->sdt, y1, ld, c->splitk_ws_r, SPLIT_LOGITS, w->b_router, c->probs, c->idx, c->wts, c->gamma, T, h, E, k,
                 Is ? 1 : 0, f.norm_topk_prob, f.rms_eps, sr);
   TileLists tl{{c->tg_a, c->tg_b, c->tg_c}, {c->tm_a, c->tm_b, c->tm_c}, {c->tf_a, c->tf_b, c->tf_c},
                {c->max_tiles_a, c->max_tiles_b, c->max_tiles_c}, {BM_A, BM_B, BM_C}, c->tile_cnt};
   launch_permute(c->idx, T, k, E, c->counts, c->offsets, c->row_map, c->inv_map, tl, sr);
-  launch_rmsnorm_fwd(dt, y1, ld, w->norm_m, c->n3, h, T, h, f.rms_eps, s);
+  launch_rmsnorm_fwd(dt, c->sdt, y1, ld, w->norm_m, c->n3, h, T, h, f.rms_eps, s);
   TRY(run_gemm(c, nt(c->n3, h, w->pup_m, h, c->Um, d, T, d, h), s));
   hipStream_t s0 = side(c, s, 0);
   if (Is) {                               // the shared expert needs Um only: next to routing + routed experts
@@ -462,9 +464,9 @@ int moe_out(revffn_ctx* c, const revffn_weights* w, const void* resid, i64 ldr, 
             int T, hipStream_t s) {
   const int d = c->cfg.d_model, h = d / 2;
   GemmArgs g = nt(c->RS, d, w->pdn_m, d, dst, ldd, T, h, d);
-  g.resid = resid; g.ldr = ldr; g.resid_sign = sign;
+  g.resid = resid; g.ldr = ldr; g.resid_sign = sign; g.resid_f32 = c->sdt == REVFFN_F32;
   if (c->taps) { g.tap = c->tapM; g.ldtap = h; }
-  return run_gemm(c, g, s);
+  return run_gemm(c, g, c->dt, c->dt, c->sdt, s);
 }
 
 int check_call(revffn_ctx* c, const revffn_weights* w, int B, int S, i64 ld) {
@@ -501,7 +503,7 @@ int inverse_impl(revffn_ctx* c, const revffn_weights* w, const void* y1, const v
   const void* y1k = y1;
   i64 ldk = ld;
   if (x1 == y1 && (n >= 1)) {             // in place: Y1 is needed after x1 starts being overwritten
-    launch_copy_rows(dt, y1, ld, c->y1c, h, T, h, s);
+    launch_copy_rows(c->sdt, y1, ld, c->y1c, h, T, h, s);
     y1k = c->y1c;
     ldk = h;
   }
@@ -510,7 +512,7 @@ int inverse_impl(revffn_ctx* c, const revffn_weights* w, const void* y1, const v
   TRY(moe_acts(c, w, y1k, ldk, T, s, n >= 1 ? y1k : nullptr, ldk, B, S));
   TRY(moe_out(c, w, y2, ld, -1.f, x2, ld, T, s));                 // X2^ = Y2 - MoE branch(Y1)
   if (n == 0) {
-    if (x1 != y1) launch_copy_rows(dt, y1, ld, x1, ld, T, h, s);
+    if (x1 != y1) launch_copy_rows(c->sdt, y1, ld, x1, ld, T, h, s);
     if (residual) launch_fill_u32((uint32_t*)residual, 0, 1, s);
   }
   for (int it = 1; it <= n; it++) {
@@ -521,7 +523,7 @@ int inverse_impl(revffn_ctx* c, const revffn_weights* w, const void* y1, const v
     if (conv || (it == n && residual)) {
       TRY(attn_out(c, w, y1k, ldk, -1.f, c->xtmp, h, T, s));
       launch_fill_u32((uint32_t*)rdst, 0, 1, s);
-      launch_absdiff_max_copy(dt, c->xtmp, h, xin, ldin, x1, ld, rdst, T, h, s);
+      launch_absdiff_max_copy(c->sdt, c->xtmp, h, xin, ldin, x1, ld, rdst, T, h, s);
     } else {
       TRY(attn_out(c, w, y1k, ldk, -1.f, x1, ld, T, s));          // x <- Y1 - attention branch(x, X2^)
     }
@@ -644,9 +646,9 @@ int backward_impl(revffn_ctx* c, const revffn_weights* w, const void* x1, const 
   if (GF(pup_m)) { after(c, s, sw); TRY(run_gemm(c, tn(c->dUm, d, c->n3, h, GF(pup_m), h, d, h, T), sw)); }
   TRY(run_gemm(c, nn(c->dUm, d, w->pup_m, h, c->dn3, h, T, h, d), s));
   // g1 = dY1 + Norm'(dn3): total gradient at Y1
-  launch_rmsnorm_bwd(dt, c->dn3, h, y1, ldy, w->norm_m, dy1, ld, c->g1, h, c->rinv3, T, h, f.rms_eps, s);
+  launch_rmsnorm_bwd(dt, c->sdt, c->dn3, h, y1, ldy, w->norm_m, dy1, ld, c->g1, h, c->rinv3, T, h, f.rms_eps, s);
   // ---- attention half backward: Y1 = X1 + P_dn_a(AO)
-  if (GF(norm_m)) { after(c, s, sc); launch_colsum(dt, y1, ldy, dt, c->dn3, h, c->rinv3, dt, GF(norm_m), c->partial, T, h, sc); }
+  if (GF(norm_m)) { after(c, s, sc); launch_colsum(c->sdt, y1, ldy, dt, c->dn3, h, c->rinv3, dt, GF(norm_m), c->partial, T, h, sc); }
   if (GF(pdn_a)) { after(c, s, s0); TRY(run_gemm(c, tn(c->g1, h, c->AO, d, GF(pdn_a), d, h, d, T), s0)); }
   TRY(run_gemm(c, nn(c->g1, h, w->pdn_a, d, c->dAO, d, T, d, h), s));
   if (GF(wo)) { after(c, s, s0); TRY(run_gemm(c, tn(c->dAO, d, c->O, d, GF(wo), d, d, d, T), s0)); }
@@ -693,13 +695,13 @@ int backward_impl(revffn_ctx* c, const revffn_weights* w, const void* x1, const 
   if (GF(pup_a)) { after(c, s, s0); TRY(run_gemm(c, tn(c->dU12, d, c->n12, h, GF(pup_a), h, d, h, 2 * T), s0)); }
   TRY(run_gemm(c, nn(c->dU12, d, w->pup_a, h, c->dn12, h, 2 * T, h, d), s));
   // dX1 = g1 + Norm'(dn1);  dX2 = dY2 + Norm'(dn2)
-  launch_rmsnorm_bwd(dt, c->dn12, h, x1, ld, w->norm_a1, c->g1, h, dx1, ld, c->rinv, T, h, f.rms_eps, s);
-  launch_rmsnorm_bwd(dt, at(c->dn12, (size_t)T * h, es), h, x2, ld, w->norm_a2, dy2, ld, dx2, ld, c->rinv + T, T, h,
+  launch_rmsnorm_bwd(dt, c->sdt, c->dn12, h, x1, ld, w->norm_a1, c->g1, h, dx1, ld, c->rinv, T, h, f.rms_eps, s);
+  launch_rmsnorm_bwd(dt, c->sdt, at(c->dn12, (size_t)T * h, es), h, x2, ld, w->norm_a2, dy2, ld, dx2, ld, c->rinv + T, T, h,
                      f.rms_eps, s);
   after(c, s, sc);
-  if (GF(norm_a1)) launch_colsum(dt, x1, ld, dt, c->dn12, h, c->rinv, dt, GF(norm_a1), c->partial, T, h, sc);
+  if (GF(norm_a1)) launch_colsum(c->sdt, x1, ld, dt, c->dn12, h, c->rinv, dt, GF(norm_a1), c->partial, T, h, sc);
   if (GF(norm_a2))
-    launch_colsum(dt, x2, ld, dt, at(c->dn12, (size_t)T * h, es), h, c->rinv + T, dt, GF(norm_a2), c->partial, T, h, sc);
+    launch_colsum(c->sdt, x2, ld, dt, at(c->dn12, (size_t)T * h, es), h, c->rinv + T, dt, GF(norm_a2), c->partial, T, h, sc);
   after(c, sw, s);                       // every weight gradient is complete for the caller's stream
   after(c, s0, s);
   after(c, sc, s);
@@ -717,6 +719,8 @@ size_t revffn_workspace_bytes(const revffn_config* cfg, int32_t max_B, int32_t m
   tmp.cfg = *cfg;
   tmp.dt = cfg->dtype;
   tmp.es = cfg->dtype == REVFFN_BF16 ? 2 : 4;
+  tmp.sdt = cfg->fp32_streams ? REVFFN_F32 : cfg->dtype;
+  tmp.ses = tmp.sdt == REVFFN_BF16 ? 2 : 4;
   tmp.maxT = max_B * max_S;
   return carve(&tmp, nullptr);
 }
@@ -738,6 +742,8 @@ int revffn_create(revffn_ctx** out, const revffn_config* cfg, int32_t max_B, int
   c->cfg = *cfg;
   c->dt = cfg->dtype;
   c->es = cfg->dtype == REVFFN_BF16 ? 2 : 4;
+  c->sdt = cfg->fp32_streams ? REVFFN_F32 : cfg->dtype;
+  c->ses = c->sdt == REVFFN_BF16 ? 2 : 4;
   c->maxT = max_B * max_S;
   c->slab_bytes = carve(c, nullptr);
   if (hipGetDevice(&c->device) != hipSuccess) { delete c->prof; delete c->ev_pool; delete c; return REVFFN_EHIP; }

@@ -12,13 +12,13 @@
 // ---------------------------------------------------------------------------------
 // RMSNorm forward: one wave per token row.
 // ---------------------------------------------------------------------------------
-template <class T>
-__global__ void __launch_bounds__(256) rmsnorm_fwd_k(const T* __restrict__ x, i64 ldx, const T* __restrict__ g,
+template <class T, class TX>
+__global__ void __launch_bounds__(256) rmsnorm_fwd_k(const TX* __restrict__ x, i64 ldx, const T* __restrict__ g,
                                                      T* __restrict__ out, i64 ldo, int rows, int h, float eps) {
   int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   int lane = threadIdx.x & 63;
   if (row >= rows) return;
-  const T* xr = x + (i64)row * ldx;
+  const TX* xr = x + (i64)row * ldx;
   float ss = 0.f;
   for (int j = lane; j < h; j += 64) { float v = to_f(xr[j]); ss += v * v; }
   ss = wave_sum(ss);
@@ -35,52 +35,77 @@ static bool rows_vec8(int dt, int h, std::initializer_list<const void*> ptrs, st
   for (i64 l : lds) if (l & 7) return false;
   return true;
 }
-__global__ void __launch_bounds__(256) rmsnorm_fwd_v8_k(const bf16* __restrict__ x, i64 ldx, const bf16* __restrict__ g,
+// 8 consecutive elements of a bf16 or float32 row as floats (float32 rows: two 16-byte loads; p 16-byte aligned)
+struct f32x8 { float v[8]; };
+__device__ __forceinline__ f32x8 load8(const bf16* p) {
+  const bf16x8_v t = *(const bf16x8_v*)p;
+  f32x8 o;
+#pragma unroll
+  for (int q = 0; q < 8; q++) o.v[q] = (float)t[q];
+  return o;
+}
+__device__ __forceinline__ f32x8 load8(const float* p) {
+  const float4 a = *(const float4*)p, b = *(const float4*)(p + 4);
+  return f32x8{{a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w}};
+}
+template <class TX>
+__global__ void __launch_bounds__(256) rmsnorm_fwd_v8_k(const TX* __restrict__ x, i64 ldx, const bf16* __restrict__ g,
                                                         bf16* __restrict__ out, i64 ldo, int rows, int h, float eps) {
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
   if (row >= rows) return;
-  const bf16* xr = x + (i64)row * ldx;
+  const TX* xr = x + (i64)row * ldx;
   float ss = 0.f;
   for (int j = lane * 8; j < h; j += 512) {
-    const bf16x8_v v = *(const bf16x8_v*)(xr + j);
+    const f32x8 v = load8(xr + j);
 #pragma unroll
-    for (int q = 0; q < 8; q++) ss += (float)v[q] * (float)v[q];
+    for (int q = 0; q < 8; q++) ss += v.v[q] * v.v[q];
   }
   ss = wave_sum(ss);
   const float r = 1.0f / sqrtf(ss / (float)h + eps);
   bf16* orow = out + (i64)row * ldo;
   for (int j = lane * 8; j < h; j += 512) {
-    const bf16x8_v v = *(const bf16x8_v*)(xr + j), gv = *(const bf16x8_v*)(g + j);
+    const f32x8 v = load8(xr + j);
+    const bf16x8_v gv = *(const bf16x8_v*)(g + j);
     bf16x8_v o;
 #pragma unroll
-    for (int q = 0; q < 8; q++) o[q] = (__bf16)((float)v[q] * r * (float)gv[q]);
+    for (int q = 0; q < 8; q++) o[q] = (__bf16)(v.v[q] * r * (float)gv[q]);
     *(bf16x8_v*)(orow + j) = o;
   }
 }
 
-void launch_rmsnorm_fwd(int dt, const void* x, i64 ldx, const void* g, void* out, i64 ldo, int rows, int h,
+void launch_rmsnorm_fwd(int dt, int tx, const void* x, i64 ldx, const void* g, void* out, i64 ldo, int rows, int h,
                         float eps, hipStream_t s) {
   if (rows <= 0) return;
+  const dim3 grid(cdiv(rows, 4)), block(256);
   if (rows_vec8(dt, h, {x, g, out}, {ldx, ldo})) {
-    hipLaunchKernelGGL(rmsnorm_fwd_v8_k, dim3(cdiv(rows, 4)), dim3(256), 0, s, (const bf16*)x, ldx, (const bf16*)g,
+    if (tx == 0)
+      hipLaunchKernelGGL(rmsnorm_fwd_v8_k<float>, grid, block, 0, s, (const float*)x, ldx, (const bf16*)g, (bf16*)out,
+                         ldo, rows, h, eps);
+    else
+      hipLaunchKernelGGL(rmsnorm_fwd_v8_k<bf16>, grid, block, 0, s, (const bf16*)x, ldx, (const bf16*)g, (bf16*)out,
+                         ldo, rows, h, eps);
+    return;
+  }
+  if (dt == 1 && tx == 0) {
+    hipLaunchKernelGGL((rmsnorm_fwd_k<bf16, float>), grid, block, 0, s, (const float*)x, ldx, (const bf16*)g,
                        (bf16*)out, ldo, rows, h, eps);
     return;
   }
-  DISPATCH_DT(dt, hipLaunchKernelGGL(rmsnorm_fwd_k<T>, dim3(cdiv(rows, 4)), dim3(256), 0, s, (const T*)x, ldx,
-                                     (const T*)g, (T*)out, ldo, rows, h, eps));
+  DISPATCH_DT(dt, hipLaunchKernelGGL((rmsnorm_fwd_k<T, T>), grid, block, 0, s, (const T*)x, ldx, (const T*)g, (T*)out,
+                                     ldo, rows, h, eps));
 }
 
 // RMSNorm backward for the input:  dx = r*(g.dy) - x*r^3*mean_j(x_j g_j dy_j), plus an
 // optional base term (the residual path of Eq. 1-2).  1/rms is kept per row.
-template <class T>
-__global__ void __launch_bounds__(256) rmsnorm_bwd_k(const T* __restrict__ dy, i64 ldd, const T* __restrict__ x,
+template <class T, class TX>
+__global__ void __launch_bounds__(256) rmsnorm_bwd_k(const T* __restrict__ dy, i64 ldd, const TX* __restrict__ x,
                                                      i64 ldx, const T* __restrict__ g, const T* base, i64 ldb,
                                                      T* dx, i64 ldo, float* __restrict__ rinv, int rows, int h,
                                                      float eps) {
   int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   int lane = threadIdx.x & 63;
   if (row >= rows) return;
-  const T* xr = x + (i64)row * ldx;
+  const TX* xr = x + (i64)row * ldx;
   const T* dr = dy + (i64)row * ldd;
   float ss = 0.f, sd = 0.f;
   for (int j = lane; j < h; j += 64) {
@@ -100,19 +125,21 @@ __global__ void __launch_bounds__(256) rmsnorm_bwd_k(const T* __restrict__ dy, i
   }
 }
 
-__global__ void __launch_bounds__(256) rmsnorm_bwd_v8_k(const bf16* __restrict__ dy, i64 ldd, const bf16* __restrict__ x,
+template <class TX>
+__global__ void __launch_bounds__(256) rmsnorm_bwd_v8_k(const bf16* __restrict__ dy, i64 ldd, const TX* __restrict__ x,
                                                         i64 ldx, const bf16* __restrict__ g, const bf16* base, i64 ldb,
                                                         bf16* dx, i64 ldo, float* __restrict__ rinv, int rows, int h,
                                                         float eps) {
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
   if (row >= rows) return;
-  const bf16* xr = x + (i64)row * ldx;
+  const TX* xr = x + (i64)row * ldx;
   const bf16* dr = dy + (i64)row * ldd;
   float ss = 0.f, sd = 0.f;
   for (int j = lane * 8; j < h; j += 512) {
-    const bf16x8_v v = *(const bf16x8_v*)(xr + j), gv = *(const bf16x8_v*)(g + j), d = *(const bf16x8_v*)(dr + j);
+    const f32x8 v = load8(xr + j);
+    const bf16x8_v gv = *(const bf16x8_v*)(g + j), d = *(const bf16x8_v*)(dr + j);
 #pragma unroll
-    for (int q = 0; q < 8; q++) { ss += (float)v[q] * (float)v[q]; sd += (float)v[q] * (float)gv[q] * (float)d[q]; }
+    for (int q = 0; q < 8; q++) { ss += v.v[q] * v.v[q]; sd += v.v[q] * (float)gv[q] * (float)d[q]; }
   }
   ss = wave_sum(ss);
   sd = wave_sum(sd);
@@ -121,13 +148,14 @@ __global__ void __launch_bounds__(256) rmsnorm_bwd_v8_k(const bf16* __restrict__
   if (lane == 0) rinv[row] = r;
   for (int j = lane * 8; j < h; j += 512) {
     // (dx may alias base or dy: every lane reads its 8 elements of all inputs before it writes them)
-    const bf16x8_v v = *(const bf16x8_v*)(xr + j), gv = *(const bf16x8_v*)(g + j), d = *(const bf16x8_v*)(dr + j);
+    const f32x8 v = load8(xr + j);
+    const bf16x8_v gv = *(const bf16x8_v*)(g + j), d = *(const bf16x8_v*)(dr + j);
     bf16x8_v b;
     if (base) b = *(const bf16x8_v*)(base + (i64)row * ldb + j);
     bf16x8_v o;
 #pragma unroll
     for (int q = 0; q < 8; q++) {
-      float t = r * (float)gv[q] * (float)d[q] - (float)v[q] * c;
+      float t = r * (float)gv[q] * (float)d[q] - v.v[q] * c;
       if (base) t += (float)b[q];
       o[q] = (__bf16)t;
     }
@@ -135,17 +163,27 @@ __global__ void __launch_bounds__(256) rmsnorm_bwd_v8_k(const bf16* __restrict__
   }
 }
 
-void launch_rmsnorm_bwd(int dt, const void* dy, i64 ldd, const void* x, i64 ldx, const void* g, const void* base,
-                        i64 ldb, void* dx, i64 ldo, float* rinv, int rows, int h, float eps, hipStream_t s) {
+void launch_rmsnorm_bwd(int dt, int tx, const void* dy, i64 ldd, const void* x, i64 ldx, const void* g,
+                        const void* base, i64 ldb, void* dx, i64 ldo, float* rinv, int rows, int h, float eps,
+                        hipStream_t s) {
   if (rows <= 0) return;
+  const dim3 grid(cdiv(rows, 4)), block(256);
   if (rows_vec8(dt, h, {dy, x, g, base, dx}, {ldd, ldx, ldb, ldo})) {
-    hipLaunchKernelGGL(rmsnorm_bwd_v8_k, dim3(cdiv(rows, 4)), dim3(256), 0, s, (const bf16*)dy, ldd, (const bf16*)x, ldx,
+    if (tx == 0)
+      hipLaunchKernelGGL(rmsnorm_bwd_v8_k<float>, grid, block, 0, s, (const bf16*)dy, ldd, (const float*)x, ldx,
+                         (const bf16*)g, (const bf16*)base, ldb, (bf16*)dx, ldo, rinv, rows, h, eps);
+    else
+      hipLaunchKernelGGL(rmsnorm_bwd_v8_k<bf16>, grid, block, 0, s, (const bf16*)dy, ldd, (const bf16*)x, ldx,
+                         (const bf16*)g, (const bf16*)base, ldb, (bf16*)dx, ldo, rinv, rows, h, eps);
+    return;
+  }
+  if (dt == 1 && tx == 0) {
+    hipLaunchKernelGGL((rmsnorm_bwd_k<bf16, float>), grid, block, 0, s, (const bf16*)dy, ldd, (const float*)x, ldx,
                        (const bf16*)g, (const bf16*)base, ldb, (bf16*)dx, ldo, rinv, rows, h, eps);
     return;
   }
-  DISPATCH_DT(dt, hipLaunchKernelGGL(rmsnorm_bwd_k<T>, dim3(cdiv(rows, 4)), dim3(256), 0, s, (const T*)dy, ldd,
-                                     (const T*)x, ldx, (const T*)g, (const T*)base, ldb, (T*)dx, ldo, rinv, rows,
-                                     h, eps));
+  DISPATCH_DT(dt, hipLaunchKernelGGL((rmsnorm_bwd_k<T, T>), grid, block, 0, s, (const T*)dy, ldd, (const T*)x, ldx,
+                                     (const T*)g, (const T*)base, ldb, (T*)dx, ldo, rinv, rows, h, eps));
 }
 
 // ---------------------------------------------------------------------------------

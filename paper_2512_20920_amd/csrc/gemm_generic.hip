@@ -125,7 +125,7 @@ __global__ void __launch_bounds__(256) gemm_generic_k(GemmArgs g) {
       if (cscale) v *= to_f(cscale[n]);
       if (bias) v += to_f(bias[n]);
       if (g.tap) g.tap[(i64)m * g.ldtap + n] = v;
-      if (resid) v = to_f(resid[(i64)m * g.ldr + n]) + g.resid_sign * v;
+      if (resid) v = (g.resid_f32 ? ((const float*)g.resid)[(i64)m * g.ldr + n] : to_f(resid[(i64)m * g.ldr + n])) + g.resid_sign * v;
       C[(i64)m * g.ldc + n] = from_f<TC>(v);
     }
   }
@@ -143,7 +143,7 @@ __global__ void __launch_bounds__(256) splitk_reduce_k(GemmArgs g) {
   if (g.col_scale) v *= to_f(((const TS*)g.col_scale)[n]);
   if (g.bias) v += to_f(((const TS*)g.bias)[n]);
   if (g.tap) g.tap[(i64)m * g.ldtap + n] = v;
-  if (g.resid) v = to_f(((const TS*)g.resid)[(i64)m * g.ldr + n]) + g.resid_sign * v;
+  if (g.resid) v = (g.resid_f32 ? ((const float*)g.resid)[(i64)m * g.ldr + n] : to_f(((const TS*)g.resid)[(i64)m * g.ldr + n])) + g.resid_sign * v;
   ((TC*)g.C)[(i64)m * g.ldc + n] = from_f<TC>(v);
 }
 
@@ -176,6 +176,7 @@ int launch_gemm_generic(const GemmArgs& g, GemmTypes t, hipStream_t s) {
     case 13: go<bf16, bf16, float, bf16>(g, s); break;              // bf16 in, fp32 out (router fold)
     case 7: go<float, bf16, bf16, bf16>(g, s); break;               // fp32 A (router logit gradients), bf16 B/C
     case 9: go<bf16, float, float, bf16>(g, s); break;              // bf16 A, fp32 B/C (router logits)
+    case 1: go<float, float, float, bf16>(g, s); break;             // router logits from float32 residual streams
     default: return -1;
   }
   return 0;

@@ -246,7 +246,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const bf16* A, cons
         if (g.row_scale) v *= g.row_scale[m];
         v += bv;
         if (g.tap) g.tap[(i64)m * g.ldtap + n] = v;
-        if (resid) v = (float)resid[(i64)m * g.ldr + n] + g.resid_sign * v;
+        if (resid) v = (g.resid_f32 ? ((const float*)g.resid)[(i64)m * g.ldr + n] : (float)resid[(i64)m * g.ldr + n]) + g.resid_sign * v;
         C[(i64)m * g.ldc + n] = (TC)v;
       }
     }

@@ -27,6 +27,7 @@ struct GemmArgs {
   const int* a_gather = nullptr; const int* b_gather = nullptr; int gather_div = 1;
   const float* row_scale = nullptr; const void* bias = nullptr;
   const void* resid = nullptr; i64 ldr = 0; float resid_sign = 1.f;
+  int resid_f32 = 0;                     // resid holds float32 whatever the side type is (fp32 residual streams)
   float* tap = nullptr; i64 ldtap = 0;
   int group_mode = 0; int n_groups = 1; const int* offsets = nullptr;
   const int* tile_group = nullptr; const int* tile_m0 = nullptr; int max_tiles = 0; int tile_bm = 0;
@@ -112,10 +113,11 @@ void launch_splitk_reduce(const GemmArgs& g, GemmTypes t, hipStream_t s);
 int launch_gemm_mfma(const GemmArgs& g, GemmTypes t, hipStream_t s);
 
 // ---- normalisation / element-wise ------------------------------------------------
-void launch_rmsnorm_fwd(int dt, const void* x, i64 ldx, const void* g, void* out, i64 ldo,
+// tx: element type of x (0 float32, 1 bf16); gains, outputs and gradients have type dt
+void launch_rmsnorm_fwd(int dt, int tx, const void* x, i64 ldx, const void* g, void* out, i64 ldo,
                         int rows, int h, float eps, hipStream_t s);
 // dx = base + rmsnorm_bwd(dy; x, g);  rinv[rows] receives 1/rms per row (for the gain gradient)
-void launch_rmsnorm_bwd(int dt, const void* dy, i64 ldd, const void* x, i64 ldx, const void* g,
+void launch_rmsnorm_bwd(int dt, int tx, const void* dy, i64 ldd, const void* x, i64 ldx, const void* g,
                         const void* base, i64 ldb, void* dx, i64 ldo, float* rinv,
                         int rows, int h, float eps, hipStream_t s);
 // out[j] = sum_t a[t*lda+j] * (b ? b[t*ldb+j] : 1) * (sc ? sc[t] : 1); ta/tb/tout element types.

@@ -43,18 +43,19 @@ def delta_err(gpu, ref, base, dt):
 class Case:
     """One workload on the GPU: uploaded inputs/weights plus a context."""
 
-    def __init__(self, wl, flags=None, mode=0, max_B=None, max_S=None, weights=None, inputs=None):
+    def __init__(self, wl, flags=None, mode=0, max_B=None, max_S=None, weights=None, inputs=None, fp32_streams=False):
         self.wl = wl
         self.flags = dict(flags or {})
         self.ocfg = oracle_cfg(wl, **self.flags)
         self.W = weights if weights is not None else synth.make_weights(wl)
         self.x1, self.x2, self.dy1, self.dy2 = inputs if inputs is not None else synth.make_inputs(wl)
-        self.cfg = Hn.make_config(wl, **self.flags)
+        self.cfg = Hn.make_config(wl, fp32_streams=fp32_streams, **self.flags)
         self.ctx = R.Context(self.cfg, max_B or wl.B, max_S or wl.S)
         self.ctx.set_kernel_mode(mode)
         self.ctx.enable_taps(True)
         self.Wd = Hn.upload_weights(self.W, wl.dtype)
         self.dt = wl.dtype
+        self.sdt = "f32" if fp32_streams else wl.dtype      # element type of the residual streams x1, x2, y1, y2
         self.B, self.S, self.T, self.h = wl.B, wl.S, wl.T, wl.h
 
     def up(self, x):
@@ -63,10 +64,16 @@ class Case:
     def empty(self):
         return torch.empty((self.T, self.h), dtype=Hn.torch_dtype(self.dt), device="cuda")
 
+    def up_s(self, x):
+        return Hn.upload(x, self.sdt)
+
+    def empty_s(self):
+        return torch.empty((self.T, self.h), dtype=Hn.torch_dtype(self.sdt), device="cuda")
+
     def forward(self, x1=None, x2=None):
-        x1d = self.up(self.x1 if x1 is None else x1)
-        x2d = self.up(self.x2 if x2 is None else x2)
-        y1d, y2d = self.empty(), self.empty()
+        x1d = self.up_s(self.x1 if x1 is None else x1)
+        x2d = self.up_s(self.x2 if x2 is None else x2)
+        y1d, y2d = self.empty_s(), self.empty_s()
         R.revffn_forward(self.ctx, self.Wd, x1d, x2d, y1d, y2d, self.B, self.S, self.h)
         torch.cuda.synchronize()
         return y1d, y2d
@@ -94,7 +101,7 @@ class Case:
     def inverse(self, y1d, y2d, n_iters=None, want_residual=False):
         if n_iters is not None:
             self.ctx.set_inv_iters(n_iters)
-        x1d, x2d = self.empty(), self.empty()
+        x1d, x2d = self.empty_s(), self.empty_s()
         res = torch.zeros((1,), dtype=torch.float32, device="cuda") if want_residual else None
         R.revffn_inverse(self.ctx, self.Wd, y1d, y2d, x1d, x2d, self.B, self.S, self.h, res)
         torch.cuda.synchronize()

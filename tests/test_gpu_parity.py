@@ -209,6 +209,62 @@ def test_inverse_backward_equals_the_two_calls(name):
             assert torch.equal(G[k], G3[k]), k
 
 
+@pytest.mark.parametrize("mode", [0, 1])
+def test_fp32_residual_streams(mode):
+    """bf16 block with float32 residual streams (config.fp32_streams): same parity bar for every branch term and
+    gradient; the coupling adds round to float32, so stream 2 is rebuilt to float32 rounding and stream 1 far below
+    the bf16 storage floor; fused / stacked calls give the same bits as the separate ones."""
+    wl = synth.WORKLOADS["mid_bf16"]
+    tol = TOL["bf16"]
+    case = Case(wl, mode=mode, fp32_streams=True)
+    y1d, y2d, rep = _forward_checks(case, tol)
+    assert y1d.dtype == torch.float32
+    a_gpu, m_gpu = case.branches()
+    y1h, y2h = Hn.download(y1d), Hn.download(y2d)
+    ulp = 2.0 ** -23
+    assert np.abs(y1h - (case.x1 + a_gpu)).max() <= ulp * np.abs(y1h).max()          # Eq. 1 rounds once, to float32
+    assert np.abs(y2h - (case.x2 + m_gpu)).max() <= ulp * np.abs(y2h).max()          # Eq. 2
+    for n in (1, 2, 0):
+        _inverse_checks(case, y1d, y2d, tol, n)
+    x1d, x2d = case.inverse(y1d, y2d, n_iters=3)
+    e2 = np.abs(Hn.download(x2d) - case.x2).max()
+    e1 = np.abs(Hn.download(x1d) - case.x1).max()
+    # the same block with bf16 streams, for scale
+    ref = Case(wl, mode=mode)
+    r1d, r2d = ref.forward()
+    q1d, q2d = ref.inverse(r1d, r2d, n_iters=3)
+    b1 = np.abs(Hn.download(q1d) - case.x1).max()
+    b2 = np.abs(Hn.download(q2d) - case.x2).max()
+    print(f"mode {mode}: rebuilt-input error fp32 streams x1 {e1:.2e} x2 {e2:.2e}; bf16 streams x1 {b1:.2e} x2 {b2:.2e}")
+    assert e2 <= 2 * ulp * np.abs(y2h).max()            # same MoE bits subtracted again: one float32 rounding each way
+    assert e1 < 0.05 * b1 and e1 < 2e-3
+    errs = _backward_checks(case, x1d, x2d, y1d, tol)
+    # fused sweep step in place == separate calls
+    case.ctx.set_inv_iters(2)
+    x1d, x2d = case.inverse(y1d, y2d)
+    dx1, dx2, G = case.backward(x1d, x2d, y1d)
+    a, b, ga, gb = y1d.clone(), y2d.clone(), case.up(case.dy1), case.up(case.dy2)
+    G2 = Hn.alloc_grads(case.Wd)
+    R.revffn_inverse_backward(case.ctx, case.Wd, a, b, a, b, ga, gb, ga, gb, G2, wl.B, wl.S, wl.h, None)
+    torch.cuda.synchronize()
+    assert torch.equal(a, x1d) and torch.equal(b, x2d) and torch.equal(ga, dx1) and torch.equal(gb, dx2)
+    for k in G:
+        if G[k] is not None:
+            assert torch.equal(G[k], G2[k]), k
+    # three-block stack: rebuilt stack input against the true one
+    L = 3
+    Wds = [Hn.upload_weights(synth.make_weights(wl, block=l), wl.dtype) for l in range(L)]
+    o1, o2 = case.empty_s(), case.empty_s()
+    R.revffn_stack_forward(case.ctx, Wds, case.up_s(case.x1), case.up_s(case.x2), o1, o2, wl.B, wl.S, wl.h)
+    g1, g2 = case.up(case.dy1), case.up(case.dy2)
+    R.revffn_stack_backward(case.ctx, Wds, None, o1, o2, g1, g2, wl.B, wl.S, wl.h)
+    torch.cuda.synchronize()
+    d1 = np.abs(Hn.download(o1) - case.x1).max()
+    d2 = np.abs(Hn.download(o2) - case.x2).max()
+    print(f"mode {mode}: 3-block stack drift fp32 streams x1 {d1:.2e} x2 {d2:.2e}")
+    assert d1 < 5e-3 and d2 < 5e-3
+
+
 def _slow_contraction_case(name):
     """The synthetic weights contract by about 1e-5 per iteration; a sharper softmax (query projection x 128) and a
     larger branch (down adapter x 128) slow that to about 1e-2, so that a tolerance separates several iteration counts."""
