@@ -16,6 +16,13 @@ the adapter display of section 3.2):
     X1^ = Y1 - Attn(Norm X1^, Norm X2^, Norm X2^)      inverse, second line,
           solved by fixed-point iteration started at X1^ = Y1
 
+The symmetric comparison block of section 3.1 (the coupling the asymmetric layout is
+contrasted with; Config.symmetric) takes the queries from stream 2 as well,
+
+    Y1 = X1 + Attn(Norm X2, Norm X2, Norm X2),   Y2 = X2 + MLP(Norm Y1),
+
+so its inverse has no implicit term: X2^ = Y2 - MLP(Norm Y1), X1^ = Y1 - Attn(Norm X2^, ...).
+
 Attn_pt is multi-head softmax attention with q/k/v biases and rotary position
 encoding (half-split pairing); MLP_pt is a sparse mixture of SwiGLU experts with
 softmax-then-top-k routing plus an optional sigmoid-gated shared SwiGLU expert.
@@ -50,6 +57,7 @@ class Config:
     use_rope: bool = True
     norm_topk_prob: bool = False
     n_inv_iters: int = 1          # the paper's value (section 3.1, last paragraph)
+    symmetric: bool = False       # queries from stream 2 too (the symmetric variant section 3.1 compares against)
     rope_theta: float = 1.0e6
     rms_eps: float = 1.0e-6
 
@@ -163,6 +171,8 @@ def attn_half_forward(x1, x2, W, cfg, B, S, keep_probs=True):
     n2 = rmsnorm(x2, W["norm_a2"], cfg.rms_eps)
     U1 = n1 @ W["pup_a"].T                      # the same P_up serves both streams
     U2 = n2 @ W["pup_a"].T
+    if cfg.symmetric:                           # self-attention on stream 2: x1 plays no part in the branch
+        n1, U1 = None, U2
     Ql = U1 @ W["wq"].T
     Kl = U2 @ W["wk"].T
     Vl = U2 @ W["wv"].T
@@ -210,6 +220,12 @@ def attn_half_backward(dA, c, W, cfg, B, S):
     g["bv"] = dVl.sum(axis=0)
     dU1 = dQl @ W["wq"]
     dU2 = dKl @ W["wk"] + dVl @ W["wv"]
+    if cfg.symmetric:                           # the query path ends in stream 2 as well
+        dU2 = dU2 + dU1
+        g["pup_a"] = dU2.T @ c["n2"]
+        dx2, g["norm_a2"] = rmsnorm_bwd(dU2 @ W["pup_a"], c["x2"], W["norm_a2"], cfg.rms_eps)
+        g["norm_a1"] = np.zeros_like(W["norm_a1"])
+        return np.zeros_like(c["x2"]), dx2, g
     g["pup_a"] = dU1.T @ c["n1"] + dU2.T @ c["n2"]
     dn1 = dU1 @ W["pup_a"]
     dn2 = dU2 @ W["pup_a"]
@@ -386,6 +402,10 @@ def inverse(y1, y2, W, cfg, B, S, n_iters=None, converge=False, return_info=Fals
     tol is given, until max|x_n - x_(n-1)| <= tol (at most max_iters times)."""
     M, cm = moe_half_forward(y1, W, cfg)
     x2 = y2 - M
+    if cfg.symmetric:                            # closed form: the branch depends on X2^ alone
+        A, _ = attn_half_forward(y1, x2, W, cfg, B, S, keep_probs=False)
+        x = y1 - A
+        return (x, x2, dict(residual=0.0, iters=0, moe=cm, residuals=[])) if return_info else (x, x2)
     x = y1.copy()
     n = cfg.n_inv_iters if n_iters is None else n_iters
     res, it = np.inf, 0

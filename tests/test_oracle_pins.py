@@ -93,6 +93,39 @@ def test_inverse_exact_where_attention_ignores_query():
     assert np.abs(r1 - x1).max() < 1e-13 and np.abs(r2 - x2).max() < 1e-13
 
 
+def test_symmetric_variant_closed_form_inverse_and_reduction():
+    """The symmetric comparison block of section 3.1 (queries from stream 2 too): its branch ignores stream 1, its
+    inverse is exact without any iteration, and where both streams and both norm gains coincide it is the
+    asymmetric block's branch."""
+    rng = np.random.default_rng(5)
+    cfg = O.replace(SMALL, symmetric=True)
+    W = rand_weights(cfg, rng, 0.5)                     # far too large for the fixed point to contract
+    B, S = 2, 6
+    x1, x2 = rng.standard_normal((B * S, cfg.h)), rng.standard_normal((B * S, cfg.h))
+    y1, y2 = O.forward(x1, x2, W, cfg, B, S)
+    assert np.abs(y1 - x1).max() > 0.1
+    r1, r2, info = O.inverse(y1, y2, W, cfg, B, S, n_iters=0, return_info=True)
+    assert np.abs(r1 - x1).max() < 1e-13 and np.abs(r2 - x2).max() < 1e-13 and info["iters"] == 0
+    # the branch is a function of stream 2 alone
+    A, _ = O.attn_half_forward(x1, x2, W, cfg, B, S)
+    A2, _ = O.attn_half_forward(rng.standard_normal(x1.shape), x2, W, cfg, B, S)
+    assert np.array_equal(A, A2)
+    # reduction to the asymmetric branch at X1 = X2 with equal gains
+    Wq = dict(W)
+    Wq["norm_a1"] = W["norm_a2"]
+    A3, _ = O.attn_half_forward(x2, x2, Wq, SMALL, B, S)
+    assert np.abs(A - A3).max() < 1e-14 and np.abs(A).max() > 0.1
+    # and it is not the asymmetric branch otherwise
+    A4, _ = O.attn_half_forward(x1, x2, W, SMALL, B, S)
+    assert np.abs(A - A4).max() > 1e-2
+    # stored and reconstructed gradient routes agree exactly (the rebuilt input is exact)
+    dy1, dy2 = rng.standard_normal(x1.shape), rng.standard_normal(x1.shape)
+    dx1, dx2, g = O.grads_stored(x1, x2, dy1, dy2, W, cfg, B, S)
+    _, _, qx1, qx2, qg = O.grads_reconstructed(y1, y2, dy1, dy2, W, cfg, B, S)
+    assert np.abs(qx1 - dx1).max() < 1e-10 and np.abs(qx2 - dx2).max() < 1e-10
+    assert np.abs(g["norm_a1"]).max() == 0.0
+
+
 def test_zero_down_projection_is_identity():
     """P_dn = 0 on both halves: Y = X, inverse exact, dX = dY (section 3.2 display)."""
     rng = np.random.default_rng(4)
@@ -138,6 +171,7 @@ FD_CASES = [
     dict(causal=False, use_rope=False, norm_topk_prob=True),
     dict(d_shared=0, norm_topk_prob=True),
     dict(top_k=5),                                                 # k = E: no selection at all
+    dict(symmetric=True),                                          # comparison block: queries from stream 2
 ]
 
 
@@ -175,6 +209,9 @@ def test_finite_differences_every_group(case):
         if k == "bk" and not cfg.use_rope:
             # without rotary encoding a key bias shifts every score of a row equally: softmax ignores it
             assert np.abs(g[k]).max() < 1e-14
+            continue
+        if k == "norm_a1" and cfg.symmetric:
+            assert np.abs(g[k]).max() == 0.0 and fd == 0.0      # stream 1 is not normalised anywhere in that block
             continue
         assert abs(an) > 1e-4, (k, "direction too weak to pin anything")
         # one single entry (catches transposed gradients that a random direction could hide)
