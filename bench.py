@@ -21,7 +21,7 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 
 
-def cpu_baseline(wl, W32, x1, x2, dy1, dy2, n_inv_iters):
+def cpu_baseline(wl, W32, x1, x2, dy1, dy2, n_inv_iters, symmetric=False):
     """Time the fp64 oracle (as it stands) on the same batch."""
     import numpy as np
     from oracle import revffn_oracle as O
@@ -29,7 +29,7 @@ def cpu_baseline(wl, W32, x1, x2, dy1, dy2, n_inv_iters):
     cores = len(os.sched_getaffinity(0))
     W = O.as_f64(W32)                         # promotion of the stored weights is not timed
     cfg = O.Config(wl.d_model, wl.n_heads, wl.head_dim, wl.n_experts, wl.top_k, wl.d_expert, wl.d_shared,
-                   n_inv_iters=n_inv_iters)
+                   n_inv_iters=n_inv_iters, symmetric=symmetric)
     nb = min(wl.B, 4)                         # whole sequences; a few seconds each
     a, b, ga, gb = (np.ascontiguousarray(t[:nb * S]) for t in (x1, x2, dy1, dy2))
     t0 = time.perf_counter()
@@ -63,7 +63,7 @@ def bench_stack(args, wl):
     x1d, x2d, dy1d, dy2d = Hn.upload(x1, sdt), Hn.upload(x2, sdt), Hn.upload(dy1, wl.dtype), Hn.upload(dy2, wl.dtype)
     new = lambda dt=sdt: torch.empty((wl.T, wl.h), dtype=Hn.torch_dtype(dt), device="cuda")
     y1d, y2d, s1, s2, g1, g2 = new(), new(), new(), new(), new(wl.dtype), new(wl.dtype)
-    ctx = R.Context(Hn.make_config(wl, n_inv_iters=args.inv_iters, fp32_streams=args.fp32_streams), wl.B, wl.S)
+    ctx = R.Context(Hn.make_config(wl, n_inv_iters=args.inv_iters, fp32_streams=args.fp32_streams, symmetric=args.symmetric), wl.B, wl.S)
     if args.inv_tol > 0:
         ctx.set_inverse_tolerance(args.inv_tol, args.inv_max_iters)
     ws = (R.Weights * L)(*[R.binding._struct(R.Weights, w) for w in Wds])
@@ -72,7 +72,7 @@ def bench_stack(args, wl):
     if args.stored:
         # the non-reversible comparison: one context (one block's activations) per layer and every block boundary
         # state kept; forward fills them, the backward walk reads them (no inverse, no recomputation)
-        ctxs = [ctx] + [R.Context(Hn.make_config(wl, n_inv_iters=args.inv_iters, fp32_streams=args.fp32_streams),
+        ctxs = [ctx] + [R.Context(Hn.make_config(wl, n_inv_iters=args.inv_iters, fp32_streams=args.fp32_streams, symmetric=args.symmetric),
                                   wl.B, wl.S) for _ in range(L - 1)]
         states = [(x1d, x2d)] + [(new(), new()) for _ in range(L)]
         wstructs = [R.binding._struct(R.Weights, w) for w in Wds]
@@ -123,6 +123,7 @@ def bench_stack(args, wl):
         "config": {"workload": f"{wl.name}: {L} RevFFN blocks at the Qwen1.5-MoE-A2.7B layer shape, B={wl.B} S={wl.S}",
                    "n_inv_iters": args.inv_iters, "setup_s": round(t_setup, 1),
                    "residual_streams": "f32" if args.fp32_streams else wl.dtype,
+                   "block": "symmetric comparison block" if args.symmetric else "RevFFN (Eq. 1-2)",
                    **({"inv_tol": args.inv_tol, "inv_max_iters": args.inv_max_iters,
                        "mean_iters_per_inverse": inv_total / max(inv_calls, 1)} if args.inv_tol > 0 else {})},
         "peak_hbm_bytes": int(torch.cuda.max_memory_allocated()) + int(ctx.workspace_bytes(wl.B, wl.S)) * (L if args.stored else 1),
@@ -158,6 +159,8 @@ def main():
                     help="stack workloads: > 0 = iterate each inverse until successive iterates differ by at most this "
                          "(host decision after every iteration), at most --inv-max-iters times")
     ap.add_argument("--inv-max-iters", type=int, default=8)
+    ap.add_argument("--symmetric", action="store_true",
+                    help="the symmetric comparison block (queries from stream 2 too; closed-form inverse) instead of Eq. 1")
     ap.add_argument("--fp32-streams", action="store_true",
                     help="keep the residual streams x1, x2, y1, y2 in float32 (weights, activations, gradients stay bf16)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -206,7 +209,7 @@ def main():
     x1d, x2d, dy1d, dy2d = Hn.upload(x1, sdt), Hn.upload(x2, sdt), Hn.upload(dy1, wl.dtype), Hn.upload(dy2, wl.dtype)
     new = lambda dt=sdt: torch.empty((wl.T, wl.h), dtype=Hn.torch_dtype(dt), device="cuda")
     y1d, y2d, r1d, r2d, dx1d, dx2d = new(), new(), new(), new(), new(wl.dtype), new(wl.dtype)
-    ctx = R.Context(Hn.make_config(wl, n_inv_iters=args.inv_iters, fp32_streams=args.fp32_streams), wl.B, wl.S)
+    ctx = R.Context(Hn.make_config(wl, n_inv_iters=args.inv_iters, fp32_streams=args.fp32_streams, symmetric=args.symmetric), wl.B, wl.S)
     wstruct = R.binding._struct(R.Weights, Wd)
     gstruct = R.binding._struct(R.Grads, G)
     stream = torch.cuda.current_stream()
@@ -283,11 +286,11 @@ def main():
         "config": {"workload": f"{wl.name}: 1 RevFFN block, d={wl.d_model}, {wl.n_heads} heads x {wl.head_dim}, "
                                f"{wl.n_experts} experts top-{wl.top_k} I={wl.d_expert}, shared {wl.d_shared}, "
                                f"B={wl.B} S={wl.S}, weights N(0,0.02) inputs N(0,1) seed {wl.seed}",
-                   "n_inv_iters": args.inv_iters, "residual_streams": "f32" if args.fp32_streams else wl.dtype, "calls": "forward+inverse+backward" if args.separate_calls else "forward+inverse_backward", "setup_s": round(t_setup, 1)},
+                   "n_inv_iters": args.inv_iters, "residual_streams": "f32" if args.fp32_streams else wl.dtype, "block": "symmetric comparison block" if args.symmetric else "RevFFN (Eq. 1-2)", "calls": "forward+inverse+backward" if args.separate_calls else "forward+inverse_backward", "setup_s": round(t_setup, 1)},
         "roofline": roofline, "kernels": kernels,
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(wl, W32, x1, x2, dy1, dy2, args.inv_iters)
+        out["cpu_baseline"] = cpu_baseline(wl, W32, x1, x2, dy1, dy2, args.inv_iters, args.symmetric)
     print(json.dumps(out))
 
 

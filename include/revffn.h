@@ -86,6 +86,15 @@ typedef struct revffn_config {
                               to float32 instead of dtype, which removes the storage
                               rounding from the reconstruction.  0 = streams have
                               dtype.  No effect with dtype REVFFN_F32.             */
+  int32_t symmetric;       /* 1 = the symmetric comparison block section 3.1
+                              contrasts the layout with: queries come from stream 2
+                              as well, Y1 = X1 + Attn(Norm X2, Norm X2, Norm X2),
+                              Y2 as in Eq. 2.  The branch of Eq. 1 then ignores X1,
+                              so revffn_inverse is closed-form and exact (no
+                              iteration: n_inv_iters and the tolerance are ignored,
+                              residual = 0), dX1 is the gradient at Y1 and the
+                              gradient of norm_a1 is zero.  0 = the paper's
+                              asymmetric block (Eq. 1).                            */
 } revffn_config;
 
 /* Weights of one block.  Device pointers, dtype = config.dtype unless noted. */

@@ -30,7 +30,8 @@ class Config(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in (
         "d_model", "n_heads", "head_dim", "n_experts", "top_k", "d_expert", "d_shared",
         "dtype", "causal", "use_rope", "norm_topk_prob", "n_inv_iters")] + [
-        ("rope_theta", ctypes.c_float), ("rms_eps", ctypes.c_float), ("fp32_streams", ctypes.c_int32)]
+        ("rope_theta", ctypes.c_float), ("rms_eps", ctypes.c_float), ("fp32_streams", ctypes.c_int32),
+        ("symmetric", ctypes.c_int32)]
 
 
 class Weights(ctypes.Structure):

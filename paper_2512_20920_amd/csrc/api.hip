@@ -107,6 +107,7 @@ int check_cfg(const revffn_config* c) {
   if (c->d_expert < 1 || c->d_shared < 0) return REVFFN_EINVAL;
   if (c->dtype != REVFFN_F32 && c->dtype != REVFFN_BF16) return REVFFN_EINVAL;
   if (c->fp32_streams != 0 && c->fp32_streams != 1) return REVFFN_EINVAL;
+  if (c->symmetric != 0 && c->symmetric != 1) return REVFFN_EINVAL;
   if (c->n_inv_iters < 0 || c->n_inv_iters > 1024) return REVFFN_EINVAL;
   if (!(c->rms_eps >= 0.f) || !(c->rope_theta > 0.f)) return REVFFN_EINVAL;
   return REVFFN_OK;
@@ -339,7 +340,19 @@ int attn_acts(revffn_ctx* c, const revffn_weights* w, const void* x1, i64 ld1, c
   const revffn_config& f = c->cfg;
   const int T = B * S, d = f.d_model, h = d / 2, es = c->es, dt = c->dt;
   hipStream_t s0 = side(c, s, 0), s1 = side(c, s, 1);
-  if (q_done) {
+  if (f.symmetric) {
+    // comparison block: queries from stream 2 as well.  n2, U2 keep their places in the second halves of n12, U12.
+    void* n2 = at(c->n12, (size_t)T * h, es);
+    void* U2s = at(c->U12, (size_t)T * d, es);
+    launch_rmsnorm_fwd(dt, c->sdt, x2, ld2, w->norm_a2, n2, h, T, h, f.rms_eps, s);
+    TRY(run_gemm(c, nt(n2, h, w->pup_a, h, U2s, d, T, d, h), s));
+    after(c, s, s0); after(c, s, s1);
+    GemmArgs gq = nt(U2s, d, w->wq, d, c->Q, d, T, d, d);
+    gq.bias = w->bq;
+    TRY(run_gemm(c, gq, s));
+    if (f.use_rope) launch_rope(dt, c->Q, c->rope_cs, T, S, f.n_heads, f.head_dim, 1.f, s);
+    do_kv = true;
+  } else if (q_done) {
     if (do_kv) {
       launch_rmsnorm_fwd(dt, c->sdt, x2, ld2, w->norm_a2, at(c->n12, (size_t)T * h, es), h, T, h, f.rms_eps, s);
       TRY(run_gemm(c, nt(at(c->n12, (size_t)T * h, es), h, w->pup_a, h, at(c->U12, (size_t)T * d, es), d, T, d, h), s));
@@ -498,8 +511,9 @@ int forward_impl(revffn_ctx* c, const revffn_weights* w, const void* x1, const v
 int inverse_impl(revffn_ctx* c, const revffn_weights* w, const void* y1, const void* y2, void* x1, void* x2, int B,
                  int S, i64 ld, float* residual, hipStream_t s, const void** y1_kept, i64* ld_kept) {
   const int T = B * S, h = c->cfg.d_model / 2, dt = c->dt;
-  const bool conv = c->inv_tol > 0.f;      // stop on the residual instead of after a fixed count
-  const int n = conv ? c->inv_max_iters : c->cfg.n_inv_iters;
+  const bool sym = c->cfg.symmetric != 0;  // closed-form inverse: one evaluation of the branch at X2^, no iteration
+  const bool conv = !sym && c->inv_tol > 0.f;      // stop on the residual instead of after a fixed count
+  const int n = sym ? 1 : conv ? c->inv_max_iters : c->cfg.n_inv_iters;
   const void* y1k = y1;
   i64 ldk = ld;
   if (x1 == y1 && (n >= 1)) {             // in place: Y1 is needed after x1 starts being overwritten
@@ -509,7 +523,7 @@ int inverse_impl(revffn_ctx* c, const revffn_weights* w, const void* y1, const v
   }
   // the first fixed-point iterate is Y1 itself, so its query side does not wait for X2^: it fills the main stream
   // while the routing chain runs
-  TRY(moe_acts(c, w, y1k, ldk, T, s, n >= 1 ? y1k : nullptr, ldk, B, S));
+  TRY(moe_acts(c, w, y1k, ldk, T, s, (n >= 1 && !sym) ? y1k : nullptr, ldk, B, S));
   TRY(moe_out(c, w, y2, ld, -1.f, x2, ld, T, s));                 // X2^ = Y2 - MoE branch(Y1)
   if (n == 0) {
     if (x1 != y1) launch_copy_rows(c->sdt, y1, ld, x1, ld, T, h, s);
@@ -518,9 +532,10 @@ int inverse_impl(revffn_ctx* c, const revffn_weights* w, const void* y1, const v
   for (int it = 1; it <= n; it++) {
     const void* xin = (it == 1) ? y1k : x1;                       // iterate, started at Y1
     i64 ldin = (it == 1) ? ldk : ld;
-    TRY(attn_acts(c, w, xin, ldin, x2, ld, B, S, it == 1, s, it == 1));   // K, V depend on X2^ only: once
+    TRY(attn_acts(c, w, xin, ldin, x2, ld, B, S, it == 1, s, it == 1 && !sym));   // K, V depend on X2^ only: once
     float* rdst = conv ? c->resid_dev : residual;
-    if (conv || (it == n && residual)) {
+    if (sym && residual) launch_fill_u32((uint32_t*)residual, 0, 1, s);     // nothing is iterated: residual 0
+    if (!sym && (conv || (it == n && residual))) {
       TRY(attn_out(c, w, y1k, ldk, -1.f, c->xtmp, h, T, s));
       launch_fill_u32((uint32_t*)rdst, 0, 1, s);
       launch_absdiff_max_copy(c->sdt, c->xtmp, h, xin, ldin, x1, ld, rdst, T, h, s);
@@ -674,12 +689,16 @@ int backward_impl(revffn_ctx* c, const revffn_weights* w, const void* x1, const 
   const void* U2 = at(c->U12, (size_t)T * d, es);
   void* dU1 = c->dU12;
   void* dU2 = at(c->dU12, (size_t)T * d, es);
+  const bool sym = f.symmetric != 0;
   after(c, s, s0);
   after(c, s, sc);
   // s0: dU1 next to dU2 on the main stream, then the projection weight gradients
-  TRY(run_gemm(c, nn(c->dQ, d, w->wq, d, dU1, d, T, d, d), s0));
-  hipEvent_t du1_done = mark(c, s0);
-  if (GF(wq)) TRY(run_gemm(c, tn(c->dQ, d, U1, d, GF(wq), d, d, d, T), s0));
+  hipEvent_t du1_done = nullptr;
+  if (!sym) {
+    TRY(run_gemm(c, nn(c->dQ, d, w->wq, d, dU1, d, T, d, d), s0));
+    du1_done = mark(c, s0);
+  }
+  if (GF(wq)) TRY(run_gemm(c, tn(c->dQ, d, sym ? U2 : U1, d, GF(wq), d, d, d, T), s0));
   if (GF(wk)) TRY(run_gemm(c, tn(c->dK, d, U2, d, GF(wk), d, d, d, T), s0));
   if (GF(wv)) TRY(run_gemm(c, tn(c->dV, d, U2, d, GF(wv), d, d, d, T), s0));
   if (GF(bq) && w->bq) launch_colsum(dt, c->dQ, d, dt, nullptr, 0, nullptr, dt, GF(bq), c->partial, T, d, sc);
@@ -690,6 +709,25 @@ int backward_impl(revffn_ctx* c, const revffn_weights* w, const void* x1, const 
     GemmArgs a = nn(c->dV, d, w->wv, d, dU2, d, T, d, d);        // dU2 += dV . Wv
     a.resid = dU2; a.ldr = d; a.resid_sign = 1.f;
     TRY(run_gemm(c, a, s));
+  }
+  if (sym) {
+    // the query path ends in stream 2 too: dU2 += dQ . Wq; stream 1 only carries the residual path
+    GemmArgs a = nn(c->dQ, d, w->wq, d, dU2, d, T, d, d);
+    a.resid = dU2; a.ldr = d; a.resid_sign = 1.f;
+    TRY(run_gemm(c, a, s));
+    void* n2 = at(c->n12, (size_t)T * h, es);
+    void* dn2 = at(c->dn12, (size_t)T * h, es);
+    if (GF(pup_a)) { after(c, s, s0); TRY(run_gemm(c, tn(dU2, d, n2, h, GF(pup_a), h, d, h, T), s0)); }
+    TRY(run_gemm(c, nn(dU2, d, w->pup_a, h, dn2, h, T, h, d), s));
+    launch_rmsnorm_bwd(dt, c->sdt, dn2, h, x2, ld, w->norm_a2, dy2, ld, dx2, ld, c->rinv + T, T, h, f.rms_eps, s);
+    launch_copy_rows(dt, c->g1, h, dx1, ld, T, h, s);              // dX1 = total gradient at Y1
+    after(c, s, sc);
+    if (GF(norm_a1)) launch_zero(dt, GF(norm_a1), h, sc);          // stream 1 is not normalised in this block
+    if (GF(norm_a2)) launch_colsum(c->sdt, x2, ld, dt, dn2, h, c->rinv + T, dt, GF(norm_a2), c->partial, T, h, sc);
+    after(c, sw, s);
+    after(c, s0, s);
+    after(c, sc, s);
+    return 0;
   }
   if (s0 != s) wait_for(s, du1_done);
   if (GF(pup_a)) { after(c, s, s0); TRY(run_gemm(c, tn(c->dU12, d, c->n12, h, GF(pup_a), h, d, h, 2 * T), s0)); }

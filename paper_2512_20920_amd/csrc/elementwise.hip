@@ -425,6 +425,16 @@ void launch_copy_rows(int dt, const void* src, i64 lds_, void* dst, i64 ldd, int
                                      (T*)dst, ldd, rows, cols));
 }
 
+template <class T>
+__global__ void zero_k(T* p, int n) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = from_f<T>(0.f);
+}
+void launch_zero(int dt, void* p, int n, hipStream_t s) {
+  if (n <= 0) return;
+  DISPATCH_DT(dt, hipLaunchKernelGGL(zero_k<T>, dim3(cdiv(n, 256)), dim3(256), 0, s, (T*)p, n));
+}
+
 __global__ void fill_u32_k(uint32_t* p, uint32_t v, int n) {
   int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = v;

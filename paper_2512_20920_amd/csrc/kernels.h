@@ -132,6 +132,7 @@ void launch_swiglu_bwd(int dt, const void* dhh, const void* gu, void* dgu, i64 r
 void launch_gather_rows(int dt, const void* src, const int* row_map, int div, void* dst, int rows, int cols,
                         hipStream_t s);
 void launch_copy_rows(int dt, const void* src, i64 lds_, void* dst, i64 ldd, int rows, int cols, hipStream_t s);
+void launch_zero(int dt, void* p, int n, hipStream_t s);           // n elements of type dt set to zero
 // res[0] = max |a - b| (bitwise max of non-negative floats; res must be zeroed first) ; dst = a
 void launch_fill_u32(uint32_t* p, uint32_t v, int n, hipStream_t s);
 void launch_absdiff_max_copy(int dt, const void* a, i64 lda, const void* b, i64 ldb, void* dst, i64 ldd,

@@ -13,14 +13,14 @@ def torch_dtype(dtype):
 
 
 def make_config(wl, causal=True, use_rope=True, norm_topk_prob=False, n_inv_iters=1,
-                rope_theta=1.0e6, rms_eps=1.0e-6, dtype=None, fp32_streams=False):
+                rope_theta=1.0e6, rms_eps=1.0e-6, dtype=None, fp32_streams=False, symmetric=False):
     """Config for a synth.Workload-like object (needs d_model, n_heads, ... and dtype)."""
     dt = wl.dtype if dtype is None else dtype
     return Config(d_model=wl.d_model, n_heads=wl.n_heads, head_dim=wl.head_dim, n_experts=wl.n_experts,
                   top_k=wl.top_k, d_expert=wl.d_expert, d_shared=wl.d_shared,
                   dtype=1 if dt == "bf16" else 0, causal=int(causal), use_rope=int(use_rope),
                   norm_topk_prob=int(norm_topk_prob), n_inv_iters=n_inv_iters,
-                  rope_theta=rope_theta, rms_eps=rms_eps, fp32_streams=int(bool(fp32_streams)))
+                  rope_theta=rope_theta, rms_eps=rms_eps, fp32_streams=int(bool(fp32_streams)), symmetric=int(bool(symmetric)))
 
 
 def upload(x, dtype, device="cuda"):

@@ -265,6 +265,59 @@ def test_fp32_residual_streams(mode):
     assert d1 < 5e-3 and d2 < 5e-3
 
 
+@pytest.mark.parametrize("name,mode", [("mid_f32", 0), ("mid_bf16", 1), ("mid_bf16", 0)])
+def test_symmetric_comparison_block(name, mode):
+    """The symmetric variant section 3.1 contrasts the layout with (queries from stream 2 too): same parity bar for
+    forward, inverse and every gradient; the inverse is closed-form, so the input comes back to storage rounding
+    without any iteration, whatever the iteration settings say."""
+    wl = synth.WORKLOADS[name]
+    tol = TOL[wl.dtype]
+    case = Case(wl, mode=mode, flags=dict(symmetric=True))
+    y1d, y2d, rep = _forward_checks(case, tol)
+    # the attention branch must not depend on stream 1
+    a0, _ = case.branches()
+    case.forward(x1=case.x1[::-1].copy())
+    a1, _ = case.branches()
+    assert np.array_equal(a0, a1)
+    case.forward()
+    for n in (1, 0):
+        _inverse_checks(case, y1d, y2d, tol, n)
+    case.ctx.set_inverse_tolerance(1e-9, 7)                        # ignored: nothing is iterated
+    x1d, x2d, res = case.inverse(y1d, y2d, want_residual=True)
+    assert res == 0.0 and case.ctx.inverse_stats()[0] == 0
+    case.ctx.set_inverse_tolerance(0.0, 0)
+    ulp = (2.0 ** -7 if wl.dtype == "bf16" else 2.0 ** -23) * np.abs(Hn.download(y1d)).max()
+    e1 = np.abs(Hn.download(x1d) - case.x1).max()
+    e2 = np.abs(Hn.download(x2d) - case.x2).max()
+    print(f"{name} mode {mode}: symmetric block rebuilt-input error x1 {e1:.2e} x2 {e2:.2e} (one unit of storage {ulp:.2e})")
+    assert e1 <= 4 * ulp and e2 <= 4 * ulp
+    errs = _backward_checks(case, x1d, x2d, y1d, tol)
+    # fused sweep step, in place == the separate calls
+    dx1, dx2, G = case.backward(x1d, x2d, y1d)
+    a, b, ga, gb = y1d.clone(), y2d.clone(), case.up(case.dy1), case.up(case.dy2)
+    G2 = Hn.alloc_grads(case.Wd)
+    R.revffn_inverse_backward(case.ctx, case.Wd, a, b, a, b, ga, gb, ga, gb, G2, wl.B, wl.S, wl.h, None)
+    torch.cuda.synchronize()
+    assert torch.equal(a, x1d) and torch.equal(b, x2d) and torch.equal(ga, dx1) and torch.equal(gb, dx2)
+    for k in G:
+        if G[k] is not None:
+            assert torch.equal(G[k], G2[k]), k
+    assert float(G["norm_a1"].float().abs().max()) == 0.0
+    # stored-activation route gives the same bits as the recomputing one at the true input
+    x1t, x2t = case.up_s(case.x1), case.up_s(case.x2)
+    o1, o2 = case.empty_s(), case.empty_s()
+    R.revffn_forward(case.ctx, case.Wd, x1t, x2t, o1, o2, wl.B, wl.S, wl.h)
+    s1, s2 = case.empty(), case.empty()
+    G3 = Hn.alloc_grads(case.Wd)
+    R.revffn_backward_stored(case.ctx, case.Wd, x1t, x2t, o1, case.up(case.dy1), case.up(case.dy2), s1, s2, G3,
+                             wl.B, wl.S, wl.h)
+    t1, t2, G4 = case.backward(x1t, x2t, o1)
+    assert torch.equal(s1, t1) and torch.equal(s2, t2)
+    for k in G3:
+        if G3[k] is not None:
+            assert torch.equal(G3[k], G4[k]), k
+
+
 def _slow_contraction_case(name):
     """The synthetic weights contract by about 1e-5 per iteration; a sharper softmax (query projection x 128) and a
     larger branch (down adapter x 128) slow that to about 1e-2, so that a tolerance separates several iteration counts."""
