@@ -46,9 +46,15 @@ WORKLOADS = {
     "qwen_stack24_b1s1024": Workload("qwen_stack24_b1s1024", B=1, S=1024, dtype="bf16", n_blocks=24, **_QWEN),
     # long context, batch 1 x seq 8192
     "qwen_b1s8192": Workload("qwen_b1s8192", B=1, S=8192, dtype="bf16", **_QWEN),
+    # a second MoE geometry for the grouped GEMMs: few large experts (8 experts, top-2, width 14336, d 4096, no shared
+    # expert), 512 rows per expert at batch 2 x seq 1024 -- the compute-bound end, where the Qwen shape is the
+    # weight-streaming end
+    "e8k2_d4096_b2s1024": Workload("e8k2_d4096_b2s1024", 4096, 32, 128, 8, 2, 14336, 0, 2, 1024, "bf16"),
     # reduced-size bf16 cases for element-by-element parity (several tiles + ragged tails)
     "mid_bf16": Workload("mid_bf16", 512, 4, 128, 12, 3, 192, 320, 2, 200, "bf16", gain_jitter=0.02),
     "mid_f32": Workload("mid_f32", 128, 4, 32, 6, 2, 96, 160, 3, 50, "f32", gain_jitter=0.02),
+    # few large experts, no shared expert, reduced: rows per expert span several 128- and 256-row tiles
+    "mid_fewbig_bf16": Workload("mid_fewbig_bf16", 512, 4, 128, 3, 2, 712, 0, 3, 232, "bf16", gain_jitter=0.02),
 }
 
 WEIGHT_FIELDS = (

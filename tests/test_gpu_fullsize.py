@@ -92,6 +92,13 @@ def test_qwen_b4s512_fp32_residual_streams():
     assert rep["inv6_x1_err_vs_true_input"] < 0.01
 
 
+def test_few_large_experts_geometry():
+    """A second MoE geometry (8 experts, top-2, width 14336, d 4096, no shared expert; 512 rows per expert):
+    the grouped GEMMs at their compute-bound end, same parity bar."""
+    rep = _full_block("e8k2_d4096_b2s1024", n_inv=(1,))
+    assert 0.8 < rep["hottest_over_mean"] < 1.5
+
+
 def test_qwen_zipf_load_imbalance():
     rep = _full_block("qwen_zipf_b2s2048", n_inv=(1,))
     assert 7.0 < rep["hottest_over_mean"] < 9.0

@@ -100,7 +100,7 @@ def _backward_checks(case, x1d, x2d, y1d, tol):
 
 
 @pytest.mark.parametrize("name,mode", [("tiny_f32", 0), ("tiny_shared_f32", 0), ("mid_f32", 0),
-                                       ("mid_bf16", 1), ("mid_bf16", 0)])
+                                       ("mid_bf16", 1), ("mid_bf16", 0), ("mid_fewbig_bf16", 0)])
 def test_block_parity(name, mode):
     wl = synth.WORKLOADS[name]
     tol = TOL[wl.dtype]
