@@ -57,13 +57,13 @@ def bench_stack(args, wl):
     for l in range(L):
         Wd = Hn.upload_weights(synth.make_weights(wl, block=l, f64=False), wl.dtype)
         Wds.append(Wd)
-        Gs.append(Hn.alloc_grads(Wd))
+        Gs.append(Hn.alloc_grads(Wd, fp32=args.fp32_grads))
     x1, x2, dy1, dy2 = synth.make_inputs(wl)
     sdt = "f32" if args.fp32_streams else wl.dtype
     x1d, x2d, dy1d, dy2d = Hn.upload(x1, sdt), Hn.upload(x2, sdt), Hn.upload(dy1, wl.dtype), Hn.upload(dy2, wl.dtype)
     new = lambda dt=sdt: torch.empty((wl.T, wl.h), dtype=Hn.torch_dtype(dt), device="cuda")
     y1d, y2d, s1, s2, g1, g2 = new(), new(), new(), new(), new(wl.dtype), new(wl.dtype)
-    ctx = R.Context(Hn.make_config(wl, n_inv_iters=args.inv_iters, fp32_streams=args.fp32_streams, symmetric=args.symmetric), wl.B, wl.S)
+    ctx = R.Context(Hn.make_config(wl, n_inv_iters=args.inv_iters, fp32_streams=args.fp32_streams, symmetric=args.symmetric, fp32_grads=args.fp32_grads), wl.B, wl.S)
     if args.inv_tol > 0:
         ctx.set_inverse_tolerance(args.inv_tol, args.inv_max_iters)
     ws = (R.Weights * L)(*[R.binding._struct(R.Weights, w) for w in Wds])
@@ -72,7 +72,7 @@ def bench_stack(args, wl):
     if args.stored:
         # the non-reversible comparison: one context (one block's activations) per layer and every block boundary
         # state kept; forward fills them, the backward walk reads them (no inverse, no recomputation)
-        ctxs = [ctx] + [R.Context(Hn.make_config(wl, n_inv_iters=args.inv_iters, fp32_streams=args.fp32_streams, symmetric=args.symmetric),
+        ctxs = [ctx] + [R.Context(Hn.make_config(wl, n_inv_iters=args.inv_iters, fp32_streams=args.fp32_streams, symmetric=args.symmetric, fp32_grads=args.fp32_grads),
                                   wl.B, wl.S) for _ in range(L - 1)]
         states = [(x1d, x2d)] + [(new(), new()) for _ in range(L)]
         wstructs = [R.binding._struct(R.Weights, w) for w in Wds]
@@ -127,7 +127,7 @@ def bench_stack(args, wl):
                    **({"inv_tol": args.inv_tol, "inv_max_iters": args.inv_max_iters,
                        "mean_iters_per_inverse": inv_total / max(inv_calls, 1)} if args.inv_tol > 0 else {})},
         "peak_hbm_bytes": int(torch.cuda.max_memory_allocated()) + int(ctx.workspace_bytes(wl.B, wl.S)) * (L if args.stored else 1),
-        "weights_bytes": int(weights_bytes), "gradient_bytes": int(weights_bytes),
+        "weights_bytes": int(weights_bytes), "gradient_bytes": int(sum(t.numel() * t.element_size() for g in Gs for t in g.values() if t is not None)),
         "activation_workspace_bytes": int(ctx.workspace_bytes(wl.B, wl.S)) * (L if args.stored else 1),
         "activations": "stored: one workspace per block + every block boundary state" if args.stored else "reversible: one workspace",
         "reconstruction_drift_at_stack_input": {"max_abs_x1": drift1, "max_abs_x2": drift2,
@@ -159,6 +159,7 @@ def main():
                     help="stack workloads: > 0 = iterate each inverse until successive iterates differ by at most this "
                          "(host decision after every iteration), at most --inv-max-iters times")
     ap.add_argument("--inv-max-iters", type=int, default=8)
+    ap.add_argument("--fp32-grads", action="store_true", help="float32 weight-gradient buffers (dtype otherwise)")
     ap.add_argument("--symmetric", action="store_true",
                     help="the symmetric comparison block (queries from stream 2 too; closed-form inverse) instead of Eq. 1")
     ap.add_argument("--fp32-streams", action="store_true",
@@ -204,12 +205,12 @@ def main():
     W32 = synth.make_weights(wl, f64=False)
     x1, x2, dy1, dy2 = synth.make_inputs(wl)
     Wd = Hn.upload_weights(W32, wl.dtype)
-    G = Hn.alloc_grads(Wd)
+    G = Hn.alloc_grads(Wd, fp32=args.fp32_grads)
     sdt = "f32" if args.fp32_streams else wl.dtype
     x1d, x2d, dy1d, dy2d = Hn.upload(x1, sdt), Hn.upload(x2, sdt), Hn.upload(dy1, wl.dtype), Hn.upload(dy2, wl.dtype)
     new = lambda dt=sdt: torch.empty((wl.T, wl.h), dtype=Hn.torch_dtype(dt), device="cuda")
     y1d, y2d, r1d, r2d, dx1d, dx2d = new(), new(), new(), new(), new(wl.dtype), new(wl.dtype)
-    ctx = R.Context(Hn.make_config(wl, n_inv_iters=args.inv_iters, fp32_streams=args.fp32_streams, symmetric=args.symmetric), wl.B, wl.S)
+    ctx = R.Context(Hn.make_config(wl, n_inv_iters=args.inv_iters, fp32_streams=args.fp32_streams, symmetric=args.symmetric, fp32_grads=args.fp32_grads), wl.B, wl.S)
     wstruct = R.binding._struct(R.Weights, Wd)
     gstruct = R.binding._struct(R.Grads, G)
     stream = torch.cuda.current_stream()
@@ -286,7 +287,7 @@ def main():
         "config": {"workload": f"{wl.name}: 1 RevFFN block, d={wl.d_model}, {wl.n_heads} heads x {wl.head_dim}, "
                                f"{wl.n_experts} experts top-{wl.top_k} I={wl.d_expert}, shared {wl.d_shared}, "
                                f"B={wl.B} S={wl.S}, weights N(0,0.02) inputs N(0,1) seed {wl.seed}",
-                   "n_inv_iters": args.inv_iters, "residual_streams": "f32" if args.fp32_streams else wl.dtype, "block": "symmetric comparison block" if args.symmetric else "RevFFN (Eq. 1-2)", "calls": "forward+inverse+backward" if args.separate_calls else "forward+inverse_backward", "setup_s": round(t_setup, 1)},
+                   "n_inv_iters": args.inv_iters, "residual_streams": "f32" if args.fp32_streams else wl.dtype, "block": "symmetric comparison block" if args.symmetric else "RevFFN (Eq. 1-2)", "weight_gradients": "f32" if args.fp32_grads else wl.dtype, "calls": "forward+inverse+backward" if args.separate_calls else "forward+inverse_backward", "setup_s": round(t_setup, 1)},
         "roofline": roofline, "kernels": kernels,
     }
     if not args.no_cpu_baseline:

@@ -95,6 +95,11 @@ typedef struct revffn_config {
                               residual = 0), dX1 is the gradient at Y1 and the
                               gradient of norm_a1 is zero.  0 = the paper's
                               asymmetric block (Eq. 1).                            */
+  int32_t fp32_grads;      /* 1 = every weight-gradient buffer of revffn_grads is a
+                              float32 array whatever dtype is (the GEMMs accumulate
+                              in float32 anyway; this skips the rounding of the
+                              result to dtype).  0 = gradients have dtype.  The
+                              input gradients dx1, dx2 keep dtype either way.      */
 } revffn_config;
 
 /* Weights of one block.  Device pointers, dtype = config.dtype unless noted. */
@@ -116,7 +121,8 @@ typedef struct revffn_weights {
 /* Where weight gradients go: same shapes and dtype as the weights (b_router:
  * float32).  A NULL field means "this gradient is not wanted" and its GEMM is
  * skipped (section 3.3: stage 1 trains only the adapters; stage 2 keeps the
- * routers frozen).  Non-NULL fields are OVERWRITTEN, not accumulated. */
+ * routers frozen).  Non-NULL fields are OVERWRITTEN, not accumulated.  With
+ * config.fp32_grads every buffer holds float32. */
 typedef struct revffn_grads {
   void *norm_a1, *norm_a2, *norm_m;
   void *pup_a, *pdn_a, *pup_m, *pdn_m;

@@ -31,7 +31,7 @@ class Config(ctypes.Structure):
         "d_model", "n_heads", "head_dim", "n_experts", "top_k", "d_expert", "d_shared",
         "dtype", "causal", "use_rope", "norm_topk_prob", "n_inv_iters")] + [
         ("rope_theta", ctypes.c_float), ("rms_eps", ctypes.c_float), ("fp32_streams", ctypes.c_int32),
-        ("symmetric", ctypes.c_int32)]
+        ("symmetric", ctypes.c_int32), ("fp32_grads", ctypes.c_int32)]
 
 
 class Weights(ctypes.Structure):

@@ -38,6 +38,7 @@ struct revffn_ctx {
   revffn_config cfg;
   int dt, es;                 // element type / size of weights, activations and gradients
   int sdt, ses;               // element type / size of the residual streams x1, x2, y1, y2 (float32 with fp32_streams)
+  int gdt, ges;               // element type / size of the weight gradients (float32 with fp32_grads)
   int maxT;
   int mode = 0;               // 0 auto, 1 generic kernels only
   int taps = 0;
@@ -108,6 +109,7 @@ int check_cfg(const revffn_config* c) {
   if (c->dtype != REVFFN_F32 && c->dtype != REVFFN_BF16) return REVFFN_EINVAL;
   if (c->fp32_streams != 0 && c->fp32_streams != 1) return REVFFN_EINVAL;
   if (c->symmetric != 0 && c->symmetric != 1) return REVFFN_EINVAL;
+  if (c->fp32_grads != 0 && c->fp32_grads != 1) return REVFFN_EINVAL;
   if (c->n_inv_iters < 0 || c->n_inv_iters > 1024) return REVFFN_EINVAL;
   if (!(c->rms_eps >= 0.f) || !(c->rope_theta > 0.f)) return REVFFN_EINVAL;
   return REVFFN_OK;
@@ -180,7 +182,7 @@ size_t carve(revffn_ctx* c, char* base) {
   c->g1 = cv.take(T * h * es);
   c->dw = (float*)cv.take(N * 4);
   c->dzext = (float*)cv.take(T * E1 * 4);
-  c->dwr_tmp = cv.take(E1 * d * es);
+  c->dwr_tmp = cv.take(E1 * d * c->ges);
   const size_t E1p = (E1 + 7) / 8 * 8;
   c->wr_ext = cv.take(E1p * d * es);
   c->dzb = cv.take(T * E1p * 2);
@@ -292,6 +294,8 @@ int run_gemm(revffn_ctx* c, GemmArgs g, int ta, int tb, int tc, hipStream_t s) {
   return e;
 }
 int run_gemm(revffn_ctx* c, const GemmArgs& g, hipStream_t s) { return run_gemm(c, g, c->dt, c->dt, c->dt, s); }
+// a GEMM whose result is a weight gradient: written in the gradient dtype (float32 with fp32_grads)
+int run_wgrad(revffn_ctx* c, const GemmArgs& g, hipStream_t s) { return run_gemm(c, g, c->dt, c->dt, c->gdt, s); }
 
 #define TRY(x) do { int _e = (x); if (_e) return _e; } while (0)
 
@@ -592,19 +596,19 @@ int backward_impl(revffn_ctx* c, const revffn_weights* w, const void* x1, const 
     // reads dy2: stays on the caller's stream when dx2 aliases dy2 (dx2 is written at the very end)
     hipStream_t sp = (dx2 == dy2) ? s : sw;
     after(c, s, sp);
-    TRY(run_gemm(c, tn(dy2, ld, c->RS, d, GF(pdn_m), d, h, d, T), sp));
+    TRY(run_wgrad(c, tn(dy2, ld, c->RS, d, GF(pdn_m), d, h, d, T), sp));
   }
   TRY(run_gemm(c, nn(dy2, ld, w->pdn_m, d, c->dRS, d, T, d, h), s));
   launch_moe_bwd_rows(dt, c->dRS, c->Yp, c->Ys, c->inv_map, c->wts, c->gamma, c->dYp, c->dYs, c->dw, c->dzext, T, d,
                       k, E1, Is ? 1 : 0, s);
   if (Is) {
     after(c, s, s0);
-    if (GF(ws_down)) { after(c, s, sw); TRY(run_gemm(c, tn(c->dYs, d, c->Hs, Is, GF(ws_down), Is, d, Is, T), sw)); }
+    if (GF(ws_down)) { after(c, s, sw); TRY(run_wgrad(c, tn(c->dYs, d, c->Hs, Is, GF(ws_down), Is, d, Is, T), sw)); }
     TRY(run_gemm(c, nn(c->dYs, d, w->ws_down, Is, c->dHs, Is, T, Is, d), s0));
     launch_swiglu_bwd(dt, c->dHs, c->GUs, c->dGUs, T, Is, s0);
     if (GF(ws_gate_up)) {
       after(c, s0, sw);
-      TRY(run_gemm(c, tn(c->dGUs, 2 * Is, c->Um, d, GF(ws_gate_up), d, 2 * Is, d, T), sw));
+      TRY(run_wgrad(c, tn(c->dGUs, 2 * Is, c->Um, d, GF(ws_gate_up), d, 2 * Is, d, T), sw));
     }
     TRY(run_gemm(c, nn(c->dGUs, 2 * Is, w->ws_gate_up, d, c->dUm_sh, d, T, d, 2 * Is), s0));
   }
@@ -613,7 +617,7 @@ int backward_impl(revffn_ctx* c, const revffn_weights* w, const void* x1, const 
       after(c, s, sw);
       GemmArgs b = tn(c->dYp, d, c->Hh, I, GF(w_down), I, d, I, N);        // dWd_e = dYp_e^T . Hh_e
       b.group_mode = 2; b.n_groups = E; b.offsets = c->offsets; b.c_group_stride = (i64)d * I;
-      TRY(run_gemm(c, b, sw));
+      TRY(run_wgrad(c, b, sw));
     }
     GemmArgs a = nn(c->dYp, d, w->w_down, I, c->dHh, I, N, I, d);          // dHh = dYp . Wd_e
     a.group_mode = 1; a.n_groups = E; a.offsets = c->offsets; a.b_group_stride = (i64)d * I;
@@ -625,7 +629,7 @@ int backward_impl(revffn_ctx* c, const revffn_weights* w, const void* x1, const 
       launch_gather_rows(dt, c->Um, c->row_map, k, c->Xg, N, d, sw);
       GemmArgs b = tn(c->dGU, 2 * I, c->Xg, d, GF(w_gate_up), d, 2 * I, d, N);
       b.group_mode = 2; b.n_groups = E; b.offsets = c->offsets; b.c_group_stride = (i64)2 * I * d;
-      TRY(run_gemm(c, b, sw));
+      TRY(run_wgrad(c, b, sw));
     }
     GemmArgs e = nn(c->dGU, 2 * I, w->w_gate_up, d, c->dXg, d, N, d, 2 * I);     // dXg = dGU . Wgu_e
     e.group_mode = 1; e.n_groups = E; e.offsets = c->offsets; e.b_group_stride = (i64)2 * I * d;
@@ -640,10 +644,10 @@ int backward_impl(revffn_ctx* c, const revffn_weights* w, const void* x1, const 
     // [dW_r ; dw_shared_gate] = dzext^T . Um in one fp32-A split-k GEMM, then the rows go to their buffers
     GemmArgs a = tn(c->dzext, E1, c->Um, d, c->dwr_tmp, d, E1, d, T);
     a.split_k = SPLIT_DWR; a.splitk_ws = c->splitk_ws;
-    GemmTypes t{0, dt, dt, dt};
+    GemmTypes t{0, dt, c->gdt, dt};
     if (launch_gemm_generic(a, t, sc)) return REVFFN_EUNSUPPORTED;
-    if (GF(w_router)) launch_copy_rows(dt, c->dwr_tmp, d, GF(w_router), d, E, d, sc);
-    if (Is && GF(ws_gate)) launch_copy_rows(dt, at(c->dwr_tmp, (size_t)E * d, es), d, GF(ws_gate), d, 1, d, sc);
+    if (GF(w_router)) launch_copy_rows(c->gdt, c->dwr_tmp, d, GF(w_router), d, E, d, sc);
+    if (Is && GF(ws_gate)) launch_copy_rows(c->gdt, at(c->dwr_tmp, (size_t)E * d, c->ges), d, GF(ws_gate), d, 1, d, sc);
   }
   if (g && g->b_router) launch_colsum(0, c->dzext, E1, 0, nullptr, 0, nullptr, 0, g->b_router, c->partial, T, E, sc);
   if (Is) after(c, s0, s);
@@ -658,15 +662,15 @@ int backward_impl(revffn_ctx* c, const revffn_weights* w, const void* x1, const 
   }
   launch_dum_finalize(dt, c->dXg, c->inv_map, Is ? c->dUm_sh : nullptr, dum_r, c->dzext, w->w_router, w->ws_gate,
                       c->dUm, T, d, k, E, E1, s);
-  if (GF(pup_m)) { after(c, s, sw); TRY(run_gemm(c, tn(c->dUm, d, c->n3, h, GF(pup_m), h, d, h, T), sw)); }
+  if (GF(pup_m)) { after(c, s, sw); TRY(run_wgrad(c, tn(c->dUm, d, c->n3, h, GF(pup_m), h, d, h, T), sw)); }
   TRY(run_gemm(c, nn(c->dUm, d, w->pup_m, h, c->dn3, h, T, h, d), s));
   // g1 = dY1 + Norm'(dn3): total gradient at Y1
   launch_rmsnorm_bwd(dt, c->sdt, c->dn3, h, y1, ldy, w->norm_m, dy1, ld, c->g1, h, c->rinv3, T, h, f.rms_eps, s);
   // ---- attention half backward: Y1 = X1 + P_dn_a(AO)
-  if (GF(norm_m)) { after(c, s, sc); launch_colsum(c->sdt, y1, ldy, dt, c->dn3, h, c->rinv3, dt, GF(norm_m), c->partial, T, h, sc); }
-  if (GF(pdn_a)) { after(c, s, s0); TRY(run_gemm(c, tn(c->g1, h, c->AO, d, GF(pdn_a), d, h, d, T), s0)); }
+  if (GF(norm_m)) { after(c, s, sc); launch_colsum(c->sdt, y1, ldy, dt, c->dn3, h, c->rinv3, c->gdt, GF(norm_m), c->partial, T, h, sc); }
+  if (GF(pdn_a)) { after(c, s, s0); TRY(run_wgrad(c, tn(c->g1, h, c->AO, d, GF(pdn_a), d, h, d, T), s0)); }
   TRY(run_gemm(c, nn(c->g1, h, w->pdn_a, d, c->dAO, d, T, d, h), s));
-  if (GF(wo)) { after(c, s, s0); TRY(run_gemm(c, tn(c->dAO, d, c->O, d, GF(wo), d, d, d, T), s0)); }
+  if (GF(wo)) { after(c, s, s0); TRY(run_wgrad(c, tn(c->dAO, d, c->O, d, GF(wo), d, d, d, T), s0)); }
   TRY(run_gemm(c, nn(c->dAO, d, w->wo, d, c->dO, d, T, d, d), s));
   {
     // five S x S x dh products (scores, dP, dV, dQ, dK), halved by the causal mask
@@ -698,12 +702,12 @@ int backward_impl(revffn_ctx* c, const revffn_weights* w, const void* x1, const 
     TRY(run_gemm(c, nn(c->dQ, d, w->wq, d, dU1, d, T, d, d), s0));
     du1_done = mark(c, s0);
   }
-  if (GF(wq)) TRY(run_gemm(c, tn(c->dQ, d, sym ? U2 : U1, d, GF(wq), d, d, d, T), s0));
-  if (GF(wk)) TRY(run_gemm(c, tn(c->dK, d, U2, d, GF(wk), d, d, d, T), s0));
-  if (GF(wv)) TRY(run_gemm(c, tn(c->dV, d, U2, d, GF(wv), d, d, d, T), s0));
-  if (GF(bq) && w->bq) launch_colsum(dt, c->dQ, d, dt, nullptr, 0, nullptr, dt, GF(bq), c->partial, T, d, sc);
-  if (GF(bk) && w->bk) launch_colsum(dt, c->dK, d, dt, nullptr, 0, nullptr, dt, GF(bk), c->partial, T, d, sc);
-  if (GF(bv) && w->bv) launch_colsum(dt, c->dV, d, dt, nullptr, 0, nullptr, dt, GF(bv), c->partial, T, d, sc);
+  if (GF(wq)) TRY(run_wgrad(c, tn(c->dQ, d, sym ? U2 : U1, d, GF(wq), d, d, d, T), s0));
+  if (GF(wk)) TRY(run_wgrad(c, tn(c->dK, d, U2, d, GF(wk), d, d, d, T), s0));
+  if (GF(wv)) TRY(run_wgrad(c, tn(c->dV, d, U2, d, GF(wv), d, d, d, T), s0));
+  if (GF(bq) && w->bq) launch_colsum(dt, c->dQ, d, dt, nullptr, 0, nullptr, c->gdt, GF(bq), c->partial, T, d, sc);
+  if (GF(bk) && w->bk) launch_colsum(dt, c->dK, d, dt, nullptr, 0, nullptr, c->gdt, GF(bk), c->partial, T, d, sc);
+  if (GF(bv) && w->bv) launch_colsum(dt, c->dV, d, dt, nullptr, 0, nullptr, c->gdt, GF(bv), c->partial, T, d, sc);
   TRY(run_gemm(c, nn(c->dK, d, w->wk, d, dU2, d, T, d, d), s));
   {
     GemmArgs a = nn(c->dV, d, w->wv, d, dU2, d, T, d, d);        // dU2 += dV . Wv
@@ -717,29 +721,29 @@ int backward_impl(revffn_ctx* c, const revffn_weights* w, const void* x1, const 
     TRY(run_gemm(c, a, s));
     void* n2 = at(c->n12, (size_t)T * h, es);
     void* dn2 = at(c->dn12, (size_t)T * h, es);
-    if (GF(pup_a)) { after(c, s, s0); TRY(run_gemm(c, tn(dU2, d, n2, h, GF(pup_a), h, d, h, T), s0)); }
+    if (GF(pup_a)) { after(c, s, s0); TRY(run_wgrad(c, tn(dU2, d, n2, h, GF(pup_a), h, d, h, T), s0)); }
     TRY(run_gemm(c, nn(dU2, d, w->pup_a, h, dn2, h, T, h, d), s));
     launch_rmsnorm_bwd(dt, c->sdt, dn2, h, x2, ld, w->norm_a2, dy2, ld, dx2, ld, c->rinv + T, T, h, f.rms_eps, s);
     launch_copy_rows(dt, c->g1, h, dx1, ld, T, h, s);              // dX1 = total gradient at Y1
     after(c, s, sc);
-    if (GF(norm_a1)) launch_zero(dt, GF(norm_a1), h, sc);          // stream 1 is not normalised in this block
-    if (GF(norm_a2)) launch_colsum(c->sdt, x2, ld, dt, dn2, h, c->rinv + T, dt, GF(norm_a2), c->partial, T, h, sc);
+    if (GF(norm_a1)) launch_zero(c->gdt, GF(norm_a1), h, sc);          // stream 1 is not normalised in this block
+    if (GF(norm_a2)) launch_colsum(c->sdt, x2, ld, dt, dn2, h, c->rinv + T, c->gdt, GF(norm_a2), c->partial, T, h, sc);
     after(c, sw, s);
     after(c, s0, s);
     after(c, sc, s);
     return 0;
   }
   if (s0 != s) wait_for(s, du1_done);
-  if (GF(pup_a)) { after(c, s, s0); TRY(run_gemm(c, tn(c->dU12, d, c->n12, h, GF(pup_a), h, d, h, 2 * T), s0)); }
+  if (GF(pup_a)) { after(c, s, s0); TRY(run_wgrad(c, tn(c->dU12, d, c->n12, h, GF(pup_a), h, d, h, 2 * T), s0)); }
   TRY(run_gemm(c, nn(c->dU12, d, w->pup_a, h, c->dn12, h, 2 * T, h, d), s));
   // dX1 = g1 + Norm'(dn1);  dX2 = dY2 + Norm'(dn2)
   launch_rmsnorm_bwd(dt, c->sdt, c->dn12, h, x1, ld, w->norm_a1, c->g1, h, dx1, ld, c->rinv, T, h, f.rms_eps, s);
   launch_rmsnorm_bwd(dt, c->sdt, at(c->dn12, (size_t)T * h, es), h, x2, ld, w->norm_a2, dy2, ld, dx2, ld, c->rinv + T, T, h,
                      f.rms_eps, s);
   after(c, s, sc);
-  if (GF(norm_a1)) launch_colsum(c->sdt, x1, ld, dt, c->dn12, h, c->rinv, dt, GF(norm_a1), c->partial, T, h, sc);
+  if (GF(norm_a1)) launch_colsum(c->sdt, x1, ld, dt, c->dn12, h, c->rinv, c->gdt, GF(norm_a1), c->partial, T, h, sc);
   if (GF(norm_a2))
-    launch_colsum(c->sdt, x2, ld, dt, at(c->dn12, (size_t)T * h, es), h, c->rinv + T, dt, GF(norm_a2), c->partial, T, h, sc);
+    launch_colsum(c->sdt, x2, ld, dt, at(c->dn12, (size_t)T * h, es), h, c->rinv + T, c->gdt, GF(norm_a2), c->partial, T, h, sc);
   after(c, sw, s);                       // every weight gradient is complete for the caller's stream
   after(c, s0, s);
   after(c, sc, s);
@@ -759,6 +763,8 @@ size_t revffn_workspace_bytes(const revffn_config* cfg, int32_t max_B, int32_t m
   tmp.es = cfg->dtype == REVFFN_BF16 ? 2 : 4;
   tmp.sdt = cfg->fp32_streams ? REVFFN_F32 : cfg->dtype;
   tmp.ses = tmp.sdt == REVFFN_BF16 ? 2 : 4;
+  tmp.gdt = cfg->fp32_grads ? REVFFN_F32 : cfg->dtype;
+  tmp.ges = tmp.gdt == REVFFN_BF16 ? 2 : 4;
   tmp.maxT = max_B * max_S;
   return carve(&tmp, nullptr);
 }
@@ -782,6 +788,8 @@ int revffn_create(revffn_ctx** out, const revffn_config* cfg, int32_t max_B, int
   c->es = cfg->dtype == REVFFN_BF16 ? 2 : 4;
   c->sdt = cfg->fp32_streams ? REVFFN_F32 : cfg->dtype;
   c->ses = c->sdt == REVFFN_BF16 ? 2 : 4;
+  c->gdt = cfg->fp32_grads ? REVFFN_F32 : cfg->dtype;
+  c->ges = c->gdt == REVFFN_BF16 ? 2 : 4;
   c->maxT = max_B * max_S;
   c->slab_bytes = carve(c, nullptr);
   if (hipGetDevice(&c->device) != hipSuccess) { delete c->prof; delete c->ev_pool; delete c; return REVFFN_EHIP; }

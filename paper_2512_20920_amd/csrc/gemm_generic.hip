@@ -177,6 +177,7 @@ int launch_gemm_generic(const GemmArgs& g, GemmTypes t, hipStream_t s) {
     case 7: go<float, bf16, bf16, bf16>(g, s); break;               // fp32 A (router logit gradients), bf16 B/C
     case 9: go<bf16, float, float, bf16>(g, s); break;              // bf16 A, fp32 B/C (router logits)
     case 1: go<float, float, float, bf16>(g, s); break;             // router logits from float32 residual streams
+    case 5: go<float, bf16, float, bf16>(g, s); break;              // router weight gradient in float32
     default: return -1;
   }
   return 0;

@@ -13,14 +13,14 @@ def torch_dtype(dtype):
 
 
 def make_config(wl, causal=True, use_rope=True, norm_topk_prob=False, n_inv_iters=1,
-                rope_theta=1.0e6, rms_eps=1.0e-6, dtype=None, fp32_streams=False, symmetric=False):
+                rope_theta=1.0e6, rms_eps=1.0e-6, dtype=None, fp32_streams=False, symmetric=False, fp32_grads=False):
     """Config for a synth.Workload-like object (needs d_model, n_heads, ... and dtype)."""
     dt = wl.dtype if dtype is None else dtype
     return Config(d_model=wl.d_model, n_heads=wl.n_heads, head_dim=wl.head_dim, n_experts=wl.n_experts,
                   top_k=wl.top_k, d_expert=wl.d_expert, d_shared=wl.d_shared,
                   dtype=1 if dt == "bf16" else 0, causal=int(causal), use_rope=int(use_rope),
                   norm_topk_prob=int(norm_topk_prob), n_inv_iters=n_inv_iters,
-                  rope_theta=rope_theta, rms_eps=rms_eps, fp32_streams=int(bool(fp32_streams)), symmetric=int(bool(symmetric)))
+                  rope_theta=rope_theta, rms_eps=rms_eps, fp32_streams=int(bool(fp32_streams)), symmetric=int(bool(symmetric)), fp32_grads=int(bool(fp32_grads)))
 
 
 def upload(x, dtype, device="cuda"):
@@ -39,12 +39,16 @@ def upload_weights(W, dtype, device="cuda"):
     return out
 
 
-def alloc_grads(Wdev, skip=()):
-    """A gradient buffer per present weight (filled with NaN so an unwritten one is noticed)."""
+def alloc_grads(Wdev, skip=(), fp32=False):
+    """A gradient buffer per present weight (filled with NaN so an unwritten one is noticed); float32 buffers with
+    fp32=True (config.fp32_grads)."""
     out = {}
     for n in WEIGHT_FIELDS:
         v = Wdev.get(n)
-        out[n] = None if (v is None or n in skip) else torch.full_like(v, float("nan"))
+        if v is None or n in skip:
+            out[n] = None
+        else:
+            out[n] = torch.full_like(v, float("nan"), dtype=torch.float32 if fp32 else v.dtype)
     return out
 
 

@@ -43,13 +43,15 @@ def delta_err(gpu, ref, base, dt):
 class Case:
     """One workload on the GPU: uploaded inputs/weights plus a context."""
 
-    def __init__(self, wl, flags=None, mode=0, max_B=None, max_S=None, weights=None, inputs=None, fp32_streams=False):
+    def __init__(self, wl, flags=None, mode=0, max_B=None, max_S=None, weights=None, inputs=None, fp32_streams=False,
+                 fp32_grads=False):
         self.wl = wl
         self.flags = dict(flags or {})
         self.ocfg = oracle_cfg(wl, **self.flags)
         self.W = weights if weights is not None else synth.make_weights(wl)
         self.x1, self.x2, self.dy1, self.dy2 = inputs if inputs is not None else synth.make_inputs(wl)
-        self.cfg = Hn.make_config(wl, fp32_streams=fp32_streams, **self.flags)
+        self.cfg = Hn.make_config(wl, fp32_streams=fp32_streams, fp32_grads=fp32_grads, **self.flags)
+        self.fp32_grads = fp32_grads
         self.ctx = R.Context(self.cfg, max_B or wl.B, max_S or wl.S)
         self.ctx.set_kernel_mode(mode)
         self.ctx.enable_taps(True)
@@ -111,7 +113,7 @@ class Case:
         dy1d = self.up(self.dy1 if dy1 is None else dy1)
         dy2d = self.up(self.dy2 if dy2 is None else dy2)
         dx1d, dx2d = self.empty(), self.empty()
-        G = Hn.alloc_grads(self.Wd, skip=skip)
+        G = Hn.alloc_grads(self.Wd, skip=skip, fp32=self.fp32_grads)
         R.revffn_backward(self.ctx, self.Wd, x1d, x2d, y1d, dy1d, dy2d, dx1d, dx2d, G, self.B, self.S, self.h)
         torch.cuda.synchronize()
         return dx1d, dx2d, G

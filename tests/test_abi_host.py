@@ -39,7 +39,7 @@ def header_text():
 
 
 def test_struct_layouts_match_header():
-    assert ctypes.sizeof(R.Config) == 16 * 4
+    assert ctypes.sizeof(R.Config) == 17 * 4
     cbody = header_text()[header_text().index("typedef struct revffn_config {"):header_text().index("} revffn_config;")]
     assert tuple(re.findall(r"(?:int32_t|float)\s+([a-z_0-9]+);", cbody)) == tuple(n for n, _ in R.Config._fields_)
     assert ctypes.sizeof(R.Weights) == 21 * ctypes.sizeof(ctypes.c_void_p)
@@ -57,7 +57,7 @@ def test_workspace_bytes_and_bad_configs(lib):
     assert lib.revffn_workspace_bytes(ctypes.byref(cfg), 4, 32) > n
     bad = [dict(d_model=63), dict(n_heads=3), dict(top_k=0), dict(top_k=9), dict(n_experts=0), dict(dtype=2),
            dict(head_dim=15, n_heads=4, d_model=60), dict(n_inv_iters=-1), dict(rope_theta=0.0), dict(d_expert=0),
-           dict(n_experts=300, top_k=2), dict(top_k=17, n_experts=32), dict(fp32_streams=2), dict(symmetric=-1)]
+           dict(n_experts=300, top_k=2), dict(top_k=17, n_experts=32), dict(fp32_streams=2), dict(symmetric=-1), dict(fp32_grads=3)]
     for kw in bad:
         c = good_cfg(**kw)
         assert lib.revffn_workspace_bytes(ctypes.byref(c), 2, 32) == 0, kw

@@ -318,6 +318,37 @@ def test_symmetric_comparison_block(name, mode):
             assert torch.equal(G3[k], G4[k]), k
 
 
+@pytest.mark.parametrize("mode", [0, 1])
+def test_fp32_weight_gradients(mode):
+    """config.fp32_grads: every weight gradient lands in a float32 buffer.  Same parity bar against the oracle, and
+    rounding the float32 result to bf16 gives exactly the bf16-gradient run (only the final rounding differs)."""
+    wl = synth.WORKLOADS["mid_bf16"]
+    tol = TOL["bf16"]
+    case = Case(wl, mode=mode, fp32_grads=True)
+    ref = Case(wl, mode=mode)
+    y1d, y2d = case.forward()
+    x1d, x2d = case.inverse(y1d, y2d, n_iters=2)
+    errs = _backward_checks(case, x1d, x2d, y1d, tol)
+    dx1, dx2, G32 = case.backward(x1d, x2d, y1d)
+    ex1, ex2, G16 = ref.backward(x1d, x2d, y1d)
+    assert torch.equal(dx1, ex1) and torch.equal(dx2, ex2)
+    for k in G32:
+        if G32[k] is None:
+            continue
+        assert G32[k].dtype == torch.float32 and G16[k].dtype == (torch.float32 if k == "b_router" else torch.bfloat16)
+        assert torch.equal(G32[k].to(G16[k].dtype), G16[k]), k
+        assert not torch.equal(G32[k], G16[k].float()) or k == "b_router", k      # it really carries more bits
+    # frozen groups and the fused call take the same buffers
+    a, b, ga, gb = y1d.clone(), y2d.clone(), case.up(case.dy1), case.up(case.dy2)
+    G2 = Hn.alloc_grads(case.Wd, skip=("w_gate_up", "w_router"), fp32=True)
+    case.ctx.set_inv_iters(2)
+    R.revffn_inverse_backward(case.ctx, case.Wd, a, b, a, b, ga, gb, ga, gb, G2, wl.B, wl.S, wl.h, None)
+    torch.cuda.synchronize()
+    for k in G2:
+        if G2[k] is not None:
+            assert torch.equal(G2[k], G32[k]), k
+
+
 def _slow_contraction_case(name):
     """The synthetic weights contract by about 1e-5 per iteration; a sharper softmax (query projection x 128) and a
     larger branch (down adapter x 128) slow that to about 1e-2, so that a tolerance separates several iteration counts."""
