@@ -21,7 +21,7 @@ if torch.cuda.is_available():
     from helpers import Case, relerr, TOL, check_routing, delta_err
 
 
-def _forward_checks(case, tol):
+def _forward_checks(case, tol, min_same=0.97):
     wl, cfg, W = case.wl, case.ocfg, case.W
     y1d, y2d = case.forward()
     y1g, y2g = Hn.download(y1d), Hn.download(y2d)
@@ -38,7 +38,7 @@ def _forward_checks(case, tol):
     # end to end against the oracle's own Y1 as well (routing flips near ties are excluded)
     y1o, y2o, cache = O.forward(case.x1, case.x2, W, cfg, wl.B, wl.S, return_cache=True)
     same = (cache["moe"]["idx"] == cm["idx"]).all(axis=-1)
-    assert same.mean() > 0.97
+    assert same.mean() > min_same
     assert relerr(m_gpu[same & safe], cache["M"][same & safe]) < tol
     return y1d, y2d, rep
 
@@ -626,3 +626,48 @@ def test_smaller_call_on_larger_context_and_ragged_sizes():
         y1d, y2d, _ = _forward_checks(case, 1e-4)
         x1d, x2d = _inverse_checks(case, y1d, y2d, 1e-4, 1)
         _backward_checks(case, x1d, x2d, y1d, 1e-4)
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+def test_degenerate_routing_and_limits_bf16(mode):
+    """The routing shapes at the edges, on the bf16 path: experts without any row, one expert that takes every
+    token, top_k = n_experts (no selection), and the largest expert count and top_k the library accepts."""
+    import dataclasses
+    base = synth.WORKLOADS["mid_bf16"]
+    tol = TOL["bf16"]
+
+    def run(wl, W=None, n_iters=1, min_same=0.97):
+        case = Case(wl, mode=mode, weights=W)
+        y1d, y2d, _ = _forward_checks(case, tol, min_same)
+        x1d, x2d = _inverse_checks(case, y1d, y2d, tol, n_iters)
+        errs = _backward_checks(case, x1d, x2d, y1d, tol)
+        return case, errs
+
+    # (1) 3 tokens x top-3 over 12 experts: at least three experts get no row; their weight gradients are exact zeros
+    wl = dataclasses.replace(base, B=1, S=3)
+    case, _ = run(wl)
+    counts = case.routing()[2]
+    assert (counts == 0).sum() >= 3
+    x1d, x2d = case.up_s(case.x1), case.up_s(case.x2)
+    y1d, _ = case.forward()
+    _, _, G = case.backward(x1d, x2d, y1d)
+    for e in np.nonzero(counts == 0)[0]:
+        assert float(G["w_gate_up"][e].float().abs().max()) == 0.0 and float(G["w_down"][e].float().abs().max()) == 0.0
+    # (2) a router bias that sends every token to expert 5 first: one expert holds T rows, several 256-row tiles
+    wl = dataclasses.replace(base, B=3, S=200)
+    W = synth.make_weights(wl)
+    b = np.zeros(wl.n_experts)
+    b[5] = 1.5                      # ten times the spread of the logits at these weights
+    W["b_router"] = b
+    case, _ = run(wl, W)
+    assert case.routing()[2][5] == wl.T
+    # (3) top_k = n_experts: every expert for every token
+    wl = dataclasses.replace(base, n_experts=4, top_k=4, B=2, S=70)
+    case, _ = run(wl)
+    assert np.all(case.routing()[2] == wl.T)
+    # (4) the largest expert count and top_k accepted (256, 16), narrow experts, no shared expert
+    wl = dataclasses.replace(base, d_model=256, n_heads=2, head_dim=128, n_experts=256, top_k=16, d_expert=64,
+                             d_shared=0, B=2, S=40)
+    # (16 of 256 nearly equal logits: the selection at the oracle's own Y1 and at the GPU's bf16 Y1 differs for more
+    # tokens than elsewhere; at one and the same Y1 it is still bit-exact outside ties)
+    run(wl, min_same=0.6)
