@@ -60,6 +60,7 @@ struct revffn_ctx {
   int *idx, *counts, *offsets, *row_map, *inv_map;
   int *tg_a, *tm_a, *tg_b, *tm_b, *tf_a, *tf_b, *tg_c, *tm_c, *tf_c;
   int max_tiles_a, max_tiles_b, max_tiles_c;
+  int expert_nt = 0, expert_nn = 0;
   int expert_tile = 0;        // m-tile height of the MFMA expert GEMMs forced to 128 or 256 (REVFFN_EXPERT_TILE), 0 = by rows per expert
   int* tile_cnt;              // tiles in use of the three lists
   void *Xg, *GU, *Hh, *Yp, *GUs, *Hs, *Ys, *RS;
@@ -272,9 +273,17 @@ int run_gemm(revffn_ctx* c, GemmArgs g, int ta, int tb, int tc, hipStream_t s) {
   ProfScope ps(c, s, fl, by);
   if (c->dt == 1 && c->mode == 0 && ta == 1 && tb == 1) {
     if (g.group_mode == 1) {
-      // experts with more than ~96 rows on average: one 256-row tile (8 waves) streams each weight tile once where two
-      // 128-row tiles stream it twice (rows past the expert's end cost no traffic); measured 2-3 % of a step
-      const bool tall = c->expert_tile ? c->expert_tile == 256 : (i64)c->lastT_rows > (i64)96 * c->cfg.n_experts;
+      // Expert tiles stream weights that nothing else reads, so what counts is weight bytes in flight per CU: a
+      // 128x256 tile (3 stages) keeps 64 KiB of them in flight, 256x128 and 128x128 half of that.  Measured: 128x256
+      // is 1.5-3 % of a step faster on every workload and both layouts, except the weights-as-[k,n] layout (data
+      // gradients) while one 256-row tile holds a typical expert (96 < mean rows <= 192), where 256x128 is 3 % of
+      // that kernel faster.  Shapes: 1 = 128x128, 2 = 256x128, 3 = 128x256 (REVFFN_EXPERT_NT / REVFFN_EXPERT_NN force one).
+      const i64 rows = c->lastT_rows, E = c->cfg.n_experts;
+      int shape = g.b_trans ? c->expert_nn : c->expert_nt;
+      if (c->expert_tile) shape = c->expert_tile == 256 ? 2 : 1;
+      if (!shape) shape = (g.b_trans && rows > 96 * E && rows <= 192 * E) ? 2 : 3;
+      const bool tall = shape == 2;
+      g.tile_bn = shape == 3 ? 256 : 128;
       if (tall) {
         g.tile_group = c->tg_c; g.tile_m0 = c->tm_c; g.max_tiles = c->max_tiles_c; g.tile_bm = BM_C; g.tile_count = c->tile_cnt + 2;
         if (c->max_tiles_c < 32768) g.tile_first = c->tf_c;      // (the packed entry holds 15 + 16 bits)
@@ -802,6 +811,8 @@ int revffn_create(revffn_ctx** out, const revffn_config* cfg, int32_t max_B, int
   (void)hipMemset(c->wr_ext, 0, (size_t)((c->cfg.n_experts + (c->cfg.d_shared ? 1 : 0) + 7) / 8 * 8) * c->cfg.d_model * c->es);
   c->use_streams = getenv("REVFFN_NO_STREAMS") == nullptr;
   { const char* e = getenv("REVFFN_EXPERT_TILE"); if (e && (atoi(e) == 256 || atoi(e) == 128)) c->expert_tile = atoi(e); }
+  { const char* e = getenv("REVFFN_EXPERT_NT"); if (e && atoi(e) >= 1 && atoi(e) <= 3) c->expert_nt = atoi(e); }
+  { const char* e = getenv("REVFFN_EXPERT_NN"); if (e && atoi(e) >= 1 && atoi(e) <= 3) c->expert_nn = atoi(e); }
   c->sync_ev = new (std::nothrow) std::vector<hipEvent_t>();
   bool ok = c->sync_ev != nullptr;
   for (int i = 0; ok && i < 3; i++) ok = hipStreamCreateWithFlags(&c->side[i], hipStreamNonBlocking) == hipSuccess;

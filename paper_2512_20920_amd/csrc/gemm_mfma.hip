@@ -333,6 +333,7 @@ static void go(const GemmArgs& g0, hipStream_t s) {
 template <bool AT, bool BT, class TC> static void go_256x128(const GemmArgs& g, hipStream_t s) { go<256, 128, 4, AT, BT, TC, 8, 3>(g, s); }
 template <bool AT, bool BT, class TC> static void go_256x256(const GemmArgs& g, hipStream_t s) { go<256, 256, 2, AT, BT, TC, 8, 2>(g, s); }
 template <bool AT, bool BT, class TC> static void go_128x128(const GemmArgs& g, hipStream_t s) { go<128, 128, 2, AT, BT, TC, 4, 4>(g, s); }
+template <bool AT, bool BT, class TC> static void go_128x256(const GemmArgs& g, hipStream_t s) { go<128, 256, 2, AT, BT, TC, 8, 3>(g, s); }
 template <bool AT, bool BT, class TC> static void go_128x64(const GemmArgs& g, hipStream_t s) { go<128, 64, 2, AT, BT, TC, 4, 3>(g, s); }
 template <bool AT, bool BT, class TC> static void go_64x128(const GemmArgs& g, hipStream_t s) { go<64, 128, 1, AT, BT, TC, 4, 3>(g, s); }
 
@@ -361,6 +362,7 @@ static void pick_tile(const GemmArgs& g, hipStream_t s) {
     if constexpr (!AT) {
       if (g.tile_bm == 64) go_64x128<AT, BT, TC>(g, s);
       else if (g.tile_bm == 256) go_256x128<AT, BT, TC>(g, s);
+      else if (g.tile_bn == 256) go_128x256<AT, BT, TC>(g, s);
       else go_128x128<AT, BT, TC>(g, s);
     }
     return;
