@@ -159,6 +159,8 @@ def main():
                     help="stack workloads: > 0 = iterate each inverse until successive iterates differ by at most this "
                          "(host decision after every iteration), at most --inv-max-iters times")
     ap.add_argument("--inv-max-iters", type=int, default=8)
+    ap.add_argument("--graph", action="store_true",
+                    help="single-block workloads: capture one step into a HIP graph and time K replays of it")
     ap.add_argument("--fp32-grads", action="store_true", help="float32 weight-gradient buffers (dtype otherwise)")
     ap.add_argument("--symmetric", action="store_true",
                     help="the symmetric comparison block (queries from stream 2 too; closed-form inverse) instead of Eq. 1")
@@ -229,12 +231,25 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    run_step = step
+    if args.graph:
+        # the same calls recorded once (helper streams and their event dependencies included) and replayed
+        eager_stream, stream = stream, torch.cuda.Stream()       # step() enqueues on `stream`
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(stream):
+            with torch.cuda.graph(graph, stream=stream):
+                step()
+        stream = eager_stream
+        run_step = graph.replay
+        for _ in range(2):
+            run_step()
+        torch.cuda.synchronize()
     # timed region: exactly K steps, nothing else on the stream
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     e0.record(stream)
     for _ in range(args.steps):
-        step()
+        run_step()
     e1.record(stream)
     torch.cuda.synchronize()
     ms_per_step = e0.elapsed_time(e1) / args.steps
@@ -287,7 +302,7 @@ def main():
         "config": {"workload": f"{wl.name}: 1 RevFFN block, d={wl.d_model}, {wl.n_heads} heads x {wl.head_dim}, "
                                f"{wl.n_experts} experts top-{wl.top_k} I={wl.d_expert}, shared {wl.d_shared}, "
                                f"B={wl.B} S={wl.S}, weights N(0,0.02) inputs N(0,1) seed {wl.seed}",
-                   "n_inv_iters": args.inv_iters, "residual_streams": "f32" if args.fp32_streams else wl.dtype, "block": "symmetric comparison block" if args.symmetric else "RevFFN (Eq. 1-2)", "weight_gradients": "f32" if args.fp32_grads else wl.dtype, "calls": "forward+inverse+backward" if args.separate_calls else "forward+inverse_backward", "setup_s": round(t_setup, 1)},
+                   "n_inv_iters": args.inv_iters, "residual_streams": "f32" if args.fp32_streams else wl.dtype, "launch": "HIP graph replay" if args.graph else "eager", "block": "symmetric comparison block" if args.symmetric else "RevFFN (Eq. 1-2)", "weight_gradients": "f32" if args.fp32_grads else wl.dtype, "calls": "forward+inverse+backward" if args.separate_calls else "forward+inverse_backward", "setup_s": round(t_setup, 1)},
         "roofline": roofline, "kernels": kernels,
     }
     if not args.no_cpu_baseline:

@@ -671,3 +671,48 @@ def test_degenerate_routing_and_limits_bf16(mode):
     # (16 of 256 nearly equal logits: the selection at the oracle's own Y1 and at the GPU's bf16 Y1 differs for more
     # tokens than elsewhere; at one and the same Y1 it is still bit-exact outside ties)
     run(wl, min_same=0.6)
+
+
+def test_calls_can_be_captured_into_a_hip_graph():
+    """A step (forward + fused inverse/backward, helper streams included) captured once into a HIP graph and
+    replayed gives the bits of the eager calls, on every replay, with eager work and synchronisations between the
+    replays: the calls only enqueue kernels and event dependencies (no allocation, no memset node, no host wait)."""
+    wl = synth.WORKLOADS["mid_bf16"]
+    case = Case(wl)
+    x1d, x2d, dy1d, dy2d = case.up(case.x1), case.up(case.x2), case.up(case.dy1), case.up(case.dy2)
+    y1d, y2d, r1d, r2d, dx1d, dx2d = (case.empty() for _ in range(6))
+    G = Hn.alloc_grads(case.Wd)
+
+    def step(stream=None):
+        R.revffn_forward(case.ctx, case.Wd, x1d, x2d, y1d, y2d, wl.B, wl.S, wl.h, stream)
+        R.revffn_inverse_backward(case.ctx, case.Wd, y1d, y2d, r1d, r2d, dy1d, dy2d, dx1d, dx2d, G, wl.B, wl.S, wl.h,
+                                  None, stream)
+
+    outs = lambda: [t.clone() for t in (y1d, y2d, r1d, r2d, dx1d, dx2d)] + [G[k].clone() for k in sorted(G) if G[k] is not None]
+    step()
+    torch.cuda.synchronize()
+    want = outs()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        step(side)                                  # every kernel variant has run once before the capture
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            step(torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for t in (y1d, y2d, r1d, r2d, dx1d, dx2d):
+            t.fill_(float("nan"))
+        for k in G:
+            if G[k] is not None:
+                G[k].fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = outs()
+        assert all(torch.equal(a, b) for a, b in zip(got, want)), rep
+        # eager work on the same context between replays
+        case.ctx.set_inv_iters(2)
+        case.inverse(y1d, y2d)
+        case.ctx.set_inv_iters(1)
+        torch.cuda.synchronize()
