@@ -215,18 +215,20 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const bf16* A, cons
   const bf16* resid = (const bf16*)g.resid;
   if (!g.row_scale && !bias && !g.tap && !resid) {
     // plain store (all weight gradients, most projections): no per-element epilogue work
+    // the column blocks of one row are stored back to back, so that the 64-byte pieces of a line reach L2 together.
+    // (Staging the tile through LDS to store whole 128-byte lines, 16 bytes per lane, measured no faster: these
+    // stores are not what bounds the weight-gradient kernels.)
     const bool full = (m0 + BM <= m_end) && (n0 + BN <= g.N);
 #pragma unroll
-    for (int j = 0; j < TN; j++) {
-      const int n = n0 + wn + j * 32 + (lane & 31);
+    for (int i = 0; i < TE; i++) {
+      TC* cp = C + (i64)(m0 + wm + i * 32 + (lane >> 5) * 4) * g.ldc + n0 + wn + (lane & 31);
 #pragma unroll
-      for (int i = 0; i < TE; i++) {
-        TC* cp = C + (i64)(m0 + wm + i * 32 + (lane >> 5) * 4) * g.ldc + n;
+      for (int e = 0; e < 16; e++) {
+        const int dm = (e >> 2) * 8 + (e & 3);
+        const bool row_ok = full || (m0 + wm + i * 32 + (lane >> 5) * 4 + dm < m_end);
 #pragma unroll
-        for (int e = 0; e < 16; e++) {
-          const int dm = (e >> 2) * 8 + (e & 3);
-          if (full || (n < g.N && m0 + wm + i * 32 + (lane >> 5) * 4 + dm < m_end)) cp[(i64)dm * g.ldc] = (TC)acc[i][j][e];
-        }
+        for (int j = 0; j < TN; j++)
+          if (row_ok && (full || n0 + wn + j * 32 + (lane & 31) < g.N)) cp[(i64)dm * g.ldc + j * 32] = (TC)acc[i][j][e];
       }
     }
     return;
