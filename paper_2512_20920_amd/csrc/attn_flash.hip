@@ -21,6 +21,8 @@ typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 #define BKV 64            // rows of the tile that is streamed through LDS
 #define KST (DH + 8)      // LDS row stride (elements) of a tile read with 16-byte fragment reads
 #define VST (DH + 32)     // LDS row stride of a tile read with transposing reads
+#define BST (DH + 24)     // LDS row stride of a tile read both ways (backward: K; Q and dO): 76 dwords, i.e. rows 12
+                          // banks apart, so that 16 rows x 16 bytes and 4 rows x 32 bytes both fall on distinct banks
 #define LOG2E 1.4426950408889634f
 #define LN2 0.6931471805599453f
 
@@ -241,8 +243,8 @@ __global__ void __launch_bounds__(256, 2) flash_bwd_dq_k(const bf16* __restrict_
                                                       const float* __restrict__ lse, const float* __restrict__ dvec,
                                                       bf16* __restrict__ dq, int S, int H, int causal, float scale) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  bf16* sK = (bf16*)smem_raw;               // 2 stages [64][KST]
-  bf16* sV = sK + 2 * BKV * KST;            // 2 stages [64][KST]
+  bf16* sK = (bf16*)smem_raw;               // 2 stages [64][BST]
+  bf16* sV = sK + 2 * BKV * BST;            // 2 stages [64][BST]
   const int qt = gridDim.y - 1 - blockIdx.y;
   const int hh = blockIdx.x, b = blockIdx.z;
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6, g = lane >> 5;
@@ -277,8 +279,8 @@ __global__ void __launch_bounds__(256, 2) flash_bwd_dq_k(const bf16* __restrict_
   uint4 rk[4], rv[4];
   load_rows64(k + boff, ld, 0, S, rk);
   load_rows64(v + boff, ld, 0, S, rv);
-  store_rows64(sK, KST, rk);
-  store_rows64(sV, KST, rv);
+  store_rows64(sK, BST, rk);
+  store_rows64(sV, BST, rv);
   __syncthreads();
   for (int t = 0; t < nt; t++) {
     const int cur = t & 1, kv0 = t * BKV;
@@ -286,8 +288,8 @@ __global__ void __launch_bounds__(256, 2) flash_bwd_dq_k(const bf16* __restrict_
       load_rows64(k + boff, ld, kv0 + BKV, S, rk);
       load_rows64(v + boff, ld, kv0 + BKV, S, rv);
     }
-    const bf16* cK = sK + cur * BKV * KST;
-    const bf16* cV = sV + cur * BKV * KST;
+    const bf16* cK = sK + cur * BKV * BST;
+    const bf16* cV = sV + cur * BKV * BST;
     if (!causal || kv0 <= qw + 31) {
       f32x16 sacc[2], dpacc[2];
 #pragma unroll
@@ -298,8 +300,8 @@ __global__ void __launch_bounds__(256, 2) flash_bwd_dq_k(const bf16* __restrict_
       for (int kk = 0; kk < 8; kk++)
 #pragma unroll
         for (int j = 0; j < 2; j++) {
-          sacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(cK, KST, j * 32, kk, lane), qf[kk], sacc[j], 0, 0, 0);
-          dpacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(cV, KST, j * 32, kk, lane), dof[kk], dpacc[j], 0, 0, 0);
+          sacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(cK, BST, j * 32, kk, lane), qf[kk], sacc[j], 0, 0, 0);
+          dpacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(cV, BST, j * 32, kk, lane), dof[kk], dpacc[j], 0, 0, 0);
         }
       const bool need_mask = (kv0 + BKV > S) || (causal && kv0 + BKV - 1 > qw);
 #pragma unroll
@@ -320,13 +322,13 @@ __global__ void __launch_bounds__(256, 2) flash_bwd_dq_k(const bf16* __restrict_
           bf16x8 dsf = acc_to_frag(sacc[j], c);
 #pragma unroll
           for (int dtile = 0; dtile < 4; dtile++)
-            acc[dtile] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols_tr(cK, KST, j * 32 + c * 16, dtile * 32, lane),
+            acc[dtile] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols_tr(cK, BST, j * 32 + c * 16, dtile * 32, lane),
                                                                  dsf, acc[dtile], 0, 0, 0);
         }
     }
     if (t + 1 < nt) {
-      store_rows64(sK + (cur ^ 1) * BKV * KST, KST, rk);
-      store_rows64(sV + (cur ^ 1) * BKV * KST, KST, rv);
+      store_rows64(sK + (cur ^ 1) * BKV * BST, BST, rk);
+      store_rows64(sV + (cur ^ 1) * BKV * BST, BST, rv);
     }
     __syncthreads();
   }
@@ -356,9 +358,9 @@ __global__ void __launch_bounds__(256) flash_bwd_dkv_k(const bf16* __restrict__ 
                                                        bf16* __restrict__ dk, bf16* __restrict__ dv, int S, int H,
                                                        int causal, float scale) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  bf16* sQ = (bf16*)smem_raw;               // 2 stages [64][KST]
-  bf16* sO = sQ + 2 * BKV * KST;            // 2 stages [64][KST]  (dO)
-  float* sL = (float*)(sO + 2 * BKV * KST); // 2 stages [64] lse (log2 domain), then 2 stages [64] D
+  bf16* sQ = (bf16*)smem_raw;               // 2 stages [64][BST]
+  bf16* sO = sQ + 2 * BKV * BST;            // 2 stages [64][BST]  (dO)
+  float* sL = (float*)(sO + 2 * BKV * BST); // 2 stages [64] lse (log2 domain), then 2 stages [64] D
   float* sD = sL + 2 * BKV;
   const int kt = blockIdx.y;                // early key tiles see the most queries when causal: first
   const int hh = blockIdx.x, b = blockIdx.z;
@@ -406,8 +408,8 @@ __global__ void __launch_bounds__(256) flash_bwd_dkv_k(const bf16* __restrict__ 
     load_rows64(q + boff, ld, t_lo * BKV, S, rq);
     load_rows64(d_o + boff, ld, t_lo * BKV, S, ro);
     load_stats(t_lo * BKV);
-    store_rows64(sQ, KST, rq);
-    store_rows64(sO, KST, ro);
+    store_rows64(sQ, BST, rq);
+    store_rows64(sO, BST, ro);
     store_stats(0);
   }
   __syncthreads();
@@ -418,8 +420,8 @@ __global__ void __launch_bounds__(256) flash_bwd_dkv_k(const bf16* __restrict__ 
       load_rows64(d_o + boff, ld, q0 + BKV, S, ro);
       load_stats(q0 + BKV);
     }
-    const bf16* cQ = sQ + cur * BKV * KST;
-    const bf16* cO = sO + cur * BKV * KST;
+    const bf16* cQ = sQ + cur * BKV * BST;
+    const bf16* cO = sO + cur * BKV * BST;
     const float* cL = sL + cur * BKV;
     const float* cD = sD + cur * BKV;
     if (!causal || q0 + BKV - 1 >= kw) {     // some query of the tile can see some key of this wave
@@ -432,8 +434,8 @@ __global__ void __launch_bounds__(256) flash_bwd_dkv_k(const bf16* __restrict__ 
       for (int kk = 0; kk < 8; kk++)
 #pragma unroll
         for (int j = 0; j < 2; j++) {
-          sacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(cQ, KST, j * 32, kk, lane), kf[kk], sacc[j], 0, 0, 0);
-          dpacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(cO, KST, j * 32, kk, lane), vf[kk], dpacc[j], 0, 0, 0);
+          sacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(cQ, BST, j * 32, kk, lane), kf[kk], sacc[j], 0, 0, 0);
+          dpacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(cO, BST, j * 32, kk, lane), vf[kk], dpacc[j], 0, 0, 0);
         }
       const bool need_mask = causal && (q0 < kw + 31);           // some query of the tile precedes some key of the wave
 #pragma unroll
@@ -460,16 +462,16 @@ __global__ void __launch_bounds__(256) flash_bwd_dkv_k(const bf16* __restrict__ 
           bf16x8 dsf = acc_to_frag(dpacc[j], c);
 #pragma unroll
           for (int dtile = 0; dtile < 4; dtile++) {
-            dvacc[dtile] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols_tr(cO, KST, j * 32 + c * 16, dtile * 32, lane),
+            dvacc[dtile] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols_tr(cO, BST, j * 32 + c * 16, dtile * 32, lane),
                                                                    pf, dvacc[dtile], 0, 0, 0);
-            dkacc[dtile] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols_tr(cQ, KST, j * 32 + c * 16, dtile * 32, lane),
+            dkacc[dtile] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols_tr(cQ, BST, j * 32 + c * 16, dtile * 32, lane),
                                                                    dsf, dkacc[dtile], 0, 0, 0);
           }
         }
     }
     if (t + 1 < nt) {
-      store_rows64(sQ + (cur ^ 1) * BKV * KST, KST, rq);
-      store_rows64(sO + (cur ^ 1) * BKV * KST, KST, ro);
+      store_rows64(sQ + (cur ^ 1) * BKV * BST, BST, rq);
+      store_rows64(sO + (cur ^ 1) * BKV * BST, BST, ro);
       store_stats(cur ^ 1);
     }
     __syncthreads();
@@ -499,7 +501,7 @@ int launch_attn_bwd_flash(const void* q, const void* k, const void* v, const voi
     return 1;
   launch_attn_dvec(1, o, d_o, dvec, B, S, H, dh, s);
   const float scale = 1.0f / sqrtf((float)dh);
-  size_t sm1 = (size_t)4 * BKV * KST * sizeof(bf16);
+  size_t sm1 = (size_t)4 * BKV * BST * sizeof(bf16);
   size_t sm2 = sm1 + 4 * BKV * sizeof(float);
   static bool attr_set = false;
   if (!attr_set) {
