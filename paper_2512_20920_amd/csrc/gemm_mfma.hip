@@ -330,17 +330,20 @@ static void go(const GemmArgs& g0, hipStream_t s) {
   hipLaunchKernelGGL((gemm_mfma_k<BM, BN, WGM, AT, BT, TC, NW, NS>), grid, dim3(NW * 64), smem, s, g);
 }
 
-// The four tile shapes: 256x128 (8 waves, one workgroup per CU), 128x128 (4 waves, 4 stages), 128x64 and 64x128
-// (4 waves, two workgroups per CU).
+// The tile shapes: 256x128 and 128x256 (8 waves, one workgroup per CU), 128x128 (8 waves of 32x64, 4 stages: with one
+// workgroup per CU, two waves per SIMD hide each other's LDS and barrier waits; 10-17 % faster than 4 waves of 64x64
+// on the 2048^3 projections), 128x64 and 64x128 (4 waves, two workgroups per CU).
 template <bool AT, bool BT, class TC> static void go_256x128(const GemmArgs& g, hipStream_t s) { go<256, 128, 4, AT, BT, TC, 8, 3>(g, s); }
 template <bool AT, bool BT, class TC> static void go_256x256(const GemmArgs& g, hipStream_t s) { go<256, 256, 2, AT, BT, TC, 8, 2>(g, s); }
-template <bool AT, bool BT, class TC> static void go_128x128(const GemmArgs& g, hipStream_t s) { go<128, 128, 2, AT, BT, TC, 4, 4>(g, s); }
+template <bool AT, bool BT, class TC> static void go_128x128(const GemmArgs& g, hipStream_t s) { go<128, 128, 4, AT, BT, TC, 8, 4>(g, s); }
+template <bool AT, bool BT, class TC> static void go_128x128_w4(const GemmArgs& g, hipStream_t s) { go<128, 128, 2, AT, BT, TC, 4, 4>(g, s); }
 template <bool AT, bool BT, class TC> static void go_128x256(const GemmArgs& g, hipStream_t s) { go<128, 256, 2, AT, BT, TC, 8, 3>(g, s); }
 template <bool AT, bool BT, class TC> static void go_128x64(const GemmArgs& g, hipStream_t s) { go<128, 64, 2, AT, BT, TC, 4, 3>(g, s); }
 template <bool AT, bool BT, class TC> static void go_64x128(const GemmArgs& g, hipStream_t s) { go<64, 128, 1, AT, BT, TC, 4, 3>(g, s); }
 
-// REVFFN_GEMM_TILE (tuning aid): 1 = 128x128, 2 = 128x64, 3 = 64x128, 4 = 256x128, 5 = 256x256 (2 stages; measured
-// +3 % at 8192^3, worse on the block's shapes) for every non-grouped problem
+// REVFFN_GEMM_TILE (tuning aid): 1 = 128x128 with 4 waves, 2 = 128x64, 3 = 64x128, 4 = 256x128, 5 = 256x256 (2 stages;
+// measured +3 % at 8192^3, worse on the block's shapes), 6 = 128x128 with 8 waves of 64x32, 7 = 128x128 as used, for
+// every non-grouped problem
 static int tile_override() {
   static int v = -1;
   if (v < 0) { const char* e = getenv("REVFFN_GEMM_TILE"); v = e ? atoi(e) : 0; }
@@ -351,11 +354,13 @@ template <bool AT, bool BT, class TC>
 static void pick_tile(const GemmArgs& g, hipStream_t s) {
   if (g.group_mode != 1 && tile_override()) {
     switch (tile_override()) {
-      case 1: go_128x128<AT, BT, TC>(g, s); return;
+      case 1: go_128x128_w4<AT, BT, TC>(g, s); return;
       case 2: go_128x64<AT, BT, TC>(g, s); return;
       case 3: go_64x128<AT, BT, TC>(g, s); return;
       case 4: go_256x128<AT, BT, TC>(g, s); return;
       case 5: go_256x256<AT, BT, TC>(g, s); return;
+      case 6: go<128, 128, 2, AT, BT, TC, 8, 4>(g, s); return;   // 128x128 with 8 waves of 64x32
+      case 7: go_128x128<AT, BT, TC>(g, s); return;
     }
   }
   if (g.group_mode == 1) {
