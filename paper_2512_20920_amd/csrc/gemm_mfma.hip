@@ -233,23 +233,57 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const bf16* A, cons
     }
     return;
   }
+  // Every load of the epilogue happens before its first store.  On this ISA one counter tracks loads and stores, so a
+  // load (or a wait placed at the join of a skipped one) between two stores waits for the earlier store to complete
+  // and the 16 * TE * TN stores of a lane run one after the other; and the residual operand may be the output itself
+  // (in-place coupling update), so the compiler cannot hoist its loads past the stores by itself.  (resid either is
+  // C, element for element, or does not overlap it.)
+  // Tiles that lie wholly inside the problem (`full`, wave-uniform) take loops without any per-element branch: the
+  // waits the compiler places at branch joins would otherwise sit between the stores as well.
+  constexpr bool PRE = TE <= 2;                      // (taller wave tiles would spill: they load the residual in the loop)
+  const bool full = (m0 + BM <= m_end) && (n0 + BN <= g.N);
+  float rs[PRE ? TE : 1][16];
+  if (PRE) {
 #pragma unroll
-  for (int j = 0; j < TN; j++) {
+    for (int i = 0; i < TE; i++)
+#pragma unroll
+      for (int e = 0; e < 16; e++) {
+        const int m = m0 + wm + i * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+        rs[PRE ? i : 0][e] = (g.row_scale && (full || m < m_end)) ? g.row_scale[m] : 1.f;
+      }
+  }
+#pragma unroll
+  for (int j = 0; j < TN; j++) {                     // one 32-column block at a time: its loads, then its stores
     const int n = n0 + wn + j * 32 + (lane & 31);
-    if (n >= g.N) continue;
-    const float bv = bias ? (float)bias[n] : 0.f;
+    const float bv = (bias && (full || n < g.N)) ? (float)bias[n] : 0.f;
+    float rv[PRE ? TE : 1][16];
+    if (PRE && resid) {
+#pragma unroll
+      for (int i = 0; i < TE; i++)
+#pragma unroll
+        for (int e = 0; e < 16; e++) {
+          const int m = m0 + wm + i * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+          float r = 0.f;
+          if (full || (n < g.N && m < m_end))
+            r = g.resid_f32 ? ((const float*)g.resid)[(i64)m * g.ldr + n] : (float)resid[(i64)m * g.ldr + n];
+          rv[PRE ? i : 0][e] = r;
+        }
+    }
 #pragma unroll
     for (int i = 0; i < TE; i++) {
 #pragma unroll
       for (int e = 0; e < 16; e++) {
         const int m = m0 + wm + i * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
-        if (m >= m_end) continue;
-        float v = acc[i][j][e];
-        if (g.row_scale) v *= g.row_scale[m];
-        v += bv;
-        if (g.tap) g.tap[(i64)m * g.ldtap + n] = v;
-        if (resid) v = (g.resid_f32 ? ((const float*)g.resid)[(i64)m * g.ldr + n] : (float)resid[(i64)m * g.ldr + n]) + g.resid_sign * v;
-        C[(i64)m * g.ldc + n] = (TC)v;
+        if (full || (n < g.N && m < m_end)) {
+          float v = acc[i][j][e] * (PRE ? rs[PRE ? i : 0][e] : (g.row_scale ? g.row_scale[m] : 1.f)) + bv;
+          if (g.tap) g.tap[(i64)m * g.ldtap + n] = v;
+          if (resid) {
+            const float r = PRE ? rv[PRE ? i : 0][e]
+                                : (g.resid_f32 ? ((const float*)g.resid)[(i64)m * g.ldr + n] : (float)resid[(i64)m * g.ldr + n]);
+            v = r + g.resid_sign * v;
+          }
+          C[(i64)m * g.ldc + n] = (TC)v;
+        }
       }
     }
   }
@@ -361,6 +395,7 @@ static void pick_tile(const GemmArgs& g, hipStream_t s) {
       case 5: go_256x256<AT, BT, TC>(g, s); return;
       case 6: go<128, 128, 2, AT, BT, TC, 8, 4>(g, s); return;   // 128x128 with 8 waves of 64x32
       case 7: go_128x128<AT, BT, TC>(g, s); return;
+      case 8: go<128, 64, 4, AT, BT, TC, 8, 3>(g, s); return;    // 128x64 with 8 waves of 32x32
     }
   }
   if (g.group_mode == 1) {
