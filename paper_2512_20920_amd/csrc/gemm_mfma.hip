@@ -366,13 +366,14 @@ static void go(const GemmArgs& g0, hipStream_t s) {
 
 // The tile shapes: 256x128 and 128x256 (8 waves, one workgroup per CU), 128x128 (8 waves of 32x64, 4 stages: with one
 // workgroup per CU, two waves per SIMD hide each other's LDS and barrier waits; 10-17 % faster than 4 waves of 64x64
-// on the 2048^3 projections), 128x64 and 64x128 (4 waves, two workgroups per CU).
+// on the 2048^3 projections), 128x64 (8 waves of 32x32, two workgroups per CU; 1.5 % of a step over 4 waves of 64x32,
+// measured on one box with both builds) and 64x128 (4 waves, two workgroups per CU).
 template <bool AT, bool BT, class TC> static void go_256x128(const GemmArgs& g, hipStream_t s) { go<256, 128, 4, AT, BT, TC, 8, 3>(g, s); }
 template <bool AT, bool BT, class TC> static void go_256x256(const GemmArgs& g, hipStream_t s) { go<256, 256, 2, AT, BT, TC, 8, 2>(g, s); }
 template <bool AT, bool BT, class TC> static void go_128x128(const GemmArgs& g, hipStream_t s) { go<128, 128, 4, AT, BT, TC, 8, 4>(g, s); }
 template <bool AT, bool BT, class TC> static void go_128x128_w4(const GemmArgs& g, hipStream_t s) { go<128, 128, 2, AT, BT, TC, 4, 4>(g, s); }
 template <bool AT, bool BT, class TC> static void go_128x256(const GemmArgs& g, hipStream_t s) { go<128, 256, 2, AT, BT, TC, 8, 3>(g, s); }
-template <bool AT, bool BT, class TC> static void go_128x64(const GemmArgs& g, hipStream_t s) { go<128, 64, 2, AT, BT, TC, 4, 3>(g, s); }
+template <bool AT, bool BT, class TC> static void go_128x64(const GemmArgs& g, hipStream_t s) { go<128, 64, 4, AT, BT, TC, 8, 3>(g, s); }
 template <bool AT, bool BT, class TC> static void go_64x128(const GemmArgs& g, hipStream_t s) { go<64, 128, 1, AT, BT, TC, 4, 3>(g, s); }
 
 // REVFFN_GEMM_TILE (tuning aid): 1 = 128x128 with 4 waves, 2 = 128x64, 3 = 64x128, 4 = 256x128, 5 = 256x256 (2 stages;
