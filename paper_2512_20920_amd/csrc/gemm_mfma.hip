@@ -417,10 +417,15 @@ static void pick_tile(const GemmArgs& g, hipStream_t s) {
     // of a step faster (one resident workgroup per CU leaves the small critical-path kernels room to start).  A
     // persistent form (a workgroup walks over tiles and issues the next tile's first loads before it stores the
     // finished one) is 5 % faster alone and 3 % of a step slower next to the main stream, so it is not used.
-    static int v = -1;                 // REVFFN_WGRAD_TILE (tuning aid): 0 = 256x128, 1 = 128x128 2 stages, 2 = 128x64 2 stages
+    // With 8 waves and 2 stages (two workgroups, 16 waves per CU) a 128x128 tile is 7 % faster alone and 1-3 % of a
+    // step slower in the step, for the same reason.
+    static int v = -1;                 // REVFFN_WGRAD_TILE (tuning aid): 0 = 256x128, 1 = 128x128 4 waves 2 stages, 2 = 128x64 2 stages,
+                                       // 3 / 4 = 128x128 8 waves with 3 / 2 stages
     if (v < 0) { const char* e = getenv("REVFFN_WGRAD_TILE"); v = e ? atoi(e) : 0; }
     if (v == 1) go<128, 128, 2, AT, BT, TC, 4, 2>(g, s);
     else if (v == 2) go<128, 64, 2, AT, BT, TC, 4, 2>(g, s);
+    else if (v == 3) go<128, 128, 4, AT, BT, TC, 8, 3>(g, s);
+    else if (v == 4) go<128, 128, 4, AT, BT, TC, 8, 2>(g, s);
     else go_256x128<AT, BT, TC>(g, s);
     return;
   }
