@@ -495,3 +495,25 @@ def test_stack_sweep_matches_blockwise_chain():
         for k in gl:
             assert np.abs(gl[k] - grads[l][k]).max() < 1e-8 * max(1.0, np.abs(gl[k]).max()), (l, k)
     assert np.abs(g1 - dx1).max() < 1e-8 and np.abs(g2 - dx2).max() < 1e-8
+
+
+def test_row_sums_and_token_permutation_equivariance():
+    """Attention probabilities sum to one over the admissible keys; renormalised routing weights sum to one; the MoE
+    half acts on each token alone, so permuting the tokens permutes its output (and its routing) the same way."""
+    rng = np.random.default_rng(21)
+    cfg = O.replace(SMALL, norm_topk_prob=True)
+    W = rand_weights(cfg, rng, 0.3)
+    B, S = 2, 7
+    T = B * S
+    x1, x2 = rng.standard_normal((T, cfg.h)), rng.standard_normal((T, cfg.h))
+    _, ca = O.attn_half_forward(x1, x2, W, cfg, B, S, keep_probs=True)
+    P = ca["P"]                                              # [B, H, S, S]
+    assert np.abs(P.sum(axis=-1) - 1.0).max() < 1e-14
+    assert np.abs(np.triu(P, k=1)).max() == 0.0              # causal: nothing above the diagonal
+    M, cm = O.moe_half_forward(x1, W, cfg)
+    assert np.abs(cm["w"].sum(axis=-1) - 1.0).max() < 1e-14
+    perm = rng.permutation(T)
+    Mp, cp = O.moe_half_forward(x1[perm], W, cfg)
+    assert np.abs(Mp - M[perm]).max() < 1e-13
+    assert np.array_equal(cp["idx"], cm["idx"][perm])
+    assert cp["counts"].sum() == T * cfg.top_k and np.array_equal(cp["counts"], cm["counts"])
