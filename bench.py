@@ -159,6 +159,9 @@ def main():
                     help="stack workloads: > 0 = iterate each inverse until successive iterates differ by at most this "
                          "(host decision after every iteration), at most --inv-max-iters times")
     ap.add_argument("--inv-max-iters", type=int, default=8)
+    ap.add_argument("--train", choices=["all", "stage1", "stage2"], default="all",
+                    help="which weight gradients are asked for (the others are NULL and their GEMMs skipped): all; "
+                         "stage1 = the four projection adapters only; stage2 = everything but the router (paper section 3.3)")
     ap.add_argument("--graph", action="store_true",
                     help="single-block workloads: capture one step into a HIP graph and time K replays of it")
     ap.add_argument("--fp32-grads", action="store_true", help="float32 weight-gradient buffers (dtype otherwise)")
@@ -207,7 +210,10 @@ def main():
     W32 = synth.make_weights(wl, f64=False)
     x1, x2, dy1, dy2 = synth.make_inputs(wl)
     Wd = Hn.upload_weights(W32, wl.dtype)
-    G = Hn.alloc_grads(Wd, fp32=args.fp32_grads)
+    adapters = ("pup_a", "pdn_a", "pup_m", "pdn_m")
+    frozen = {"all": (), "stage1": tuple(n for n in R.WEIGHT_FIELDS if n not in adapters),
+              "stage2": ("w_router", "b_router")}[args.train]
+    G = Hn.alloc_grads(Wd, skip=frozen, fp32=args.fp32_grads)
     sdt = "f32" if args.fp32_streams else wl.dtype
     x1d, x2d, dy1d, dy2d = Hn.upload(x1, sdt), Hn.upload(x2, sdt), Hn.upload(dy1, wl.dtype), Hn.upload(dy2, wl.dtype)
     new = lambda dt=sdt: torch.empty((wl.T, wl.h), dtype=Hn.torch_dtype(dt), device="cuda")
@@ -302,7 +308,7 @@ def main():
         "config": {"workload": f"{wl.name}: 1 RevFFN block, d={wl.d_model}, {wl.n_heads} heads x {wl.head_dim}, "
                                f"{wl.n_experts} experts top-{wl.top_k} I={wl.d_expert}, shared {wl.d_shared}, "
                                f"B={wl.B} S={wl.S}, weights N(0,0.02) inputs N(0,1) seed {wl.seed}",
-                   "n_inv_iters": args.inv_iters, "residual_streams": "f32" if args.fp32_streams else wl.dtype, "launch": "HIP graph replay" if args.graph else "eager", "block": "symmetric comparison block" if args.symmetric else "RevFFN (Eq. 1-2)", "weight_gradients": "f32" if args.fp32_grads else wl.dtype, "calls": "forward+inverse+backward" if args.separate_calls else "forward+inverse_backward", "setup_s": round(t_setup, 1)},
+                   "n_inv_iters": args.inv_iters, "residual_streams": "f32" if args.fp32_streams else wl.dtype, "launch": "HIP graph replay" if args.graph else "eager", "block": "symmetric comparison block" if args.symmetric else "RevFFN (Eq. 1-2)", "weight_gradients": "f32" if args.fp32_grads else wl.dtype, "trained": args.train, "calls": "forward+inverse+backward" if args.separate_calls else "forward+inverse_backward", "setup_s": round(t_setup, 1)},
         "roofline": roofline, "kernels": kernels,
     }
     if not args.no_cpu_baseline:
