@@ -191,7 +191,7 @@ void launch_rmsnorm_bwd(int dt, int tx, const void* dy, i64 ldd, const void* x, 
 // Stage 1: block (column tile of 64, row chunk c) -> partial[c][col]; stage 2 adds the
 // chunks in index order.
 // ---------------------------------------------------------------------------------
-#define COLSUM_CHUNKS 16
+#define COLSUM_CHUNKS 32
 static int colsum_chunk_rows(int rows) { int c = cdiv(rows > 0 ? rows : 1, COLSUM_CHUNKS); return c < 32 ? 32 : c; }
 size_t colsum_partial_floats(int rows, int cols) { return (size_t)(COLSUM_CHUNKS + 1) * cols; }
 
@@ -220,6 +220,44 @@ __global__ void __launch_bounds__(256) colsum1_k(const TA* __restrict__ a, i64 l
     partial[(i64)blockIdx.y * cols + c] = v;
   }
 }
+// bf16 operands with 8 | cols at 16-byte aligned addresses: a thread owns 8 adjacent columns (16-byte loads) and every
+// 8th row of the chunk; the 8 row lanes are added in lane order.  Same two-stage, fixed-order scheme.
+__global__ void __launch_bounds__(256) colsum1_v8_k(const bf16* __restrict__ a, i64 lda, const bf16* __restrict__ b,
+                                                    i64 ldb, const float* __restrict__ sc,
+                                                    float* __restrict__ partial, int rows, int cols, int chunk) {
+  __shared__ float red[8][256];
+  const int cg = threadIdx.x & 31, q = threadIdx.x >> 5;
+  const int c = blockIdx.x * 256 + cg * 8;
+  const int r0 = blockIdx.y * chunk, r1 = min(rows, r0 + chunk);
+  float acc[8];
+#pragma unroll
+  for (int i = 0; i < 8; i++) acc[i] = 0.f;
+  if (c < cols) {
+#pragma unroll 4
+    for (int t = r0 + q; t < r1; t += 8) {
+      const bf16x8_v av = *(const bf16x8_v*)(a + (i64)t * lda + c);
+      const float w = sc ? sc[t] : 1.f;
+      if (b) {
+        const bf16x8_v bv = *(const bf16x8_v*)(b + (i64)t * ldb + c);
+#pragma unroll
+        for (int i = 0; i < 8; i++) acc[i] += (float)av[i] * (float)bv[i] * w;
+      } else {
+#pragma unroll
+        for (int i = 0; i < 8; i++) acc[i] += (float)av[i] * w;
+      }
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < 8; i++) red[q][cg * 8 + i] = acc[i];
+  __syncthreads();
+  const int cc = blockIdx.x * 256 + threadIdx.x;
+  if (cc < cols) {
+    float v = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; j++) v += red[j][threadIdx.x];
+    partial[(i64)blockIdx.y * cols + cc] = v;
+  }
+}
 template <class TO>
 __global__ void colsum2_k(const float* __restrict__ partial, TO* __restrict__ out, int chunks, int cols) {
   int c = blockIdx.x * blockDim.x + threadIdx.x;
@@ -234,8 +272,15 @@ static void colsum_go(const void* a, i64 lda, const void* b, i64 ldb, const floa
                       float* partial, int rows, int cols, hipStream_t s) {
   int chunk = colsum_chunk_rows(rows);
   int chunks = cdiv(rows > 0 ? rows : 1, chunk);
-  hipLaunchKernelGGL((colsum1_k<TA, TB>), dim3(cdiv(cols, 64), chunks), dim3(256), 0, s, (const TA*)a, lda,
-                     (const TB*)b, ldb, sc, partial, rows, cols, chunk);
+  constexpr bool both_bf16 = sizeof(TA) == 2 && sizeof(TB) == 2;
+  if (both_bf16 && (cols & 7) == 0 && (lda & 7) == 0 && (!b || (ldb & 7) == 0) && ((uintptr_t)a & 15) == 0 &&
+      ((uintptr_t)b & 15) == 0) {
+    hipLaunchKernelGGL(colsum1_v8_k, dim3(cdiv(cols, 256), chunks), dim3(256), 0, s, (const bf16*)a, lda, (const bf16*)b,
+                       ldb, sc, partial, rows, cols, chunk);
+  } else {
+    hipLaunchKernelGGL((colsum1_k<TA, TB>), dim3(cdiv(cols, 64), chunks), dim3(256), 0, s, (const TA*)a, lda,
+                       (const TB*)b, ldb, sc, partial, rows, cols, chunk);
+  }
   if (tout == 0)
     hipLaunchKernelGGL(colsum2_k<float>, dim3(cdiv(cols, 256)), dim3(256), 0, s, partial, (float*)out, chunks, cols);
   else
