@@ -1062,9 +1062,13 @@ int revffn_get_branch(revffn_ctx* c, int32_t which, float* dst, void* stream) {
 int revffn_op_gemm(int32_t dtype, int32_t kernel_mode, const void* a, const void* b, void* c, int32_t M, int32_t N,
                    int32_t K, int64_t lda, int64_t ldb, int64_t ldc, int32_t a_trans, int32_t b_trans,
                    int32_t out_f32, void* stream) {
-  if ((dtype != 0 && dtype != 1) || kernel_mode < 0 || kernel_mode > 2 || !a || !b || !c || M < 1 || N < 1 || K < 0)
+  const int tile = kernel_mode >> 8;       // bits 8 and up: MFMA tile shape to force (1..8), 0 = chosen by size
+  kernel_mode &= 0xff;
+  if ((dtype != 0 && dtype != 1) || kernel_mode < 0 || kernel_mode > 2 || tile < 0 || tile > 8 || !a || !b || !c ||
+      M < 1 || N < 1 || K < 0)
     return REVFFN_EINVAL;
   GemmArgs g = nt(a, lda, b, ldb, c, ldc, M, N, K);
+  g.force_tile = tile;
   g.a_trans = a_trans ? 1 : 0;
   g.b_trans = b_trans ? 1 : 0;
   GemmTypes t{dtype, dtype, out_f32 ? 0 : dtype, dtype};

@@ -387,8 +387,9 @@ static int tile_override() {
 
 template <bool AT, bool BT, class TC>
 static void pick_tile(const GemmArgs& g, hipStream_t s) {
-  if (g.group_mode != 1 && tile_override()) {
-    switch (tile_override()) {
+  const int forced = g.force_tile ? g.force_tile : tile_override();
+  if (g.group_mode != 1 && forced) {
+    switch (forced) {
       case 1: go_128x128_w4<AT, BT, TC>(g, s); return;
       case 2: go_128x64<AT, BT, TC>(g, s); return;
       case 3: go_64x128<AT, BT, TC>(g, s); return;

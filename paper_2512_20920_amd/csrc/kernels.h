@@ -31,6 +31,7 @@ struct GemmArgs {
   float* tap = nullptr; i64 ldtap = 0;
   int group_mode = 0; int n_groups = 1; const int* offsets = nullptr;
   const int* tile_group = nullptr; const int* tile_m0 = nullptr; int max_tiles = 0; int tile_bm = 0;
+  int force_tile = 0;                    // MFMA kernel, dense problems: tile shape forced for this launch (unit tests), 0 = by size
   int tile_bn = 0;                       // MFMA expert tiles of height 128: 256 = 128x256 tiles, else 128x128
   i64 b_group_stride = 0, c_group_stride = 0;
   // generic kernel only: the k range is cut into split_k slices whose fp32 partial tiles go to

@@ -47,6 +47,27 @@ def test_mfma_gemm_layouts(layout, M, N, K):
     assert relerr(Hn.download(cd), ref) < 6e-3
 
 
+@pytest.mark.parametrize("tile", [1, 2, 3, 4, 5, 6, 7, 8])
+@pytest.mark.parametrize("layout", ["nt", "nn", "tn"])
+def test_mfma_gemm_every_tile_shape(layout, tile):
+    """Every tile shape of the MFMA kernel (forced per launch) on shapes with ragged last tiles in m, n and k,
+    including problems smaller than one tile."""
+    for (M, N, K) in [(264, 328, 136), (520, 264, 200), (40, 72, 24)]:
+        rng = np.random.default_rng(M + 3 * N + 5 * K + tile)
+        A, Bm = _bf(rng, (M, K)), _bf(rng, (K, N))
+        ref = A @ Bm
+        a_trans, b_trans = layout == "tn", layout in ("nn", "tn")
+        a_host = A.T.copy() if a_trans else A
+        b_host = Bm if b_trans else Bm.T.copy()
+        ad, bd = Hn.upload(a_host, "bf16"), Hn.upload(b_host, "bf16")
+        for out_f32 in (False, True):
+            cd = torch.full((M, N), float("nan"), dtype=torch.float32 if out_f32 else torch.bfloat16, device="cuda")
+            R.revffn_op_gemm(1, 2 + 256 * tile, ad, bd, cd, M, N, K, a_host.shape[1], b_host.shape[1], N, a_trans,
+                             b_trans, out_f32)
+            torch.cuda.synchronize()
+            assert relerr(Hn.download(cd), ref) < (1e-5 if out_f32 else 6e-3), (layout, tile, M, N, K, out_f32)
+
+
 def _attention_case(B, S, H, dh, causal, mode, dtype):
     rng = np.random.default_rng(S * 31 + H + (7 if causal else 0))
     rnd = (lambda s, sc=1.0: _bf(rng, s, sc)) if dtype == 1 else \
