@@ -296,7 +296,9 @@ int revffn_op_tile_placement(int32_t group_mode, int32_t tiles_m, int32_t tiles_
  * host until the recorded events have completed and returns the sums over all launches of
  * kernel `kid` since enable: elapsed milliseconds, launch count, flops, bytes (any output
  * may be NULL).  kernel_name(kid) is the kernel family the id stands for, NULL past the
- * last id. */
+ * last id.  Families: the matrix-core GEMM by operand layout ("gemm_mfma_nt" / "_nn" / "_tn"),
+ * the same three over per-expert weights ("..._experts": tile lists or per-expert row
+ * ranges, each expert's weights moved once), the generic GEMM, and the attention kernels. */
 int revffn_profile_enable(revffn_ctx *ctx, int32_t on);
 int revffn_profile_read(revffn_ctx *ctx, int32_t kid, double *ms_total, int64_t *launches,
                         double *flops, double *bytes);

@@ -24,11 +24,15 @@ struct Carver {            // hands out 256-byte aligned slices of one allocatio
 
 }  // namespace
 
+// Kernel families of the per-launch timing.  The expert GEMMs (one weight matrix per expert, streamed once: bound by
+// HBM) are kept apart from the dense GEMMs of the same operand layout (bound by the matrix cores).
 enum { KID_GEMM_NT = 0, KID_GEMM_NN, KID_GEMM_TN, KID_GEMM_GENERIC, KID_ATTN_FWD_FLASH, KID_ATTN_BWD_FLASH,
-       KID_ATTN_FWD_GENERIC, KID_ATTN_BWD_GENERIC, KID_COUNT };
+       KID_ATTN_FWD_GENERIC, KID_ATTN_BWD_GENERIC, KID_GEMM_NT_EXPERTS, KID_GEMM_NN_EXPERTS, KID_GEMM_TN_EXPERTS,
+       KID_COUNT };
 static const char* const kid_names[KID_COUNT] = {"gemm_mfma_nt", "gemm_mfma_nn", "gemm_mfma_tn", "gemm_generic",
                                                  "attn_fwd_flash", "attn_bwd_flash", "attn_fwd_generic",
-                                                 "attn_bwd_generic"};
+                                                 "attn_bwd_generic", "gemm_mfma_nt_experts", "gemm_mfma_nn_experts",
+                                                 "gemm_mfma_tn_experts"};
 struct ProfRec { int kid; hipEvent_t a, b; double flops, bytes; };
 
 struct revffn_ctx {
@@ -293,7 +297,8 @@ int run_gemm(revffn_ctx* c, GemmArgs g, int ta, int tb, int tc, hipStream_t s) {
       }
     }
     if (launch_gemm_mfma(g, t, s) == 0) {
-      ps.done(g.a_trans ? KID_GEMM_TN : (g.b_trans ? KID_GEMM_NN : KID_GEMM_NT));
+      if (g.group_mode) ps.done(g.a_trans ? KID_GEMM_TN_EXPERTS : (g.b_trans ? KID_GEMM_NN_EXPERTS : KID_GEMM_NT_EXPERTS));
+      else ps.done(g.a_trans ? KID_GEMM_TN : (g.b_trans ? KID_GEMM_NN : KID_GEMM_NT));
       return 0;
     }
   }

@@ -233,58 +233,86 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const bf16* A, cons
     }
     return;
   }
-  // Every load of the epilogue happens before its first store.  On this ISA one counter tracks loads and stores, so a
-  // load (or a wait placed at the join of a skipped one) between two stores waits for the earlier store to complete
-  // and the 16 * TE * TN stores of a lane run one after the other; and the residual operand may be the output itself
-  // (in-place coupling update), so the compiler cannot hoist its loads past the stores by itself.  (resid either is
-  // C, element for element, or does not overlap it.)
-  // Tiles that lie wholly inside the problem (`full`, wave-uniform) take loops without any per-element branch: the
-  // waits the compiler places at branch joins would otherwise sit between the stores as well.
-  constexpr bool PRE = TE <= 2;                      // (taller wave tiles would spill: they load the residual in the loop)
+  // Two phases per 32-column block: every load (row scale, bias, residual) and all arithmetic on loaded values
+  // first, then nothing but stores.  On this ISA one counter tracks loads and stores, and where a store may or may
+  // not have been issued (rows and columns past the problem's edge are masked per lane) the compiler can only wait
+  // for "everything": a use of a loaded value between two stores then waits for the earlier store to complete, and
+  // the 16 * TE * TN stores of a lane run one after the other (the coupling GEMMs with a residual operand took
+  // twice as long as the same GEMM with a plain store).  So loads are never masked (indices past the edge are
+  // clamped to the last valid row / column instead), the finished values are pinned in registers before the first
+  // store (the empty asm keeps the compiler from sinking the arithmetic into the masked store blocks), and the
+  // store phase has nothing to wait for.  The residual operand may be the output itself (in-place coupling update):
+  // it either is C, element for element, or does not overlap it, and each lane reads its elements before it writes.
+  constexpr int GI = 1;                              // 32-row blocks whose loads are issued together (more would spill at TE = 2)
   const bool full = (m0 + BM <= m_end) && (n0 + BN <= g.N);
-  float rs[PRE ? TE : 1][16];
-  if (PRE) {
+  const int m_last = m_end - 1, n_last = g.N - 1;
+  auto row_of = [&](int i, int e) { return m0 + wm + i * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3); };
+  float rs[GI][16];
+  auto load_rs = [&](int i0) {
+    if (g.row_scale) {
 #pragma unroll
-    for (int i = 0; i < TE; i++)
+      for (int ii = 0; ii < GI; ii++)
 #pragma unroll
-      for (int e = 0; e < 16; e++) {
-        const int m = m0 + wm + i * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
-        rs[PRE ? i : 0][e] = (g.row_scale && (full || m < m_end)) ? g.row_scale[m] : 1.f;
-      }
-  }
+        for (int e = 0; e < 16; e++) rs[ii][e] = g.row_scale[min(row_of(i0 + ii, e), m_last)];
+    } else {
 #pragma unroll
-  for (int j = 0; j < TN; j++) {                     // one 32-column block at a time: its loads, then its stores
+      for (int ii = 0; ii < GI; ii++)
+#pragma unroll
+        for (int e = 0; e < 16; e++) rs[ii][e] = 1.f;
+    }
+  };
+  if (GI == TE) load_rs(0);
+#pragma unroll
+  for (int j = 0; j < TN; j++) {
     const int n = n0 + wn + j * 32 + (lane & 31);
-    const float bv = (bias && (full || n < g.N)) ? (float)bias[n] : 0.f;
-    float rv[PRE ? TE : 1][16];
-    if (PRE && resid) {
+    const bool n_ok = full || n < g.N;
+    const int nn = min(n, n_last);
+    const float bv = bias ? (float)bias[nn] : 0.f;
 #pragma unroll
-      for (int i = 0; i < TE; i++)
+    for (int i0 = 0; i0 < TE; i0 += GI) {
+      if (GI != TE) load_rs(i0);
+      // ---- phase 1: loads and arithmetic
+      float rv[GI][16];
+      if (resid) {
+        if (g.resid_f32) {
+#pragma unroll
+          for (int ii = 0; ii < GI; ii++)
+#pragma unroll
+            for (int e = 0; e < 16; e++)
+              rv[ii][e] = ((const float*)g.resid)[(i64)min(row_of(i0 + ii, e), m_last) * g.ldr + nn];
+        } else {
+#pragma unroll
+          for (int ii = 0; ii < GI; ii++)
+#pragma unroll
+            for (int e = 0; e < 16; e++) rv[ii][e] = (float)resid[(i64)min(row_of(i0 + ii, e), m_last) * g.ldr + nn];
+        }
+      } else {
+#pragma unroll
+        for (int ii = 0; ii < GI; ii++)
+#pragma unroll
+          for (int e = 0; e < 16; e++) rv[ii][e] = 0.f;
+      }
+#pragma unroll
+      for (int ii = 0; ii < GI; ii++)
 #pragma unroll
         for (int e = 0; e < 16; e++) {
-          const int m = m0 + wm + i * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
-          float r = 0.f;
-          if (full || (n < g.N && m < m_end))
-            r = g.resid_f32 ? ((const float*)g.resid)[(i64)m * g.ldr + n] : (float)resid[(i64)m * g.ldr + n];
-          rv[PRE ? i : 0][e] = r;
+          float v = acc[i0 + ii][j][e] * rs[ii][e] + bv;       // the value the tap records
+          float o = resid ? rv[ii][e] + g.resid_sign * v : v;
+          asm volatile("" : "+v"(v), "+v"(o));
+          acc[i0 + ii][j][e] = v;
+          rv[ii][e] = o;
         }
-    }
+      // ---- phase 2: stores
 #pragma unroll
-    for (int i = 0; i < TE; i++) {
+      for (int ii = 0; ii < GI; ii++)
 #pragma unroll
-      for (int e = 0; e < 16; e++) {
-        const int m = m0 + wm + i * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
-        if (full || (n < g.N && m < m_end)) {
-          float v = acc[i][j][e] * (PRE ? rs[PRE ? i : 0][e] : (g.row_scale ? g.row_scale[m] : 1.f)) + bv;
-          if (g.tap) g.tap[(i64)m * g.ldtap + n] = v;
-          if (resid) {
-            const float r = PRE ? rv[PRE ? i : 0][e]
-                                : (g.resid_f32 ? ((const float*)g.resid)[(i64)m * g.ldr + n] : (float)resid[(i64)m * g.ldr + n]);
-            v = r + g.resid_sign * v;
+        for (int e = 0; e < 16; e++) {
+          const int m = row_of(i0 + ii, e);
+          if (n_ok && (full || m < m_end)) {
+            if (g.tap) g.tap[(i64)m * g.ldtap + n] = acc[i0 + ii][j][e];
+            C[(i64)m * g.ldc + n] = (TC)rv[ii][e];
           }
-          C[(i64)m * g.ldc + n] = (TC)v;
         }
-      }
     }
   }
 }
