@@ -116,12 +116,11 @@ __global__ void __launch_bounds__(256) gemm_generic_k(GemmArgs g) {
   for (int i = 0; i < 4; i++) {
     int m = m0 + ty * 4 + i;
     if (m >= m_end) continue;
-    float rs = g.row_scale ? g.row_scale[m] : 1.f;
 #pragma unroll
     for (int j = 0; j < 4; j++) {
       int n = n0 + tx * 4 + j;
       if (n >= g.N) continue;
-      float v = acc[i][j] * rs;
+      float v = acc[i][j];
       if (cscale) v *= to_f(cscale[n]);
       if (bias) v += to_f(bias[n]);
       if (g.tap) g.tap[(i64)m * g.ldtap + n] = v;
@@ -139,7 +138,6 @@ __global__ void __launch_bounds__(256) splitk_reduce_k(GemmArgs g) {
   int m = (int)(e / g.N), n = (int)(e % g.N);
   float v = 0.f;
   for (int z = 0; z < g.split_k; z++) v += g.splitk_ws[(i64)z * g.M * g.N + e];
-  if (g.row_scale) v *= g.row_scale[m];
   if (g.col_scale) v *= to_f(((const TS*)g.col_scale)[n]);
   if (g.bias) v += to_f(((const TS*)g.bias)[n]);
   if (g.tap) g.tap[(i64)m * g.ldtap + n] = v;

@@ -213,7 +213,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const bf16* A, cons
   }
   const bf16* bias = (const bf16*)g.bias;
   const bf16* resid = (const bf16*)g.resid;
-  if (!g.row_scale && !bias && !g.tap && !resid) {
+  if (!bias && !g.tap && !resid) {
     // plain store (all weight gradients, most projections): no per-element epilogue work
     // the column blocks of one row are stored back to back, so that the 64-byte pieces of a line reach L2 together.
     // (Staging the tile through LDS to store whole 128-byte lines, 16 bytes per lane, measured no faster: these
@@ -233,7 +233,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const bf16* A, cons
     }
     return;
   }
-  // Two phases per 32-column block: every load (row scale, bias, residual) and all arithmetic on loaded values
+  // Two phases per 32-column block: every load (bias, residual) and all arithmetic on loaded values
   // first, then nothing but stores.  On this ISA one counter tracks loads and stores, and where a store may or may
   // not have been issued (rows and columns past the problem's edge are masked per lane) the compiler can only wait
   // for "everything": a use of a loaded value between two stores then waits for the earlier store to complete, and
@@ -247,21 +247,6 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const bf16* A, cons
   const bool full = (m0 + BM <= m_end) && (n0 + BN <= g.N);
   const int m_last = m_end - 1, n_last = g.N - 1;
   auto row_of = [&](int i, int e) { return m0 + wm + i * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3); };
-  float rs[GI][16];
-  auto load_rs = [&](int i0) {
-    if (g.row_scale) {
-#pragma unroll
-      for (int ii = 0; ii < GI; ii++)
-#pragma unroll
-        for (int e = 0; e < 16; e++) rs[ii][e] = g.row_scale[min(row_of(i0 + ii, e), m_last)];
-    } else {
-#pragma unroll
-      for (int ii = 0; ii < GI; ii++)
-#pragma unroll
-        for (int e = 0; e < 16; e++) rs[ii][e] = 1.f;
-    }
-  };
-  if (GI == TE) load_rs(0);
 #pragma unroll
   for (int j = 0; j < TN; j++) {
     const int n = n0 + wn + j * 32 + (lane & 31);
@@ -270,7 +255,6 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const bf16* A, cons
     const float bv = bias ? (float)bias[nn] : 0.f;
 #pragma unroll
     for (int i0 = 0; i0 < TE; i0 += GI) {
-      if (GI != TE) load_rs(i0);
       // ---- phase 1: loads and arithmetic
       float rv[GI][16];
       if (resid) {
@@ -296,7 +280,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const bf16* A, cons
       for (int ii = 0; ii < GI; ii++)
 #pragma unroll
         for (int e = 0; e < 16; e++) {
-          float v = acc[i0 + ii][j][e] * rs[ii][e] + bv;       // the value the tap records
+          float v = acc[i0 + ii][j][e] + bv;                   // the value the tap records
           float o = resid ? rv[ii][e] + g.resid_sign * v : v;
           asm volatile("" : "+v"(v), "+v"(o));
           acc[i0 + ii][j][e] = v;

@@ -9,7 +9,7 @@
 //   b_trans = 0: B(k,n) = RB[n*ldb + k]  ([out,in] weight)   b_trans = 1: B(k,n) = RB[row(k)*ldb + n]
 // row(i) = i, or gather[i] / gather_div when a gather list is given (a_gather acts on
 // the RA row index, b_gather on the RB row index when b_trans = 1).
-// Epilogue:  v = acc * (row_scale ? row_scale[m] : 1) + (bias ? bias[n] : 0);
+// Epilogue:  v = acc + (bias ? bias[n] : 0);
 //            (generic kernel only: v *= col_scale[n] first, if col_scale is given)
 //            if (tap) tap[m*ldtap+n] = v;
 //            if (resid) v = resid[m*ldr+n] + resid_sign * v;      C[m*ldc+n] = v
@@ -25,7 +25,7 @@ struct GemmArgs {
   i64 lda = 0, ldb = 0, ldc = 0;
   int a_trans = 0, b_trans = 0;
   const int* a_gather = nullptr; const int* b_gather = nullptr; int gather_div = 1;
-  const float* row_scale = nullptr; const void* bias = nullptr;
+  const void* bias = nullptr;
   const void* resid = nullptr; i64 ldr = 0; float resid_sign = 1.f;
   int resid_f32 = 0;                     // resid holds float32 whatever the side type is (fp32 residual streams)
   float* tap = nullptr; i64 ldtap = 0;
