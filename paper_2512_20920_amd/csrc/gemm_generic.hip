@@ -74,8 +74,7 @@ __global__ void __launch_bounds__(256) gemm_generic_k(GemmArgs g) {
         if (!g.b_trans) {
           v = to_f(Bm[(i64)n * g.ldb + k]);
         } else {
-          i64 r = g.b_gather ? (i64)(g.b_gather[k] / g.gather_div) : (i64)k;
-          v = to_f(Bm[r * g.ldb + n]);
+          v = to_f(Bm[(i64)k * g.ldb + n]);
         }
       }
       Bs[kk][nn] = v;

@@ -465,7 +465,6 @@ int launch_gemm_mfma(const GemmArgs& g, GemmTypes t, hipStream_t s) {
   if (g.group_mode == 2 && !(g.a_trans && g.b_trans)) return 1;
   if (g.group_mode == 1 && (g.a_trans || (g.tile_bm != 128 && g.tile_bm != 64 && g.tile_bm != 256))) return 1;
   if (g.a_gather && g.a_trans) return 1;
-  if (g.b_gather) return 1;                              // gather along k is not taken: materialise the rows
   if (g.group_mode != 1 && g.M <= 0) return 1;
   if (g.split_k > 1 && (g.group_mode != 0 || !g.splitk_ws)) return 1;
   if (g.col_scale && g.split_k <= 1) return 1;           // column scale lives in the split-k reduction only

@@ -6,9 +6,8 @@
 // One GEMM problem  C[M,N] = epilogue( sum_k A(m,k) * B(k,n) ).
 // Operands are row-major matrices RA / RB addressed through a transpose flag:
 //   a_trans = 0: A(m,k) = RA[row(m)*lda + k]      a_trans = 1: A(m,k) = RA[row(k)*lda + m]
-//   b_trans = 0: B(k,n) = RB[n*ldb + k]  ([out,in] weight)   b_trans = 1: B(k,n) = RB[row(k)*ldb + n]
-// row(i) = i, or gather[i] / gather_div when a gather list is given (a_gather acts on
-// the RA row index, b_gather on the RB row index when b_trans = 1).
+//   b_trans = 0: B(k,n) = RB[n*ldb + k]  ([out,in] weight)   b_trans = 1: B(k,n) = RB[k*ldb + n]
+// row(i) = i, or a_gather[i] / gather_div when a gather list is given (it acts on the RA row index).
 // Epilogue:  v = acc + (bias ? bias[n] : 0);
 //            (generic kernel only: v *= col_scale[n] first, if col_scale is given)
 //            if (tap) tap[m*ldtap+n] = v;
@@ -24,7 +23,7 @@ struct GemmArgs {
   int M = 0, N = 0, K = 0;
   i64 lda = 0, ldb = 0, ldc = 0;
   int a_trans = 0, b_trans = 0;
-  const int* a_gather = nullptr; const int* b_gather = nullptr; int gather_div = 1;
+  const int* a_gather = nullptr; int gather_div = 1;
   const void* bias = nullptr;
   const void* resid = nullptr; i64 ldr = 0; float resid_sign = 1.f;
   int resid_f32 = 0;                     // resid holds float32 whatever the side type is (fp32 residual streams)
