@@ -65,6 +65,7 @@ struct revffn_ctx {
   int *tg_a, *tm_a, *tg_b, *tm_b, *tf_a, *tf_b, *tg_c, *tm_c, *tf_c;
   int max_tiles_a, max_tiles_b, max_tiles_c;
   int expert_nt = 0, expert_nn = 0;
+  bool no_fused_swiglu = false; // REVFFN_NO_FUSED_SWIGLU (tuning aid): SwiGLU as a kernel of its own after the gate/up GEMM
   int expert_tile = 0;        // m-tile height of the MFMA expert GEMMs forced to 128 or 256 (REVFFN_EXPERT_TILE), 0 = by rows per expert
   int* tile_cnt;              // tiles in use of the three lists
   void *Xg, *GU, *Hh, *Yp, *GUs, *Hs, *Ys, *RS;
@@ -268,6 +269,7 @@ void gemm_work(const revffn_ctx* c, const GemmArgs& g, int ta, int tb, int tc, d
     *flops = 2 * M * N * R; *bytes = R * M * ea + R * N * eb + G * M * N * ec; }
   else { *flops = 2 * M * N * K; *bytes = M * K * ea + N * K * eb + M * N * ec; }
   if (g.resid) *bytes += M * N * (g.resid_f32 ? 4 : c->es);
+  if (g.act_half) *bytes += M * (double)g.act_half * ec;
 }
 
 int run_gemm(revffn_ctx* c, GemmArgs g, int ta, int tb, int tc, hipStream_t s) {
@@ -275,6 +277,13 @@ int run_gemm(revffn_ctx* c, GemmArgs g, int ta, int tb, int tc, hipStream_t s) {
   double fl = 0, by = 0;
   if (c->prof_on) gemm_work(c, g, ta, tb, tc, &fl, &by);
   ProfScope ps(c, s, fl, by);
+  // A gate/up GEMM asks for silu(gate) * up beside its output.  The matrix-core kernel does that in its epilogue;
+  // on every other route the GEMM is followed by the SwiGLU kernel, which reads the output back.
+  void* act_out = g.act_out;
+  const int act_half = g.act_half;
+  const i64 act_rows = g.group_mode == 1 ? c->lastT_rows : g.M;
+  if (act_half && c->no_fused_swiglu) { g.act_out = nullptr; g.act_half = 0; }
+  auto swiglu_after = [&]() { if (act_half && !g.act_half) launch_swiglu_fwd(c->dt, g.C, act_out, act_rows, act_half, s); };
   if (c->dt == 1 && c->mode == 0 && ta == 1 && tb == 1) {
     if (g.group_mode == 1) {
       // Expert tiles stream weights that nothing else reads, so what counts is weight bytes in flight per CU: a
@@ -299,12 +308,15 @@ int run_gemm(revffn_ctx* c, GemmArgs g, int ta, int tb, int tc, hipStream_t s) {
     if (launch_gemm_mfma(g, t, s) == 0) {
       if (g.group_mode) ps.done(g.a_trans ? KID_GEMM_TN_EXPERTS : (g.b_trans ? KID_GEMM_NN_EXPERTS : KID_GEMM_NT_EXPERTS));
       else ps.done(g.a_trans ? KID_GEMM_TN : (g.b_trans ? KID_GEMM_NN : KID_GEMM_NT));
+      swiglu_after();
       return 0;
     }
   }
   if (g.group_mode == 1) { g.tile_group = c->tg_a; g.tile_m0 = c->tm_a; g.max_tiles = c->max_tiles_a; g.tile_bm = BM_A; g.tile_count = c->tile_cnt; }
+  g.act_out = nullptr; g.act_half = 0;
   int e = launch_gemm_generic(g, t, s) == 0 ? 0 : REVFFN_EUNSUPPORTED;
   ps.done(KID_GEMM_GENERIC);
+  if (!e) swiglu_after();
   return e;
 }
 int run_gemm(revffn_ctx* c, const GemmArgs& g, hipStream_t s) { return run_gemm(c, g, c->dt, c->dt, c->dt, s); }
@@ -470,8 +482,9 @@ int moe_acts(revffn_ctx* c, const revffn_weights* w, const void* y1, i64 ld, int
   hipStream_t s0 = side(c, s, 0);
   if (Is) {                               // the shared expert needs Um only: next to routing + routed experts
     after(c, s, s0);
-    TRY(run_gemm(c, nt(c->Um, d, w->ws_gate_up, d, c->GUs, 2 * Is, T, 2 * Is, d), s0));
-    launch_swiglu_fwd(dt, c->GUs, c->Hs, T, Is, s0);
+    GemmArgs gs = nt(c->Um, d, w->ws_gate_up, d, c->GUs, 2 * Is, T, 2 * Is, d);
+    gs.act_out = c->Hs; gs.ldact = Is; gs.act_half = Is;      // Hs = silu(gate) * up with the GEMM
+    TRY(run_gemm(c, gs, s0));
     TRY(run_gemm(c, nt(c->Hs, Is, w->ws_down, Is, c->Ys, d, T, d, Is), s0));
   }
   if (q_x1) TRY(attn_q(c, w, q_x1, q_ld, qB, qS, s));
@@ -480,8 +493,8 @@ int moe_acts(revffn_ctx* c, const revffn_weights* w, const void* y1, i64 ld, int
   GemmArgs g1 = nt(c->Um, d, w->w_gate_up, d, c->GU, 2 * I, N, 2 * I, d);
   g1.group_mode = 1; g1.n_groups = E; g1.offsets = c->offsets; g1.b_group_stride = (i64)2 * I * d;
   g1.a_gather = c->row_map; g1.gather_div = k;
+  g1.act_out = c->Hh; g1.ldact = I; g1.act_half = I;          // Hh = silu(gate) * up with the GEMM
   TRY(run_gemm(c, g1, s));
-  launch_swiglu_fwd(dt, c->GU, c->Hh, N, I, s);
   GemmArgs g2 = nt(c->Hh, I, w->w_down, I, c->Yp, d, N, d, I);
   g2.group_mode = 1; g2.n_groups = E; g2.offsets = c->offsets; g2.b_group_stride = (i64)d * I;
   TRY(run_gemm(c, g2, s));
@@ -816,6 +829,7 @@ int revffn_create(revffn_ctx** out, const revffn_config* cfg, int32_t max_B, int
   (void)hipMemset(c->wr_ext, 0, (size_t)((c->cfg.n_experts + (c->cfg.d_shared ? 1 : 0) + 7) / 8 * 8) * c->cfg.d_model * c->es);
   c->use_streams = getenv("REVFFN_NO_STREAMS") == nullptr;
   { const char* e = getenv("REVFFN_EXPERT_TILE"); if (e && (atoi(e) == 256 || atoi(e) == 128)) c->expert_tile = atoi(e); }
+  { const char* e = getenv("REVFFN_NO_FUSED_SWIGLU"); c->no_fused_swiglu = e && atoi(e) != 0; }
   { const char* e = getenv("REVFFN_EXPERT_NT"); if (e && atoi(e) >= 1 && atoi(e) <= 3) c->expert_nt = atoi(e); }
   { const char* e = getenv("REVFFN_EXPERT_NN"); if (e && atoi(e) >= 1 && atoi(e) <= 3) c->expert_nn = atoi(e); }
   c->sync_ev = new (std::nothrow) std::vector<hipEvent_t>();

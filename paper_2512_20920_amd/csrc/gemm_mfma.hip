@@ -77,6 +77,21 @@ __device__ __forceinline__ void chunk_source(int pos, int row0, int row_lim, uns
   }
 }
 
+// The same for the weight tile of a gate/up GEMM with the SwiGLU epilogue: LDS row r of the tile holds weight row
+// (r>>5 & 1) * half + col0 + (r>>6) * 32 + (r & 31), i.e. each wave's 64 rows are 32 gate rows and the 32 up rows of
+// the same columns col0 + 32 w .. + 31 (col0 = first gate column of the tile; columns >= half are zeros).
+__device__ __forceinline__ void chunk_source_gate_up(int pos, int col0, int half, unsigned ld_bytes, int k0, int krange,
+                                                     unsigned* base, int* ntiles) {
+  const int r = pos >> 3, slot = pos & 7;
+  const int c = slot ^ ((r >> 1) & 7);
+  int col = col0 + (r >> 6) * 32 + (r & 31);
+  const bool in = col < half;
+  if (!in) col = half - 1;
+  const unsigned row = (unsigned)(((r >> 5) & 1) * half + col);
+  *base = row * ld_bytes + (unsigned)(k0 + c * 8) * 2u;
+  *ntiles = in ? (krange - c * 8 + BK - 1) / BK : 0;
+}
+
 // Per-lane LDS byte offset (inside the operand's tile, k-step kk = 0) of the MFMA fragment rows r0..r0+31:
 // lane (r = lane & 31, g = lane >> 5) holds k = 16*kk + 8*g .. +7 of row r0 + r.
 template <bool TR, int ROWS>
@@ -133,6 +148,8 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const bf16* A, cons
   for (int i = 0; i < LPW; i++) {
     const int j = wv * LPW + i;
     if (j < BM / 8) chunk_source<AT, BM>(j * 64 + lane, m0, m_end, lda_b, k0, krange, g.a_gather, g.gather_div, &base[i], &ntile[i]);
+    else if (!AT && !BT && TN == 2 && g.act_half)
+      chunk_source_gate_up((j - BM / 8) * 64 + lane, bx * (BN / 2), g.act_half, ldb_b, k0, krange, &base[i], &ntile[i]);
     else chunk_source<BT, BN>((j - BM / 8) * 64 + lane, n0, g.N, ldb_b, k0, krange, nullptr, 1, &base[i], &ntile[i]);
   }
   const unsigned lds0 = (unsigned)(unsigned long long)(__attribute__((address_space(3))) unsigned char*)smem;
@@ -208,6 +225,32 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const bf16* A, cons
           const int m = m0 + wm + i * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
           if (m < m_end) ws[(i64)m * g.N + n] = acc[i][j][e];
         }
+    }
+    return;
+  }
+  if (g.act_half) {
+    // gate/up GEMM with the SwiGLU epilogue: this wave's first 32-column block is gate columns, its second the up
+    // columns of the same indices.  Both go to C (the backward pass needs them), and silu(gate) * up, from the
+    // rounded values, to act_out.
+    if constexpr (!AT && !BT && TN == 2) {
+      TC* H = (TC*)g.act_out;
+      const int half = g.act_half;
+      const int col = bx * (BN / 2) + (wn >> 6) * 32 + (lane & 31);
+      if (col < half) {
+#pragma unroll
+        for (int i = 0; i < TE; i++)
+#pragma unroll
+          for (int e = 0; e < 16; e++) {
+            const int m = m0 + wm + i * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+            if (m < m_end) {
+              const TC gb = (TC)acc[i][0][e], ub = (TC)acc[i][1][e];
+              const float gv = (float)gb;
+              C[(i64)m * g.ldc + col] = gb;
+              C[(i64)m * g.ldc + half + col] = ub;
+              H[(i64)m * g.ldact + col] = (TC)(gv * sigmoid_f(gv) * (float)ub);
+            }
+          }
+      }
     }
     return;
   }
@@ -347,7 +390,7 @@ static int xcd_enabled() {
 template <int BM, int BN, int WGM, bool AT, bool BT, class TC, int NW, int NS>
 static void go(const GemmArgs& g0, hipStream_t s) {
   GemmArgs g = g0;
-  g.tiles_n = cdiv(g.N, BN);
+  g.tiles_n = g.act_half ? cdiv(g.act_half, BN / 2) : cdiv(g.N, BN);
   g.tiles_m = g.group_mode == 1 ? g.max_tiles : cdiv(g.M, BM);
   const int zdim = g.group_mode == 2 ? g.n_groups : (g.group_mode == 0 && g.split_k > 1 ? g.split_k : 1);
   if (g.tiles_n <= 0 || g.tiles_m <= 0 || zdim <= 0) return;
@@ -400,6 +443,12 @@ static int tile_override() {
 template <bool AT, bool BT, class TC>
 static void pick_tile(const GemmArgs& g, hipStream_t s) {
   const int forced = g.force_tile ? g.force_tile : tile_override();
+  if (g.act_half && g.group_mode == 0) {
+    // SwiGLU epilogue: only tiles whose waves are 64 columns wide (a gate and an up block)
+    if ((i64)cdiv(g.M, 256) * cdiv(g.N, 128) >= 512) go_256x128<AT, BT, TC>(g, s);
+    else go_128x128<AT, BT, TC>(g, s);
+    return;
+  }
   if (g.group_mode != 1 && forced) {
     switch (forced) {
       case 1: go_128x128_w4<AT, BT, TC>(g, s); return;
@@ -416,7 +465,7 @@ static void pick_tile(const GemmArgs& g, hipStream_t s) {
     // expert tiles.  Skipping the MFMAs of the 32-row blocks past an expert's end (waves spanning all rows, a loop
     // specialised per block count) measured no gain, and neither did a fifth LDS stage.
     if constexpr (!AT) {
-      if (g.tile_bm == 64) go_64x128<AT, BT, TC>(g, s);
+      if (g.tile_bm == 64 && !g.act_half) go_64x128<AT, BT, TC>(g, s);
       else if (g.tile_bm == 256) go_256x128<AT, BT, TC>(g, s);
       else if (g.tile_bn == 256) go_128x256<AT, BT, TC>(g, s);
       else go_128x128<AT, BT, TC>(g, s);
@@ -468,6 +517,10 @@ int launch_gemm_mfma(const GemmArgs& g, GemmTypes t, hipStream_t s) {
   if (g.group_mode != 1 && g.M <= 0) return 1;
   if (g.split_k > 1 && (g.group_mode != 0 || !g.splitk_ws)) return 1;
   if (g.col_scale && g.split_k <= 1) return 1;           // column scale lives in the split-k reduction only
+  if (g.act_half) {
+    if (g.a_trans || g.b_trans || g.group_mode == 2 || g.split_k > 1 || g.bias || g.resid || g.tap || !g.act_out) return 1;
+    if (g.N != 2 * g.act_half || (g.group_mode == 1 && g.tile_bm == 64)) return 1;
+  }
   // every operand must span less than 2 GiB from its base (32-bit buffer offsets)
   {
     const i64 lim = (i64)1 << 30;                        // elements

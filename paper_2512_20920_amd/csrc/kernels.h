@@ -33,6 +33,10 @@ struct GemmArgs {
   int force_tile = 0;                    // MFMA kernel, dense problems: tile shape forced for this launch (unit tests), 0 = by size
   int tile_bn = 0;                       // MFMA expert tiles of height 128: 256 = 128x256 tiles, else 128x128
   i64 b_group_stride = 0, c_group_stride = 0;
+  // MFMA kernel, [out,in] weights whose rows are [gate rows | up rows] (N = 2 * act_half): a tile holds matching gate
+  // and up columns and also writes act_out[m*ldact + c] = silu(gate) * up, computed from the rounded outputs exactly
+  // as the separate SwiGLU kernel does from C.  Ignored by the generic kernel (the caller runs that kernel instead).
+  void* act_out = nullptr; i64 ldact = 0; int act_half = 0;
   // generic kernel only: the k range is cut into split_k slices whose fp32 partial tiles go to
   // splitk_ws[slice][M][N]; a second kernel adds the slices in index order and applies the epilogue
   int split_k = 1; float* splitk_ws = nullptr;

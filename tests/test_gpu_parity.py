@@ -318,6 +318,28 @@ def test_symmetric_comparison_block(name, mode):
             assert torch.equal(G3[k], G4[k]), k
 
 
+@pytest.mark.gpu
+@pytest.mark.parametrize("name", ["mid_bf16", "mid_fewbig_bf16"])
+def test_fused_swiglu_epilogue_matches_the_separate_kernel(name, monkeypatch):
+    """The gate/up GEMMs write silu(gate) * up from their epilogue (a tile holds matching gate and up columns).  Same
+    bits as the GEMM followed by the SwiGLU kernel, through forward, inverse and every gradient; the expert widths of
+    these workloads (192 and 320; 712) leave tiles whose gate columns end inside the tile."""
+    wl = synth.WORKLOADS[name]
+    outs = []
+    for separate in (False, True):
+        if separate:
+            monkeypatch.setenv("REVFFN_NO_FUSED_SWIGLU", "1")
+        else:
+            monkeypatch.delenv("REVFFN_NO_FUSED_SWIGLU", raising=False)
+        case = Case(wl)
+        y1d, y2d = case.forward()
+        x1d, x2d = case.inverse(y1d, y2d, n_iters=1)
+        dx1, dx2, G = case.backward(x1d, x2d, y1d)
+        outs.append([y1d, y2d, x1d, x2d, dx1, dx2] + [G[k] for k in sorted(G) if G[k] is not None])
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
+
+
 @pytest.mark.parametrize("mode", [0, 1])
 def test_fp32_weight_gradients(mode):
     """config.fp32_grads: every weight gradient lands in a float32 buffer.  Same parity bar against the oracle, and
