@@ -113,6 +113,34 @@ def test_block_parity(name, mode):
     print(name, "mode", mode, "ties", rep, {k: f"{v:.2e}" for k, v in errs.items()})
 
 
+def _drawn_geometries(n, seed=11):
+    """Seeded draw of block geometries that the fixed workloads do not cover: odd head counts, head widths with and
+    without the flash-attention kernels, expert widths that end inside a tile, with and without a shared expert."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for i in range(n):
+        dh = 64 if i % 3 == 2 else 128          # 64: no flash-attention kernel, generic attention
+        H = int(rng.integers(2, 5))
+        E = int(rng.integers(3, 21))
+        k = int(rng.integers(1, min(4, E) + 1))
+        I = 8 * int(rng.integers(5, 66))
+        Is = 0 if rng.random() < 0.3 else 8 * int(rng.integers(5, 90))
+        B, S = int(rng.integers(1, 4)), int(rng.integers(17, 261))
+        out.append(synth.Workload(f"drawn{i}", H * dh, H, dh, E, k, I, Is, B, S, "bf16", gain_jitter=0.02, seed=100 + i))
+    return out
+
+
+@pytest.mark.parametrize("wl", _drawn_geometries(6), ids=lambda w: f"{w.name}_d{w.d_model}_dh{w.head_dim}_E{w.n_experts}k{w.top_k}_I{w.d_expert}_Is{w.d_shared}_B{w.B}S{w.S}")
+def test_block_parity_drawn_geometries(wl):
+    """Forward, inverse and backward against the oracle on seeded random geometries (bf16, matrix-core kernels)."""
+    tol = TOL[wl.dtype]
+    case = Case(wl)
+    y1d, y2d, rep = _forward_checks(case, tol, min_same=0.9)
+    x1d, x2d = _inverse_checks(case, y1d, y2d, tol, 1)
+    errs = _backward_checks(case, x1d, x2d, y1d, tol)
+    print(wl.name, "ties", rep, {k: f"{v:.2e}" for k, v in errs.items()})
+
+
 @pytest.mark.parametrize("flags", [dict(causal=False, use_rope=False, norm_topk_prob=True),
                                    dict(causal=True, use_rope=True, norm_topk_prob=True)])
 @pytest.mark.parametrize("name", ["mid_f32", "mid_bf16"])
