@@ -51,14 +51,26 @@ __device__ __forceinline__ bf16x8 acc_to_frag(const f32x16& a, int c) {
   return r;
 }
 
-// global [rows, DH] slice (row stride ld) -> registers: 64 rows x 16 chunks of 16 bytes, 4 per thread;
-// rows at or past row_lim are zero
-__device__ __forceinline__ void load_rows64(const bf16* base, i64 ld, int row0, int row_lim, uint4 (&r)[4]) {
+// global [rows, DH] slice (row stride ld) -> registers: 64 rows x 16 chunks of 16 bytes, 4 per thread; rows at or
+// past the sequence end are zero.  The loads are range-checked buffer loads: the descriptor covers the slice of one
+// (batch, head) up to the last byte of row S - 1, so a row past the end is out of range and reads as zeros with no
+// branch and no traffic, the address is one 32-bit offset per lane, and the loads of a tile issue back to back.
+// (Predicated pointer loads put a branch and a full wait after every load and spilled their 64-bit addresses.)
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+struct RowSlice { __amdgpu_buffer_rsrc_t rs; unsigned ldb; };    // ldb = row stride in bytes
+__device__ __forceinline__ RowSlice row_slice(const bf16* base, i64 ld, int S) {
+  RowSlice r;
+  r.rs = __builtin_amdgcn_make_buffer_rsrc((void*)base, (short)0, (int)(((i64)S - 1) * ld * 2 + DH * 2), 0x00020000);
+  r.ldb = (unsigned)(ld * 2);
+  return r;
+}
+__device__ __forceinline__ void load_rows64(const RowSlice& sl, int row0, uint4 (&r)[4]) {
 #pragma unroll
   for (int i = 0; i < 4; i++) {
-    int c = threadIdx.x + 256 * i;
-    int row = row0 + (c >> 4);
-    r[i] = (row < row_lim) ? *(const uint4*)(base + (i64)row * ld + (c & 15) * 8) : make_uint4(0, 0, 0, 0);
+    const int c = threadIdx.x + 256 * i;
+    const unsigned voff = (unsigned)(row0 + (c >> 4)) * sl.ldb + (unsigned)(c & 15) * 16u;
+    const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(sl.rs, (int)voff, 0, 0);
+    r[i] = make_uint4(v[0], v[1], v[2], v[3]);
   }
 }
 __device__ __forceinline__ void store_rows64(bf16* lds, int stride, const uint4 (&r)[4]) {
@@ -108,16 +120,17 @@ __global__ void __launch_bounds__(256, 2) flash_fwd_k(const bf16* __restrict__ q
   float m = -INFINITY, l = 0.f;
 
   uint4 rk[4], rv[4];
-  load_rows64(kb, ld, 0, S, rk);
-  load_rows64(vb, ld, 0, S, rv);
+  const RowSlice slK = row_slice(kb, ld, S), slV = row_slice(vb, ld, S);
+  load_rows64(slK, 0, rk);
+  load_rows64(slV, 0, rv);
   store_rows64(sK, KST, rk);
   store_rows64(sV, VST, rv);
   __syncthreads();
   for (int t = 0; t < nt; t++) {
     const int cur = t & 1, kv0 = t * BKV;
     if (t + 1 < nt) {
-      load_rows64(kb, ld, kv0 + BKV, S, rk);
-      load_rows64(vb, ld, kv0 + BKV, S, rv);
+      load_rows64(slK, kv0 + BKV, rk);
+      load_rows64(slV, kv0 + BKV, rv);
     }
     const bf16* cK = sK + cur * BKV * KST;
     const bf16* cV = sV + cur * BKV * VST;
@@ -220,6 +233,7 @@ __global__ void __launch_bounds__(256, 2) flash_fwd_k(const bf16* __restrict__ q
 int launch_attn_fwd_flash(const void* q, const void* k, const void* v, void* o, float* lse, int B, int S, int H,
                           int dh, int causal, hipStream_t s) {
   if (dh != DH || B <= 0 || S <= 0) return 1;
+  if ((i64)S * H * DH * 2 >= ((i64)1 << 31)) return 1;      // one sequence of one tensor is addressed with 32-bit offsets
   if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)o) & 15) return 1;
   size_t smem = (size_t)2 * BKV * (KST + VST) * sizeof(bf16);
   static bool attr_set = false;
@@ -277,16 +291,17 @@ __global__ void __launch_bounds__(256, 2) flash_bwd_dq_k(const bf16* __restrict_
     for (int e = 0; e < 16; e++) acc[i][e] = 0.f;
 
   uint4 rk[4], rv[4];
-  load_rows64(k + boff, ld, 0, S, rk);
-  load_rows64(v + boff, ld, 0, S, rv);
+  const RowSlice slK = row_slice(k + boff, ld, S), slV = row_slice(v + boff, ld, S);
+  load_rows64(slK, 0, rk);
+  load_rows64(slV, 0, rv);
   store_rows64(sK, BST, rk);
   store_rows64(sV, BST, rv);
   __syncthreads();
   for (int t = 0; t < nt; t++) {
     const int cur = t & 1, kv0 = t * BKV;
     if (t + 1 < nt) {
-      load_rows64(k + boff, ld, kv0 + BKV, S, rk);
-      load_rows64(v + boff, ld, kv0 + BKV, S, rv);
+      load_rows64(slK, kv0 + BKV, rk);
+      load_rows64(slV, kv0 + BKV, rv);
     }
     const bf16* cK = sK + cur * BKV * BST;
     const bf16* cV = sV + cur * BKV * BST;
@@ -393,6 +408,7 @@ __global__ void __launch_bounds__(256) flash_bwd_dkv_k(const bf16* __restrict__ 
     for (int e = 0; e < 16; e++) { dkacc[i][e] = 0.f; dvacc[i][e] = 0.f; }
 
   uint4 rq[4], ro[4];
+  const RowSlice slQ = row_slice(q + boff, ld, S), slO = row_slice(d_o + boff, ld, S);
   float rl = 0.f, rd = 0.f;
   auto load_stats = [&](int q0) {
     if (threadIdx.x < BKV) {
@@ -405,8 +421,8 @@ __global__ void __launch_bounds__(256) flash_bwd_dkv_k(const bf16* __restrict__ 
     if (threadIdx.x < BKV) { sL[stage * BKV + threadIdx.x] = rl; sD[stage * BKV + threadIdx.x] = rd; }
   };
   if (t_lo < nt) {
-    load_rows64(q + boff, ld, t_lo * BKV, S, rq);
-    load_rows64(d_o + boff, ld, t_lo * BKV, S, ro);
+    load_rows64(slQ, t_lo * BKV, rq);
+    load_rows64(slO, t_lo * BKV, ro);
     load_stats(t_lo * BKV);
     store_rows64(sQ, BST, rq);
     store_rows64(sO, BST, ro);
@@ -416,8 +432,8 @@ __global__ void __launch_bounds__(256) flash_bwd_dkv_k(const bf16* __restrict__ 
   for (int t = t_lo; t < nt; t++) {
     const int cur = (t - t_lo) & 1, q0 = t * BKV;
     if (t + 1 < nt) {
-      load_rows64(q + boff, ld, q0 + BKV, S, rq);
-      load_rows64(d_o + boff, ld, q0 + BKV, S, ro);
+      load_rows64(slQ, q0 + BKV, rq);
+      load_rows64(slO, q0 + BKV, ro);
       load_stats(q0 + BKV);
     }
     const bf16* cQ = sQ + cur * BKV * BST;
@@ -496,6 +512,7 @@ int launch_attn_bwd_flash(const void* q, const void* k, const void* v, const voi
                           const float* lse, float* dvec, void* dq, void* dk, void* dv, int B, int S, int H, int dh,
                           int causal, hipStream_t s) {
   if (dh != DH || B <= 0 || S <= 0) return 1;
+  if ((i64)S * H * DH * 2 >= ((i64)1 << 31)) return 1;      // one sequence of one tensor is addressed with 32-bit offsets
   if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)o | (uintptr_t)d_o | (uintptr_t)dq | (uintptr_t)dk |
        (uintptr_t)dv) & 15)
     return 1;
