@@ -662,7 +662,11 @@ int backward_impl(revffn_ctx* c, const revffn_weights* w, const void* x1, const 
     e.group_mode = 1; e.n_groups = E; e.offsets = c->offsets; e.b_group_stride = (i64)2 * I * d;
     TRY(run_gemm(c, e, s));
   }
-  launch_router_bwd(c->probs, c->idx, c->wts, c->dw, c->dzext, T, E, k, E1, f.norm_topk_prob, s);
+  // (the bf16 copy of the logit gradients for the matrix-core router GEMM below is written by the same kernel)
+  const bool dz_bf16 = dt == 1 && c->mode == 0;
+  const int E1p = (E1 + 7) / 8 * 8;
+  launch_router_bwd(c->probs, c->idx, c->wts, c->dw, c->dzext, T, E, k, E1, f.norm_topk_prob, s,
+                    dz_bf16 ? c->dzb : nullptr, E1p);
   // every column sum (bias and gain gradients) goes to helper stream 2: they share one scratch buffer, and the
   // weight-gradient GEMMs keep helper stream 1 to themselves.  The router weight gradient goes there too.
   hipStream_t sc = side(c, s, 2);
@@ -679,10 +683,8 @@ int backward_impl(revffn_ctx* c, const revffn_weights* w, const void* x1, const 
   if (g && g->b_router) launch_colsum(0, c->dzext, E1, 0, nullptr, 0, nullptr, 0, g->b_router, c->partial, T, E, sc);
   if (Is) after(c, s0, s);
   const void* dum_r = nullptr;
-  if (dt == 1 && c->mode == 0) {
+  if (dz_bf16) {
     // router term of dUm on the matrix cores: dUm_r = dz . [W_r ; w_gate ; 0], contraction over E1p
-    const int E1p = (E1 + 7) / 8 * 8;
-    launch_dz_to_bf16(c->dzext, c->dzb, T, E1, E1p, s);
     GemmArgs a = nn(c->dzb, E1p, c->wr_ext, d, c->dUm_r, d, T, d, E1p);
     GemmTypes tt{1, 1, 1, 1};
     if (launch_gemm_mfma(a, tt, s) == 0) dum_r = c->dUm_r;
@@ -713,8 +715,7 @@ int backward_impl(revffn_ctx* c, const revffn_weights* w, const void* x1, const 
     ps.done(done ? KID_ATTN_BWD_FLASH : KID_ATTN_BWD_GENERIC);
   }
   if (f.use_rope) {
-    launch_rope(dt, c->dQ, c->rope_cs, T, S, f.n_heads, f.head_dim, -1.f, s);
-    launch_rope(dt, c->dK, c->rope_cs, T, S, f.n_heads, f.head_dim, -1.f, s);
+    launch_rope(dt, c->dQ, c->rope_cs, T, S, f.n_heads, f.head_dim, -1.f, s, c->dK);   // both in one launch
   }
   const void* U1 = c->U12;
   const void* U2 = at(c->U12, (size_t)T * d, es);

@@ -302,10 +302,11 @@ void launch_colsum(int ta, const void* a, i64 lda, int tb, const void* b, i64 ld
 // sign = -1 applies the inverse rotation (the backward of the forward rotation).
 // ---------------------------------------------------------------------------------
 template <class T>
-__global__ void __launch_bounds__(256) rope_k(T* __restrict__ buf, const float2* __restrict__ cs, i64 total, int S,
-                                              int H, int half, float sign) {
+__global__ void __launch_bounds__(256) rope_k(T* __restrict__ buf, T* __restrict__ buf2, const float2* __restrict__ cs,
+                                              i64 total, int S, int H, int half, float sign) {
   i64 e = (i64)blockIdx.x * 256 + threadIdx.x;
   if (e >= total) return;
+  if (blockIdx.y) buf = buf2;                // second tensor of the launch
   int i = (int)(e % half);
   i64 th = e / half;          // token*H + head
   i64 t = th / H;
@@ -319,10 +320,12 @@ __global__ void __launch_bounds__(256) rope_k(T* __restrict__ buf, const float2*
 }
 
 // bf16, half % 8 == 0: one lane rotates 8 consecutive pairs of one (token, head) with 16-byte accesses
-__global__ void __launch_bounds__(256) rope_v8_k(bf16* __restrict__ buf, const float2* __restrict__ cs, int total8,
-                                                 int S, int H, int half8, float sign) {
+__global__ void __launch_bounds__(256) rope_v8_k(bf16* __restrict__ buf, bf16* __restrict__ buf2,
+                                                 const float2* __restrict__ cs, int total8, int S, int H, int half8,
+                                                 float sign) {
   const int e = blockIdx.x * 256 + threadIdx.x;
   if (e >= total8) return;
+  if (blockIdx.y) buf = buf2;                // second tensor of the launch
   const int i = (e % half8) * 8;
   const int th = e / half8;          // token*H + head
   const int spos = (th / H) % S;
@@ -343,15 +346,16 @@ __global__ void __launch_bounds__(256) rope_v8_k(bf16* __restrict__ buf, const f
 }
 
 void launch_rope(int dt, void* buf, const float* cs_table, int Tn, int S, int H, int dh, float sign,
-                 hipStream_t s) {
+                 hipStream_t s, void* buf2) {
   i64 total = (i64)Tn * H * (dh / 2);
   if (total <= 0) return;
-  if (dt == 1 && (dh & 15) == 0 && ((uintptr_t)buf & 15) == 0 && total / 8 < (i64)1 << 31) {
-    hipLaunchKernelGGL(rope_v8_k, dim3(cdiv(total / 8, 256)), dim3(256), 0, s, (bf16*)buf, (const float2*)cs_table,
-                       (int)(total / 8), S, H, dh / 16, sign);
+  const unsigned ny = buf2 ? 2 : 1;
+  if (dt == 1 && (dh & 15) == 0 && (((uintptr_t)buf | (uintptr_t)buf2) & 15) == 0 && total / 8 < (i64)1 << 31) {
+    hipLaunchKernelGGL(rope_v8_k, dim3(cdiv(total / 8, 256), ny), dim3(256), 0, s, (bf16*)buf, (bf16*)buf2,
+                       (const float2*)cs_table, (int)(total / 8), S, H, dh / 16, sign);
     return;
   }
-  DISPATCH_DT(dt, hipLaunchKernelGGL(rope_k<T>, dim3(cdiv(total, 256)), dim3(256), 0, s, (T*)buf,
+  DISPATCH_DT(dt, hipLaunchKernelGGL(rope_k<T>, dim3(cdiv(total, 256), ny), dim3(256), 0, s, (T*)buf, (T*)buf2,
                                      (const float2*)cs_table, total, S, H, dh / 2, sign));
 }
 

@@ -130,8 +130,9 @@ void launch_rmsnorm_bwd(int dt, int tx, const void* dy, i64 ldd, const void* x, 
 size_t colsum_partial_floats(int rows, int cols);
 void launch_colsum(int ta, const void* a, i64 lda, int tb, const void* b, i64 ldb, const float* sc,
                    int tout, void* out, float* partial, int rows, int cols, hipStream_t s);
+// rotates buf (and, in the same launch, buf2 of the same shape when it is not null) in place
 void launch_rope(int dt, void* buf, const float* cs_table, int T, int S, int H, int dh, float sign,
-                 hipStream_t s);
+                 hipStream_t s, void* buf2 = nullptr);
 void launch_swiglu_fwd(int dt, const void* gu, void* hh, i64 rows, int I, hipStream_t s);
 void launch_swiglu_bwd(int dt, const void* dhh, const void* gu, void* dgu, i64 rows, int I, hipStream_t s);
 void launch_gather_rows(int dt, const void* src, const int* row_map, int div, void* dst, int rows, int cols,
@@ -160,12 +161,12 @@ void launch_combine(int dt, const void* yp, const int* inv_map, const float* wts
 void launch_moe_bwd_rows(int dt, const void* drs, const void* yp, const void* ys, const int* inv_map,
                          const float* wts, const float* gamma, void* dyp, void* dys, float* dw, float* dzext,
                          int T, int d, int k, int E1, int has_gate, hipStream_t s);
+// dzb != null: also writes all E1 columns of dzext as bf16 rows of width E1p (zero padded) for the matrix-core GEMMs
 void launch_router_bwd(const float* probs, const int* idx, const float* wts, const float* dw, float* dzext,
-                       int T, int E, int k, int E1, int norm_topk, hipStream_t s);
+                       int T, int E, int k, int E1, int norm_topk, hipStream_t s, void* dzb = nullptr, int E1p = 0);
 void launch_dum_finalize(int dt, const void* dxg, const int* inv_map, const void* dum_sh, const void* dum_r,
                          const float* dzext, const void* w_router, const void* ws_gate, void* dum, int T, int d,
                          int k, int E, int E1, hipStream_t s);
-void launch_dz_to_bf16(const float* dzext, void* dzb, int T, int E1, int E1p, hipStream_t s);
 
 // ---- attention -------------------------------------------------------------------
 // Q,K,V,O,dO,...: [T, H*dh] token-major, head hh occupies columns hh*dh..; lse/dvec: [B,H,S] float

@@ -373,7 +373,7 @@ void launch_moe_bwd_rows(int dt, const void* drs, const void* yp, const void* ys
 __global__ void __launch_bounds__(256) router_bwd_k(const float* __restrict__ probs, const int* __restrict__ idx,
                                                     const float* __restrict__ wts, const float* __restrict__ dw,
                                                     float* __restrict__ dzext, int Tn, int E, int k, int E1,
-                                                    int norm_topk) {
+                                                    int norm_topk, bf16* __restrict__ dzb, int E1p) {
   const int t = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
   if (t >= Tn) return;                     // whole wave
   const float* p = probs + (i64)t * E;
@@ -390,14 +390,19 @@ __global__ void __launch_bounds__(256) router_bwd_k(const float* __restrict__ pr
   for (int j = lane; j < E; j += 64) {
     float dp = 0.f;
     for (int s = 0; s < k; s++) { const int sel = __shfl(my_sel, s, WAVE); const float v = __shfl(my_dp, s, WAVE); if (sel == j) dp = v; }
-    dzext[(i64)t * E1 + j] = p[j] * (dp - inner);
+    const float dz = p[j] * (dp - inner);
+    dzext[(i64)t * E1 + j] = dz;
+    if (dzb) dzb[(i64)t * E1p + j] = (bf16)dz;
   }
+  // the remaining columns of the bf16 copy: the shared-gate column (written to dzext by an earlier kernel), zeros
+  if (dzb)
+    for (int j = E + lane; j < E1p; j += 64) dzb[(i64)t * E1p + j] = j < E1 ? (bf16)dzext[(i64)t * E1 + j] : (bf16)0.f;
 }
 void launch_router_bwd(const float* probs, const int* idx, const float* wts, const float* dw, float* dzext, int Tn,
-                       int E, int k, int E1, int norm_topk, hipStream_t s) {
+                       int E, int k, int E1, int norm_topk, hipStream_t s, void* dzb, int E1p) {
   if (Tn <= 0) return;
   hipLaunchKernelGGL(router_bwd_k, dim3(cdiv(Tn, 4)), dim3(256), 0, s, probs, idx, wts, dw, dzext, Tn, E, k, E1,
-                     norm_topk);
+                     norm_topk, (bf16*)dzb, E1p);
 }
 
 // ---------------------------------------------------------------------------------
@@ -471,16 +476,3 @@ void launch_dum_finalize(int dt, const void* dxg, const int* inv_map, const void
                                      (const T*)ws_gate, (T*)dum, d, k, E, E1));
 }
 
-// bf16 copy of the logit gradients, zero-padded to E1p columns: the A operand of the router term GEMM
-__global__ void __launch_bounds__(256) dz_to_bf16_k(const float* __restrict__ dzext, bf16* __restrict__ dzb, int Tn,
-                                                    int E1, int E1p) {
-  i64 i = (i64)blockIdx.x * 256 + threadIdx.x;
-  if (i >= (i64)Tn * E1p) return;
-  int e = (int)(i % E1p);
-  i64 t = i / E1p;
-  dzb[i] = (e < E1) ? (bf16)dzext[t * E1 + e] : (bf16)0.f;
-}
-void launch_dz_to_bf16(const float* dzext, void* dzb, int Tn, int E1, int E1p, hipStream_t s) {
-  if (Tn <= 0) return;
-  hipLaunchKernelGGL(dz_to_bf16_k, dim3(cdiv((i64)Tn * E1p, 256)), dim3(256), 0, s, dzext, (bf16*)dzb, Tn, E1, E1p);
-}
