@@ -474,21 +474,22 @@ static void pick_tile(const GemmArgs& g, hipStream_t s) {
   }
   if (g.group_mode == 2) {
     // per-expert weight gradients: the k range is one expert's rows, a few k-tiles only, so a workgroup is mostly
-    // load latency and output stores.  Alone, 128x128 tiles with 2 stages (two workgroups per CU) and 256x128 tiles
-    // (one per CU) take the same time; next to the data-gradient chain on the main stream the 256x128 tile is 4 %
-    // of a step faster (one resident workgroup per CU leaves the small critical-path kernels room to start).  A
-    // persistent form (a workgroup walks over tiles and issues the next tile's first loads before it stores the
-    // finished one) is 5 % faster alone and 3 % of a step slower next to the main stream, so it is not used.
-    // With 8 waves and 2 stages (two workgroups, 16 waves per CU) a 128x128 tile is 7 % faster alone and 1-3 % of a
-    // step slower in the step, for the same reason.
-    static int v = -1;                 // REVFFN_WGRAD_TILE (tuning aid): 0 = 256x128, 1 = 128x128 4 waves 2 stages, 2 = 128x64 2 stages,
-                                       // 3 / 4 = 128x128 8 waves with 3 / 2 stages
+    // fixed cost (start-up, first load latency) and output stores, none of which overlap on a CU that holds one
+    // workgroup.  The largest tile, 256x256 (2 stages), spreads the fixed cost over the most output: 12 % faster than
+    // 256x128 on these kernels and 1-1.6 % of a step, even where the last tile column is half empty (N = 1408).
+    // Smaller tiles with two workgroups per CU (128x128 with 2 stages, 4 or 8 waves) are up to 7 % faster than
+    // 256x128 alone but slower inside the step, next to the data-gradient chain on the main stream; a persistent
+    // form of 256x128 (a workgroup walks over tiles and issues the next tile's first loads before it stores the
+    // finished one) was 5 % faster alone and 3 % of a step slower.
+    static int v = -1;                 // REVFFN_WGRAD_TILE (tuning aid): 0 = 256x256, 1 = 128x128 4 waves 2 stages, 2 = 128x64 2 stages,
+                                       // 3 / 4 = 128x128 8 waves with 3 / 2 stages, 5 = 256x128
     if (v < 0) { const char* e = getenv("REVFFN_WGRAD_TILE"); v = e ? atoi(e) : 0; }
     if (v == 1) go<128, 128, 2, AT, BT, TC, 4, 2>(g, s);
     else if (v == 2) go<128, 64, 2, AT, BT, TC, 4, 2>(g, s);
     else if (v == 3) go<128, 128, 4, AT, BT, TC, 8, 3>(g, s);
     else if (v == 4) go<128, 128, 4, AT, BT, TC, 8, 2>(g, s);
-    else go_256x128<AT, BT, TC>(g, s);
+    else if (v == 5) go_256x128<AT, BT, TC>(g, s);
+    else go_256x256<AT, BT, TC>(g, s);
     return;
   }
   // the largest tile that still gives every CU work: 256x128 from two rounds of workgroups on, 128x128 down to
