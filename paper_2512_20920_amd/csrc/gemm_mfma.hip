@@ -120,6 +120,16 @@ __device__ __forceinline__ bf16x8 load_frag(const unsigned char* tile, unsigned 
   }
 }
 
+// Two neighbouring lanes (columns n, n+1) hold values x0, x1 of rows r, r+1.  After the swap the even lane holds row r
+// and the odd lane row r+1, each as (left column, right column): one 4-byte store of two 2-byte results per lane.
+// Both lanes of a pair must be active.
+__device__ __forceinline__ void pair_rows(bool odd, float x0, float x1, float* left, float* right) {
+  const float send = odd ? x0 : x1;
+  const float recv = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, send), 0xB1, 0xf, 0xf, false));
+  *left = odd ? recv : x0;
+  *right = odd ? x1 : recv;
+}
+
 // One output tile; TE = 32-row blocks per wave.
 template <int BM, int BN, int WGM, bool AT, bool BT, class TC, int NW, int NS, int TE>
 __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const bf16* A, const bf16* Bm, TC* C, int bx, int bz,
@@ -236,6 +246,41 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const bf16* A, cons
       TC* H = (TC*)g.act_out;
       const int half = g.act_half;
       const int col = bx * (BN / 2) + (wn >> 6) * 32 + (lane & 31);
+      if constexpr (sizeof(TC) == 2) {
+        // pairs of lanes store two columns of one row each (see the plain store below); rows past the end are masked
+        // per lane after the swap, columns per pair (the width is even)
+        if (!(g.ldc & 1) && !(g.ldact & 1) && !(half & 1) && !((uintptr_t)C & 3) && !((uintptr_t)H & 3) && !g.no_packed_stores) {
+          const bool odd = lane & 1;
+          const int colp = col - (odd ? 1 : 0);
+          typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_v;
+          if (colp < half) {
+#pragma unroll
+            for (int i = 0; i < TE; i++)
+#pragma unroll
+              for (int e = 0; e < 16; e += 2) {
+                const int m = m0 + wm + i * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3) + (odd ? 1 : 0);
+                float gq[2], uq[2], hq[2];
+#pragma unroll
+                for (int p = 0; p < 2; p++) {
+                  const TC gb = (TC)acc[i][0][e + p], ub = (TC)acc[i][1][e + p];
+                  gq[p] = (float)gb; uq[p] = (float)ub;
+                  hq[p] = (float)(TC)(gq[p] * sigmoid_f(gq[p]) * uq[p]);
+                }
+                float l, r;
+                bf16x2_v wg, wu, wh;
+                pair_rows(odd, gq[0], gq[1], &l, &r); wg[0] = (__bf16)l; wg[1] = (__bf16)r;
+                pair_rows(odd, uq[0], uq[1], &l, &r); wu[0] = (__bf16)l; wu[1] = (__bf16)r;
+                pair_rows(odd, hq[0], hq[1], &l, &r); wh[0] = (__bf16)l; wh[1] = (__bf16)r;
+                if (m < m_end) {
+                  *(bf16x2_v*)(C + (i64)m * g.ldc + colp) = wg;
+                  *(bf16x2_v*)(C + (i64)m * g.ldc + half + colp) = wu;
+                  *(bf16x2_v*)(H + (i64)m * g.ldact + colp) = wh;
+                }
+              }
+          }
+          return;
+        }
+      }
       if (col < half) {
 #pragma unroll
         for (int i = 0; i < TE; i++)
@@ -262,6 +307,36 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const bf16* A, cons
     // (Staging the tile through LDS to store whole 128-byte lines, 16 bytes per lane, measured no faster: these
     // stores are not what bounds the weight-gradient kernels.)
     const bool full = (m0 + BM <= m_end) && (n0 + BN <= g.N);
+    if constexpr (sizeof(TC) == 2) {
+      // Whole tiles of 2-byte results: neighbouring lanes hold neighbouring columns of the same rows, so a pair of
+      // lanes swaps one value per two rows (the even lane gives its value of the odd row and gets the neighbour's
+      // value of the even row) and each lane stores 4 bytes, two columns of one row: half as many store
+      // instructions, and the stores of a tile are bound by their number (per-expert weight gradients 10 % faster,
+      // 1-2 % of a step).  Going on to a 4x4 transpose inside a quad and 8-byte stores is slower than no packing at
+      // all: one instruction then touches eight rows.
+      if (full && !(g.ldc & 1) && !((uintptr_t)C & 3) && !g.no_packed_stores) {
+        const bool odd = lane & 1;
+        typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_v;
+#pragma unroll
+        for (int i = 0; i < TE; i++) {
+          // even lane: row of element e, its own column; odd lane: the row below, the column to its left
+          TC* cp = C + (i64)(m0 + wm + i * 32 + (lane >> 5) * 4 + (odd ? 1 : 0)) * g.ldc + n0 + wn + (lane & 31) - (odd ? 1 : 0);
+#pragma unroll
+          for (int e = 0; e < 16; e += 2) {
+            const int dm = (e >> 2) * 8 + (e & 3);
+#pragma unroll
+            for (int j = 0; j < TN; j++) {
+              float l, r;
+              pair_rows(odd, acc[i][j][e], acc[i][j][e + 1], &l, &r);
+              bf16x2_v w;
+              w[0] = (__bf16)l; w[1] = (__bf16)r;
+              *(bf16x2_v*)(cp + (i64)dm * g.ldc + j * 32) = w;
+            }
+          }
+        }
+        return;
+      }
+    }
 #pragma unroll
     for (int i = 0; i < TE; i++) {
       TC* cp = C + (i64)(m0 + wm + i * 32 + (lane >> 5) * 4) * g.ldc + n0 + wn + (lane & 31);
@@ -330,6 +405,25 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const bf16* A, cons
           rv[ii][e] = o;
         }
       // ---- phase 2: stores
+      if constexpr (sizeof(TC) == 2) {
+        // two columns of one row per lane (see the plain store above); the swap runs on every lane, the masks after it
+        if (!g.tap && !(g.ldc & 1) && !(g.N & 1) && !((uintptr_t)C & 3) && !g.no_packed_stores) {
+          const bool odd = lane & 1;
+          typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_v;
+#pragma unroll
+          for (int ii = 0; ii < GI; ii++)
+#pragma unroll
+            for (int e = 0; e < 16; e += 2) {
+              float l, r;
+              pair_rows(odd, rv[ii][e], rv[ii][e + 1], &l, &r);
+              bf16x2_v w;
+              w[0] = (__bf16)l; w[1] = (__bf16)r;
+              const int m = row_of(i0 + ii, e) + (odd ? 1 : 0);
+              if (n_ok && (full || m < m_end)) *(bf16x2_v*)(C + (i64)m * g.ldc + n - (odd ? 1 : 0)) = w;
+            }
+          continue;
+        }
+      }
 #pragma unroll
       for (int ii = 0; ii < GI; ii++)
 #pragma unroll
@@ -390,6 +484,7 @@ static int xcd_enabled() {
 template <int BM, int BN, int WGM, bool AT, bool BT, class TC, int NW, int NS>
 static void go(const GemmArgs& g0, hipStream_t s) {
   GemmArgs g = g0;
+  { static int off = -1; if (off < 0) { const char* e = getenv("REVFFN_NO_PACKED_STORES"); off = e ? atoi(e) : 0; } g.no_packed_stores = off; }
   g.tiles_n = g.act_half ? cdiv(g.act_half, BN / 2) : cdiv(g.N, BN);
   g.tiles_m = g.group_mode == 1 ? g.max_tiles : cdiv(g.M, BM);
   const int zdim = g.group_mode == 2 ? g.n_groups : (g.group_mode == 0 && g.split_k > 1 ? g.split_k : 1);

@@ -30,6 +30,7 @@ struct GemmArgs {
   float* tap = nullptr; i64 ldtap = 0;
   int group_mode = 0; int n_groups = 1; const int* offsets = nullptr;
   const int* tile_group = nullptr; const int* tile_m0 = nullptr; int max_tiles = 0; int tile_bm = 0;
+  int no_packed_stores = 0;              // (tuning aid) 2-byte results stored one column per lane even in whole tiles
   int force_tile = 0;                    // MFMA kernel, dense problems: tile shape forced for this launch (unit tests), 0 = by size
   int tile_bn = 0;                       // MFMA expert tiles of height 128: 256 = 128x256 tiles, else 128x128
   i64 b_group_stride = 0, c_group_stride = 0;
