@@ -126,12 +126,12 @@ def rope(v, theta, sign=1.0):
 # --------------------------------------------------------------------------
 # attention half:  A = P_dn_a( Attn_pt(P_up_a Norm X1, P_up_a Norm X2, P_up_a Norm X2) )
 # --------------------------------------------------------------------------
-def attention_core(Q, K, V, causal):
+def attention_core(Q, K, V, causal, keep_probs=True):
     """softmax(Q K^T / sqrt(dh) + mask) V for Q, K, V of shape [B, S, H, dh].
-    Returns O [B, S, H, dh] and the probabilities P [B, H, S, S]."""
+    Returns O [B, S, H, dh] and the probabilities P [B, H, S, S] (None unless keep_probs)."""
     B, S, H, dh = Q.shape
     O = np.zeros_like(Q)
-    P = np.zeros((B, H, S, S))
+    P = np.zeros((B, H, S, S)) if keep_probs else None
     for b in range(B):
         for hh in range(H):
             sc = Q[b, :, hh, :] @ K[b, :, hh, :].T / np.sqrt(dh)
@@ -140,7 +140,8 @@ def attention_core(Q, K, V, causal):
             sc = sc - sc.max(axis=-1, keepdims=True)
             e = np.exp(sc)
             p = e / e.sum(axis=-1, keepdims=True)
-            P[b, hh] = p
+            if keep_probs:
+                P[b, hh] = p
             O[b, :, hh, :] = p @ V[b, :, hh, :]
     return O, P
 
@@ -154,6 +155,31 @@ def attention_core_backward(dO, Q, K, V, P):
     for b in range(B):
         for hh in range(H):
             p = P[b, hh]
+            do = dO[b, :, hh, :]
+            dV[b, :, hh, :] = p.T @ do
+            dp = do @ V[b, :, hh, :].T
+            ds = p * (dp - np.sum(dp * p, axis=-1, keepdims=True))
+            dQ[b, :, hh, :] = ds @ K[b, :, hh, :] / np.sqrt(dh)
+            dK[b, :, hh, :] = ds.T @ Q[b, :, hh, :] / np.sqrt(dh)
+    return dQ, dK, dV
+
+
+def attention_core_backward_streaming(dO, Q, K, V, causal):
+    """The same gradients as attention_core_backward without a stored probability tensor: the
+    probabilities of one (batch, head) pair are evaluated again from Q and K (the statements of
+    attention_core), used, and dropped, so the memory in flight is one S x S matrix."""
+    B, S, H, dh = Q.shape
+    dQ = np.zeros_like(Q)
+    dK = np.zeros_like(K)
+    dV = np.zeros_like(V)
+    for b in range(B):
+        for hh in range(H):
+            sc = Q[b, :, hh, :] @ K[b, :, hh, :].T / np.sqrt(dh)
+            if causal:
+                sc = np.where(np.tril(np.ones((S, S), dtype=bool)), sc, -np.inf)
+            sc = sc - sc.max(axis=-1, keepdims=True)
+            e = np.exp(sc)
+            p = e / e.sum(axis=-1, keepdims=True)
             do = dO[b, :, hh, :]
             dV[b, :, hh, :] = p.T @ do
             dp = do @ V[b, :, hh, :].T
@@ -188,12 +214,12 @@ def attn_half_forward(x1, x2, W, cfg, B, S, keep_probs=True):
     if cfg.use_rope:
         Q = rope(Q, cfg.rope_theta)
         K = rope(K, cfg.rope_theta)
-    O4, P = attention_core(Q, K, V, cfg.causal)
+    O4, P = attention_core(Q, K, V, cfg.causal, keep_probs)
     O = O4.reshape(T, d)
     AO = O @ W["wo"].T
     A = AO @ W["pdn_a"].T
     cache = dict(x1=x1, x2=x2, n1=n1, n2=n2, U1=U1, U2=U2, Q=Q, K=K, V=V,
-                 P=P if keep_probs else None, O=O, AO=AO)
+                 P=P, O=O, AO=AO)
     return A, cache
 
 
@@ -207,7 +233,10 @@ def attn_half_backward(dA, c, W, cfg, B, S):
     dAO = dA @ W["pdn_a"]
     g["wo"] = dAO.T @ c["O"]
     dO = (dAO @ W["wo"]).reshape(B, S, H, dh)
-    dQ, dK, dV = attention_core_backward(dO, c["Q"], c["K"], c["V"], c["P"])
+    if c["P"] is None:                          # forward ran with keep_probs=False (long sequences)
+        dQ, dK, dV = attention_core_backward_streaming(dO, c["Q"], c["K"], c["V"], cfg.causal)
+    else:
+        dQ, dK, dV = attention_core_backward(dO, c["Q"], c["K"], c["V"], c["P"])
     if cfg.use_rope:
         dQ = rope(dQ, cfg.rope_theta, sign=-1.0)
         dK = rope(dK, cfg.rope_theta, sign=-1.0)
@@ -237,16 +266,26 @@ def attn_half_backward(dA, c, W, cfg, B, S):
 # --------------------------------------------------------------------------
 # routing: integer, deterministic
 # --------------------------------------------------------------------------
-def route(z, cfg):
+def route(z, cfg, forced_idx=None):
     """Softmax over all experts, then the top_k largest logits per token.
     Slots are ordered by descending logit; equal logits go to the lower expert
-    index.  Routing weight = softmax probability (renormalised over the selected
-    set only if norm_topk_prob).  Returns idx [T,k] int32, w [T,k], p [T,E]."""
+    index.  A logit that is not a number ranks as minus infinity in the selection
+    (so a token with a non-finite input still selects top_k distinct, valid experts;
+    its weights are not numbers).  Routing weight = softmax probability (renormalised
+    over the selected set only if norm_topk_prob).  forced_idx [T,k]: take this
+    selection instead of ranking the logits (used to evaluate the block under a
+    selection that differs from this one's on a near-tie); the weights are still
+    this softmax's.  Returns idx [T,k] int32, w [T,k], p [T,E]."""
     zs = z - z.max(axis=-1, keepdims=True)
     e = np.exp(zs)
     p = e / e.sum(axis=-1, keepdims=True)
-    order = np.argsort(-z, axis=-1, kind="stable")
-    idx = order[:, :cfg.top_k].astype(np.int32)
+    if forced_idx is not None:
+        idx = np.asarray(forced_idx).astype(np.int32)
+        assert idx.shape == (z.shape[0], cfg.top_k)
+    else:
+        zr = np.where(np.isnan(z), -np.inf, z)
+        order = np.argsort(-zr, axis=-1, kind="stable")
+        idx = order[:, :cfg.top_k].astype(np.int32)
     w = np.take_along_axis(p, idx.astype(np.int64), axis=-1)
     if cfg.norm_topk_prob:
         w = w / w.sum(axis=-1, keepdims=True)
@@ -276,7 +315,7 @@ def permutation(idx, n_experts):
 # --------------------------------------------------------------------------
 # MoE half:  M = P_dn_m( MLP_pt(P_up_m Norm Y1) )
 # --------------------------------------------------------------------------
-def moe_half_forward(y1, W, cfg):
+def moe_half_forward(y1, W, cfg, forced_idx=None):
     W = as_f64(W)
     T = y1.shape[0]
     E, k, I, d = cfg.n_experts, cfg.top_k, cfg.d_expert, cfg.d_model
@@ -285,7 +324,7 @@ def moe_half_forward(y1, W, cfg):
     z = Um @ W["w_router"].T
     if W.get("b_router") is not None:
         z = z + W["b_router"]
-    idx, w, p = route(z, cfg)
+    idx, w, p = route(z, cfg, forced_idx)
     counts, offsets, row_map = permutation(idx, E)
     R = np.zeros((T, d))
     per_expert = []
@@ -384,17 +423,18 @@ def moe_half_backward(dM, c, W, cfg):
 # --------------------------------------------------------------------------
 # block: forward (Eq. 1-2), inverse, backward
 # --------------------------------------------------------------------------
-def forward(x1, x2, W, cfg, B, S, return_cache=False):
+def forward(x1, x2, W, cfg, B, S, return_cache=False, forced_idx=None):
     A, ca = attn_half_forward(x1, x2, W, cfg, B, S, keep_probs=return_cache)
     y1 = x1 + A                                  # Eq. 1
-    M, cm = moe_half_forward(y1, W, cfg)
+    M, cm = moe_half_forward(y1, W, cfg, forced_idx)
     y2 = x2 + M                                  # Eq. 2
     if return_cache:
         return y1, y2, dict(attn=ca, moe=cm, A=A, M=M)
     return y1, y2
 
 
-def inverse(y1, y2, W, cfg, B, S, n_iters=None, converge=False, return_info=False, tol=None, max_iters=64):
+def inverse(y1, y2, W, cfg, B, S, n_iters=None, converge=False, return_info=False, tol=None, max_iters=64,
+            forced_idx=None):
     """Rebuild the block input from its output.  Stream 2 is exact.  Stream 1 is
     the fixed-point iteration x <- Y1 - Attn(Norm x, Norm X2^, Norm X2^) started
     from x = Y1, run n_iters times (default cfg.n_inv_iters), or, if converge, until
@@ -428,15 +468,17 @@ def inverse(y1, y2, W, cfg, B, S, n_iters=None, converge=False, return_info=Fals
     return x, x2
 
 
-def backward(x1, x2, y1, dy1, dy2, W, cfg, B, S):
+def backward(x1, x2, y1, dy1, dy2, W, cfg, B, S, forced_idx=None, keep_probs=True):
     """Gradients of the block at input (x1, x2) for upstream (dy1, dy2).
     The attention half is recomputed at (x1, x2); the MoE half is recomputed at
     y1 (the exact block output the sweep holds) or at x1 + A(x1, x2) if y1 is None.
+    keep_probs=False: the attention probabilities are not stored but evaluated again
+    head by head in the backward pass (same statements; for long sequences).
     Returns dx1, dx2, grads (dict keyed like the weights)."""
-    A, ca = attn_half_forward(x1, x2, W, cfg, B, S, keep_probs=True)
+    A, ca = attn_half_forward(x1, x2, W, cfg, B, S, keep_probs=keep_probs)
     if y1 is None:
         y1 = x1 + A
-    _, cm = moe_half_forward(y1, W, cfg)
+    _, cm = moe_half_forward(y1, W, cfg, forced_idx)
     dy1_moe, gm = moe_half_backward(dy2, cm, W, cfg)      # Y2 = X2 + M(Y1)
     g1 = dy1 + dy1_moe                                     # total gradient at Y1
     dx1_att, dx2_att, ga = attn_half_backward(g1, ca, W, cfg, B, S)  # Y1 = X1 + A(X1, X2)

@@ -517,3 +517,128 @@ def test_row_sums_and_token_permutation_equivariance():
     assert np.abs(Mp - M[perm]).max() < 1e-13
     assert np.array_equal(cp["idx"], cm["idx"][perm])
     assert cp["counts"].sum() == T * cfg.top_k and np.array_equal(cp["counts"], cm["counts"])
+
+
+# --------------------------------------------------------------------------
+# helpers the GPU parity tests lean on: margin, forced selection, streaming attention backward
+# --------------------------------------------------------------------------
+def test_topk_margin_on_constructed_logits():
+    """The margin decides which tokens the GPU routing comparison may skip, so it is pinned on logits whose k-th and
+    (k+1)-th largest values are known by construction, and against a python sort."""
+    rng = np.random.default_rng(31)
+    E, k = 9, 3
+    z = np.zeros((6, E))
+    gaps = [0.5, 1e-3, 0.0, 2.5e-4, 7.0, 1e-9]
+    for t, gap in enumerate(gaps):
+        top = 3.0 + rng.random(k - 1)                   # k - 1 clearly larger logits
+        kth = 1.0
+        rest = kth - gap - np.concatenate([[0.0], rng.random(E - k - 1)])   # the (k+1)-th is kth - gap exactly
+        row = np.concatenate([top, [kth], rest])
+        z[t] = row[rng.permutation(E)]
+    m = O.topk_margin(z, k)
+    for t, gap in enumerate(gaps):
+        assert abs(m[t] - gap) <= 1e-15, (t, m[t], gap)
+        srt = sorted(z[t].tolist(), reverse=True)
+        assert m[t] == srt[k - 1] - srt[k]
+    # k = E: nothing can flip
+    assert np.all(np.isinf(O.topk_margin(z, E))) and np.all(O.topk_margin(z, E) > 0)
+    # a dropped "-1" or a margin taken between the wrong ranks would show here
+    z2 = np.array([[5.0, 4.0, 2.0, 1.5]])
+    assert O.topk_margin(z2, 1)[0] == 1.0 and O.topk_margin(z2, 2)[0] == 2.0 and O.topk_margin(z2, 3)[0] == 0.5
+
+
+def test_forced_selection_is_the_identity_on_own_selection_and_swaps_experts_otherwise():
+    """forced_idx bypasses the ranking only: forcing the block's own selection reproduces every output and gradient
+    bit for bit; forcing another selection equals the dense all-experts computation masked with that selection."""
+    rng = np.random.default_rng(32)
+    cfg = SMALL
+    W = rand_weights(cfg, rng, 0.3)
+    B, S = 2, 5
+    T = B * S
+    x1, x2 = rng.standard_normal((T, cfg.h)), rng.standard_normal((T, cfg.h))
+    dy1, dy2 = rng.standard_normal((T, cfg.h)), rng.standard_normal((T, cfg.h))
+    y1, y2, cache = O.forward(x1, x2, W, cfg, B, S, return_cache=True)
+    own = cache["moe"]["idx"]
+    y1f, y2f = O.forward(x1, x2, W, cfg, B, S, forced_idx=own)
+    assert np.array_equal(y1, y1f) and np.array_equal(y2, y2f)
+    a = O.backward(x1, x2, y1, dy1, dy2, W, cfg, B, S)
+    b = O.backward(x1, x2, y1, dy1, dy2, W, cfg, B, S, forced_idx=own)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+    for k in a[2]:
+        assert np.array_equal(a[2][k], b[2][k]), k
+    xa = O.inverse(y1, y2, W, cfg, B, S, n_iters=2)
+    xb = O.inverse(y1, y2, W, cfg, B, S, n_iters=2, forced_idx=own)
+    assert np.array_equal(xa[0], xb[0]) and np.array_equal(xa[1], xb[1])
+    # another selection: token 3 takes its two LOWEST-ranked experts instead
+    other = own.copy()
+    z = cache["moe"]["z"]
+    other[3] = np.argsort(z[3], kind="stable")[:cfg.top_k]
+    M, cm = O.moe_half_forward(y1, W, cfg, forced_idx=other)
+    assert np.array_equal(cm["idx"], other)
+    Wf = O.as_f64(W)
+    Um, p, I = cm["Um"], cm["p"], cfg.d_expert
+    assert np.abs(p - scipy.special.softmax(z, axis=-1)).max() < 1e-15       # weights are still this softmax's
+    R = np.zeros((T, cfg.d_model))
+    for t in range(T):
+        for e in other[t]:
+            hh = O.silu(Um[t] @ Wf["w_gate_up"][e, :I].T) * (Um[t] @ Wf["w_gate_up"][e, I:].T)
+            R[t] += p[t, e] * (hh @ Wf["w_down"][e].T)
+    assert np.abs(cm["R"] - R).max() < 1e-13
+    M0 = cache["M"]
+    assert np.abs(M[3] - M0[3]).max() > 1e-6                                # the forced token changed ...
+    keep = np.arange(T) != 3
+    assert np.array_equal(M[keep], M0[keep])                                # ... and only that token
+
+
+def test_route_ranks_not_a_number_as_minus_infinity():
+    cfg = O.replace(SMALL, n_experts=6, top_k=3)
+    z = np.array([[0.1, np.nan, 0.7, -0.2, np.nan, 0.3],
+                  [np.nan] * 6,
+                  [np.nan, -np.inf, np.nan, 2.0, -np.inf, np.nan],
+                  [0.4, 0.9, 0.1, 0.2, 0.3, 0.8]])
+    idx, w, p = O.route(z, cfg)
+    assert idx[0].tolist() == [2, 5, 0]                 # finite logits first
+    assert idx[1].tolist() == [0, 1, 2]                 # all equal (minus infinity): lower index first
+    assert idx[2].tolist() == [3, 0, 1]                 # the finite one, then the tie of NaN and -inf by index
+    assert idx[3].tolist() == [1, 5, 0]                 # a clean row is untouched
+    for t in range(4):
+        assert len(set(idx[t].tolist())) == 3 and idx[t].min() >= 0 and idx[t].max() < 6
+    assert np.all(np.isfinite(w[3]))
+    # the stable grouping of such indices is still a permutation of all (token, slot) pairs
+    counts, offsets, row_map = O.permutation(idx, 6)
+    assert counts.sum() == 12 and sorted(row_map.tolist()) == list(range(12))
+
+
+@pytest.mark.parametrize("causal", [True, False])
+def test_streaming_attention_backward_equals_stored_probabilities(causal):
+    rng = np.random.default_rng(33)
+    B, S, H, dh = 2, 19, 3, 8
+    Q, K, V, dO = (rng.standard_normal((B, S, H, dh)) for _ in range(4))
+    O4, P = O.attention_core(Q, K, V, causal)
+    O4n, none = O.attention_core(Q, K, V, causal, keep_probs=False)
+    assert none is None and np.array_equal(O4, O4n)
+    a = O.attention_core_backward(dO, Q, K, V, P)
+    b = O.attention_core_backward_streaming(dO, Q, K, V, causal)
+    for u, v in zip(a, b):
+        assert np.array_equal(u, v)
+    # and against autograd through the library attention (an independent route to the same gradients)
+    tq, tk, tv = (torch.tensor(np.transpose(t, (0, 2, 1, 3)), dtype=torch.float64, requires_grad=True) for t in (Q, K, V))
+    out = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, is_causal=causal)
+    out.backward(torch.tensor(np.transpose(dO, (0, 2, 1, 3))))
+    for g, t in zip(b, (tq, tk, tv)):
+        assert np.abs(g - np.transpose(t.grad.numpy(), (0, 2, 1, 3))).max() < 1e-12
+
+
+def test_block_backward_without_stored_probabilities():
+    rng = np.random.default_rng(34)
+    cfg = SMALL
+    W = rand_weights(cfg, rng, 0.3)
+    B, S = 2, 6
+    T = B * S
+    x1, x2, dy1, dy2 = (rng.standard_normal((T, cfg.h)) for _ in range(4))
+    y1, _ = O.forward(x1, x2, W, cfg, B, S)
+    a = O.backward(x1, x2, y1, dy1, dy2, W, cfg, B, S)
+    b = O.backward(x1, x2, y1, dy1, dy2, W, cfg, B, S, keep_probs=False)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+    for k in a[2]:
+        assert np.array_equal(a[2][k], b[2][k]), k
