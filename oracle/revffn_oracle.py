@@ -434,18 +434,47 @@ def forward(x1, x2, W, cfg, B, S, return_cache=False, forced_idx=None):
 
 
 def inverse(y1, y2, W, cfg, B, S, n_iters=None, converge=False, return_info=False, tol=None, max_iters=64,
-            forced_idx=None):
+            forced_idx=None, block_positions=0):
     """Rebuild the block input from its output.  Stream 2 is exact.  Stream 1 is
     the fixed-point iteration x <- Y1 - Attn(Norm x, Norm X2^, Norm X2^) started
     from x = Y1, run n_iters times (default cfg.n_inv_iters), or, if converge, until
     successive iterates differ by less than 1e-14 * max|Y1| (at most 64 times), or, if
-    tol is given, until max|x_n - x_(n-1)| <= tol (at most max_iters times)."""
+    tol is given, until max|x_n - x_(n-1)| <= tol (at most max_iters times).
+    With tol and block_positions > 0 the rule is applied to each run of block_positions positions
+    of each sequence on its own (a query row's iterate depends on that row alone, since keys and
+    values come from X2^): a block that has met the tolerance keeps its iterate while the others go
+    on; info then also holds block_iters and block_residuals in (sequence, range) order, and
+    residual / iters are the largest over the blocks."""
     M, cm = moe_half_forward(y1, W, cfg)
     x2 = y2 - M
     if cfg.symmetric:                            # closed form: the branch depends on X2^ alone
         A, _ = attn_half_forward(y1, x2, W, cfg, B, S, keep_probs=False)
         x = y1 - A
         return (x, x2, dict(residual=0.0, iters=0, moe=cm, residuals=[])) if return_info else (x, x2)
+    if tol is not None and block_positions > 0:
+        nj = -(-S // block_positions)
+        rows = [np.arange(b * S + j * block_positions, b * S + min(S, (j + 1) * block_positions))
+                for b in range(B) for j in range(nj)]
+        x = y1.copy()
+        active = [True] * len(rows)
+        b_it, b_res = [0] * len(rows), [0.0] * len(rows)
+        for it in range(1, max_iters + 1):
+            A, _ = attn_half_forward(x, x2, W, cfg, B, S, keep_probs=False)
+            xn = y1 - A
+            for q, r in enumerate(rows):
+                if not active[q]:
+                    continue
+                b_res[q] = float(np.max(np.abs(xn[r] - x[r])))
+                b_it[q] = it
+                x[r] = xn[r]
+                if b_res[q] <= tol:
+                    active[q] = False
+            if not any(active):
+                break
+        if return_info:
+            return x, x2, dict(residual=max(b_res), iters=max(b_it), moe=cm, residuals=[],
+                               block_iters=b_it, block_residuals=b_res)
+        return x, x2
     x = y1.copy()
     n = cfg.n_inv_iters if n_iters is None else n_iters
     res, it = np.inf, 0

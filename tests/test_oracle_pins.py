@@ -642,3 +642,41 @@ def test_block_backward_without_stored_probabilities():
     assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
     for k in a[2]:
         assert np.array_equal(a[2][k], b[2][k]), k
+
+
+def test_blockwise_stopping_rule_lands_on_fixed_counts():
+    """The per-block stopping rule of the inverse: every block's rebuilt rows are bit for bit those of the fixed-count
+    iteration run as many times as that block ran (a row's iterate depends on that row alone), counts are 1 under a
+    huge tolerance and the cap under a zero one."""
+    rng = np.random.default_rng(41)
+    cfg = O.replace(SMALL, n_heads=2, head_dim=8)
+    W = rand_weights(cfg, rng, 0.25)
+    B, S, bp = 2, 12, 4
+    T = B * S
+    x1, x2 = rng.standard_normal((T, cfg.h)), rng.standard_normal((T, cfg.h))
+    y1, y2 = O.forward(x1, x2, W, cfg, B, S)
+    _, _, whole = O.inverse(y1, y2, W, cfg, B, S, tol=0.0, max_iters=6, return_info=True)
+    r = whole["residuals"]
+    assert len(r) == 6 and r[1] < r[0]
+    tol = float(np.sqrt(r[2] * r[3]))
+    xb, x2b, info = O.inverse(y1, y2, W, cfg, B, S, tol=tol, max_iters=12, return_info=True, block_positions=bp)
+    its = info["block_iters"]
+    assert len(its) == B * 3 and max(its) == info["iters"] and min(its) >= 1
+    assert len(set(its)) > 1, its                       # the blocks do stop at different counts here
+    fixed = {n: O.inverse(y1, y2, W, cfg, B, S, n_iters=n)[0] for n in set(its)}
+    for q, n in enumerate(its):
+        b, j = divmod(q, 3)
+        rows = slice(b * S + j * bp, b * S + (j + 1) * bp)
+        assert np.array_equal(xb[rows], fixed[n][rows]), (q, n)
+        assert info["block_residuals"][q] <= tol
+    assert np.array_equal(x2b, O.inverse(y1, y2, W, cfg, B, S, n_iters=1)[1])
+    # limits of the rule
+    _, _, big = O.inverse(y1, y2, W, cfg, B, S, tol=1e9, max_iters=12, return_info=True, block_positions=bp)
+    assert big["block_iters"] == [1] * 6
+    _, _, cap = O.inverse(y1, y2, W, cfg, B, S, tol=0.0, max_iters=5, return_info=True, block_positions=bp)
+    assert cap["block_iters"] == [5] * 6
+    # one block covering everything is the whole-call rule
+    xa, _, ia = O.inverse(y1, y2, W, cfg, B, S, tol=tol, max_iters=12, return_info=True)
+    xw, _, iw = O.inverse(y1, y2, W, cfg, B, S, tol=tol, max_iters=12, return_info=True, block_positions=10 ** 6)
+    # (block_positions >= S: one block per sequence; the whole-call count is the largest of them)
+    assert max(iw["block_iters"]) == ia["iters"]
