@@ -26,7 +26,8 @@
  *  - A stream is token-major [T, h], T = B*S, token t = b*S + s, with row
  *    stride `ld` elements (ld >= h).  ld = d lets the two halves of one [T, d]
  *    hidden tensor be passed without a copy (section 3.1, the split display).
- *  - Every call only enqueues work and returns; it never synchronises the host.
+ *  - Every compute call only enqueues work and returns; it never synchronises the host (the setters and getters of
+ *    the tolerance-driven inverse and revffn_profile_read say where they wait).
  *    Work is ordered after what `hip_stream` (a hipStream_t; NULL = the default
  *    stream) already holds, and `hip_stream` is ordered after all of it when the call
  *    returns; independent branches inside a call run on three helper streams owned by
@@ -34,7 +35,9 @@
  *    variable REVFFN_NO_STREAMS=1 at creation keep everything on `hip_stream`).  Calls on one context must be issued on one stream at a time
  *    (they share the context workspace).
  *  - Return value: 0 on success, a negative REVFFN_E* code otherwise.  No call
- *    throws or aborts.  On error nothing has been enqueued.
+ *    throws or aborts.  Arguments are validated before the first launch, so REVFFN_EINVAL / ESHAPE / ENULL mean
+ *    that nothing has been enqueued; REVFFN_EHIP / EUNSUPPORTED can come from the middle of a call, after part
+ *    of its work has been enqueued (outputs are then undefined).
  *  - Results are deterministic: no floating-point atomics anywhere, so the same
  *    inputs give bit-identical outputs, and the routing recomputed by the
  *    inverse/backward from Y1 is bit-identical to the forward routing.
@@ -150,19 +153,33 @@ int revffn_set_inv_iters(revffn_ctx *ctx, int32_t n_inv_iters);
 /* Tolerance-driven inverse (the fixed-point iteration of section 3.1 run to a stopping rule instead of a fixed
  * count).  tol > 0: every inverse on this context (revffn_inverse, revffn_inverse_backward, each block of
  * revffn_stack_backward) iterates until max |x_n - x_(n-1)| <= tol (absolute, in the units of the streams) or
- * max_iters (1..1024) iterations have run, whichever comes first, and n_inv_iters is ignored.  The stopping
- * decision is taken on the host: after every iteration the call copies the one-float residual back and waits for
- * the stream, so these calls are no longer asynchronous and cannot be captured into a graph.  In bf16 successive
- * iterates stop changing at the rounding of the stored iterate (about 2^-8 of its largest element); a tolerance
- * below that floor runs to max_iters.  tol = 0 switches back to the fixed count (max_iters ignored).  Resets the
- * statistics below.  Returns REVFFN_EINVAL for a negative or NaN tol or max_iters out of range. */
+ * max_iters (1..1024) iterations have run, whichever comes first, and n_inv_iters is ignored.
+ * The decision is taken on the device, per block of rows: a query row's iterate depends on that row alone (keys and
+ * values come from the rebuilt stream 2, which the iteration does not change), so a block that has met the
+ * tolerance keeps its iterate, bit for bit the one a fixed count of that many iterations gives, while other blocks
+ * go on.  block_positions > 0: a block is a run of that many positions of one sequence (the error of the iteration
+ * sits in the first causal positions, which see few keys: section 3.1, last paragraph); block_positions == 0 (and
+ * revffn_set_inverse_tolerance): one block, the whole call stops together.  The call enqueues all max_iters
+ * iterations and returns; workgroups whose rows are all finished exit at once (a finished iteration costs its
+ * launches, a few microseconds each, so max_iters should be a small cap).  The calls stay asynchronous and can be
+ * captured into a HIP graph.  In bf16 successive iterates stop changing at the rounding of the stored iterate (about
+ * 2^-8 of its largest element); a tolerance below that floor runs to max_iters.  tol = 0 switches back to the fixed
+ * count.  Both setters wait for the device and reset the statistics below (call them outside graph capture).
+ * Return REVFFN_EINVAL for a negative or NaN tol, max_iters out of range or a negative block_positions. */
 int revffn_set_inverse_tolerance(revffn_ctx *ctx, float tol, int32_t max_iters);
+int revffn_set_inverse_tolerance_blocked(revffn_ctx *ctx, float tol, int32_t max_iters, int32_t block_positions);
 
-/* Host-side statistics of the tolerance-driven inverse since revffn_set_inverse_tolerance: number of inverses run,
- * iterations summed over them, and the iteration count and residual of the most recent one.  Any pointer may be
- * NULL.  All zero while the tolerance is off. */
+/* Statistics of the tolerance-driven inverse since the tolerance was set, kept on the device and read back here
+ * (the call waits for the device): inverses run, iterations summed over them (per inverse: the largest count over
+ * its blocks), and the iteration count and residual (largest over the blocks, each at its last iteration) of the
+ * most recent one.  Any pointer may be NULL.  All zero while the tolerance is off. */
 int revffn_get_inverse_stats(revffn_ctx *ctx, int64_t *calls, int64_t *iters_total,
                              int32_t *last_iters, float *last_residual);
+
+/* Per block of the most recent tolerance-driven inverse: iterations run and the residual at the last of them, in
+ * block order (sequence-major, then position range).  iters / residuals: HOST arrays of cap entries (either may be
+ * NULL); *n_blocks receives the number of blocks (B * ceil(S / block_positions), or 1).  Waits for the device. */
+int revffn_get_inverse_blocks(revffn_ctx *ctx, int32_t *iters, float *residuals, int32_t cap, int32_t *n_blocks);
 
 /* Eq. 1-2.  x1, x2: [T,h] inputs; y1, y2: [T,h] outputs, all with row stride ld.
  * y1 may alias x1 and y2 may alias x2 (in-place update). */

@@ -7,7 +7,8 @@ _LIB = None
 
 EXPORTED_SYMBOLS = (
     "revffn_workspace_bytes", "revffn_create", "revffn_destroy", "revffn_set_inv_iters",
-    "revffn_set_inverse_tolerance", "revffn_get_inverse_stats",
+    "revffn_set_inverse_tolerance", "revffn_set_inverse_tolerance_blocked", "revffn_get_inverse_stats",
+    "revffn_get_inverse_blocks",
     "revffn_forward", "revffn_inverse", "revffn_backward", "revffn_backward_stored", "revffn_inverse_backward", "revffn_stack_forward",
     "revffn_stack_backward", "revffn_get_routing", "revffn_enable_taps", "revffn_get_branch",
     "revffn_set_kernel_mode", "revffn_set_helper_streams", "revffn_strerror", "revffn_profile_enable", "revffn_profile_read",
@@ -64,6 +65,8 @@ def load_library():
     lib.revffn_destroy.restype = None
     lib.revffn_set_inv_iters.argtypes = [vp, i32]
     lib.revffn_set_inverse_tolerance.argtypes = [vp, ctypes.c_float, i32]
+    lib.revffn_set_inverse_tolerance_blocked.argtypes = [vp, ctypes.c_float, i32, i32]
+    lib.revffn_get_inverse_blocks.argtypes = [vp, vp, vp, i32, ctypes.POINTER(i32)]
     lib.revffn_get_inverse_stats.argtypes = [vp, ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int64),
                                              ctypes.POINTER(i32), ctypes.POINTER(ctypes.c_float)]
     lib.revffn_enable_taps.argtypes = [vp, i32]
@@ -163,8 +166,21 @@ class Context:
     def set_inv_iters(self, n):
         _check(self.lib.revffn_set_inv_iters(self.handle, n))
 
-    def set_inverse_tolerance(self, tol, max_iters=16):
-        _check(self.lib.revffn_set_inverse_tolerance(self.handle, float(tol), int(max_iters)))
+    def set_inverse_tolerance(self, tol, max_iters=16, block_positions=0):
+        _check(self.lib.revffn_set_inverse_tolerance_blocked(self.handle, float(tol), int(max_iters),
+                                                             int(block_positions)))
+
+    def inverse_blocks(self):
+        """(iterations, residuals) per block of the most recent tolerance-driven inverse, as numpy arrays."""
+        import numpy as np
+        n = ctypes.c_int32(0)
+        _check(self.lib.revffn_get_inverse_blocks(self.handle, None, None, 0, ctypes.byref(n)))
+        it = np.zeros(n.value, dtype=np.int32)
+        rs = np.zeros(n.value, dtype=np.float32)
+        if n.value:
+            _check(self.lib.revffn_get_inverse_blocks(self.handle, it.ctypes.data, rs.ctypes.data, n.value,
+                                                      ctypes.byref(n)))
+        return it, rs
 
     def inverse_stats(self):
         """(inverses run, iterations summed, iterations of the last one, residual of the last one)."""
@@ -302,3 +318,4 @@ def revffn_op_attention_bwd(dtype, kernel_mode, q, k, v, o, d_o, lse, dvec, dq, 
     _check(load_library().revffn_op_attention_bwd(dtype, kernel_mode, _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(d_o),
                                                   _ptr(lse), _ptr(dvec), _ptr(dq), _ptr(dk), _ptr(dv), B, S, H, dh,
                                                   int(causal), _stream(stream)))
+

@@ -28,11 +28,17 @@ struct Carver {            // hands out 256-byte aligned slices of one allocatio
 // HBM) are kept apart from the dense GEMMs of the same operand layout (bound by the matrix cores).
 enum { KID_GEMM_NT = 0, KID_GEMM_NN, KID_GEMM_TN, KID_GEMM_GENERIC, KID_ATTN_FWD_FLASH, KID_ATTN_BWD_FLASH,
        KID_ATTN_FWD_GENERIC, KID_ATTN_BWD_GENERIC, KID_GEMM_NT_EXPERTS, KID_GEMM_NN_EXPERTS, KID_GEMM_TN_EXPERTS,
+       // the memory-bound kernels: algorithmic bytes only (every input read once, every output written once)
+       KID_RMSNORM_FWD, KID_RMSNORM_BWD, KID_ROPE, KID_ROUTER, KID_PERMUTE, KID_COMBINE, KID_MOE_BWD_ROWS,
+       KID_ROUTER_BWD, KID_DUM_FINALIZE, KID_SWIGLU_BWD, KID_COLSUM, KID_GATHER_ROWS, KID_COPY_ROWS,
        KID_COUNT };
 static const char* const kid_names[KID_COUNT] = {"gemm_mfma_nt", "gemm_mfma_nn", "gemm_mfma_tn", "gemm_generic",
                                                  "attn_fwd_flash", "attn_bwd_flash", "attn_fwd_generic",
                                                  "attn_bwd_generic", "gemm_mfma_nt_experts", "gemm_mfma_nn_experts",
-                                                 "gemm_mfma_tn_experts"};
+                                                 "gemm_mfma_tn_experts",
+                                                 "rmsnorm_fwd", "rmsnorm_bwd", "rope", "router", "permute", "combine",
+                                                 "moe_bwd_rows", "router_bwd", "dum_finalize", "swiglu_bwd", "colsum",
+                                                 "gather_rows", "copy_rows"};
 struct ProfRec { int kid; hipEvent_t a, b; double flops, bytes; };
 
 struct revffn_ctx {
@@ -72,12 +78,15 @@ struct revffn_ctx {
   float *tapA, *tapM;
   void *y1c, *xtmp;
   float* resid_dev;
-  // tolerance-driven inverse: > 0 = iterate until max|x_n - x_(n-1)| <= inv_tol, at most inv_max_iters times
+  // tolerance-driven inverse: > 0 = every block of rows iterates until its max|x_n - x_(n-1)| <= inv_tol, at most
+  // inv_max_iters times; inv_block = positions per block inside a sequence (0 = one block for the whole call).
+  // The decision is taken on the device (conv_* kernels); conv holds its state.
   float inv_tol = 0.f;
   int inv_max_iters = 0;
-  long long inv_calls = 0, inv_iters_total = 0;   // since the tolerance was last set
-  int inv_last_iters = 0;
-  float inv_last_residual = 0.f;
+  int inv_block = 0;
+  ConvState conv;
+  size_t conv_zero_words = 0;                     // 32-bit words from conv.row_done on that start every inverse at zero
+  int conv_last_nblk = 0;
   // backward
   void *dRS, *dYp, *dYs, *dHs, *dGUs, *dUm_sh, *dHh, *dGU, *dXg, *dUm, *dn3, *g1;
   float *dw, *dzext, *rinv, *rinv3, *partial;
@@ -174,6 +183,18 @@ size_t carve(revffn_ctx* c, char* base) {
   c->y1c = cv.take(T * h * c->ses);
   c->xtmp = cv.take(T * h * c->ses);
   c->resid_dev = (float*)cv.take(256);
+  {
+    // state of the device-side stopping rule: the four arrays that start every inverse at zero are contiguous
+    const size_t Tp = (T + 3) & ~(size_t)3;
+    char* z = (char*)cv.take(Tp * (1 + 1 + 4 + 4));
+    c->conv.row_done = (unsigned char*)z;
+    c->conv.blk_done = (unsigned char*)(base ? z + Tp : nullptr);
+    c->conv.blk_bits = (unsigned*)(base ? z + 2 * Tp : nullptr);
+    c->conv.blk_iters = (int*)(base ? z + 6 * Tp : nullptr);
+    c->conv_zero_words = Tp * 10 / 4;
+    c->conv.blk_res = (float*)cv.take(Tp * 4);
+    c->conv.stats = (int*)cv.take(256);
+  }
   c->dRS = cv.take(T * d * es);
   c->dYp = cv.take(N * d * es);
   c->dYs = Is ? cv.take(T * d * es) : nullptr;
@@ -323,6 +344,89 @@ int run_gemm(revffn_ctx* c, const GemmArgs& g, hipStream_t s) { return run_gemm(
 // a GEMM whose result is a weight gradient: written in the gradient dtype (float32 with fp32_grads)
 int run_wgrad(revffn_ctx* c, const GemmArgs& g, hipStream_t s) { return run_gemm(c, g, c->dt, c->dt, c->gdt, s); }
 
+// ---- the memory-bound kernels, timed like the GEMMs when profiling is on: algorithmic bytes = every input read
+// once and every output written once (index arrays and per-row scalars included, gains and tables left out)
+inline double esz(int dt) { return dt ? 2.0 : 4.0; }
+void p_rmsnorm_fwd(revffn_ctx* c, int dt, int tx, const void* x, i64 ldx, const void* g, void* out, i64 ldo, int rows,
+                   int h, float eps, hipStream_t s, const unsigned char* skip = nullptr) {
+  ProfScope ps(c, s, 0, (double)rows * h * (esz(tx) + esz(dt)));
+  launch_rmsnorm_fwd(dt, tx, x, ldx, g, out, ldo, rows, h, eps, s, skip);
+  ps.done(KID_RMSNORM_FWD);
+}
+void p_rmsnorm_bwd(revffn_ctx* c, int dt, int tx, const void* dy, i64 ldd, const void* x, i64 ldx, const void* g,
+                   const void* base, i64 ldb, void* dx, i64 ldo, float* rinv, int rows, int h, float eps, hipStream_t s) {
+  ProfScope ps(c, s, 0, (double)rows * h * (esz(tx) + (base ? 3 : 2) * esz(dt)) + rows * 4.0);
+  launch_rmsnorm_bwd(dt, tx, dy, ldd, x, ldx, g, base, ldb, dx, ldo, rinv, rows, h, eps, s);
+  ps.done(KID_RMSNORM_BWD);
+}
+void p_rope(revffn_ctx* c, int dt, void* buf, const float* cs, int T, int S, int H, int dh, float sign, hipStream_t s,
+            void* buf2 = nullptr, const unsigned char* skip = nullptr) {
+  ProfScope ps(c, s, 0, (buf2 ? 2.0 : 1.0) * 2.0 * T * H * dh * esz(dt));
+  launch_rope(dt, buf, cs, T, S, H, dh, sign, s, buf2, skip);
+  ps.done(KID_ROPE);
+}
+void p_router(revffn_ctx* c, int dt, const void* y1, i64 ld, const float* zparts, int n_parts, const float* b_router,
+              float* probs, int* idx, float* wts, float* gamma, int T, int h, int E, int k, int has_gate, int norm_topk,
+              float eps, hipStream_t s) {
+  ProfScope ps(c, s, 0, (double)T * (h * esz(dt) + (double)n_parts * (E + has_gate) * 4 + E * 4 + k * 8 + has_gate * 4));
+  launch_router(dt, y1, ld, zparts, n_parts, b_router, probs, idx, wts, gamma, T, h, E, k, has_gate, norm_topk, eps, s);
+  ps.done(KID_ROUTER);
+}
+void p_permute(revffn_ctx* c, const int* idx, int T, int k, int E, int* counts, int* offsets, int* row_map, int* inv_map,
+               const TileLists& tl, hipStream_t s) {
+  ProfScope ps(c, s, 0, (double)T * k * 4 * 4);                    // idx read twice, row_map and inv_map written
+  launch_permute(idx, T, k, E, counts, offsets, row_map, inv_map, tl, s);
+  ps.done(KID_PERMUTE);
+}
+void p_combine(revffn_ctx* c, int dt, const void* yp, const int* inv_map, const float* wts, const void* ys,
+               const float* gamma, void* rs, int T, int d, int k, hipStream_t s) {
+  ProfScope ps(c, s, 0, (double)T * d * esz(dt) * (k + (ys ? 2 : 1)) + (double)T * k * 8);
+  launch_combine(dt, yp, inv_map, wts, ys, gamma, rs, T, d, k, s);
+  ps.done(KID_COMBINE);
+}
+void p_moe_bwd_rows(revffn_ctx* c, int dt, const void* drs, const void* yp, const void* ys, const int* inv_map,
+                    const float* wts, const float* gamma, void* dyp, void* dys, float* dw, float* dzext, int T, int d,
+                    int k, int E1, int has_gate, hipStream_t s) {
+  ProfScope ps(c, s, 0, (double)T * d * esz(dt) * (1 + 2 * k + (has_gate ? 2 : 0)) + (double)T * k * 12);
+  launch_moe_bwd_rows(dt, drs, yp, ys, inv_map, wts, gamma, dyp, dys, dw, dzext, T, d, k, E1, has_gate, s);
+  ps.done(KID_MOE_BWD_ROWS);
+}
+void p_router_bwd(revffn_ctx* c, const float* probs, const int* idx, const float* wts, const float* dw, float* dzext,
+                  int T, int E, int k, int E1, int norm_topk, hipStream_t s, void* dzb = nullptr, int E1p = 0) {
+  ProfScope ps(c, s, 0, (double)T * (E * 8.0 + k * 12.0 + (dzb ? E1p * 2.0 : 0.0)));
+  launch_router_bwd(probs, idx, wts, dw, dzext, T, E, k, E1, norm_topk, s, dzb, E1p);
+  ps.done(KID_ROUTER_BWD);
+}
+void p_dum_finalize(revffn_ctx* c, int dt, const void* dxg, const int* inv_map, const void* dum_sh, const void* dum_r,
+                    const float* dzext, const void* w_router, const void* ws_gate, void* dum, int T, int d, int k, int E,
+                    int E1, hipStream_t s) {
+  ProfScope ps(c, s, 0, (double)T * d * esz(dt) * (k + 1 + (dum_sh ? 1 : 0) + (dum_r ? 1 : 0)) + (double)T * k * 4);
+  launch_dum_finalize(dt, dxg, inv_map, dum_sh, dum_r, dzext, w_router, ws_gate, dum, T, d, k, E, E1, s);
+  ps.done(KID_DUM_FINALIZE);
+}
+void p_swiglu_bwd(revffn_ctx* c, int dt, const void* dhh, const void* gu, void* dgu, i64 rows, int I, hipStream_t s) {
+  ProfScope ps(c, s, 0, 5.0 * rows * I * esz(dt));
+  launch_swiglu_bwd(dt, dhh, gu, dgu, rows, I, s);
+  ps.done(KID_SWIGLU_BWD);
+}
+void p_colsum(revffn_ctx* c, int ta, const void* a, i64 lda, int tb, const void* b, i64 ldb, const float* sc, int tout,
+              void* out, float* partial, int rows, int cols, hipStream_t s) {
+  ProfScope ps(c, s, 0, (double)rows * cols * (esz(ta) + (b ? esz(tb) : 0.0)) + (sc ? rows * 4.0 : 0.0));
+  launch_colsum(ta, a, lda, tb, b, ldb, sc, tout, out, partial, rows, cols, s);
+  ps.done(KID_COLSUM);
+}
+void p_gather_rows(revffn_ctx* c, int dt, const void* src, const int* row_map, int div, void* dst, int rows, int cols,
+                   hipStream_t s) {
+  ProfScope ps(c, s, 0, 2.0 * rows * cols * esz(dt) + rows * 4.0);
+  launch_gather_rows(dt, src, row_map, div, dst, rows, cols, s);
+  ps.done(KID_GATHER_ROWS);
+}
+void p_copy_rows(revffn_ctx* c, int dt, const void* src, i64 lds_, void* dst, i64 ldd, int rows, int cols, hipStream_t s) {
+  ProfScope ps(c, s, 0, 2.0 * rows * cols * esz(dt));
+  launch_copy_rows(dt, src, lds_, dst, ldd, rows, cols, s);
+  ps.done(KID_COPY_ROWS);
+}
+
 #define TRY(x) do { int _e = (x); if (_e) return _e; } while (0)
 
 // ---- fork / join between the caller's stream and the context's helper streams ----------
@@ -353,20 +457,25 @@ hipStream_t side(revffn_ctx* c, hipStream_t main, int i) { return c->use_streams
 
 // ---- attention half ---------------------------------------------------------------
 // Query side of the attention half at x1: n12[0:T], U12[0:T], Q.
-int attn_q(revffn_ctx* c, const revffn_weights* w, const void* x1, i64 ld1, int B, int S, hipStream_t s) {
+// skip (may be null): rows marked there are finished rows of the inverse's iteration and are left alone.
+int attn_q(revffn_ctx* c, const revffn_weights* w, const void* x1, i64 ld1, int B, int S, hipStream_t s,
+           const unsigned char* skip = nullptr) {
   const revffn_config& f = c->cfg;
   const int T = B * S, d = f.d_model, h = d / 2, dt = c->dt;
-  launch_rmsnorm_fwd(dt, c->sdt, x1, ld1, w->norm_a1, c->n12, h, T, h, f.rms_eps, s);
-  TRY(run_gemm(c, nt(c->n12, h, w->pup_a, h, c->U12, d, T, d, h), s));
+  p_rmsnorm_fwd(c, dt, c->sdt, x1, ld1, w->norm_a1, c->n12, h, T, h, f.rms_eps, s, skip);
+  GemmArgs gu = nt(c->n12, h, w->pup_a, h, c->U12, d, T, d, h);
+  gu.row_skip = skip;
+  TRY(run_gemm(c, gu, s));
   GemmArgs gq = nt(c->U12, d, w->wq, d, c->Q, d, T, d, d);
   gq.bias = w->bq;
+  gq.row_skip = skip;
   TRY(run_gemm(c, gq, s));
-  if (f.use_rope) launch_rope(dt, c->Q, c->rope_cs, T, S, f.n_heads, f.head_dim, 1.f, s);
+  if (f.use_rope) p_rope(c, dt, c->Q, c->rope_cs, T, S, f.n_heads, f.head_dim, 1.f, s, nullptr, skip);
   return 0;
 }
 // Recomputes n12, U12, Q, (K, V), O, lse, AO at streams (x1, x2).  q_done: attn_q(x1) has been enqueued already.
 int attn_acts(revffn_ctx* c, const revffn_weights* w, const void* x1, i64 ld1, const void* x2, i64 ld2, int B, int S,
-              bool do_kv, hipStream_t s, bool q_done = false) {
+              bool do_kv, hipStream_t s, bool q_done = false, const unsigned char* skip = nullptr) {
   const revffn_config& f = c->cfg;
   const int T = B * S, d = f.d_model, h = d / 2, es = c->es, dt = c->dt;
   hipStream_t s0 = side(c, s, 0), s1 = side(c, s, 1);
@@ -374,37 +483,39 @@ int attn_acts(revffn_ctx* c, const revffn_weights* w, const void* x1, i64 ld1, c
     // comparison block: queries from stream 2 as well.  n2, U2 keep their places in the second halves of n12, U12.
     void* n2 = at(c->n12, (size_t)T * h, es);
     void* U2s = at(c->U12, (size_t)T * d, es);
-    launch_rmsnorm_fwd(dt, c->sdt, x2, ld2, w->norm_a2, n2, h, T, h, f.rms_eps, s);
+    p_rmsnorm_fwd(c, dt, c->sdt, x2, ld2, w->norm_a2, n2, h, T, h, f.rms_eps, s);
     TRY(run_gemm(c, nt(n2, h, w->pup_a, h, U2s, d, T, d, h), s));
     after(c, s, s0); after(c, s, s1);
     GemmArgs gq = nt(U2s, d, w->wq, d, c->Q, d, T, d, d);
     gq.bias = w->bq;
     TRY(run_gemm(c, gq, s));
-    if (f.use_rope) launch_rope(dt, c->Q, c->rope_cs, T, S, f.n_heads, f.head_dim, 1.f, s);
+    if (f.use_rope) p_rope(c, dt, c->Q, c->rope_cs, T, S, f.n_heads, f.head_dim, 1.f, s);
     do_kv = true;
   } else if (q_done) {
     if (do_kv) {
-      launch_rmsnorm_fwd(dt, c->sdt, x2, ld2, w->norm_a2, at(c->n12, (size_t)T * h, es), h, T, h, f.rms_eps, s);
+      p_rmsnorm_fwd(c, dt, c->sdt, x2, ld2, w->norm_a2, at(c->n12, (size_t)T * h, es), h, T, h, f.rms_eps, s);
       TRY(run_gemm(c, nt(at(c->n12, (size_t)T * h, es), h, w->pup_a, h, at(c->U12, (size_t)T * d, es), d, T, d, h), s));
       after(c, s, s0); after(c, s, s1);
     }
+  } else if (!do_kv) {
+    TRY(attn_q(c, w, x1, ld1, B, S, s, skip));          // a later iterate of the inverse: query side only
   } else {
-    launch_rmsnorm_fwd(dt, c->sdt, x1, ld1, w->norm_a1, c->n12, h, T, h, f.rms_eps, s);
-    if (do_kv) launch_rmsnorm_fwd(dt, c->sdt, x2, ld2, w->norm_a2, at(c->n12, (size_t)T * h, es), h, T, h, f.rms_eps, s);
+    p_rmsnorm_fwd(c, dt, c->sdt, x1, ld1, w->norm_a1, c->n12, h, T, h, f.rms_eps, s);
+    if (do_kv) p_rmsnorm_fwd(c, dt, c->sdt, x2, ld2, w->norm_a2, at(c->n12, (size_t)T * h, es), h, T, h, f.rms_eps, s);
     // the same P_up serves both streams: one GEMM over the stacked rows
     TRY(run_gemm(c, nt(c->n12, h, w->pup_a, h, c->U12, d, do_kv ? 2 * T : T, d, h), s));
     if (do_kv) { after(c, s, s0); after(c, s, s1); }
     GemmArgs gq = nt(c->U12, d, w->wq, d, c->Q, d, T, d, d);
     gq.bias = w->bq;
     TRY(run_gemm(c, gq, s));
-    if (f.use_rope) launch_rope(dt, c->Q, c->rope_cs, T, S, f.n_heads, f.head_dim, 1.f, s);
+    if (f.use_rope) p_rope(c, dt, c->Q, c->rope_cs, T, S, f.n_heads, f.head_dim, 1.f, s);
   }
   if (do_kv) {
     const void* U2 = at(c->U12, (size_t)T * d, es);
     GemmArgs gk = nt(U2, d, w->wk, d, c->K, d, T, d, d);
     gk.bias = w->bk;
     TRY(run_gemm(c, gk, s0));
-    if (f.use_rope) launch_rope(dt, c->K, c->rope_cs, T, S, f.n_heads, f.head_dim, 1.f, s0);
+    if (f.use_rope) p_rope(c, dt, c->K, c->rope_cs, T, S, f.n_heads, f.head_dim, 1.f, s0);
     GemmArgs gv = nt(U2, d, w->wv, d, c->V, d, T, d, d);
     gv.bias = w->bv;
     TRY(run_gemm(c, gv, s1));
@@ -417,18 +528,21 @@ int attn_acts(revffn_ctx* c, const revffn_weights* w, const void* x1, i64 ld1, c
     ProfScope ps(c, s, fl, by);
     bool done = false;
     if (dt == 1 && c->mode == 0)
-      done = launch_attn_fwd_flash(c->Q, c->K, c->V, c->O, c->lse, B, S, f.n_heads, f.head_dim, f.causal, s) == 0;
-    if (!done) launch_attn_fwd_generic(dt, c->Q, c->K, c->V, c->O, c->lse, B, S, f.n_heads, f.head_dim, f.causal, s);
+      done = launch_attn_fwd_flash(c->Q, c->K, c->V, c->O, c->lse, B, S, f.n_heads, f.head_dim, f.causal, s, skip) == 0;
+    if (!done) launch_attn_fwd_generic(dt, c->Q, c->K, c->V, c->O, c->lse, B, S, f.n_heads, f.head_dim, f.causal, s, skip);
     ps.done(done ? KID_ATTN_FWD_FLASH : KID_ATTN_FWD_GENERIC);
   }
-  TRY(run_gemm(c, nt(c->O, d, w->wo, d, c->AO, d, T, d, d), s));
+  GemmArgs go = nt(c->O, d, w->wo, d, c->AO, d, T, d, d);
+  go.row_skip = skip;
+  TRY(run_gemm(c, go, s));
   return 0;
 }
 // dst = resid + sign * P_dn_a(AO)     (Eq. 1 and the second line of the inverse)
 int attn_out(revffn_ctx* c, const revffn_weights* w, const void* resid, i64 ldr, float sign, void* dst, i64 ldd,
-             int T, hipStream_t s) {
+             int T, hipStream_t s, const unsigned char* skip = nullptr) {
   const int d = c->cfg.d_model, h = d / 2;
   GemmArgs g = nt(c->AO, d, w->pdn_a, d, dst, ldd, T, h, d);
+  g.row_skip = skip;
   g.resid = resid; g.ldr = ldr; g.resid_sign = sign; g.resid_f32 = c->sdt == REVFFN_F32;
   if (c->taps) { g.tap = c->tapA; g.ldtap = h; }
   return run_gemm(c, g, c->dt, c->dt, c->sdt, s);
@@ -443,8 +557,8 @@ void router_fold(revffn_ctx* c, const revffn_weights* w, hipStream_t s) {
   hipStream_t sr = side(c, s, 2);
   after(c, s, sr);                        // everything that read wr_ext / wrp before is on s
   // [W_r ; w_shared_gate] stacked into one [E1, d] matrix so that the fold is a single GEMM
-  launch_copy_rows(dt, w->w_router, d, c->wr_ext, d, E, d, sr);
-  if (Is) launch_copy_rows(dt, w->ws_gate, d, at(c->wr_ext, (size_t)E * d, c->es), d, 1, d, sr);
+  p_copy_rows(c, dt, w->w_router, d, c->wr_ext, d, E, d, sr);
+  if (Is) p_copy_rows(c, dt, w->ws_gate, d, at(c->wr_ext, (size_t)E * d, c->es), d, 1, d, sr);
   GemmArgs a = nn(c->wr_ext, d, w->pup_m, h, c->wrp, h, E + (Is ? 1 : 0), h, d);
   a.split_k = SPLIT_FOLD; a.splitk_ws = c->splitk_ws_r; a.col_scale = w->norm_m;
   (void)run_gemm(c, a, dt, dt, 0, sr);
@@ -454,7 +568,7 @@ void router_fold(revffn_ctx* c, const revffn_weights* w, hipStream_t s) {
 // Recomputes n3, Um, routing, GU, Hh, Yp, shared expert and RS at y1.  q_x1 != null: the query side of the attention
 // half at q_x1 (which must not depend on this MoE evaluation) is enqueued on s while the routing chain runs.
 int moe_acts(revffn_ctx* c, const revffn_weights* w, const void* y1, i64 ld, int T, hipStream_t s,
-             const void* q_x1 = nullptr, i64 q_ld = 0, int qB = 0, int qS = 0) {
+             const void* q_x1 = nullptr, i64 q_ld = 0, int qB = 0, int qS = 0, const unsigned char* q_skip = nullptr) {
   const revffn_config& f = c->cfg;
   const int d = f.d_model, h = d / 2, E = f.n_experts, k = f.top_k, I = f.d_expert, Is = f.d_shared, dt = c->dt;
   const int N = T * k, E1 = E + (Is ? 1 : 0);
@@ -472,12 +586,12 @@ int moe_acts(revffn_ctx* c, const revffn_weights* w, const void* y1, i64 ld, int
     GemmTypes tz{c->sdt, 0, 0, dt};
     if (launch_gemm_generic(z, tz, sr)) return REVFFN_EUNSUPPORTED;
   }
-  launch_router(c->sdt, y1, ld, c->splitk_ws_r, SPLIT_LOGITS, w->b_router, c->probs, c->idx, c->wts, c->gamma, T, h, E, k,
+  p_router(c, c->sdt, y1, ld, c->splitk_ws_r, SPLIT_LOGITS, w->b_router, c->probs, c->idx, c->wts, c->gamma, T, h, E, k,
                 Is ? 1 : 0, f.norm_topk_prob, f.rms_eps, sr);
   TileLists tl{{c->tg_a, c->tg_b, c->tg_c}, {c->tm_a, c->tm_b, c->tm_c}, {c->tf_a, c->tf_b, c->tf_c},
                {c->max_tiles_a, c->max_tiles_b, c->max_tiles_c}, {BM_A, BM_B, BM_C}, c->tile_cnt};
-  launch_permute(c->idx, T, k, E, c->counts, c->offsets, c->row_map, c->inv_map, tl, sr);
-  launch_rmsnorm_fwd(dt, c->sdt, y1, ld, w->norm_m, c->n3, h, T, h, f.rms_eps, s);
+  p_permute(c, c->idx, T, k, E, c->counts, c->offsets, c->row_map, c->inv_map, tl, sr);
+  p_rmsnorm_fwd(c, dt, c->sdt, y1, ld, w->norm_m, c->n3, h, T, h, f.rms_eps, s);
   TRY(run_gemm(c, nt(c->n3, h, w->pup_m, h, c->Um, d, T, d, h), s));
   hipStream_t s0 = side(c, s, 0);
   if (Is) {                               // the shared expert needs Um only: next to routing + routed experts
@@ -487,7 +601,7 @@ int moe_acts(revffn_ctx* c, const revffn_weights* w, const void* y1, i64 ld, int
     TRY(run_gemm(c, gs, s0));
     TRY(run_gemm(c, nt(c->Hs, Is, w->ws_down, Is, c->Ys, d, T, d, Is), s0));
   }
-  if (q_x1) TRY(attn_q(c, w, q_x1, q_ld, qB, qS, s));
+  if (q_x1) TRY(attn_q(c, w, q_x1, q_ld, qB, qS, s, q_skip));
   after(c, sr, s);                        // routing and permutation are ready
   // routed experts: GU = Xg . Wgu_e^T (rows gathered from Um through row_map), SwiGLU, Yp = Hh . Wd_e^T
   GemmArgs g1 = nt(c->Um, d, w->w_gate_up, d, c->GU, 2 * I, N, 2 * I, d);
@@ -499,7 +613,7 @@ int moe_acts(revffn_ctx* c, const revffn_weights* w, const void* y1, i64 ld, int
   g2.group_mode = 1; g2.n_groups = E; g2.offsets = c->offsets; g2.b_group_stride = (i64)d * I;
   TRY(run_gemm(c, g2, s));
   if (Is) after(c, s0, s);
-  launch_combine(dt, c->Yp, c->inv_map, c->wts, Is ? c->Ys : nullptr, c->gamma, c->RS, T, d, k, s);
+  p_combine(c, dt, c->Yp, c->inv_map, c->wts, Is ? c->Ys : nullptr, c->gamma, c->RS, T, d, k, s);
   c->lastT = T;
   return 0;
 }
@@ -548,48 +662,50 @@ int inverse_impl(revffn_ctx* c, const revffn_weights* w, const void* y1, const v
   const void* y1k = y1;
   i64 ldk = ld;
   if (x1 == y1 && (n >= 1)) {             // in place: Y1 is needed after x1 starts being overwritten
-    launch_copy_rows(c->sdt, y1, ld, c->y1c, h, T, h, s);
+    p_copy_rows(c, c->sdt, y1, ld, c->y1c, h, T, h, s);
     y1k = c->y1c;
     ldk = h;
   }
+  const unsigned char* skip = nullptr;
+  if (conv) {
+    // the stopping rule runs on the device: row marks, per-block residuals and counts start at zero (a fill kernel,
+    // so that the call can be captured into a graph)
+    c->conv.S = S;
+    c->conv.bp = c->inv_block;
+    c->conv.nj = c->inv_block > 0 ? (S + c->inv_block - 1) / c->inv_block : 1;
+    c->conv.nblk = c->inv_block > 0 ? B * c->conv.nj : 1;
+    c->conv_last_nblk = c->conv.nblk;
+    launch_fill_u32((uint32_t*)c->conv.row_done, 0, (int)c->conv_zero_words, s);
+    skip = c->conv.row_done;
+  }
   // the first fixed-point iterate is Y1 itself, so its query side does not wait for X2^: it fills the main stream
   // while the routing chain runs
-  TRY(moe_acts(c, w, y1k, ldk, T, s, (n >= 1 && !sym) ? y1k : nullptr, ldk, B, S));
+  TRY(moe_acts(c, w, y1k, ldk, T, s, (n >= 1 && !sym) ? y1k : nullptr, ldk, B, S, skip));
   TRY(moe_out(c, w, y2, ld, -1.f, x2, ld, T, s));                 // X2^ = Y2 - MoE branch(Y1)
   if (n == 0) {
-    if (x1 != y1) launch_copy_rows(c->sdt, y1, ld, x1, ld, T, h, s);
+    if (x1 != y1) p_copy_rows(c, c->sdt, y1, ld, x1, ld, T, h, s);
     if (residual) launch_fill_u32((uint32_t*)residual, 0, 1, s);
   }
   for (int it = 1; it <= n; it++) {
     const void* xin = (it == 1) ? y1k : x1;                       // iterate, started at Y1
     i64 ldin = (it == 1) ? ldk : ld;
-    TRY(attn_acts(c, w, xin, ldin, x2, ld, B, S, it == 1, s, it == 1 && !sym));   // K, V depend on X2^ only: once
-    float* rdst = conv ? c->resid_dev : residual;
+    TRY(attn_acts(c, w, xin, ldin, x2, ld, B, S, it == 1, s, it == 1 && !sym, skip));   // K, V depend on X2^ only: once
     if (sym && residual) launch_fill_u32((uint32_t*)residual, 0, 1, s);     // nothing is iterated: residual 0
-    if (!sym && (conv || (it == n && residual))) {
+    if (conv) {
+      // every iteration up to the cap is enqueued; workgroups whose rows have all met the tolerance exit at once,
+      // and the update below touches the other rows only.  The host takes no part in the decision.
+      TRY(attn_out(c, w, y1k, ldk, -1.f, c->xtmp, h, T, s, skip));
+      launch_conv_update(c->sdt, c->xtmp, h, xin, ldin, x1, ld, c->conv, T, h, s);
+      launch_conv_decide(c->conv, T, c->inv_tol, it, s);
+    } else if (!sym && it == n && residual) {
       TRY(attn_out(c, w, y1k, ldk, -1.f, c->xtmp, h, T, s));
-      launch_fill_u32((uint32_t*)rdst, 0, 1, s);
-      launch_absdiff_max_copy(c->sdt, c->xtmp, h, xin, ldin, x1, ld, rdst, T, h, s);
+      launch_fill_u32((uint32_t*)residual, 0, 1, s);
+      launch_absdiff_max_copy(c->sdt, c->xtmp, h, xin, ldin, x1, ld, residual, T, h, s);
     } else {
       TRY(attn_out(c, w, y1k, ldk, -1.f, x1, ld, T, s));          // x <- Y1 - attention branch(x, X2^)
     }
-    if (conv) {
-      // the one place where the host waits for the device inside a call: the stopping decision
-      float r = 0.f;
-      if (hipMemcpyAsync(&r, c->resid_dev, sizeof(float), hipMemcpyDeviceToHost, s) != hipSuccess) return REVFFN_EHIP;
-      if (hipStreamSynchronize(s) != hipSuccess) return REVFFN_EHIP;
-      c->inv_last_iters = it;
-      c->inv_last_residual = r;
-      if (r <= c->inv_tol || it == n) {     // (a NaN residual never passes and runs to the cap)
-        if (residual) launch_copy_rows(0 /* float */, c->resid_dev, 1, residual, 1, 1, 1, s);
-        break;
-      }
-    }
   }
-  if (conv) {
-    c->inv_calls++;
-    c->inv_iters_total += c->inv_last_iters;
-  }
+  if (conv) launch_conv_finalize(c->conv, residual, s);
   if (y1_kept) { *y1_kept = y1k; *ld_kept = ldk; }
   return 0;
 }
@@ -626,13 +742,13 @@ int backward_impl(revffn_ctx* c, const revffn_weights* w, const void* x1, const 
     TRY(run_wgrad(c, tn(dy2, ld, c->RS, d, GF(pdn_m), d, h, d, T), sp));
   }
   TRY(run_gemm(c, nn(dy2, ld, w->pdn_m, d, c->dRS, d, T, d, h), s));
-  launch_moe_bwd_rows(dt, c->dRS, c->Yp, c->Ys, c->inv_map, c->wts, c->gamma, c->dYp, c->dYs, c->dw, c->dzext, T, d,
+  p_moe_bwd_rows(c, dt, c->dRS, c->Yp, c->Ys, c->inv_map, c->wts, c->gamma, c->dYp, c->dYs, c->dw, c->dzext, T, d,
                       k, E1, Is ? 1 : 0, s);
   if (Is) {
     after(c, s, s0);
     if (GF(ws_down)) { after(c, s, sw); TRY(run_wgrad(c, tn(c->dYs, d, c->Hs, Is, GF(ws_down), Is, d, Is, T), sw)); }
     TRY(run_gemm(c, nn(c->dYs, d, w->ws_down, Is, c->dHs, Is, T, Is, d), s0));
-    launch_swiglu_bwd(dt, c->dHs, c->GUs, c->dGUs, T, Is, s0);
+    p_swiglu_bwd(c, dt, c->dHs, c->GUs, c->dGUs, T, Is, s0);
     if (GF(ws_gate_up)) {
       after(c, s0, sw);
       TRY(run_wgrad(c, tn(c->dGUs, 2 * Is, c->Um, d, GF(ws_gate_up), d, 2 * Is, d, T), sw));
@@ -649,11 +765,11 @@ int backward_impl(revffn_ctx* c, const revffn_weights* w, const void* x1, const 
     GemmArgs a = nn(c->dYp, d, w->w_down, I, c->dHh, I, N, I, d);          // dHh = dYp . Wd_e
     a.group_mode = 1; a.n_groups = E; a.offsets = c->offsets; a.b_group_stride = (i64)d * I;
     TRY(run_gemm(c, a, s));
-    launch_swiglu_bwd(dt, c->dHh, c->GU, c->dGU, N, I, s);
+    p_swiglu_bwd(c, dt, c->dHh, c->GU, c->dGU, N, I, s);
     if (GF(w_gate_up)) {
       // dWgu_e = dGU_e^T . Xg_e, with the permuted input rows Xg materialised once
       after(c, s, sw);
-      launch_gather_rows(dt, c->Um, c->row_map, k, c->Xg, N, d, sw);
+      p_gather_rows(c, dt, c->Um, c->row_map, k, c->Xg, N, d, sw);
       GemmArgs b = tn(c->dGU, 2 * I, c->Xg, d, GF(w_gate_up), d, 2 * I, d, N);
       b.group_mode = 2; b.n_groups = E; b.offsets = c->offsets; b.c_group_stride = (i64)2 * I * d;
       TRY(run_wgrad(c, b, sw));
@@ -665,7 +781,7 @@ int backward_impl(revffn_ctx* c, const revffn_weights* w, const void* x1, const 
   // (the bf16 copy of the logit gradients for the matrix-core router GEMM below is written by the same kernel)
   const bool dz_bf16 = dt == 1 && c->mode == 0;
   const int E1p = (E1 + 7) / 8 * 8;
-  launch_router_bwd(c->probs, c->idx, c->wts, c->dw, c->dzext, T, E, k, E1, f.norm_topk_prob, s,
+  p_router_bwd(c, c->probs, c->idx, c->wts, c->dw, c->dzext, T, E, k, E1, f.norm_topk_prob, s,
                     dz_bf16 ? c->dzb : nullptr, E1p);
   // every column sum (bias and gain gradients) goes to helper stream 2: they share one scratch buffer, and the
   // weight-gradient GEMMs keep helper stream 1 to themselves.  The router weight gradient goes there too.
@@ -677,10 +793,10 @@ int backward_impl(revffn_ctx* c, const revffn_weights* w, const void* x1, const 
     a.split_k = SPLIT_DWR; a.splitk_ws = c->splitk_ws;
     GemmTypes t{0, dt, c->gdt, dt};
     if (launch_gemm_generic(a, t, sc)) return REVFFN_EUNSUPPORTED;
-    if (GF(w_router)) launch_copy_rows(c->gdt, c->dwr_tmp, d, GF(w_router), d, E, d, sc);
-    if (Is && GF(ws_gate)) launch_copy_rows(c->gdt, at(c->dwr_tmp, (size_t)E * d, c->ges), d, GF(ws_gate), d, 1, d, sc);
+    if (GF(w_router)) p_copy_rows(c, c->gdt, c->dwr_tmp, d, GF(w_router), d, E, d, sc);
+    if (Is && GF(ws_gate)) p_copy_rows(c, c->gdt, at(c->dwr_tmp, (size_t)E * d, c->ges), d, GF(ws_gate), d, 1, d, sc);
   }
-  if (g && g->b_router) launch_colsum(0, c->dzext, E1, 0, nullptr, 0, nullptr, 0, g->b_router, c->partial, T, E, sc);
+  if (g && g->b_router) p_colsum(c, 0, c->dzext, E1, 0, nullptr, 0, nullptr, 0, g->b_router, c->partial, T, E, sc);
   if (Is) after(c, s0, s);
   const void* dum_r = nullptr;
   if (dz_bf16) {
@@ -689,14 +805,14 @@ int backward_impl(revffn_ctx* c, const revffn_weights* w, const void* x1, const 
     GemmTypes tt{1, 1, 1, 1};
     if (launch_gemm_mfma(a, tt, s) == 0) dum_r = c->dUm_r;
   }
-  launch_dum_finalize(dt, c->dXg, c->inv_map, Is ? c->dUm_sh : nullptr, dum_r, c->dzext, w->w_router, w->ws_gate,
+  p_dum_finalize(c, dt, c->dXg, c->inv_map, Is ? c->dUm_sh : nullptr, dum_r, c->dzext, w->w_router, w->ws_gate,
                       c->dUm, T, d, k, E, E1, s);
   if (GF(pup_m)) { after(c, s, sw); TRY(run_wgrad(c, tn(c->dUm, d, c->n3, h, GF(pup_m), h, d, h, T), sw)); }
   TRY(run_gemm(c, nn(c->dUm, d, w->pup_m, h, c->dn3, h, T, h, d), s));
   // g1 = dY1 + Norm'(dn3): total gradient at Y1
-  launch_rmsnorm_bwd(dt, c->sdt, c->dn3, h, y1, ldy, w->norm_m, dy1, ld, c->g1, h, c->rinv3, T, h, f.rms_eps, s);
+  p_rmsnorm_bwd(c, dt, c->sdt, c->dn3, h, y1, ldy, w->norm_m, dy1, ld, c->g1, h, c->rinv3, T, h, f.rms_eps, s);
   // ---- attention half backward: Y1 = X1 + P_dn_a(AO)
-  if (GF(norm_m)) { after(c, s, sc); launch_colsum(c->sdt, y1, ldy, dt, c->dn3, h, c->rinv3, c->gdt, GF(norm_m), c->partial, T, h, sc); }
+  if (GF(norm_m)) { after(c, s, sc); p_colsum(c, c->sdt, y1, ldy, dt, c->dn3, h, c->rinv3, c->gdt, GF(norm_m), c->partial, T, h, sc); }
   if (GF(pdn_a)) { after(c, s, s0); TRY(run_wgrad(c, tn(c->g1, h, c->AO, d, GF(pdn_a), d, h, d, T), s0)); }
   TRY(run_gemm(c, nn(c->g1, h, w->pdn_a, d, c->dAO, d, T, d, h), s));
   if (GF(wo)) { after(c, s, s0); TRY(run_wgrad(c, tn(c->dAO, d, c->O, d, GF(wo), d, d, d, T), s0)); }
@@ -715,7 +831,7 @@ int backward_impl(revffn_ctx* c, const revffn_weights* w, const void* x1, const 
     ps.done(done ? KID_ATTN_BWD_FLASH : KID_ATTN_BWD_GENERIC);
   }
   if (f.use_rope) {
-    launch_rope(dt, c->dQ, c->rope_cs, T, S, f.n_heads, f.head_dim, -1.f, s, c->dK);   // both in one launch
+    p_rope(c, dt, c->dQ, c->rope_cs, T, S, f.n_heads, f.head_dim, -1.f, s, c->dK);   // both in one launch
   }
   const void* U1 = c->U12;
   const void* U2 = at(c->U12, (size_t)T * d, es);
@@ -733,9 +849,9 @@ int backward_impl(revffn_ctx* c, const revffn_weights* w, const void* x1, const 
   if (GF(wq)) TRY(run_wgrad(c, tn(c->dQ, d, sym ? U2 : U1, d, GF(wq), d, d, d, T), s0));
   if (GF(wk)) TRY(run_wgrad(c, tn(c->dK, d, U2, d, GF(wk), d, d, d, T), s0));
   if (GF(wv)) TRY(run_wgrad(c, tn(c->dV, d, U2, d, GF(wv), d, d, d, T), s0));
-  if (GF(bq) && w->bq) launch_colsum(dt, c->dQ, d, dt, nullptr, 0, nullptr, c->gdt, GF(bq), c->partial, T, d, sc);
-  if (GF(bk) && w->bk) launch_colsum(dt, c->dK, d, dt, nullptr, 0, nullptr, c->gdt, GF(bk), c->partial, T, d, sc);
-  if (GF(bv) && w->bv) launch_colsum(dt, c->dV, d, dt, nullptr, 0, nullptr, c->gdt, GF(bv), c->partial, T, d, sc);
+  if (GF(bq) && w->bq) p_colsum(c, dt, c->dQ, d, dt, nullptr, 0, nullptr, c->gdt, GF(bq), c->partial, T, d, sc);
+  if (GF(bk) && w->bk) p_colsum(c, dt, c->dK, d, dt, nullptr, 0, nullptr, c->gdt, GF(bk), c->partial, T, d, sc);
+  if (GF(bv) && w->bv) p_colsum(c, dt, c->dV, d, dt, nullptr, 0, nullptr, c->gdt, GF(bv), c->partial, T, d, sc);
   TRY(run_gemm(c, nn(c->dK, d, w->wk, d, dU2, d, T, d, d), s));
   {
     GemmArgs a = nn(c->dV, d, w->wv, d, dU2, d, T, d, d);        // dU2 += dV . Wv
@@ -751,11 +867,11 @@ int backward_impl(revffn_ctx* c, const revffn_weights* w, const void* x1, const 
     void* dn2 = at(c->dn12, (size_t)T * h, es);
     if (GF(pup_a)) { after(c, s, s0); TRY(run_wgrad(c, tn(dU2, d, n2, h, GF(pup_a), h, d, h, T), s0)); }
     TRY(run_gemm(c, nn(dU2, d, w->pup_a, h, dn2, h, T, h, d), s));
-    launch_rmsnorm_bwd(dt, c->sdt, dn2, h, x2, ld, w->norm_a2, dy2, ld, dx2, ld, c->rinv + T, T, h, f.rms_eps, s);
-    launch_copy_rows(dt, c->g1, h, dx1, ld, T, h, s);              // dX1 = total gradient at Y1
+    p_rmsnorm_bwd(c, dt, c->sdt, dn2, h, x2, ld, w->norm_a2, dy2, ld, dx2, ld, c->rinv + T, T, h, f.rms_eps, s);
+    p_copy_rows(c, dt, c->g1, h, dx1, ld, T, h, s);              // dX1 = total gradient at Y1
     after(c, s, sc);
     if (GF(norm_a1)) launch_zero(c->gdt, GF(norm_a1), h, sc);          // stream 1 is not normalised in this block
-    if (GF(norm_a2)) launch_colsum(c->sdt, x2, ld, dt, dn2, h, c->rinv + T, c->gdt, GF(norm_a2), c->partial, T, h, sc);
+    if (GF(norm_a2)) p_colsum(c, c->sdt, x2, ld, dt, dn2, h, c->rinv + T, c->gdt, GF(norm_a2), c->partial, T, h, sc);
     after(c, sw, s);
     after(c, s0, s);
     after(c, sc, s);
@@ -765,13 +881,13 @@ int backward_impl(revffn_ctx* c, const revffn_weights* w, const void* x1, const 
   if (GF(pup_a)) { after(c, s, s0); TRY(run_wgrad(c, tn(c->dU12, d, c->n12, h, GF(pup_a), h, d, h, 2 * T), s0)); }
   TRY(run_gemm(c, nn(c->dU12, d, w->pup_a, h, c->dn12, h, 2 * T, h, d), s));
   // dX1 = g1 + Norm'(dn1);  dX2 = dY2 + Norm'(dn2)
-  launch_rmsnorm_bwd(dt, c->sdt, c->dn12, h, x1, ld, w->norm_a1, c->g1, h, dx1, ld, c->rinv, T, h, f.rms_eps, s);
-  launch_rmsnorm_bwd(dt, c->sdt, at(c->dn12, (size_t)T * h, es), h, x2, ld, w->norm_a2, dy2, ld, dx2, ld, c->rinv + T, T, h,
+  p_rmsnorm_bwd(c, dt, c->sdt, c->dn12, h, x1, ld, w->norm_a1, c->g1, h, dx1, ld, c->rinv, T, h, f.rms_eps, s);
+  p_rmsnorm_bwd(c, dt, c->sdt, at(c->dn12, (size_t)T * h, es), h, x2, ld, w->norm_a2, dy2, ld, dx2, ld, c->rinv + T, T, h,
                      f.rms_eps, s);
   after(c, s, sc);
-  if (GF(norm_a1)) launch_colsum(c->sdt, x1, ld, dt, c->dn12, h, c->rinv, c->gdt, GF(norm_a1), c->partial, T, h, sc);
+  if (GF(norm_a1)) p_colsum(c, c->sdt, x1, ld, dt, c->dn12, h, c->rinv, c->gdt, GF(norm_a1), c->partial, T, h, sc);
   if (GF(norm_a2))
-    launch_colsum(c->sdt, x2, ld, dt, at(c->dn12, (size_t)T * h, es), h, c->rinv + T, c->gdt, GF(norm_a2), c->partial, T, h, sc);
+    p_colsum(c, c->sdt, x2, ld, dt, at(c->dn12, (size_t)T * h, es), h, c->rinv + T, c->gdt, GF(norm_a2), c->partial, T, h, sc);
   after(c, sw, s);                       // every weight gradient is complete for the caller's stream
   after(c, s0, s);
   after(c, sc, s);
@@ -828,6 +944,7 @@ int revffn_create(revffn_ctx** out, const revffn_config* cfg, int32_t max_B, int
   }
   carve(c, (char*)c->slab);
   (void)hipMemset(c->wr_ext, 0, (size_t)((c->cfg.n_experts + (c->cfg.d_shared ? 1 : 0) + 7) / 8 * 8) * c->cfg.d_model * c->es);
+  (void)hipMemset(c->conv.stats, 0, 4 * sizeof(int));
   c->use_streams = getenv("REVFFN_NO_STREAMS") == nullptr;
   { const char* e = getenv("REVFFN_EXPERT_TILE"); if (e && (atoi(e) == 256 || atoi(e) == 128)) c->expert_tile = atoi(e); }
   { const char* e = getenv("REVFFN_NO_FUSED_SWIGLU"); c->no_fused_swiglu = e && atoi(e) != 0; }
@@ -920,23 +1037,46 @@ int revffn_set_inv_iters(revffn_ctx* c, int32_t n) {
   c->cfg.n_inv_iters = n;
   return 0;
 }
-int revffn_set_inverse_tolerance(revffn_ctx* c, float tol, int32_t max_iters) {
+int revffn_set_inverse_tolerance_blocked(revffn_ctx* c, float tol, int32_t max_iters, int32_t block_positions) {
   if (!c) return REVFFN_ENULL;
-  if (!(tol >= 0.f) || (tol > 0.f && (max_iters < 1 || max_iters > 1024))) return REVFFN_EINVAL;
+  if (!(tol >= 0.f) || (tol > 0.f && (max_iters < 1 || max_iters > 1024)) || block_positions < 0) return REVFFN_EINVAL;
+  if (hipDeviceSynchronize() != hipSuccess) return REVFFN_EHIP;            // earlier inverses still update the statistics
+  if (hipMemset(c->conv.stats, 0, 4 * sizeof(int)) != hipSuccess) return REVFFN_EHIP;
   c->inv_tol = tol;
   c->inv_max_iters = tol > 0.f ? max_iters : 0;
-  c->inv_calls = c->inv_iters_total = 0;
-  c->inv_last_iters = 0;
-  c->inv_last_residual = 0.f;
+  c->inv_block = tol > 0.f ? block_positions : 0;
+  c->conv_last_nblk = 0;
   return 0;
+}
+int revffn_set_inverse_tolerance(revffn_ctx* c, float tol, int32_t max_iters) {
+  return revffn_set_inverse_tolerance_blocked(c, tol, max_iters, 0);
 }
 int revffn_get_inverse_stats(revffn_ctx* c, int64_t* calls, int64_t* iters_total, int32_t* last_iters,
                              float* last_residual) {
   if (!c) return REVFFN_ENULL;
-  if (calls) *calls = c->inv_calls;
-  if (iters_total) *iters_total = c->inv_iters_total;
-  if (last_iters) *last_iters = c->inv_last_iters;
-  if (last_residual) *last_residual = c->inv_last_residual;
+  int st[4] = {0, 0, 0, 0};
+  if (c->inv_tol > 0.f) {
+    if (hipDeviceSynchronize() != hipSuccess) return REVFFN_EHIP;
+    if (hipMemcpy(st, c->conv.stats, sizeof(st), hipMemcpyDeviceToHost) != hipSuccess) return REVFFN_EHIP;
+  }
+  float r;
+  memcpy(&r, &st[3], sizeof(r));
+  if (calls) *calls = st[0];
+  if (iters_total) *iters_total = st[1];
+  if (last_iters) *last_iters = st[2];
+  if (last_residual) *last_residual = r;
+  return 0;
+}
+int revffn_get_inverse_blocks(revffn_ctx* c, int32_t* iters, float* residuals, int32_t cap, int32_t* n_blocks) {
+  if (!c) return REVFFN_ENULL;
+  if (cap < 0) return REVFFN_EINVAL;
+  const int n = c->inv_tol > 0.f ? c->conv_last_nblk : 0;
+  if (n_blocks) *n_blocks = n;
+  const int m = n < cap ? n : cap;
+  if (m == 0) return 0;
+  if (hipDeviceSynchronize() != hipSuccess) return REVFFN_EHIP;
+  if (iters && hipMemcpy(iters, c->conv.blk_iters, (size_t)m * 4, hipMemcpyDeviceToHost) != hipSuccess) return REVFFN_EHIP;
+  if (residuals && hipMemcpy(residuals, c->conv.blk_res, (size_t)m * 4, hipMemcpyDeviceToHost) != hipSuccess) return REVFFN_EHIP;
   return 0;
 }
 int revffn_enable_taps(revffn_ctx* c, int32_t on) {

@@ -87,12 +87,18 @@ __device__ __forceinline__ void store_rows64(bf16* lds, int stride, const uint4 
 // ------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(256, 2) flash_fwd_k(const bf16* __restrict__ q, const bf16* __restrict__ k,
                                                    const bf16* __restrict__ v, bf16* __restrict__ o,
-                                                   float* __restrict__ lse, int S, int H, int causal, float scale) {
+                                                   float* __restrict__ lse, int S, int H, int causal, float scale,
+                                                   const unsigned char* __restrict__ row_skip) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   bf16* sK = (bf16*)smem_raw;               // 2 stages [64][KST]
   bf16* sV = sK + 2 * BKV * KST;            // 2 stages [64][VST]
   const int qt = gridDim.y - 1 - blockIdx.y;        // long (late) query tiles first, for every head
   const int hh = blockIdx.x, b = blockIdx.z;
+  if (row_skip) {                           // every query of the tile is a finished row of the inverse's iteration
+    const int r = qt * 128 + (int)threadIdx.x;
+    const int live = threadIdx.x < 128 && r < S && row_skip[(i64)b * S + r] == 0;
+    if (!__syncthreads_or(live)) return;
+  }
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6, g = lane >> 5;
   const i64 ld = (i64)H * DH;
   const bf16* qb = q + (i64)b * S * ld + hh * DH;
@@ -231,7 +237,7 @@ __global__ void __launch_bounds__(256, 2) flash_fwd_k(const bf16* __restrict__ q
 }
 
 int launch_attn_fwd_flash(const void* q, const void* k, const void* v, void* o, float* lse, int B, int S, int H,
-                          int dh, int causal, hipStream_t s) {
+                          int dh, int causal, hipStream_t s, const unsigned char* row_skip) {
   if (dh != DH || B <= 0 || S <= 0) return 1;
   if ((i64)S * H * DH * 2 >= ((i64)1 << 31)) return 1;      // one sequence of one tensor is addressed with 32-bit offsets
   if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)o) & 15) return 1;
@@ -242,7 +248,7 @@ int launch_attn_fwd_flash(const void* q, const void* k, const void* v, void* o, 
     attr_set = true;
   }
   hipLaunchKernelGGL(flash_fwd_k, dim3(H, cdiv(S, 128), B), dim3(256), smem, s, (const bf16*)q, (const bf16*)k,
-                     (const bf16*)v, (bf16*)o, lse, S, H, causal, 1.0f / sqrtf((float)dh));
+                     (const bf16*)v, (bf16*)o, lse, S, H, causal, 1.0f / sqrtf((float)dh), row_skip);
   return 0;
 }
 

@@ -18,12 +18,14 @@ template <class T>
 __global__ void __launch_bounds__(256) attn_fwd_generic_k(const T* __restrict__ q, const T* __restrict__ k,
                                                           const T* __restrict__ v, T* __restrict__ o,
                                                           float* __restrict__ lse, int S, int H, int dh,
-                                                          int causal, float scale) {
+                                                          int causal, float scale,
+                                                          const unsigned char* __restrict__ row_skip) {
   extern __shared__ float sm[];            // qs[dh], ps[256], red[4]
   float* qs = sm;
   float* ps = sm + dh;
   float* red = ps + 256;
   const int i = blockIdx.x, hh = blockIdx.y, b = blockIdx.z;
+  if (row_skip && row_skip[(i64)b * S + i]) return;       // a finished row of the inverse's iteration
   const i64 d = (i64)H * dh;
   const i64 base = (i64)b * S * d + (i64)hh * dh;
   const int nk = causal ? i + 1 : S;
@@ -76,12 +78,12 @@ __global__ void __launch_bounds__(256) attn_fwd_generic_k(const T* __restrict__ 
 }
 
 void launch_attn_fwd_generic(int dt, const void* q, const void* k, const void* v, void* o, float* lse, int B,
-                             int S, int H, int dh, int causal, hipStream_t s) {
+                             int S, int H, int dh, int causal, hipStream_t s, const unsigned char* row_skip) {
   if (B <= 0 || S <= 0) return;
   size_t smem = (size_t)(dh + 256 + 4) * sizeof(float);
   float scale = 1.0f / sqrtf((float)dh);
   DISPATCH_DT(dt, hipLaunchKernelGGL(attn_fwd_generic_k<T>, dim3(S, H, B), dim3(256), smem, s, (const T*)q,
-                                     (const T*)k, (const T*)v, (T*)o, lse, S, H, dh, causal, scale));
+                                     (const T*)k, (const T*)v, (T*)o, lse, S, H, dh, causal, scale, row_skip));
 }
 
 // dvec[b,h,i] = sum_c dO[i,c] * O[i,c]   (the row sum of dP.P in the softmax backward)

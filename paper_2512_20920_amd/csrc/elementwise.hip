@@ -14,10 +14,11 @@
 // ---------------------------------------------------------------------------------
 template <class T, class TX>
 __global__ void __launch_bounds__(256) rmsnorm_fwd_k(const TX* __restrict__ x, i64 ldx, const T* __restrict__ g,
-                                                     T* __restrict__ out, i64 ldo, int rows, int h, float eps) {
+                                                     T* __restrict__ out, i64 ldo, int rows, int h, float eps,
+                                                     const unsigned char* __restrict__ row_skip) {
   int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   int lane = threadIdx.x & 63;
-  if (row >= rows) return;
+  if (row >= rows || (row_skip && row_skip[row])) return;
   const TX* xr = x + (i64)row * ldx;
   float ss = 0.f;
   for (int j = lane; j < h; j += 64) { float v = to_f(xr[j]); ss += v * v; }
@@ -50,9 +51,10 @@ __device__ __forceinline__ f32x8 load8(const float* p) {
 }
 template <class TX>
 __global__ void __launch_bounds__(256) rmsnorm_fwd_v8_k(const TX* __restrict__ x, i64 ldx, const bf16* __restrict__ g,
-                                                        bf16* __restrict__ out, i64 ldo, int rows, int h, float eps) {
+                                                        bf16* __restrict__ out, i64 ldo, int rows, int h, float eps,
+                                                        const unsigned char* __restrict__ row_skip) {
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
-  if (row >= rows) return;
+  if (row >= rows || (row_skip && row_skip[row])) return;
   const TX* xr = x + (i64)row * ldx;
   float ss = 0.f;
   for (int j = lane * 8; j < h; j += 512) {
@@ -74,25 +76,25 @@ __global__ void __launch_bounds__(256) rmsnorm_fwd_v8_k(const TX* __restrict__ x
 }
 
 void launch_rmsnorm_fwd(int dt, int tx, const void* x, i64 ldx, const void* g, void* out, i64 ldo, int rows, int h,
-                        float eps, hipStream_t s) {
+                        float eps, hipStream_t s, const unsigned char* row_skip) {
   if (rows <= 0) return;
   const dim3 grid(cdiv(rows, 4)), block(256);
   if (rows_vec8(dt, h, {x, g, out}, {ldx, ldo})) {
     if (tx == 0)
       hipLaunchKernelGGL(rmsnorm_fwd_v8_k<float>, grid, block, 0, s, (const float*)x, ldx, (const bf16*)g, (bf16*)out,
-                         ldo, rows, h, eps);
+                         ldo, rows, h, eps, row_skip);
     else
       hipLaunchKernelGGL(rmsnorm_fwd_v8_k<bf16>, grid, block, 0, s, (const bf16*)x, ldx, (const bf16*)g, (bf16*)out,
-                         ldo, rows, h, eps);
+                         ldo, rows, h, eps, row_skip);
     return;
   }
   if (dt == 1 && tx == 0) {
     hipLaunchKernelGGL((rmsnorm_fwd_k<bf16, float>), grid, block, 0, s, (const float*)x, ldx, (const bf16*)g,
-                       (bf16*)out, ldo, rows, h, eps);
+                       (bf16*)out, ldo, rows, h, eps, row_skip);
     return;
   }
   DISPATCH_DT(dt, hipLaunchKernelGGL((rmsnorm_fwd_k<T, T>), grid, block, 0, s, (const T*)x, ldx, (const T*)g, (T*)out,
-                                     ldo, rows, h, eps));
+                                     ldo, rows, h, eps, row_skip));
 }
 
 // RMSNorm backward for the input:  dx = r*(g.dy) - x*r^3*mean_j(x_j g_j dy_j), plus an
@@ -303,13 +305,15 @@ void launch_colsum(int ta, const void* a, i64 lda, int tb, const void* b, i64 ld
 // ---------------------------------------------------------------------------------
 template <class T>
 __global__ void __launch_bounds__(256) rope_k(T* __restrict__ buf, T* __restrict__ buf2, const float2* __restrict__ cs,
-                                              i64 total, int S, int H, int half, float sign) {
+                                              i64 total, int S, int H, int half, float sign,
+                                              const unsigned char* __restrict__ row_skip) {
   i64 e = (i64)blockIdx.x * 256 + threadIdx.x;
   if (e >= total) return;
   if (blockIdx.y) buf = buf2;                // second tensor of the launch
   int i = (int)(e % half);
   i64 th = e / half;          // token*H + head
   i64 t = th / H;
+  if (row_skip && row_skip[t]) return;
   int spos = (int)(t % S);
   float2 c = cs[(i64)spos * half + i];
   float sn = sign * c.y;
@@ -322,12 +326,13 @@ __global__ void __launch_bounds__(256) rope_k(T* __restrict__ buf, T* __restrict
 // bf16, half % 8 == 0: one lane rotates 8 consecutive pairs of one (token, head) with 16-byte accesses
 __global__ void __launch_bounds__(256) rope_v8_k(bf16* __restrict__ buf, bf16* __restrict__ buf2,
                                                  const float2* __restrict__ cs, int total8, int S, int H, int half8,
-                                                 float sign) {
+                                                 float sign, const unsigned char* __restrict__ row_skip) {
   const int e = blockIdx.x * 256 + threadIdx.x;
   if (e >= total8) return;
   if (blockIdx.y) buf = buf2;                // second tensor of the launch
   const int i = (e % half8) * 8;
   const int th = e / half8;          // token*H + head
+  if (row_skip && row_skip[th / H]) return;
   const int spos = (th / H) % S;
   const int half = half8 * 8;
   bf16* p = buf + (i64)th * (2 * half) + i;
@@ -346,17 +351,17 @@ __global__ void __launch_bounds__(256) rope_v8_k(bf16* __restrict__ buf, bf16* _
 }
 
 void launch_rope(int dt, void* buf, const float* cs_table, int Tn, int S, int H, int dh, float sign,
-                 hipStream_t s, void* buf2) {
+                 hipStream_t s, void* buf2, const unsigned char* row_skip) {
   i64 total = (i64)Tn * H * (dh / 2);
   if (total <= 0) return;
   const unsigned ny = buf2 ? 2 : 1;
   if (dt == 1 && (dh & 15) == 0 && (((uintptr_t)buf | (uintptr_t)buf2) & 15) == 0 && total / 8 < (i64)1 << 31) {
     hipLaunchKernelGGL(rope_v8_k, dim3(cdiv(total / 8, 256), ny), dim3(256), 0, s, (bf16*)buf, (bf16*)buf2,
-                       (const float2*)cs_table, (int)(total / 8), S, H, dh / 16, sign);
+                       (const float2*)cs_table, (int)(total / 8), S, H, dh / 16, sign, row_skip);
     return;
   }
   DISPATCH_DT(dt, hipLaunchKernelGGL(rope_k<T>, dim3(cdiv(total, 256), ny), dim3(256), 0, s, (T*)buf, (T*)buf2,
-                                     (const float2*)cs_table, total, S, H, dh / 2, sign));
+                                     (const float2*)cs_table, total, S, H, dh / 2, sign, row_skip));
 }
 
 // ---------------------------------------------------------------------------------
@@ -522,4 +527,89 @@ void launch_absdiff_max_copy(int dt, const void* a, i64 lda, const void* b, i64 
   if (total <= 0) return;
   DISPATCH_DT(dt, hipLaunchKernelGGL(absdiff_max_copy_k<T>, dim3(cdiv(total, 256)), dim3(256), 0, s, (const T*)a,
                                      lda, (const T*)b, ldb, (T*)dst, ldd, res, rows, cols));
+}
+
+// ---------------------------------------------------------------------------------
+// Stopping rule of the inverse's fixed-point iteration (x <- Y1 - attention branch(x, X2^)), decided on the device.
+// Each query row's iterate depends on that row alone (keys and values come from X2^, which is fixed), so a block of
+// rows can stop on its own: once max |x_n - x_(n-1)| over the block is <= tol its rows are marked, and the kernels of
+// later iterations leave marked rows alone.  The host enqueues max_iters iterations and never waits.
+// ---------------------------------------------------------------------------------
+__device__ __forceinline__ int conv_block_of(int row, int S, int bp, int nj) {
+  if (bp <= 0) return 0;
+  const int b = row / S;
+  return b * nj + (row - b * S) / bp;
+}
+template <class T>
+__global__ void __launch_bounds__(256) conv_update_k(const T* __restrict__ xn, i64 ldn, const T* xin, i64 ldi, T* dst,
+                                                     i64 ldd, ConvState cs, int rows, int cols) {
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (row >= rows || cs.row_done[row]) return;            // whole wave
+  float m = 0.f;
+  for (int c = lane; c < cols; c += 64) {
+    const T a = xn[(i64)row * ldn + c];
+    m = fmaxf(m, fabsf(to_f(a) - to_f(xin[(i64)row * ldi + c])));   // (dst may be xin: read before the write)
+    dst[(i64)row * ldd + c] = a;
+  }
+  // fmaxf drops a NaN operand; a row with a non-finite difference must not look converged
+  for (int c = lane; c < cols; c += 64) { const float a = to_f(xn[(i64)row * ldn + c]); if (!(a == a)) m = INFINITY; }
+  m = wave_max(m);
+  if (lane == 0) atomicMax(cs.blk_bits + conv_block_of(row, cs.S, cs.bp, cs.nj), __float_as_uint(m));
+}
+__global__ void __launch_bounds__(64) conv_decide_k(ConvState cs, int rows, float tol, int it) {
+  const int blk = blockIdx.x;
+  if (cs.blk_done[blk]) return;
+  const float res = __uint_as_float(cs.blk_bits[blk]);
+  const bool done = res <= tol;
+  __syncthreads();                                        // every lane has read the running maximum
+  if (threadIdx.x == 0) {
+    cs.blk_iters[blk] = it;
+    cs.blk_res[blk] = res;
+    cs.blk_bits[blk] = 0u;
+    if (done) cs.blk_done[blk] = 1;
+  }
+  if (!done) return;
+  int r0, r1;
+  if (cs.bp <= 0) { r0 = 0; r1 = rows; }
+  else {
+    const int b = blk / cs.nj, j = blk - b * cs.nj;
+    r0 = b * cs.S + j * cs.bp;
+    r1 = min(b * cs.S + min(cs.S, (j + 1) * cs.bp), rows);
+  }
+  for (int r = r0 + (int)threadIdx.x; r < r1; r += 64) cs.row_done[r] = 1;
+}
+__global__ void __launch_bounds__(256) conv_finalize_k(ConvState cs, float* residual_out) {
+  __shared__ unsigned rb[4];
+  __shared__ int ri[4];
+  unsigned bits = 0;
+  int iters = 0;
+  for (int b = threadIdx.x; b < cs.nblk; b += 256) {
+    bits = max(bits, __float_as_uint(cs.blk_res[b]));     // residuals are non-negative (or +inf / NaN, which rank above)
+    iters = max(iters, cs.blk_iters[b]);
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) { bits = max(bits, (unsigned)__shfl_xor((int)bits, o, WAVE)); iters = max(iters, __shfl_xor(iters, o, WAVE)); }
+  if ((threadIdx.x & 63) == 0) { rb[threadIdx.x >> 6] = bits; ri[threadIdx.x >> 6] = iters; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    bits = max(max(rb[0], rb[1]), max(rb[2], rb[3]));
+    iters = max(max(ri[0], ri[1]), max(ri[2], ri[3]));
+    if (residual_out) *residual_out = __uint_as_float(bits);
+    cs.stats[0] += 1;
+    cs.stats[1] += iters;
+    cs.stats[2] = iters;
+    cs.stats[3] = (int)bits;
+  }
+}
+void launch_conv_update(int dt, const void* xn, i64 ldn, const void* xin, i64 ldi, void* dst, i64 ldd,
+                        const ConvState& cs, int rows, int cols, hipStream_t s) {
+  if (rows <= 0) return;
+  DISPATCH_DT(dt, hipLaunchKernelGGL(conv_update_k<T>, dim3(cdiv(rows, 4)), dim3(256), 0, s, (const T*)xn, ldn,
+                                     (const T*)xin, ldi, (T*)dst, ldd, cs, rows, cols));
+}
+void launch_conv_decide(const ConvState& cs, int rows, float tol, int it, hipStream_t s) {
+  hipLaunchKernelGGL(conv_decide_k, dim3(cs.nblk), dim3(64), 0, s, cs, rows, tol, it);
+}
+void launch_conv_finalize(const ConvState& cs, float* residual_out, hipStream_t s) {
+  hipLaunchKernelGGL(conv_finalize_k, dim3(1), dim3(256), 0, s, cs, residual_out);
 }

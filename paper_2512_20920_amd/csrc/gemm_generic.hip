@@ -36,6 +36,11 @@ __global__ void __launch_bounds__(256) gemm_generic_k(GemmArgs g) {
       k_end = min(g.K, k0 + per);
     }
   }
+  if (g.row_skip && g.group_mode == 0) {             // nothing to do if every row of the tile is marked as finished
+    int live = 0;
+    for (int r = m0 + (int)threadIdx.x; r < min(m_end, m0 + GT); r += 256) live |= g.row_skip[r] == 0;
+    if (!__syncthreads_or(live)) return;
+  }
   const int n0 = blockIdx.x * GT;
   const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
   float acc[4][4];

@@ -471,6 +471,11 @@ __global__ void __launch_bounds__(NW * 64) gemm_mfma_k(GemmArgs g) {
       k_end = min(g.K, k0 + per);
     }
   }
+  if (g.row_skip && g.group_mode == 0) {             // nothing to do if every row of the tile is marked as finished
+    int live = 0;
+    for (int r = m0 + (int)threadIdx.x; r < min(m_end, m0 + BM); r += NW * 64) live |= g.row_skip[r] == 0;
+    if (!__syncthreads_or(live)) return;
+  }
   gemm_tile<BM, BN, WGM, AT, BT, TC, NW, NS, TM>(g, A, Bm, C, bx, bz, m0, m_end, k0, k_end);
 }
 

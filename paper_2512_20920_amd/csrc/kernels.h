@@ -46,6 +46,9 @@ struct GemmArgs {
   // group_mode 1: number of m-tiles of the list actually in use (device scalar written by the permutation kernel)
   const int* tile_count = nullptr;
   const int* tile_first = nullptr;       // per tile: (first tile of its expert) << 16 | tiles of that expert
+  // dense problems: row_skip[m] != 0 marks an output row that is not wanted (a finished part of the fixed-point
+  // iteration of the inverse); a workgroup whose rows are all marked exits at once, the others compute every row
+  const unsigned char* row_skip = nullptr;
   // set by the MFMA launcher: XCD-aware placement of the tiles (0 = plain 2-D grid), tile counts of the problem
   int xcd_m = 0, tiles_m = 0, tiles_n = 0;
 };
@@ -120,8 +123,9 @@ int launch_gemm_mfma(const GemmArgs& g, GemmTypes t, hipStream_t s);
 
 // ---- normalisation / element-wise ------------------------------------------------
 // tx: element type of x (0 float32, 1 bf16); gains, outputs and gradients have type dt
+// row_skip (may be null): rows marked there are left alone (see GemmArgs::row_skip)
 void launch_rmsnorm_fwd(int dt, int tx, const void* x, i64 ldx, const void* g, void* out, i64 ldo,
-                        int rows, int h, float eps, hipStream_t s);
+                        int rows, int h, float eps, hipStream_t s, const unsigned char* row_skip = nullptr);
 // dx = base + rmsnorm_bwd(dy; x, g);  rinv[rows] receives 1/rms per row (for the gain gradient)
 void launch_rmsnorm_bwd(int dt, int tx, const void* dy, i64 ldd, const void* x, i64 ldx, const void* g,
                         const void* base, i64 ldb, void* dx, i64 ldo, float* rinv,
@@ -133,7 +137,7 @@ void launch_colsum(int ta, const void* a, i64 lda, int tb, const void* b, i64 ld
                    int tout, void* out, float* partial, int rows, int cols, hipStream_t s);
 // rotates buf (and, in the same launch, buf2 of the same shape when it is not null) in place
 void launch_rope(int dt, void* buf, const float* cs_table, int T, int S, int H, int dh, float sign,
-                 hipStream_t s, void* buf2 = nullptr);
+                 hipStream_t s, void* buf2 = nullptr, const unsigned char* row_skip = nullptr);
 void launch_swiglu_fwd(int dt, const void* gu, void* hh, i64 rows, int I, hipStream_t s);
 void launch_swiglu_bwd(int dt, const void* dhh, const void* gu, void* dgu, i64 rows, int I, hipStream_t s);
 void launch_gather_rows(int dt, const void* src, const int* row_map, int div, void* dst, int rows, int cols,
@@ -144,6 +148,24 @@ void launch_zero(int dt, void* p, int n, hipStream_t s);           // n elements
 void launch_fill_u32(uint32_t* p, uint32_t v, int n, hipStream_t s);
 void launch_absdiff_max_copy(int dt, const void* a, i64 lda, const void* b, i64 ldb, void* dst, i64 ldd,
                              float* res, int rows, int cols, hipStream_t s);
+// ---- stopping rule of the fixed-point iteration, decided on the device per block of rows ----------------------
+// Block of row t (token b*S + s): bp > 0: (b, s / bp), nj = ceil(S / bp) blocks per sequence; bp == 0: one block.
+struct ConvState {
+  unsigned char* row_done;    // [T]   1 = the row's block has met the tolerance: later kernels leave it alone
+  unsigned char* blk_done;    // [nblk]
+  unsigned* blk_bits;         // [nblk] running max |x_n - x_(n-1)| of the current iteration (float bits), 0 between
+  int* blk_iters;             // [nblk] iterations the block has run
+  float* blk_res;             // [nblk] its last residual
+  int* stats;                 // calls, iterations summed (max over blocks per call), last call's iterations, its residual bits
+  int S, bp, nj, nblk;
+};
+// rows not done: res[block] = max(res[block], max |xn - xin|), dst = xn
+void launch_conv_update(int dt, const void* xn, i64 ldn, const void* xin, i64 ldi, void* dst, i64 ldd,
+                        const ConvState& cs, int rows, int cols, hipStream_t s);
+// blocks not done: record iteration `it` and the residual; residual <= tol marks the block and its rows done
+void launch_conv_decide(const ConvState& cs, int rows, float tol, int it, hipStream_t s);
+// end of one inverse: max over blocks -> residual_out (may be null) and the statistics
+void launch_conv_finalize(const ConvState& cs, float* residual_out, hipStream_t s);
 
 // ---- routing ---------------------------------------------------------------------
 // zraw[T,E1] = Y1 . (gain * wrp)^T in fp32 (E1 = E (+1: shared gate row)); the kernel scales by 1/rms(Y1)
@@ -172,7 +194,8 @@ void launch_dum_finalize(int dt, const void* dxg, const int* inv_map, const void
 // ---- attention -------------------------------------------------------------------
 // Q,K,V,O,dO,...: [T, H*dh] token-major, head hh occupies columns hh*dh..; lse/dvec: [B,H,S] float
 void launch_attn_fwd_generic(int dt, const void* q, const void* k, const void* v, void* o, float* lse,
-                             int B, int S, int H, int dh, int causal, hipStream_t s);
+                             int B, int S, int H, int dh, int causal, hipStream_t s,
+                             const unsigned char* row_skip = nullptr);
 void launch_attn_dvec(int dt, const void* o, const void* d_o, float* dvec, int B, int S, int H, int dh,
                       hipStream_t s);
 void launch_attn_bwd_generic(int dt, const void* q, const void* k, const void* v, const void* o,
@@ -180,7 +203,8 @@ void launch_attn_bwd_generic(int dt, const void* q, const void* k, const void* v
                              int B, int S, int H, int dh, int causal, hipStream_t s);
 // MFMA flash kernels (bf16, dh = 128); return 1 if unsupported shape.
 int launch_attn_fwd_flash(const void* q, const void* k, const void* v, void* o, float* lse,
-                          int B, int S, int H, int dh, int causal, hipStream_t s);
+                          int B, int S, int H, int dh, int causal, hipStream_t s,
+                          const unsigned char* row_skip = nullptr);
 int launch_attn_bwd_flash(const void* q, const void* k, const void* v, const void* o, const void* d_o,
                           const float* lse, float* dvec, void* dq, void* dk, void* dv,
                           int B, int S, int H, int dh, int causal, hipStream_t s);

@@ -52,15 +52,21 @@ __global__ void __launch_bounds__(256) router_k(const T* __restrict__ y1, i64 ld
   sum = wave_sum(sum);
   const float inv = 1.0f / sum;
   for (int e = lane; e < E; e += 64) probs[(i64)t * E + e] = __expf(z[e] - mx) * inv;
-  // top-k by k rounds of (value desc, index asc) arg-max; a chosen logit is overwritten by -inf
+  // top-k by k rounds of (value desc, index asc) arg-max over the experts not chosen yet.  A logit that is not a
+  // number ranks as minus infinity, and a lane remembers which of its own experts (e = lane + 64 j, E <= 256) are
+  // taken, so every round finds a valid expert that no earlier round has chosen, whatever the logits hold: a token
+  // with a non-finite input cannot disturb the tables of other tokens.
   __builtin_amdgcn_wave_barrier();
   float wsum = 0.f;
   float myw = 0.f;                        // lane s keeps the weight of slot s
+  unsigned taken = 0;                     // bit j: expert lane + 64 j has been chosen
   for (int s = 0; s < k; s++) {
     float bv = -INFINITY;
     int bi = 0x7fffffff;
-    for (int e = lane; e < E; e += 64) {
+    for (int e = lane, j = 0; e < E; e += 64, j++) {
+      if ((taken >> j) & 1u) continue;
       float v = z[e];
+      v = (v == v) ? v : -INFINITY;
       if (v > bv || (v == bv && e < bi)) { bv = v; bi = e; }
     }
 #pragma unroll
@@ -69,12 +75,14 @@ __global__ void __launch_bounds__(256) router_k(const T* __restrict__ y1, i64 ld
       int oi = __shfl_xor(bi, o, WAVE);
       if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
     }
-    // the comparator is a total order, so every lane now holds the same (bv, bi)
+    // the comparator is a total order (no NaN takes part), so every lane now holds the same (bv, bi); with
+    // top_k <= E at least one expert was left, so bi < E (the clamp only guards the stores below)
+    bi = min(bi, E - 1);
+    if ((bi & 63) == lane) taken |= 1u << (bi >> 6);
     float p = __expf(bv - mx) * inv;
     wsum += p;
     if (lane == s) myw = p;
-    if (lane == 0) { idx[(i64)t * k + s] = bi; z[bi] = -INFINITY; }
-    __builtin_amdgcn_wave_barrier();      // LDS traffic of one wave is executed in order
+    if (lane == 0) idx[(i64)t * k + s] = bi;
   }
   if (lane < k) wts[(i64)t * k + lane] = norm_topk ? myw / wsum : myw;
   if (has_gate && lane == 0) gamma[t] = sigmoid_f(z[E]);
@@ -130,7 +138,7 @@ __global__ void __launch_bounds__(PERM_WAVES * 64) permute_k(
     for (int u = 0; u < PERM_UNROLL; u++) {
       int f = base0 + u * 64 + lane;
       bool valid = f < hi;
-      int x = xs[u];
+      int x = min(max(xs[u], 0), E - 1);    // an index outside [0, E) cannot reach the LDS tables
       unsigned long long same;
       same_expert_mask(x, valid, nbits, same);
       if (valid && (same & below) == 0) mycnt[x] += __popcll(same);   // group leader; groups are disjoint
@@ -186,7 +194,7 @@ __global__ void __launch_bounds__(PERM_WAVES * 64) permute_k(
     for (int u = 0; u < PERM_UNROLL; u++) {
       int f = base0 + u * 64 + lane;
       bool valid = f < hi;
-      int x = xs[u];
+      int x = min(max(xs[u], 0), E - 1);
       unsigned long long same;
       same_expert_mask(x, valid, nbits, same);
       int rank = __popcll(same & below);

@@ -75,8 +75,12 @@ def _attention_case(B, S, H, dh, causal, mode, dtype):
     d = H * dh
     q, k, v, do = rnd((B * S, d), 1.5), rnd((B * S, d), 1.5), rnd((B * S, d)), rnd((B * S, d))
     r4 = lambda a: a.reshape(B, S, H, dh)
-    o_ref, P = O.attention_core(r4(q), r4(k), r4(v), causal)
-    dq_ref, dk_ref, dv_ref = O.attention_core_backward(r4(do), r4(q), r4(k), r4(v), P)
+    if S > 2048:          # long sequences: one S x S matrix in flight instead of a stored probability tensor
+        o_ref, _ = O.attention_core(r4(q), r4(k), r4(v), causal, keep_probs=False)
+        dq_ref, dk_ref, dv_ref = O.attention_core_backward_streaming(r4(do), r4(q), r4(k), r4(v), causal)
+    else:
+        o_ref, P = O.attention_core(r4(q), r4(k), r4(v), causal)
+        dq_ref, dk_ref, dv_ref = O.attention_core_backward(r4(do), r4(q), r4(k), r4(v), P)
     sname = "bf16" if dtype == 1 else "f32"
     qd, kd, vd, dod = (Hn.upload(a, sname) for a in (q, k, v, do))
     od = torch.full_like(qd, float("nan"))
@@ -103,6 +107,16 @@ def _attention_case(B, S, H, dh, causal, mode, dtype):
 @pytest.mark.parametrize("B,S,H", [(1, 128, 1), (2, 200, 3), (1, 64, 2), (1, 1, 1), (1, 451, 2)])
 def test_flash_attention(B, S, H, causal):
     _attention_case(B, S, H, 128, causal, 2, 1)
+
+
+@pytest.mark.parametrize("causal", [True, False])
+def test_flash_attention_long_sequence(causal):
+    """One head at the long-context sequence length (S = 8192): forward, dQ, dK and dV element by element."""
+    _attention_case(1, 8192, 1, 128, causal, 2, 1)
+
+
+def test_flash_attention_ragged_long_sequence():
+    _attention_case(1, 2500, 2, 128, True, 2, 1)
 
 
 @pytest.mark.parametrize("dtype,dh", [(0, 16), (1, 32), (0, 80)])

@@ -31,10 +31,11 @@ def _forward_checks(case, tol, min_same=0.97):
     assert relerr(y1g, case.x1 + A_ref) < tol
     # the MoE half is a function of Y1 alone: compare it at the GPU's own (stored) Y1
     rep = {}
-    cm, safe = check_routing(case, y1g, rep)
-    M_ref, _ = O.moe_half_forward(y1g, W, cfg)
-    assert relerr(m_gpu[safe], M_ref[safe]) < tol, "MoE branch"
-    assert relerr(y2g[safe], (case.x2 + M_ref)[safe]) < tol
+    cm, safe, idx_gpu = check_routing(case, y1g, rep)
+    # every token is compared: on a near-tie the oracle evaluates the GPU's selection
+    M_ref, _ = O.moe_half_forward(y1g, W, cfg, forced_idx=idx_gpu)
+    assert relerr(m_gpu, M_ref) < tol, "MoE branch"
+    assert relerr(y2g, case.x2 + M_ref) < tol
     # end to end against the oracle's own Y1 as well (routing flips near ties are excluded)
     y1o, y2o, cache = O.forward(case.x1, case.x2, W, cfg, wl.B, wl.S, return_cache=True)
     same = (cache["moe"]["idx"] == cm["idx"]).all(axis=-1)
@@ -48,13 +49,13 @@ def _inverse_checks(case, y1d, y2d, tol, n_iters):
     y1h, y2h = Hn.download(y1d), Hn.download(y2d)
     x1d, x2d, res = case.inverse(y1d, y2d, n_iters=n_iters, want_residual=True)
     a_gpu, m_gpu = case.branches()
-    x1o, x2o, info = O.inverse(y1h, y2h, W, cfg, wl.B, wl.S, n_iters=n_iters, return_info=True)
-    cm, safe = check_routing(case, y1h)
-    assert relerr(m_gpu[safe], (y2h - x2o)[safe]) < tol, "MoE branch in the inverse"
+    cm, safe, idx_gpu = check_routing(case, y1h)
+    x1o, x2o, info = O.inverse(y1h, y2h, W, cfg, wl.B, wl.S, n_iters=n_iters, return_info=True, forced_idx=idx_gpu)
+    assert relerr(m_gpu, y2h - x2o) < tol, "MoE branch in the inverse"
     if n_iters > 0:
         assert relerr(a_gpu, y1h - x1o) < tol, "attention branch in the inverse"
         assert abs(res - info["residual"]) <= max(tol * info["residual"], 2 * np.abs(y1h).max() * (2.0 ** -8 if case.dt == "bf16" else 2.0 ** -22))
-    assert relerr(Hn.download(x2d)[safe], x2o[safe]) < tol
+    assert relerr(Hn.download(x2d), x2o) < tol
     assert relerr(Hn.download(x1d), x1o) < tol
     return x1d, x2d
 
@@ -63,11 +64,11 @@ def _backward_checks(case, x1d, x2d, y1d, tol):
     wl, cfg, W = case.wl, case.ocfg, case.W
     x1h, x2h, y1h = Hn.download(x1d), Hn.download(x2d), Hn.download(y1d)
     dx1d, dx2d, G = case.backward(x1d, x2d, y1d)
-    dx1o, dx2o, go = O.backward(x1h, x2h, y1h, case.dy1, case.dy2, W, cfg, wl.B, wl.S)
-    _, cm = O.moe_half_forward(y1h, W, cfg)
-    idx = case.routing()[0]
-    flips = int((idx != cm["idx"]).any(axis=-1).sum())
-    assert flips == 0 or O.topk_margin(cm["z"], cfg.top_k).min() < 1e-3
+    # routing of the backward call: no flip where the margin is clear; the oracle then takes the GPU's selection,
+    # so that every gradient is compared whatever a near-tie did (forcing its own selection changes nothing)
+    rep = {}
+    _, _, idx = check_routing(case, y1h, rep)
+    dx1o, dx2o, go = O.backward(x1h, x2h, y1h, case.dy1, case.dy2, W, cfg, wl.B, wl.S, forced_idx=idx)
     errs, bad = {}, {}
     # dX = dY + (branch gradient): as stored, the update is resolvable only down to the rounding of dX
     for name, gd, ref, base in (("dx1", dx1d, dx1o, case.dy1), ("dx2", dx2d, dx2o, case.dy2)):
@@ -85,17 +86,17 @@ def _backward_checks(case, x1d, x2d, y1d, tol):
             errs[k] = relerr(Hn.download(G[k]), ref)
         if not errs[k] < tol:
             bad[k] = errs[k]
-    assert not bad or flips > 0, (bad, errs)
+    assert not bad, (bad, errs, rep)
     # the branch gradients alone, at full tolerance: with dY1 = 0 the stream-1 input gradient has no
     # residual term in front of it, and with dY2 = 0 neither has the stream-2 one
     zero = np.zeros_like(case.dy1)
     dxa, _, _ = case.backward(x1d, x2d, y1d, dy1=zero)
-    ra, _, _ = O.backward(x1h, x2h, y1h, zero, case.dy2, W, cfg, wl.B, wl.S)
+    ra, _, _ = O.backward(x1h, x2h, y1h, zero, case.dy2, W, cfg, wl.B, wl.S, forced_idx=idx)
     errs["dx1|dy1=0"] = relerr(Hn.download(dxa), ra)
     _, dxb, _ = case.backward(x1d, x2d, y1d, dy2=zero)
-    _, rb, _ = O.backward(x1h, x2h, y1h, case.dy1, zero, W, cfg, wl.B, wl.S)
+    _, rb, _ = O.backward(x1h, x2h, y1h, case.dy1, zero, W, cfg, wl.B, wl.S, forced_idx=idx)
     errs["dx2|dy2=0"] = relerr(Hn.download(dxb), rb)
-    assert flips > 0 or (errs["dx1|dy1=0"] < tol and errs["dx2|dy2=0"] < tol), errs
+    assert errs["dx1|dy1=0"] < tol and errs["dx2|dy2=0"] < tol, errs
     return errs
 
 
@@ -766,3 +767,108 @@ def test_calls_can_be_captured_into_a_hip_graph():
         case.inverse(y1d, y2d)
         case.ctx.set_inv_iters(1)
         torch.cuda.synchronize()
+
+
+def test_non_finite_token_does_not_disturb_other_tokens():
+    """One token whose stream-1 row holds a NaN: its own outputs are not numbers, but it selects top_k distinct valid
+    experts (a logit that is not a number ranks as minus infinity, ties to the lower index: experts 0..k-1), and
+    every other token's indices, weights and MoE output are bit-identical to the clean run; counts, offsets and the
+    row map are the stable grouping of those indices."""
+    wl = synth.WORKLOADS["mid_bf16"]
+    case = Case(wl)
+    y1a, y2a = case.forward()
+    idx0, wts0, counts0, offsets0, row_map0 = case.routing()
+    t_bad = 7
+    x1 = case.x1.copy()
+    x1[t_bad, 3] = np.nan
+    y1b, y2b = case.forward(x1=x1)
+    idx1, wts1, counts1, offsets1, row_map1 = case.routing()
+    keep = np.arange(wl.T) != t_bad
+    assert torch.isnan(y1b[t_bad].float()).any()
+    assert idx1[t_bad].tolist() == list(range(wl.top_k))
+    assert np.array_equal(idx1[keep], idx0[keep]) and np.array_equal(wts1[keep], wts0[keep])
+    c2, o2, r2 = O.permutation(idx1, wl.n_experts)
+    assert np.array_equal(counts1, c2) and np.array_equal(offsets1, o2) and np.array_equal(row_map1, r2)
+    assert counts1.sum() == wl.T * wl.top_k
+    keep_t = torch.from_numpy(keep).cuda()
+    assert torch.equal(y1b[keep_t], y1a[keep_t]) and torch.equal(y2b[keep_t], y2a[keep_t])
+    # the oracle's rule on the same stored stream gives the same selection for the poisoned token
+    _, cm = O.moe_half_forward(Hn.download(y1b), case.W, case.ocfg)
+    assert cm["idx"][t_bad].tolist() == idx1[t_bad].tolist()
+
+
+@pytest.mark.parametrize("name,bp", [("mid_f32", 16), ("mid_bf16", 128)])
+def test_inverse_tolerance_per_position_block(name, bp):
+    """The stopping rule applied per (sequence, range of positions), decided on the device: every block's rebuilt rows
+    are bit for bit those of the fixed-count inverse run as many times as that block ran; the per-block counts are the
+    oracle's wherever the residuals are clear of the tolerance; stream 2 and the residual follow; the call is
+    asynchronous, so a captured graph of it replays to the same bits."""
+    case = _slow_contraction_case(name)
+    wl, cfg, W = case.wl, case.ocfg, case.W
+    y1o, y2o = O.forward(case.x1, case.x2, W, cfg, wl.B, wl.S)
+    y1d, y2d = case.up(y1o), case.up(y2o)
+    y1h, y2h = Hn.download(y1d), Hn.download(y2d)
+    _, _, whole = O.inverse(y1h, y2h, W, cfg, wl.B, wl.S, tol=0.0, max_iters=4, return_info=True)
+    r = whole["residuals"]
+    tol = float(np.sqrt(r[1] * r[2])) if name == "mid_f32" else float(np.sqrt(r[0] * r[1]))
+    cap = 6
+    xo, x2o, oi = O.inverse(y1h, y2h, W, cfg, wl.B, wl.S, tol=tol, max_iters=cap, return_info=True, block_positions=bp)
+    case.ctx.set_inverse_tolerance(tol, cap, block_positions=bp)
+    x1d, x2d, res = case.inverse(y1d, y2d, want_residual=True)
+    its, rs = case.ctx.inverse_blocks()
+    nj = -(-wl.S // bp)
+    assert len(its) == wl.B * nj == len(oi["block_iters"])
+    calls, total, last, res_host = case.ctx.inverse_stats()
+    assert (calls, total, last) == (1, int(its.max()), int(its.max())) and res == res_host == float(rs.max())
+    print(f"{name}: block iterations gpu {its.tolist()} oracle {oi['block_iters']}")
+    # counts: the oracle's, except where an oracle residual sits within rounding of the tolerance
+    floor = 8 * np.abs(y1h).max() * (2.0 ** -23 if wl.dtype == "f32" else 2.0 ** -8)
+    for q, (a, b) in enumerate(zip(its.tolist(), oi["block_iters"])):
+        if abs(oi["block_residuals"][q] - tol) > 0.05 * tol + floor and b < cap:
+            assert a == b or (wl.dtype == "bf16" and abs(a - b) <= 1), (q, a, b)
+    assert relerr(Hn.download(x1d), xo) < TOL[wl.dtype] and relerr(Hn.download(x2d), x2o) < TOL[wl.dtype]
+    # bits: each block equals the fixed-count run with its own count
+    case.ctx.set_inverse_tolerance(0.0, 0)
+    fixed = {}
+    for n in sorted(set(its.tolist())):
+        f1, f2 = case.inverse(y1d, y2d, n_iters=n)
+        fixed[n] = f1.clone()
+        assert torch.equal(f2, x2d)
+    for q, n in enumerate(its.tolist()):
+        b, j = divmod(q, nj)
+        lo, hi = b * wl.S + j * bp, b * wl.S + min(wl.S, (j + 1) * bp)
+        assert torch.equal(x1d[lo:hi], fixed[n][lo:hi]), (q, n)
+    # captured graph of the tolerance-driven sweep step: replays give the eager bits, with eager work in between
+    case.ctx.set_inverse_tolerance(tol, cap, block_positions=bp)
+    dy1d, dy2d = case.up(case.dy1), case.up(case.dy2)
+    r1d, r2d, dx1d, dx2d = (case.empty() for _ in range(4))
+    resd = torch.zeros((1,), dtype=torch.float32, device="cuda")
+    G = Hn.alloc_grads(case.Wd)
+
+    def step(stream=None):
+        R.revffn_inverse_backward(case.ctx, case.Wd, y1d, y2d, r1d, r2d, dy1d, dy2d, dx1d, dx2d, G, wl.B, wl.S, wl.h,
+                                  resd, stream)
+
+    outs = lambda: [t.clone() for t in (r1d, r2d, dx1d, dx2d, resd)] + [G[k].clone() for k in sorted(G) if G[k] is not None]
+    step()
+    torch.cuda.synchronize()
+    want = outs()
+    assert torch.equal(r1d, x1d) and torch.equal(r2d, x2d) and float(resd.item()) == res
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        step(side)
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            step(torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for t in (r1d, r2d, dx1d, dx2d):
+            t.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert all(torch.equal(a, b) for a, b in zip(outs(), want)), rep
+        case.forward()                                   # eager work on the same context between replays
+        torch.cuda.synchronize()
+    assert case.ctx.inverse_stats()[0] == 1 + 1 + 3      # the eager step, the warm-up on the side stream, three replays
