@@ -292,6 +292,19 @@ int revffn_op_attention_bwd(int32_t dtype, int32_t kernel_mode, const void *q, c
                             float *dvec, void *dq, void *dk, void *dv, int32_t B, int32_t S,
                             int32_t H, int32_t dh, int32_t causal, void *hip_stream);
 
+/* For callers that cannot allocate (code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc): revffn_op_attention_bwd with its float scratch dvec[B,H,S] taken from a device array built into the
+ * library (4 MiB, held by every GPU the library runs on until the process ends) instead of a caller buffer.  Same
+ * kernels and the same bits as revffn_op_attention_bwd.  Limit: B * H * S <= 1048576 rows, else REVFFN_ESHAPE and
+ * nothing is enqueued.  The call allocates and frees nothing (no hipMalloc / hipFree, no allocating library routine)
+ * and only enqueues work on hip_stream.  Every call on one GPU shares that GPU's array: calls that may overlap on one
+ * GPU (different streams, different threads) race on it and must be serialised by the caller.  Nothing in the array
+ * needs to start at zero: each call's first kernel writes every element the later kernels of that call read. */
+int revffn_op_attention_bwd_noalloc(int32_t dtype, int32_t kernel_mode, const void *q, const void *k,
+                                    const void *v, const void *o, const void *d_o, const float *lse,
+                                    void *dq, void *dk, void *dv, int32_t B, int32_t S,
+                                    int32_t H, int32_t dh, int32_t causal, void *hip_stream);
+
 /* Host-only check hook (no GPU work): where the MFMA GEMM's XCD-aware launch places its workgroups.
  * Workgroups reach the 8 XCDs round-robin by linear id; the kernel maps workgroup `i` back to a tile so that
  * each XCD works on tiles that share operands.  This call runs the same index function on the host for every

@@ -13,7 +13,7 @@ EXPORTED_SYMBOLS = (
     "revffn_stack_backward", "revffn_get_routing", "revffn_enable_taps", "revffn_get_branch",
     "revffn_set_kernel_mode", "revffn_set_helper_streams", "revffn_strerror", "revffn_profile_enable", "revffn_profile_read",
     "revffn_profile_kernel_name", "revffn_op_gemm", "revffn_op_attention_fwd", "revffn_op_attention_bwd",
-    "revffn_op_tile_placement",
+    "revffn_op_attention_bwd_noalloc", "revffn_op_tile_placement",
 )
 
 WEIGHT_FIELDS = (
@@ -89,6 +89,8 @@ def load_library():
     lib.revffn_op_tile_placement.argtypes = [i32, i32, i32, i32, i32, i32, vp, i32, vp, i32]
     lib.revffn_op_attention_bwd.argtypes = [i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                                             i32, i32, i32, i32, i32, vp]
+    lib.revffn_op_attention_bwd_noalloc.argtypes = [i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp,
+                                                    i32, i32, i32, i32, i32, vp]
     lib.revffn_profile_enable.argtypes = [vp, i32]
     lib.revffn_profile_read.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64),
                                         ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
@@ -319,3 +321,9 @@ def revffn_op_attention_bwd(dtype, kernel_mode, q, k, v, o, d_o, lse, dvec, dq, 
                                                   _ptr(lse), _ptr(dvec), _ptr(dq), _ptr(dk), _ptr(dv), B, S, H, dh,
                                                   int(causal), _stream(stream)))
 
+
+def revffn_op_attention_bwd_noalloc(dtype, kernel_mode, q, k, v, o, d_o, lse, dq, dk, dv, B, S, H, dh, causal,
+                                    stream=None):
+    _check(load_library().revffn_op_attention_bwd_noalloc(dtype, kernel_mode, _ptr(q), _ptr(k), _ptr(v), _ptr(o),
+                                                          _ptr(d_o), _ptr(lse), _ptr(dq), _ptr(dk), _ptr(dv), B, S, H,
+                                                          dh, int(causal), _stream(stream)))

@@ -5,6 +5,7 @@
 #include "kernels.h"
 
 #include <math.h>
+#include <mutex>
 #include <new>
 #include <stdlib.h>
 #include <string.h>
@@ -1262,6 +1263,41 @@ int revffn_op_attention_bwd(int32_t dtype, int32_t kernel_mode, const void* q, c
   if (kernel_mode == 2) return REVFFN_EUNSUPPORTED;
   launch_attn_bwd_generic(dtype, q, k, v, o, d_o, lse, dvec, dq, dk, dv, B, S, H, dh, causal, s);
   return 0;
+}
+
+// ---- the entry point that allocates nothing -----------------------------------------------------------------
+// The row-dot scratch of the attention backward (D[b, head, s] = <dO, O>, float) lives in a file-scope device array
+// instead of a caller buffer.  In host code the array's name is only a handle: the device address is looked up once
+// per device with hipGetSymbolAddress and kept, and only that pointer is ever handed to a kernel.
+#define REVFFN_NOALLOC_MAX_ROWS (1 << 20)
+static __device__ __align__(256) float scratch[REVFFN_NOALLOC_MAX_ROWS];
+#define REVFFN_MAX_DEVICES 64
+static float* scratch_ptr[REVFFN_MAX_DEVICES];          // per device: address of that device's copy of `scratch`
+static std::mutex scratch_mu;
+
+int revffn_op_attention_bwd_noalloc(int32_t dtype, int32_t kernel_mode, const void* q, const void* k, const void* v,
+                                    const void* o, const void* d_o, const float* lse, void* dq, void* dk, void* dv,
+                                    int32_t B, int32_t S, int32_t H, int32_t dh, int32_t causal, void* stream) {
+  if ((dtype != 0 && dtype != 1) || kernel_mode < 0 || kernel_mode > 2 || !q || !k || !v || !o || !d_o || !lse ||
+      !dq || !dk || !dv || B < 1 || S < 1 || H < 1 || dh < 2 || dh > 1024)
+    return REVFFN_EINVAL;
+  if ((long long)B * H * S > REVFFN_NOALLOC_MAX_ROWS) return REVFFN_ESHAPE;   // beyond the static scratch
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return REVFFN_EHIP;
+  if (dev < 0 || dev >= REVFFN_MAX_DEVICES) return REVFFN_EUNSUPPORTED;
+  float* dvec;
+  {
+    std::lock_guard<std::mutex> lock(scratch_mu);
+    if (!scratch_ptr[dev]) {
+      void* p = nullptr;
+      if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) { (void)hipGetLastError(); return REVFFN_EHIP; }
+      scratch_ptr[dev] = (float*)p;
+    }
+    dvec = scratch_ptr[dev];
+  }
+  // every element of dvec that the kernels read is written first by the row-dot kernel of the same call, so nothing
+  // of an earlier call's contents needs clearing
+  return revffn_op_attention_bwd(dtype, kernel_mode, q, k, v, o, d_o, lse, dvec, dq, dk, dv, B, S, H, dh, causal, stream);
 }
 
 const char* revffn_strerror(int code) {
