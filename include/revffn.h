@@ -278,9 +278,8 @@ int revffn_set_helper_streams(revffn_ctx *ctx, int32_t on);
  * and dvec float [B,H,S]; the backward needs o and lse from the forward and uses dvec as
  * scratch.  Return 0, REVFFN_EINVAL, or REVFFN_EUNSUPPORTED (kernel_mode 2 = MFMA kernels
  * only, refused when the shape does not fit them).  op_gemm only: kernel_mode + 256 * t with
- * t in 1..8 forces one tile shape of the MFMA kernel for this launch (1 = 128x128 with 4 waves,
- * 2 = 128x64, 3 = 64x128, 4 = 256x128, 5 = 256x256, 6 = 128x128 with 8 waves of 64x32,
- * 7 = 128x128 as used, 8 = 128x64 as used), so that a test can reach every shape at small sizes. */
+ * t in 1..4 forces one tile shape of the MFMA kernel for this launch (1 = 128x64, 2 = 128x128, 3 = 256x128,
+ * 4 = 256x256), so that a test can reach every shape at small sizes. */
 int revffn_op_gemm(int32_t dtype, int32_t kernel_mode, const void *a, const void *b, void *c,
                    int32_t M, int32_t N, int32_t K, int64_t lda, int64_t ldb, int64_t ldc,
                    int32_t a_trans, int32_t b_trans, int32_t out_f32, void *hip_stream);

@@ -628,6 +628,15 @@ int moe_out(revffn_ctx* c, const revffn_weights* w, const void* resid, i64 ldr, 
   return run_gemm(c, g, c->dt, c->dt, c->sdt, s);
 }
 
+// End of an entry point: a call that failed half way (REVFFN_EHIP / EUNSUPPORTED from a launch) may have forked work
+// onto the helper streams; the caller's stream is made to wait for them, so that whatever was enqueued is ordered
+// before the caller's next work.
+int finish(revffn_ctx* c, hipStream_t s, int e) {
+  if (e && c && c->use_streams)
+    for (int i = 0; i < 3; i++) after(c, c->side[i], s);
+  return e;
+}
+
 int check_call(revffn_ctx* c, const revffn_weights* w, int B, int S, i64 ld) {
   if (!c || !w) return REVFFN_ENULL;
   c->fold_queued = false;
@@ -901,7 +910,7 @@ int backward_impl(revffn_ctx* c, const revffn_weights* w, const void* x1, const 
 extern "C" {
 
 size_t revffn_workspace_bytes(const revffn_config* cfg, int32_t max_B, int32_t max_S) {
-  if (check_cfg(cfg) || max_B < 1 || max_S < 1) return 0;
+  if (check_cfg(cfg) || max_B < 1 || max_S < 1 || (long long)max_B * max_S > (1 << 24)) return 0;
   revffn_ctx tmp;
   tmp.cfg = *cfg;
   tmp.dt = cfg->dtype;
@@ -960,9 +969,11 @@ int revffn_create(revffn_ctx** out, const revffn_config* cfg, int32_t max_B, int
     if (ok) c->sync_ev->push_back(e);
   }
   if (!ok) { revffn_destroy(c); return REVFFN_EHIP; }
-  // rotary table: cs[s][i] = (cos, sin)(s * theta^(-2i/dh)), built in double precision on the host
+  // rotary table: cs[s][i] = (cos, sin)(s * theta^(-2i/dh)), built in double precision on the host.  One entry per
+  // position a call may use: a call may put all maxT tokens into one sequence.
   const int half = cfg->head_dim / 2;
-  std::vector<float> tab((size_t)c->maxT * half * 2);
+  std::vector<float> tab;
+  try { tab.resize((size_t)c->maxT * half * 2); } catch (...) { revffn_destroy(c); return REVFFN_EWORKSPACE; }
   for (int sp = 0; sp < c->maxT; sp++)
     for (int i = 0; i < half; i++) {
       double ang = (double)sp * pow((double)cfg->rope_theta, -2.0 * i / (double)cfg->head_dim);
@@ -970,8 +981,7 @@ int revffn_create(revffn_ctx** out, const revffn_config* cfg, int32_t max_B, int
       tab[((size_t)sp * half + i) * 2 + 1] = (float)sin(ang);
     }
   if (hipMemcpy(c->rope_cs, tab.data(), tab.size() * 4, hipMemcpyHostToDevice) != hipSuccess) {
-    (void)hipFree(c->slab);
-    delete c->prof; delete c->ev_pool; delete c;
+    revffn_destroy(c);                      // streams, events and the workspace go with it
     return REVFFN_EHIP;
   }
   *out = c;
@@ -1122,7 +1132,7 @@ int revffn_forward(revffn_ctx* c, const revffn_weights* w, const void* x1, const
                    int32_t B, int32_t S, int64_t ld, void* stream) {
   TRY(check_call(c, w, B, S, ld));
   if (!x1 || !x2 || !y1 || !y2) return REVFFN_ENULL;
-  TRY(forward_impl(c, w, x1, x2, y1, y2, B, S, ld, (hipStream_t)stream));
+  TRY(finish(c, (hipStream_t)stream, forward_impl(c, w, x1, x2, y1, y2, B, S, ld, (hipStream_t)stream)));
   if (x1 != y1 && x2 != y2) { c->fwd_x1 = x1; c->fwd_x2 = x2; c->fwd_y1 = y1; c->fwd_B = B; c->fwd_S = S; c->fwd_ld = ld; }
   return 0;
 }
@@ -1137,14 +1147,16 @@ int revffn_backward_stored(revffn_ctx* c, const revffn_weights* w, const void* x
   if (!x1 || !x2 || !y1 || !dy1 || !dy2 || !dx1 || !dx2) return REVFFN_ENULL;
   if (!match) return REVFFN_EINVAL;
   if (dx1 == x1 || dx1 == x2 || dx2 == x1 || dx2 == x2 || dx1 == y1 || dx2 == y1) return REVFFN_EINVAL;
-  return backward_impl(c, w, x1, x2, y1, ld, dy1, dy2, dx1, dx2, g, B, S, ld, true, true, (hipStream_t)stream, true);
+  return finish(c, (hipStream_t)stream,
+                backward_impl(c, w, x1, x2, y1, ld, dy1, dy2, dx1, dx2, g, B, S, ld, true, true, (hipStream_t)stream, true));
 }
 
 int revffn_inverse(revffn_ctx* c, const revffn_weights* w, const void* y1, const void* y2, void* x1, void* x2,
                    int32_t B, int32_t S, int64_t ld, float* residual, void* stream) {
   TRY(check_call(c, w, B, S, ld));
   if (!x1 || !x2 || !y1 || !y2) return REVFFN_ENULL;
-  return inverse_impl(c, w, y1, y2, x1, x2, B, S, ld, residual, (hipStream_t)stream, nullptr, nullptr);
+  return finish(c, (hipStream_t)stream,
+                inverse_impl(c, w, y1, y2, x1, x2, B, S, ld, residual, (hipStream_t)stream, nullptr, nullptr));
 }
 
 int revffn_backward(revffn_ctx* c, const revffn_weights* w, const void* x1, const void* x2, const void* y1,
@@ -1152,7 +1164,8 @@ int revffn_backward(revffn_ctx* c, const revffn_weights* w, const void* x1, cons
                     int32_t S, int64_t ld, void* stream) {
   TRY(check_call(c, w, B, S, ld));
   if (!x1 || !x2 || !dy1 || !dy2 || !dx1 || !dx2) return REVFFN_ENULL;
-  return backward_impl(c, w, x1, x2, y1, ld, dy1, dy2, dx1, dx2, g, B, S, ld, false, false, (hipStream_t)stream);
+  return finish(c, (hipStream_t)stream,
+                backward_impl(c, w, x1, x2, y1, ld, dy1, dy2, dx1, dx2, g, B, S, ld, false, false, (hipStream_t)stream));
 }
 
 int revffn_inverse_backward(revffn_ctx* c, const revffn_weights* w, const void* y1, const void* y2, void* x1, void* x2,
@@ -1163,8 +1176,8 @@ int revffn_inverse_backward(revffn_ctx* c, const revffn_weights* w, const void* 
   hipStream_t s = (hipStream_t)stream;
   const void* y1k = nullptr;
   i64 ldk = 0;
-  TRY(inverse_impl(c, w, y1, y2, x1, x2, B, S, ld, residual, s, &y1k, &ldk));
-  return backward_impl(c, w, x1, x2, y1k, ldk, dy1, dy2, dx1, dx2, g, B, S, ld, true, c->cfg.n_inv_iters >= 1, s);
+  TRY(finish(c, s, inverse_impl(c, w, y1, y2, x1, x2, B, S, ld, residual, s, &y1k, &ldk)));
+  return finish(c, s, backward_impl(c, w, x1, x2, y1k, ldk, dy1, dy2, dx1, dx2, g, B, S, ld, true, c->cfg.n_inv_iters >= 1, s));
 }
 
 int revffn_stack_forward(revffn_ctx* c, const revffn_weights* w, int32_t n_blocks, const void* x1, const void* x2,
@@ -1174,7 +1187,7 @@ int revffn_stack_forward(revffn_ctx* c, const revffn_weights* w, int32_t n_block
   for (int l = 0; l < n_blocks; l++) TRY(check_call(c, w + l, B, S, ld));
   if (!x1 || !x2 || !y1 || !y2) return REVFFN_ENULL;
   for (int l = 0; l < n_blocks; l++) {
-    TRY(forward_impl(c, w + l, l == 0 ? x1 : y1, l == 0 ? x2 : y2, y1, y2, B, S, ld, (hipStream_t)stream));
+    TRY(finish(c, (hipStream_t)stream, forward_impl(c, w + l, l == 0 ? x1 : y1, l == 0 ? x2 : y2, y1, y2, B, S, ld, (hipStream_t)stream)));
   }
   return 0;
 }
@@ -1191,8 +1204,8 @@ int revffn_stack_backward(revffn_ctx* c, const revffn_weights* w, const revffn_g
     // activations computed at it by the inverse are reused by the backward pass
     const void* y1k = nullptr;
     i64 ldk = 0;
-    TRY(inverse_impl(c, w + l, y1, y2, y1, y2, B, S, ld, nullptr, s, &y1k, &ldk));
-    TRY(backward_impl(c, w + l, y1, y2, y1k, ldk, dy1, dy2, dy1, dy2, g ? g + l : nullptr, B, S, ld, true, c->cfg.n_inv_iters >= 1, s));
+    TRY(finish(c, s, inverse_impl(c, w + l, y1, y2, y1, y2, B, S, ld, nullptr, s, &y1k, &ldk)));
+    TRY(finish(c, s, backward_impl(c, w + l, y1, y2, y1k, ldk, dy1, dy2, dy1, dy2, g ? g + l : nullptr, B, S, ld, true, c->cfg.n_inv_iters >= 1, s)));
   }
   return 0;
 }
@@ -1223,9 +1236,9 @@ int revffn_get_branch(revffn_ctx* c, int32_t which, float* dst, void* stream) {
 int revffn_op_gemm(int32_t dtype, int32_t kernel_mode, const void* a, const void* b, void* c, int32_t M, int32_t N,
                    int32_t K, int64_t lda, int64_t ldb, int64_t ldc, int32_t a_trans, int32_t b_trans,
                    int32_t out_f32, void* stream) {
-  const int tile = kernel_mode >> 8;       // bits 8 and up: MFMA tile shape to force (1..8), 0 = chosen by size
+  const int tile = kernel_mode >> 8;       // bits 8 and up: MFMA tile shape to force (1..4), 0 = chosen by size
   kernel_mode &= 0xff;
-  if ((dtype != 0 && dtype != 1) || kernel_mode < 0 || kernel_mode > 2 || tile < 0 || tile > 8 || !a || !b || !c ||
+  if ((dtype != 0 && dtype != 1) || kernel_mode < 0 || kernel_mode > 2 || tile < 0 || tile > 4 || !a || !b || !c ||
       M < 1 || N < 1 || K < 0)
     return REVFFN_EINVAL;
   GemmArgs g = nt(a, lda, b, ldb, c, ldc, M, N, K);

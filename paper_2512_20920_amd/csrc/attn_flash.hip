@@ -95,9 +95,9 @@ __global__ void __launch_bounds__(256, 2) flash_fwd_k(const bf16* __restrict__ q
   const int qt = gridDim.y - 1 - blockIdx.y;        // long (late) query tiles first, for every head
   const int hh = blockIdx.x, b = blockIdx.z;
   if (row_skip) {                           // every query of the tile is a finished row of the inverse's iteration
-    const int r = qt * 128 + (int)threadIdx.x;
-    const int live = threadIdx.x < 128 && r < S && row_skip[(i64)b * S + r] == 0;
-    if (!__syncthreads_or(live)) return;
+    int live = 0;                           // every wave checks all 128 rows of the tile: same answer, no LDS
+    for (int r = qt * 128 + (int)(threadIdx.x & 63); r < min(S, qt * 128 + 128); r += 64) live |= row_skip[(i64)b * S + r] == 0;
+    if (!__any(live)) return;
   }
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6, g = lane >> 5;
   const i64 ld = (i64)H * DH;
@@ -242,10 +242,10 @@ int launch_attn_fwd_flash(const void* q, const void* k, const void* v, void* o, 
   if ((i64)S * H * DH * 2 >= ((i64)1 << 31)) return 1;      // one sequence of one tensor is addressed with 32-bit offsets
   if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)o) & 15) return 1;
   size_t smem = (size_t)2 * BKV * (KST + VST) * sizeof(bf16);
-  static bool attr_set = false;
-  if (!attr_set) {
+  static std::atomic<unsigned long long> attr_mask{0};
+  if (attr_needed(attr_mask)) {
     (void)hipFuncSetAttribute((const void*)flash_fwd_k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    attr_set = true;
+    attr_done(attr_mask);
   }
   hipLaunchKernelGGL(flash_fwd_k, dim3(H, cdiv(S, 128), B), dim3(256), smem, s, (const bf16*)q, (const bf16*)k,
                      (const bf16*)v, (bf16*)o, lse, S, H, causal, 1.0f / sqrtf((float)dh), row_skip);
@@ -526,11 +526,11 @@ int launch_attn_bwd_flash(const void* q, const void* k, const void* v, const voi
   const float scale = 1.0f / sqrtf((float)dh);
   size_t sm1 = (size_t)4 * BKV * BST * sizeof(bf16);
   size_t sm2 = sm1 + 4 * BKV * sizeof(float);
-  static bool attr_set = false;
-  if (!attr_set) {
+  static std::atomic<unsigned long long> attr_mask{0};
+  if (attr_needed(attr_mask)) {
     (void)hipFuncSetAttribute((const void*)flash_bwd_dq_k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm1);
     (void)hipFuncSetAttribute((const void*)flash_bwd_dkv_k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm2);
-    attr_set = true;
+    attr_done(attr_mask);
   }
   dim3 grid(H, cdiv(S, 128), B);
   hipLaunchKernelGGL(flash_bwd_dq_k, grid, dim3(256), sm1, s, (const bf16*)q, (const bf16*)k, (const bf16*)v,

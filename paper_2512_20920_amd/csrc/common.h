@@ -36,3 +36,17 @@ __device__ __forceinline__ float block_sum_256(float v, float* red) {
 __device__ __forceinline__ float sigmoid_f(float x) { return 1.0f / (1.0f + __expf(-x)); }
 
 static inline int cdiv(i64 a, i64 b) { return (int)((a + b - 1) / b); }
+
+// A kernel's dynamic-LDS limit is an attribute per device: `mask` (one per kernel instantiation) keeps one bit per
+// device id.  attr_needed: the current device has not been marked yet (the caller sets the attribute, then calls
+// attr_done; several threads may do so at once, which is harmless, and none launches before its own call returned).
+#include <atomic>
+static inline bool attr_needed(const std::atomic<unsigned long long>& mask) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev > 63) return true;
+  return (mask.load(std::memory_order_acquire) & (1ull << dev)) == 0;
+}
+static inline void attr_done(std::atomic<unsigned long long>& mask) {
+  int dev = 0;
+  if (hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev <= 63) mask.fetch_or(1ull << dev, std::memory_order_acq_rel);
+}

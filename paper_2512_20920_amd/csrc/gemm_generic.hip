@@ -37,9 +37,9 @@ __global__ void __launch_bounds__(256) gemm_generic_k(GemmArgs g) {
     }
   }
   if (g.row_skip && g.group_mode == 0) {             // nothing to do if every row of the tile is marked as finished
-    int live = 0;
-    for (int r = m0 + (int)threadIdx.x; r < min(m_end, m0 + GT); r += 256) live |= g.row_skip[r] == 0;
-    if (!__syncthreads_or(live)) return;
+    int live = 0;                                    // every wave checks all rows of the tile: same answer, no LDS
+    for (int r = m0 + (int)(threadIdx.x & 63); r < min(m_end, m0 + GT); r += 64) live |= g.row_skip[r] == 0;
+    if (!__any(live)) return;
   }
   const int n0 = blockIdx.x * GT;
   const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;

@@ -472,9 +472,11 @@ __global__ void __launch_bounds__(NW * 64) gemm_mfma_k(GemmArgs g) {
     }
   }
   if (g.row_skip && g.group_mode == 0) {             // nothing to do if every row of the tile is marked as finished
+    // every wave looks at all rows of the tile itself and reaches the same answer: no LDS, no barrier (a block-wide
+    // vote adds 1 KiB of static LDS in front of the stages, which a tile that uses all 160 KiB for them cannot afford)
     int live = 0;
-    for (int r = m0 + (int)threadIdx.x; r < min(m_end, m0 + BM); r += NW * 64) live |= g.row_skip[r] == 0;
-    if (!__syncthreads_or(live)) return;
+    for (int r = m0 + (int)(threadIdx.x & 63); r < min(m_end, m0 + BM); r += 64) live |= g.row_skip[r] == 0;
+    if (!__any(live)) return;
   }
   gemm_tile<BM, BN, WGM, AT, BT, TC, NW, NS, TM>(g, A, Bm, C, bx, bz, m0, m_end, k0, k_end);
 }
@@ -510,63 +512,46 @@ static void go(const GemmArgs& g0, hipStream_t s) {
   }
   constexpr size_t smem = (size_t)NS * (BM + BN) * 128;
   static_assert(smem <= 160 * 1024, "LDS stages exceed the CU's 160 KiB");
-  static bool attr_set = false;
-  if (!attr_set) {
+  static std::atomic<unsigned long long> attr_mask{0};
+  if (attr_needed(attr_mask)) {
     (void)hipFuncSetAttribute((const void*)gemm_mfma_k<BM, BN, WGM, AT, BT, TC, NW, NS>,
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    attr_set = true;
+    attr_done(attr_mask);
   }
   hipLaunchKernelGGL((gemm_mfma_k<BM, BN, WGM, AT, BT, TC, NW, NS>), grid, dim3(NW * 64), smem, s, g);
 }
 
-// The tile shapes: 256x128 and 128x256 (8 waves, one workgroup per CU), 128x128 (8 waves of 32x64, 4 stages: with one
-// workgroup per CU, two waves per SIMD hide each other's LDS and barrier waits; 10-17 % faster than 4 waves of 64x64
-// on the 2048^3 projections), 128x64 (8 waves of 32x32, two workgroups per CU; 1.5 % of a step over 4 waves of 64x32,
-// measured on one box with both builds) and 64x128 (4 waves, two workgroups per CU).
+// The tile shapes: 256x128 and 128x256 (8 waves, one workgroup per CU), 256x256 (2 stages), 128x128 (8 waves of 32x64,
+// 4 stages: with one workgroup per CU, two waves per SIMD hide each other's LDS and barrier waits; 10-17 % faster than
+// 4 waves of 64x64 on the 2048^3 projections) and 128x64 (8 waves of 32x32, two workgroups per CU; 1.5 % of a step
+// over 4 waves of 64x32, measured on one box with both builds).
 template <bool AT, bool BT, class TC> static void go_256x128(const GemmArgs& g, hipStream_t s) { go<256, 128, 4, AT, BT, TC, 8, 3>(g, s); }
 template <bool AT, bool BT, class TC> static void go_256x256(const GemmArgs& g, hipStream_t s) { go<256, 256, 2, AT, BT, TC, 8, 2>(g, s); }
 template <bool AT, bool BT, class TC> static void go_128x128(const GemmArgs& g, hipStream_t s) { go<128, 128, 4, AT, BT, TC, 8, 4>(g, s); }
-template <bool AT, bool BT, class TC> static void go_128x128_w4(const GemmArgs& g, hipStream_t s) { go<128, 128, 2, AT, BT, TC, 4, 4>(g, s); }
 template <bool AT, bool BT, class TC> static void go_128x256(const GemmArgs& g, hipStream_t s) { go<128, 256, 2, AT, BT, TC, 8, 3>(g, s); }
 template <bool AT, bool BT, class TC> static void go_128x64(const GemmArgs& g, hipStream_t s) { go<128, 64, 4, AT, BT, TC, 8, 3>(g, s); }
-template <bool AT, bool BT, class TC> static void go_64x128(const GemmArgs& g, hipStream_t s) { go<64, 128, 1, AT, BT, TC, 4, 3>(g, s); }
-
-// REVFFN_GEMM_TILE (tuning aid): 1 = 128x128 with 4 waves, 2 = 128x64, 3 = 64x128, 4 = 256x128, 5 = 256x256 (2 stages;
-// measured +3 % at 8192^3, worse on the block's shapes), 6 = 128x128 with 8 waves of 64x32, 7 = 128x128 as used, for
-// every non-grouped problem
-static int tile_override() {
-  static int v = -1;
-  if (v < 0) { const char* e = getenv("REVFFN_GEMM_TILE"); v = e ? atoi(e) : 0; }
-  return v;
-}
 
 template <bool AT, bool BT, class TC>
 static void pick_tile(const GemmArgs& g, hipStream_t s) {
-  const int forced = g.force_tile ? g.force_tile : tile_override();
   if (g.act_half && g.group_mode == 0) {
     // SwiGLU epilogue: only tiles whose waves are 64 columns wide (a gate and an up block)
     if ((i64)cdiv(g.M, 256) * cdiv(g.N, 128) >= 512) go_256x128<AT, BT, TC>(g, s);
     else go_128x128<AT, BT, TC>(g, s);
     return;
   }
-  if (g.group_mode != 1 && forced) {
-    switch (forced) {
-      case 1: go_128x128_w4<AT, BT, TC>(g, s); return;
-      case 2: go_128x64<AT, BT, TC>(g, s); return;
-      case 3: go_64x128<AT, BT, TC>(g, s); return;
-      case 4: go_256x128<AT, BT, TC>(g, s); return;
-      case 5: go_256x256<AT, BT, TC>(g, s); return;
-      case 6: go<128, 128, 2, AT, BT, TC, 8, 4>(g, s); return;   // 128x128 with 8 waves of 64x32
-      case 7: go_128x128<AT, BT, TC>(g, s); return;
-      case 8: go<128, 64, 4, AT, BT, TC, 8, 3>(g, s); return;    // 128x64 with 8 waves of 32x32
+  if (g.group_mode != 1 && g.force_tile) {           // a unit test asks for one of the shapes (dense problems)
+    switch (g.force_tile) {
+      case 1: go_128x64<AT, BT, TC>(g, s); return;
+      case 2: go_128x128<AT, BT, TC>(g, s); return;
+      case 3: go_256x128<AT, BT, TC>(g, s); return;
+      case 4: go_256x256<AT, BT, TC>(g, s); return;
     }
   }
   if (g.group_mode == 1) {
     // expert tiles.  Skipping the MFMAs of the 32-row blocks past an expert's end (waves spanning all rows, a loop
     // specialised per block count) measured no gain, and neither did a fifth LDS stage.
     if constexpr (!AT) {
-      if (g.tile_bm == 64 && !g.act_half) go_64x128<AT, BT, TC>(g, s);
-      else if (g.tile_bm == 256) go_256x128<AT, BT, TC>(g, s);
+      if (g.tile_bm == 256) go_256x128<AT, BT, TC>(g, s);
       else if (g.tile_bn == 256) go_128x256<AT, BT, TC>(g, s);
       else go_128x128<AT, BT, TC>(g, s);
     }
@@ -577,19 +562,11 @@ static void pick_tile(const GemmArgs& g, hipStream_t s) {
     // fixed cost (start-up, first load latency) and output stores, none of which overlap on a CU that holds one
     // workgroup.  The largest tile, 256x256 (2 stages), spreads the fixed cost over the most output: 12 % faster than
     // 256x128 on these kernels and 1-1.6 % of a step, even where the last tile column is half empty (N = 1408).
-    // Smaller tiles with two workgroups per CU (128x128 with 2 stages, 4 or 8 waves) are up to 7 % faster than
+    // Smaller tiles with two workgroups per CU (128x128 with 2 stages, 4 or 8 waves) were up to 7 % faster than
     // 256x128 alone but slower inside the step, next to the data-gradient chain on the main stream; a persistent
     // form of 256x128 (a workgroup walks over tiles and issues the next tile's first loads before it stores the
     // finished one) was 5 % faster alone and 3 % of a step slower.
-    static int v = -1;                 // REVFFN_WGRAD_TILE (tuning aid): 0 = 256x256, 1 = 128x128 4 waves 2 stages, 2 = 128x64 2 stages,
-                                       // 3 / 4 = 128x128 8 waves with 3 / 2 stages, 5 = 256x128
-    if (v < 0) { const char* e = getenv("REVFFN_WGRAD_TILE"); v = e ? atoi(e) : 0; }
-    if (v == 1) go<128, 128, 2, AT, BT, TC, 4, 2>(g, s);
-    else if (v == 2) go<128, 64, 2, AT, BT, TC, 4, 2>(g, s);
-    else if (v == 3) go<128, 128, 4, AT, BT, TC, 8, 3>(g, s);
-    else if (v == 4) go<128, 128, 4, AT, BT, TC, 8, 2>(g, s);
-    else if (v == 5) go_256x128<AT, BT, TC>(g, s);
-    else go_256x256<AT, BT, TC>(g, s);
+    go_256x256<AT, BT, TC>(g, s);
     return;
   }
   // the largest tile that still gives every CU work: 256x128 from two rounds of workgroups on, 128x128 down to
@@ -613,14 +590,14 @@ int launch_gemm_mfma(const GemmArgs& g, GemmTypes t, hipStream_t s) {
   if (g.b_trans && (g.N & 7)) return 1;
   if (g.a_trans && !g.b_trans) return 1;                 // layout not used by the block
   if (g.group_mode == 2 && !(g.a_trans && g.b_trans)) return 1;
-  if (g.group_mode == 1 && (g.a_trans || (g.tile_bm != 128 && g.tile_bm != 64 && g.tile_bm != 256))) return 1;
+  if (g.group_mode == 1 && (g.a_trans || (g.tile_bm != 128 && g.tile_bm != 256))) return 1;
   if (g.a_gather && g.a_trans) return 1;
   if (g.group_mode != 1 && g.M <= 0) return 1;
   if (g.split_k > 1 && (g.group_mode != 0 || !g.splitk_ws)) return 1;
   if (g.col_scale && g.split_k <= 1) return 1;           // column scale lives in the split-k reduction only
   if (g.act_half) {
     if (g.a_trans || g.b_trans || g.group_mode == 2 || g.split_k > 1 || g.bias || g.resid || g.tap || !g.act_out) return 1;
-    if (g.N != 2 * g.act_half || (g.group_mode == 1 && g.tile_bm == 64)) return 1;
+    if (g.N != 2 * g.act_half) return 1;
   }
   // every operand must span less than 2 GiB from its base (32-bit buffer offsets)
   {

@@ -161,15 +161,17 @@ __global__ void __launch_bounds__(PERM_WAVES * 64) permute_k(
   __syncthreads();
   for (int e = threadIdx.x; e <= E; e += blockDim.x) offsets[e] = off[e];
   // tile lists: expert e owns the slots after the tiles of experts 0..e-1; slots past the last tile are marked
-  // unused.  Tile heights are powers of two, so tile counts are shifts (no integer division in these loops).
+  // unused.  The number of tiles of an expert is an exact division: the fill loop below writes ceil(rows / bm) slots
+  // per expert, and a count taken any other way (a shift, for a height that is not a power of two) would leave
+  // slots of the list unwritten, with whatever the workspace held, for the GEMM to use as an expert index.
   int* tcnt = cnt + PERM_WAVES * E + E + 1;   // [E + 1]: tiles per expert, then their total
   for (int pass = 0; pass < 3; pass++) {
-    const int bm = tl.bm[pass], mx = tl.max_tiles[pass], sh = 31 - __clz(bm);
+    const int bm = tl.bm[pass], mx = tl.max_tiles[pass];
     int* tg = tl.group[pass];
     int* tm = tl.m0[pass];
     int* tf = tl.first[pass];
     __syncthreads();                        // the previous pass is done with tcnt
-    for (int e = threadIdx.x; e < E; e += blockDim.x) tcnt[e] = (off[e + 1] - off[e] + bm - 1) >> sh;
+    for (int e = threadIdx.x; e < E; e += blockDim.x) tcnt[e] = (off[e + 1] - off[e] + bm - 1) / bm;
     __syncthreads();
     if (threadIdx.x == 0) { int t = 0; for (int e = 0; e < E; e++) t += tcnt[e]; tcnt[E] = t; }
     for (int e = threadIdx.x; e < E; e += blockDim.x) {
