@@ -349,9 +349,10 @@ int run_wgrad(revffn_ctx* c, const GemmArgs& g, hipStream_t s) { return run_gemm
 // once and every output written once (index arrays and per-row scalars included, gains and tables left out)
 inline double esz(int dt) { return dt ? 2.0 : 4.0; }
 void p_rmsnorm_fwd(revffn_ctx* c, int dt, int tx, const void* x, i64 ldx, const void* g, void* out, i64 ldo, int rows,
-                   int h, float eps, hipStream_t s, const unsigned char* skip = nullptr) {
-  ProfScope ps(c, s, 0, (double)rows * h * (esz(tx) + esz(dt)));
-  launch_rmsnorm_fwd(dt, tx, x, ldx, g, out, ldo, rows, h, eps, s, skip);
+                   int h, float eps, hipStream_t s, const unsigned char* skip = nullptr, const void* x2 = nullptr,
+                   const void* g2 = nullptr, void* out2 = nullptr) {
+  ProfScope ps(c, s, 0, (x2 ? 2.0 : 1.0) * rows * h * (esz(tx) + esz(dt)));
+  launch_rmsnorm_fwd(dt, tx, x, ldx, g, out, ldo, rows, h, eps, s, skip, x2, g2, out2);
   ps.done(KID_RMSNORM_FWD);
 }
 void p_rmsnorm_bwd(revffn_ctx* c, int dt, int tx, const void* dy, i64 ldd, const void* x, i64 ldx, const void* g,
@@ -416,6 +417,13 @@ void p_colsum(revffn_ctx* c, int ta, const void* a, i64 lda, int tb, const void*
   launch_colsum(ta, a, lda, tb, b, ldb, sc, tout, out, partial, rows, cols, s);
   ps.done(KID_COLSUM);
 }
+void p_colsum_batch(revffn_ctx* c, int n, int ta, const void* const* a, const i64* lda, int tb, const void* const* b,
+                    const i64* ldb, const float* const* sc, int tout, void* const* out, int rows, int cols, hipStream_t s) {
+  if (n <= 0) return;
+  ProfScope ps(c, s, 0, (double)n * ((double)rows * cols * (esz(ta) + (b ? esz(tb) : 0.0)) + (sc ? rows * 4.0 : 0.0)));
+  launch_colsum_batch(n, ta, a, lda, tb, b, ldb, sc, tout, out, c->partial, rows, cols, s);
+  ps.done(KID_COLSUM);
+}
 void p_gather_rows(revffn_ctx* c, int dt, const void* src, const int* row_map, int div, void* dst, int rows, int cols,
                    hipStream_t s) {
   ProfScope ps(c, s, 0, 2.0 * rows * cols * esz(dt) + rows * 4.0);
@@ -426,6 +434,33 @@ void p_copy_rows(revffn_ctx* c, int dt, const void* src, i64 lds_, void* dst, i6
   ProfScope ps(c, s, 0, 2.0 * rows * cols * esz(dt));
   launch_copy_rows(dt, src, lds_, dst, ldd, rows, cols, s);
   ps.done(KID_COPY_ROWS);
+}
+
+// n <= 3 dense GEMMs of one shape, layout and strides as ONE launch of the matrix-core kernel (the 2048-wide
+// projections are one round of workgroups each: together they fill the chip for several rounds); where that kernel
+// does not take the problem they run one after the other.  tc: element type of the results.
+int run_gemm_multi(revffn_ctx* c, const GemmArgs* subs, int n, int tc, hipStream_t s) {
+  if (n <= 0) return 0;
+  if (n > 1 && c->dt == 1 && c->mode == 0) {
+    GemmArgs g = subs[0];
+    g.n_sub = n;
+    for (int z = 1; z < n; z++) {
+      g.subA[z - 1] = subs[z].A; g.subB[z - 1] = subs[z].B; g.subC[z - 1] = subs[z].C; g.subBias[z - 1] = subs[z].bias;
+    }
+    GemmTypes t{c->dt, c->dt, tc, c->dt};
+    double fl = 0, by = 0;
+    if (c->prof_on) { gemm_work(c, subs[0], c->dt, c->dt, tc, &fl, &by); fl *= n; by *= n; }
+    ProfScope ps(c, s, fl, by);
+    if (launch_gemm_mfma(g, t, s) == 0) {
+      ps.done(g.a_trans ? KID_GEMM_TN : (g.b_trans ? KID_GEMM_NN : KID_GEMM_NT));
+      return 0;
+    }
+  }
+  for (int z = 0; z < n; z++) {
+    int e = run_gemm(c, subs[z], c->dt, c->dt, tc, s);
+    if (e) return e;
+  }
+  return 0;
 }
 
 #define TRY(x) do { int _e = (x); if (_e) return _e; } while (0)
@@ -479,14 +514,12 @@ int attn_acts(revffn_ctx* c, const revffn_weights* w, const void* x1, i64 ld1, c
               bool do_kv, hipStream_t s, bool q_done = false, const unsigned char* skip = nullptr) {
   const revffn_config& f = c->cfg;
   const int T = B * S, d = f.d_model, h = d / 2, es = c->es, dt = c->dt;
-  hipStream_t s0 = side(c, s, 0), s1 = side(c, s, 1);
   if (f.symmetric) {
     // comparison block: queries from stream 2 as well.  n2, U2 keep their places in the second halves of n12, U12.
     void* n2 = at(c->n12, (size_t)T * h, es);
     void* U2s = at(c->U12, (size_t)T * d, es);
     p_rmsnorm_fwd(c, dt, c->sdt, x2, ld2, w->norm_a2, n2, h, T, h, f.rms_eps, s);
     TRY(run_gemm(c, nt(n2, h, w->pup_a, h, U2s, d, T, d, h), s));
-    after(c, s, s0); after(c, s, s1);
     GemmArgs gq = nt(U2s, d, w->wq, d, c->Q, d, T, d, d);
     gq.bias = w->bq;
     TRY(run_gemm(c, gq, s));
@@ -496,32 +529,43 @@ int attn_acts(revffn_ctx* c, const revffn_weights* w, const void* x1, i64 ld1, c
     if (do_kv) {
       p_rmsnorm_fwd(c, dt, c->sdt, x2, ld2, w->norm_a2, at(c->n12, (size_t)T * h, es), h, T, h, f.rms_eps, s);
       TRY(run_gemm(c, nt(at(c->n12, (size_t)T * h, es), h, w->pup_a, h, at(c->U12, (size_t)T * d, es), d, T, d, h), s));
-      after(c, s, s0); after(c, s, s1);
     }
   } else if (!do_kv) {
     TRY(attn_q(c, w, x1, ld1, B, S, s, skip));          // a later iterate of the inverse: query side only
   } else {
-    p_rmsnorm_fwd(c, dt, c->sdt, x1, ld1, w->norm_a1, c->n12, h, T, h, f.rms_eps, s);
-    if (do_kv) p_rmsnorm_fwd(c, dt, c->sdt, x2, ld2, w->norm_a2, at(c->n12, (size_t)T * h, es), h, T, h, f.rms_eps, s);
+    // both streams in one launch (the two streams of a call share their row stride)
+    if (do_kv && ld1 == ld2)
+      p_rmsnorm_fwd(c, dt, c->sdt, x1, ld1, w->norm_a1, c->n12, h, T, h, f.rms_eps, s, nullptr, x2, w->norm_a2,
+                    at(c->n12, (size_t)T * h, es));
+    else {
+      p_rmsnorm_fwd(c, dt, c->sdt, x1, ld1, w->norm_a1, c->n12, h, T, h, f.rms_eps, s);
+      if (do_kv) p_rmsnorm_fwd(c, dt, c->sdt, x2, ld2, w->norm_a2, at(c->n12, (size_t)T * h, es), h, T, h, f.rms_eps, s);
+    }
     // the same P_up serves both streams: one GEMM over the stacked rows
     TRY(run_gemm(c, nt(c->n12, h, w->pup_a, h, c->U12, d, do_kv ? 2 * T : T, d, h), s));
-    if (do_kv) { after(c, s, s0); after(c, s, s1); }
-    GemmArgs gq = nt(c->U12, d, w->wq, d, c->Q, d, T, d, d);
-    gq.bias = w->bq;
-    TRY(run_gemm(c, gq, s));
-    if (f.use_rope) p_rope(c, dt, c->Q, c->rope_cs, T, S, f.n_heads, f.head_dim, 1.f, s);
+    if (do_kv) {
+      // Q, K and V projections as one launch (three problems of one shape), then one rotary launch for Q and K
+      const void* U2 = at(c->U12, (size_t)T * d, es);
+      GemmArgs q3[3] = {nt(c->U12, d, w->wq, d, c->Q, d, T, d, d), nt(U2, d, w->wk, d, c->K, d, T, d, d),
+                        nt(U2, d, w->wv, d, c->V, d, T, d, d)};
+      q3[0].bias = w->bq; q3[1].bias = w->bk; q3[2].bias = w->bv;
+      TRY(run_gemm_multi(c, q3, 3, dt, s));
+      if (f.use_rope) p_rope(c, dt, c->Q, c->rope_cs, T, S, f.n_heads, f.head_dim, 1.f, s, c->K);
+      do_kv = false;                                   // done here
+    } else {
+      GemmArgs gq = nt(c->U12, d, w->wq, d, c->Q, d, T, d, d);
+      gq.bias = w->bq;
+      TRY(run_gemm(c, gq, s));
+      if (f.use_rope) p_rope(c, dt, c->Q, c->rope_cs, T, S, f.n_heads, f.head_dim, 1.f, s);
+    }
   }
   if (do_kv) {
+    // (the query side was enqueued earlier, or comes from stream 2 in the symmetric block): K and V as one launch
     const void* U2 = at(c->U12, (size_t)T * d, es);
-    GemmArgs gk = nt(U2, d, w->wk, d, c->K, d, T, d, d);
-    gk.bias = w->bk;
-    TRY(run_gemm(c, gk, s0));
-    if (f.use_rope) p_rope(c, dt, c->K, c->rope_cs, T, S, f.n_heads, f.head_dim, 1.f, s0);
-    GemmArgs gv = nt(U2, d, w->wv, d, c->V, d, T, d, d);
-    gv.bias = w->bv;
-    TRY(run_gemm(c, gv, s1));
-    after(c, s0, s);
-    after(c, s1, s);
+    GemmArgs kv[2] = {nt(U2, d, w->wk, d, c->K, d, T, d, d), nt(U2, d, w->wv, d, c->V, d, T, d, d)};
+    kv[0].bias = w->bk; kv[1].bias = w->bv;
+    TRY(run_gemm_multi(c, kv, 2, dt, s));
+    if (f.use_rope) p_rope(c, dt, c->K, c->rope_cs, T, S, f.n_heads, f.head_dim, 1.f, s);
   }
   {
     // algorithmic work of the attention core: QK^T and PV, halved by the causal mask
@@ -558,8 +602,11 @@ void router_fold(revffn_ctx* c, const revffn_weights* w, hipStream_t s) {
   hipStream_t sr = side(c, s, 2);
   after(c, s, sr);                        // everything that read wr_ext / wrp before is on s
   // [W_r ; w_shared_gate] stacked into one [E1, d] matrix so that the fold is a single GEMM
-  p_copy_rows(c, dt, w->w_router, d, c->wr_ext, d, E, d, sr);
-  if (Is) p_copy_rows(c, dt, w->ws_gate, d, at(c->wr_ext, (size_t)E * d, c->es), d, 1, d, sr);
+  {
+    ProfScope ps(c, sr, 0, 2.0 * (E + (Is ? 1 : 0)) * d * esz(dt));
+    launch_copy_rows2(dt, w->w_router, d, E, Is ? w->ws_gate : w->w_router, d, Is ? 1 : 0, c->wr_ext, d, d, sr);
+    ps.done(KID_COPY_ROWS);
+  }
   GemmArgs a = nn(c->wr_ext, d, w->pup_m, h, c->wrp, h, E + (Is ? 1 : 0), h, d);
   a.split_k = SPLIT_FOLD; a.splitk_ws = c->splitk_ws_r; a.col_scale = w->norm_m;
   (void)run_gemm(c, a, dt, dt, 0, sr);
@@ -856,12 +903,23 @@ int backward_impl(revffn_ctx* c, const revffn_weights* w, const void* x1, const 
     TRY(run_gemm(c, nn(c->dQ, d, w->wq, d, dU1, d, T, d, d), s0));
     du1_done = mark(c, s0);
   }
-  if (GF(wq)) TRY(run_wgrad(c, tn(c->dQ, d, sym ? U2 : U1, d, GF(wq), d, d, d, T), s0));
-  if (GF(wk)) TRY(run_wgrad(c, tn(c->dK, d, U2, d, GF(wk), d, d, d, T), s0));
-  if (GF(wv)) TRY(run_wgrad(c, tn(c->dV, d, U2, d, GF(wv), d, d, d, T), s0));
-  if (GF(bq) && w->bq) p_colsum(c, dt, c->dQ, d, dt, nullptr, 0, nullptr, c->gdt, GF(bq), c->partial, T, d, sc);
-  if (GF(bk) && w->bk) p_colsum(c, dt, c->dK, d, dt, nullptr, 0, nullptr, c->gdt, GF(bk), c->partial, T, d, sc);
-  if (GF(bv) && w->bv) p_colsum(c, dt, c->dV, d, dt, nullptr, 0, nullptr, c->gdt, GF(bv), c->partial, T, d, sc);
+  {
+    // the projection weight gradients asked for, as one launch (problems of one shape)
+    GemmArgs wg[3];
+    int nw = 0;
+    if (GF(wq)) wg[nw++] = tn(c->dQ, d, sym ? U2 : U1, d, GF(wq), d, d, d, T);
+    if (GF(wk)) wg[nw++] = tn(c->dK, d, U2, d, GF(wk), d, d, d, T);
+    if (GF(wv)) wg[nw++] = tn(c->dV, d, U2, d, GF(wv), d, d, d, T);
+    TRY(run_gemm_multi(c, wg, nw, c->gdt, s0));
+  }
+  {
+    // the three bias gradients (column sums of dQ, dK, dV) in one launch pair
+    const void* ba[3]; void* bo[3]; i64 bl[3]; int nb = 0;
+    if (GF(bq) && w->bq) { ba[nb] = c->dQ; bo[nb] = GF(bq); bl[nb++] = d; }
+    if (GF(bk) && w->bk) { ba[nb] = c->dK; bo[nb] = GF(bk); bl[nb++] = d; }
+    if (GF(bv) && w->bv) { ba[nb] = c->dV; bo[nb] = GF(bv); bl[nb++] = d; }
+    p_colsum_batch(c, nb, dt, ba, bl, dt, nullptr, nullptr, nullptr, c->gdt, bo, T, d, sc);
+  }
   TRY(run_gemm(c, nn(c->dK, d, w->wk, d, dU2, d, T, d, d), s));
   {
     GemmArgs a = nn(c->dV, d, w->wv, d, dU2, d, T, d, d);        // dU2 += dV . Wv
@@ -895,9 +953,13 @@ int backward_impl(revffn_ctx* c, const revffn_weights* w, const void* x1, const 
   p_rmsnorm_bwd(c, dt, c->sdt, at(c->dn12, (size_t)T * h, es), h, x2, ld, w->norm_a2, dy2, ld, dx2, ld, c->rinv + T, T, h,
                      f.rms_eps, s);
   after(c, s, sc);
-  if (GF(norm_a1)) p_colsum(c, c->sdt, x1, ld, dt, c->dn12, h, c->rinv, c->gdt, GF(norm_a1), c->partial, T, h, sc);
-  if (GF(norm_a2))
-    p_colsum(c, c->sdt, x2, ld, dt, at(c->dn12, (size_t)T * h, es), h, c->rinv + T, c->gdt, GF(norm_a2), c->partial, T, h, sc);
+  {
+    // the two gain gradients (sum over tokens of x * dn / rms) in one launch pair
+    const void* ga[2]; const void* gb[2]; const float* gs[2]; void* go[2]; i64 gla[2], glb[2]; int ng = 0;
+    if (GF(norm_a1)) { ga[ng] = x1; gb[ng] = c->dn12; gs[ng] = c->rinv; go[ng] = GF(norm_a1); gla[ng] = ld; glb[ng++] = h; }
+    if (GF(norm_a2)) { ga[ng] = x2; gb[ng] = at(c->dn12, (size_t)T * h, es); gs[ng] = c->rinv + T; go[ng] = GF(norm_a2); gla[ng] = ld; glb[ng++] = h; }
+    p_colsum_batch(c, ng, c->sdt, ga, gla, dt, gb, glb, gs, c->gdt, go, T, h, sc);
+  }
   after(c, sw, s);                       // every weight gradient is complete for the caller's stream
   after(c, s0, s);
   after(c, sc, s);

@@ -12,13 +12,16 @@
 // ---------------------------------------------------------------------------------
 // RMSNorm forward: one wave per token row.
 // ---------------------------------------------------------------------------------
+// (blockIdx.y == 1: the second problem of the launch, same shape: x2, g2, out2)
 template <class T, class TX>
 __global__ void __launch_bounds__(256) rmsnorm_fwd_k(const TX* __restrict__ x, i64 ldx, const T* __restrict__ g,
                                                      T* __restrict__ out, i64 ldo, int rows, int h, float eps,
-                                                     const unsigned char* __restrict__ row_skip) {
+                                                     const unsigned char* __restrict__ row_skip,
+                                                     const TX* __restrict__ x2, const T* __restrict__ g2, T* __restrict__ out2) {
   int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   int lane = threadIdx.x & 63;
   if (row >= rows || (row_skip && row_skip[row])) return;
+  if (blockIdx.y) { x = x2; g = g2; out = out2; }
   const TX* xr = x + (i64)row * ldx;
   float ss = 0.f;
   for (int j = lane; j < h; j += 64) { float v = to_f(xr[j]); ss += v * v; }
@@ -52,9 +55,12 @@ __device__ __forceinline__ f32x8 load8(const float* p) {
 template <class TX>
 __global__ void __launch_bounds__(256) rmsnorm_fwd_v8_k(const TX* __restrict__ x, i64 ldx, const bf16* __restrict__ g,
                                                         bf16* __restrict__ out, i64 ldo, int rows, int h, float eps,
-                                                        const unsigned char* __restrict__ row_skip) {
+                                                        const unsigned char* __restrict__ row_skip,
+                                                        const TX* __restrict__ x2, const bf16* __restrict__ g2,
+                                                        bf16* __restrict__ out2) {
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
   if (row >= rows || (row_skip && row_skip[row])) return;
+  if (blockIdx.y) { x = x2; g = g2; out = out2; }
   const TX* xr = x + (i64)row * ldx;
   float ss = 0.f;
   for (int j = lane * 8; j < h; j += 512) {
@@ -76,25 +82,26 @@ __global__ void __launch_bounds__(256) rmsnorm_fwd_v8_k(const TX* __restrict__ x
 }
 
 void launch_rmsnorm_fwd(int dt, int tx, const void* x, i64 ldx, const void* g, void* out, i64 ldo, int rows, int h,
-                        float eps, hipStream_t s, const unsigned char* row_skip) {
+                        float eps, hipStream_t s, const unsigned char* row_skip, const void* x2, const void* g2,
+                        void* out2) {
   if (rows <= 0) return;
-  const dim3 grid(cdiv(rows, 4)), block(256);
-  if (rows_vec8(dt, h, {x, g, out}, {ldx, ldo})) {
+  const dim3 grid(cdiv(rows, 4), x2 ? 2 : 1), block(256);
+  if (rows_vec8(dt, h, {x, g, out, x2, g2, out2}, {ldx, ldo})) {
     if (tx == 0)
       hipLaunchKernelGGL(rmsnorm_fwd_v8_k<float>, grid, block, 0, s, (const float*)x, ldx, (const bf16*)g, (bf16*)out,
-                         ldo, rows, h, eps, row_skip);
+                         ldo, rows, h, eps, row_skip, (const float*)x2, (const bf16*)g2, (bf16*)out2);
     else
       hipLaunchKernelGGL(rmsnorm_fwd_v8_k<bf16>, grid, block, 0, s, (const bf16*)x, ldx, (const bf16*)g, (bf16*)out,
-                         ldo, rows, h, eps, row_skip);
+                         ldo, rows, h, eps, row_skip, (const bf16*)x2, (const bf16*)g2, (bf16*)out2);
     return;
   }
   if (dt == 1 && tx == 0) {
     hipLaunchKernelGGL((rmsnorm_fwd_k<bf16, float>), grid, block, 0, s, (const float*)x, ldx, (const bf16*)g,
-                       (bf16*)out, ldo, rows, h, eps, row_skip);
+                       (bf16*)out, ldo, rows, h, eps, row_skip, (const float*)x2, (const bf16*)g2, (bf16*)out2);
     return;
   }
   DISPATCH_DT(dt, hipLaunchKernelGGL((rmsnorm_fwd_k<T, T>), grid, block, 0, s, (const T*)x, ldx, (const T*)g, (T*)out,
-                                     ldo, rows, h, eps, row_skip));
+                                     ldo, rows, h, eps, row_skip, (const T*)x2, (const T*)g2, (T*)out2));
 }
 
 // RMSNorm backward for the input:  dx = r*(g.dy) - x*r^3*mean_j(x_j g_j dy_j), plus an
@@ -195,40 +202,55 @@ void launch_rmsnorm_bwd(int dt, int tx, const void* dy, i64 ldd, const void* x, 
 // ---------------------------------------------------------------------------------
 #define COLSUM_CHUNKS 32
 static int colsum_chunk_rows(int rows) { int c = cdiv(rows > 0 ? rows : 1, COLSUM_CHUNKS); return c < 32 ? 32 : c; }
-size_t colsum_partial_floats(int rows, int cols) { return (size_t)(COLSUM_CHUNKS + 1) * cols; }
+size_t colsum_partial_floats(int rows, int cols) { return (size_t)COLSUM_BATCH * (COLSUM_CHUNKS + 1) * cols; }
 
+// Up to COLSUM_BATCH problems of one shape and type go into one launch pair (blockIdx.z = problem).
+struct ColsumBatch {
+  const void* a[COLSUM_BATCH]; const void* b[COLSUM_BATCH]; const float* sc[COLSUM_BATCH]; void* out[COLSUM_BATCH];
+  i64 lda[COLSUM_BATCH], ldb[COLSUM_BATCH];
+};
 template <class TA, class TB>
-__global__ void __launch_bounds__(256) colsum1_k(const TA* __restrict__ a, i64 lda, const TB* __restrict__ b,
-                                                 i64 ldb, const float* __restrict__ sc,
-                                                 float* __restrict__ partial, int rows, int cols, int chunk) {
+__global__ void __launch_bounds__(256) colsum1_k(ColsumBatch q, float* __restrict__ partial_all, int rows, int cols,
+                                                 int chunk, int chunks) {
   __shared__ float red[4][64];
+  const int z = blockIdx.z;
+  const TA* __restrict__ a = (const TA*)q.a[z];
+  const TB* __restrict__ b = (const TB*)q.b[z];
+  const float* __restrict__ sc = q.sc[z];
+  const i64 lda = q.lda[z], ldb = q.ldb[z];
+  float* partial = partial_all + (i64)z * chunks * cols;
   int c = blockIdx.x * 64 + (threadIdx.x & 63);
-  int q = threadIdx.x >> 6;
+  int qd = threadIdx.x >> 6;
   int r0 = blockIdx.y * chunk;
   int r1 = min(rows, r0 + chunk);
   float acc = 0.f;
   if (c < cols) {
-    for (int t = r0 + q; t < r1; t += 4) {
+    for (int t = r0 + qd; t < r1; t += 4) {
       float v = to_f(a[(i64)t * lda + c]);
       if (b) v *= to_f(b[(i64)t * ldb + c]);
       if (sc) v *= sc[t];
       acc += v;
     }
   }
-  red[q][threadIdx.x & 63] = acc;
+  red[qd][threadIdx.x & 63] = acc;
   __syncthreads();
-  if (q == 0 && c < cols) {
+  if (qd == 0 && c < cols) {
     float v = (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
     partial[(i64)blockIdx.y * cols + c] = v;
   }
 }
 // bf16 operands with 8 | cols at 16-byte aligned addresses: a thread owns 8 adjacent columns (16-byte loads) and every
 // 8th row of the chunk; the 8 row lanes are added in lane order.  Same two-stage, fixed-order scheme.
-__global__ void __launch_bounds__(256) colsum1_v8_k(const bf16* __restrict__ a, i64 lda, const bf16* __restrict__ b,
-                                                    i64 ldb, const float* __restrict__ sc,
-                                                    float* __restrict__ partial, int rows, int cols, int chunk) {
+__global__ void __launch_bounds__(256) colsum1_v8_k(ColsumBatch q, float* __restrict__ partial_all, int rows, int cols,
+                                                    int chunk, int chunks) {
   __shared__ float red[8][256];
-  const int cg = threadIdx.x & 31, q = threadIdx.x >> 5;
+  const int z = blockIdx.z;
+  const bf16* __restrict__ a = (const bf16*)q.a[z];
+  const bf16* __restrict__ b = (const bf16*)q.b[z];
+  const float* __restrict__ sc = q.sc[z];
+  const i64 lda = q.lda[z], ldb = q.ldb[z];
+  float* partial = partial_all + (i64)z * chunks * cols;
+  const int cg = threadIdx.x & 31, qd = threadIdx.x >> 5;
   const int c = blockIdx.x * 256 + cg * 8;
   const int r0 = blockIdx.y * chunk, r1 = min(rows, r0 + chunk);
   float acc[8];
@@ -236,7 +258,7 @@ __global__ void __launch_bounds__(256) colsum1_v8_k(const bf16* __restrict__ a, 
   for (int i = 0; i < 8; i++) acc[i] = 0.f;
   if (c < cols) {
 #pragma unroll 4
-    for (int t = r0 + q; t < r1; t += 8) {
+    for (int t = r0 + qd; t < r1; t += 8) {
       const bf16x8_v av = *(const bf16x8_v*)(a + (i64)t * lda + c);
       const float w = sc ? sc[t] : 1.f;
       if (b) {
@@ -250,7 +272,7 @@ __global__ void __launch_bounds__(256) colsum1_v8_k(const bf16* __restrict__ a, 
     }
   }
 #pragma unroll
-  for (int i = 0; i < 8; i++) red[q][cg * 8 + i] = acc[i];
+  for (int i = 0; i < 8; i++) red[qd][cg * 8 + i] = acc[i];
   __syncthreads();
   const int cc = blockIdx.x * 256 + threadIdx.x;
   if (cc < cols) {
@@ -261,41 +283,52 @@ __global__ void __launch_bounds__(256) colsum1_v8_k(const bf16* __restrict__ a, 
   }
 }
 template <class TO>
-__global__ void colsum2_k(const float* __restrict__ partial, TO* __restrict__ out, int chunks, int cols) {
+__global__ void colsum2_k(const float* __restrict__ partial_all, ColsumBatch q, int chunks, int cols) {
   int c = blockIdx.x * blockDim.x + threadIdx.x;
   if (c >= cols) return;
+  const float* partial = partial_all + (i64)blockIdx.z * chunks * cols;
   float acc = 0.f;
   for (int i = 0; i < chunks; i++) acc += partial[(i64)i * cols + c];
-  out[c] = from_f<TO>(acc);
+  ((TO*)q.out[blockIdx.z])[c] = from_f<TO>(acc);
 }
 
 template <class TA, class TB>
-static void colsum_go(const void* a, i64 lda, const void* b, i64 ldb, const float* sc, int tout, void* out,
-                      float* partial, int rows, int cols, hipStream_t s) {
+static void colsum_go(const ColsumBatch& q, int n, int tout, float* partial, int rows, int cols, hipStream_t s) {
   int chunk = colsum_chunk_rows(rows);
   int chunks = cdiv(rows > 0 ? rows : 1, chunk);
   constexpr bool both_bf16 = sizeof(TA) == 2 && sizeof(TB) == 2;
-  if (both_bf16 && (cols & 7) == 0 && (lda & 7) == 0 && (!b || (ldb & 7) == 0) && ((uintptr_t)a & 15) == 0 &&
-      ((uintptr_t)b & 15) == 0) {
-    hipLaunchKernelGGL(colsum1_v8_k, dim3(cdiv(cols, 256), chunks), dim3(256), 0, s, (const bf16*)a, lda, (const bf16*)b,
-                       ldb, sc, partial, rows, cols, chunk);
+  bool v8 = both_bf16 && (cols & 7) == 0;
+  for (int z = 0; z < n; z++)
+    v8 = v8 && (q.lda[z] & 7) == 0 && (!q.b[z] || (q.ldb[z] & 7) == 0) && ((uintptr_t)q.a[z] & 15) == 0 && ((uintptr_t)q.b[z] & 15) == 0;
+  if (v8) {
+    hipLaunchKernelGGL(colsum1_v8_k, dim3(cdiv(cols, 256), chunks, n), dim3(256), 0, s, q, partial, rows, cols, chunk, chunks);
   } else {
-    hipLaunchKernelGGL((colsum1_k<TA, TB>), dim3(cdiv(cols, 64), chunks), dim3(256), 0, s, (const TA*)a, lda,
-                       (const TB*)b, ldb, sc, partial, rows, cols, chunk);
+    hipLaunchKernelGGL((colsum1_k<TA, TB>), dim3(cdiv(cols, 64), chunks, n), dim3(256), 0, s, q, partial, rows, cols, chunk, chunks);
   }
   if (tout == 0)
-    hipLaunchKernelGGL(colsum2_k<float>, dim3(cdiv(cols, 256)), dim3(256), 0, s, partial, (float*)out, chunks, cols);
+    hipLaunchKernelGGL(colsum2_k<float>, dim3(cdiv(cols, 256), 1, n), dim3(256), 0, s, partial, q, chunks, cols);
   else
-    hipLaunchKernelGGL(colsum2_k<bf16>, dim3(cdiv(cols, 256)), dim3(256), 0, s, partial, (bf16*)out, chunks, cols);
+    hipLaunchKernelGGL(colsum2_k<bf16>, dim3(cdiv(cols, 256), 1, n), dim3(256), 0, s, partial, q, chunks, cols);
 }
 
+void launch_colsum_batch(int n, int ta, const void* const* a, const i64* lda, int tb, const void* const* b, const i64* ldb,
+                         const float* const* sc, int tout, void* const* out, float* partial, int rows, int cols,
+                         hipStream_t s) {
+  if (cols <= 0 || n <= 0 || n > COLSUM_BATCH) return;
+  ColsumBatch q;
+  for (int z = 0; z < COLSUM_BATCH; z++) {
+    const int y = z < n ? z : 0;
+    q.a[z] = a[y]; q.b[z] = b ? b[y] : nullptr; q.sc[z] = sc ? sc[y] : nullptr; q.out[z] = out[y];
+    q.lda[z] = lda[y]; q.ldb[z] = ldb ? ldb[y] : 0;
+  }
+  if (ta == 0 && tb == 0) colsum_go<float, float>(q, n, tout, partial, rows, cols, s);
+  else if (ta == 0 && tb == 1) colsum_go<float, bf16>(q, n, tout, partial, rows, cols, s);
+  else if (ta == 1 && tb == 0) colsum_go<bf16, float>(q, n, tout, partial, rows, cols, s);
+  else colsum_go<bf16, bf16>(q, n, tout, partial, rows, cols, s);
+}
 void launch_colsum(int ta, const void* a, i64 lda, int tb, const void* b, i64 ldb, const float* sc, int tout,
                    void* out, float* partial, int rows, int cols, hipStream_t s) {
-  if (cols <= 0) return;
-  if (ta == 0 && tb == 0) colsum_go<float, float>(a, lda, b, ldb, sc, tout, out, partial, rows, cols, s);
-  else if (ta == 0 && tb == 1) colsum_go<float, bf16>(a, lda, b, ldb, sc, tout, out, partial, rows, cols, s);
-  else if (ta == 1 && tb == 0) colsum_go<bf16, float>(a, lda, b, ldb, sc, tout, out, partial, rows, cols, s);
-  else colsum_go<bf16, bf16>(a, lda, b, ldb, sc, tout, out, partial, rows, cols, s);
+  launch_colsum_batch(1, ta, &a, &lda, tb, &b, &ldb, &sc, tout, &out, partial, rows, cols, s);
 }
 
 // ---------------------------------------------------------------------------------
@@ -477,6 +510,25 @@ void launch_copy_rows(int dt, const void* src, i64 lds_, void* dst, i64 ldd, int
   if (total <= 0) return;
   DISPATCH_DT(dt, hipLaunchKernelGGL(copy_rows_k<T>, dim3(cdiv(total, 256)), dim3(256), 0, s, (const T*)src, lds_,
                                      (T*)dst, ldd, rows, cols));
+}
+
+// dst rows [0, rows_a) = src_a rows, dst rows [rows_a, rows_a + rows_b) = src_b rows (the stacked router matrix)
+template <class T>
+__global__ void __launch_bounds__(256) copy_rows2_k(const T* __restrict__ src_a, i64 lds_a, int rows_a,
+                                                    const T* __restrict__ src_b, i64 lds_b, int rows_b,
+                                                    T* __restrict__ dst, i64 ldd, int cols) {
+  i64 e = (i64)blockIdx.x * 256 + threadIdx.x;
+  if (e >= (i64)(rows_a + rows_b) * cols) return;
+  i64 r = e / cols;
+  int c = (int)(e % cols);
+  dst[r * ldd + c] = r < rows_a ? src_a[r * lds_a + c] : src_b[(r - rows_a) * lds_b + c];
+}
+void launch_copy_rows2(int dt, const void* src_a, i64 lds_a, int rows_a, const void* src_b, i64 lds_b, int rows_b,
+                       void* dst, i64 ldd, int cols, hipStream_t s) {
+  i64 total = (i64)(rows_a + rows_b) * cols;
+  if (total <= 0) return;
+  DISPATCH_DT(dt, hipLaunchKernelGGL(copy_rows2_k<T>, dim3(cdiv(total, 256)), dim3(256), 0, s, (const T*)src_a, lds_a,
+                                     rows_a, (const T*)src_b, lds_b, rows_b, (T*)dst, ldd, cols));
 }
 
 template <class T>

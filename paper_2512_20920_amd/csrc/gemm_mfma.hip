@@ -46,8 +46,11 @@ __device__ __forceinline__ void load_lds_b128(u32x4 desc, unsigned lds_addr, uns
 template <int N> __device__ __forceinline__ void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory"); }
 
 __device__ __forceinline__ u32x4 make_desc(const void* p) {
+  // (operand bases are the same for every lane; saying so keeps the descriptor in scalar registers whatever the
+  // compiler can prove about how the base was picked)
   const unsigned long long a = (unsigned long long)p;
-  u32x4 d = {(unsigned)a, (unsigned)(a >> 32), BUF_RECORDS, 0x00020000u};
+  u32x4 d = {(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)a),
+             (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(a >> 32)), BUF_RECORDS, 0x00020000u};
   return d;
 }
 
@@ -132,8 +135,8 @@ __device__ __forceinline__ void pair_rows(bool odd, float x0, float x1, float* l
 
 // One output tile; TE = 32-row blocks per wave.
 template <int BM, int BN, int WGM, bool AT, bool BT, class TC, int NW, int NS, int TE>
-__device__ __forceinline__ void gemm_tile(const GemmArgs& g, const bf16* A, const bf16* Bm, TC* C, int bx, int bz,
-                                          int m0, int m_end, int k0, int k_end) {
+__device__ __forceinline__ void gemm_tile(const GemmArgs& g, const bf16* A, const bf16* Bm, TC* C, const void* bias_ptr,
+                                          int bx, int bz, int m0, int m_end, int k0, int k_end) {
   constexpr int WGN = NW / WGM;                      // waves along n
   constexpr int WM = BM / WGM, WN = BN / WGN, TN = WN / 32;
   constexpr int STAGE = (BM + BN) * 128;             // bytes of one LDS stage: A tile, then B tile
@@ -299,7 +302,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const bf16* A, cons
     }
     return;
   }
-  const bf16* bias = (const bf16*)g.bias;
+  const bf16* bias = (const bf16*)bias_ptr;
   const bf16* resid = (const bf16*)g.resid;
   if (!bias && !g.tap && !resid) {
     // plain store (all weight gradients, most projections): no per-element epilogue work
@@ -444,6 +447,7 @@ __global__ void __launch_bounds__(NW * 64) gemm_mfma_k(GemmArgs g) {
   const bf16* A = (const bf16*)g.A;
   const bf16* Bm = (const bf16*)g.B;
   TC* C = (TC*)g.C;
+  const void* bias = g.bias;
   // ---- which tile this workgroup computes (plain 2-D grid, or the XCD-aware placement of a 1-D grid)
   int bx = blockIdx.x, by = blockIdx.y, bz = blockIdx.z;
   if (g.xcd_m != 0 && !place_tile(g.group_mode, g.xcd_m, g.tiles_m, g.tiles_n, g.n_groups,
@@ -469,6 +473,10 @@ __global__ void __launch_bounds__(NW * 64) gemm_mfma_k(GemmArgs g) {
       int per = ((g.K + BK - 1) / BK + g.split_k - 1) / g.split_k * BK;
       k0 = min(g.K, bz * per);
       k_end = min(g.K, k0 + per);
+    } else if (g.n_sub > 1 && bz > 0) {              // one of several problems of one shape launched together
+      // (constant indices: the argument block stays in scalar registers)
+      if (bz == 1) { A = (const bf16*)g.subA[0]; Bm = (const bf16*)g.subB[0]; C = (TC*)g.subC[0]; bias = g.subBias[0]; }
+      else { A = (const bf16*)g.subA[1]; Bm = (const bf16*)g.subB[1]; C = (TC*)g.subC[1]; bias = g.subBias[1]; }
     }
   }
   if (g.row_skip && g.group_mode == 0) {             // nothing to do if every row of the tile is marked as finished
@@ -478,7 +486,7 @@ __global__ void __launch_bounds__(NW * 64) gemm_mfma_k(GemmArgs g) {
     for (int r = m0 + (int)(threadIdx.x & 63); r < min(m_end, m0 + BM); r += 64) live |= g.row_skip[r] == 0;
     if (!__any(live)) return;
   }
-  gemm_tile<BM, BN, WGM, AT, BT, TC, NW, NS, TM>(g, A, Bm, C, bx, bz, m0, m_end, k0, k_end);
+  gemm_tile<BM, BN, WGM, AT, BT, TC, NW, NS, TM>(g, A, Bm, C, bias, bx, bz, m0, m_end, k0, k_end);
 }
 
 // REVFFN_XCD (tuning aid): 0 = plain 2-D grids, tiles land on the XCDs round-robin
@@ -494,7 +502,7 @@ static void go(const GemmArgs& g0, hipStream_t s) {
   { static int off = -1; if (off < 0) { const char* e = getenv("REVFFN_NO_PACKED_STORES"); off = e ? atoi(e) : 0; } g.no_packed_stores = off; }
   g.tiles_n = g.act_half ? cdiv(g.act_half, BN / 2) : cdiv(g.N, BN);
   g.tiles_m = g.group_mode == 1 ? g.max_tiles : cdiv(g.M, BM);
-  const int zdim = g.group_mode == 2 ? g.n_groups : (g.group_mode == 0 && g.split_k > 1 ? g.split_k : 1);
+  const int zdim = g.group_mode == 2 ? g.n_groups : (g.group_mode == 0 && g.split_k > 1 ? g.split_k : (g.group_mode == 0 ? g.n_sub : 1));
   if (g.tiles_n <= 0 || g.tiles_m <= 0 || zdim <= 0) return;
   dim3 grid(g.tiles_n, g.tiles_m, zdim);
   g.xcd_m = 0;
@@ -572,7 +580,7 @@ static void pick_tile(const GemmArgs& g, hipStream_t s) {
   // the largest tile that still gives every CU work: 256x128 from two rounds of workgroups on, 128x128 down to
   // ~200 tiles, else 128x64
   const i64 t256 = (i64)cdiv(g.M, 256) * cdiv(g.N, 128), t128 = (i64)cdiv(g.M, 128) * cdiv(g.N, 128);
-  const int z = g.split_k > 1 ? g.split_k : 1;
+  const int z = g.split_k > 1 ? g.split_k : g.n_sub;
   if (t256 * z >= 512) go_256x128<AT, BT, TC>(g, s);
   else if ((t128 * z >= 200) || g.N < 128) go_128x128<AT, BT, TC>(g, s);
   else go_128x64<AT, BT, TC>(g, s);
@@ -594,6 +602,9 @@ int launch_gemm_mfma(const GemmArgs& g, GemmTypes t, hipStream_t s) {
   if (g.a_gather && g.a_trans) return 1;
   if (g.group_mode != 1 && g.M <= 0) return 1;
   if (g.split_k > 1 && (g.group_mode != 0 || !g.splitk_ws)) return 1;
+  if (g.n_sub < 1 || g.n_sub > 3 || (g.n_sub > 1 && (g.group_mode != 0 || g.split_k > 1 || g.resid || g.tap || g.act_half))) return 1;
+  for (int z = 1; z < g.n_sub; z++)
+    if (!g.subA[z - 1] || !g.subB[z - 1] || !g.subC[z - 1] || !aligned16(g.subA[z - 1]) || !aligned16(g.subB[z - 1])) return 1;
   if (g.col_scale && g.split_k <= 1) return 1;           // column scale lives in the split-k reduction only
   if (g.act_half) {
     if (g.a_trans || g.b_trans || g.group_mode == 2 || g.split_k > 1 || g.bias || g.resid || g.tap || !g.act_out) return 1;

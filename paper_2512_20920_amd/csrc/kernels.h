@@ -46,6 +46,11 @@ struct GemmArgs {
   // group_mode 1: number of m-tiles of the list actually in use (device scalar written by the permutation kernel)
   const int* tile_count = nullptr;
   const int* tile_first = nullptr;       // per tile: (first tile of its expert) << 16 | tiles of that expert
+  // MFMA kernel, dense problems without split-k: n_sub > 1 launches that many problems of one shape, layout and
+  // strides together (grid z = problem); problem z >= 1 takes its operands, result and bias from sub*[z-1]
+  int n_sub = 1;
+  const void* subA[2] = {nullptr, nullptr}; const void* subB[2] = {nullptr, nullptr};
+  void* subC[2] = {nullptr, nullptr}; const void* subBias[2] = {nullptr, nullptr};
   // dense problems: row_skip[m] != 0 marks an output row that is not wanted (a finished part of the fixed-point
   // iteration of the inverse); a workgroup whose rows are all marked exits at once, the others compute every row
   const unsigned char* row_skip = nullptr;
@@ -124,15 +129,22 @@ int launch_gemm_mfma(const GemmArgs& g, GemmTypes t, hipStream_t s);
 // ---- normalisation / element-wise ------------------------------------------------
 // tx: element type of x (0 float32, 1 bf16); gains, outputs and gradients have type dt
 // row_skip (may be null): rows marked there are left alone (see GemmArgs::row_skip)
+// x2 != null: a second problem of the same shape and strides (x2, g2 -> out2) in the same launch
 void launch_rmsnorm_fwd(int dt, int tx, const void* x, i64 ldx, const void* g, void* out, i64 ldo,
-                        int rows, int h, float eps, hipStream_t s, const unsigned char* row_skip = nullptr);
+                        int rows, int h, float eps, hipStream_t s, const unsigned char* row_skip = nullptr,
+                        const void* x2 = nullptr, const void* g2 = nullptr, void* out2 = nullptr);
 // dx = base + rmsnorm_bwd(dy; x, g);  rinv[rows] receives 1/rms per row (for the gain gradient)
 void launch_rmsnorm_bwd(int dt, int tx, const void* dy, i64 ldd, const void* x, i64 ldx, const void* g,
                         const void* base, i64 ldb, void* dx, i64 ldo, float* rinv,
                         int rows, int h, float eps, hipStream_t s);
 // out[j] = sum_t a[t*lda+j] * (b ? b[t*ldb+j] : 1) * (sc ? sc[t] : 1); ta/tb/tout element types.
 // partial must hold >= colsum_partial_floats(rows, cols) floats.
+#define COLSUM_BATCH 3
 size_t colsum_partial_floats(int rows, int cols);
+// n <= COLSUM_BATCH column sums of one shape and type in one launch pair (b, ldb, sc may be null arrays)
+void launch_colsum_batch(int n, int ta, const void* const* a, const i64* lda, int tb, const void* const* b, const i64* ldb,
+                         const float* const* sc, int tout, void* const* out, float* partial, int rows, int cols,
+                         hipStream_t s);
 void launch_colsum(int ta, const void* a, i64 lda, int tb, const void* b, i64 ldb, const float* sc,
                    int tout, void* out, float* partial, int rows, int cols, hipStream_t s);
 // rotates buf (and, in the same launch, buf2 of the same shape when it is not null) in place
@@ -143,6 +155,8 @@ void launch_swiglu_bwd(int dt, const void* dhh, const void* gu, void* dgu, i64 r
 void launch_gather_rows(int dt, const void* src, const int* row_map, int div, void* dst, int rows, int cols,
                         hipStream_t s);
 void launch_copy_rows(int dt, const void* src, i64 lds_, void* dst, i64 ldd, int rows, int cols, hipStream_t s);
+void launch_copy_rows2(int dt, const void* src_a, i64 lds_a, int rows_a, const void* src_b, i64 lds_b, int rows_b,
+                       void* dst, i64 ldd, int cols, hipStream_t s);
 void launch_zero(int dt, void* p, int n, hipStream_t s);           // n elements of type dt set to zero
 // res[0] = max |a - b| (bitwise max of non-negative floats; res must be zeroed first) ; dst = a
 void launch_fill_u32(uint32_t* p, uint32_t v, int n, hipStream_t s);
