@@ -268,7 +268,7 @@ def bench_block(args, wl, headline):
     # timed region: exactly K steps, each between its own event pair, nothing else on the stream
     ms_per_step, ms_mean = time_steps(torch, run_step, stream, args.steps)
     other_ms = None
-    if headline and not args.graph:
+    if headline and not args.graph and not args.no_other_form:
         other = step_fused if args.separate_calls else step_three
         for _ in range(2):
             other()
@@ -381,6 +381,9 @@ def main():
     ap.add_argument("--separate-calls", action="store_true",
                     help="time revffn_inverse + revffn_backward as two calls (MoE half evaluated twice) as the headline "
                          "instead of revffn_inverse_backward (the other form is reported beside it either way)")
+    ap.add_argument("--no-other-form", action="store_true",
+                    help="skip the pass that times the other call form (used under the profiler, so that every step of "
+                         "the run launches the same kernels)")
     ap.add_argument("--no-other-workloads", action="store_true",
                     help="headline workload only: skip the compact records of the skewed-routing and long-sequence workloads")
     args = ap.parse_args()
