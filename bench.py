@@ -329,6 +329,25 @@ def bench_block(args, wl, headline):
                    "n_inv_iters": args.inv_iters, "residual_streams": "f32" if args.fp32_streams else wl.dtype, "launch": "HIP graph replay" if args.graph else "eager", "block": "symmetric comparison block" if args.symmetric else "RevFFN (Eq. 1-2)", "weight_gradients": "f32" if args.fp32_grads else wl.dtype, "trained": args.train, "calls": calls, "setup_s": round(t_setup, 1)},
         "roofline": roofline, "kernels": kernels, "launches_per_step": launches, "csrc_sha16": csrc_hash(),
     }
+    if headline and not args.no_merged and not args.symmetric:
+        # passes that need no gradients (static weights): adapters multiplied into the pre-trained weights once
+        Md = Hn.alloc_merged(wl)
+        mstruct = R.binding._m(Md)
+        merge = lambda: R.revffn_merge_adapters(ctx, wstruct, mstruct, stream)
+        fwd_u = lambda: R.revffn_forward(ctx, wstruct, x1d, x2d, y1d, y2d, wl.B, wl.S, wl.h, stream)
+        inv_u = lambda: R.revffn_inverse(ctx, wstruct, y1d, y2d, r1d, r2d, wl.B, wl.S, wl.h, None, stream)
+        fwd_m = lambda: R.revffn_forward_merged(ctx, wstruct, mstruct, x1d, x2d, y1d, y2d, wl.B, wl.S, wl.h, stream)
+        inv_m = lambda: R.revffn_inverse_merged(ctx, wstruct, mstruct, y1d, y2d, r1d, r2d, wl.B, wl.S, wl.h, None, stream)
+        rec = {}
+        for name, fn, k in (("merge_ms", merge, 3), ("forward_ms", fwd_u, args.steps), ("forward_merged_ms", fwd_m, args.steps),
+                            ("inverse_ms", inv_u, args.steps), ("inverse_merged_ms", inv_m, args.steps)):
+            for _ in range(2):
+                fn()
+            rec[name] = round(time_steps(torch, fn, stream, k)[0], 4)
+        rec["note"] = ("section 3.2 with static weights: W.P_up and P_dn.W formed once by merge (merge_ms), then forward and "
+                       "inverse without adapter GEMMs; not part of `value`")
+        out["merged_adapters"] = rec
+        del Md
     if other_ms is not None:
         # both call forms: the fused sweep step (MoE half evaluated once) and the literal three calls
         out["three_call_ms_per_step" if not args.separate_calls else "fused_ms_per_step"] = other_ms
@@ -384,6 +403,7 @@ def main():
     ap.add_argument("--no-other-form", action="store_true",
                     help="skip the pass that times the other call form (used under the profiler, so that every step of "
                          "the run launches the same kernels)")
+    ap.add_argument("--no-merged", action="store_true", help="skip the forward/inverse timings with pre-merged adapters")
     ap.add_argument("--no-other-workloads", action="store_true",
                     help="headline workload only: skip the compact records of the skewed-routing and long-sequence workloads")
     args = ap.parse_args()

@@ -137,6 +137,19 @@ typedef struct revffn_grads {
   void *ws_gate_up, *ws_down, *ws_gate;
 } revffn_grads;
 
+/* Pre-merged adapter weights (section 3.2: each pre-trained module is wrapped as P_dn(module(P_up .)), so with static
+ * weights the products can be formed once).  Device buffers owned by the caller, dtype = config.dtype except
+ * w_router (float32); filled by revffn_merge_adapters, read by revffn_forward_merged / revffn_inverse_merged. */
+typedef struct revffn_merged {
+  void *wq, *wk, *wv;     /* [d,h]   = Wq P_up_a, Wk P_up_a, Wv P_up_a                               */
+  void *wo;               /* [h,d]   = P_dn_a Wo                                                      */
+  void *w_gate_up;        /* [E,2I,h] = W_gate_up[e] P_up_m                                           */
+  void *w_down;           /* [E,h,I] = P_dn_m W_down[e]                                               */
+  void *ws_gate_up;       /* [2Is,h] = Ws_gate_up P_up_m;  NULL iff d_shared == 0                     */
+  void *ws_down;          /* [h,Is]  = P_dn_m Ws_down                                                 */
+  float *w_router;        /* [E (+1 with a shared expert), h] float32 = [W_r ; ws_gate] P_up_m diag(norm_m) */
+} revffn_merged;
+
 typedef struct revffn_ctx revffn_ctx; /* opaque: owns the device workspace only */
 
 /* Device bytes a context for up to max_B x max_S tokens allocates; 0 if cfg is invalid. */
@@ -229,6 +242,25 @@ int revffn_inverse_backward(revffn_ctx *ctx, const revffn_weights *w,
                             const void *dy1, const void *dy2, void *dx1, void *dx2,
                             const revffn_grads *g, int32_t B, int32_t S, int64_t ld,
                             float *residual, void *hip_stream);
+
+/* Pre-merged adapters, for passes with static weights (inference-like forward passes; rebuilding inputs).
+ * revffn_merge_adapters forms the products of revffn_merged from w (matrix-core GEMMs; about 1 Tflop at the
+ * Qwen1.5-MoE shape, so it pays only when the weights stay fixed over many calls; the merged set is half the size
+ * of the block's weights).  revffn_forward_merged / revffn_inverse_merged compute Eq. 1-2 / the inverse display from
+ * it: no adapter GEMMs, projections and expert gate-up GEMMs contract over h instead of d, expert down GEMMs write
+ * width h, and half the expert weight bytes are streamed.  w still supplies the norm gains, the q/k/v biases and
+ * b_router (and must be the weights m was merged from).  Same conventions as revffn_forward / revffn_inverse (in
+ * place allowed, residual optional); results agree with the unmerged calls to the rounding of the merged products
+ * (they are stored in dtype), not bit for bit.  The inverse runs config.n_inv_iters iterations (the tolerance rule
+ * applies to the unmerged calls only).  Gradients are taken with revffn_backward on the unmerged weights: it is
+ * the same function.  REVFFN_EUNSUPPORTED with config.symmetric. */
+int revffn_merge_adapters(revffn_ctx *ctx, const revffn_weights *w, const revffn_merged *m, void *hip_stream);
+int revffn_forward_merged(revffn_ctx *ctx, const revffn_weights *w, const revffn_merged *m,
+                          const void *x1, const void *x2, void *y1, void *y2,
+                          int32_t B, int32_t S, int64_t ld, void *hip_stream);
+int revffn_inverse_merged(revffn_ctx *ctx, const revffn_weights *w, const revffn_merged *m,
+                          const void *y1, const void *y2, void *x1, void *x2,
+                          int32_t B, int32_t S, int64_t ld, float *residual, void *hip_stream);
 
 /* Stack of n_blocks blocks (section 3.1: only the last hidden state is kept).
  * Forward: (x1,x2) -> (y1,y2) through w[0..n_blocks-1], no stream swap between

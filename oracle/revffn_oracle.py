@@ -326,6 +326,7 @@ def moe_half_forward(y1, W, cfg, forced_idx=None):
         z = z + W["b_router"]
     idx, w, p = route(z, cfg, forced_idx)
     counts, offsets, row_map = permutation(idx, E)
+    d = W["w_down"].shape[1]                    # width of the pre-trained space (h when the adapters are merged in)
     R = np.zeros((T, d))
     per_expert = []
     for e in range(E):
@@ -355,6 +356,31 @@ def moe_half_forward(y1, W, cfg, forced_idx=None):
     M = RS @ W["pdn_m"].T
     c.update(RS=RS, Sh=Sh)
     return M, c
+
+
+def merge_adapters(W):
+    """Section 3.2 wraps each pre-trained module as P_dn(module(P_up .)).  With static weights the products can be
+    formed first: every matrix that reads the up-projected input is multiplied by P_up from the right, every matrix
+    whose output is down-projected by P_dn from the left.  Returned in the layout of W with identity adapters, so the
+    same functions evaluate it; in exact arithmetic nothing changes (associativity)."""
+    W = as_f64(W)
+    h = W["pup_a"].shape[1]
+    M = dict(W)
+    M["pup_a"] = np.eye(h)
+    M["pdn_a"] = np.eye(h)
+    M["pup_m"] = np.eye(h)
+    M["pdn_m"] = np.eye(h)
+    for n in ("wq", "wk", "wv"):
+        M[n] = W[n] @ W["pup_a"]                                    # [d,d][d,h]
+    M["wo"] = W["pdn_a"] @ W["wo"]                                  # [h,d][d,d]
+    M["w_router"] = W["w_router"] @ W["pup_m"]                      # [E,d][d,h]
+    M["w_gate_up"] = W["w_gate_up"] @ W["pup_m"]                    # [E,2I,d][d,h]
+    M["w_down"] = np.einsum("hd,edi->ehi", W["pdn_m"], W["w_down"])
+    if W.get("ws_gate_up") is not None:
+        M["ws_gate_up"] = W["ws_gate_up"] @ W["pup_m"]
+        M["ws_down"] = W["pdn_m"] @ W["ws_down"]
+        M["ws_gate"] = W["pup_m"].T @ W["ws_gate"]                  # gamma = sigmoid(Um . ws_gate) = sigmoid(n3 . (P_up^T ws_gate))
+    return M
 
 
 def moe_half_backward(dM, c, W, cfg):

@@ -9,6 +9,7 @@ EXPORTED_SYMBOLS = (
     "revffn_workspace_bytes", "revffn_create", "revffn_destroy", "revffn_set_inv_iters",
     "revffn_set_inverse_tolerance", "revffn_set_inverse_tolerance_blocked", "revffn_get_inverse_stats",
     "revffn_get_inverse_blocks",
+    "revffn_merge_adapters", "revffn_forward_merged", "revffn_inverse_merged",
     "revffn_forward", "revffn_inverse", "revffn_backward", "revffn_backward_stored", "revffn_inverse_backward", "revffn_stack_forward",
     "revffn_stack_backward", "revffn_get_routing", "revffn_enable_taps", "revffn_get_branch",
     "revffn_set_kernel_mode", "revffn_set_helper_streams", "revffn_strerror", "revffn_profile_enable", "revffn_profile_read",
@@ -43,6 +44,13 @@ class Grads(ctypes.Structure):
     _fields_ = [(n, ctypes.c_void_p) for n in WEIGHT_FIELDS]
 
 
+MERGED_FIELDS = ("wq", "wk", "wv", "wo", "w_gate_up", "w_down", "ws_gate_up", "ws_down", "w_router")
+
+
+class Merged(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in MERGED_FIELDS]
+
+
 def library_path():
     return os.path.join(_HERE, "librevffn.so")
 
@@ -72,6 +80,9 @@ def load_library():
     lib.revffn_enable_taps.argtypes = [vp, i32]
     lib.revffn_set_kernel_mode.argtypes = [vp, i32]
     lib.revffn_set_helper_streams.argtypes = [vp, i32]
+    lib.revffn_merge_adapters.argtypes = [vp, ctypes.POINTER(Weights), ctypes.POINTER(Merged), vp]
+    lib.revffn_forward_merged.argtypes = [vp, ctypes.POINTER(Weights), ctypes.POINTER(Merged), vp, vp, vp, vp, i32, i32, i64, vp]
+    lib.revffn_inverse_merged.argtypes = [vp, ctypes.POINTER(Weights), ctypes.POINTER(Merged), vp, vp, vp, vp, i32, i32, i64, vp, vp]
     lib.revffn_forward.argtypes = [vp, ctypes.POINTER(Weights), vp, vp, vp, vp, i32, i32, i64, vp]
     lib.revffn_inverse.argtypes = [vp, ctypes.POINTER(Weights), vp, vp, vp, vp, i32, i32, i64, vp, vp]
     lib.revffn_backward.argtypes = [vp, ctypes.POINTER(Weights), vp, vp, vp, vp, vp, vp, vp,
@@ -327,3 +338,29 @@ def revffn_op_attention_bwd_noalloc(dtype, kernel_mode, q, k, v, o, d_o, lse, dq
     _check(load_library().revffn_op_attention_bwd_noalloc(dtype, kernel_mode, _ptr(q), _ptr(k), _ptr(v), _ptr(o),
                                                           _ptr(d_o), _ptr(lse), _ptr(dq), _ptr(dk), _ptr(dv), B, S, H,
                                                           dh, int(causal), _stream(stream)))
+
+
+def _m(merged):
+    if isinstance(merged, Merged):
+        return merged
+    s = Merged()
+    for n in MERGED_FIELDS:
+        setattr(s, n, _ptr(merged.get(n)))
+    return s
+
+
+def revffn_merge_adapters(ctx, weights, merged, stream=None):
+    w, m = _w(weights), _m(merged)
+    _check(ctx.lib.revffn_merge_adapters(ctx.handle, ctypes.byref(w), ctypes.byref(m), _stream(stream)))
+
+
+def revffn_forward_merged(ctx, weights, merged, x1, x2, y1, y2, B, S, ld, stream=None):
+    w, m = _w(weights), _m(merged)
+    _check(ctx.lib.revffn_forward_merged(ctx.handle, ctypes.byref(w), ctypes.byref(m), _ptr(x1), _ptr(x2), _ptr(y1),
+                                         _ptr(y2), B, S, ld, _stream(stream)))
+
+
+def revffn_inverse_merged(ctx, weights, merged, y1, y2, x1, x2, B, S, ld, residual=None, stream=None):
+    w, m = _w(weights), _m(merged)
+    _check(ctx.lib.revffn_inverse_merged(ctx.handle, ctypes.byref(w), ctypes.byref(m), _ptr(y1), _ptr(y2), _ptr(x1),
+                                         _ptr(x2), B, S, ld, _ptr(residual), _stream(stream)))

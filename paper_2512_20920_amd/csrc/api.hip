@@ -596,10 +596,11 @@ int attn_out(revffn_ctx* c, const revffn_weights* w, const void* resid, i64 ldr,
 // ---- MoE half ---------------------------------------------------------------------
 // Folded fp32 router matrix wrp = [W_r ; w_shared_gate] . P_up_m . diag(gain).  It depends on the weights only, so a
 // call that starts with the attention half enqueues it at once on helper stream 2, next to that half.
-void router_fold(revffn_ctx* c, const revffn_weights* w, hipStream_t s) {
+// dst != null: the fold goes there (pre-merged weights) and runs on s itself.
+void router_fold(revffn_ctx* c, const revffn_weights* w, hipStream_t s, float* dst = nullptr) {
   const revffn_config& f = c->cfg;
   const int d = f.d_model, h = d / 2, E = f.n_experts, Is = f.d_shared, dt = c->dt;
-  hipStream_t sr = side(c, s, 2);
+  hipStream_t sr = dst ? s : side(c, s, 2);
   after(c, s, sr);                        // everything that read wr_ext / wrp before is on s
   // [W_r ; w_shared_gate] stacked into one [E1, d] matrix so that the fold is a single GEMM
   {
@@ -607,10 +608,10 @@ void router_fold(revffn_ctx* c, const revffn_weights* w, hipStream_t s) {
     launch_copy_rows2(dt, w->w_router, d, E, Is ? w->ws_gate : w->w_router, d, Is ? 1 : 0, c->wr_ext, d, d, sr);
     ps.done(KID_COPY_ROWS);
   }
-  GemmArgs a = nn(c->wr_ext, d, w->pup_m, h, c->wrp, h, E + (Is ? 1 : 0), h, d);
+  GemmArgs a = nn(c->wr_ext, d, w->pup_m, h, dst ? dst : c->wrp, h, E + (Is ? 1 : 0), h, d);
   a.split_k = SPLIT_FOLD; a.splitk_ws = c->splitk_ws_r; a.col_scale = w->norm_m;
   (void)run_gemm(c, a, dt, dt, 0, sr);
-  c->fold_queued = true;
+  if (!dst) c->fold_queued = true;
 }
 
 // Recomputes n3, Um, routing, GU, Hh, Yp, shared expert and RS at y1.  q_x1 != null: the query side of the attention
@@ -682,6 +683,133 @@ int finish(revffn_ctx* c, hipStream_t s, int e) {
   if (e && c && c->use_streams)
     for (int i = 0; i < 3; i++) after(c, c->side[i], s);
   return e;
+}
+
+// ---- pre-merged adapters (section 3.2: Attn(.) = P_dn(Attn_pt(P_up .)), MLP(.) = P_dn(MLP_pt(P_up .))) ------------
+// With static weights the products W . P_up and P_dn . W can be formed once; the forward and inverse passes then
+// work on half-width inputs and outputs: no adapter GEMMs, Q/K/V projections and expert gate-up GEMMs with half the
+// contraction length, expert down GEMMs with half the output width, and half the expert weight bytes to stream.
+int merge_impl(revffn_ctx* c, const revffn_weights* w, const revffn_merged* m, hipStream_t s) {
+  const revffn_config& f = c->cfg;
+  const int d = f.d_model, h = d / 2, E = f.n_experts, I = f.d_expert, Is = f.d_shared, es = c->es;
+  GemmArgs q3[3] = {nn(w->wq, d, w->pup_a, h, m->wq, h, d, h, d), nn(w->wk, d, w->pup_a, h, m->wk, h, d, h, d),
+                    nn(w->wv, d, w->pup_a, h, m->wv, h, d, h, d)};
+  TRY(run_gemm_multi(c, q3, 3, c->dt, s));
+  TRY(run_gemm(c, nn(w->pdn_a, d, w->wo, d, m->wo, d, h, d, d), s));
+  {
+    // every expert's gate-up rows at once: [E * 2I, d] . [d, h]; in slices that keep 32-bit operand offsets valid
+    const i64 rows = (i64)E * 2 * I, step = ((i64)1 << 29) / d;
+    for (i64 r0 = 0; r0 < rows; r0 += step) {
+      const int mrows = (int)((rows - r0) < step ? (rows - r0) : step);
+      TRY(run_gemm(c, nn(at(w->w_gate_up, (size_t)r0 * d, es), d, w->pup_m, h, at(m->w_gate_up, (size_t)r0 * h, es), h, mrows, h, d), s));
+    }
+  }
+  for (int e = 0; e < E; e++)
+    TRY(run_gemm(c, nn(w->pdn_m, d, at(w->w_down, (size_t)e * d * I, es), I, at(m->w_down, (size_t)e * h * I, es), I, h, I, d), s));
+  if (Is) {
+    TRY(run_gemm(c, nn(w->ws_gate_up, d, w->pup_m, h, m->ws_gate_up, h, 2 * Is, h, d), s));
+    TRY(run_gemm(c, nn(w->pdn_m, d, w->ws_down, Is, m->ws_down, Is, h, Is, d), s));
+  }
+  router_fold(c, w, s, m->w_router);
+  return 0;
+}
+
+// n12, Q, (K, V), O, lse at streams (x1, x2) from merged projections.  do_kv = false: the query side only (a later
+// iterate of the inverse).
+int attn_acts_merged(revffn_ctx* c, const revffn_weights* w, const revffn_merged* m, const void* x1, i64 ld1,
+                     const void* x2, i64 ld2, int B, int S, bool do_kv, hipStream_t s) {
+  const revffn_config& f = c->cfg;
+  const int T = B * S, d = f.d_model, h = d / 2, es = c->es, dt = c->dt;
+  void* n2 = at(c->n12, (size_t)T * h, es);
+  if (do_kv) {
+    if (ld1 == ld2) p_rmsnorm_fwd(c, dt, c->sdt, x1, ld1, w->norm_a1, c->n12, h, T, h, f.rms_eps, s, nullptr, x2, w->norm_a2, n2);
+    else {
+      p_rmsnorm_fwd(c, dt, c->sdt, x1, ld1, w->norm_a1, c->n12, h, T, h, f.rms_eps, s);
+      p_rmsnorm_fwd(c, dt, c->sdt, x2, ld2, w->norm_a2, n2, h, T, h, f.rms_eps, s);
+    }
+    GemmArgs q3[3] = {nt(c->n12, h, m->wq, h, c->Q, d, T, d, h), nt(n2, h, m->wk, h, c->K, d, T, d, h),
+                      nt(n2, h, m->wv, h, c->V, d, T, d, h)};
+    q3[0].bias = w->bq; q3[1].bias = w->bk; q3[2].bias = w->bv;
+    TRY(run_gemm_multi(c, q3, 3, dt, s));
+    if (f.use_rope) p_rope(c, dt, c->Q, c->rope_cs, T, S, f.n_heads, f.head_dim, 1.f, s, c->K);
+  } else {
+    p_rmsnorm_fwd(c, dt, c->sdt, x1, ld1, w->norm_a1, c->n12, h, T, h, f.rms_eps, s);
+    GemmArgs gq = nt(c->n12, h, m->wq, h, c->Q, d, T, d, h);
+    gq.bias = w->bq;
+    TRY(run_gemm(c, gq, s));
+    if (f.use_rope) p_rope(c, dt, c->Q, c->rope_cs, T, S, f.n_heads, f.head_dim, 1.f, s);
+  }
+  double fl = 4.0 * B * (double)S * S * d * (f.causal ? 0.5 : 1.0), by = 4.0 * T * d * es;
+  ProfScope ps(c, s, fl, by);
+  bool done = false;
+  if (dt == 1 && c->mode == 0)
+    done = launch_attn_fwd_flash(c->Q, c->K, c->V, c->O, c->lse, B, S, f.n_heads, f.head_dim, f.causal, s) == 0;
+  if (!done) launch_attn_fwd_generic(dt, c->Q, c->K, c->V, c->O, c->lse, B, S, f.n_heads, f.head_dim, f.causal, s);
+  ps.done(done ? KID_ATTN_FWD_FLASH : KID_ATTN_FWD_GENERIC);
+  return 0;
+}
+// dst = resid + sign * O . (P_dn_a Wo)^T
+int attn_out_merged(revffn_ctx* c, const revffn_merged* m, const void* resid, i64 ldr, float sign, void* dst, i64 ldd,
+                    int T, hipStream_t s) {
+  const int d = c->cfg.d_model, h = d / 2;
+  GemmArgs g = nt(c->O, d, m->wo, d, dst, ldd, T, h, d);
+  g.resid = resid; g.ldr = ldr; g.resid_sign = sign; g.resid_f32 = c->sdt == REVFFN_F32;
+  if (c->taps) { g.tap = c->tapA; g.ldtap = h; }
+  return run_gemm(c, g, c->dt, c->dt, c->sdt, s);
+}
+// dst = resid + sign * MoE branch at y1, everything from merged weights (routing from the stored fp32 fold)
+int moe_merged(revffn_ctx* c, const revffn_weights* w, const revffn_merged* m, const void* y1, i64 ld, const void* resid,
+               i64 ldr, float sign, void* dst, i64 ldd, int T, hipStream_t s) {
+  const revffn_config& f = c->cfg;
+  const int d = f.d_model, h = d / 2, E = f.n_experts, k = f.top_k, I = f.d_expert, Is = f.d_shared, dt = c->dt;
+  const int N = T * k, E1 = E + (Is ? 1 : 0);
+  c->lastT = T;
+  c->lastT_rows = N;
+  hipStream_t sr = side(c, s, 2), s0 = side(c, s, 0);
+  after(c, s, sr);
+  {
+    GemmArgs z = nt(y1, ld, m->w_router, h, c->splitk_ws_r, E1, T, E1, h);
+    z.split_k = SPLIT_LOGITS; z.splitk_ws = c->splitk_ws_r; z.splitk_raw = 1;
+    GemmTypes tz{c->sdt, 0, 0, dt};
+    if (launch_gemm_generic(z, tz, sr)) return REVFFN_EUNSUPPORTED;
+  }
+  p_router(c, c->sdt, y1, ld, c->splitk_ws_r, SPLIT_LOGITS, w->b_router, c->probs, c->idx, c->wts, c->gamma, T, h, E, k,
+           Is ? 1 : 0, f.norm_topk_prob, f.rms_eps, sr);
+  TileLists tl{{c->tg_a, c->tg_b, c->tg_c}, {c->tm_a, c->tm_b, c->tm_c}, {c->tf_a, c->tf_b, c->tf_c},
+               {c->max_tiles_a, c->max_tiles_b, c->max_tiles_c}, {BM_A, BM_B, BM_C}, c->tile_cnt};
+  p_permute(c, c->idx, T, k, E, c->counts, c->offsets, c->row_map, c->inv_map, tl, sr);
+  p_rmsnorm_fwd(c, dt, c->sdt, y1, ld, w->norm_m, c->n3, h, T, h, f.rms_eps, s);
+  if (Is) {
+    after(c, s, s0);
+    GemmArgs gs = nt(c->n3, h, m->ws_gate_up, h, c->GUs, 2 * Is, T, 2 * Is, h);
+    gs.act_out = c->Hs; gs.ldact = Is; gs.act_half = Is;
+    TRY(run_gemm(c, gs, s0));
+    TRY(run_gemm(c, nt(c->Hs, Is, m->ws_down, Is, c->Ys, h, T, h, Is), s0));
+  }
+  after(c, sr, s);
+  GemmArgs g1 = nt(c->n3, h, m->w_gate_up, h, c->GU, 2 * I, N, 2 * I, h);
+  g1.group_mode = 1; g1.n_groups = E; g1.offsets = c->offsets; g1.b_group_stride = (i64)2 * I * h;
+  g1.a_gather = c->row_map; g1.gather_div = k;
+  g1.act_out = c->Hh; g1.ldact = I; g1.act_half = I;
+  TRY(run_gemm(c, g1, s));
+  GemmArgs g2 = nt(c->Hh, I, m->w_down, I, c->Yp, h, N, h, I);
+  g2.group_mode = 1; g2.n_groups = E; g2.offsets = c->offsets; g2.b_group_stride = (i64)h * I;
+  TRY(run_gemm(c, g2, s));
+  if (Is) after(c, s0, s);
+  {
+    ProfScope ps(c, s, 0, (double)T * h * esz(dt) * (k + (Is ? 1 : 0)) + 2.0 * T * h * esz(c->sdt));
+    launch_combine_couple(dt, c->sdt, c->Yp, c->inv_map, c->wts, Is ? c->Ys : nullptr, c->gamma, resid, ldr, sign, dst, ldd,
+                          c->taps ? c->tapM : nullptr, T, h, k, s);
+    ps.done(KID_COMBINE);
+  }
+  return 0;
+}
+int check_merged(const revffn_ctx* c, const revffn_merged* m) {
+  if (!m) return REVFFN_ENULL;
+  if (c->cfg.symmetric) return REVFFN_EUNSUPPORTED;
+  if (!m->wq || !m->wk || !m->wv || !m->wo || !m->w_gate_up || !m->w_down || !m->w_router) return REVFFN_ENULL;
+  if (c->cfg.d_shared && (!m->ws_gate_up || !m->ws_down)) return REVFFN_ENULL;
+  return 0;
 }
 
 int check_call(revffn_ctx* c, const revffn_weights* w, int B, int S, i64 ld) {
@@ -1240,6 +1368,58 @@ int revffn_inverse_backward(revffn_ctx* c, const revffn_weights* w, const void* 
   i64 ldk = 0;
   TRY(finish(c, s, inverse_impl(c, w, y1, y2, x1, x2, B, S, ld, residual, s, &y1k, &ldk)));
   return finish(c, s, backward_impl(c, w, x1, x2, y1k, ldk, dy1, dy2, dx1, dx2, g, B, S, ld, true, c->cfg.n_inv_iters >= 1, s));
+}
+
+int revffn_merge_adapters(revffn_ctx* c, const revffn_weights* w, const revffn_merged* m, void* stream) {
+  TRY(check_call(c, w, 1, 1, c ? c->cfg.d_model / 2 : 0));
+  TRY(check_merged(c, m));
+  return finish(c, (hipStream_t)stream, merge_impl(c, w, m, (hipStream_t)stream));
+}
+
+int revffn_forward_merged(revffn_ctx* c, const revffn_weights* w, const revffn_merged* m, const void* x1, const void* x2,
+                          void* y1, void* y2, int32_t B, int32_t S, int64_t ld, void* stream) {
+  TRY(check_call(c, w, B, S, ld));
+  TRY(check_merged(c, m));
+  if (!x1 || !x2 || !y1 || !y2) return REVFFN_ENULL;
+  hipStream_t s = (hipStream_t)stream;
+  const int T = B * S;
+  TRY(finish(c, s, attn_acts_merged(c, w, m, x1, ld, x2, ld, B, S, true, s)));
+  TRY(finish(c, s, attn_out_merged(c, m, x1, ld, 1.f, y1, ld, T, s)));                 // Eq. 1
+  return finish(c, s, moe_merged(c, w, m, y1, ld, x2, ld, 1.f, y2, ld, T, s));         // Eq. 2
+}
+
+int revffn_inverse_merged(revffn_ctx* c, const revffn_weights* w, const revffn_merged* m, const void* y1, const void* y2,
+                          void* x1, void* x2, int32_t B, int32_t S, int64_t ld, float* residual, void* stream) {
+  TRY(check_call(c, w, B, S, ld));
+  TRY(check_merged(c, m));
+  if (!x1 || !x2 || !y1 || !y2) return REVFFN_ENULL;
+  hipStream_t s = (hipStream_t)stream;
+  const int T = B * S, h = c->cfg.d_model / 2, n = c->cfg.n_inv_iters;
+  const void* y1k = y1;
+  i64 ldk = ld;
+  if (x1 == y1 && n >= 1) {               // in place: Y1 is needed after x1 starts being overwritten
+    p_copy_rows(c, c->sdt, y1, ld, c->y1c, h, T, h, s);
+    y1k = c->y1c;
+    ldk = h;
+  }
+  TRY(finish(c, s, moe_merged(c, w, m, y1k, ldk, y2, ld, -1.f, x2, ld, T, s)));        // X2^ = Y2 - MoE branch(Y1)
+  if (n == 0) {
+    if (x1 != y1) p_copy_rows(c, c->sdt, y1, ld, x1, ld, T, h, s);
+    if (residual) launch_fill_u32((uint32_t*)residual, 0, 1, s);
+  }
+  for (int it = 1; it <= n; it++) {
+    const void* xin = (it == 1) ? y1k : x1;
+    const i64 ldin = (it == 1) ? ldk : ld;
+    TRY(finish(c, s, attn_acts_merged(c, w, m, xin, ldin, x2, ld, B, S, it == 1, s)));  // K, V depend on X2^ only: once
+    if (it == n && residual) {
+      TRY(finish(c, s, attn_out_merged(c, m, y1k, ldk, -1.f, c->xtmp, h, T, s)));
+      launch_fill_u32((uint32_t*)residual, 0, 1, s);
+      launch_absdiff_max_copy(c->sdt, c->xtmp, h, xin, ldin, x1, ld, residual, T, h, s);
+    } else {
+      TRY(finish(c, s, attn_out_merged(c, m, y1k, ldk, -1.f, x1, ld, T, s)));          // x <- Y1 - attention branch(x, X2^)
+    }
+  }
+  return 0;
 }
 
 int revffn_stack_forward(revffn_ctx* c, const revffn_weights* w, int32_t n_blocks, const void* x1, const void* x2,

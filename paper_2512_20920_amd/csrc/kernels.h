@@ -195,6 +195,10 @@ void launch_permute(const int* idx, int T, int k, int E, int* counts, int* offse
                     const TileLists& tl, hipStream_t s);
 void launch_combine(int dt, const void* yp, const int* inv_map, const float* wts, const void* ys,
                     const float* gamma, void* rs, int T, int d, int k, hipStream_t s);
+// half-width combine + coupling update (pre-merged adapters): dst = resid + sign * (sum_slot w * yp[pos] + gamma * ys)
+void launch_combine_couple(int dt, int ts, const void* yp, const int* inv_map, const float* wts, const void* ys,
+                           const float* gamma, const void* resid, i64 ldr, float sign, void* dst, i64 ldd, float* tap,
+                           int T, int h, int k, hipStream_t s);
 void launch_moe_bwd_rows(int dt, const void* drs, const void* yp, const void* ys, const int* inv_map,
                          const float* wts, const float* gamma, void* dyp, void* dys, float* dw, float* dzext,
                          int T, int d, int k, int E1, int has_gate, hipStream_t s);

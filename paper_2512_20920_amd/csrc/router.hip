@@ -285,6 +285,42 @@ void launch_combine(int dt, const void* yp, const int* inv_map, const float* wts
                                      (const T*)ys, gamma, (T*)rs, d, k));
 }
 
+// Combine in the half-width space of the streams (pre-merged down projections: expert outputs already have width h)
+// with the coupling update of Eq. 2 / the first line of the inverse in the same pass:
+//   branch[t] = sum_slot wts[t,slot] * yp[inv_map[t*k+slot]] + gamma[t] * ys[t]      (slot order, fp32)
+//   dst[t] = resid[t] + sign * branch[t]   (rounded once to the stream type); tap (optional) keeps branch in fp32.
+template <class T, class TS>
+__global__ void __launch_bounds__(256) combine_couple_k(const T* __restrict__ yp, const int* __restrict__ inv_map,
+                                                        const float* __restrict__ wts, const T* __restrict__ ys,
+                                                        const float* __restrict__ gamma, const TS* resid, i64 ldr,
+                                                        float sign, TS* dst, i64 ldd, float* __restrict__ tap, int h, int k) {
+  const int t = blockIdx.x;
+  for (int c = threadIdx.x; c < h; c += 256) {
+    float acc = 0.f;
+    for (int s = 0; s < k; s++) {
+      int pos = inv_map[(i64)t * k + s];
+      acc += wts[(i64)t * k + s] * to_f(yp[(i64)pos * h + c]);
+    }
+    if (ys) acc += gamma[t] * to_f(ys[(i64)t * h + c]);
+    if (tap) tap[(i64)t * h + c] = acc;
+    dst[(i64)t * ldd + c] = from_f<TS>(to_f(resid[(i64)t * ldr + c]) + sign * acc);   // (dst may be resid: same element)
+  }
+}
+void launch_combine_couple(int dt, int ts, const void* yp, const int* inv_map, const float* wts, const void* ys,
+                           const float* gamma, const void* resid, i64 ldr, float sign, void* dst, i64 ldd, float* tap,
+                           int Tn, int h, int k, hipStream_t s) {
+  if (Tn <= 0) return;
+  if (dt == 0)
+    hipLaunchKernelGGL((combine_couple_k<float, float>), dim3(Tn), dim3(256), 0, s, (const float*)yp, inv_map, wts,
+                       (const float*)ys, gamma, (const float*)resid, ldr, sign, (float*)dst, ldd, tap, h, k);
+  else if (ts == 0)
+    hipLaunchKernelGGL((combine_couple_k<bf16, float>), dim3(Tn), dim3(256), 0, s, (const bf16*)yp, inv_map, wts,
+                       (const bf16*)ys, gamma, (const float*)resid, ldr, sign, (float*)dst, ldd, tap, h, k);
+  else
+    hipLaunchKernelGGL((combine_couple_k<bf16, bf16>), dim3(Tn), dim3(256), 0, s, (const bf16*)yp, inv_map, wts,
+                       (const bf16*)ys, gamma, (const bf16*)resid, ldr, sign, (bf16*)dst, ldd, tap, h, k);
+}
+
 // ---------------------------------------------------------------------------------
 // Backward of the combine, one workgroup per token:
 //   dgamma = <drs, ys>, gate-logit gradient dzext[t,E] = dgamma*gamma*(1-gamma), dys = gamma*drs

@@ -54,3 +54,13 @@ def alloc_grads(Wdev, skip=(), fp32=False):
 
 def download(t):
     return t.detach().float().cpu().numpy().astype(np.float64)
+
+
+def alloc_merged(wl, device="cuda"):
+    """Device buffers for the pre-merged adapter weights of one block (binding.Merged fields)."""
+    d, h, E, I, Is = wl.d_model, wl.d_model // 2, wl.n_experts, wl.d_expert, wl.d_shared
+    dt = torch_dtype(wl.dtype)
+    new = lambda *shape, t=dt: torch.full(shape, float("nan"), dtype=t, device=device)
+    return {"wq": new(d, h), "wk": new(d, h), "wv": new(d, h), "wo": new(h, d), "w_gate_up": new(E, 2 * I, h),
+            "w_down": new(E, h, I), "ws_gate_up": new(2 * Is, h) if Is else None, "ws_down": new(h, Is) if Is else None,
+            "w_router": new(E + (1 if Is else 0), h, t=torch.float32)}

@@ -75,6 +75,10 @@ def test_null_context_and_strerror(lib):
     assert lib.revffn_forward(None, ctypes.byref(w), 1, 1, 1, 1, 1, 1, 32, None) == -3
     assert lib.revffn_inverse(None, ctypes.byref(w), 1, 1, 1, 1, 1, 1, 32, None, None) == -3
     assert lib.revffn_backward(None, ctypes.byref(w), 1, 1, 1, 1, 1, 1, 1, None, 1, 1, 32, None) == -3
+    m = R.Merged()
+    assert lib.revffn_merge_adapters(None, ctypes.byref(w), ctypes.byref(m), None) == -3
+    assert lib.revffn_forward_merged(None, ctypes.byref(w), ctypes.byref(m), 1, 1, 1, 1, 1, 1, 32, None) == -3
+    assert lib.revffn_inverse_merged(None, ctypes.byref(w), ctypes.byref(m), 1, 1, 1, 1, 1, 1, 32, None, None) == -3
     assert lib.revffn_get_routing(None, None, None, None, None, None, None) == -3
     assert lib.revffn_set_inv_iters(None, 1) == -3
     assert lib.revffn_set_inverse_tolerance(None, 1e-3, 4) == -3

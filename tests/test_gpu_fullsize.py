@@ -88,6 +88,57 @@ def test_qwen_b4s512_headline_config():
     assert rep["inv1_oracle_x1_err_vs_true_input"] > 3 * rep["inv3_oracle_x1_err_vs_true_input"]
 
 
+def test_qwen_b4s512_merged_adapters():
+    """Headline shape through the pre-merged adapter weights (section 3.2 with static weights): the stored products
+    against fp64 products (attention side whole, three experts and the shared expert), forward and one-iteration
+    inverse against the oracle evaluating the unmerged definition with the GPU's selection forced.  The merged
+    products carry one more rounding to bfloat16 than the definition; the same tolerance still holds."""
+    wl = synth.WORKLOADS["qwen_b4s512"]
+    tol = TOL["bf16"]
+    W32 = synth.make_weights(wl, f64=False)
+    W = O.as_f64(W32)
+    case = Case(wl, weights=W)
+    cfg = case.ocfg
+    Md = Hn.alloc_merged(wl)
+    R.revffn_merge_adapters(case.ctx, case.Wd, Md)
+    torch.cuda.synchronize()
+    rep = {}
+    for n in ("wq", "wk", "wv"):
+        rep[n] = relerr(Hn.download(Md[n]), W[n] @ W["pup_a"])
+    rep["wo"] = relerr(Hn.download(Md["wo"]), W["pdn_a"] @ W["wo"])
+    rep["ws_gate_up"] = relerr(Hn.download(Md["ws_gate_up"]), W["ws_gate_up"] @ W["pup_m"])
+    rep["ws_down"] = relerr(Hn.download(Md["ws_down"]), W["pdn_m"] @ W["ws_down"])
+    for e in (0, 31, wl.n_experts - 1):
+        rep[f"w_gate_up[{e}]"] = relerr(Hn.download(Md["w_gate_up"][e]), W["w_gate_up"][e] @ W["pup_m"])
+        rep[f"w_down[{e}]"] = relerr(Hn.download(Md["w_down"][e]), W["pdn_m"] @ W["w_down"][e])
+    assert max(rep.values()) < 4.5e-3, rep                    # half a unit of bfloat16 storage is up to 2^-8 of the largest element, plus accumulation order
+    assert not torch.isnan(Md["w_gate_up"].float()).any() and not torch.isnan(Md["w_down"].float()).any()
+    x1d, x2d = case.up_s(case.x1), case.up_s(case.x2)
+    y1d, y2d = case.empty_s(), case.empty_s()
+    R.revffn_forward_merged(case.ctx, case.Wd, Md, x1d, x2d, y1d, y2d, wl.B, wl.S, wl.h)
+    torch.cuda.synchronize()
+    y1g, y2g = Hn.download(y1d), Hn.download(y2d)
+    a_gpu, m_gpu = case.branches()
+    A_ref, _ = O.attn_half_forward(case.x1, case.x2, W, cfg, wl.B, wl.S, keep_probs=False)
+    cm, safe, idx_gpu = check_routing(case, y1g, rep)
+    M_ref, _ = O.moe_half_forward(y1g, W, cfg, forced_idx=idx_gpu)
+    rep["attn_branch"], rep["moe_branch"] = relerr(a_gpu, A_ref), relerr(m_gpu, M_ref)
+    assert rep["attn_branch"] < tol and rep["moe_branch"] < tol, rep
+    assert relerr(y1g, case.x1 + A_ref) < tol and relerr(y2g, case.x2 + M_ref) < tol
+    case.ctx.set_inv_iters(1)
+    r1d, r2d = case.empty_s(), case.empty_s()
+    R.revffn_inverse_merged(case.ctx, case.Wd, Md, y1d, y2d, r1d, r2d, wl.B, wl.S, wl.h, None)
+    torch.cuda.synchronize()
+    ai, mi = case.branches()
+    _, _, idx_inv = check_routing(case, y1g)
+    assert np.array_equal(idx_inv, idx_gpu)
+    x1o, x2o = O.inverse(y1g, y2g, W, cfg, wl.B, wl.S, n_iters=1, forced_idx=idx_gpu)
+    rep["inv1_attn_branch"], rep["inv1_moe_branch"] = relerr(ai, y1g - x1o), relerr(mi, y2g - x2o)
+    assert rep["inv1_attn_branch"] < tol and rep["inv1_moe_branch"] < tol, rep
+    assert torch.equal(r2d.float(), (y2d.float() - torch.from_numpy(mi).cuda().float()).to(r2d.dtype).float())   # one rounding
+    print("FULLSIZE merged", {k: (float(f"{v:.2e}") if isinstance(v, float) else v) for k, v in rep.items()})
+
+
 def test_qwen_b4s512_fp32_residual_streams():
     """Headline shape with float32 residual streams: same parity bar; the rebuilt input is no longer limited by
     the bf16 rounding of the stored streams but by the truncated iteration (the oracle's own error at that count)

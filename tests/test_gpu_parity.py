@@ -872,3 +872,97 @@ def test_inverse_tolerance_per_position_block(name, bp):
         case.forward()                                   # eager work on the same context between replays
         torch.cuda.synchronize()
     assert case.ctx.inverse_stats()[0] == 1 + 1 + 3      # the eager step, the warm-up on the side stream, three replays
+
+
+# ---- pre-merged adapters (section 3.2) -------------------------------------------------------------------------
+STORED_MERGED = ("wq", "wk", "wv", "wo", "w_gate_up", "w_down", "ws_gate_up", "ws_down")
+
+
+def _oracle_merged(case):
+    """The oracle's products, with the tensors that the library stores in the compute dtype rounded to it by the
+    oracle side itself (the router rows stay unrounded: the library keeps them in float32)."""
+    M = O.merge_adapters(case.W)
+    Mr = dict(M)
+    if case.dt == "bf16":
+        for n in STORED_MERGED:
+            if M.get(n) is not None:
+                Mr[n] = synth.round_bf16(M[n])
+    return M, Mr
+
+
+@pytest.mark.parametrize("name", ["tiny_shared_f32", "mid_f32", "mid_bf16", "mid_fewbig_bf16"])
+def test_merged_adapters_parity(name):
+    wl = synth.WORKLOADS[name]
+    tol = TOL[wl.dtype]
+    case = Case(wl)
+    M, Mr = _oracle_merged(case)
+    Md = Hn.alloc_merged(wl)
+    R.revffn_merge_adapters(case.ctx, case.Wd, Md)
+    torch.cuda.synchronize()
+    # the products themselves: rounding to storage (half a unit of bfloat16 is up to 2^-8 of the largest element)
+    # plus the accumulation order
+    wtol = 4.5e-3 if wl.dtype == "bf16" else 1e-5
+    for n in STORED_MERGED:
+        if M.get(n) is None:
+            assert Md[n] is None
+            continue
+        g = Hn.download(Md[n])
+        assert g.shape == M[n].shape, n
+        assert relerr(g, M[n]) < wtol, n
+    # forward from the merged set against the oracle evaluating its own merged set
+    x1d, x2d = case.up_s(case.x1), case.up_s(case.x2)
+    y1d, y2d = case.empty_s(), case.empty_s()
+    R.revffn_forward_merged(case.ctx, case.Wd, Md, x1d, x2d, y1d, y2d, wl.B, wl.S, wl.h)
+    torch.cuda.synchronize()
+    y1g, y2g = Hn.download(y1d), Hn.download(y2d)
+    a_gpu, m_gpu = case.branches()
+    A_ref, _ = O.attn_half_forward(case.x1, case.x2, Mr, case.ocfg, wl.B, wl.S, keep_probs=False)
+    assert relerr(a_gpu, A_ref) < tol, "attention branch"
+    assert relerr(y1g, case.x1 + A_ref) < tol
+    rep = {}
+    cm, safe, idx_gpu = check_routing(case, y1g, rep)
+    M_ref, _ = O.moe_half_forward(y1g, Mr, case.ocfg, forced_idx=idx_gpu)
+    assert relerr(m_gpu, M_ref) < tol, "MoE branch"
+    assert relerr(y2g, case.x2 + M_ref) < tol
+    # and against the unmerged definition (the merged products carry one more rounding)
+    A_def, _ = O.attn_half_forward(case.x1, case.x2, case.W, case.ocfg, wl.B, wl.S, keep_probs=False)
+    M_def, _ = O.moe_half_forward(y1g, case.W, case.ocfg, forced_idx=idx_gpu)
+    assert relerr(a_gpu, A_def) < 2 * tol and relerr(m_gpu, M_def) < 2 * tol
+    # inverse from the merged set
+    for n in (1, 2, 0):
+        case.ctx.set_inv_iters(n)
+        r1d, r2d = case.empty_s(), case.empty_s()
+        res = torch.zeros((1,), dtype=torch.float32, device="cuda")
+        R.revffn_inverse_merged(case.ctx, case.Wd, Md, y1d, y2d, r1d, r2d, wl.B, wl.S, wl.h, res)
+        torch.cuda.synchronize()
+        a_inv, m_inv = case.branches()
+        _, _, idx_inv = check_routing(case, y1g)
+        x1o, x2o, info = O.inverse(y1g, y2g, Mr, case.ocfg, wl.B, wl.S, n_iters=n, return_info=True, forced_idx=idx_inv)
+        assert relerr(m_inv, y2g - x2o) < tol, "MoE branch in the inverse"
+        assert relerr(Hn.download(r2d), x2o) < tol and relerr(Hn.download(r1d), x1o) < tol
+        if n > 0:
+            assert relerr(a_inv, y1g - x1o) < tol, "attention branch in the inverse"
+            r = float(res.item())
+            assert abs(r - info["residual"]) <= max(tol * info["residual"], 2 * np.abs(y1g).max() * (2.0 ** -8 if case.dt == "bf16" else 2.0 ** -22))
+        else:
+            assert torch.equal(r1d, y1d)
+        # in place on the two halves of one [T, d] tensor
+        H = torch.cat([y1d, y2d], dim=1).contiguous()
+        p1, p2 = H.data_ptr(), H.data_ptr() + wl.h * H.element_size()
+        R.revffn_inverse_merged(case.ctx, case.Wd, Md, p1, p2, p1, p2, wl.B, wl.S, wl.d_model, None)
+        torch.cuda.synchronize()
+        assert torch.equal(H[:, :wl.h], r1d) and torch.equal(H[:, wl.h:], r2d)
+    print(name, "merged", rep)
+
+
+def test_merged_adapters_argument_errors():
+    wl = synth.WORKLOADS["tiny_shared_f32"]
+    case = Case(wl)
+    Md = Hn.alloc_merged(wl)
+    bad = dict(Md)
+    bad["w_down"] = None
+    with pytest.raises(RuntimeError):
+        R.revffn_merge_adapters(case.ctx, case.Wd, bad)
+    sym = Case(wl, flags=dict(symmetric=True))
+    with pytest.raises(RuntimeError):
+        R.revffn_merge_adapters(sym.ctx, sym.Wd, Md)

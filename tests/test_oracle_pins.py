@@ -680,3 +680,27 @@ def test_blockwise_stopping_rule_lands_on_fixed_counts():
     xw, _, iw = O.inverse(y1, y2, W, cfg, B, S, tol=tol, max_iters=12, return_info=True, block_positions=10 ** 6)
     # (block_positions >= S: one block per sequence; the whole-call count is the largest of them)
     assert max(iw["block_iters"]) == ia["iters"]
+
+
+def test_merged_adapters_are_the_same_function():
+    """Section 3.2: P_dn(module(P_up x)) with the products formed first is the same map (associativity), so forward
+    and inverse agree to fp64 rounding; a transposed or misplaced adapter in the merge changes them at once."""
+    wl = synth.WORKLOADS["tiny_shared_f32"]
+    cfg = cfg_of(wl)
+    W = synth.make_weights(wl)
+    x1, x2, _, _ = synth.make_inputs(wl)
+    M = O.merge_adapters(W)
+    h = wl.d_model // 2
+    assert M["wq"].shape == (wl.d_model, h) and M["wo"].shape == (h, wl.d_model)
+    assert M["w_gate_up"].shape == (wl.n_experts, 2 * wl.d_expert, h) and M["w_down"].shape == (wl.n_experts, h, wl.d_expert)
+    y1, y2 = O.forward(x1, x2, W, cfg, wl.B, wl.S)
+    z1, z2 = O.forward(x1, x2, M, cfg, wl.B, wl.S)
+    assert np.abs(z1 - y1).max() < 1e-12 * max(1.0, np.abs(y1).max())
+    assert np.abs(z2 - y2).max() < 1e-12 * max(1.0, np.abs(y2).max())
+    a1, a2 = O.inverse(y1, y2, W, cfg, wl.B, wl.S, n_iters=2)
+    b1, b2 = O.inverse(y1, y2, M, cfg, wl.B, wl.S, n_iters=2)
+    assert np.abs(a1 - b1).max() < 1e-12 and np.abs(a2 - b2).max() < 1e-12
+    # one element by hand: (Wq P_up)[i, j] = sum_c Wq[i, c] P_up[c, j]
+    Wf = O.as_f64(W)
+    assert abs(M["wq"][3, 5] - sum(Wf["wq"][3, c] * Wf["pup_a"][c, 5] for c in range(wl.d_model))) < 1e-15
+    assert abs(M["w_down"][1, 2, 4] - sum(Wf["pdn_m"][2, c] * Wf["w_down"][1, c, 4] for c in range(wl.d_model))) < 1e-15
