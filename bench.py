@@ -365,6 +365,34 @@ def bench_block(args, wl, headline):
     return out
 
 
+def gemm_sweep():
+    """One dense GEMM kernel (128x128 tiles) at growing k: a single tile, and 2048 x 2048 outputs (one tile per CU).
+    The k = 64 rows are the fixed cost of a launch in a stream; the slope is the time of one k-step."""
+    import torch
+    import paper_2512_20920_amd as R
+    rows = []
+    for (M, N) in ((128, 128), (2048, 2048)):
+        for K in (64, 256, 1024, 2048, 4096, 8192):
+            a = torch.randn((M, K), device="cuda").bfloat16()
+            b = torch.randn((N, K), device="cuda").bfloat16()
+            c = torch.empty((M, N), device="cuda", dtype=torch.bfloat16)
+            st = torch.cuda.current_stream()
+            f = lambda: R.revffn_op_gemm(1, 2 + 256 * 2, a, b, c, M, N, K, K, K, N, False, False, False, st)
+            for _ in range(3):
+                f()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(100):
+                f()
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 10.0
+            rows.append({"M": M, "N": N, "K": K, "us_per_launch": round(us, 2), "tflops": round(2.0 * M * N * K / us / 1e6, 1)})
+    print(json.dumps({"gemm_sweep": "C[M,N] = A[M,K] B[N,K]^T, bf16, 128x128 tiles, 100 launches back to back on one stream",
+                      "rows": rows}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -403,6 +431,8 @@ def main():
     ap.add_argument("--no-other-form", action="store_true",
                     help="skip the pass that times the other call form (used under the profiler, so that every step of "
                          "the run launches the same kernels)")
+    ap.add_argument("--gemm-sweep", action="store_true",
+                    help="time one dense GEMM kernel at growing k (launch floor and time per k-step) and exit")
     ap.add_argument("--no-merged", action="store_true", help="skip the forward/inverse timings with pre-merged adapters")
     ap.add_argument("--no-other-workloads", action="store_true",
                     help="headline workload only: skip the compact records of the skewed-routing and long-sequence workloads")
@@ -426,6 +456,8 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"copy_calibration_bytes": a.numel(), "copies": 3}))
         return
+    if args.gemm_sweep:
+        return gemm_sweep()
     wl = synth.WORKLOADS[args.workload]
     if wl.n_blocks > 1:
         return bench_stack(args, wl)
