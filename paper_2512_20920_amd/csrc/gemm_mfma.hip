@@ -136,7 +136,7 @@ __device__ __forceinline__ void pair_rows(bool odd, float x0, float x1, float* l
 // One output tile; TE = 32-row blocks per wave.
 template <int BM, int BN, int WGM, bool AT, bool BT, class TC, int NW, int NS, int TE>
 __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const bf16* A, const bf16* Bm, TC* C, const void* bias_ptr,
-                                          int bx, int bz, int m0, int m_end, int k0, int k_end) {
+                                          int bx, int bz, int m0, int m_end, int k0, int k_end, int rot_seed) {
   constexpr int WGN = NW / WGM;                      // waves along n
   constexpr int WM = BM / WGM, WN = BN / WGN, TN = WN / 32;
   constexpr int STAGE = (BM + BN) * 128;             // bytes of one LDS stage: A tile, then B tile
@@ -167,9 +167,16 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const bf16* A, cons
   }
   const unsigned lds0 = (unsigned)(unsigned long long)(__attribute__((address_space(3))) unsigned char*)smem;
   const unsigned lw = __builtin_amdgcn_readfirstlane(lds0 + (unsigned)wv * LPW * 1024u);
-  auto issue = [&](int kt, int i) {                  // wave-load i of k-tile kt into stage kt % NS
+  // The k-tiles are walked from a start that differs from workgroup to workgroup (and wraps around): workgroups
+  // that stream weights from HBM otherwise all ask for the same address bits above the cache-line offset at the
+  // same time (every tile row starts a multiple of 4 KiB from its operand's base), which lands on a few memory
+  // channels at a time; staggered starts spread the requests over all of them.  The sum over k is the same set of
+  // products in a rotated, per-tile fixed order.
+  const int rot = __builtin_amdgcn_readfirstlane(nk > 0 ? rot_seed % nk : 0);
+  auto issue = [&](int kt, int i) {                  // wave-load i of the kt-th k-tile walked, into stage kt % NS
     const bool isA = (wv * LPW + i) < BM / 8;        // wave-uniform
-    const unsigned off = kt < ntile[i] ? base[i] + (unsigned)kt * (isA ? kstep_a : kstep_b) : OOB;
+    const int kr = kt + rot >= nk ? kt + rot - nk : kt + rot;
+    const unsigned off = (kt < nk && kr < ntile[i]) ? base[i] + (unsigned)kr * (isA ? kstep_a : kstep_b) : OOB;
     load_lds_b128(isA ? da : db, lw + (unsigned)(kt % NS) * STAGE + i * 1024, off);
   };
 
@@ -453,8 +460,9 @@ __global__ void __launch_bounds__(NW * 64) gemm_mfma_k(GemmArgs g) {
   if (g.xcd_m != 0 && !place_tile(g.group_mode, g.xcd_m, g.tiles_m, g.tiles_n, g.n_groups,
                                   g.group_mode == 1 ? g.tile_count[0] : 0, g.tile_first, (int)blockIdx.x, &bx, &by, &bz))
     return;
-  int m0, m_end, k0 = 0, k_end = g.K;
+  int m0, m_end, k0 = 0, k_end = g.K, rot_seed = 0;
   if (g.group_mode == 1) {
+    if (!BT) rot_seed = by;     // per row tile (weights with k as the slow index are spread by their column tile already)
     int ti = by;
     int grp = g.tile_group[ti];
     if (grp < 0) return;
@@ -486,7 +494,7 @@ __global__ void __launch_bounds__(NW * 64) gemm_mfma_k(GemmArgs g) {
     for (int r = m0 + (int)(threadIdx.x & 63); r < min(m_end, m0 + BM); r += 64) live |= g.row_skip[r] == 0;
     if (!__any(live)) return;
   }
-  gemm_tile<BM, BN, WGM, AT, BT, TC, NW, NS, TM>(g, A, Bm, C, bias, bx, bz, m0, m_end, k0, k_end);
+  gemm_tile<BM, BN, WGM, AT, BT, TC, NW, NS, TM>(g, A, Bm, C, bias, bx, bz, m0, m_end, k0, k_end, rot_seed);
 }
 
 // REVFFN_XCD (tuning aid): 0 = plain 2-D grids, tiles land on the XCDs round-robin
