@@ -549,10 +549,22 @@ template <bool AT, bool BT, class TC> static void go_128x64(const GemmArgs& g, h
 
 template <bool AT, bool BT, class TC>
 static void pick_tile(const GemmArgs& g, hipStream_t s) {
+  // Dense problems: the tile whose rounds of workgroups over the 256 CUs cost least.  One tile of 256x128 takes about
+  // 1.72 times, one of 256x256 about 3.05 times as long as one of 128x128 (measured on this block's shapes at 1024 to
+  // 8192 tokens: larger tiles do more work per loaded byte, but a last, partly filled round costs a whole tile's time).
+  auto dense_choice = [&]() {
+    const int z = g.split_k > 1 ? g.split_k : g.n_sub;
+    auto rounds = [&](int bm, int bn) { return (double)cdiv((i64)cdiv(g.M, bm) * cdiv(g.N, bn) * z, 256); };
+    const double c2 = rounds(128, 128), c3 = 1.72 * rounds(256, 128), c4 = 3.05 * rounds(256, 256);
+    return (c4 < c3 && c4 < c2) ? 4 : (c3 < c2 ? 3 : 2);
+  };
   if (g.act_half && g.group_mode == 0) {
     // SwiGLU epilogue: only tiles whose waves are 64 columns wide (a gate and an up block)
-    if ((i64)cdiv(g.M, 256) * cdiv(g.N, 128) >= 512) go_256x128<AT, BT, TC>(g, s);
-    else go_128x128<AT, BT, TC>(g, s);
+    switch (g.force_tile >= 2 ? g.force_tile : dense_choice()) {
+      case 4: go_256x256<AT, BT, TC>(g, s); break;
+      case 3: go_256x128<AT, BT, TC>(g, s); break;
+      default: go_128x128<AT, BT, TC>(g, s);
+    }
     return;
   }
   if (g.group_mode != 1 && g.force_tile) {           // a unit test asks for one of the shapes (dense problems)
@@ -585,13 +597,14 @@ static void pick_tile(const GemmArgs& g, hipStream_t s) {
     go_256x256<AT, BT, TC>(g, s);
     return;
   }
-  // the largest tile that still gives every CU work: 256x128 from two rounds of workgroups on, 128x128 down to
-  // ~200 tiles, else 128x64
-  const i64 t256 = (i64)cdiv(g.M, 256) * cdiv(g.N, 128), t128 = (i64)cdiv(g.M, 128) * cdiv(g.N, 128);
-  const int z = g.split_k > 1 ? g.split_k : g.n_sub;
-  if (t256 * z >= 512) go_256x128<AT, BT, TC>(g, s);
-  else if ((t128 * z >= 200) || g.N < 128) go_128x128<AT, BT, TC>(g, s);
-  else go_128x64<AT, BT, TC>(g, s);
+  // below ~200 tiles of 128x128: 128x64 (two workgroups per CU)
+  const i64 t128 = (i64)cdiv(g.M, 128) * cdiv(g.N, 128) * (g.split_k > 1 ? g.split_k : g.n_sub);
+  if (t128 < 200 && g.N >= 128) { go_128x64<AT, BT, TC>(g, s); return; }
+  switch (dense_choice()) {
+    case 4: go_256x256<AT, BT, TC>(g, s); break;
+    case 3: go_256x128<AT, BT, TC>(g, s); break;
+    default: go_128x128<AT, BT, TC>(g, s);
+  }
 }
 
 static bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
