@@ -343,7 +343,13 @@ int run_gemm(revffn_ctx* c, GemmArgs g, int ta, int tb, int tc, hipStream_t s) {
 }
 int run_gemm(revffn_ctx* c, const GemmArgs& g, hipStream_t s) { return run_gemm(c, g, c->dt, c->dt, c->dt, s); }
 // a GEMM whose result is a weight gradient: written in the gradient dtype (float32 with fp32_grads)
-int run_wgrad(revffn_ctx* c, const GemmArgs& g, hipStream_t s) { return run_gemm(c, g, c->dt, c->dt, c->gdt, s); }
+// (weight gradients run on helper streams beside the data-gradient chain: the tile with the least CU-time, see
+// GemmArgs::bulk; measured 1.3 % of a headline step with the shared expert's forward GEMMs treated the same way)
+int run_wgrad(revffn_ctx* c, const GemmArgs& g0, hipStream_t s) {
+  GemmArgs g = g0;
+  g.bulk = c->use_streams;
+  return run_gemm(c, g, c->dt, c->dt, c->gdt, s);
+}
 
 // ---- the memory-bound kernels, timed like the GEMMs when profiling is on: algorithmic bytes = every input read
 // once and every output written once (index arrays and per-row scalars included, gains and tables left out)
@@ -647,8 +653,11 @@ int moe_acts(revffn_ctx* c, const revffn_weights* w, const void* y1, i64 ld, int
     after(c, s, s0);
     GemmArgs gs = nt(c->Um, d, w->ws_gate_up, d, c->GUs, 2 * Is, T, 2 * Is, d);
     gs.act_out = c->Hs; gs.ldact = Is; gs.act_half = Is;      // Hs = silu(gate) * up with the GEMM
+    gs.bulk = c->use_streams;                                 // beside the routed experts' GEMMs
     TRY(run_gemm(c, gs, s0));
-    TRY(run_gemm(c, nt(c->Hs, Is, w->ws_down, Is, c->Ys, d, T, d, Is), s0));
+    GemmArgs gd = nt(c->Hs, Is, w->ws_down, Is, c->Ys, d, T, d, Is);
+    gd.bulk = gs.bulk;
+    TRY(run_gemm(c, gd, s0));
   }
   if (q_x1) TRY(attn_q(c, w, q_x1, q_ld, qB, qS, s, q_skip));
   after(c, sr, s);                        // routing and permutation are ready
@@ -783,8 +792,11 @@ int moe_merged(revffn_ctx* c, const revffn_weights* w, const revffn_merged* m, c
     after(c, s, s0);
     GemmArgs gs = nt(c->n3, h, m->ws_gate_up, h, c->GUs, 2 * Is, T, 2 * Is, h);
     gs.act_out = c->Hs; gs.ldact = Is; gs.act_half = Is;
+    gs.bulk = c->use_streams;
     TRY(run_gemm(c, gs, s0));
-    TRY(run_gemm(c, nt(c->Hs, Is, m->ws_down, Is, c->Ys, h, T, h, Is), s0));
+    GemmArgs gd = nt(c->Hs, Is, m->ws_down, Is, c->Ys, h, T, h, Is);
+    gd.bulk = gs.bulk;
+    TRY(run_gemm(c, gd, s0));
   }
   after(c, sr, s);
   GemmArgs g1 = nt(c->n3, h, m->w_gate_up, h, c->GU, 2 * I, N, 2 * I, h);
@@ -1038,6 +1050,7 @@ int backward_impl(revffn_ctx* c, const revffn_weights* w, const void* x1, const 
     if (GF(wq)) wg[nw++] = tn(c->dQ, d, sym ? U2 : U1, d, GF(wq), d, d, d, T);
     if (GF(wk)) wg[nw++] = tn(c->dK, d, U2, d, GF(wk), d, d, d, T);
     if (GF(wv)) wg[nw++] = tn(c->dV, d, U2, d, GF(wv), d, d, d, T);
+    if (nw) wg[0].bulk = c->use_streams;
     TRY(run_gemm_multi(c, wg, nw, c->gdt, s0));
   }
   {

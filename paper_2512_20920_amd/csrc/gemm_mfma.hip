@@ -554,7 +554,11 @@ static void pick_tile(const GemmArgs& g, hipStream_t s) {
   // 8192 tokens: larger tiles do more work per loaded byte, but a last, partly filled round costs a whole tile's time).
   auto dense_choice = [&]() {
     const int z = g.split_k > 1 ? g.split_k : g.n_sub;
-    auto rounds = [&](int bm, int bn) { return (double)cdiv((i64)cdiv(g.M, bm) * cdiv(g.N, bn) * z, 256); };
+    // (a launch that runs beside others on a helper stream fills only the CUs it needs: its cost is its tile count)
+    auto rounds = [&](int bm, int bn) {
+      const i64 tiles = (i64)cdiv(g.M, bm) * cdiv(g.N, bn) * z;
+      return g.bulk ? (double)tiles / 256.0 : (double)cdiv(tiles, 256);
+    };
     const double c2 = rounds(128, 128), c3 = 1.72 * rounds(256, 128), c4 = 3.05 * rounds(256, 256);
     return (c4 < c3 && c4 < c2) ? 4 : (c3 < c2 ? 3 : 2);
   };
@@ -599,7 +603,7 @@ static void pick_tile(const GemmArgs& g, hipStream_t s) {
   }
   // below ~200 tiles of 128x128: 128x64 (two workgroups per CU)
   const i64 t128 = (i64)cdiv(g.M, 128) * cdiv(g.N, 128) * (g.split_k > 1 ? g.split_k : g.n_sub);
-  if (t128 < 200 && g.N >= 128) { go_128x64<AT, BT, TC>(g, s); return; }
+  if (t128 < 200 && g.N >= 128 && !(g.bulk && g.M >= 256 && g.N >= 256)) { go_128x64<AT, BT, TC>(g, s); return; }
   switch (dense_choice()) {
     case 4: go_256x256<AT, BT, TC>(g, s); break;
     case 3: go_256x128<AT, BT, TC>(g, s); break;

@@ -53,6 +53,7 @@ struct GemmArgs {
   void* subC[2] = {nullptr, nullptr}; const void* subBias[2] = {nullptr, nullptr};
   // dense problems: row_skip[m] != 0 marks an output row that is not wanted (a finished part of the fixed-point
   // iteration of the inverse); a workgroup whose rows are all marked exits at once, the others compute every row
+  int bulk = 0;                           // 1: not on the caller's critical path (runs beside other kernels): least CU-time wins
   const unsigned char* row_skip = nullptr;
   // set by the MFMA launcher: XCD-aware placement of the tiles (0 = plain 2-D grid), tile counts of the problem
   int xcd_m = 0, tiles_m = 0, tiles_n = 0;
