@@ -56,7 +56,7 @@ struct revffn_ctx {
   int device = 0;
   void* slab = nullptr;
   size_t slab_bytes = 0;
-  hipStream_t side[3] = {nullptr, nullptr, nullptr};   // helper streams for independent branches of one call
+  hipStream_t side[4] = {nullptr, nullptr, nullptr, nullptr};   // helper streams for independent branches of one call
   std::vector<hipEvent_t>* sync_ev = nullptr;  // ring of timing-free events for fork/join
   size_t sync_next = 0;
   bool use_streams = true;
@@ -690,7 +690,7 @@ int moe_out(revffn_ctx* c, const revffn_weights* w, const void* resid, i64 ldr, 
 // before the caller's next work.
 int finish(revffn_ctx* c, hipStream_t s, int e) {
   if (e && c && c->use_streams)
-    for (int i = 0; i < 3; i++) after(c, c->side[i], s);
+    for (int i = 0; i < 4; i++) after(c, c->side[i], s);
   return e;
 }
 
@@ -851,7 +851,8 @@ int forward_impl(revffn_ctx* c, const revffn_weights* w, const void* x1, const v
 
 // y1k/ldk: where the exact Y1 stays readable during and after the call (== y1 unless in place)
 int inverse_impl(revffn_ctx* c, const revffn_weights* w, const void* y1, const void* y2, void* x1, void* x2, int B,
-                 int S, i64 ld, float* residual, hipStream_t s, const void** y1_kept, i64* ld_kept) {
+                 int S, i64 ld, float* residual, hipStream_t s, const void** y1_kept, i64* ld_kept,
+                 hipStream_t s_attn = nullptr, hipStream_t* s_attn_used = nullptr) {
   const int T = B * S, h = c->cfg.d_model / 2, dt = c->dt;
   const bool sym = c->cfg.symmetric != 0;  // closed-form inverse: one evaluation of the branch at X2^, no iteration
   const bool conv = !sym && c->inv_tol > 0.f;      // stop on the residual instead of after a fixed count
@@ -883,26 +884,32 @@ int inverse_impl(revffn_ctx* c, const revffn_weights* w, const void* y1, const v
     if (x1 != y1) p_copy_rows(c, c->sdt, y1, ld, x1, ld, T, h, s);
     if (residual) launch_fill_u32((uint32_t*)residual, 0, 1, s);
   }
+  // The iteration needs X2^ and nothing else of the MoE half.  A caller that goes on with work that does not need X1^
+  // (the fused sweep step: the MoE half's backward pass) hands over a stream of its own for it and joins that stream
+  // itself, where X1^ is first needed.
+  hipStream_t sa = s;
+  if (s_attn && c->use_streams && n >= 1) { sa = s_attn; after(c, s, sa); }
+  if (s_attn_used) *s_attn_used = sa;     // == s: nothing was left on another stream
   for (int it = 1; it <= n; it++) {
     const void* xin = (it == 1) ? y1k : x1;                       // iterate, started at Y1
     i64 ldin = (it == 1) ? ldk : ld;
-    TRY(attn_acts(c, w, xin, ldin, x2, ld, B, S, it == 1, s, it == 1 && !sym, skip));   // K, V depend on X2^ only: once
-    if (sym && residual) launch_fill_u32((uint32_t*)residual, 0, 1, s);     // nothing is iterated: residual 0
+    TRY(attn_acts(c, w, xin, ldin, x2, ld, B, S, it == 1, sa, it == 1 && !sym, skip));   // K, V depend on X2^ only: once
+    if (sym && residual) launch_fill_u32((uint32_t*)residual, 0, 1, sa);    // nothing is iterated: residual 0
     if (conv) {
       // every iteration up to the cap is enqueued; workgroups whose rows have all met the tolerance exit at once,
       // and the update below touches the other rows only.  The host takes no part in the decision.
-      TRY(attn_out(c, w, y1k, ldk, -1.f, c->xtmp, h, T, s, skip));
-      launch_conv_update(c->sdt, c->xtmp, h, xin, ldin, x1, ld, c->conv, T, h, s);
-      launch_conv_decide(c->conv, T, c->inv_tol, it, s);
+      TRY(attn_out(c, w, y1k, ldk, -1.f, c->xtmp, h, T, sa, skip));
+      launch_conv_update(c->sdt, c->xtmp, h, xin, ldin, x1, ld, c->conv, T, h, sa);
+      launch_conv_decide(c->conv, T, c->inv_tol, it, sa);
     } else if (!sym && it == n && residual) {
-      TRY(attn_out(c, w, y1k, ldk, -1.f, c->xtmp, h, T, s));
-      launch_fill_u32((uint32_t*)residual, 0, 1, s);
-      launch_absdiff_max_copy(c->sdt, c->xtmp, h, xin, ldin, x1, ld, residual, T, h, s);
+      TRY(attn_out(c, w, y1k, ldk, -1.f, c->xtmp, h, T, sa));
+      launch_fill_u32((uint32_t*)residual, 0, 1, sa);
+      launch_absdiff_max_copy(c->sdt, c->xtmp, h, xin, ldin, x1, ld, residual, T, h, sa);
     } else {
-      TRY(attn_out(c, w, y1k, ldk, -1.f, x1, ld, T, s));          // x <- Y1 - attention branch(x, X2^)
+      TRY(attn_out(c, w, y1k, ldk, -1.f, x1, ld, T, sa));         // x <- Y1 - attention branch(x, X2^)
     }
   }
-  if (conv) launch_conv_finalize(c->conv, residual, s);
+  if (conv) launch_conv_finalize(c->conv, residual, sa);
   if (y1_kept) { *y1_kept = y1k; *ld_kept = ldk; }
   return 0;
 }
@@ -912,14 +919,25 @@ void* gfield(const revffn_grads* g, size_t off) { return g ? *(void* const*)((co
 
 int backward_impl(revffn_ctx* c, const revffn_weights* w, const void* x1, const void* x2, const void* y1, i64 ldy,
                   const void* dy1, const void* dy2, void* dx1, void* dx2, const revffn_grads* g, int B, int S,
-                  i64 ld, bool reuse_moe, bool reuse_kv, hipStream_t s, bool reuse_attn = false) {
+                  i64 ld, bool reuse_moe, bool reuse_kv, hipStream_t s, bool reuse_attn = false,
+                  hipStream_t s_attn = nullptr) {
   const revffn_config& f = c->cfg;
   const int T = B * S, d = f.d_model, h = d / 2, E = f.n_experts, k = f.top_k, I = f.d_expert, Is = f.d_shared;
   const int N = T * k, E1 = E + (Is ? 1 : 0), dt = c->dt, es = c->es;
   // ---- recompute the attention half at (x1, x2)
   // (K, V and the normalised, lifted X2 are still those of the inverse when it ran in the same call: same X2 bits)
+  // The MoE half's backward pass needs dY2, Y1 and the MoE activations only; the attention half is recomputed beside
+  // it on a stream of its own (sa) and joined where its activations are first used.  (With y1 == NULL the MoE half
+  // needs the recomputed Y1 first: one stream.)  s_attn: the stream the caller's inverse left X1^ on.
+  hipStream_t sa = s;
+  if (y1 && c->use_streams && !reuse_attn) {
+    sa = s_attn ? s_attn : c->side[3];
+    if (!s_attn) after(c, s, sa);
+  } else if (s_attn && s_attn != s) {
+    after(c, s_attn, s);                  // no overlap in this call: X1^ is needed on s from here on
+  }
   if (!y1 || !reuse_moe) router_fold(c, w, s);
-  if (!reuse_attn) TRY(attn_acts(c, w, x1, ld, x2, ld, B, S, !reuse_kv, s));
+  if (!reuse_attn) TRY(attn_acts(c, w, x1, ld, x2, ld, B, S, !reuse_kv, sa));
   if (!y1) {
     TRY(attn_out(c, w, x1, ld, 1.f, c->y1c, h, T, s));
     y1 = c->y1c;
@@ -1009,6 +1027,7 @@ int backward_impl(revffn_ctx* c, const revffn_weights* w, const void* x1, const 
   // g1 = dY1 + Norm'(dn3): total gradient at Y1
   p_rmsnorm_bwd(c, dt, c->sdt, c->dn3, h, y1, ldy, w->norm_m, dy1, ld, c->g1, h, c->rinv3, T, h, f.rms_eps, s);
   // ---- attention half backward: Y1 = X1 + P_dn_a(AO)
+  if (sa != s) after(c, sa, s);           // the recomputed attention activations (and X1^ of a fused call)
   if (GF(norm_m)) { after(c, s, sc); p_colsum(c, c->sdt, y1, ldy, dt, c->dn3, h, c->rinv3, c->gdt, GF(norm_m), c->partial, T, h, sc); }
   if (GF(pdn_a)) { after(c, s, s0); TRY(run_wgrad(c, tn(c->g1, h, c->AO, d, GF(pdn_a), d, h, d, T), s0)); }
   TRY(run_gemm(c, nn(c->g1, h, w->pdn_a, d, c->dAO, d, T, d, h), s));
@@ -1165,7 +1184,7 @@ int revffn_create(revffn_ctx** out, const revffn_config* cfg, int32_t max_B, int
   { const char* e = getenv("REVFFN_EXPERT_NN"); if (e && atoi(e) >= 1 && atoi(e) <= 3) c->expert_nn = atoi(e); }
   c->sync_ev = new (std::nothrow) std::vector<hipEvent_t>();
   bool ok = c->sync_ev != nullptr;
-  for (int i = 0; ok && i < 3; i++) ok = hipStreamCreateWithFlags(&c->side[i], hipStreamNonBlocking) == hipSuccess;
+  for (int i = 0; ok && i < 4; i++) ok = hipStreamCreateWithFlags(&c->side[i], hipStreamNonBlocking) == hipSuccess;
   for (int i = 0; ok && i < 96; i++) {
     hipEvent_t e;
     ok = hipEventCreateWithFlags(&e, hipEventDisableTiming) == hipSuccess;
@@ -1209,7 +1228,7 @@ void revffn_destroy(revffn_ctx* c) {
     for (hipEvent_t e : *c->sync_ev) (void)hipEventDestroy(e);
     delete c->sync_ev;
   }
-  for (int i = 0; i < 3; i++) if (c->side[i]) (void)hipStreamDestroy(c->side[i]);
+  for (int i = 0; i < 4; i++) if (c->side[i]) (void)hipStreamDestroy(c->side[i]);
   if (c->slab) (void)hipFree(c->slab);
   delete c;
 }
@@ -1379,8 +1398,10 @@ int revffn_inverse_backward(revffn_ctx* c, const revffn_weights* w, const void* 
   hipStream_t s = (hipStream_t)stream;
   const void* y1k = nullptr;
   i64 ldk = 0;
-  TRY(finish(c, s, inverse_impl(c, w, y1, y2, x1, x2, B, S, ld, residual, s, &y1k, &ldk)));
-  return finish(c, s, backward_impl(c, w, x1, x2, y1k, ldk, dy1, dy2, dx1, dx2, g, B, S, ld, true, c->cfg.n_inv_iters >= 1, s));
+  hipStream_t sa = s;                     // the stream the inverse leaves X1^ on (helper stream 3 beside the MoE backward pass)
+  TRY(finish(c, s, inverse_impl(c, w, y1, y2, x1, x2, B, S, ld, residual, s, &y1k, &ldk, c->side[3], &sa)));
+  return finish(c, s, backward_impl(c, w, x1, x2, y1k, ldk, dy1, dy2, dx1, dx2, g, B, S, ld, true, c->cfg.n_inv_iters >= 1, s,
+                                    false, sa == s ? nullptr : sa));
 }
 
 int revffn_merge_adapters(revffn_ctx* c, const revffn_weights* w, const revffn_merged* m, void* stream) {
@@ -1459,8 +1480,10 @@ int revffn_stack_backward(revffn_ctx* c, const revffn_weights* w, const revffn_g
     // activations computed at it by the inverse are reused by the backward pass
     const void* y1k = nullptr;
     i64 ldk = 0;
-    TRY(finish(c, s, inverse_impl(c, w + l, y1, y2, y1, y2, B, S, ld, nullptr, s, &y1k, &ldk)));
-    TRY(finish(c, s, backward_impl(c, w + l, y1, y2, y1k, ldk, dy1, dy2, dy1, dy2, g ? g + l : nullptr, B, S, ld, true, c->cfg.n_inv_iters >= 1, s)));
+    hipStream_t sa = s;
+    TRY(finish(c, s, inverse_impl(c, w + l, y1, y2, y1, y2, B, S, ld, nullptr, s, &y1k, &ldk, c->side[3], &sa)));
+    TRY(finish(c, s, backward_impl(c, w + l, y1, y2, y1k, ldk, dy1, dy2, dy1, dy2, g ? g + l : nullptr, B, S, ld, true, c->cfg.n_inv_iters >= 1, s,
+                                   false, sa == s ? nullptr : sa)));
   }
   return 0;
 }
