@@ -132,6 +132,7 @@ def bench_stack(args, wl):
         "activations": "stored: one workspace per block + every block boundary state" if args.stored else "reversible: one workspace",
         "reconstruction_drift_at_stack_input": {"max_abs_x1": drift1, "max_abs_x2": drift2,
                                                 "note": "max |rebuilt - true| after walking all blocks down"},
+        "csrc_sha16": csrc_hash(),
     }
     print(json.dumps(out))
 
