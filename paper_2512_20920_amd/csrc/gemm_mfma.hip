@@ -546,6 +546,9 @@ template <bool AT, bool BT, class TC> static void go_256x256(const GemmArgs& g, 
 template <bool AT, bool BT, class TC> static void go_128x128(const GemmArgs& g, hipStream_t s) { go<128, 128, 4, AT, BT, TC, 8, 4>(g, s); }
 template <bool AT, bool BT, class TC> static void go_128x256(const GemmArgs& g, hipStream_t s) { go<128, 256, 2, AT, BT, TC, 8, 3>(g, s); }
 template <bool AT, bool BT, class TC> static void go_128x64(const GemmArgs& g, hipStream_t s) { go<128, 64, 4, AT, BT, TC, 8, 3>(g, s); }
+// 160x256 for the routed experts' forward GEMMs where one 160-row tile holds a typical expert: 4 waves side by side,
+// each 160 rows x 64 columns (a gate and an up block for the SwiGLU epilogue), one wave per SIMD, 3 stages of 52 KiB
+template <bool AT, bool BT, class TC> static void go_160x256(const GemmArgs& g, hipStream_t s) { go<160, 256, 1, AT, BT, TC, 4, 3>(g, s); }
 
 template <bool AT, bool BT, class TC>
 static void pick_tile(const GemmArgs& g, hipStream_t s) {
@@ -583,6 +586,7 @@ static void pick_tile(const GemmArgs& g, hipStream_t s) {
     // expert tiles.  Skipping the MFMAs of the 32-row blocks past an expert's end (waves spanning all rows, a loop
     // specialised per block count) measured no gain, and neither did a fifth LDS stage.
     if constexpr (!AT) {
+      if constexpr (!BT) { if (g.tile_bm == 160) { go_160x256<AT, BT, TC>(g, s); return; } }
       if (g.tile_bm == 256) go_256x128<AT, BT, TC>(g, s);
       else if (g.tile_bn == 256) go_128x256<AT, BT, TC>(g, s);
       else go_128x128<AT, BT, TC>(g, s);
@@ -627,7 +631,7 @@ int launch_gemm_mfma(const GemmArgs& g, GemmTypes t, hipStream_t s) {
   if (g.b_trans && (g.N & 7)) return 1;
   if (g.a_trans && !g.b_trans) return 1;                 // layout not used by the block
   if (g.group_mode == 2 && !(g.a_trans && g.b_trans)) return 1;
-  if (g.group_mode == 1 && (g.a_trans || (g.tile_bm != 128 && g.tile_bm != 256))) return 1;
+  if (g.group_mode == 1 && (g.a_trans || (g.tile_bm != 128 && g.tile_bm != 256 && !(g.tile_bm == 160 && !g.b_trans && g.tile_bn == 256)))) return 1;
   if (g.a_gather && g.a_trans) return 1;
   if (g.group_mode != 1 && g.M <= 0) return 1;
   if (g.split_k > 1 && (g.group_mode != 0 || !g.splitk_ws)) return 1;

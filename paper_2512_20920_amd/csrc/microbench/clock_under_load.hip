@@ -1,7 +1,8 @@
 // Core clock under load, and how matrix-core and vector work of ONE wave overlap.  A wave runs, per iteration, 16 MFMAs
 // (v_mfma_f32_32x32x16_bf16), or 128 independent fused multiply-adds, or both interleaved (one MFMA, eight multiply-adds,
 // sixteen times), or 32 independent exp2.  It reads the shader clock counter (s_memtime) and the constant 100 MHz counter
-// (s_memrealtime) around the loop: their ratio is the clock the CU actually ran at.  One workgroup alone and one on every
+// (s_memrealtime) around the loop: their ratio is the clock the CU actually ran at.  With two waves per SIMD the span from
+// the first wave's start to the last wave's end shows how much of the two waves' work the SIMD overlapped.  One workgroup alone and one on every
 // CU, one and two waves per SIMD, random operand data.
 // Build: make -C paper_2512_20920_amd/csrc microbench; run: paper_2512_20920_amd/csrc/_build/clock_under_load
 #include <hip/hip_runtime.h>
@@ -53,19 +54,22 @@ __global__ void __launch_bounds__(512) k(const unsigned* seed, float* out, unsig
   for (int i = 0; i < 4; i++) s += acc[i][0];
   if (s == 12345.678f) out[0] = s;
   if (blockIdx.x == 0 && threadIdx.x == 0) { t[0] = c1 - c0; t[1] = r1 - r0; }
+  if (blockIdx.x == 0 && (threadIdx.x & 63) == 0) { t[2 + 2 * (threadIdx.x >> 6)] = c0; t[3 + 2 * (threadIdx.x >> 6)] = c1; }
 }
 int main() {
-  unsigned* seed; float* out; unsigned long long* t; unsigned long long h[2];
-  (void)hipMalloc(&seed, 4); (void)hipMalloc(&out, 4); (void)hipMalloc(&t, 16); (void)hipMemset(seed, 1, 4);
+  unsigned* seed; float* out; unsigned long long* t; unsigned long long h[18];
+  (void)hipMalloc(&seed, 4); (void)hipMalloc(&out, 4); (void)hipMalloc(&t, 18 * 8); (void)hipMemset(seed, 1, 4);
   const char* names[4] = {"16 MFMA", "128 FMA", "16 MFMA + 128 FMA interleaved", "32 exp2"};
   for (int blocks : {1, 256}) for (int threads : {256, 512}) for (int mode = 0; mode < 4; mode++) {
     const int iters = 20000;
     auto kern = mode == 0 ? k<0> : mode == 1 ? k<1> : mode == 2 ? k<2> : k<3>;
     hipLaunchKernelGGL(kern, dim3(blocks), dim3(threads), 0, 0, seed, out, t, 200);
     hipLaunchKernelGGL(kern, dim3(blocks), dim3(threads), 0, 0, seed, out, t, iters);
-    (void)hipMemcpy(h, t, 16, hipMemcpyDeviceToHost);
-    printf("workgroups %3d, waves per SIMD %d, %-30s: %6.0f clocks per iteration (first wave), clock %.2f GHz\n", blocks, threads / 256, names[mode],
-           (double)h[0] / iters, (double)h[0] / (double)h[1] * 0.1);
+    (void)hipMemcpy(h, t, 18 * 8, hipMemcpyDeviceToHost);
+    unsigned long long lo = ~0ull, hi = 0;
+    for (int w = 0; w < threads / 64; w++) { lo = h[2 + 2 * w] < lo ? h[2 + 2 * w] : lo; hi = h[3 + 2 * w] > hi ? h[3 + 2 * w] : hi; }
+    printf("workgroups %3d, waves per SIMD %d, %-30s: %6.0f clocks per iteration (first wave), %6.0f (first start to last end, all waves of the workgroup), clock %.2f GHz\n",
+           blocks, threads / 256, names[mode], (double)h[0] / iters, (double)(hi - lo) / iters, (double)h[0] / (double)h[1] * 0.1);
     fflush(stdout);
   }
   return 0;

@@ -55,6 +55,9 @@ WORKLOADS = {
     "mid_f32": Workload("mid_f32", 128, 4, 32, 6, 2, 96, 160, 3, 50, "f32", gain_jitter=0.02),
     # few large experts, no shared expert, reduced: rows per expert span several 128- and 256-row tiles
     "mid_fewbig_bf16": Workload("mid_fewbig_bf16", 512, 4, 128, 3, 2, 712, 0, 3, 232, "bf16", gain_jitter=0.02),
+    # 137 rows per expert on average, the Qwen shape's figure at 2048 tokens: the routed forward GEMMs take the tiles
+    # that are 160 rows high; expert width 200 leaves a gate column tile that ends inside the tile
+    "mid_rows137_bf16": Workload("mid_rows137_bf16", 512, 4, 128, 6, 2, 200, 160, 2, 206, "bf16", gain_jitter=0.02),
 }
 
 WEIGHT_FIELDS = (

@@ -101,7 +101,8 @@ def _backward_checks(case, x1d, x2d, y1d, tol):
 
 
 @pytest.mark.parametrize("name,mode", [("tiny_f32", 0), ("tiny_shared_f32", 0), ("mid_f32", 0),
-                                       ("mid_bf16", 1), ("mid_bf16", 0), ("mid_fewbig_bf16", 0)])
+                                       ("mid_bf16", 1), ("mid_bf16", 0), ("mid_fewbig_bf16", 0),
+                                       ("mid_rows137_bf16", 0)])
 def test_block_parity(name, mode):
     wl = synth.WORKLOADS[name]
     tol = TOL[wl.dtype]
@@ -348,11 +349,11 @@ def test_symmetric_comparison_block(name, mode):
 
 
 @pytest.mark.gpu
-@pytest.mark.parametrize("name", ["mid_bf16", "mid_fewbig_bf16"])
+@pytest.mark.parametrize("name", ["mid_bf16", "mid_fewbig_bf16", "mid_rows137_bf16"])
 def test_fused_swiglu_epilogue_matches_the_separate_kernel(name, monkeypatch):
     """The gate/up GEMMs write silu(gate) * up from their epilogue (a tile holds matching gate and up columns).  Same
     bits as the GEMM followed by the SwiGLU kernel, through forward, inverse and every gradient; the expert widths of
-    these workloads (192 and 320; 712) leave tiles whose gate columns end inside the tile."""
+    these workloads (192 and 320; 712; 200 and 160) leave tiles whose gate columns end inside the tile."""
     wl = synth.WORKLOADS[name]
     outs = []
     for separate in (False, True):
@@ -890,7 +891,7 @@ def _oracle_merged(case):
     return M, Mr
 
 
-@pytest.mark.parametrize("name", ["tiny_shared_f32", "mid_f32", "mid_bf16", "mid_fewbig_bf16"])
+@pytest.mark.parametrize("name", ["tiny_shared_f32", "mid_f32", "mid_bf16", "mid_fewbig_bf16", "mid_rows137_bf16"])
 def test_merged_adapters_parity(name):
     wl = synth.WORKLOADS[name]
     tol = TOL[wl.dtype]
