@@ -343,7 +343,8 @@ int revffn_op_attention_bwd_noalloc(int32_t dtype, int32_t kernel_mode, const vo
  * (-1,-1,-1) for a workgroup that exits without a tile.  group_mode 0: dense problem of tiles_m x tiles_n tiles
  * of bm x bn elements; 1: expert tile list with room for tiles_m entries of which n_used are in use,
  * tile_first[t] (host pointer, n_used entries, may be NULL) = (first tile of t's expert) << 16 | tiles of that
- * expert; 2: per-expert weight gradients, n_groups experts of tiles_m x tiles_n tiles each.  Returns the
+ * expert; 2: per-expert weight gradients, n_groups experts of tiles_m x tiles_n tiles each, n_used != 0: the placement
+ * taken while the routing is even (two XCDs share an expert), n_used == 0: the plain walk over all tiles.  Returns the
  * number of workgroups in the grid, or REVFFN_EINVAL (bad arguments, or more workgroups than max_wg). */
 int revffn_op_tile_placement(int32_t group_mode, int32_t tiles_m, int32_t tiles_n, int32_t bm, int32_t bn,
                              int32_t n_groups, const int32_t *tile_first, int32_t n_used, int32_t *out,

@@ -75,7 +75,7 @@ struct revffn_ctx {
   int expert_nt = 0, expert_nn = 0;
   bool no_fused_swiglu = false; // REVFFN_NO_FUSED_SWIGLU (tuning aid): SwiGLU as a kernel of its own after the gate/up GEMM
   int expert_tile = 0;        // m-tile height of the MFMA expert GEMMs forced to 128 or 256 (REVFFN_EXPERT_TILE), 0 = by rows per expert
-  int* tile_cnt;              // tiles in use of the three lists
+  int* tile_cnt;              // tiles in use of the three lists, then the flag that the routing is even
   void *Xg, *GU, *Hh, *Yp, *GUs, *Hs, *Ys, *RS;
   float *tapA, *tapM;
   void *y1c, *xtmp;
@@ -169,7 +169,7 @@ size_t carve(revffn_ctx* c, char* base) {
   c->tg_c = (int*)cv.take(c->max_tiles_c * 4);
   c->tm_c = (int*)cv.take(c->max_tiles_c * 4);
   c->tf_c = (int*)cv.take(c->max_tiles_c * 4);
-  c->tile_cnt = (int*)cv.take(3 * 4);
+  c->tile_cnt = (int*)cv.take(4 * 4);
   c->tf_a = (int*)cv.take(c->max_tiles_a * 4);
   c->tf_b = (int*)cv.take(c->max_tiles_b * 4);
   c->Xg = cv.take(N * d * es);
@@ -992,7 +992,7 @@ int backward_impl(revffn_ctx* c, const revffn_weights* w, const void* x1, const 
     if (GF(w_down)) {
       after(c, s, sw);
       GemmArgs b = tn(c->dYp, d, c->Hh, I, GF(w_down), I, d, I, N);        // dWd_e = dYp_e^T . Hh_e
-      b.group_mode = 2; b.n_groups = E; b.offsets = c->offsets; b.c_group_stride = (i64)d * I;
+      b.group_mode = 2; b.n_groups = E; b.offsets = c->offsets; b.tile_count = c->tile_cnt + 3; b.c_group_stride = (i64)d * I;
       TRY(run_wgrad(c, b, sw));
     }
     GemmArgs a = nn(c->dYp, d, w->w_down, I, c->dHh, I, N, I, d);          // dHh = dYp . Wd_e
@@ -1004,7 +1004,7 @@ int backward_impl(revffn_ctx* c, const revffn_weights* w, const void* x1, const 
       after(c, s, sw);
       p_gather_rows(c, dt, c->Um, c->row_map, k, c->Xg, N, d, sw);
       GemmArgs b = tn(c->dGU, 2 * I, c->Xg, d, GF(w_gate_up), d, 2 * I, d, N);
-      b.group_mode = 2; b.n_groups = E; b.offsets = c->offsets; b.c_group_stride = (i64)2 * I * d;
+      b.group_mode = 2; b.n_groups = E; b.offsets = c->offsets; b.tile_count = c->tile_cnt + 3; b.c_group_stride = (i64)2 * I * d;
       TRY(run_wgrad(c, b, sw));
     }
     GemmArgs e = nn(c->dGU, 2 * I, w->w_gate_up, d, c->dXg, d, N, d, 2 * I);     // dXg = dGU . Wgu_e
@@ -1352,7 +1352,7 @@ int revffn_op_tile_placement(int32_t group_mode, int32_t tiles_m, int32_t tiles_
   long long grid;
   if (group_mode == 0) { xcd_m = pick_xcd_m(tiles_m, tiles_n, bm, bn); grid = dense_grid_x(xcd_m, tiles_m, tiles_n); }
   else if (group_mode == 1) grid = (long long)tiles_n * tiles_m;
-  else grid = 8LL * ((n_groups + 7) / 8) * tiles_n * tiles_m;
+  else { xcd_m = 2; grid = wgrad_grid_x(xcd_m, tiles_m, tiles_n, n_groups); }
   if (grid > max_wg) return REVFFN_EINVAL;
   for (int i = 0; i < (int)grid; i++) {
     int bx = -1, by = -1, bz = 0;

@@ -43,7 +43,8 @@ struct GemmArgs {
   int split_k = 1; float* splitk_ws = nullptr;
   int splitk_raw = 0;                    // generic kernel: leave the slices in splitk_ws, the consumer adds them
   const void* col_scale = nullptr;
-  // group_mode 1: number of m-tiles of the list actually in use (device scalar written by the permutation kernel)
+  // group_mode 1: number of m-tiles of the list actually in use (device scalar written by the permutation kernel);
+  // group_mode 2: the permutation kernel's flag that the routing is even (null: treated as uneven)
   const int* tile_count = nullptr;
   const int* tile_first = nullptr;       // per tile: (first tile of its expert) << 16 | tiles of that expert
   // MFMA kernel, dense problems without split-k: n_sub > 1 launches that many problems of one shape, layout and
@@ -67,7 +68,10 @@ struct GemmArgs {
 //   expert tiles (group_mode 1): a consecutive run of the (n-tile, m-tile) pairs of the tile list in use
 //     (n_used entries); inside one expert the m-tiles are the fastest index (tile_first[t] = first tile of t's
 //     expert << 16 | tiles of that expert), so the workgroups that read one weight tile run next to each other;
-//   per-expert weight gradients (group_mode 2): whole experts per XCD, bz = the expert.
+//   per-expert weight gradients (group_mode 2): n_used != 0 (the routing is even, see the permutation kernel):
+//     xcd_m XCDs share an expert (bz), each taking a band of its column tiles, so that an operand panel is fetched
+//     by xcd_m L2s instead of 8; n_used == 0: the plain walk, which spreads every expert over all XCDs (a hot expert
+//     must not be left to two of them).
 // Returns false for a workgroup that has no tile (it exits at once).  Host and device share this code so that
 // the index arithmetic can be checked on the host.
 __host__ __device__ inline bool place_tile(int group_mode, int xcd_m, int tiles_m, int tiles_n, int n_groups,
@@ -87,12 +91,22 @@ __host__ __device__ inline bool place_tile(int group_mode, int xcd_m, int tiles_
     return true;
   }
   if (group_mode == 2) {
-    const int per = tiles_n * tiles_m;
+    if (!n_used) {                        // plain walk: n-tile fastest, then m-tile, then expert
+      const int per = tiles_n * tiles_m;
+      *bz = bid / per;
+      if (*bz >= n_groups) return false;
+      const int t = bid - *bz * per;
+      *by = t / tiles_n; *bx = t - *by * tiles_n;
+      return true;
+    }
+    // xcd_m XCDs share one expert, each taking a band of its column tiles; 8 / xcd_m experts are in flight at a time
+    const int p = xcd_m, G = 8 / p, gi = c / p, mi = c - gi * p;
+    const int cn = (tiles_n + p - 1) / p, per = cn * tiles_m;
     const int round = loc / per, t = loc - round * per;
-    *bz = round * 8 + c;
+    *bz = round * G + gi;
     if (*bz >= n_groups) return false;
-    *by = t / tiles_n; *bx = t - *by * tiles_n;
-    return true;
+    *by = t / cn; *bx = mi * cn + (t - *by * cn);
+    return *bx < tiles_n;
   }
   const int xm = xcd_m, xn = 8 / xm;
   const int sm = (tiles_m + xm - 1) / xm, sn = (tiles_n + xn - 1) / xn;
@@ -111,6 +125,13 @@ inline int pick_xcd_m(int tiles_m, int tiles_n, int bm, int bn) {
     if (best < 0 || cost < best) { best = cost; pick = xm; }
   }
   return pick;
+}
+// workgroups of a per-expert weight-gradient launch: enough for the plain walk and for the paired placement
+inline long long wgrad_grid_x(int xcd_m, int tiles_m, int tiles_n, int n_groups) {
+  const long long plain = (long long)n_groups * tiles_m * tiles_n;
+  const int G = 8 / xcd_m;
+  const long long paired = 8LL * ((n_groups + G - 1) / G) * ((tiles_n + xcd_m - 1) / xcd_m) * tiles_m;
+  return plain > paired ? plain : paired;
 }
 inline int dense_grid_x(int xcd_m, int tiles_m, int tiles_n) {
   return 8 * ((tiles_m + xcd_m - 1) / xcd_m) * ((tiles_n + 8 / xcd_m - 1) / (8 / xcd_m));
@@ -190,6 +211,7 @@ void launch_router(int dt, const void* y1, i64 ld, const float* zparts, int n_pa
 // m-tile lists of the grouped GEMMs for three tile heights: list i covers every expert's rows with
 // tiles of bm[i] rows (group[i][t] = expert or -1 for an unused slot, m0[i][t] = first row, first[i][t] = packed
 // (first tile of t's expert) * 65536 + (tiles of that expert), count[i] = tiles in use)
+// count[0..2]: tiles in use of the three lists; count[3]: 1 if the rows are spread evenly over the experts (place_tile)
 struct TileLists { int* group[3]; int* m0[3]; int* first[3]; int max_tiles[3]; int bm[3]; int* count; };
 // counts/offsets/row_map/inv_map and the tile lists
 void launch_permute(const int* idx, int T, int k, int E, int* counts, int* offsets, int* row_map, int* inv_map,

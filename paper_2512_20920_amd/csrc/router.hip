@@ -160,6 +160,17 @@ __global__ void __launch_bounds__(PERM_WAVES * 64) permute_k(
   }
   __syncthreads();
   for (int e = threadIdx.x; e <= E; e += blockDim.x) offsets[e] = off[e];
+  if (threadIdx.x == 0) {
+    // Is the routing even enough for the per-expert weight-gradient launches to give each expert to two XCDs?  Then
+    // experts e = 4 r + q (q = 0..3) are worked on by XCD pair q in round r, and the pairs finish together only if
+    // their experts cost about the same: a tile costs a fixed part (first loads, stores: about 5 k-steps' worth) plus
+    // one k-step per 64 rows of the expert.  Even = no pair more than 6 % above the mean.
+    int cost[4] = {0, 0, 0, 0};
+    for (int e = 0; e < E; e++) cost[e & 3] += 5 + (off[e + 1] - off[e] + 63) / 64;
+    const int tot = cost[0] + cost[1] + cost[2] + cost[3];
+    const int mx = max(max(cost[0], cost[1]), max(cost[2], cost[3]));
+    tl.count[3] = (E >= 8 && 400 * mx <= 106 * tot) ? 1 : 0;
+  }
   // tile lists: expert e owns the slots after the tiles of experts 0..e-1; slots past the last tile are marked
   // unused.  The number of tiles of an expert is an exact division: the fill loop below writes ceil(rows / bm) slots
   // per expert, and a count taken any other way (a shift, for a height that is not a power of two) would leave

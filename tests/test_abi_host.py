@@ -136,10 +136,16 @@ def test_tile_placement_covers_every_tile_once():
                     for j in range(1, int(c)):
                         a, b = order[(0, int(f) + j - 1)], order[(0, int(f) + j)]
                         assert (a & 7) != (b & 7) or b - a == 8
-    # per-expert weight gradients: every (expert, tile) once, whole experts per XCD
-    wg = R.revffn_op_tile_placement(2, 3, 5, 128, 128, n_groups=13)
-    live = wg[wg[:, 0] >= 0]
-    assert len(live) == 13 * 15 and len({tuple(map(int, r)) for r in live}) == 13 * 15
-    xcd = np.arange(len(wg)) & 7
-    for e in range(13):
-        assert len(set(xcd[(wg[:, 2] == e)])) == 1
+    # per-expert weight gradients: every (expert, tile) once, under both placements and for tile counts and expert
+    # counts that the split over XCD pairs does not divide evenly; with an even routing an expert stays on two XCDs
+    for tiles_m, tiles_n, E in [(3, 5, 13), (11, 8, 60), (8, 6, 60), (1, 1, 1), (2, 9, 7)]:
+        for even in (1, 0):
+            wg = R.revffn_op_tile_placement(2, tiles_m, tiles_n, 256, 256, n_groups=E, n_used=even)
+            live = wg[wg[:, 0] >= 0]
+            assert len(live) == E * tiles_m * tiles_n and len({tuple(map(int, r)) for r in live}) == E * tiles_m * tiles_n
+            assert live[:, 0].max() < tiles_n and live[:, 1].max() < tiles_m and live[:, 2].max() < E
+            if even:
+                xcd = np.arange(len(wg)) & 7
+                for e in range(E):
+                    used = set(xcd[(wg[:, 2] == e)])
+                    assert len(used) <= 2 and len({x >> 1 for x in used}) == 1
