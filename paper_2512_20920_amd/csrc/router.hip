@@ -115,6 +115,20 @@ __device__ __forceinline__ void same_expert_mask(int x, bool valid, int nbits, u
   }
 }
 
+__device__ __forceinline__ int wave_inclusive_scan(int v, int lane) {
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int u = __shfl_up(v, o, WAVE);
+    if (lane >= o) v += u;
+  }
+  return v;
+}
+__device__ __forceinline__ int wave_sum(int v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
+  return v;
+}
+
 __global__ void __launch_bounds__(PERM_WAVES * 64) permute_k(
     const int* __restrict__ idx, int N, int E, int* __restrict__ counts, int* __restrict__ offsets,
     int* __restrict__ row_map, int* __restrict__ inv_map, TileLists tl) {
@@ -154,51 +168,60 @@ __global__ void __launch_bounds__(PERM_WAVES * 64) permute_k(
     off[e + 1] = run;                     // totals for now
   }
   __syncthreads();
-  if (threadIdx.x == 0) {
-    off[0] = 0;
-    for (int e = 0; e < E; e++) off[e + 1] += off[e];
+  if (wv == 0) {                          // offsets = prefix sums of the totals, 64 experts per step
+    if (lane == 0) off[0] = 0;
+    int carry = 0;
+    for (int base = 0; base < E; base += 64) {
+      const int e = base + lane;
+      const int incl = carry + wave_inclusive_scan(e < E ? off[e + 1] : 0, lane);
+      if (e < E) off[e + 1] = incl;
+      carry = __shfl(incl, 63, WAVE);
+    }
   }
   __syncthreads();
   for (int e = threadIdx.x; e <= E; e += blockDim.x) offsets[e] = off[e];
-  if (threadIdx.x == 0) {
+  // Waves 0-2 write one tile list each, wave 3 the evenness flag; none of them changes what the row pass below
+  // reads (off, cnt), so nothing waits for them.
+  if (wv < 3) {
+    // tile lists: expert e owns the slots after the tiles of experts 0..e-1; slots past the last tile are marked
+    // unused.  The number of tiles of an expert is an exact division: the fill loop below writes ceil(rows / bm)
+    // slots per expert, and a count taken any other way (a shift, for a height that is not a power of two) would
+    // leave slots of the list unwritten, with whatever the workspace held, for the GEMM to use as an expert index.
+    const int pass = wv;
+    const int bm = tl.bm[pass], mx = tl.max_tiles[pass];
+    int* tg = tl.group[pass];
+    int* tm = tl.m0[pass];
+    int* tf = tl.first[pass];
+    int total = 0;
+    for (int base = 0; base < E; base += 64) {
+      const int e = base + lane;
+      const int m_lo = e < E ? off[e] : 0, m_hi = e < E ? off[e + 1] : 0;
+      const int mine = (m_hi - m_lo + bm - 1) / bm;
+      const int incl = wave_inclusive_scan(mine, lane);
+      const int first = total + incl - mine;
+      int i = first;
+      for (int m = m_lo; m < m_hi; m += bm, i++)
+        if (i < mx) { tg[i] = e; tm[i] = m; tf[i] = (first << 16) | mine; }
+      total += __shfl(incl, 63, WAVE);
+    }
+    for (int i = total + lane; i < mx; i += 64) { tg[i] = -1; tm[i] = 0; tf[i] = (i << 16) | 1; }
+    if (lane == 0) tl.count[pass] = min(total, mx);
+  } else if (wv == 3) {
     // Is the routing even enough for the per-expert weight-gradient launches to give each expert to two XCDs?  Then
     // experts e = 4 r + q (q = 0..3) are worked on by XCD pair q in round r, and the pairs finish together only if
     // their experts cost about the same: a tile costs a fixed part (first loads, stores: about 5 k-steps' worth) plus
     // one k-step per 64 rows of the expert.  Even = no pair more than 6 % above the mean.
     int cost[4] = {0, 0, 0, 0};
-    for (int e = 0; e < E; e++) cost[e & 3] += 5 + (off[e + 1] - off[e] + 63) / 64;
+    for (int base = 0; base < E; base += 64) {
+      const int e = base + lane;
+      const int mine = e < E ? 5 + (off[e + 1] - off[e] + 63) / 64 : 0;
+#pragma unroll
+      for (int q = 0; q < 4; q++) cost[q] += wave_sum((e & 3) == q ? mine : 0);
+    }
     const int tot = cost[0] + cost[1] + cost[2] + cost[3];
     const int mx = max(max(cost[0], cost[1]), max(cost[2], cost[3]));
-    tl.count[3] = (E >= 8 && 400 * mx <= 106 * tot) ? 1 : 0;
+    if (lane == 0) tl.count[3] = (E >= 8 && 400 * mx <= 106 * tot) ? 1 : 0;
   }
-  // tile lists: expert e owns the slots after the tiles of experts 0..e-1; slots past the last tile are marked
-  // unused.  The number of tiles of an expert is an exact division: the fill loop below writes ceil(rows / bm) slots
-  // per expert, and a count taken any other way (a shift, for a height that is not a power of two) would leave
-  // slots of the list unwritten, with whatever the workspace held, for the GEMM to use as an expert index.
-  int* tcnt = cnt + PERM_WAVES * E + E + 1;   // [E + 1]: tiles per expert, then their total
-  for (int pass = 0; pass < 3; pass++) {
-    const int bm = tl.bm[pass], mx = tl.max_tiles[pass];
-    int* tg = tl.group[pass];
-    int* tm = tl.m0[pass];
-    int* tf = tl.first[pass];
-    __syncthreads();                        // the previous pass is done with tcnt
-    for (int e = threadIdx.x; e < E; e += blockDim.x) tcnt[e] = (off[e + 1] - off[e] + bm - 1) / bm;
-    __syncthreads();
-    if (threadIdx.x == 0) { int t = 0; for (int e = 0; e < E; e++) t += tcnt[e]; tcnt[E] = t; }
-    for (int e = threadIdx.x; e < E; e += blockDim.x) {
-      int first = 0;
-      for (int q = 0; q < e; q++) first += tcnt[q];
-      int i = first;
-      const int mine = tcnt[e];
-      for (int m = off[e]; m < off[e + 1]; m += bm, i++)
-        if (i < mx) { tg[i] = e; tm[i] = m; tf[i] = (first << 16) | mine; }
-    }
-    __syncthreads();
-    const int total = tcnt[E];
-    for (int i = total + threadIdx.x; i < mx; i += blockDim.x) { tg[i] = -1; tm[i] = 0; tf[i] = (i << 16) | 1; }
-    if (threadIdx.x == 0) tl.count[pass] = min(total, mx);
-  }
-  __syncthreads();
   for (int base0 = lo; base0 < hi; base0 += 64 * PERM_UNROLL) {
     int xs[PERM_UNROLL];
 #pragma unroll
