@@ -558,10 +558,14 @@ static void pick_tile(const GemmArgs& g, hipStream_t s) {
   // 8192 tokens: larger tiles do more work per loaded byte, but a last, partly filled round costs a whole tile's time).
   auto dense_choice = [&]() {
     const int z = g.split_k > 1 ? g.split_k : g.n_sub;
-    // (a launch that runs beside others on a helper stream fills only the CUs it needs: its cost is its tile count)
+    // (a launch that runs beside others on a helper stream fills only the CUs it needs: its cost is its tile count.
+    // Not for a problem of fewer than 128 of the largest tiles: on a fraction of the CUs it takes several times as
+    // long, and helper streams are chains too -- 32-tile weight gradients at the end of a call were the last thing
+    // running, on an eighth of the chip.)
+    const bool bulk = g.bulk && (i64)cdiv(g.M, 256) * cdiv(g.N, 256) * z >= 128;
     auto rounds = [&](int bm, int bn) {
       const i64 tiles = (i64)cdiv(g.M, bm) * cdiv(g.N, bn) * z;
-      return g.bulk ? (double)tiles / 256.0 : (double)cdiv(tiles, 256);
+      return bulk ? (double)tiles / 256.0 : (double)cdiv(tiles, 256);
     };
     const double c2 = rounds(128, 128), c3 = 1.72 * rounds(256, 128), c4 = 3.05 * rounds(256, 256);
     return (c4 < c3 && c4 < c2) ? 4 : (c3 < c2 ? 3 : 2);
@@ -608,7 +612,7 @@ static void pick_tile(const GemmArgs& g, hipStream_t s) {
   }
   // below ~200 tiles of 128x128: 128x64 (two workgroups per CU)
   const i64 t128 = (i64)cdiv(g.M, 128) * cdiv(g.N, 128) * (g.split_k > 1 ? g.split_k : g.n_sub);
-  if (t128 < 200 && g.N >= 128 && !(g.bulk && g.M >= 256 && g.N >= 256)) { go_128x64<AT, BT, TC>(g, s); return; }
+  if (t128 < 200 && g.N >= 128) { go_128x64<AT, BT, TC>(g, s); return; }
   switch (dense_choice()) {
     case 4: go_256x256<AT, BT, TC>(g, s); break;
     case 3:
