@@ -569,7 +569,7 @@ def test_frozen_groups_are_skipped():
     assert torch.equal(o1, dx1) and torch.equal(o2, dx2)
 
 
-@pytest.mark.parametrize("name", ["tiny_shared_f32", "mid_bf16"])
+@pytest.mark.parametrize("name", ["tiny_shared_f32", "mid_bf16", "mid_rows137_bf16"])
 def test_stored_activation_backward(name):
     """The non-reversible comparison route: gradients from the activations the forward call left in the workspace.
     Same bits as the recomputing backward at the true input, within tolerance of the oracle's stored route, and
