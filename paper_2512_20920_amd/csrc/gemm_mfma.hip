@@ -57,9 +57,10 @@ __device__ __forceinline__ u32x4 make_desc(const void* p) {
 // Where the 16-byte chunk at LDS position `pos` (in chunks, lane order of the wave-loads) of one operand tile
 // comes from: byte offset of that chunk at k-tile 0 relative to the operand base, and the number of k-tiles for
 // which it lies inside the k range (0 = never: a row past the limit).  krange = elements of the k range.
-template <bool TR, int ROWS>
+template <bool TR, int ROWS, int KB = BK>
 __device__ __forceinline__ void chunk_source(int pos, int row0, int row_lim, unsigned ld_bytes, int k0, int krange,
                                              const int* gather, int div, unsigned* base, int* ntiles) {
+  static_assert(KB == BK || TR, "rows x k tiles are laid out for 128-byte rows");
   if (!TR) {
     const int r = pos >> 3, slot = pos & 7;
     const int c = slot ^ ((r >> 1) & 7);                          // k-chunk of row r that lives in this slot
@@ -76,7 +77,7 @@ __device__ __forceinline__ void chunk_source(int pos, int row0, int row_lim, uns
     const int c = (((slot >> 2) ^ gsw) << 2) | (slot & 3);        // 8-element column chunk that lives in this slot
     const int col = row0 + c * 8;
     *base = (unsigned)(k0 + kr) * ld_bytes + (unsigned)col * 2u;
-    *ntiles = col < row_lim ? (krange - kr + BK - 1) / BK : 0;
+    *ntiles = col < row_lim ? (krange - kr + KB - 1) / KB : 0;
   }
 }
 
@@ -134,36 +135,41 @@ __device__ __forceinline__ void pair_rows(bool odd, float x0, float x1, float* l
 }
 
 // One output tile; TE = 32-row blocks per wave.
-template <int BM, int BN, int WGM, bool AT, bool BT, class TC, int NW, int NS, int TE>
+template <int BM, int BN, int WGM, bool AT, bool BT, class TC, int NW, int NS, int TE, int KB = BK>
 __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const bf16* A, const bf16* Bm, TC* C, const void* bias_ptr,
                                           int bx, int bz, int m0, int m_end, int k0, int k_end, int rot_seed) {
   constexpr int WGN = NW / WGM;                      // waves along n
   constexpr int WM = BM / WGM, WN = BN / WGN, TN = WN / 32;
-  constexpr int STAGE = (BM + BN) * 128;             // bytes of one LDS stage: A tile, then B tile
-  constexpr int LPW = (BM + BN) / 8 / NW;            // wave-loads (1 KiB) per wave per stage
+  // KB: elements of k per LDS stage (64; 32 for the per-expert weight gradients, whose k range is a few dozen rows)
+  constexpr int STAGE = (BM + BN) * KB * 2;          // bytes of one LDS stage: A tile, then B tile
+  constexpr int ALOADS = BM * KB / 512;              // wave-loads (1 KiB) of the A tile
+  constexpr int LPW = (BM + BN) * KB / 512 / NW;     // wave-loads per wave per stage
+  constexpr int KS = KB / 16;                        // MFMA k-steps per stage
   static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile must be made of 32x32 blocks");
+  static_assert(((BM + BN) * KB) % (512 * NW) == 0 && (BM * KB) % 512 == 0 && LPW % KS == 0 || KB == BK, "wave-loads must divide evenly");
   static_assert((BM + BN) % (8 * NW) == 0 && BM % 8 == 0, "wave-loads must divide evenly");
+  static_assert(KB == BK || (AT && BT), "a shorter k-tile only for operands stored k x rows");
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   const int n0 = bx * BN;
   const int lane = threadIdx.x & 63, wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wm = (wv / WGN) * WM, wn = (wv % WGN) * WN;
   const int krange = k_end - k0;
-  const int nk = (krange + BK - 1) / BK;
+  const int nk = (krange + KB - 1) / KB;
 
   // ---- this wave's loads: wave-load j = wv*LPW + i fills LDS chunks [64 j, 64 j + 64) of a stage; the first
   // BM/8 wave-loads are the A tile, the rest the B tile
   const u32x4 da = make_desc(A), db = make_desc(Bm);
   const unsigned lda_b = (unsigned)g.lda * 2u, ldb_b = (unsigned)g.ldb * 2u;
-  const unsigned kstep_a = AT ? BK * lda_b : BK * 2u, kstep_b = BT ? BK * ldb_b : BK * 2u;
+  const unsigned kstep_a = AT ? KB * lda_b : KB * 2u, kstep_b = BT ? KB * ldb_b : KB * 2u;
   unsigned base[LPW];
   int ntile[LPW];
 #pragma unroll
   for (int i = 0; i < LPW; i++) {
     const int j = wv * LPW + i;
-    if (j < BM / 8) chunk_source<AT, BM>(j * 64 + lane, m0, m_end, lda_b, k0, krange, g.a_gather, g.gather_div, &base[i], &ntile[i]);
+    if (j < ALOADS) chunk_source<AT, BM, KB>(j * 64 + lane, m0, m_end, lda_b, k0, krange, g.a_gather, g.gather_div, &base[i], &ntile[i]);
     else if (!AT && !BT && TN == 2 && g.act_half)
-      chunk_source_gate_up((j - BM / 8) * 64 + lane, bx * (BN / 2), g.act_half, ldb_b, k0, krange, &base[i], &ntile[i]);
-    else chunk_source<BT, BN>((j - BM / 8) * 64 + lane, n0, g.N, ldb_b, k0, krange, nullptr, 1, &base[i], &ntile[i]);
+      chunk_source_gate_up((j - ALOADS) * 64 + lane, bx * (BN / 2), g.act_half, ldb_b, k0, krange, &base[i], &ntile[i]);
+    else chunk_source<BT, BN, KB>((j - ALOADS) * 64 + lane, n0, g.N, ldb_b, k0, krange, nullptr, 1, &base[i], &ntile[i]);
   }
   const unsigned lds0 = (unsigned)(unsigned long long)(__attribute__((address_space(3))) unsigned char*)smem;
   const unsigned lw = __builtin_amdgcn_readfirstlane(lds0 + (unsigned)wv * LPW * 1024u);
@@ -174,7 +180,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const bf16* A, cons
   // products in a rotated, per-tile fixed order.
   const int rot = __builtin_amdgcn_readfirstlane(nk > 0 ? rot_seed % nk : 0);
   auto issue = [&](int kt, int i) {                  // wave-load i of the kt-th k-tile walked, into stage kt % NS
-    const bool isA = (wv * LPW + i) < BM / 8;        // wave-uniform
+    const bool isA = (wv * LPW + i) < ALOADS;        // wave-uniform
     const int kr = kt + rot >= nk ? kt + rot - nk : kt + rot;
     const unsigned off = (kt < nk && kr < ntile[i]) ? base[i] + (unsigned)kr * (isA ? kstep_a : kstep_b) : OOB;
     load_lds_b128(isA ? da : db, lw + (unsigned)(kt % NS) * STAGE + i * 1024, off);
@@ -191,7 +197,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const bf16* A, cons
 #pragma unroll
   for (int i = 0; i < TE; i++) fba[i] = frag_base<AT, BM>(wm + i * 32, lane);
 #pragma unroll
-  for (int j = 0; j < TN; j++) fbb[j] = BM * 128u + frag_base<BT, BN>(wn + j * 32, lane);
+  for (int j = 0; j < TN; j++) fbb[j] = BM * KB * 2u + frag_base<BT, BN>(wn + j * 32, lane);
 
   // ---- pipeline: tiles kt+1 .. kt+NS-1 are in flight while tile kt is multiplied.  A tile past the end of the
   // k range is loaded as zeros (OOB), so every iteration issues the same number of loads and the wait count
@@ -213,10 +219,10 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const bf16* A, cons
 #pragma unroll
     for (int j = 0; j < TN; j++) fb[0][j] = load_frag<BT, BN>(st, fbb[j], wn + j * 32, 0, lane);
 #pragma unroll
-    for (int kk = 0; kk < BK / 16; kk++) {
+    for (int kk = 0; kk < KS; kk++) {
 #pragma unroll
-      for (int i = kk * LPW / 4; i < (kk + 1) * LPW / 4; i++) issue(kt + NS - 1, i);
-      if (kk + 1 < BK / 16) {
+      for (int i = kk * LPW / KS; i < (kk + 1) * LPW / KS; i++) issue(kt + NS - 1, i);
+      if (kk + 1 < KS) {
 #pragma unroll
         for (int i = 0; i < TE; i++) fa[(kk + 1) & 1][i] = load_frag<AT, BM>(st, fba[i], wm + i * 32, kk + 1, lane);
 #pragma unroll
@@ -448,7 +454,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const bf16* A, cons
   }
 }
 
-template <int BM, int BN, int WGM, bool AT, bool BT, class TC, int NW, int NS>
+template <int BM, int BN, int WGM, bool AT, bool BT, class TC, int NW, int NS, int KB = BK>
 __global__ void __launch_bounds__(NW * 64) gemm_mfma_k(GemmArgs g) {
   constexpr int TM = BM / WGM / 32;
   const bf16* A = (const bf16*)g.A;
@@ -494,7 +500,7 @@ __global__ void __launch_bounds__(NW * 64) gemm_mfma_k(GemmArgs g) {
     for (int r = m0 + (int)(threadIdx.x & 63); r < min(m_end, m0 + BM); r += 64) live |= g.row_skip[r] == 0;
     if (!__any(live)) return;
   }
-  gemm_tile<BM, BN, WGM, AT, BT, TC, NW, NS, TM>(g, A, Bm, C, bias, bx, bz, m0, m_end, k0, k_end, rot_seed);
+  gemm_tile<BM, BN, WGM, AT, BT, TC, NW, NS, TM, KB>(g, A, Bm, C, bias, bx, bz, m0, m_end, k0, k_end, rot_seed);
 }
 
 // REVFFN_XCD (tuning aid): 0 = plain 2-D grids, tiles land on the XCDs round-robin
@@ -504,7 +510,7 @@ static int xcd_enabled() {
   return v;
 }
 
-template <int BM, int BN, int WGM, bool AT, bool BT, class TC, int NW, int NS>
+template <int BM, int BN, int WGM, bool AT, bool BT, class TC, int NW, int NS, int KB = BK>
 static void go(const GemmArgs& g0, hipStream_t s) {
   GemmArgs g = g0;
   { static int off = -1; if (off < 0) { const char* e = getenv("REVFFN_NO_PACKED_STORES"); off = e ? atoi(e) : 0; } g.no_packed_stores = off; }
@@ -527,15 +533,15 @@ static void go(const GemmArgs& g0, hipStream_t s) {
       grid = dim3(dense_grid_x(g.xcd_m, g.tiles_m, g.tiles_n), 1, zdim);
     }
   }
-  constexpr size_t smem = (size_t)NS * (BM + BN) * 128;
+  constexpr size_t smem = (size_t)NS * (BM + BN) * KB * 2;
   static_assert(smem <= 160 * 1024, "LDS stages exceed the CU's 160 KiB");
   static std::atomic<unsigned long long> attr_mask{0};
   if (attr_needed(attr_mask)) {
-    (void)hipFuncSetAttribute((const void*)gemm_mfma_k<BM, BN, WGM, AT, BT, TC, NW, NS>,
+    (void)hipFuncSetAttribute((const void*)gemm_mfma_k<BM, BN, WGM, AT, BT, TC, NW, NS, KB>,
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     attr_done(attr_mask);
   }
-  hipLaunchKernelGGL((gemm_mfma_k<BM, BN, WGM, AT, BT, TC, NW, NS>), grid, dim3(NW * 64), smem, s, g);
+  hipLaunchKernelGGL((gemm_mfma_k<BM, BN, WGM, AT, BT, TC, NW, NS, KB>), grid, dim3(NW * 64), smem, s, g);
 }
 
 // The tile shapes: 256x128 and 128x256 (8 waves, one workgroup per CU), 256x256 (2 stages), 128x128 (8 waves of 32x64,
@@ -584,7 +590,10 @@ static void pick_tile(const GemmArgs& g, hipStream_t s) {
       case 1: go_128x64<AT, BT, TC>(g, s); return;
       case 2: go_128x128<AT, BT, TC>(g, s); return;
       case 3: go_256x128<AT, BT, TC>(g, s); return;
-      case 4: go_256x256<AT, BT, TC>(g, s); return;
+      case 4:
+        if constexpr (AT && BT) go<256, 256, 2, AT, BT, TC, 8, 4, 32>(g, s);
+        else go_256x256<AT, BT, TC>(g, s);
+        return;
     }
   }
   if (g.group_mode == 1) {
@@ -607,14 +616,22 @@ static void pick_tile(const GemmArgs& g, hipStream_t s) {
     // 256x128 alone but slower inside the step, next to the data-gradient chain on the main stream; a persistent
     // form of 256x128 (a workgroup walks over tiles and issues the next tile's first loads before it stores the
     // finished one) was 5 % faster alone and 3 % of a step slower.
-    go_256x256<AT, BT, TC>(g, s);
-    return;
+    // With k-tiles of 32 rows (4 stages of 32 KiB) an expert of 137 rows is 5 k-tiles instead of 3 of 64 (17 % fewer
+    // multiplied zero rows), and all but the last are in flight at once: these kernels 10 % faster, a step 1.1 %.
+    // (5 stages: 8 % slower again; 3: the same.)
+    if constexpr (AT && BT) { go<256, 256, 2, AT, BT, TC, 8, 4, 32>(g, s); return; }
+    return;                                            // (launch_gemm_mfma admits this mode for that layout only)
   }
   // below ~200 tiles of 128x128: 128x64 (two workgroups per CU)
   const i64 t128 = (i64)cdiv(g.M, 128) * cdiv(g.N, 128) * (g.split_k > 1 ? g.split_k : g.n_sub);
   if (t128 < 200 && g.N >= 128) { go_128x64<AT, BT, TC>(g, s); return; }
   switch (dense_choice()) {
-    case 4: go_256x256<AT, BT, TC>(g, s); break;
+    case 4:
+      // (weight gradients: four stages of 32 rows of k instead of two of 64 keep more loads in flight; 0.5-1.2 % of a
+      // step on the skewed and long-sequence workloads)
+      if constexpr (AT && BT) go<256, 256, 2, AT, BT, TC, 8, 4, 32>(g, s);
+      else go_256x256<AT, BT, TC>(g, s);
+      break;
     case 3:
       // (the same tile count either way; with k contiguous in both operands the wide tile measured 1-4 % faster)
       if (!AT && !BT && g.N % 256 == 0) go_128x256<AT, BT, TC>(g, s);
