@@ -30,7 +30,7 @@
  *    the tolerance-driven inverse and revffn_profile_read say where they wait).
  *    Work is ordered after what `hip_stream` (a hipStream_t; NULL = the default
  *    stream) already holds, and `hip_stream` is ordered after all of it when the call
- *    returns; independent branches inside a call run on three helper streams owned by
+ *    returns; independent branches inside a call run on four helper streams owned by
  *    the context (default priority; revffn_set_helper_streams(ctx, 0) or the environment
  *    variable REVFFN_NO_STREAMS=1 at creation keep everything on `hip_stream`).  Calls on one context must be issued on one stream at a time
  *    (they share the context workspace).
